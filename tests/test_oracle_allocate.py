@@ -1,0 +1,214 @@
+"""Pins for the oracle's Phase-B allocation (CPU only).
+
+Sec. 3.2 Eq. 4, Alg. 1 "Phase B", Prop. 1 and its proof in App. A.  The
+allocation is checked against brute-force enumeration and against the
+exchange condition, both in exact rational arithmetic, so nothing here reuses
+the oracle's floating-point evaluation.
+"""
+from fractions import Fraction
+from itertools import product
+
+import numpy as np
+import pytest
+
+from test_oracle_gains import exact_gain, exact_utility
+
+
+def compositions(n, total, cap):
+    """All (d_1..d_n) of non-negative ints <= cap with sum == total."""
+    if n == 1:
+        if total <= cap:
+            yield (total,)
+        return
+    for first in range(min(total, cap) + 1):
+        for rest in compositions(n - 1, total - first, cap):
+            yield (first,) + rest
+
+
+def brute_force_best(ab, budget, cap):
+    best = None
+    for d in compositions(len(ab), budget, cap):
+        val = sum(exact_utility(a, b, k) for (a, b), k in zip(ab, d))
+        if best is None or val > best:
+            best = val
+    return best
+
+
+def exchange_condition_holds(ab, delta, cap):
+    """App. A: min_{i: d_i>0} M_i(d_i - 1) >= max_{j not capped} M_j(d_j), exactly."""
+    taken = [exact_gain(a, b, d - 1) for (a, b), d in zip(ab, delta) if d > 0]
+    avail = [exact_gain(a, b, d) for (a, b), d in zip(ab, delta) if not (cap and d >= cap)]
+    if not taken or not avail:
+        return True
+    return min(taken) >= max(avail)
+
+
+@pytest.mark.parametrize("g0", [2, 4, 8])
+def test_greedy_reaches_brute_force_optimum(oracle, g0):
+    rng = np.random.default_rng(100 + g0)
+    for trial in range(25):
+        n = int(rng.integers(1, 6))
+        budget = int(rng.integers(0, 9))
+        c = rng.integers(0, g0 + 1, n).astype(np.int32)
+        delta = oracle.allocate(c, g0, budget)
+        assert delta.sum() == budget and (delta >= 0).all()
+        ab = [(Fraction(1 + int(ci)), Fraction(1 + g0 - int(ci))) for ci in c]
+        got = sum(exact_utility(a, b, int(d)) for (a, b), d in zip(ab, delta))
+        assert got == brute_force_best(ab, budget, budget), (c, budget, delta)
+        assert exchange_condition_holds(ab, delta, 0)
+
+
+def test_greedy_with_cap_reaches_brute_force_optimum(oracle):
+    rng = np.random.default_rng(7)
+    g0 = 4
+    for trial in range(25):
+        n = int(rng.integers(2, 6))
+        cap = int(rng.integers(1, 4))
+        budget = int(rng.integers(0, n * cap + 1))
+        c = rng.integers(0, g0 + 1, n).astype(np.int32)
+        delta = oracle.allocate(c, g0, budget, delta_max=cap)
+        assert delta.sum() == budget and (delta >= 0).all() and (delta <= cap).all()
+        ab = [(Fraction(1 + int(ci)), Fraction(1 + g0 - int(ci))) for ci in c]
+        got = sum(exact_utility(a, b, int(d)) for (a, b), d in zip(ab, delta))
+        assert got == brute_force_best(ab, budget, cap)
+        assert exchange_condition_holds(ab, delta, cap)
+
+
+def test_binding_cap_cases(oracle):
+    c = np.zeros(4, dtype=np.int32)
+    assert oracle.allocate(c, 4, 12, delta_max=3).tolist() == [3, 3, 3, 3]
+    assert oracle.allocate(c, 4, 13, delta_max=4).tolist() == [4, 3, 3, 3]
+    with pytest.raises(oracle.OracleError) as e:
+        oracle.allocate(c, 4, 13, delta_max=3)
+    assert e.value.code == oracle.ERR_INFEASIBLE
+    # a hard prompt next to saturated ones: the cap diverts budget to the others
+    c = np.array([0, 8, 8], dtype=np.int32)
+    free = oracle.allocate(c, 8, 12)
+    capped = oracle.allocate(c, 8, 12, delta_max=5)
+    assert free[0] > 5 and capped[0] == 5 and capped.sum() == 12
+
+
+def test_real_valued_posteriors_have_a_unique_optimum(oracle):
+    # With generic real alpha, beta no two gains coincide, so the optimum of Eq. 4
+    # is unique and the oracle's allocation must equal the exact greedy one.
+    rng = np.random.default_rng(11)
+    for trial in range(20):
+        n = int(rng.integers(2, 7))
+        budget = int(rng.integers(1, 40))
+        alpha = rng.uniform(0.05, 9.0, n)
+        beta = rng.uniform(0.05, 9.0, n)
+        got = oracle.allocate_posterior(alpha, beta, budget)
+        ab = [(Fraction(float(a)), Fraction(float(b))) for a, b in zip(alpha, beta)]
+        want = [0] * n
+        for _ in range(budget):
+            gains = [exact_gain(a, b, d) for (a, b), d in zip(ab, want)]
+            assert len(set(gains)) == n
+            want[gains.index(max(gains))] += 1
+        assert got.tolist() == want
+
+
+def test_heap_and_linear_scan_agree_bit_for_bit(oracle):
+    rng = np.random.default_rng(3)
+    for g0 in (2, 4, 8):
+        for trial in range(10):
+            n = int(rng.integers(1, 200))
+            budget = int(rng.integers(0, 6 * n))
+            cap = int(rng.choice([0, 0, 3, 9]))
+            if cap and budget > n * cap:
+                budget = n * cap
+            c = rng.integers(0, g0 + 1, n).astype(np.int32)
+            a = oracle.allocate(c, g0, budget, delta_max=cap)
+            b = oracle.allocate(c, g0, budget, delta_max=cap, scan=True)
+            assert np.array_equal(a, b)
+
+
+def test_allocation_is_incremental_in_budget(oracle):
+    # Greedy is incremental: raising B by one adds one unit to exactly one prompt.
+    rng = np.random.default_rng(9)
+    c = rng.integers(0, 5, 40).astype(np.int32)
+    prev = oracle.allocate(c, 4, 0)
+    assert not prev.any()
+    for budget in range(1, 200):
+        cur = oracle.allocate(c, 4, budget)
+        diff = cur - prev
+        assert diff.sum() == 1 and diff.max() == 1 and diff.min() == 0
+        prev = cur
+
+
+def test_equal_prompts_share_evenly_lower_index_first(oracle):
+    # Prompts of one class have identical gain sequences: they differ by at most
+    # one unit and the extra unit sits on the lower indices (the tie rule).
+    rng = np.random.default_rng(21)
+    g0 = 8
+    c = rng.integers(0, g0 + 1, 500).astype(np.int32)
+    for budget in (0, 1, 499, 500, 1234, 4000):
+        delta = oracle.allocate(c, g0, budget)
+        assert delta.sum() == budget
+        for k in range(g0 + 1):
+            d = delta[c == k]
+            if d.size:
+                assert d.max() - d.min() <= 1
+                assert np.all(np.diff(d) <= 0)
+
+
+def test_worked_example_g0_4(oracle):
+    # G0 = 4, uniform prior, c = (0, 2, 4).  Exact gain sequences:
+    #   c=0: 1/6, 5/42, 5/56, ...   c=2: 1/2, 3/14, 3/28, 5/84   c=4: 5/6, 5/42, 5/168
+    # B = 1..4 and 6..7 involve no tie between the prompts still competing, so those
+    # rows follow from the rationals alone.  At B = 5 prompts 0 and 2 tie at 5/42;
+    # either choice is optimal (sum U = 11/6); this build's rule (canonical fp64
+    # gain, then index) is recorded in tests/golden/worked_example_g0_4.txt.
+    c = np.array([0, 2, 4], dtype=np.int32)
+    forced = {0: (0, 0, 0), 1: (0, 0, 1), 2: (0, 1, 1), 3: (0, 2, 1), 4: (1, 2, 1),
+              6: (2, 2, 2), 7: (2, 3, 2)}
+    for budget, want in forced.items():
+        assert tuple(oracle.allocate(c, 4, budget)) == want
+    d5 = tuple(oracle.allocate(c, 4, 5))
+    assert d5 in ((2, 2, 1), (1, 2, 2))
+    ab = [(Fraction(1), Fraction(5)), (Fraction(3), Fraction(3)), (Fraction(5), Fraction(1))]
+    assert sum(exact_utility(a, b, d) for (a, b), d in zip(ab, d5)) == Fraction(11, 6)
+    import os
+    path = os.path.join(os.path.dirname(__file__), "golden", "worked_example_g0_4.txt")
+    rows = [tuple(int(x) for x in line.split()) for line in open(path) if not line.startswith("#")]
+    for budget, d0, d1, d2 in rows:
+        assert tuple(oracle.allocate(c, 4, budget)) == (d0, d1, d2)
+
+
+def test_exchange_condition_at_scale(oracle):
+    # The optimality certificate of App. A is O(N), so it also covers sizes that
+    # enumeration cannot reach.  Gains depend on the class c only: check per class.
+    from paper_2605_07114_amd import workloads as wl
+    for w in (wl.TINY, wl.SMALL, wl.scaled(wl.SKEWED, 8192), wl.scaled(wl.LARGE_ALLOC, 1 << 16)):
+        a = wl.phase_a(w)
+        delta = oracle.allocate(a.c, w.g0, w.budget, delta_max=w.delta_max)
+        assert delta.sum() == w.budget
+        taken, avail = [], []
+        for k in range(w.g0 + 1):
+            d = delta[a.c == k]
+            if not d.size:
+                continue
+            fa, fb = Fraction(1 + k), Fraction(1 + w.g0 - k)
+            if d.max() > 0:
+                taken.append(exact_gain(fa, fb, int(d.max()) - 1))
+            if not (w.delta_max and d.min() >= w.delta_max):
+                avail.append(exact_gain(fa, fb, int(d.min())))
+        assert min(taken) >= max(avail)
+
+
+def test_argument_errors(oracle):
+    c = np.array([0, 1], dtype=np.int32)
+    with pytest.raises(oracle.OracleError) as e:
+        oracle.allocate(np.array([0, 5], dtype=np.int32), 4, 3)
+    assert e.value.code == oracle.ERR_RANGE
+    with pytest.raises(oracle.OracleError):
+        oracle.allocate(c, 4, -1)
+    with pytest.raises(oracle.OracleError):
+        oracle.allocate(np.zeros(0, dtype=np.int32), 4, 1)
+    assert oracle.allocate(np.zeros(0, dtype=np.int32), 4, 0).size == 0
+
+
+def test_group_offsets(oracle):
+    delta = np.array([3, 0, 5, 1], dtype=np.int64)
+    off = oracle.group_offsets(delta, 4)
+    assert off.tolist() == [0, 7, 11, 20, 25]
+    assert np.array_equal(off[1:], np.cumsum(4 + delta))
