@@ -1,0 +1,224 @@
+#!/usr/bin/env python3
+"""Benchmark of the HORA rollout path on one MI355X.
+
+Metric: prompts allocated/s at N = 2^20 (workload "large_alloc": posterior -> gains ->
+allocation -> utilities -> group offsets), and the per-token advantage broadcast in
+GB/s against the HBM peak (workload "large_bcast": allocation -> RLOO and GRPO group
+advantages -> token broadcast, whole path timed, broadcast kernel timed on its own).
+Inputs are seeded synthetic arrays already resident in HBM when timing starts.
+
+Prints one JSON line.  The CPU baseline is the test oracle, timed on this host.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
+
+
+def ensure_library():
+    from paper_2605_07114_amd import build, hora
+    if not os.path.exists(hora.LIB_PATH):
+        build.build_library()
+    return hora.load_library()
+
+
+def timed(torch, fn, steps, warmup):
+    """Wall-clock and HIP-event time of `steps` calls of fn on the current stream."""
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    start.record()
+    for _ in range(steps):
+        fn()
+    stop.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    return wall, start.elapsed_time(stop) * 1e-3
+
+
+def per_launch_events(torch, fn, steps, warmup):
+    """Average duration of one call of fn, from a HIP event pair around every call."""
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    for a, b in pairs:
+        a.record()
+        fn()
+        b.record()
+    torch.cuda.synchronize()
+    ms = np.array([a.elapsed_time(b) for a, b in pairs])
+    return float(ms.mean()) * 1e-3, float(ms.min()) * 1e-3
+
+
+def cpu_baseline(wl, oracle, w_alloc, a_alloc, bcast_inputs):
+    """The oracle as it stands, single thread, on this host."""
+    best = float("inf")
+    reps = 2
+    for _ in range(reps):
+        t0 = time.perf_counter()
+        oracle.allocate(a_alloc.c, w_alloc.g0, w_alloc.budget, delta_max=w_alloc.delta_max)
+        best = min(best, time.perf_counter() - t0)
+    out = {"value": w_alloc.n / best, "unit": "prompts/s", "cores": 1, "kind": "oracle",
+           "sample": f"full {w_alloc.name} (N={w_alloc.n}, B={w_alloc.budget}): posterior + max-heap greedy, "
+                     f"best of {reps}, {best:.3f} s per pass"}
+    w_b, a_b = bcast_inputs                          # the oracle's own pass over the broadcast workload
+    delta = oracle.allocate(a_b.c, w_b.g0, w_b.budget, delta_max=w_b.delta_max)
+    b = wl.phase_b(w_b, a_b, delta)
+    adv = oracle.group_advantage(b.group_off, b.reward, "rloo")
+    n_resp = min(adv.size, 16384)                    # bounded sample of the broadcast workload
+    sub_off = b.tok_off[:n_resp + 1]
+    buf = np.empty(int(sub_off[-1]), dtype=np.float64)
+    t0 = time.perf_counter()
+    oracle.token_broadcast(adv[:n_resp], sub_off, out=buf)
+    dt = time.perf_counter() - t0
+    out["broadcast_GBps"] = buf.size * 8 / dt / 1e9
+    out["broadcast_sample"] = f"first {n_resp} responses of large_bcast, {buf.size} tokens, binary64 stores"
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        return 2
+
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py needs the GPU (there is no CPU fallback)", file=sys.stderr)
+        return 2
+    ensure_library()
+    from paper_2605_07114_amd import hora, workloads as wl
+    torch.cuda.set_device(0)
+    sess = hora.Session("cuda:0")
+    steps, warmup = args.steps, args.warmup
+
+    # ---- workload 1: large allocation (N = 2^20, G0 = 4, B = 4N, no cap) -------------------
+    w1 = wl.LARGE_ALLOC
+    a1 = wl.phase_a(w1)
+    c1 = torch.from_numpy(a1.c).to("cuda:0")
+    delta1 = torch.empty(w1.n, dtype=torch.int32, device="cuda:0")
+    util1 = torch.empty(w1.n, dtype=torch.float64, device="cuda:0")
+    goff1 = torch.empty(w1.n + 1, dtype=torch.int32, device="cuda:0")
+    ws = sess.workspace(w1.n, w1.g0)
+
+    def step_alloc():
+        hora.hora_allocate(c1, w1.g0, w1.budget, delta1, sess.dev_status, ws, util=util1, group_off=goff1)
+
+    wall1, ev1 = timed(torch, step_alloc, steps, warmup)
+    assert sess.status() == 0 and int(delta1.sum()) == w1.budget
+    alloc_bytes = w1.n * (4 + 4 + 8 + 4)      # c in; delta, util, group_off out
+    ms_alloc = wall1 / steps * 1e3
+
+    # ---- workload 2: large broadcast (N = 4096, G0 = 8, B = 8N; ~1.7e8 tokens) ---------------
+    w2 = wl.LARGE_BCAST
+    a2 = wl.phase_a(w2)
+    c2 = torch.from_numpy(a2.c).to("cuda:0")
+    alloc2 = sess.allocate(c2, w2.g0, w2.budget, off_dtype=torch.int32, want_util=False, want_summary=False)
+    b2 = wl.phase_b(w2, a2, alloc2.delta.cpu().numpy())
+    n_resp, n_tok = b2.reward.size, int(b2.tok_off[-1])
+    reward2 = torch.from_numpy(b2.reward.astype(np.float32)).to("cuda:0")
+    tok_off2 = torch.from_numpy(b2.tok_off).to("cuda:0")                     # packed int64 offsets
+    delta2 = torch.empty(w2.n, dtype=torch.int32, device="cuda:0")
+    goff2 = torch.empty(w2.n + 1, dtype=torch.int32, device="cuda:0")
+    adv_rloo = torch.empty(n_resp, dtype=torch.float32, device="cuda:0")
+    adv_grpo = torch.empty(n_resp, dtype=torch.float32, device="cuda:0")
+    tok_rloo = torch.empty(n_tok, dtype=torch.float32, device="cuda:0")
+    tok_grpo = torch.empty(n_tok, dtype=torch.float32, device="cuda:0")
+
+    def step_path():
+        hora.hora_allocate(c2, w2.g0, w2.budget, delta2, sess.dev_status, ws, group_off=goff2)
+        hora.hora_group_advantage(goff2, reward2, adv_rloo, hora.ADV_RLOO, sess.dev_status)
+        hora.hora_group_advantage(goff2, reward2, adv_grpo, hora.ADV_GRPO, sess.dev_status, eps=w2.eps)
+        hora.hora_token_broadcast(adv_rloo, tok_off2, tok_rloo, n_tok, sess.dev_status)
+        hora.hora_token_broadcast(adv_grpo, tok_off2, tok_grpo, n_tok, sess.dev_status)
+
+    wall2, ev2 = timed(torch, step_path, max(steps // 4, 10), max(warmup // 4, 3))
+    steps2 = max(steps // 4, 10)
+    assert sess.status() == 0
+
+    def one_broadcast():
+        hora.hora_token_broadcast(adv_rloo, tok_off2, tok_rloo, n_tok, sess.dev_status)
+
+    bc_mean, bc_min = per_launch_events(torch, one_broadcast, steps2, 3)
+    bcast_bytes = 4 * n_tok + n_resp * (8 + 4)       # float stores; offsets and advantages in
+    bcast_gbs = bcast_bytes / bc_mean / 1e9
+
+    result = {
+        "metric": "prompts allocated/s at N=1M; advantage broadcast GB/s as % of HBM peak",
+        "value": w1.n / (wall1 / steps),
+        "unit": "prompts/s",
+        "n_gpus": 1,
+        "steps": steps,
+        "warmup": warmup,
+        "ms_per_step": ms_alloc,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f64",
+        "data": "synthetic",
+        "config": {
+            "workload": f"large_alloc: N={w1.n} prompts, G0={w1.g0}, budget={w1.budget}, no cap, "
+                        "c ~ Binomial(G0, p), p ~ Beta(0.5, 0.5); outputs int32 delta, f64 utility, int32 group offsets",
+            "method": "class histogram + threshold solve + index-ordered tie pass",
+            "event_ms_per_step": ev1 / steps * 1e3,
+        },
+        "broadcast": {
+            "workload": f"large_bcast: N={w2.n}, G0={w2.g0}, budget={w2.budget}, {n_resp} responses, "
+                        f"{n_tok} tokens, int64 packed offsets, f32 token advantages",
+            "GBps": bcast_gbs,
+            "pct_of_hbm_peak": 100.0 * bcast_gbs / HBM_PEAK_GBS,
+            "kernel_ms_mean": bc_mean * 1e3,
+            "kernel_ms_min": bc_min * 1e3,
+            "whole_path_ms_per_step": wall2 / steps2 * 1e3,
+            "whole_path": "allocate + RLOO and GRPO group advantages + two token broadcasts",
+            "tokens_per_s_whole_path": 2 * n_tok / (wall2 / steps2),
+        },
+        "roofline": {
+            "kernel": "k_token_broadcast<float,float,int64> (large_bcast)",
+            "bound": "hbm",
+            "achieved": bcast_gbs,
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": bcast_gbs / HBM_PEAK_GBS,
+            "traffic": None,
+            "bytes_per_launch": bcast_bytes,
+        },
+        "roofline_allocate": {
+            "kernel": "k_class_hist + k_class_solve + k_alloc_write (large_alloc)",
+            "bound": "hbm",
+            "achieved": alloc_bytes / (ev1 / steps) / 1e9,
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": alloc_bytes / (ev1 / steps) / 1e9 / HBM_PEAK_GBS,
+            "traffic": None,
+            "bytes_per_launch": alloc_bytes,
+        },
+    }
+    if not args.no_cpu_baseline:
+        from oracle import hora_oracle
+        hora_oracle.build()
+        result["cpu_baseline"] = cpu_baseline(wl, hora_oracle, w1, a1, (w2, a2))
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,193 @@
+/*
+ * hora.h -- C ABI of the HORA rollout-layer library for AMD MI355X (gfx950).
+ *
+ * HORA (Hit-Utility Optimal Rollout Allocation) splits the rollouts of one
+ * RLVR training step into G0 pre-rollouts per prompt (Phase A) and a budget of
+ * additional rollouts (Phase B) that is distributed over the prompts so as to
+ * maximise the total posterior "hit utility".  This library holds the
+ * data-parallel part between rollout generation and the policy loss:
+ *
+ *   Phase-A counts c_i -> Beta posterior -> marginal gains -> optimal budgeted
+ *   allocation Delta_i -> variable-size groups G_i = G0 + Delta_i ->
+ *   group-relative advantages (GRPO or RLOO) -> per-token advantages.
+ *
+ * Conventions that hold for every entry point unless it says otherwise:
+ *  - Pointers marked "device" are GPU global memory owned by the caller and
+ *    must stay valid until the work enqueued on `stream` has finished.  The
+ *    library allocates nothing and copies nothing between host and device.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Calls validate their host-visible arguments, enqueue kernels on `stream`
+ *    and return without synchronising.
+ *  - The return value reports argument / launch errors.  Errors that depend on
+ *    device data (a count outside [0, G0], offsets that decrease, ...) are
+ *    reported through `dev_status`, a device int32 that the library only ever
+ *    writes when it finds such an error (it then holds the hora_status code).
+ *    The caller zeroes it once and reads it after synchronising; it is sticky
+ *    across calls.  After a data error the outputs of that call are
+ *    unspecified, but no access leaves the caller's buffers.
+ *  - n = 0 and budget = 0 are valid and give empty / all-zero outputs.
+ */
+#ifndef HORA_H
+#define HORA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    HORA_OK = 0,
+    HORA_ERR_INVALID_ARG = -1, /* null pointer, negative size, unknown enum, misaligned buffer */
+    HORA_ERR_INFEASIBLE = -2,  /* budget cannot be placed: n == 0, or budget > n * delta_max   */
+    HORA_ERR_WORKSPACE = -3,   /* workspace missing or smaller than *_workspace_bytes()        */
+    HORA_ERR_RANGE = -4,       /* device data out of range (via dev_status)                    */
+    HORA_ERR_HIP = -5,         /* a HIP runtime call or kernel launch failed                   */
+    HORA_ERR_UNSUPPORTED = -6, /* size outside what this entry point / method handles          */
+    HORA_ERR_TIMEOUT = -7      /* a bounded device-side wait gave up (via dev_status)          */
+} hora_status;
+
+typedef enum { HORA_ADV_GRPO = 0, HORA_ADV_RLOO = 1 } hora_adv_mode;
+typedef enum { HORA_F32 = 0, HORA_F64 = 1 } hora_ftype;
+typedef enum { HORA_I32 = 0, HORA_I64 = 1 } hora_itype;
+
+/* How hora_allocate finds the allocation.  All methods return bit-identical results. */
+typedef enum {
+    HORA_ALLOC_AUTO = 0,   /* the library picks (CLASS when g0 allows it, else BISECT)             */
+    HORA_ALLOC_CLASS = 1,  /* shared prior only: histogram of c, threshold solved per class       */
+    HORA_ALLOC_BISECT = 2  /* bisection on the gain threshold with per-prompt monotone searches   */
+} hora_alloc_method;
+
+/* Largest G0 the CLASS method handles (one wavefront lane per class c = 0..G0). */
+#define HORA_CLASS_MAX_G0 63
+
+/* Optional device-side report of one allocation (all fields written by the call). */
+typedef struct {
+    double tau;           /* threshold gain: the budget-th largest marginal gain (0 if budget = 0) */
+    int64_t count_gt;     /* number of (prompt, l) pairs whose gain is > tau                       */
+    int64_t tie_units;    /* budget - count_gt: units handed to prompts tied at tau, by index      */
+    int64_t tie_prompts;  /* prompts whose next gain equals tau                                    */
+} hora_alloc_summary;
+
+const char *hora_status_string(int status);
+
+/* Library version, major * 10000 + minor * 100 + patch. */
+int hora_version(void);
+
+/*
+ * Marginal hit utility and hit utility tables (Sec. 3.2, Eq. 3 and Eq. 5; App. A).
+ *
+ * For every posterior (alpha[i], beta[i]), i < n, evaluates
+ *   M_i(l) = B(alpha+1, beta+l) / B(alpha, beta),      l = 0 .. count-1
+ *   U_i(l) = 1 - B(alpha, beta+l) / B(alpha, beta),    l = 0 .. count-1
+ * in binary64 by the paper's recurrences, each step one multiply then one
+ * divide, walked from l = 0:
+ *   s = alpha+beta;  M(0) = alpha/s;  M(l+1) = (M(l) * (beta+l)) / (s + (l+1));
+ *   E(0) = 1;  E(l+1) = (E(l) * (beta+l)) / (s + l);  U(l) = 1 - E(l).
+ * These binary64 values are the "canonical gains" that order the allocation.
+ *
+ * alpha, beta : device, n doubles each, all > 0.
+ * gains       : device out, count*n doubles, l-major: gains[l*n + i] = M_i(l).  Nullable.
+ * util        : device out, count*n doubles, same layout: util[l*n + i] = U_i(l).  Nullable.
+ */
+int hora_marginal_gains(int64_t n, const double *alpha, const double *beta, int32_t count,
+                        double *gains, double *util, void *stream);
+
+/*
+ * Bytes of workspace hora_allocate / hora_allocate_posterior need for n prompts.
+ * The workspace is device memory, 256-byte aligned.  It must be zero-filled once
+ * before its first use; every call leaves it ready for the next one.  Two calls
+ * that may run concurrently need separate workspaces.
+ */
+size_t hora_allocate_workspace_bytes(int64_t n, int32_t g0);
+
+/*
+ * Phase-B allocation under a shared prior (Sec. 3.2 Eq. 2-5, Alg. 1 Phase A/B, Prop. 1).
+ *
+ * Posterior of prompt i: alpha_i = alpha0 + c[i], beta_i = beta0 + g0 - c[i].
+ * Result: delta maximises sum_i U_i(delta_i) subject to sum_i delta_i = budget,
+ * 0 <= delta_i (<= delta_max if delta_max > 0).  By Prop. 1 this is the greedy
+ * allocation, i.e. the `budget` largest elements of {M_i(l)} are selected and
+ * delta_i counts those of prompt i.  The paper's argmax has no tie rule; here
+ * elements are ordered by (canonical gain descending, prompt index ascending),
+ * which makes delta unique and equal to a greedy run that prefers the lower
+ * index among equal gains.
+ *
+ * n, g0     : number of prompts (>= 0) and pre-rollouts per prompt (>= 0).
+ * c         : device, n int32, each in [0, g0] (else HORA_ERR_RANGE in dev_status).
+ * alpha0, beta0 : prior, both > 0 and finite (the paper uses 1, 1).
+ * budget    : Phase-B budget, 0 <= budget < 2^62; need not be a multiple of n.
+ * delta_max : per-prompt cap; <= 0 means none (the paper states none).
+ * method    : hora_alloc_method.
+ * delta     : device out, n int32.
+ * util      : device out, n doubles, U_i(delta_i) by the product recurrence.  Nullable.
+ * group_off : device out, n+1 offsets of type off_t: exclusive prefix sums of
+ *             g0 + delta_i (group i holds responses group_off[i] .. group_off[i+1]-1,
+ *             pre-rollouts first).  Nullable.  With HORA_I32 the total n*g0 + budget
+ *             must be < 2^31 (else HORA_ERR_INVALID_ARG).
+ * summary   : device out, one hora_alloc_summary.  Nullable.
+ * dev_status: device, one int32, see the conventions above.  Required.
+ * workspace : device, >= hora_allocate_workspace_bytes(n, g0).
+ */
+int hora_allocate(int64_t n, int32_t g0, const int32_t *c, double alpha0, double beta0,
+                  int64_t budget, int32_t delta_max, int32_t method, int32_t *delta, double *util,
+                  void *group_off, int32_t off_t, hora_alloc_summary *summary,
+                  int32_t *dev_status, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Phase-B allocation for per-prompt posteriors (App. D, prompt-conditioned prior:
+ * alpha_i = s_i p_i + c_i, beta_i = s_i (1 - p_i) + G0 - c_i are formed by the caller).
+ * Same result definition, outputs and conventions as hora_allocate; always uses the
+ * bisection method.  g0 only enters group_off (pass 0 to get prefix sums of delta).
+ *
+ * alpha, beta : device, n doubles each, all > 0 and finite (else HORA_ERR_RANGE in dev_status).
+ */
+int hora_allocate_posterior(int64_t n, int32_t g0, const double *alpha, const double *beta,
+                            int64_t budget, int32_t delta_max, int32_t *delta, double *util,
+                            void *group_off, int32_t off_t, hora_alloc_summary *summary,
+                            int32_t *dev_status, void *workspace, size_t workspace_bytes,
+                            void *stream);
+
+/*
+ * Group-relative advantages over variable-size groups (Sec. 3.1 for GRPO; Sec. 4
+ * "compatible with GRPO-family objectives" and App. E for RLOO).
+ *
+ * Group g holds responses group_off[g] .. group_off[g+1]-1 (G_g of them).
+ *   GRPO: adv_j = (R_j - mean) / (std + eps), mean and std over the group's rewards,
+ *         std with divisor G_g - ddof.  A group whose rewards are all equal (zero
+ *         empirical std) gets exactly 0, as does a group with G_g - ddof <= 0.
+ *   RLOO: adv_j = R_j - (S - R_j) / (G_g - 1), S the group's reward sum; G_g = 1 gives 0.
+ * Sums run over the group in storage order in binary64; the result is rounded once
+ * when stored as float.
+ *
+ * group_off : device, n_groups+1 offsets of type off_t, group_off[0] = 0, non-decreasing
+ *             (else HORA_ERR_RANGE in dev_status).
+ * reward, adv : device, n_resp values of type ft (HORA_F32 or HORA_F64); n_resp must
+ *             equal group_off[n_groups] (else HORA_ERR_RANGE in dev_status).
+ * eps >= 0; ddof is 0 or 1 (both ignored for RLOO).
+ */
+int hora_group_advantage(int64_t n_groups, const void *group_off, int32_t off_t, int64_t n_resp,
+                         const void *reward, void *adv, int32_t ft, int32_t mode, double eps,
+                         int32_t ddof, int32_t *dev_status, void *stream);
+
+/*
+ * Per-token advantages (Sec. 3.1: the advantage in the objective carries a token
+ * index but does not depend on it): tok_adv[t] = adv[j] for tok_off[j] <= t < tok_off[j+1].
+ *
+ * adv      : device, n_resp values of type adv_t.
+ * tok_off  : device, n_resp+1 packed token offsets of type off_t, tok_off[0] = 0,
+ *            non-decreasing, tok_off[n_resp] = n_tokens (else HORA_ERR_RANGE in
+ *            dev_status).  Zero-length responses are allowed.
+ * tok_adv  : device out, n_tokens values of type out_t (a binary64 advantage stored as
+ *            float is rounded to nearest once).  Must be aligned to its element size;
+ *            16-byte alignment gives the fastest path.
+ */
+int hora_token_broadcast(int64_t n_resp, const void *adv, int32_t adv_t, const void *tok_off,
+                         int32_t off_t, void *tok_adv, int32_t out_t, int64_t n_tokens,
+                         int32_t *dev_status, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HORA_H */

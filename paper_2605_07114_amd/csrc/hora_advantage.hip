@@ -1,0 +1,147 @@
+// Group-relative advantages over variable-size groups (Sec. 3.1 GRPO; Sec. 4 / App. E RLOO).
+//
+// A sub-group of L lanes (L a power of two, chosen from the mean group size) owns one
+// group: the lanes stride over the group's rewards, so a wavefront reads a contiguous
+// run of the reward array, and combine their partial sums with a butterfly.  All sums
+// are binary64; a float output is rounded once at the store.
+#include <hip/hip_runtime.h>
+
+#include <climits>
+#include <cstdint>
+
+#include "hora.h"
+#include "hora_device.h"
+
+namespace hora {
+
+template <int L>
+__device__ __forceinline__ double sub_sum(double v) {
+#pragma unroll
+    for (int d = L / 2; d > 0; d >>= 1) v += __shfl_xor(v, d, L);
+    return v;
+}
+
+template <int L>
+__device__ __forceinline__ int sub_and(int v) {
+#pragma unroll
+    for (int d = L / 2; d > 0; d >>= 1) v &= __shfl_xor(v, d, L);
+    return v;
+}
+
+template <typename F, typename I, int L>
+__global__ __launch_bounds__(kThreads) void k_group_adv(long long n_groups, const I* __restrict__ off,
+                                                        long long n_resp, const F* __restrict__ reward,
+                                                        F* __restrict__ adv, int mode, double eps, int ddof,
+                                                        int32_t* dev_status) {
+    const int sub = (int)(threadIdx.x % L);
+    const long long g = ((long long)blockIdx.x * kThreads + threadIdx.x) / L;
+    const bool live = g < n_groups;
+    long long lo = 0, hi = 0;
+    if (live) {
+        lo = (long long)off[g];
+        hi = (long long)off[g + 1];
+        bool bad = lo < 0 || hi < lo || hi > n_resp;
+        if (g == 0 && lo != 0) bad = true;
+        if (g == n_groups - 1 && hi != n_resp) bad = true;
+        if (bad) {
+            if (sub == 0) report(dev_status, HORA_ERR_RANGE);
+            lo = lo < 0 ? 0 : (lo > n_resp ? n_resp : lo);
+            hi = hi < lo ? lo : (hi > n_resp ? n_resp : hi);
+        }
+    }
+    const long long size = hi - lo;
+
+    double sum = 0.0;
+    int equal = 1;
+    const double first = size > 0 ? (double)reward[lo] : 0.0;
+    for (long long j = lo + sub; j < hi; j += L) {
+        const double x = (double)reward[j];
+        sum += x;
+        equal &= (x == first) ? 1 : 0;
+    }
+    sum = sub_sum<L>(sum);
+    equal = sub_and<L>(equal);
+
+    if (mode == HORA_ADV_RLOO) {
+        const double denom = (double)(size - 1);
+        for (long long j = lo + sub; j < hi; j += L) {
+            const double x = (double)reward[j];
+            adv[j] = (F)(size == 1 ? 0.0 : x - (sum - x) / denom);
+        }
+        return;
+    }
+
+    const bool zero = equal || (size - ddof <= 0);
+    const double mean = size > 0 ? sum / (double)size : 0.0;
+    double ss = 0.0;
+    if (!zero) {
+        for (long long j = lo + sub; j < hi; j += L) {
+            const double d = (double)reward[j] - mean;
+            ss += d * d;
+        }
+    }
+    ss = sub_sum<L>(ss);
+    const double scale = zero ? 1.0 : sqrt(ss / (double)(size - ddof)) + eps;
+    for (long long j = lo + sub; j < hi; j += L) {
+        const double x = (double)reward[j];
+        adv[j] = (F)(zero ? 0.0 : (x - mean) / scale);
+    }
+}
+
+template <typename F, typename I>
+static int launch_adv(int64_t n_groups, const void* off, int64_t n_resp, const void* reward, void* adv, int mode,
+                      double eps, int ddof, int32_t* dev_status, hipStream_t stream) {
+    const long long mean_size = n_groups > 0 ? n_resp / n_groups : 0;
+    int lanes = 1;
+    while (lanes < kWave && lanes * 2 <= mean_size) lanes *= 2;   // largest power of two <= mean size
+    if (lanes < 2) lanes = 2;
+#define HORA_LAUNCH_ADV(LL)                                                                                   \
+    do {                                                                                                      \
+        const long long blocks = (n_groups * LL + kThreads - 1) / kThreads;                                   \
+        if (blocks > INT_MAX) return HORA_ERR_UNSUPPORTED;                                                    \
+        hipLaunchKernelGGL((k_group_adv<F, I, LL>), dim3((unsigned)blocks), dim3(kThreads), 0, stream,         \
+                           (long long)n_groups, (const I*)off, (long long)n_resp, (const F*)reward, (F*)adv,  \
+                           mode, eps, ddof, dev_status);                                                      \
+    } while (0)
+    switch (lanes) {
+        case 2: HORA_LAUNCH_ADV(2); break;
+        case 4: HORA_LAUNCH_ADV(4); break;
+        case 8: HORA_LAUNCH_ADV(8); break;
+        case 16: HORA_LAUNCH_ADV(16); break;
+        case 32: HORA_LAUNCH_ADV(32); break;
+        default: HORA_LAUNCH_ADV(64); break;
+    }
+#undef HORA_LAUNCH_ADV
+    return hipGetLastError() == hipSuccess ? HORA_OK : HORA_ERR_HIP;
+}
+
+}  // namespace hora
+
+using namespace hora;
+
+extern "C" int hora_group_advantage(int64_t n_groups, const void* group_off, int32_t off_t, int64_t n_resp,
+                                    const void* reward, void* adv, int32_t ft, int32_t mode, double eps,
+                                    int32_t ddof, int32_t* dev_status, void* stream) {
+    if (n_groups < 0 || n_resp < 0 || !dev_status) return HORA_ERR_INVALID_ARG;
+    if (off_t != HORA_I32 && off_t != HORA_I64) return HORA_ERR_INVALID_ARG;
+    if (ft != HORA_F32 && ft != HORA_F64) return HORA_ERR_INVALID_ARG;
+    if (mode != HORA_ADV_GRPO && mode != HORA_ADV_RLOO) return HORA_ERR_INVALID_ARG;
+    if (!(eps >= 0.0) || (ddof != 0 && ddof != 1)) return HORA_ERR_INVALID_ARG;
+    if (n_groups == 0) return n_resp == 0 ? HORA_OK : HORA_ERR_INVALID_ARG;
+    if (!group_off) return HORA_ERR_INVALID_ARG;
+    if (n_resp > 0 && (!reward || !adv)) return HORA_ERR_INVALID_ARG;
+    if (off_t == HORA_I32 && n_resp >= (1ll << 31)) return HORA_ERR_INVALID_ARG;
+    const uintptr_t fmask = ft == HORA_F32 ? 3 : 7, imask = off_t == HORA_I32 ? 3 : 7;
+    if ((reinterpret_cast<uintptr_t>(reward) & fmask) || (reinterpret_cast<uintptr_t>(adv) & fmask) ||
+        (reinterpret_cast<uintptr_t>(group_off) & imask))
+        return HORA_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    if (ft == HORA_F32) {
+        if (off_t == HORA_I32)
+            return launch_adv<float, int32_t>(n_groups, group_off, n_resp, reward, adv, mode, eps, ddof, dev_status, s);
+        return launch_adv<float, long long>(n_groups, group_off, n_resp, reward, adv, mode, eps, ddof, dev_status, s);
+    }
+    if (off_t == HORA_I32)
+        return launch_adv<double, int32_t>(n_groups, group_off, n_resp, reward, adv, mode, eps, ddof, dev_status, s);
+    return launch_adv<double, long long>(n_groups, group_off, n_resp, reward, adv, mode, eps, ddof, dev_status, s);
+}

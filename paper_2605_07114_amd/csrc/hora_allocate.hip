@@ -1,0 +1,907 @@
+// Phase-B allocation kernels and entry points (Sec. 3.2, Alg. 1, Prop. 1, App. A).
+//
+// The allocation is the set of the `budget` largest marginal gains over all
+// (prompt, l) pairs, ordered by (canonical binary64 gain descending, prompt index
+// ascending).  Because every prompt's gain sequence decreases strictly, this set is
+// described by a threshold tau (the budget-th largest gain): prompt i gets
+//     delta_i = #{l : M_i(l) > tau} + [M_i(k_i) == tau and rank_i < r],
+// where rank_i counts the prompts tied at tau with a lower index and
+// r = budget - sum_i #{l : M_i(l) > tau}.
+//
+// Two ways to find tau:
+//  CLASS  (shared prior): gains depend on c_i only, so a histogram over c and a
+//         class-level greedy over at most G0+1 sequences solve the threshold.
+//  BISECT (any posterior): bisection on the bit pattern of tau; every step counts
+//         #{(i,l) : M_i(l) > tau} with a monotone walk per prompt.
+// Both end in the same scan + write pass that resolves the ties by prompt index.
+#include <hip/hip_runtime.h>
+
+#include <climits>
+#include <cmath>
+#include <cstdint>
+
+#include "hora.h"
+#include "hora_device.h"
+
+namespace hora {
+
+constexpr int kItems = 4;                     // consecutive prompts per thread and tile
+constexpr int kTile = kThreads * kItems;      // 1024 prompts
+constexpr int kMaxBlocks = 1024;              // workgroups of the allocation passes
+constexpr int kMaxClasses = HORA_CLASS_MAX_G0 + 1;
+constexpr int kBisectSteps = 64;              // enough for any 63-bit bracket
+constexpr unsigned kTiedBit = 0x80000000u;
+
+struct AllocHeader {              // 256 bytes at the start of the workspace, zero at rest
+    unsigned long long lo_inv;    // ~bits of min_i M_i(W-1), gathered with atomicMax
+    unsigned long long hi;        // bits of max_i M_i(0), gathered with atomicMax
+    unsigned long long count;     // pairs counted so far in the running bisection step
+    unsigned int ticket;          // workgroups that have contributed to `count`
+    unsigned int pad0;
+    unsigned long long lo_cur;    // bracket: count_gt(lo_cur) >= budget
+    unsigned long long hi_cur;    // bracket: count_gt(hi_cur) <  budget
+    unsigned long long pad[26];
+};
+static_assert(sizeof(AllocHeader) == 256, "header size");
+
+struct AllocSolution {
+    double tau;
+    long long count_gt;
+    long long r;                  // units for the prompts tied at tau
+    long long tie_prompts;
+    int k[kMaxClasses];           // CLASS: #{l : M_c(l) > tau}
+    int tied[kMaxClasses];        // CLASS: M_c(k_c) == tau and k_c below the cap
+    double u0[kMaxClasses];       // CLASS: U_c(k_c)
+    double u1[kMaxClasses];       // CLASS: U_c(k_c + 1)
+    long long pad[28];
+};
+static_assert(sizeof(AllocSolution) % 256 == 0, "solution size");
+
+struct Plan {
+    long long chunk;  // prompts per workgroup, a multiple of kTile
+    int nb;           // workgroups
+};
+
+static Plan make_plan(int64_t n) {
+    long long tiles = (n + kTile - 1) / kTile;
+    long long tpb = (tiles + kMaxBlocks - 1) / kMaxBlocks;
+    if (tpb < 1) tpb = 1;
+    Plan p;
+    p.chunk = tpb * kTile;
+    p.nb = (int)((n + p.chunk - 1) / p.chunk);
+    if (p.nb < 1) p.nb = 1;
+    return p;
+}
+
+static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+struct Workspace {
+    AllocHeader* header;
+    AllocSolution* sol;
+    int* block_hist;        // [nb][g0+1]
+    long long* block_ksum;  // [nb] sums, then exclusive prefixes, of k_i
+    long long* block_tied;  // [nb] sums, then exclusive prefixes, of tied flags
+    size_t bytes;
+};
+
+// The arrays are sized for kMaxBlocks workgroups whatever n is, so that a workspace
+// that served one batch size serves every other one.
+static Workspace carve(void* base, int32_t g0) {
+    struct { int nb; } p = {kMaxBlocks};
+    Workspace w;
+    char* ptr = (char*)base;
+    size_t off = 0;
+    w.header = (AllocHeader*)(ptr + off);
+    off += sizeof(AllocHeader);
+    w.sol = (AllocSolution*)(ptr + off);
+    off += sizeof(AllocSolution);
+    w.block_hist = (int*)(ptr + off);
+    off += align256((size_t)p.nb * (size_t)(g0 + 1) * sizeof(int));
+    w.block_ksum = (long long*)(ptr + off);
+    off += align256((size_t)p.nb * sizeof(long long));
+    w.block_tied = (long long*)(ptr + off);
+    off += align256((size_t)p.nb * sizeof(long long));
+    w.bytes = off;
+    return w;
+}
+
+// ----------------------------------------------------------------------------------
+// Posterior sources (Sec. 3.2 Eq. 2; App. D for the per-prompt form).
+// ----------------------------------------------------------------------------------
+struct CountsSource {
+    const int32_t* c;
+    int g0;
+    double alpha0, beta0;
+    __device__ __forceinline__ bool load(long long i, double& a, double& b) const {
+        int x = c[i];
+        bool ok = (x >= 0) && (x <= g0);
+        x = x < 0 ? 0 : (x > g0 ? g0 : x);
+        a = alpha0 + (double)x;
+        b = beta0 + (double)(g0 - x);
+        return ok;
+    }
+};
+
+struct PosteriorSource {
+    const double* alpha;
+    const double* beta;
+    __device__ __forceinline__ bool load(long long i, double& a, double& b) const {
+        a = alpha[i];
+        b = beta[i];
+        bool ok = (a > 0.0) && (b > 0.0) && (a < INFINITY) && (b < INFINITY);
+        if (!ok) { a = 1.0; b = 1.0; }
+        return ok;
+    }
+};
+
+// ----------------------------------------------------------------------------------
+// Gain / utility tables (Eq. 3, Eq. 5): one thread per posterior, l-major output so
+// that the stores of a wavefront are contiguous.
+// ----------------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void k_gain_table(long long n, const double* __restrict__ alpha,
+                                                         const double* __restrict__ beta, int count,
+                                                         double* __restrict__ gains,
+                                                         double* __restrict__ util) {
+    long long i = (long long)blockIdx.x * kThreads + threadIdx.x;
+    if (i >= n) return;
+    double a = alpha[i], b = beta[i];
+    double s = a + b;
+    double m = gain_first(a, s);
+    double e = 1.0;
+    double lf = 0.0;
+    for (int l = 0; l < count; ++l) {
+        if (gains) gains[(long long)l * n + i] = m;
+        if (util) util[(long long)l * n + i] = 1.0 - e;
+        m = gain_next(m, b, s, lf);
+        e = surv_next(e, b, s, lf);
+        lf += 1.0;
+    }
+}
+
+// ----------------------------------------------------------------------------------
+// CLASS pass 1: per-workgroup histogram of c.  Lane k of every wavefront accumulates
+// the count of class k from wavefront ballots.
+// ----------------------------------------------------------------------------------
+__device__ __forceinline__ void load_counts4(const int32_t* __restrict__ c, long long pos, long long end,
+                                             bool vec_ok, int (&v)[kItems]) {
+    if (vec_ok && pos + kItems <= end) {
+        v4i x = *reinterpret_cast<const v4i*>(c + pos);
+        v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w;
+    } else {
+#pragma unroll
+        for (int j = 0; j < kItems; ++j) v[j] = (pos + j < end) ? c[pos + j] : -1;
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void k_class_hist(const int32_t* __restrict__ c, long long n, int g0,
+                                                         long long chunk, int* __restrict__ block_hist,
+                                                         int32_t* dev_status) {
+    __shared__ int s_cnt[kWaves][kWave];
+    const long long base = (long long)blockIdx.x * chunk;
+    const long long end = base + chunk < n ? base + chunk : n;
+    const bool vec_ok = (reinterpret_cast<uintptr_t>(c) & 15) == 0;
+    const int lane = lane_id();
+    int cnt = 0;
+    bool bad = false;
+    for (long long t0 = base; t0 < end; t0 += kTile) {
+        const long long pos = t0 + (long long)threadIdx.x * kItems;
+        int v[kItems];
+        load_counts4(c, pos, end, vec_ok, v);
+#pragma unroll
+        for (int j = 0; j < kItems; ++j) {
+            if (pos + j < end) {
+                if (v[j] < 0 || v[j] > g0) { bad = true; v[j] = v[j] < 0 ? 0 : g0; }
+            } else {
+                v[j] = -1;
+            }
+        }
+        for (int k = 0; k <= g0; ++k) {
+            int pop = 0;
+#pragma unroll
+            for (int j = 0; j < kItems; ++j) pop += __popcll(__ballot(v[j] == k));
+            if (lane == k) cnt += pop;
+        }
+    }
+    s_cnt[wave_id()][lane] = cnt;
+    __syncthreads();
+    if (threadIdx.x <= (unsigned)g0) {
+        int tot = 0;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) tot += s_cnt[w][threadIdx.x];
+        block_hist[(long long)blockIdx.x * (g0 + 1) + threadIdx.x] = tot;
+    }
+    if (bad) report(dev_status, HORA_ERR_RANGE);
+}
+
+// ----------------------------------------------------------------------------------
+// Exclusive scans of the per-workgroup sums (k and tied counts), in place.
+// Returns the totals to every thread.
+// ----------------------------------------------------------------------------------
+__device__ void scan_block_sums(int nb, long long* block_ksum, long long* block_tied, long long& ksum_total,
+                                long long& tied_total) {
+    __shared__ long long s_scan[kWaves];
+    long long kcarry = 0, tcarry = 0;
+    for (int b0 = 0; b0 < nb; b0 += kThreads) {
+        int b = b0 + (int)threadIdx.x;
+        long long kv = b < nb ? block_ksum[b] : 0;
+        long long tv = b < nb ? block_tied[b] : 0;
+        long long ktot, ttot;
+        long long kex = block_excl_scan<long long>(kv, s_scan, ktot);
+        long long tex = block_excl_scan<long long>(tv, s_scan, ttot);
+        if (b < nb) {
+            block_ksum[b] = kcarry + kex;
+            block_tied[b] = tcarry + tex;
+        }
+        kcarry += ktot;
+        tcarry += ttot;
+    }
+    ksum_total = kcarry;
+    tied_total = tcarry;
+}
+
+// ----------------------------------------------------------------------------------
+// CLASS pass 2 (one workgroup): total histogram, class-level greedy, block prefixes.
+//
+// Lane c of wavefront 0 owns class c: its posterior, its position l_c in the gain
+// sequence and the current gain.  Each round takes the largest current gain over the
+// classes that still have prompts and room below the cap; all classes tied at that
+// value advance together, consuming n_c units each.  The round in which the remaining
+// budget no longer covers the tied classes fixes tau; the leftover r units go to the
+// tied prompts in index order (resolved by the write pass).  This is Alg. 1's greedy
+// loop run on classes instead of prompts: prompts of one class have identical
+// sequences, so the greedy hands them their l-th unit in one uninterrupted run.
+// ----------------------------------------------------------------------------------
+__device__ __forceinline__ unsigned long long read_lane_u64(unsigned long long v, int src) {
+    unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(v & 0xffffffffull), src);
+    unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(v >> 32), src);
+    return ((unsigned long long)hi << 32) | lo;
+}
+
+__global__ __launch_bounds__(kThreads) void k_class_solve(int g0, double alpha0, double beta0, long long budget,
+                                                          int cap, int nb, const int* __restrict__ block_hist,
+                                                          AllocSolution* __restrict__ sol,
+                                                          long long* __restrict__ block_ksum,
+                                                          long long* __restrict__ block_tied,
+                                                          hora_alloc_summary* __restrict__ summary,
+                                                          int32_t* dev_status) {
+    __shared__ long long s_part[kWaves][kWave];
+    __shared__ long long s_n[kWave];
+    __shared__ int s_k[kWave];
+    __shared__ int s_tied[kWave];
+    const int nc = g0 + 1;
+    const int lane = lane_id();
+    const int w = wave_id();
+
+    {   // total histogram
+        long long acc = 0;
+        if (lane < nc)
+            for (int b = w; b < nb; b += kWaves) acc += block_hist[(long long)b * nc + lane];
+        s_part[w][lane] = acc;
+        __syncthreads();
+        if (threadIdx.x < kWave) {
+            long long tot = 0;
+#pragma unroll
+            for (int i = 0; i < kWaves; ++i) tot += s_part[i][threadIdx.x];
+            s_n[threadIdx.x] = tot;
+        }
+        __syncthreads();
+    }
+
+    if (w == 0) {
+        const bool has = lane < nc;
+        const long long ncount = has ? s_n[lane] : 0;
+        const double a = alpha0 + (double)(has ? lane : 0);
+        const double b = beta0 + (double)(has ? g0 - lane : 0);
+        const double s = a + b;
+        double g = gain_first(a, s);
+        double e = 1.0;
+        double lf = 0.0;
+        long long k = 0;
+        const long long cap_eff = cap > 0 ? (long long)cap : LLONG_MAX;
+        long long remaining = budget;
+        unsigned long long tau_bits = 0;
+        long long tie_prompts = 0;
+        bool tied = false;
+        while (remaining > 0) {
+            const bool active = has && ncount > 0 && k < cap_eff;
+            const unsigned long long key = active ? gain_bits(g) : 0ull;
+            unsigned long long best = 0;
+            for (int j = 0; j < nc; ++j) {
+                unsigned long long kj = read_lane_u64(key, j);
+                best = kj > best ? kj : best;
+            }
+            if (best == 0) {  // nothing left to give to: cannot happen when budget <= n * cap
+                report(dev_status, HORA_ERR_INFEASIBLE);
+                break;
+            }
+            const bool at_best = active && key == best;
+            const unsigned long long mine = at_best ? (unsigned long long)ncount : 0ull;
+            long long tsum = 0;
+            for (int j = 0; j < nc; ++j) tsum += (long long)read_lane_u64(mine, j);
+            tau_bits = best;
+            if (tsum >= remaining) {  // the budget ends inside this round
+                tied = at_best;
+                tie_prompts = tsum;
+                break;
+            }
+            remaining -= tsum;
+            if (at_best) {
+                e = surv_next(e, b, s, lf);
+                g = gain_next(g, b, s, lf);
+                lf += 1.0;
+                k += 1;
+            }
+        }
+        if (budget <= 0) remaining = 0;
+        s_k[lane] = has ? (int)k : 0;
+        s_tied[lane] = (has && tied) ? 1 : 0;
+        sol->k[lane] = has ? (int)k : 0;
+        sol->tied[lane] = (has && tied) ? 1 : 0;
+        sol->u0[lane] = 1.0 - e;
+        sol->u1[lane] = 1.0 - surv_next(e, b, s, lf);
+        if (lane == 0) {
+            const double tau = budget > 0 ? __longlong_as_double((long long)tau_bits) : 0.0;
+            const long long r = (tie_prompts > 0) ? remaining : 0;
+            sol->tau = tau;
+            sol->r = r;
+            sol->tie_prompts = tie_prompts;
+            sol->count_gt = budget - r;
+            if (summary) {
+                summary->tau = tau;
+                summary->count_gt = budget - r;
+                summary->tie_units = r;
+                summary->tie_prompts = tie_prompts;
+            }
+        }
+    }
+    __syncthreads();
+
+    // per-workgroup sums of k and of tied prompts, then their exclusive prefixes
+    for (int b = (int)threadIdx.x; b < nb; b += kThreads) {
+        long long ks = 0, ts = 0;
+        for (int cc = 0; cc < nc; ++cc) {
+            long long h = block_hist[(long long)b * nc + cc];
+            ks += h * s_k[cc];
+            ts += h * s_tied[cc];
+        }
+        block_ksum[b] = ks;
+        block_tied[b] = ts;
+    }
+    __syncthreads();
+    long long ksum_total, tied_total;
+    scan_block_sums(nb, block_ksum, block_tied, ksum_total, tied_total);
+}
+
+// ----------------------------------------------------------------------------------
+// Final pass: resolve ties by prompt index and write delta, util, group offsets.
+//
+// kClass: (k, tied, U) come from the class tables indexed by c[i].
+// else  : delta[i] holds k_i with the tied flag in bit 31 and util[i] holds the
+//         survival product E_i(k_i), both left there by k_bisect_finalize.
+// kOff  : 0 no offsets, 1 int32 offsets, 2 int64 offsets.
+// ----------------------------------------------------------------------------------
+template <class Src, bool kClass, int kOff>
+__global__ __launch_bounds__(kThreads) void k_alloc_write(Src src, const int32_t* __restrict__ c, long long n,
+                                                          int g0, long long chunk,
+                                                          const AllocSolution* __restrict__ sol,
+                                                          const long long* __restrict__ block_ksum,
+                                                          const long long* __restrict__ block_tied,
+                                                          int32_t* __restrict__ delta, double* __restrict__ util,
+                                                          void* __restrict__ group_off) {
+    __shared__ int s_k[kWave];
+    __shared__ int s_tied[kWave];
+    __shared__ double s_u0[kWave];
+    __shared__ double s_u1[kWave];
+    __shared__ int s_scan_i[kWaves];
+    __shared__ long long s_scan_l[kWaves];
+
+    if (kClass) {
+        if (threadIdx.x < kWave) {
+            s_k[threadIdx.x] = sol->k[threadIdx.x];
+            s_tied[threadIdx.x] = sol->tied[threadIdx.x];
+            s_u0[threadIdx.x] = sol->u0[threadIdx.x];
+            s_u1[threadIdx.x] = sol->u1[threadIdx.x];
+        }
+        __syncthreads();
+    }
+    const long long r = sol->r;
+    const long long base = (long long)blockIdx.x * chunk;
+    const long long end = base + chunk < n ? base + chunk : n;
+    long long rank_base = block_tied[blockIdx.x];
+    long long ks_base = block_ksum[blockIdx.x];
+    const bool c_vec = kClass && (reinterpret_cast<uintptr_t>(c) & 15) == 0;
+    const bool d_vec = (reinterpret_cast<uintptr_t>(delta) & 15) == 0;
+    const bool u_vec = (reinterpret_cast<uintptr_t>(util) & 15) == 0;
+    const bool o_vec = (reinterpret_cast<uintptr_t>(group_off) & 15) == 0;
+
+    for (long long t0 = base; t0 < end; t0 += kTile) {
+        const long long pos = t0 + (long long)threadIdx.x * kItems;
+        const bool full = pos + kItems <= end;
+        int kk[kItems], td[kItems], cls[kItems];
+        if (kClass) {
+            load_counts4(c, pos, end, c_vec, cls);
+#pragma unroll
+            for (int j = 0; j < kItems; ++j) {
+                if (pos + j < end) {
+                    int x = cls[j] < 0 ? 0 : (cls[j] > g0 ? g0 : cls[j]);
+                    cls[j] = x;
+                    kk[j] = s_k[x];
+                    td[j] = s_tied[x];
+                } else {
+                    cls[j] = 0; kk[j] = 0; td[j] = 0;
+                }
+            }
+        } else {
+            unsigned raw[kItems];
+            if (full && d_vec) {
+                v4i x = *reinterpret_cast<const v4i*>(delta + pos);
+                raw[0] = (unsigned)x.x; raw[1] = (unsigned)x.y; raw[2] = (unsigned)x.z; raw[3] = (unsigned)x.w;
+            } else {
+#pragma unroll
+                for (int j = 0; j < kItems; ++j) raw[j] = (pos + j < end) ? (unsigned)delta[pos + j] : 0u;
+            }
+#pragma unroll
+            for (int j = 0; j < kItems; ++j) {
+                kk[j] = (int)(raw[j] & ~kTiedBit);
+                td[j] = (raw[j] & kTiedBit) ? 1 : 0;
+                cls[j] = 0;
+            }
+        }
+        const int tcnt = td[0] + td[1] + td[2] + td[3];
+        int t_total;
+        const int t_excl = block_excl_scan<int>(tcnt, s_scan_i, t_total);
+        long long ks_excl = 0, ks_total = 0;
+        if (kOff != 0) {
+            const long long ks = (long long)kk[0] + kk[1] + kk[2] + kk[3];
+            ks_excl = block_excl_scan<long long>(ks, s_scan_l, ks_total);
+        }
+        int dd[kItems];
+        bool win[kItems];
+        long long off[kItems + 1];
+        long long rank = rank_base + t_excl;       // tied prompts with a lower index
+        long long kprior = ks_base + ks_excl;      // sum of k over prompts with a lower index
+#pragma unroll
+        for (int j = 0; j < kItems; ++j) {
+            off[j] = (long long)g0 * (pos + j) + kprior + (rank < r ? rank : r);
+            win[j] = td[j] && rank < r;
+            dd[j] = kk[j] + (win[j] ? 1 : 0);
+            rank += td[j];
+            kprior += kk[j];
+        }
+        off[kItems] = (long long)g0 * (pos + kItems) + kprior + (rank < r ? rank : r);
+
+        if (full && d_vec) {
+            v4i x = {dd[0], dd[1], dd[2], dd[3]};
+            *reinterpret_cast<v4i*>(delta + pos) = x;
+        } else {
+#pragma unroll
+            for (int j = 0; j < kItems; ++j)
+                if (pos + j < end) delta[pos + j] = dd[j];
+        }
+        if (util) {
+            double uu[kItems];
+#pragma unroll
+            for (int j = 0; j < kItems; ++j) {
+                if (kClass) {
+                    uu[j] = win[j] ? s_u1[cls[j]] : s_u0[cls[j]];
+                } else {
+                    double e = 1.0;
+                    if (pos + j < end) {
+                        e = util[pos + j];
+                        if (win[j]) {
+                            double a, b;
+                            src.load(pos + j, a, b);
+                            e = surv_next(e, b, a + b, (double)kk[j]);
+                        }
+                    }
+                    uu[j] = 1.0 - e;
+                }
+            }
+            if (full && u_vec) {
+                v2d x0 = {uu[0], uu[1]}, x1 = {uu[2], uu[3]};
+                *reinterpret_cast<v2d*>(util + pos) = x0;
+                *reinterpret_cast<v2d*>(util + pos + 2) = x1;
+            } else {
+#pragma unroll
+                for (int j = 0; j < kItems; ++j)
+                    if (pos + j < end) util[pos + j] = uu[j];
+            }
+        }
+        if (kOff == 1) {
+            int32_t* go = reinterpret_cast<int32_t*>(group_off);
+            if (full && o_vec) {
+                v4i x = {(int)off[0], (int)off[1], (int)off[2], (int)off[3]};
+                *reinterpret_cast<v4i*>(go + pos) = x;
+            } else {
+#pragma unroll
+                for (int j = 0; j < kItems; ++j)
+                    if (pos + j < end) go[pos + j] = (int32_t)off[j];
+            }
+#pragma unroll
+            for (int j = 0; j < kItems; ++j)
+                if (pos + j == n - 1) go[n] = (int32_t)off[j + 1];
+        } else if (kOff == 2) {
+            long long* go = reinterpret_cast<long long*>(group_off);
+            if (full && o_vec) {
+                v2l x0 = {off[0], off[1]}, x1 = {off[2], off[3]};
+                *reinterpret_cast<v2l*>(go + pos) = x0;
+                *reinterpret_cast<v2l*>(go + pos + 2) = x1;
+            } else {
+#pragma unroll
+                for (int j = 0; j < kItems; ++j)
+                    if (pos + j < end) go[pos + j] = off[j];
+            }
+#pragma unroll
+            for (int j = 0; j < kItems; ++j)
+                if (pos + j == n - 1) go[n] = off[j + 1];
+        }
+        rank_base += t_total;
+        ks_base += ks_total;
+    }
+}
+
+// ----------------------------------------------------------------------------------
+// BISECT pass 0: bracket of tau.  With W = ceil(budget / n) every prompt has at least
+// W gains >= lo = min_i M_i(W-1), so count_ge(lo) >= budget and tau >= lo; and no
+// gain exceeds hi = max_i M_i(0).  Both are gathered with integer atomicMax.
+// ----------------------------------------------------------------------------------
+template <class Src>
+__global__ __launch_bounds__(kThreads) void k_bisect_bracket(Src src, long long n, long long chunk, long long w_steps,
+                                                             AllocHeader* __restrict__ hdr, int32_t* dev_status) {
+    __shared__ unsigned long long s_red[kWaves];
+    const long long base = (long long)blockIdx.x * chunk;
+    const long long end = base + chunk < n ? base + chunk : n;
+    unsigned long long hi = 0, lo_inv = 0;
+    bool bad = false;
+    for (long long i = base + threadIdx.x; i < end; i += kThreads) {
+        double a, b;
+        bad |= !src.load(i, a, b);
+        const double s = a + b;
+        double g = gain_first(a, s);
+        unsigned long long gb = gain_bits(g);
+        hi = gb > hi ? gb : hi;
+        double lf = 0.0;
+        for (long long l = 1; l < w_steps; ++l) {
+            g = gain_next(g, b, s, lf);
+            lf += 1.0;
+        }
+        gb = ~gain_bits(g);
+        lo_inv = gb > lo_inv ? gb : lo_inv;
+    }
+    hi = wave_max_u64(hi);
+    lo_inv = wave_max_u64(lo_inv);
+    if (lane_id() == 0) s_red[wave_id()] = hi;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        unsigned long long m = 0;
+        for (int i = 0; i < kWaves; ++i) m = s_red[i] > m ? s_red[i] : m;
+        atomicMax(&hdr->hi, m);
+    }
+    __syncthreads();
+    if (lane_id() == 0) s_red[wave_id()] = lo_inv;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        unsigned long long m = 0;
+        for (int i = 0; i < kWaves; ++i) m = s_red[i] > m ? s_red[i] : m;
+        atomicMax(&hdr->lo_inv, m);
+    }
+    if (bad) report(dev_status, HORA_ERR_RANGE);
+}
+
+// Number of gains of one prompt that exceed tau, at most `limit`; also leaves the next
+// gain (the first one <= tau) in `g`, l as a double in `lf` and, if asked, the survival
+// product E(k) in `e`.
+template <bool kSurvival>
+__device__ __forceinline__ long long walk_above(double a, double b, unsigned long long tau_bits, long long limit,
+                                                double& g, double& lf, double& e) {
+    const double s = a + b;
+    g = gain_first(a, s);
+    lf = 0.0;
+    e = 1.0;
+    long long k = 0;
+    while (k < limit && gain_bits(g) > tau_bits) {
+        if (kSurvival) e = surv_next(e, b, s, lf);
+        g = gain_next(g, b, s, lf);
+        lf += 1.0;
+        k += 1;
+    }
+    return k;
+}
+
+// ----------------------------------------------------------------------------------
+// BISECT step: count the pairs above the midpoint of the bracket.  The workgroup that
+// contributes last narrows the bracket for the next launch and clears the counters.
+// Invariant: count_gt(lo_cur) >= budget > count_gt(hi_cur).  Step 0 seeds the bracket
+// from pass 0.  Once hi_cur - lo_cur <= 1, tau = hi_cur and later launches return at once.
+// ----------------------------------------------------------------------------------
+template <class Src>
+__global__ __launch_bounds__(kThreads) void k_bisect_step(Src src, long long n, long long chunk, long long budget,
+                                                          long long limit, int step, AllocHeader* __restrict__ hdr) {
+    __shared__ long long s_red[kWaves];
+    unsigned long long lo, hi;
+    if (step == 0) {
+        lo = ~hdr->lo_inv - 1ull;
+        hi = hdr->hi;
+    } else {
+        lo = hdr->lo_cur;
+        hi = hdr->hi_cur;
+    }
+    if (hi - lo <= 1ull) {
+        if (step == 0 && blockIdx.x == 0 && threadIdx.x == 0) { hdr->lo_cur = lo; hdr->hi_cur = hi; }
+        return;
+    }
+    const unsigned long long mid = lo + (hi - lo) / 2ull;
+    const long long base = (long long)blockIdx.x * chunk;
+    const long long end = base + chunk < n ? base + chunk : n;
+    long long cnt = 0;
+    for (long long i = base + threadIdx.x; i < end; i += kThreads) {
+        double a, b, g, lf, e;
+        src.load(i, a, b);
+        cnt += walk_above<false>(a, b, mid, limit, g, lf, e);
+        if (cnt > budget) cnt = budget;  // only the comparison with budget matters
+    }
+    long long tot = block_sum<long long>(cnt, s_red);
+    if (threadIdx.x == 0) {
+        if (tot > budget) tot = budget;
+        atomicAdd(&hdr->count, (unsigned long long)tot);
+        __threadfence();
+        unsigned int t = atomicAdd(&hdr->ticket, 1u);
+        if (t == gridDim.x - 1) {
+            __threadfence();
+            unsigned long long total = atomicAdd(&hdr->count, 0ull);
+            if (total < (unsigned long long)budget) hi = mid; else lo = mid;
+            hdr->lo_cur = lo;
+            hdr->hi_cur = hi;
+            hdr->count = 0ull;
+            hdr->ticket = 0u;
+        }
+    }
+}
+
+// ----------------------------------------------------------------------------------
+// BISECT finalize: with tau = hi_cur, k_i = #{l : M_i(l) > tau} and the tied flag go
+// to delta[i] (flag in bit 31), the survival product E_i(k_i) to util[i]; per-workgroup
+// sums go to block_ksum / block_tied.
+// ----------------------------------------------------------------------------------
+template <class Src>
+__global__ __launch_bounds__(kThreads) void k_bisect_finalize(Src src, long long n, long long chunk, long long budget,
+                                                              long long limit, const AllocHeader* __restrict__ hdr,
+                                                              int32_t* __restrict__ delta, double* __restrict__ util,
+                                                              long long* __restrict__ block_ksum,
+                                                              long long* __restrict__ block_tied) {
+    __shared__ long long s_red[kWaves];
+    const unsigned long long tau_bits = budget > 0 ? hdr->hi_cur : ~0ull;
+    const long long base = (long long)blockIdx.x * chunk;
+    const long long end = base + chunk < n ? base + chunk : n;
+    long long ks = 0, ts = 0;
+    for (long long i = base + threadIdx.x; i < end; i += kThreads) {
+        double a, b, g, lf, e;
+        src.load(i, a, b);
+        const long long k = walk_above<true>(a, b, tau_bits, limit, g, lf, e);
+        const bool tied = (k < limit) && (gain_bits(g) == tau_bits);
+        delta[i] = (int32_t)((unsigned)k | (tied ? kTiedBit : 0u));
+        if (util) util[i] = e;
+        ks += k;
+        ts += tied ? 1 : 0;
+    }
+    ks = block_sum<long long>(ks, s_red);
+    ts = block_sum<long long>(ts, s_red);
+    if (threadIdx.x == 0) {
+        block_ksum[blockIdx.x] = ks;
+        block_tied[blockIdx.x] = ts;
+    }
+}
+
+// BISECT scan (one workgroup): prefixes over the workgroups, r, the report, and the
+// header back to its rest state.
+__global__ __launch_bounds__(kThreads) void k_bisect_scan(int nb, long long budget, AllocHeader* __restrict__ hdr,
+                                                          AllocSolution* __restrict__ sol,
+                                                          long long* __restrict__ block_ksum,
+                                                          long long* __restrict__ block_tied,
+                                                          hora_alloc_summary* __restrict__ summary,
+                                                          int32_t* dev_status) {
+    long long ksum_total, tied_total;
+    scan_block_sums(nb, block_ksum, block_tied, ksum_total, tied_total);
+    if (threadIdx.x == 0) {
+        const unsigned long long tau_bits = hdr->hi_cur;
+        const long long r = budget - ksum_total;
+        const double tau = budget > 0 ? __longlong_as_double((long long)tau_bits) : 0.0;
+        if (r < 0 || r > tied_total) report(dev_status, HORA_ERR_RANGE);  // invalid posteriors upstream
+        sol->tau = tau;
+        sol->r = r;
+        sol->count_gt = ksum_total;
+        sol->tie_prompts = tied_total;
+        if (summary) {
+            summary->tau = tau;
+            summary->count_gt = ksum_total;
+            summary->tie_units = r;
+            summary->tie_prompts = tied_total;
+        }
+        hdr->lo_inv = 0ull;
+        hdr->hi = 0ull;
+        hdr->count = 0ull;
+        hdr->ticket = 0u;
+        hdr->lo_cur = 0ull;
+        hdr->hi_cur = 0ull;
+    }
+}
+
+template <typename T>
+__global__ void k_store_one(T* p, T v) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) *p = v;
+}
+
+__global__ void k_zero_summary(hora_alloc_summary* s) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) { s->tau = 0.0; s->count_gt = 0; s->tie_units = 0; s->tie_prompts = 0; }
+}
+
+// ----------------------------------------------------------------------------------
+// Host side
+// ----------------------------------------------------------------------------------
+static int check_launch() { return hipGetLastError() == hipSuccess ? HORA_OK : HORA_ERR_HIP; }
+
+struct CommonArgs {
+    int64_t n;
+    int32_t g0;
+    int64_t budget;
+    int32_t delta_max;
+    int32_t* delta;
+    double* util;
+    void* group_off;
+    int32_t off_t;
+    hora_alloc_summary* summary;
+    int32_t* dev_status;
+    void* workspace;
+    size_t workspace_bytes;
+    hipStream_t stream;
+};
+
+static int validate_common(const CommonArgs& a) {
+    if (a.n < 0 || a.g0 < 0 || a.budget < 0) return HORA_ERR_INVALID_ARG;
+    if (!a.dev_status) return HORA_ERR_INVALID_ARG;
+    if (a.n > 0 && !a.delta) return HORA_ERR_INVALID_ARG;
+    if (a.group_off && a.off_t != HORA_I32 && a.off_t != HORA_I64) return HORA_ERR_INVALID_ARG;
+    if (a.budget >= (1ll << 52)) return HORA_ERR_UNSUPPORTED;
+    if (a.n >= (1ll << 40)) return HORA_ERR_UNSUPPORTED;
+    if ((reinterpret_cast<uintptr_t>(a.delta) & 3) || (reinterpret_cast<uintptr_t>(a.util) & 7) ||
+        (reinterpret_cast<uintptr_t>(a.dev_status) & 3))
+        return HORA_ERR_INVALID_ARG;
+    if (a.group_off) {
+        const uintptr_t mask = a.off_t == HORA_I32 ? 3 : 7;
+        if (reinterpret_cast<uintptr_t>(a.group_off) & mask) return HORA_ERR_INVALID_ARG;
+    }
+    if (a.budget > 0 && a.n == 0) return HORA_ERR_INFEASIBLE;
+    if (a.delta_max > 0 && a.budget > 0 && (a.budget + a.delta_max - 1) / a.delta_max > a.n)
+        return HORA_ERR_INFEASIBLE;
+    // delta is int32: the largest value a prompt can get must fit
+    const long long per_prompt_max = a.delta_max > 0 ? (a.budget < a.delta_max ? a.budget : a.delta_max) : a.budget;
+    if (per_prompt_max >= (1ll << 31) - 1) return HORA_ERR_UNSUPPORTED;
+    if (a.group_off && a.off_t == HORA_I32) {
+        const long long total = a.n * (long long)a.g0 + a.budget;
+        if (total >= (1ll << 31)) return HORA_ERR_INVALID_ARG;
+    }
+    return HORA_OK;
+}
+
+static int handle_empty(const CommonArgs& a) {  // n == 0 (budget == 0 checked before)
+    if (a.group_off) {
+        if (a.off_t == HORA_I32) hipLaunchKernelGGL(k_store_one<int32_t>, 1, 1, 0, a.stream, (int32_t*)a.group_off, 0);
+        else hipLaunchKernelGGL(k_store_one<long long>, 1, 1, 0, a.stream, (long long*)a.group_off, 0ll);
+    }
+    if (a.summary) hipLaunchKernelGGL(k_zero_summary, 1, 1, 0, a.stream, a.summary);
+    return check_launch();
+}
+
+template <class Src, bool kClass>
+static int launch_write(const Src& src, const int32_t* c, const CommonArgs& a, const Plan& p, const Workspace& w) {
+    const int mode = a.group_off ? (a.off_t == HORA_I32 ? 1 : 2) : 0;
+#define HORA_LAUNCH_WRITE(M)                                                                              \
+    hipLaunchKernelGGL((k_alloc_write<Src, kClass, M>), dim3(p.nb), dim3(kThreads), 0, a.stream, src, c, \
+                       (long long)a.n, (int)a.g0, p.chunk, w.sol, w.block_ksum, w.block_tied, a.delta,   \
+                       a.util, a.group_off)
+    if (mode == 0) HORA_LAUNCH_WRITE(0);
+    else if (mode == 1) HORA_LAUNCH_WRITE(1);
+    else HORA_LAUNCH_WRITE(2);
+#undef HORA_LAUNCH_WRITE
+    return check_launch();
+}
+
+template <class Src>
+static int run_bisect(const Src& src, const CommonArgs& a, const Plan& p, const Workspace& w) {
+    const long long n = a.n;
+    long long limit = a.delta_max > 0 ? (long long)a.delta_max : a.budget;
+    if (limit > a.budget) limit = a.budget;
+    if (a.budget > 0) {
+        const long long w_steps = (a.budget + n - 1) / n;
+        hipLaunchKernelGGL((k_bisect_bracket<Src>), dim3(p.nb), dim3(kThreads), 0, a.stream, src, n, p.chunk,
+                           w_steps, w.header, a.dev_status);
+        for (int step = 0; step < kBisectSteps; ++step)
+            hipLaunchKernelGGL((k_bisect_step<Src>), dim3(p.nb), dim3(kThreads), 0, a.stream, src, n, p.chunk,
+                               (long long)a.budget, limit, step, w.header);
+    }
+    hipLaunchKernelGGL((k_bisect_finalize<Src>), dim3(p.nb), dim3(kThreads), 0, a.stream, src, n, p.chunk,
+                       (long long)a.budget, limit, w.header, a.delta, a.util, w.block_ksum, w.block_tied);
+    hipLaunchKernelGGL(k_bisect_scan, dim3(1), dim3(kThreads), 0, a.stream, p.nb, (long long)a.budget, w.header,
+                       w.sol, w.block_ksum, w.block_tied, a.summary, a.dev_status);
+    int rc = check_launch();
+    if (rc != HORA_OK) return rc;
+    return launch_write<Src, false>(src, nullptr, a, p, w);
+}
+
+}  // namespace hora
+
+using namespace hora;
+
+extern "C" {
+
+size_t hora_allocate_workspace_bytes(int64_t n, int32_t g0) {
+    if (n < 0 || g0 < 0) return 0;
+    Workspace w = carve(nullptr, g0);
+    return w.bytes;
+}
+
+int hora_marginal_gains(int64_t n, const double* alpha, const double* beta, int32_t count, double* gains,
+                        double* util, void* stream) {
+    if (n < 0 || count < 0) return HORA_ERR_INVALID_ARG;
+    if (n == 0 || count == 0 || (!gains && !util)) return HORA_OK;
+    if (!alpha || !beta) return HORA_ERR_INVALID_ARG;
+    const long long blocks = (n + kThreads - 1) / kThreads;
+    if (blocks > INT_MAX) return HORA_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(k_gain_table, dim3((unsigned)blocks), dim3(kThreads), 0, (hipStream_t)stream, (long long)n,
+                       alpha, beta, (int)count, gains, util);
+    return check_launch();
+}
+
+int hora_allocate(int64_t n, int32_t g0, const int32_t* c, double alpha0, double beta0, int64_t budget,
+                  int32_t delta_max, int32_t method, int32_t* delta, double* util, void* group_off, int32_t off_t,
+                  hora_alloc_summary* summary, int32_t* dev_status, void* workspace, size_t workspace_bytes,
+                  void* stream) {
+    CommonArgs a{n, g0, budget, delta_max, delta, util, group_off, off_t, summary, dev_status,
+                 workspace, workspace_bytes, (hipStream_t)stream};
+    int rc = validate_common(a);
+    if (rc != HORA_OK) return rc;
+    if (!(alpha0 > 0.0) || !(beta0 > 0.0) || !std::isfinite(alpha0) || !std::isfinite(beta0))
+        return HORA_ERR_INVALID_ARG;
+    if (method != HORA_ALLOC_AUTO && method != HORA_ALLOC_CLASS && method != HORA_ALLOC_BISECT)
+        return HORA_ERR_INVALID_ARG;
+    if (method == HORA_ALLOC_CLASS && g0 > HORA_CLASS_MAX_G0) return HORA_ERR_UNSUPPORTED;
+    if (method == HORA_ALLOC_AUTO) method = g0 <= HORA_CLASS_MAX_G0 ? HORA_ALLOC_CLASS : HORA_ALLOC_BISECT;
+    if (n == 0) return handle_empty(a);
+    if (!c || (reinterpret_cast<uintptr_t>(c) & 3)) return HORA_ERR_INVALID_ARG;
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255)) return HORA_ERR_WORKSPACE;
+    Workspace w = carve(workspace, g0);
+    if (workspace_bytes < w.bytes) return HORA_ERR_WORKSPACE;
+    const Plan p = make_plan(n);
+    CountsSource src{c, g0, alpha0, beta0};
+    if (method == HORA_ALLOC_BISECT) return run_bisect(src, a, p, w);
+
+    hipLaunchKernelGGL(k_class_hist, dim3(p.nb), dim3(kThreads), 0, a.stream, c, (long long)n, (int)g0, p.chunk,
+                       w.block_hist, dev_status);
+    hipLaunchKernelGGL(k_class_solve, dim3(1), dim3(kThreads), 0, a.stream, (int)g0, alpha0, beta0,
+                       (long long)budget, (int)(delta_max > 0 ? delta_max : 0), p.nb, w.block_hist, w.sol,
+                       w.block_ksum, w.block_tied, summary, dev_status);
+    rc = check_launch();
+    if (rc != HORA_OK) return rc;
+    return launch_write<CountsSource, true>(src, c, a, p, w);
+}
+
+int hora_allocate_posterior(int64_t n, int32_t g0, const double* alpha, const double* beta, int64_t budget,
+                            int32_t delta_max, int32_t* delta, double* util, void* group_off, int32_t off_t,
+                            hora_alloc_summary* summary, int32_t* dev_status, void* workspace,
+                            size_t workspace_bytes, void* stream) {
+    CommonArgs a{n, g0, budget, delta_max, delta, util, group_off, off_t, summary, dev_status,
+                 workspace, workspace_bytes, (hipStream_t)stream};
+    int rc = validate_common(a);
+    if (rc != HORA_OK) return rc;
+    if (n == 0) return handle_empty(a);
+    if (!alpha || !beta || (reinterpret_cast<uintptr_t>(alpha) & 7) || (reinterpret_cast<uintptr_t>(beta) & 7))
+        return HORA_ERR_INVALID_ARG;
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255)) return HORA_ERR_WORKSPACE;
+    Workspace w = carve(workspace, g0);
+    if (workspace_bytes < w.bytes) return HORA_ERR_WORKSPACE;
+    const Plan p = make_plan(n);
+    PosteriorSource src{alpha, beta};
+    return run_bisect(src, a, p, w);
+}
+
+}  // extern "C"

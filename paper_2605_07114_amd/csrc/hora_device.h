@@ -1,0 +1,104 @@
+// Device-side helpers shared by the HORA kernels (gfx950, wave64).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "hora.h"
+
+namespace hora {
+
+constexpr int kWave = 64;
+constexpr int kThreads = 256;              // threads per workgroup in every kernel here
+constexpr int kWaves = kThreads / kWave;   // 4
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef double v2d __attribute__((ext_vector_type(2)));
+typedef long long v2l __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & (kWave - 1)); }
+__device__ __forceinline__ int wave_id() { return (int)(threadIdx.x >> 6); }
+
+// Positive binary64 values order like their bit patterns read as unsigned integers.
+__device__ __forceinline__ unsigned long long gain_bits(double g) {
+    return (unsigned long long)__double_as_longlong(g);
+}
+
+// Marginal-gain recurrence (Sec. 3.2, stable update below Eq. 5).  One multiply, then
+// one divide per step; `lf` is l as a double, `s` is alpha+beta.  The order of the
+// operations is part of the result: these values break ties between prompts.
+__device__ __forceinline__ double gain_first(double a, double s) { return a / s; }
+__device__ __forceinline__ double gain_next(double m, double b, double s, double lf) {
+    return (m * (b + lf)) / (s + (lf + 1.0));
+}
+// Survival product of the hit utility (App. A): E(l+1) = E(l) (beta+l)/(alpha+beta+l).
+__device__ __forceinline__ double surv_next(double e, double b, double s, double lf) {
+    return (e * (b + lf)) / (s + lf);
+}
+
+template <typename T>
+__device__ __forceinline__ T wave_incl_scan(T v) {
+    const int lane = lane_id();
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        T o = __shfl_up(v, d, kWave);
+        if (lane >= d) v += o;
+    }
+    return v;
+}
+
+template <typename T>
+__device__ __forceinline__ T wave_sum(T v) {
+#pragma unroll
+    for (int d = kWave / 2; d > 0; d >>= 1) v += __shfl_xor(v, d, kWave);
+    return v;
+}
+
+__device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long v) {
+#pragma unroll
+    for (int d = kWave / 2; d > 0; d >>= 1) {
+        unsigned long long o = (unsigned long long)__shfl_xor((long long)v, d, kWave);
+        v = o > v ? o : v;
+    }
+    return v;
+}
+
+// Exclusive scan over the kThreads threads of a workgroup; `total` gets the sum.
+// `lds` points at kWaves elements of LDS that the caller may reuse afterwards.
+template <typename T>
+__device__ __forceinline__ T block_excl_scan(T v, T* lds, T& total) {
+    T inc = wave_incl_scan(v);
+    const int w = wave_id();
+    if (lane_id() == kWave - 1) lds[w] = inc;
+    __syncthreads();
+    T base = 0, tot = 0;
+#pragma unroll
+    for (int i = 0; i < kWaves; ++i) {
+        T x = lds[i];
+        if (i < w) base += x;
+        tot += x;
+    }
+    __syncthreads();
+    total = tot;
+    return base + inc - v;
+}
+
+template <typename T>
+__device__ __forceinline__ T block_sum(T v, T* lds) {
+    v = wave_sum(v);
+    if (lane_id() == 0) lds[wave_id()] = v;
+    __syncthreads();
+    T tot = 0;
+#pragma unroll
+    for (int i = 0; i < kWaves; ++i) tot += lds[i];
+    __syncthreads();
+    return tot;
+}
+
+__device__ __forceinline__ void report(int32_t* dev_status, int code) {
+    // every writer stores an error code; which one lands is immaterial
+    *reinterpret_cast<volatile int32_t*>(dev_status) = code;
+}
+
+}  // namespace hora

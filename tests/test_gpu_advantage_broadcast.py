@@ -1,0 +1,226 @@
+"""GPU parity: hora_group_advantage and hora_token_broadcast against the CPU oracle,
+through the C ABI (Sec. 3.1; Sec. 4 / App. E).  Tolerances: 1e-12 relative for binary64
+outputs, 1e-6 for float outputs; the broadcast is a copy and must be bit-exact."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+RTOL64, RTOL32 = 1e-12, 1e-6
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    from paper_2605_07114_amd import hora
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    hora.load_library()
+    return hora.Session("cuda:0"), torch, hora
+
+
+def dev(torch, a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+
+
+def check_advantage(gpu, oracle, group_off, reward64, ftype, itype, mode, eps=0.0, ddof=0):
+    sess, torch, hora = gpu
+    fdt = {"f32": np.float32, "f64": np.float64}[ftype]
+    idt = {"i32": np.int32, "i64": np.int64}[itype]
+    reward = reward64.astype(fdt)
+    want = oracle.group_advantage(group_off, reward.astype(np.float64), mode, eps=eps, ddof=ddof)
+    m = {"grpo": hora.ADV_GRPO, "rloo": hora.ADV_RLOO}[mode]
+    print(f"group_advantage groups={group_off.size - 1} resp={reward.size} {ftype} {itype} {mode}", flush=True)
+    got = sess.group_advantage(dev(torch, group_off.astype(idt)), dev(torch, reward), m, eps=eps, ddof=ddof)
+    assert sess.status() == 0
+    got = got.cpu().numpy()
+    assert got.dtype == fdt
+    if ftype == "f64":
+        np.testing.assert_allclose(got, want, rtol=RTOL64, atol=RTOL64)   # |x-y| <= tol * max(1, |y|)
+    else:
+        np.testing.assert_allclose(got, want.astype(np.float32), rtol=RTOL32, atol=RTOL32)
+    if mode == "grpo":
+        assert np.array_equal(got == 0, want == 0)      # zero-variance groups are exactly zero
+    return got, want
+
+
+@pytest.mark.parametrize("name", ["tiny", "small", "skewed", "large_bcast"])
+def test_advantage_parity_on_the_workloads(gpu, oracle, name):
+    from paper_2605_07114_amd import workloads as wl
+    w = wl.WORKLOADS[name]
+    a = wl.phase_a(w)
+    delta = oracle.allocate(a.c, w.g0, w.budget, delta_max=w.delta_max)
+    b = wl.phase_b(w, a, delta, with_tokens=False)
+    # parity, then invariants on the GPU result (RLOO sums to zero per group; GRPO has zero group mean)
+    sizes = np.diff(b.group_off)
+    gid = np.repeat(np.arange(w.n), sizes)
+    tol = 1e-5 if w.float_type == "f32" else 1e-11
+    for mode in w.modes:
+        got, _ = check_advantage(gpu, oracle, b.group_off, b.reward, w.float_type, w.group_off_type, mode,
+                                 eps=w.eps)
+        sums = np.bincount(gid, weights=got.astype(np.float64), minlength=w.n)
+        assert np.abs(sums).max() <= tol * sizes.max()
+
+
+def test_advantage_general_rewards_modes_and_types(gpu, oracle):
+    rng = np.random.default_rng(31)
+    for n_groups, lo, hi in ((1, 1, 1), (1, 700, 700), (257, 1, 3), (5000, 1, 40), (300, 30, 900), (6, 3000, 9000)):
+        sizes = rng.integers(lo, hi + 1, n_groups)
+        off = np.zeros(n_groups + 1, dtype=np.int64)
+        np.cumsum(sizes, out=off[1:])
+        reward = rng.normal(size=off[-1])
+        for ftype in ("f64", "f32"):
+            for itype in ("i32", "i64"):
+                check_advantage(gpu, oracle, off, reward, ftype, itype, "rloo")
+                for ddof in (0, 1):
+                    for eps in (0.0, 1e-6):
+                        check_advantage(gpu, oracle, off, reward, ftype, itype, "grpo", eps=eps, ddof=ddof)
+
+
+def test_advantage_edge_groups(gpu, oracle):
+    # empty groups, singletons, zero-variance groups whose mean is not representable,
+    # rewards in {0, 1/2, 1}
+    off = np.array([0, 0, 1, 1, 4, 6, 6, 10, 13, 13], dtype=np.int64)
+    reward = np.array([1.0, 0.1, 0.1, 0.1, 1.0, 1.0, 0.0, 0.5, 1.0, 0.5, 0.3, 0.3, 0.3])
+    for ftype in ("f64", "f32"):
+        for mode in ("grpo", "rloo"):
+            for eps in (0.0, 1e-6):
+                got, want = check_advantage(gpu, oracle, off, reward, ftype, "i64", mode, eps=eps)
+                if mode == "grpo":
+                    assert np.all(got[[0, 1, 2, 3, 4, 5, 10, 11, 12]] == 0)
+    from paper_2605_07114_amd import workloads as wl
+    w = wl.TINY
+    a = wl.phase_a(w)
+    delta = oracle.allocate(a.c, w.g0, w.budget)
+    b = wl.phase_b(w, a, delta, half_rewards=True, with_tokens=False)
+    for mode in ("grpo", "rloo"):
+        check_advantage(gpu, oracle, b.group_off, b.reward, "f64", "i64", mode, eps=1e-6)
+
+
+def test_advantage_bad_offsets_are_reported(gpu):
+    sess, torch, hora = gpu
+    reward = torch.ones(10, dtype=torch.float64, device="cuda:0")
+    for off in ([0, 4, 3, 10], [1, 4, 6, 10], [0, 4, 6, 9], [0, 4, 60, 10]):
+        sess.group_advantage(torch.tensor(off, dtype=torch.int64, device="cuda:0"), reward, hora.ADV_GRPO)
+        assert sess.status() == hora.ERR_RANGE
+        sess.dev_status.zero_()
+
+
+# ---------------------------------------------------------------------------------
+# token broadcast
+# ---------------------------------------------------------------------------------
+def run_broadcast(gpu, adv, tok_off, out_dtype, itype, skew=0):
+    sess, torch, hora = gpu
+    idt = {"i32": np.int32, "i64": np.int64}[itype]
+    total = int(tok_off[-1])
+    tdt = {"f32": torch.float32, "f64": torch.float64}[out_dtype]
+    buf = torch.full((total + skew + 5,), float("nan"), dtype=tdt, device="cuda:0")
+    out = buf[skew:skew + total]
+    print(f"token_broadcast resp={adv.size} tokens={total} {adv.dtype}->{out_dtype} {itype} skew={skew}", flush=True)
+    hora.hora_token_broadcast(dev(torch, adv), dev(torch, tok_off.astype(idt)), out, total, sess.dev_status)
+    assert sess.status() == 0
+    return buf
+
+
+def check_broadcast(gpu, oracle, adv, tok_off, out_dtype="f32", itype="i64", skew=0):
+    buf = run_broadcast(gpu, adv, tok_off, out_dtype, itype, skew)
+    total = int(tok_off[-1])
+    host = buf.cpu().numpy()
+    ndt = {"f32": np.float32, "f64": np.float64}[out_dtype]
+    want = oracle.token_broadcast(adv.astype(np.float64), tok_off).astype(ndt)
+    assert np.array_equal(host[skew:skew + total], want)
+    assert np.isnan(host[:skew]).all() and np.isnan(host[skew + total:]).all()   # nothing outside
+
+
+def lengths_to_off(lengths):
+    off = np.zeros(lengths.size + 1, dtype=np.int64)
+    np.cumsum(lengths, out=off[1:])
+    return off
+
+
+def test_broadcast_parity_tiny_and_small(gpu, oracle):
+    from paper_2605_07114_amd import workloads as wl
+    for w in (wl.TINY, wl.SMALL):
+        a = wl.phase_a(w)
+        delta = oracle.allocate(a.c, w.g0, w.budget, delta_max=w.delta_max)
+        b = wl.phase_b(w, a, delta)
+        for mode in w.modes:
+            adv = oracle.group_advantage(b.group_off, b.reward, mode, eps=w.eps)
+            adv = adv.astype(wl.np_float(w.float_type))
+            check_broadcast(gpu, oracle, adv, b.tok_off, out_dtype=w.token_type, itype=w.tok_off_type)
+
+
+def test_broadcast_shapes_and_edges(gpu, oracle):
+    rng = np.random.default_rng(41)
+    cases = {
+        "one token": np.array([1]),
+        "one long response": np.array([200001]),
+        "zero-length runs": np.concatenate([np.zeros(5000, dtype=np.int64), [3], np.zeros(4000, dtype=np.int64),
+                                            rng.integers(0, 3, 30000), [70000], np.zeros(17, dtype=np.int64)]),
+        "all empty but one": np.concatenate([np.zeros(100, dtype=np.int64), [1]]),
+        "tiny segments": rng.integers(1, 4, 200000),          # > 2048 responses per tile
+        "ones": np.ones(100000, dtype=np.int64),
+        "mixed": rng.integers(0, 40000, 300),
+        "ragged tail": np.array([16384 * 3 + 1]),
+        "exact tiles": np.array([16384, 16384, 8192, 8192]),
+    }
+    for name, lengths in cases.items():
+        off = lengths_to_off(lengths.astype(np.int64))
+        adv = rng.normal(size=lengths.size)
+        print("case:", name, flush=True)
+        check_broadcast(gpu, oracle, adv, off, "f64", "i64")
+        check_broadcast(gpu, oracle, adv.astype(np.float32), off, "f32", "i32")
+        check_broadcast(gpu, oracle, adv, off, "f32", "i64")       # rounded once to float
+    # output buffers that do not start on a 16-byte boundary
+    lengths = rng.integers(0, 3000, 500)
+    off = lengths_to_off(lengths)
+    adv = rng.normal(size=500)
+    for skew in (1, 2, 3):
+        check_broadcast(gpu, oracle, adv.astype(np.float32), off, "f32", "i64", skew=skew)
+    check_broadcast(gpu, oracle, adv, off, "f64", "i64", skew=1)
+    # nothing to write
+    sess, torch, hora = gpu
+    hora.hora_token_broadcast(dev(torch, adv[:3]), torch.zeros(4, dtype=torch.int64, device="cuda:0"),
+                              torch.zeros(0, dtype=torch.float32, device="cuda:0"), 0, sess.dev_status)
+    assert sess.status() == 0
+
+
+def test_broadcast_bad_offsets_are_reported(gpu):
+    sess, torch, hora = gpu
+    adv = torch.ones(3, dtype=torch.float32, device="cuda:0")
+    out = torch.zeros(100, dtype=torch.float32, device="cuda:0")
+    for off in ([0, 50, 40, 100], [5, 50, 60, 100], [0, 50, 60, 90]):
+        hora.hora_token_broadcast(adv, torch.tensor(off, dtype=torch.int64, device="cuda:0"), out, 100,
+                                  sess.dev_status)
+        assert sess.status() == hora.ERR_RANGE
+        sess.dev_status.zero_()
+
+
+@pytest.mark.parametrize("name", ["large_bcast", "skewed"])
+def test_broadcast_full_size_windows(gpu, oracle, name):
+    """Full-size runs in the launch shape the benchmark times: windows of responses are
+    compared element by element with the oracle, the rest through properties."""
+    from paper_2605_07114_amd import workloads as wl
+    sess, torch, hora = gpu
+    w = wl.WORKLOADS[name]
+    a = wl.phase_a(w)
+    delta = oracle.allocate(a.c, w.g0, w.budget, delta_max=w.delta_max)
+    b = wl.phase_b(w, a, delta)
+    adv = oracle.group_advantage(b.group_off, b.reward, "rloo").astype(np.float32)
+    total = int(b.tok_off[-1])
+    buf = run_broadcast(gpu, adv, b.tok_off, "f32", w.tok_off_type)
+    assert not bool(torch.isnan(buf[:total]).any())            # every token written
+    assert bool(torch.isnan(buf[total:]).all())
+    rng = np.random.default_rng(43)
+    r = adv.size
+    starts = [0, r - 3000] + rng.integers(0, r - 3000, 12).tolist()
+    for j0 in starts:
+        j1 = j0 + 3000
+        t0, t1 = int(b.tok_off[j0]), int(b.tok_off[j1])
+        want = oracle.token_broadcast(adv[j0:j1].astype(np.float64), b.tok_off[j0:j1 + 1] - t0)
+        got = buf[t0:t1].cpu().numpy()
+        assert np.array_equal(got, want.astype(np.float32)), (name, j0)
+    # sum over tokens = sum_j adv_j * len_j (binary64 on both sides)
+    got_sum = float(buf[:total].double().sum())
+    want_sum = float(np.dot(adv.astype(np.float64), b.lengths.astype(np.float64)))
+    scale = float(np.dot(np.abs(adv).astype(np.float64), b.lengths.astype(np.float64)))
+    assert abs(got_sum - want_sum) <= 1e-9 * scale
