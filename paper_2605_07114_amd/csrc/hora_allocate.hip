@@ -84,10 +84,11 @@ struct Workspace {
     size_t bytes;
 };
 
-// The arrays are sized for kMaxBlocks workgroups whatever n is, so that a workspace
-// that served one batch size serves every other one.
-static Workspace carve(void* base, int32_t g0) {
+// The arrays are sized for kMaxBlocks workgroups and kMaxClasses classes whatever n and
+// g0 are, so that a workspace that served one batch serves every other one.
+static Workspace carve(void* base) {
     struct { int nb; } p = {kMaxBlocks};
+    const int g0 = kMaxClasses - 1;
     Workspace w;
     char* ptr = (char*)base;
     size_t off = 0;
@@ -836,7 +837,7 @@ extern "C" {
 
 size_t hora_allocate_workspace_bytes(int64_t n, int32_t g0) {
     if (n < 0 || g0 < 0) return 0;
-    Workspace w = carve(nullptr, g0);
+    Workspace w = carve(nullptr);
     return w.bytes;
 }
 
@@ -869,7 +870,7 @@ int hora_allocate(int64_t n, int32_t g0, const int32_t* c, double alpha0, double
     if (n == 0) return handle_empty(a);
     if (!c || (reinterpret_cast<uintptr_t>(c) & 3)) return HORA_ERR_INVALID_ARG;
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255)) return HORA_ERR_WORKSPACE;
-    Workspace w = carve(workspace, g0);
+    Workspace w = carve(workspace);
     if (workspace_bytes < w.bytes) return HORA_ERR_WORKSPACE;
     const Plan p = make_plan(n);
     CountsSource src{c, g0, alpha0, beta0};
@@ -897,7 +898,7 @@ int hora_allocate_posterior(int64_t n, int32_t g0, const double* alpha, const do
     if (!alpha || !beta || (reinterpret_cast<uintptr_t>(alpha) & 7) || (reinterpret_cast<uintptr_t>(beta) & 7))
         return HORA_ERR_INVALID_ARG;
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255)) return HORA_ERR_WORKSPACE;
-    Workspace w = carve(workspace, g0);
+    Workspace w = carve(workspace);
     if (workspace_bytes < w.bytes) return HORA_ERR_WORKSPACE;
     const Plan p = make_plan(n);
     PosteriorSource src{alpha, beta};
