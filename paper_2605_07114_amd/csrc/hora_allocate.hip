@@ -9,11 +9,13 @@
 // r = budget - sum_i #{l : M_i(l) > tau}.
 //
 // Two ways to find tau:
-//  CLASS  (shared prior): gains depend on c_i only, so a histogram over c and a
-//         class-level greedy over at most G0+1 sequences solve the threshold.
+//  CLASS  (shared prior): gains depend on c_i only.  Pass 1 takes a histogram of c per
+//         workgroup and evaluates the G0+1 gain sequences once into a table.  Pass 2
+//         (every workgroup on its own, no grid-wide wait) ranks the table entries
+//         against the histogram to find tau, then writes its share of the outputs.
 //  BISECT (any posterior): bisection on the bit pattern of tau; every step counts
 //         #{(i,l) : M_i(l) > tau} with a monotone walk per prompt.
-// Both end in the same scan + write pass that resolves the ties by prompt index.
+// Both resolve the ties at tau by prompt index with prefix counts.
 #include <hip/hip_runtime.h>
 
 #include <climits>
@@ -27,8 +29,11 @@ namespace hora {
 
 constexpr int kItems = 4;                     // consecutive prompts per thread and tile
 constexpr int kTile = kThreads * kItems;      // 1024 prompts
-constexpr int kMaxBlocks = 1024;              // workgroups of the allocation passes
+constexpr int kMaxBlocks = 512;               // workgroups of the allocation passes
 constexpr int kMaxClasses = HORA_CLASS_MAX_G0 + 1;
+constexpr int kMinDepth = 32;                 // gain-table entries per class, at least
+constexpr int kMaxDepth = 256;                // ... and at most
+constexpr int kTableCap = kMaxClasses * (kMinDepth + 1);   // doubles per table (2112)
 constexpr int kBisectSteps = 64;              // enough for any 63-bit bracket
 constexpr unsigned kTiedBit = 0x80000000u;
 
@@ -44,18 +49,11 @@ struct AllocHeader {              // 256 bytes at the start of the workspace, ze
 };
 static_assert(sizeof(AllocHeader) == 256, "header size");
 
-struct AllocSolution {
-    double tau;
-    long long count_gt;
+struct BisectSolution {           // written by k_bisect_scan, read by k_bisect_write
     long long r;                  // units for the prompts tied at tau
-    long long tie_prompts;
-    int k[kMaxClasses];           // CLASS: #{l : M_c(l) > tau}
-    int tied[kMaxClasses];        // CLASS: M_c(k_c) == tau and k_c below the cap
-    double u0[kMaxClasses];       // CLASS: U_c(k_c)
-    double u1[kMaxClasses];       // CLASS: U_c(k_c + 1)
-    long long pad[28];
+    long long pad[31];
 };
-static_assert(sizeof(AllocSolution) % 256 == 0, "solution size");
+static_assert(sizeof(BisectSolution) == 256, "solution size");
 
 struct Plan {
     long long chunk;  // prompts per workgroup, a multiple of kTile
@@ -77,31 +75,35 @@ static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct Workspace {
     AllocHeader* header;
-    AllocSolution* sol;
-    int* block_hist;        // [nb][g0+1]
-    long long* block_ksum;  // [nb] sums, then exclusive prefixes, of k_i
-    long long* block_tied;  // [nb] sums, then exclusive prefixes, of tied flags
+    BisectSolution* sol;
+    int* class_hist;        // [kMaxClasses][kMaxBlocks]: prompts of class c in workgroup b
+    double* gain_table;     // [nc][depth+1]: M_c(l), l <= depth
+    double* surv_table;     // [nc][depth+1]: E_c(l), l <= depth
+    long long* block_ksum;  // [nb] sums, then exclusive prefixes, of k_i          (BISECT)
+    long long* block_tied;  // [nb] sums, then exclusive prefixes, of tied flags   (BISECT)
     size_t bytes;
 };
 
 // The arrays are sized for kMaxBlocks workgroups and kMaxClasses classes whatever n and
 // g0 are, so that a workspace that served one batch serves every other one.
 static Workspace carve(void* base) {
-    struct { int nb; } p = {kMaxBlocks};
-    const int g0 = kMaxClasses - 1;
     Workspace w;
     char* ptr = (char*)base;
     size_t off = 0;
     w.header = (AllocHeader*)(ptr + off);
     off += sizeof(AllocHeader);
-    w.sol = (AllocSolution*)(ptr + off);
-    off += sizeof(AllocSolution);
-    w.block_hist = (int*)(ptr + off);
-    off += align256((size_t)p.nb * (size_t)(g0 + 1) * sizeof(int));
+    w.sol = (BisectSolution*)(ptr + off);
+    off += sizeof(BisectSolution);
+    w.class_hist = (int*)(ptr + off);
+    off += align256((size_t)kMaxClasses * kMaxBlocks * sizeof(int));
+    w.gain_table = (double*)(ptr + off);
+    off += align256((size_t)kTableCap * sizeof(double));
+    w.surv_table = (double*)(ptr + off);
+    off += align256((size_t)kTableCap * sizeof(double));
     w.block_ksum = (long long*)(ptr + off);
-    off += align256((size_t)p.nb * sizeof(long long));
+    off += align256((size_t)kMaxBlocks * sizeof(long long));
     w.block_tied = (long long*)(ptr + off);
-    off += align256((size_t)p.nb * sizeof(long long));
+    off += align256((size_t)kMaxBlocks * sizeof(long long));
     w.bytes = off;
     return w;
 }
@@ -160,8 +162,103 @@ __global__ __launch_bounds__(kThreads) void k_gain_table(long long n, const doub
 }
 
 // ----------------------------------------------------------------------------------
-// CLASS pass 1: per-workgroup histogram of c.  Lane k of every wavefront accumulates
-// the count of class k from wavefront ballots.
+// Tie resolution and output of one tile of a workgroup's chunk, shared by both methods.
+//
+// Every thread holds kItems consecutive prompts with k (gains above tau) and the tied
+// flag.  A workgroup scan of the tied flags gives each prompt the number of tied prompts
+// before it; the first r of them (by index) win one more unit.  The group offset of
+// prompt i is g0*i + sum_{i'<i} k_i' + min(tied prompts before i, r).
+// ----------------------------------------------------------------------------------
+struct EmitCarry {
+    long long rank_base;   // tied prompts with a lower index than the current tile
+    long long ks_base;     // sum of k over prompts with a lower index than the current tile
+};
+
+template <int kOff>
+__device__ __forceinline__ void emit_tile(long long pos, long long end, long long n, int g0, long long r,
+                                          const int (&kk)[kItems], const int (&td)[kItems], EmitCarry& carry,
+                                          int (&dd)[kItems], bool (&win)[kItems], int32_t* __restrict__ delta,
+                                          void* __restrict__ group_off, bool d_vec, bool o_vec, int* s_scan_i,
+                                          long long* s_scan_l) {
+    const bool full = pos + kItems <= end;
+    const int tcnt = td[0] + td[1] + td[2] + td[3];
+    int t_total;
+    const int t_excl = block_excl_scan<int>(tcnt, s_scan_i, t_total);
+    long long ks_excl = 0, ks_total = 0;
+    if (kOff != 0) {
+        const long long ks = (long long)kk[0] + kk[1] + kk[2] + kk[3];
+        ks_excl = block_excl_scan<long long>(ks, s_scan_l, ks_total);
+    }
+    long long off[kItems + 1];
+    long long rank = carry.rank_base + t_excl;
+    long long kprior = carry.ks_base + ks_excl;
+#pragma unroll
+    for (int j = 0; j < kItems; ++j) {
+        off[j] = (long long)g0 * (pos + j) + kprior + (rank < r ? rank : r);
+        win[j] = td[j] && rank < r;
+        dd[j] = kk[j] + (win[j] ? 1 : 0);
+        rank += td[j];
+        kprior += kk[j];
+    }
+    off[kItems] = (long long)g0 * (pos + kItems) + kprior + (rank < r ? rank : r);
+
+    if (full && d_vec) {
+        v4i x = {dd[0], dd[1], dd[2], dd[3]};
+        *reinterpret_cast<v4i*>(delta + pos) = x;
+    } else {
+#pragma unroll
+        for (int j = 0; j < kItems; ++j)
+            if (pos + j < end) delta[pos + j] = dd[j];
+    }
+    if (kOff == 1) {
+        int32_t* go = reinterpret_cast<int32_t*>(group_off);
+        if (full && o_vec) {
+            v4i x = {(int)off[0], (int)off[1], (int)off[2], (int)off[3]};
+            *reinterpret_cast<v4i*>(go + pos) = x;
+        } else {
+#pragma unroll
+            for (int j = 0; j < kItems; ++j)
+                if (pos + j < end) go[pos + j] = (int32_t)off[j];
+        }
+#pragma unroll
+        for (int j = 0; j < kItems; ++j)
+            if (pos + j == n - 1) go[n] = (int32_t)off[j + 1];
+    } else if (kOff == 2) {
+        long long* go = reinterpret_cast<long long*>(group_off);
+        if (full && o_vec) {
+            v2l x0 = {off[0], off[1]}, x1 = {off[2], off[3]};
+            *reinterpret_cast<v2l*>(go + pos) = x0;
+            *reinterpret_cast<v2l*>(go + pos + 2) = x1;
+        } else {
+#pragma unroll
+            for (int j = 0; j < kItems; ++j)
+                if (pos + j < end) go[pos + j] = off[j];
+        }
+#pragma unroll
+        for (int j = 0; j < kItems; ++j)
+            if (pos + j == n - 1) go[n] = off[j + 1];
+    }
+    carry.rank_base += t_total;
+    carry.ks_base += ks_total;
+}
+
+__device__ __forceinline__ void store_util4(double* __restrict__ util, long long pos, long long end, bool u_vec,
+                                            const double (&uu)[kItems]) {
+    if (pos + kItems <= end && u_vec) {
+        v2d x0 = {uu[0], uu[1]}, x1 = {uu[2], uu[3]};
+        *reinterpret_cast<v2d*>(util + pos) = x0;
+        *reinterpret_cast<v2d*>(util + pos + 2) = x1;
+    } else {
+#pragma unroll
+        for (int j = 0; j < kItems; ++j)
+            if (pos + j < end) util[pos + j] = uu[j];
+    }
+}
+
+// ----------------------------------------------------------------------------------
+// CLASS pass 1: per-workgroup histogram of c (lane k of every wavefront accumulates the
+// count of class k from wavefront ballots), and, in one extra workgroup, the gain and
+// survival tables of the G0+1 classes.
 // ----------------------------------------------------------------------------------
 __device__ __forceinline__ void load_counts4(const int32_t* __restrict__ c, long long pos, long long end,
                                              bool vec_ok, int (&v)[kItems]) {
@@ -175,13 +272,37 @@ __device__ __forceinline__ void load_counts4(const int32_t* __restrict__ c, long
 }
 
 __global__ __launch_bounds__(kThreads) void k_class_hist(const int32_t* __restrict__ c, long long n, int g0,
-                                                         long long chunk, int* __restrict__ block_hist,
-                                                         int32_t* dev_status) {
+                                                         double alpha0, double beta0, long long chunk, int nb,
+                                                         int depth, int* __restrict__ class_hist,
+                                                         double* __restrict__ gain_table,
+                                                         double* __restrict__ surv_table, int32_t* dev_status) {
     __shared__ int s_cnt[kWaves][kWave];
+    const int lane = lane_id();
+    if ((int)blockIdx.x == nb) {   // the extra workgroup: tables, one lane per class
+        if (threadIdx.x <= (unsigned)g0) {
+            const double a = alpha0 + (double)lane;
+            const double b = beta0 + (double)(g0 - lane);
+            const double s = a + b;
+            double m = gain_first(a, s);
+            double e = 1.0;
+            double lf = 0.0;
+            double* grow = gain_table + (long long)lane * (depth + 1);
+            double* srow = surv_table + (long long)lane * (depth + 1);
+            for (int l = 0; l < depth; ++l) {
+                grow[l] = m;
+                srow[l] = e;
+                e = surv_next(e, b, s, lf);
+                m = gain_next(m, b, s, lf);
+                lf += 1.0;
+            }
+            grow[depth] = m;
+            srow[depth] = e;
+        }
+        return;
+    }
     const long long base = (long long)blockIdx.x * chunk;
     const long long end = base + chunk < n ? base + chunk : n;
     const bool vec_ok = (reinterpret_cast<uintptr_t>(c) & 15) == 0;
-    const int lane = lane_id();
     int cnt = 0;
     bool bad = false;
     for (long long t0 = base; t0 < end; t0 += kTile) {
@@ -209,86 +330,106 @@ __global__ __launch_bounds__(kThreads) void k_class_hist(const int32_t* __restri
         int tot = 0;
 #pragma unroll
         for (int w = 0; w < kWaves; ++w) tot += s_cnt[w][threadIdx.x];
-        block_hist[(long long)blockIdx.x * (g0 + 1) + threadIdx.x] = tot;
+        class_hist[(long long)threadIdx.x * kMaxBlocks + blockIdx.x] = tot;
     }
     if (bad) report(dev_status, HORA_ERR_RANGE);
 }
 
 // ----------------------------------------------------------------------------------
-// Exclusive scans of the per-workgroup sums (k and tied counts), in place.
-// Returns the totals to every thread.
+// CLASS solve, run by every workgroup of pass 2 on its own copy of the tables.
+//
+// Table entry (c, l) with value v is the threshold iff
+//     count_gt(v) < budget <= count_gt(v) + count_eq(v),
+// with count_gt(v) = sum_c' n_c' #{l' : M_c'(l') > v} and count_eq(v) the prompts whose
+// next gain equals v; each count is a binary search in a decreasing table row.  The
+// answer is only accepted when no populated class has its whole row above v (unless the
+// row ends at the cap): otherwise gains beyond the table would be missing from the
+// counts, and the class-level greedy below decides instead.
 // ----------------------------------------------------------------------------------
-__device__ void scan_block_sums(int nb, long long* block_ksum, long long* block_tied, long long& ksum_total,
-                                long long& tied_total) {
-    __shared__ long long s_scan[kWaves];
-    long long kcarry = 0, tcarry = 0;
-    for (int b0 = 0; b0 < nb; b0 += kThreads) {
-        int b = b0 + (int)threadIdx.x;
-        long long kv = b < nb ? block_ksum[b] : 0;
-        long long tv = b < nb ? block_tied[b] : 0;
-        long long ktot, ttot;
-        long long kex = block_excl_scan<long long>(kv, s_scan, ktot);
-        long long tex = block_excl_scan<long long>(tv, s_scan, ttot);
-        if (b < nb) {
-            block_ksum[b] = kcarry + kex;
-            block_tied[b] = tcarry + tex;
-        }
-        kcarry += ktot;
-        tcarry += ttot;
+struct ClassSolution {      // LDS
+    unsigned long long tau_bits;
+    long long r;
+    long long tie_prompts;
+    int found;
+    int k[kMaxClasses];
+    int tied[kMaxClasses];
+    double u0[kMaxClasses];   // U_c(k_c)
+    double u1[kMaxClasses];   // U_c(k_c + 1)
+};
+
+__device__ __forceinline__ int row_count_above(const double* row, int len, unsigned long long v) {
+    int lo = 0, hi = len;     // first index whose gain is <= v
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (gain_bits(row[mid]) > v) lo = mid + 1; else hi = mid;
     }
-    ksum_total = kcarry;
-    tied_total = tcarry;
+    return lo;
 }
 
-// ----------------------------------------------------------------------------------
-// CLASS pass 2 (one workgroup): total histogram, class-level greedy, block prefixes.
-//
-// Lane c of wavefront 0 owns class c: its posterior, its position l_c in the gain
-// sequence and the current gain.  Each round takes the largest current gain over the
-// classes that still have prompts and room below the cap; all classes tied at that
-// value advance together, consuming n_c units each.  The round in which the remaining
-// budget no longer covers the tied classes fixes tau; the leftover r units go to the
-// tied prompts in index order (resolved by the write pass).  This is Alg. 1's greedy
-// loop run on classes instead of prompts: prompts of one class have identical
-// sequences, so the greedy hands them their l-th unit in one uninterrupted run.
-// ----------------------------------------------------------------------------------
+__device__ void solve_by_table(int nc, int depth, long long cap_eff, long long budget, const long long* s_n,
+                               const double* s_gain, const double* s_surv, ClassSolution* sol) {
+    const int stride = depth + 1;
+    const int len = cap_eff < depth ? (int)cap_eff : depth;   // usable entries per row
+    const bool rows_end_at_cap = cap_eff <= depth;
+    if (threadIdx.x == 0) sol->found = 0;
+    __syncthreads();
+    for (int idx = (int)threadIdx.x; idx < nc * len; idx += kThreads) {
+        const int c = idx / len, l = idx - c * len;
+        if (s_n[c] == 0) continue;
+        const unsigned long long v = gain_bits(s_gain[c * stride + l]);
+        long long gt = 0, eq = 0;
+        bool complete = true;
+        for (int c2 = 0; c2 < nc; ++c2) {
+            const long long n2 = s_n[c2];
+            if (n2 == 0) continue;
+            const double* row = s_gain + c2 * stride;
+            const int cnt = row_count_above(row, len, v);
+            gt += n2 * cnt;
+            if (cnt < len) {
+                if (gain_bits(row[cnt]) == v) eq += n2;
+            } else if (!rows_end_at_cap) {
+                complete = false;
+            }
+        }
+        if (complete && gt < budget && budget <= gt + eq) {   // every such thread writes the same values
+            sol->tau_bits = v;
+            sol->r = budget - gt;
+            sol->tie_prompts = eq;
+            sol->found = 1;
+        }
+    }
+    __syncthreads();
+    if (sol->found && threadIdx.x < (unsigned)nc) {
+        const int c = (int)threadIdx.x;
+        const double* row = s_gain + c * stride;
+        const int cnt = row_count_above(row, len, sol->tau_bits);
+        const bool tied = cnt < len && gain_bits(row[cnt]) == sol->tau_bits;
+        sol->k[c] = cnt;
+        sol->tied[c] = tied ? 1 : 0;
+        sol->u0[c] = 1.0 - s_surv[c * stride + cnt];
+        sol->u1[c] = 1.0 - s_surv[c * stride + (cnt < depth ? cnt + 1 : cnt)];
+    }
+    __syncthreads();
+}
+
 __device__ __forceinline__ unsigned long long read_lane_u64(unsigned long long v, int src) {
     unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(v & 0xffffffffull), src);
     unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(v >> 32), src);
     return ((unsigned long long)hi << 32) | lo;
 }
 
-__global__ __launch_bounds__(kThreads) void k_class_solve(int g0, double alpha0, double beta0, long long budget,
-                                                          int cap, int nb, const int* __restrict__ block_hist,
-                                                          AllocSolution* __restrict__ sol,
-                                                          long long* __restrict__ block_ksum,
-                                                          long long* __restrict__ block_tied,
-                                                          hora_alloc_summary* __restrict__ summary,
-                                                          int32_t* dev_status) {
-    __shared__ long long s_part[kWaves][kWave];
-    __shared__ long long s_n[kWave];
-    __shared__ int s_k[kWave];
-    __shared__ int s_tied[kWave];
-    const int nc = g0 + 1;
-    const int lane = lane_id();
-    const int w = wave_id();
-
-    {   // total histogram
-        long long acc = 0;
-        if (lane < nc)
-            for (int b = w; b < nb; b += kWaves) acc += block_hist[(long long)b * nc + lane];
-        s_part[w][lane] = acc;
-        __syncthreads();
-        if (threadIdx.x < kWave) {
-            long long tot = 0;
-#pragma unroll
-            for (int i = 0; i < kWaves; ++i) tot += s_part[i][threadIdx.x];
-            s_n[threadIdx.x] = tot;
-        }
-        __syncthreads();
-    }
-
-    if (w == 0) {
+// Class-level greedy, for allocations deeper than the table.  Lane c of wavefront 0 owns
+// class c: its posterior, its position l_c and the current gain.  Each round takes the
+// largest current gain over the classes that still have prompts and room below the cap;
+// all classes tied at that value advance together, consuming n_c units each.  The round
+// in which the remaining budget no longer covers the tied classes fixes tau.  This is
+// Alg. 1's greedy loop run on classes: prompts of one class have identical sequences, so
+// the greedy hands them their l-th unit in one uninterrupted run.
+__device__ void solve_by_greedy(int g0, double alpha0, double beta0, long long cap_eff, long long budget,
+                                const long long* s_n, ClassSolution* sol, int32_t* dev_status) {
+    if (wave_id() == 0) {
+        const int nc = g0 + 1;
+        const int lane = lane_id();
         const bool has = lane < nc;
         const long long ncount = has ? s_n[lane] : 0;
         const double a = alpha0 + (double)(has ? lane : 0);
@@ -298,7 +439,6 @@ __global__ __launch_bounds__(kThreads) void k_class_solve(int g0, double alpha0,
         double e = 1.0;
         double lf = 0.0;
         long long k = 0;
-        const long long cap_eff = cap > 0 ? (long long)cap : LLONG_MAX;
         long long remaining = budget;
         unsigned long long tau_bits = 0;
         long long tie_prompts = 0;
@@ -333,211 +473,132 @@ __global__ __launch_bounds__(kThreads) void k_class_solve(int g0, double alpha0,
                 k += 1;
             }
         }
-        if (budget <= 0) remaining = 0;
-        s_k[lane] = has ? (int)k : 0;
-        s_tied[lane] = (has && tied) ? 1 : 0;
         sol->k[lane] = has ? (int)k : 0;
         sol->tied[lane] = (has && tied) ? 1 : 0;
         sol->u0[lane] = 1.0 - e;
         sol->u1[lane] = 1.0 - surv_next(e, b, s, lf);
         if (lane == 0) {
-            const double tau = budget > 0 ? __longlong_as_double((long long)tau_bits) : 0.0;
-            const long long r = (tie_prompts > 0) ? remaining : 0;
-            sol->tau = tau;
-            sol->r = r;
+            sol->tau_bits = tau_bits;
+            sol->r = tie_prompts > 0 ? remaining : 0;
             sol->tie_prompts = tie_prompts;
-            sol->count_gt = budget - r;
-            if (summary) {
-                summary->tau = tau;
-                summary->count_gt = budget - r;
-                summary->tie_units = r;
-                summary->tie_prompts = tie_prompts;
-            }
+            sol->found = 1;
         }
     }
     __syncthreads();
-
-    // per-workgroup sums of k and of tied prompts, then their exclusive prefixes
-    for (int b = (int)threadIdx.x; b < nb; b += kThreads) {
-        long long ks = 0, ts = 0;
-        for (int cc = 0; cc < nc; ++cc) {
-            long long h = block_hist[(long long)b * nc + cc];
-            ks += h * s_k[cc];
-            ts += h * s_tied[cc];
-        }
-        block_ksum[b] = ks;
-        block_tied[b] = ts;
-    }
-    __syncthreads();
-    long long ksum_total, tied_total;
-    scan_block_sums(nb, block_ksum, block_tied, ksum_total, tied_total);
 }
 
 // ----------------------------------------------------------------------------------
-// Final pass: resolve ties by prompt index and write delta, util, group offsets.
-//
-// kClass: (k, tied, U) come from the class tables indexed by c[i].
-// else  : delta[i] holds k_i with the tied flag in bit 31 and util[i] holds the
-//         survival product E_i(k_i), both left there by k_bisect_finalize.
-// kOff  : 0 no offsets, 1 int32 offsets, 2 int64 offsets.
+// CLASS pass 2: solve (redundantly per workgroup), then write the workgroup's chunk.
+// kOff: 0 no offsets, 1 int32 offsets, 2 int64 offsets.
 // ----------------------------------------------------------------------------------
-template <class Src, bool kClass, int kOff>
-__global__ __launch_bounds__(kThreads) void k_alloc_write(Src src, const int32_t* __restrict__ c, long long n,
-                                                          int g0, long long chunk,
-                                                          const AllocSolution* __restrict__ sol,
-                                                          const long long* __restrict__ block_ksum,
-                                                          const long long* __restrict__ block_tied,
+template <int kOff>
+__global__ __launch_bounds__(kThreads) void k_class_write(const int32_t* __restrict__ c, long long n, int g0,
+                                                          double alpha0, double beta0, long long budget, int cap,
+                                                          long long chunk, int nb, int depth,
+                                                          const int* __restrict__ class_hist,
+                                                          const double* __restrict__ gain_table,
+                                                          const double* __restrict__ surv_table,
                                                           int32_t* __restrict__ delta, double* __restrict__ util,
-                                                          void* __restrict__ group_off) {
-    __shared__ int s_k[kWave];
-    __shared__ int s_tied[kWave];
-    __shared__ double s_u0[kWave];
-    __shared__ double s_u1[kWave];
+                                                          void* __restrict__ group_off,
+                                                          hora_alloc_summary* __restrict__ summary,
+                                                          int32_t* dev_status) {
+    __shared__ double s_gain[kTableCap];
+    __shared__ double s_surv[kTableCap];
+    __shared__ long long s_n[kMaxClasses];       // prompts per class, whole batch
+    __shared__ long long s_before[kMaxClasses];  // prompts per class in workgroups before this one
+    __shared__ ClassSolution s_sol;
     __shared__ int s_scan_i[kWaves];
     __shared__ long long s_scan_l[kWaves];
 
-    if (kClass) {
-        if (threadIdx.x < kWave) {
-            s_k[threadIdx.x] = sol->k[threadIdx.x];
-            s_tied[threadIdx.x] = sol->tied[threadIdx.x];
-            s_u0[threadIdx.x] = sol->u0[threadIdx.x];
-            s_u1[threadIdx.x] = sol->u1[threadIdx.x];
-        }
-        __syncthreads();
-    }
-    const long long r = sol->r;
+    const int nc = g0 + 1;
+    const int lane = lane_id();
     const long long base = (long long)blockIdx.x * chunk;
     const long long end = base + chunk < n ? base + chunk : n;
-    long long rank_base = block_tied[blockIdx.x];
-    long long ks_base = block_ksum[blockIdx.x];
-    const bool c_vec = kClass && (reinterpret_cast<uintptr_t>(c) & 15) == 0;
+    const bool c_vec = (reinterpret_cast<uintptr_t>(c) & 15) == 0;
     const bool d_vec = (reinterpret_cast<uintptr_t>(delta) & 15) == 0;
     const bool u_vec = (reinterpret_cast<uintptr_t>(util) & 15) == 0;
     const bool o_vec = (reinterpret_cast<uintptr_t>(group_off) & 15) == 0;
 
+    // first tile of c: issued now, used after the solve
+    int first_tile[kItems];
+    load_counts4(c, base + (long long)threadIdx.x * kItems, end, c_vec, first_tile);
+
+    // class totals and the part that lies before this workgroup
+    for (int cc = wave_id(); cc < nc; cc += kWaves) {
+        long long tot = 0, before = 0;
+        for (int b = lane; b < nb; b += kWave) {
+            const long long h = class_hist[(long long)cc * kMaxBlocks + b];
+            tot += h;
+            if (b < (int)blockIdx.x) before += h;
+        }
+        tot = wave_sum(tot);
+        before = wave_sum(before);
+        if (lane == 0) { s_n[cc] = tot; s_before[cc] = before; }
+    }
+    const int table_len = nc * (depth + 1);
+    for (int i = (int)threadIdx.x; i < table_len; i += kThreads) {
+        s_gain[i] = gain_table[i];
+        s_surv[i] = surv_table[i];
+    }
+    __syncthreads();
+
+    const long long cap_eff = cap > 0 ? (long long)cap : LLONG_MAX;
+    if (budget > 0) {
+        solve_by_table(nc, depth, cap_eff, budget, s_n, s_gain, s_surv, &s_sol);
+        if (!s_sol.found) solve_by_greedy(g0, alpha0, beta0, cap_eff, budget, s_n, &s_sol, dev_status);
+    } else {
+        if (threadIdx.x < kMaxClasses) {
+            s_sol.k[threadIdx.x] = 0;
+            s_sol.tied[threadIdx.x] = 0;
+            s_sol.u0[threadIdx.x] = 0.0;
+            s_sol.u1[threadIdx.x] = 0.0;
+        }
+        if (threadIdx.x == 0) { s_sol.tau_bits = 0; s_sol.r = 0; s_sol.tie_prompts = 0; s_sol.found = 1; }
+        __syncthreads();
+    }
+    const long long r = s_sol.r;
+    if (summary && blockIdx.x == 0 && threadIdx.x == 0) {
+        summary->tau = __longlong_as_double((long long)s_sol.tau_bits);
+        summary->count_gt = budget - r;
+        summary->tie_units = r;
+        summary->tie_prompts = s_sol.tie_prompts;
+    }
+
+    EmitCarry carry = {0, 0};
+    for (int cc = 0; cc < nc; ++cc) {
+        carry.rank_base += s_sol.tied[cc] ? s_before[cc] : 0;
+        carry.ks_base += s_before[cc] * s_sol.k[cc];
+    }
+
     for (long long t0 = base; t0 < end; t0 += kTile) {
         const long long pos = t0 + (long long)threadIdx.x * kItems;
-        const bool full = pos + kItems <= end;
-        int kk[kItems], td[kItems], cls[kItems];
-        if (kClass) {
-            load_counts4(c, pos, end, c_vec, cls);
-#pragma unroll
-            for (int j = 0; j < kItems; ++j) {
-                if (pos + j < end) {
-                    int x = cls[j] < 0 ? 0 : (cls[j] > g0 ? g0 : cls[j]);
-                    cls[j] = x;
-                    kk[j] = s_k[x];
-                    td[j] = s_tied[x];
-                } else {
-                    cls[j] = 0; kk[j] = 0; td[j] = 0;
-                }
-            }
-        } else {
-            unsigned raw[kItems];
-            if (full && d_vec) {
-                v4i x = *reinterpret_cast<const v4i*>(delta + pos);
-                raw[0] = (unsigned)x.x; raw[1] = (unsigned)x.y; raw[2] = (unsigned)x.z; raw[3] = (unsigned)x.w;
-            } else {
-#pragma unroll
-                for (int j = 0; j < kItems; ++j) raw[j] = (pos + j < end) ? (unsigned)delta[pos + j] : 0u;
-            }
-#pragma unroll
-            for (int j = 0; j < kItems; ++j) {
-                kk[j] = (int)(raw[j] & ~kTiedBit);
-                td[j] = (raw[j] & kTiedBit) ? 1 : 0;
-                cls[j] = 0;
-            }
-        }
-        const int tcnt = td[0] + td[1] + td[2] + td[3];
-        int t_total;
-        const int t_excl = block_excl_scan<int>(tcnt, s_scan_i, t_total);
-        long long ks_excl = 0, ks_total = 0;
-        if (kOff != 0) {
-            const long long ks = (long long)kk[0] + kk[1] + kk[2] + kk[3];
-            ks_excl = block_excl_scan<long long>(ks, s_scan_l, ks_total);
-        }
-        int dd[kItems];
+        int cls[kItems], kk[kItems], td[kItems], dd[kItems];
         bool win[kItems];
-        long long off[kItems + 1];
-        long long rank = rank_base + t_excl;       // tied prompts with a lower index
-        long long kprior = ks_base + ks_excl;      // sum of k over prompts with a lower index
+        if (t0 == base) {
+#pragma unroll
+            for (int j = 0; j < kItems; ++j) cls[j] = first_tile[j];
+        } else {
+            load_counts4(c, pos, end, c_vec, cls);
+        }
 #pragma unroll
         for (int j = 0; j < kItems; ++j) {
-            off[j] = (long long)g0 * (pos + j) + kprior + (rank < r ? rank : r);
-            win[j] = td[j] && rank < r;
-            dd[j] = kk[j] + (win[j] ? 1 : 0);
-            rank += td[j];
-            kprior += kk[j];
+            if (pos + j < end) {
+                const int x = cls[j] < 0 ? 0 : (cls[j] > g0 ? g0 : cls[j]);
+                cls[j] = x;
+                kk[j] = s_sol.k[x];
+                td[j] = s_sol.tied[x];
+            } else {
+                cls[j] = 0; kk[j] = 0; td[j] = 0;
+            }
         }
-        off[kItems] = (long long)g0 * (pos + kItems) + kprior + (rank < r ? rank : r);
-
-        if (full && d_vec) {
-            v4i x = {dd[0], dd[1], dd[2], dd[3]};
-            *reinterpret_cast<v4i*>(delta + pos) = x;
-        } else {
-#pragma unroll
-            for (int j = 0; j < kItems; ++j)
-                if (pos + j < end) delta[pos + j] = dd[j];
-        }
+        emit_tile<kOff>(pos, end, n, g0, r, kk, td, carry, dd, win, delta, group_off, d_vec, o_vec, s_scan_i,
+                        s_scan_l);
         if (util) {
             double uu[kItems];
 #pragma unroll
-            for (int j = 0; j < kItems; ++j) {
-                if (kClass) {
-                    uu[j] = win[j] ? s_u1[cls[j]] : s_u0[cls[j]];
-                } else {
-                    double e = 1.0;
-                    if (pos + j < end) {
-                        e = util[pos + j];
-                        if (win[j]) {
-                            double a, b;
-                            src.load(pos + j, a, b);
-                            e = surv_next(e, b, a + b, (double)kk[j]);
-                        }
-                    }
-                    uu[j] = 1.0 - e;
-                }
-            }
-            if (full && u_vec) {
-                v2d x0 = {uu[0], uu[1]}, x1 = {uu[2], uu[3]};
-                *reinterpret_cast<v2d*>(util + pos) = x0;
-                *reinterpret_cast<v2d*>(util + pos + 2) = x1;
-            } else {
-#pragma unroll
-                for (int j = 0; j < kItems; ++j)
-                    if (pos + j < end) util[pos + j] = uu[j];
-            }
+            for (int j = 0; j < kItems; ++j) uu[j] = win[j] ? s_sol.u1[cls[j]] : s_sol.u0[cls[j]];
+            store_util4(util, pos, end, u_vec, uu);
         }
-        if (kOff == 1) {
-            int32_t* go = reinterpret_cast<int32_t*>(group_off);
-            if (full && o_vec) {
-                v4i x = {(int)off[0], (int)off[1], (int)off[2], (int)off[3]};
-                *reinterpret_cast<v4i*>(go + pos) = x;
-            } else {
-#pragma unroll
-                for (int j = 0; j < kItems; ++j)
-                    if (pos + j < end) go[pos + j] = (int32_t)off[j];
-            }
-#pragma unroll
-            for (int j = 0; j < kItems; ++j)
-                if (pos + j == n - 1) go[n] = (int32_t)off[j + 1];
-        } else if (kOff == 2) {
-            long long* go = reinterpret_cast<long long*>(group_off);
-            if (full && o_vec) {
-                v2l x0 = {off[0], off[1]}, x1 = {off[2], off[3]};
-                *reinterpret_cast<v2l*>(go + pos) = x0;
-                *reinterpret_cast<v2l*>(go + pos + 2) = x1;
-            } else {
-#pragma unroll
-                for (int j = 0; j < kItems; ++j)
-                    if (pos + j < end) go[pos + j] = off[j];
-            }
-#pragma unroll
-            for (int j = 0; j < kItems; ++j)
-                if (pos + j == n - 1) go[n] = off[j + 1];
-        }
-        rank_base += t_total;
-        ks_base += ks_total;
     }
 }
 
@@ -693,30 +754,39 @@ __global__ __launch_bounds__(kThreads) void k_bisect_finalize(Src src, long long
     }
 }
 
-// BISECT scan (one workgroup): prefixes over the workgroups, r, the report, and the
-// header back to its rest state.
+// BISECT scan (one workgroup): exclusive prefixes over the workgroups, r, the report,
+// and the header back to its rest state.
 __global__ __launch_bounds__(kThreads) void k_bisect_scan(int nb, long long budget, AllocHeader* __restrict__ hdr,
-                                                          AllocSolution* __restrict__ sol,
+                                                          BisectSolution* __restrict__ sol,
                                                           long long* __restrict__ block_ksum,
                                                           long long* __restrict__ block_tied,
                                                           hora_alloc_summary* __restrict__ summary,
                                                           int32_t* dev_status) {
-    long long ksum_total, tied_total;
-    scan_block_sums(nb, block_ksum, block_tied, ksum_total, tied_total);
+    __shared__ long long s_scan[kWaves];
+    long long kcarry = 0, tcarry = 0;
+    for (int b0 = 0; b0 < nb; b0 += kThreads) {
+        const int b = b0 + (int)threadIdx.x;
+        const long long kv = b < nb ? block_ksum[b] : 0;
+        const long long tv = b < nb ? block_tied[b] : 0;
+        long long ktot, ttot;
+        const long long kex = block_excl_scan<long long>(kv, s_scan, ktot);
+        const long long tex = block_excl_scan<long long>(tv, s_scan, ttot);
+        if (b < nb) {
+            block_ksum[b] = kcarry + kex;
+            block_tied[b] = tcarry + tex;
+        }
+        kcarry += ktot;
+        tcarry += ttot;
+    }
     if (threadIdx.x == 0) {
-        const unsigned long long tau_bits = hdr->hi_cur;
-        const long long r = budget - ksum_total;
-        const double tau = budget > 0 ? __longlong_as_double((long long)tau_bits) : 0.0;
-        if (r < 0 || r > tied_total) report(dev_status, HORA_ERR_RANGE);  // invalid posteriors upstream
-        sol->tau = tau;
+        const long long r = budget - kcarry;
+        if (r < 0 || r > tcarry) report(dev_status, HORA_ERR_RANGE);  // invalid posteriors upstream
         sol->r = r;
-        sol->count_gt = ksum_total;
-        sol->tie_prompts = tied_total;
         if (summary) {
-            summary->tau = tau;
-            summary->count_gt = ksum_total;
+            summary->tau = budget > 0 ? __longlong_as_double((long long)hdr->hi_cur) : 0.0;
+            summary->count_gt = kcarry;
             summary->tie_units = r;
-            summary->tie_prompts = tied_total;
+            summary->tie_prompts = tcarry;
         }
         hdr->lo_inv = 0ull;
         hdr->hi = 0ull;
@@ -724,6 +794,63 @@ __global__ __launch_bounds__(kThreads) void k_bisect_scan(int nb, long long budg
         hdr->ticket = 0u;
         hdr->lo_cur = 0ull;
         hdr->hi_cur = 0ull;
+    }
+}
+
+// BISECT write: delta[i] holds k_i with the tied flag in bit 31 and util[i] the survival
+// product E_i(k_i); a winner's utility takes one more step of the product.
+template <class Src, int kOff>
+__global__ __launch_bounds__(kThreads) void k_bisect_write(Src src, long long n, int g0, long long chunk,
+                                                           const BisectSolution* __restrict__ sol,
+                                                           const long long* __restrict__ block_ksum,
+                                                           const long long* __restrict__ block_tied,
+                                                           int32_t* __restrict__ delta, double* __restrict__ util,
+                                                           void* __restrict__ group_off) {
+    __shared__ int s_scan_i[kWaves];
+    __shared__ long long s_scan_l[kWaves];
+    const long long r = sol->r;
+    const long long base = (long long)blockIdx.x * chunk;
+    const long long end = base + chunk < n ? base + chunk : n;
+    const bool d_vec = (reinterpret_cast<uintptr_t>(delta) & 15) == 0;
+    const bool u_vec = (reinterpret_cast<uintptr_t>(util) & 15) == 0;
+    const bool o_vec = (reinterpret_cast<uintptr_t>(group_off) & 15) == 0;
+    EmitCarry carry = {block_tied[blockIdx.x], block_ksum[blockIdx.x]};
+    for (long long t0 = base; t0 < end; t0 += kTile) {
+        const long long pos = t0 + (long long)threadIdx.x * kItems;
+        unsigned raw[kItems];
+        if (pos + kItems <= end && d_vec) {
+            v4i x = *reinterpret_cast<const v4i*>(delta + pos);
+            raw[0] = (unsigned)x.x; raw[1] = (unsigned)x.y; raw[2] = (unsigned)x.z; raw[3] = (unsigned)x.w;
+        } else {
+#pragma unroll
+            for (int j = 0; j < kItems; ++j) raw[j] = (pos + j < end) ? (unsigned)delta[pos + j] : 0u;
+        }
+        int kk[kItems], td[kItems], dd[kItems];
+        bool win[kItems];
+#pragma unroll
+        for (int j = 0; j < kItems; ++j) {
+            kk[j] = (int)(raw[j] & ~kTiedBit);
+            td[j] = (raw[j] & kTiedBit) ? 1 : 0;
+        }
+        emit_tile<kOff>(pos, end, n, g0, r, kk, td, carry, dd, win, delta, group_off, d_vec, o_vec, s_scan_i,
+                        s_scan_l);
+        if (util) {
+            double uu[kItems];
+#pragma unroll
+            for (int j = 0; j < kItems; ++j) {
+                double e = 1.0;
+                if (pos + j < end) {
+                    e = util[pos + j];
+                    if (win[j]) {
+                        double a, b;
+                        src.load(pos + j, a, b);
+                        e = surv_next(e, b, a + b, (double)kk[j]);
+                    }
+                }
+                uu[j] = 1.0 - e;
+            }
+            store_util4(util, pos, end, u_vec, uu);
+        }
     }
 }
 
@@ -793,17 +920,36 @@ static int handle_empty(const CommonArgs& a) {  // n == 0 (budget == 0 checked b
     return check_launch();
 }
 
-template <class Src, bool kClass>
-static int launch_write(const Src& src, const int32_t* c, const CommonArgs& a, const Plan& p, const Workspace& w) {
+// Entries per class of the gain table: deep enough for a few times the mean allocation,
+// within what fits the table (the class-level greedy covers whatever is deeper).
+static int table_depth(int nc, int64_t n, int64_t budget, int32_t delta_max) {
+    const int fit = kTableCap / nc - 1;   // >= kMinDepth
+    long long mean = (budget + n - 1) / n;
+    long long want = kMinDepth;
+    while (want < 4 * mean && want < kMaxDepth) want *= 2;
+    if (delta_max > 0 && want > delta_max) want = delta_max < kMinDepth ? kMinDepth : delta_max;
+    if (want > fit) want = fit;
+    if (want > kMaxDepth) want = kMaxDepth;
+    return (int)want;
+}
+
+static int run_class(const int32_t* c, double alpha0, double beta0, const CommonArgs& a, const Plan& p,
+                     const Workspace& w) {
+    const int nc = a.g0 + 1;
+    const int depth = table_depth(nc, a.n, a.budget, a.delta_max);
+    const int cap = a.delta_max > 0 ? a.delta_max : 0;
+    hipLaunchKernelGGL(k_class_hist, dim3(p.nb + 1), dim3(kThreads), 0, a.stream, c, (long long)a.n, (int)a.g0,
+                       alpha0, beta0, p.chunk, p.nb, depth, w.class_hist, w.gain_table, w.surv_table,
+                       a.dev_status);
     const int mode = a.group_off ? (a.off_t == HORA_I32 ? 1 : 2) : 0;
-#define HORA_LAUNCH_WRITE(M)                                                                              \
-    hipLaunchKernelGGL((k_alloc_write<Src, kClass, M>), dim3(p.nb), dim3(kThreads), 0, a.stream, src, c, \
-                       (long long)a.n, (int)a.g0, p.chunk, w.sol, w.block_ksum, w.block_tied, a.delta,   \
-                       a.util, a.group_off)
-    if (mode == 0) HORA_LAUNCH_WRITE(0);
-    else if (mode == 1) HORA_LAUNCH_WRITE(1);
-    else HORA_LAUNCH_WRITE(2);
-#undef HORA_LAUNCH_WRITE
+#define HORA_LAUNCH_CLASS_WRITE(M)                                                                              \
+    hipLaunchKernelGGL((k_class_write<M>), dim3(p.nb), dim3(kThreads), 0, a.stream, c, (long long)a.n,          \
+                       (int)a.g0, alpha0, beta0, (long long)a.budget, cap, p.chunk, p.nb, depth, w.class_hist, \
+                       w.gain_table, w.surv_table, a.delta, a.util, a.group_off, a.summary, a.dev_status)
+    if (mode == 0) HORA_LAUNCH_CLASS_WRITE(0);
+    else if (mode == 1) HORA_LAUNCH_CLASS_WRITE(1);
+    else HORA_LAUNCH_CLASS_WRITE(2);
+#undef HORA_LAUNCH_CLASS_WRITE
     return check_launch();
 }
 
@@ -824,9 +970,15 @@ static int run_bisect(const Src& src, const CommonArgs& a, const Plan& p, const 
                        (long long)a.budget, limit, w.header, a.delta, a.util, w.block_ksum, w.block_tied);
     hipLaunchKernelGGL(k_bisect_scan, dim3(1), dim3(kThreads), 0, a.stream, p.nb, (long long)a.budget, w.header,
                        w.sol, w.block_ksum, w.block_tied, a.summary, a.dev_status);
-    int rc = check_launch();
-    if (rc != HORA_OK) return rc;
-    return launch_write<Src, false>(src, nullptr, a, p, w);
+    const int mode = a.group_off ? (a.off_t == HORA_I32 ? 1 : 2) : 0;
+#define HORA_LAUNCH_BISECT_WRITE(M)                                                                          \
+    hipLaunchKernelGGL((k_bisect_write<Src, M>), dim3(p.nb), dim3(kThreads), 0, a.stream, src, n, (int)a.g0, \
+                       p.chunk, w.sol, w.block_ksum, w.block_tied, a.delta, a.util, a.group_off)
+    if (mode == 0) HORA_LAUNCH_BISECT_WRITE(0);
+    else if (mode == 1) HORA_LAUNCH_BISECT_WRITE(1);
+    else HORA_LAUNCH_BISECT_WRITE(2);
+#undef HORA_LAUNCH_BISECT_WRITE
+    return check_launch();
 }
 
 }  // namespace hora
@@ -873,17 +1025,11 @@ int hora_allocate(int64_t n, int32_t g0, const int32_t* c, double alpha0, double
     Workspace w = carve(workspace);
     if (workspace_bytes < w.bytes) return HORA_ERR_WORKSPACE;
     const Plan p = make_plan(n);
-    CountsSource src{c, g0, alpha0, beta0};
-    if (method == HORA_ALLOC_BISECT) return run_bisect(src, a, p, w);
-
-    hipLaunchKernelGGL(k_class_hist, dim3(p.nb), dim3(kThreads), 0, a.stream, c, (long long)n, (int)g0, p.chunk,
-                       w.block_hist, dev_status);
-    hipLaunchKernelGGL(k_class_solve, dim3(1), dim3(kThreads), 0, a.stream, (int)g0, alpha0, beta0,
-                       (long long)budget, (int)(delta_max > 0 ? delta_max : 0), p.nb, w.block_hist, w.sol,
-                       w.block_ksum, w.block_tied, summary, dev_status);
-    rc = check_launch();
-    if (rc != HORA_OK) return rc;
-    return launch_write<CountsSource, true>(src, c, a, p, w);
+    if (method == HORA_ALLOC_BISECT) {
+        CountsSource src{c, g0, alpha0, beta0};
+        return run_bisect(src, a, p, w);
+    }
+    return run_class(c, alpha0, beta0, a, p, w);
 }
 
 int hora_allocate_posterior(int64_t n, int32_t g0, const double* alpha, const double* beta, int64_t budget,
