@@ -27,13 +27,14 @@
 
 namespace hora {
 
-constexpr int kItems = 4;                     // consecutive prompts per thread and tile
-constexpr int kTile = kThreads * kItems;      // 1024 prompts
-constexpr int kMaxBlocks = 512;               // workgroups of the allocation passes
+constexpr int kItems = 8;                     // consecutive prompts per thread and tile
+constexpr int kTile = kThreads * kItems;      // 2048 prompts
+constexpr int kMaxBlocks = 512;               // workgroups of the allocation passes (a power of two)
 constexpr int kMaxClasses = HORA_CLASS_MAX_G0 + 1;
-constexpr int kMinDepth = 32;                 // gain-table entries per class, at least
-constexpr int kMaxDepth = 256;                // ... and at most
-constexpr int kTableCap = kMaxClasses * (kMinDepth + 1);   // doubles per table (2112)
+constexpr int kMinRow = 32;                   // gain-table row length (a power of two), at least
+constexpr int kMaxRow = 256;                  // ... and at most
+constexpr int kTableCap = kMaxClasses * kMinRow;   // doubles per table (2048)
+static_assert(kMaxBlocks == 2 * kThreads, "pass 2 reads two histogram entries per thread and class");
 constexpr int kBisectSteps = 64;              // enough for any 63-bit bracket
 constexpr unsigned kTiedBit = 0x80000000u;
 
@@ -77,8 +78,8 @@ struct Workspace {
     AllocHeader* header;
     BisectSolution* sol;
     int* class_hist;        // [kMaxClasses][kMaxBlocks]: prompts of class c in workgroup b
-    double* gain_table;     // [nc][depth+1]: M_c(l), l <= depth
-    double* surv_table;     // [nc][depth+1]: E_c(l), l <= depth
+    double* gain_table;     // [nc][row]: M_c(l)
+    double* surv_table;     // [nc][row]: E_c(l)
     long long* block_ksum;  // [nb] sums, then exclusive prefixes, of k_i          (BISECT)
     long long* block_tied;  // [nb] sums, then exclusive prefixes, of tied flags   (BISECT)
     size_t bytes;
@@ -174,24 +175,74 @@ struct EmitCarry {
     long long ks_base;     // sum of k over prompts with a lower index than the current tile
 };
 
-template <int kOff>
-__device__ __forceinline__ void emit_tile(long long pos, long long end, long long n, int g0, long long r,
-                                          const int (&kk)[kItems], const int (&td)[kItems], EmitCarry& carry,
-                                          int (&dd)[kItems], bool (&win)[kItems], int32_t* __restrict__ delta,
-                                          void* __restrict__ group_off, bool d_vec, bool o_vec, int* s_scan_i,
-                                          long long* s_scan_l) {
-    const bool full = pos + kItems <= end;
-    const int tcnt = td[0] + td[1] + td[2] + td[3];
-    int t_total;
-    const int t_excl = block_excl_scan<int>(tcnt, s_scan_i, t_total);
-    long long ks_excl = 0, ks_total = 0;
-    if (kOff != 0) {
-        const long long ks = (long long)kk[0] + kk[1] + kk[2] + kk[3];
-        ks_excl = block_excl_scan<long long>(ks, s_scan_l, ks_total);
+struct EmitShared {        // LDS exchange between the wavefronts of a workgroup, double-buffered
+    int tied[2][kWaves];
+    long long ksum[2][kWaves];
+};
+
+template <typename V, typename T>
+__device__ __forceinline__ void store_items(T* __restrict__ dst, long long pos, long long end, bool vec_ok,
+                                            const T (&x)[kItems]) {
+    constexpr int kPer = (int)(sizeof(V) / sizeof(T));
+    if (vec_ok && pos + kItems <= end) {
+#pragma unroll
+        for (int q = 0; q < kItems / kPer; ++q) {
+            V v;
+#pragma unroll
+            for (int i = 0; i < kPer; ++i) v[i] = x[q * kPer + i];
+            *reinterpret_cast<V*>(dst + pos + q * kPer) = v;
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < kItems; ++j)
+            if (pos + j < end) dst[pos + j] = x[j];
     }
+}
+
+template <int kOff>
+__device__ __forceinline__ void emit_tile(int tile_parity, long long pos, long long end, long long n, int g0,
+                                          long long r, const int (&kk)[kItems], const int (&td)[kItems],
+                                          EmitCarry& carry, int (&dd)[kItems], bool (&win)[kItems],
+                                          int32_t* __restrict__ delta, void* __restrict__ group_off, bool d_vec,
+                                          bool o_vec, EmitShared* sh) {
+    const int w = wave_id();
+    // tied prompts before this thread inside the wavefront: ballots, no data movement
+    int t_before = 0, t_wave = 0;
+#pragma unroll
+    for (int j = 0; j < kItems; ++j) {
+        const unsigned long long m = __ballot(td[j] != 0);
+        t_before += lanes_below(m);
+        t_wave += __popcll(m);
+    }
+    long long ks = 0, ks_incl = 0, ks_wave = 0;
+    if (kOff != 0) {
+#pragma unroll
+        for (int j = 0; j < kItems; ++j) ks += kk[j];
+        ks_incl = wave_incl_scan_i64(ks);
+        ks_wave = ((long long)wave_last_i32((int)(ks_incl >> 32)) << 32) |
+                  (unsigned)wave_last_i32((int)(ks_incl & 0xffffffffll));
+    }
+    if (lane_id() == 0) {
+        sh->tied[tile_parity][w] = t_wave;
+        if (kOff != 0) sh->ksum[tile_parity][w] = ks_wave;
+    }
+    __syncthreads();
+    int t_lower = 0, t_total = 0;
+    long long ks_lower = 0, ks_total = 0;
+#pragma unroll
+    for (int i = 0; i < kWaves; ++i) {
+        const int t = sh->tied[tile_parity][i];
+        if (i < w) t_lower += t;
+        t_total += t;
+        if (kOff != 0) {
+            const long long q = sh->ksum[tile_parity][i];
+            if (i < w) ks_lower += q;
+            ks_total += q;
+        }
+    }
+    long long rank = carry.rank_base + t_lower + t_before;
+    long long kprior = carry.ks_base + ks_lower + (ks_incl - ks);
     long long off[kItems + 1];
-    long long rank = carry.rank_base + t_excl;
-    long long kprior = carry.ks_base + ks_excl;
 #pragma unroll
     for (int j = 0; j < kItems; ++j) {
         off[j] = (long long)g0 * (pos + j) + kprior + (rank < r ? rank : r);
@@ -202,38 +253,22 @@ __device__ __forceinline__ void emit_tile(long long pos, long long end, long lon
     }
     off[kItems] = (long long)g0 * (pos + kItems) + kprior + (rank < r ? rank : r);
 
-    if (full && d_vec) {
-        v4i x = {dd[0], dd[1], dd[2], dd[3]};
-        *reinterpret_cast<v4i*>(delta + pos) = x;
-    } else {
-#pragma unroll
-        for (int j = 0; j < kItems; ++j)
-            if (pos + j < end) delta[pos + j] = dd[j];
-    }
+    store_items<v4i, int32_t>(delta, pos, end, d_vec, dd);
     if (kOff == 1) {
         int32_t* go = reinterpret_cast<int32_t*>(group_off);
-        if (full && o_vec) {
-            v4i x = {(int)off[0], (int)off[1], (int)off[2], (int)off[3]};
-            *reinterpret_cast<v4i*>(go + pos) = x;
-        } else {
+        int32_t o32[kItems];
 #pragma unroll
-            for (int j = 0; j < kItems; ++j)
-                if (pos + j < end) go[pos + j] = (int32_t)off[j];
-        }
+        for (int j = 0; j < kItems; ++j) o32[j] = (int32_t)off[j];
+        store_items<v4i, int32_t>(go, pos, end, o_vec, o32);
 #pragma unroll
         for (int j = 0; j < kItems; ++j)
             if (pos + j == n - 1) go[n] = (int32_t)off[j + 1];
     } else if (kOff == 2) {
         long long* go = reinterpret_cast<long long*>(group_off);
-        if (full && o_vec) {
-            v2l x0 = {off[0], off[1]}, x1 = {off[2], off[3]};
-            *reinterpret_cast<v2l*>(go + pos) = x0;
-            *reinterpret_cast<v2l*>(go + pos + 2) = x1;
-        } else {
+        long long o64[kItems];
 #pragma unroll
-            for (int j = 0; j < kItems; ++j)
-                if (pos + j < end) go[pos + j] = off[j];
-        }
+        for (int j = 0; j < kItems; ++j) o64[j] = off[j];
+        store_items<v2l, long long>(go, pos, end, o_vec, o64);
 #pragma unroll
         for (int j = 0; j < kItems; ++j)
             if (pos + j == n - 1) go[n] = off[j + 1];
@@ -242,38 +277,28 @@ __device__ __forceinline__ void emit_tile(long long pos, long long end, long lon
     carry.ks_base += ks_total;
 }
 
-__device__ __forceinline__ void store_util4(double* __restrict__ util, long long pos, long long end, bool u_vec,
-                                            const double (&uu)[kItems]) {
-    if (pos + kItems <= end && u_vec) {
-        v2d x0 = {uu[0], uu[1]}, x1 = {uu[2], uu[3]};
-        *reinterpret_cast<v2d*>(util + pos) = x0;
-        *reinterpret_cast<v2d*>(util + pos + 2) = x1;
-    } else {
-#pragma unroll
-        for (int j = 0; j < kItems; ++j)
-            if (pos + j < end) util[pos + j] = uu[j];
-    }
-}
-
 // ----------------------------------------------------------------------------------
 // CLASS pass 1: per-workgroup histogram of c (lane k of every wavefront accumulates the
 // count of class k from wavefront ballots), and, in one extra workgroup, the gain and
 // survival tables of the G0+1 classes.
 // ----------------------------------------------------------------------------------
-__device__ __forceinline__ void load_counts4(const int32_t* __restrict__ c, long long pos, long long end,
-                                             bool vec_ok, int (&v)[kItems]) {
+__device__ __forceinline__ void load_items_i32(const int32_t* __restrict__ src, long long pos, long long end,
+                                               bool vec_ok, int fill, int (&v)[kItems]) {
     if (vec_ok && pos + kItems <= end) {
-        v4i x = *reinterpret_cast<const v4i*>(c + pos);
-        v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w;
+#pragma unroll
+        for (int q = 0; q < kItems / 4; ++q) {
+            const v4i x = *reinterpret_cast<const v4i*>(src + pos + 4 * q);
+            v[4 * q] = x.x; v[4 * q + 1] = x.y; v[4 * q + 2] = x.z; v[4 * q + 3] = x.w;
+        }
     } else {
 #pragma unroll
-        for (int j = 0; j < kItems; ++j) v[j] = (pos + j < end) ? c[pos + j] : -1;
+        for (int j = 0; j < kItems; ++j) v[j] = (pos + j < end) ? src[pos + j] : fill;
     }
 }
 
 __global__ __launch_bounds__(kThreads) void k_class_hist(const int32_t* __restrict__ c, long long n, int g0,
                                                          double alpha0, double beta0, long long chunk, int nb,
-                                                         int depth, int* __restrict__ class_hist,
+                                                         int row, int* __restrict__ class_hist,
                                                          double* __restrict__ gain_table,
                                                          double* __restrict__ surv_table, int32_t* dev_status) {
     __shared__ int s_cnt[kWaves][kWave];
@@ -286,17 +311,15 @@ __global__ __launch_bounds__(kThreads) void k_class_hist(const int32_t* __restri
             double m = gain_first(a, s);
             double e = 1.0;
             double lf = 0.0;
-            double* grow = gain_table + (long long)lane * (depth + 1);
-            double* srow = surv_table + (long long)lane * (depth + 1);
-            for (int l = 0; l < depth; ++l) {
+            double* grow = gain_table + (long long)lane * row;
+            double* srow = surv_table + (long long)lane * row;
+            for (int l = 0; l < row; ++l) {
                 grow[l] = m;
                 srow[l] = e;
                 e = surv_next(e, b, s, lf);
                 m = gain_next(m, b, s, lf);
                 lf += 1.0;
             }
-            grow[depth] = m;
-            srow[depth] = e;
         }
         return;
     }
@@ -308,7 +331,7 @@ __global__ __launch_bounds__(kThreads) void k_class_hist(const int32_t* __restri
     for (long long t0 = base; t0 < end; t0 += kTile) {
         const long long pos = t0 + (long long)threadIdx.x * kItems;
         int v[kItems];
-        load_counts4(c, pos, end, vec_ok, v);
+        load_items_i32(c, pos, end, vec_ok, -1, v);
 #pragma unroll
         for (int j = 0; j < kItems; ++j) {
             if (pos + j < end) {
@@ -341,10 +364,12 @@ __global__ __launch_bounds__(kThreads) void k_class_hist(const int32_t* __restri
 // Table entry (c, l) with value v is the threshold iff
 //     count_gt(v) < budget <= count_gt(v) + count_eq(v),
 // with count_gt(v) = sum_c' n_c' #{l' : M_c'(l') > v} and count_eq(v) the prompts whose
-// next gain equals v; each count is a binary search in a decreasing table row.  The
-// answer is only accepted when no populated class has its whole row above v (unless the
-// row ends at the cap): otherwise gains beyond the table would be missing from the
-// counts, and the class-level greedy below decides instead.
+// next gain equals v.  Rows hold `len` gains followed by zeros up to the row length (a
+// power of two), so each count is a branch-free binary search; four rows are searched
+// in lockstep to overlap their LDS latencies.  The answer is only accepted when no
+// populated class has all its `len` gains above v (unless the row ends at the cap):
+// otherwise gains beyond the table would be missing from the counts, and the class-level
+// greedy below decides instead.
 // ----------------------------------------------------------------------------------
 struct ClassSolution {      // LDS
     unsigned long long tau_bits;
@@ -357,38 +382,48 @@ struct ClassSolution {      // LDS
     double u1[kMaxClasses];   // U_c(k_c + 1)
 };
 
-__device__ __forceinline__ int row_count_above(const double* row, int len, unsigned long long v) {
-    int lo = 0, hi = len;     // first index whose gain is <= v
-    while (lo < hi) {
-        const int mid = (lo + hi) >> 1;
-        if (gain_bits(row[mid]) > v) lo = mid + 1; else hi = mid;
-    }
-    return lo;
+// #{l : row[l] > v} for a decreasing row of `row_len` (power of two) entries whose last
+// entry is not above v.
+__device__ __forceinline__ int row_count_above(const double* row, int row_len, unsigned long long v) {
+    int pos = 0;
+    for (int step = row_len >> 1; step > 0; step >>= 1)
+        if (gain_bits(row[pos + step - 1]) > v) pos += step;
+    return pos;
 }
 
-__device__ void solve_by_table(int nc, int depth, long long cap_eff, long long budget, const long long* s_n,
-                               const double* s_gain, const double* s_surv, ClassSolution* sol) {
-    const int stride = depth + 1;
-    const int len = cap_eff < depth ? (int)cap_eff : depth;   // usable entries per row
-    const bool rows_end_at_cap = cap_eff <= depth;
+__device__ void solve_by_table(int nc, int row_len, int len, bool rows_end_at_cap, long long budget,
+                               const long long* s_n, const double* s_gain, const double* s_surv,
+                               ClassSolution* sol) {
     if (threadIdx.x == 0) sol->found = 0;
     __syncthreads();
-    for (int idx = (int)threadIdx.x; idx < nc * len; idx += kThreads) {
-        const int c = idx / len, l = idx - c * len;
-        if (s_n[c] == 0) continue;
-        const unsigned long long v = gain_bits(s_gain[c * stride + l]);
+    const int row_shift = __ffs(row_len) - 1;
+    for (int idx = (int)threadIdx.x; idx < nc * row_len; idx += kThreads) {
+        const int c = idx >> row_shift, l = idx & (row_len - 1);
+        if (l >= len || s_n[c] == 0) continue;
+        const unsigned long long v = gain_bits(s_gain[idx]);
         long long gt = 0, eq = 0;
         bool complete = true;
-        for (int c2 = 0; c2 < nc; ++c2) {
-            const long long n2 = s_n[c2];
-            if (n2 == 0) continue;
-            const double* row = s_gain + c2 * stride;
-            const int cnt = row_count_above(row, len, v);
-            gt += n2 * cnt;
-            if (cnt < len) {
-                if (gain_bits(row[cnt]) == v) eq += n2;
-            } else if (!rows_end_at_cap) {
-                complete = false;
+        for (int c0 = 0; c0 < nc; c0 += 4) {
+            const double* rows[4];
+            long long n2[4];
+            int pos[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const bool in = c0 + i < nc;
+                rows[i] = s_gain + (in ? c0 + i : 0) * row_len;
+                n2[i] = in ? s_n[c0 + i] : 0;
+                pos[i] = 0;
+            }
+            for (int step = row_len >> 1; step > 0; step >>= 1) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (gain_bits(rows[i][pos[i] + step - 1]) > v) pos[i] += step;
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                gt += n2[i] * pos[i];
+                if (gain_bits(rows[i][pos[i]]) == v) eq += n2[i];
+                if (n2[i] != 0 && pos[i] >= len && !rows_end_at_cap) complete = false;
             }
         }
         if (complete && gt < budget && budget <= gt + eq) {   // every such thread writes the same values
@@ -401,13 +436,12 @@ __device__ void solve_by_table(int nc, int depth, long long cap_eff, long long b
     __syncthreads();
     if (sol->found && threadIdx.x < (unsigned)nc) {
         const int c = (int)threadIdx.x;
-        const double* row = s_gain + c * stride;
-        const int cnt = row_count_above(row, len, sol->tau_bits);
-        const bool tied = cnt < len && gain_bits(row[cnt]) == sol->tau_bits;
+        const double* row = s_gain + c * row_len;
+        const int cnt = row_count_above(row, row_len, sol->tau_bits);
         sol->k[c] = cnt;
-        sol->tied[c] = tied ? 1 : 0;
-        sol->u0[c] = 1.0 - s_surv[c * stride + cnt];
-        sol->u1[c] = 1.0 - s_surv[c * stride + (cnt < depth ? cnt + 1 : cnt)];
+        sol->tied[c] = gain_bits(row[cnt]) == sol->tau_bits ? 1 : 0;
+        sol->u0[c] = 1.0 - s_surv[c * row_len + cnt];
+        sol->u1[c] = 1.0 - s_surv[c * row_len + (cnt + 1 < row_len ? cnt + 1 : cnt)];
     }
     __syncthreads();
 }
@@ -494,7 +528,7 @@ __device__ void solve_by_greedy(int g0, double alpha0, double beta0, long long c
 template <int kOff>
 __global__ __launch_bounds__(kThreads) void k_class_write(const int32_t* __restrict__ c, long long n, int g0,
                                                           double alpha0, double beta0, long long budget, int cap,
-                                                          long long chunk, int nb, int depth,
+                                                          long long chunk, int nb, int row_len,
                                                           const int* __restrict__ class_hist,
                                                           const double* __restrict__ gain_table,
                                                           const double* __restrict__ surv_table,
@@ -504,47 +538,70 @@ __global__ __launch_bounds__(kThreads) void k_class_write(const int32_t* __restr
                                                           int32_t* dev_status) {
     __shared__ double s_gain[kTableCap];
     __shared__ double s_surv[kTableCap];
+    __shared__ long long s_part[kWaves][2][kMaxClasses];
     __shared__ long long s_n[kMaxClasses];       // prompts per class, whole batch
     __shared__ long long s_before[kMaxClasses];  // prompts per class in workgroups before this one
     __shared__ ClassSolution s_sol;
-    __shared__ int s_scan_i[kWaves];
-    __shared__ long long s_scan_l[kWaves];
+    __shared__ EmitShared s_emit;
 
     const int nc = g0 + 1;
     const int lane = lane_id();
+    const int w = wave_id();
     const long long base = (long long)blockIdx.x * chunk;
     const long long end = base + chunk < n ? base + chunk : n;
     const bool c_vec = (reinterpret_cast<uintptr_t>(c) & 15) == 0;
     const bool d_vec = (reinterpret_cast<uintptr_t>(delta) & 15) == 0;
     const bool u_vec = (reinterpret_cast<uintptr_t>(util) & 15) == 0;
     const bool o_vec = (reinterpret_cast<uintptr_t>(group_off) & 15) == 0;
+    const long long cap_eff = cap > 0 ? (long long)cap : LLONG_MAX;
+    const int len = cap_eff < row_len - 1 ? (int)cap_eff : row_len - 1;   // usable gains per row
+    const bool rows_end_at_cap = cap_eff <= row_len - 1;
 
     // first tile of c: issued now, used after the solve
     int first_tile[kItems];
-    load_counts4(c, base + (long long)threadIdx.x * kItems, end, c_vec, first_tile);
+    load_items_i32(c, base + (long long)threadIdx.x * kItems, end, c_vec, -1, first_tile);
 
-    // class totals and the part that lies before this workgroup
-    for (int cc = wave_id(); cc < nc; cc += kWaves) {
-        long long tot = 0, before = 0;
-        for (int b = lane; b < nb; b += kWave) {
-            const long long h = class_hist[(long long)cc * kMaxBlocks + b];
-            tot += h;
-            if (b < (int)blockIdx.x) before += h;
-        }
-        tot = wave_sum(tot);
-        before = wave_sum(before);
-        if (lane == 0) { s_n[cc] = tot; s_before[cc] = before; }
-    }
-    const int table_len = nc * (depth + 1);
+    // tables into LDS, gains beyond `len` replaced by zeros
+    const int table_len = nc * row_len;
     for (int i = (int)threadIdx.x; i < table_len; i += kThreads) {
-        s_gain[i] = gain_table[i];
+        const double g = gain_table[i];
+        s_gain[i] = (i & (row_len - 1)) < len ? g : 0.0;
         s_surv[i] = surv_table[i];
+    }
+
+    // class totals and the part that lies before this workgroup: thread t reads the
+    // counts of workgroups t and t + 256 of each class, four classes per round
+    for (int c0 = 0; c0 < nc; c0 += 4) {
+        int h0[4], h1[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int cc = c0 + i < nc ? c0 + i : c0;
+            const int b0 = (int)threadIdx.x, b1 = (int)threadIdx.x + kThreads;
+            h0[i] = b0 < nb ? class_hist[cc * kMaxBlocks + b0] : 0;
+            h1[i] = b1 < nb ? class_hist[cc * kMaxBlocks + b1] : 0;
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const long long tot = (long long)h0[i] + h1[i];
+            const long long bef = ((int)threadIdx.x < (int)blockIdx.x ? (long long)h0[i] : 0) +
+                                  ((int)threadIdx.x + kThreads < (int)blockIdx.x ? (long long)h1[i] : 0);
+            const long long tot_w = wave_total_i64(tot);
+            const long long bef_w = wave_total_i64(bef);
+            if (lane == 0 && c0 + i < nc) { s_part[w][0][c0 + i] = tot_w; s_part[w][1][c0 + i] = bef_w; }
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x < (unsigned)nc) {
+        long long tot = 0, bef = 0;
+#pragma unroll
+        for (int i = 0; i < kWaves; ++i) { tot += s_part[i][0][threadIdx.x]; bef += s_part[i][1][threadIdx.x]; }
+        s_n[threadIdx.x] = tot;
+        s_before[threadIdx.x] = bef;
     }
     __syncthreads();
 
-    const long long cap_eff = cap > 0 ? (long long)cap : LLONG_MAX;
     if (budget > 0) {
-        solve_by_table(nc, depth, cap_eff, budget, s_n, s_gain, s_surv, &s_sol);
+        solve_by_table(nc, row_len, len, rows_end_at_cap, budget, s_n, s_gain, s_surv, &s_sol);
         if (!s_sol.found) solve_by_greedy(g0, alpha0, beta0, cap_eff, budget, s_n, &s_sol, dev_status);
     } else {
         if (threadIdx.x < kMaxClasses) {
@@ -570,7 +627,8 @@ __global__ __launch_bounds__(kThreads) void k_class_write(const int32_t* __restr
         carry.ks_base += s_before[cc] * s_sol.k[cc];
     }
 
-    for (long long t0 = base; t0 < end; t0 += kTile) {
+    int parity = 0;
+    for (long long t0 = base; t0 < end; t0 += kTile, parity ^= 1) {
         const long long pos = t0 + (long long)threadIdx.x * kItems;
         int cls[kItems], kk[kItems], td[kItems], dd[kItems];
         bool win[kItems];
@@ -578,7 +636,7 @@ __global__ __launch_bounds__(kThreads) void k_class_write(const int32_t* __restr
 #pragma unroll
             for (int j = 0; j < kItems; ++j) cls[j] = first_tile[j];
         } else {
-            load_counts4(c, pos, end, c_vec, cls);
+            load_items_i32(c, pos, end, c_vec, -1, cls);
         }
 #pragma unroll
         for (int j = 0; j < kItems; ++j) {
@@ -591,13 +649,13 @@ __global__ __launch_bounds__(kThreads) void k_class_write(const int32_t* __restr
                 cls[j] = 0; kk[j] = 0; td[j] = 0;
             }
         }
-        emit_tile<kOff>(pos, end, n, g0, r, kk, td, carry, dd, win, delta, group_off, d_vec, o_vec, s_scan_i,
-                        s_scan_l);
+        emit_tile<kOff>(parity, pos, end, n, g0, r, kk, td, carry, dd, win, delta, group_off, d_vec, o_vec,
+                        &s_emit);
         if (util) {
             double uu[kItems];
 #pragma unroll
             for (int j = 0; j < kItems; ++j) uu[j] = win[j] ? s_sol.u1[cls[j]] : s_sol.u0[cls[j]];
-            store_util4(util, pos, end, u_vec, uu);
+            store_items<v2d, double>(util, pos, end, u_vec, uu);
         }
     }
 }
@@ -806,8 +864,7 @@ __global__ __launch_bounds__(kThreads) void k_bisect_write(Src src, long long n,
                                                            const long long* __restrict__ block_tied,
                                                            int32_t* __restrict__ delta, double* __restrict__ util,
                                                            void* __restrict__ group_off) {
-    __shared__ int s_scan_i[kWaves];
-    __shared__ long long s_scan_l[kWaves];
+    __shared__ EmitShared s_emit;
     const long long r = sol->r;
     const long long base = (long long)blockIdx.x * chunk;
     const long long end = base + chunk < n ? base + chunk : n;
@@ -815,25 +872,20 @@ __global__ __launch_bounds__(kThreads) void k_bisect_write(Src src, long long n,
     const bool u_vec = (reinterpret_cast<uintptr_t>(util) & 15) == 0;
     const bool o_vec = (reinterpret_cast<uintptr_t>(group_off) & 15) == 0;
     EmitCarry carry = {block_tied[blockIdx.x], block_ksum[blockIdx.x]};
-    for (long long t0 = base; t0 < end; t0 += kTile) {
+    int parity = 0;
+    for (long long t0 = base; t0 < end; t0 += kTile, parity ^= 1) {
         const long long pos = t0 + (long long)threadIdx.x * kItems;
-        unsigned raw[kItems];
-        if (pos + kItems <= end && d_vec) {
-            v4i x = *reinterpret_cast<const v4i*>(delta + pos);
-            raw[0] = (unsigned)x.x; raw[1] = (unsigned)x.y; raw[2] = (unsigned)x.z; raw[3] = (unsigned)x.w;
-        } else {
-#pragma unroll
-            for (int j = 0; j < kItems; ++j) raw[j] = (pos + j < end) ? (unsigned)delta[pos + j] : 0u;
-        }
+        int raw[kItems];
+        load_items_i32(delta, pos, end, d_vec, 0, raw);
         int kk[kItems], td[kItems], dd[kItems];
         bool win[kItems];
 #pragma unroll
         for (int j = 0; j < kItems; ++j) {
-            kk[j] = (int)(raw[j] & ~kTiedBit);
-            td[j] = (raw[j] & kTiedBit) ? 1 : 0;
+            kk[j] = (int)((unsigned)raw[j] & ~kTiedBit);
+            td[j] = ((unsigned)raw[j] & kTiedBit) ? 1 : 0;
         }
-        emit_tile<kOff>(pos, end, n, g0, r, kk, td, carry, dd, win, delta, group_off, d_vec, o_vec, s_scan_i,
-                        s_scan_l);
+        emit_tile<kOff>(parity, pos, end, n, g0, r, kk, td, carry, dd, win, delta, group_off, d_vec, o_vec,
+                        &s_emit);
         if (util) {
             double uu[kItems];
 #pragma unroll
@@ -849,7 +901,7 @@ __global__ __launch_bounds__(kThreads) void k_bisect_write(Src src, long long n,
                 }
                 uu[j] = 1.0 - e;
             }
-            store_util4(util, pos, end, u_vec, uu);
+            store_items<v2d, double>(util, pos, end, u_vec, uu);
         }
     }
 }
@@ -920,31 +972,32 @@ static int handle_empty(const CommonArgs& a) {  // n == 0 (budget == 0 checked b
     return check_launch();
 }
 
-// Entries per class of the gain table: deep enough for a few times the mean allocation,
-// within what fits the table (the class-level greedy covers whatever is deeper).
-static int table_depth(int nc, int64_t n, int64_t budget, int32_t delta_max) {
-    const int fit = kTableCap / nc - 1;   // >= kMinDepth
-    long long mean = (budget + n - 1) / n;
-    long long want = kMinDepth;
-    while (want < 4 * mean && want < kMaxDepth) want *= 2;
-    if (delta_max > 0 && want > delta_max) want = delta_max < kMinDepth ? kMinDepth : delta_max;
-    if (want > fit) want = fit;
-    if (want > kMaxDepth) want = kMaxDepth;
-    return (int)want;
+// Row length of the gain table (a power of two; the last entry is padding): long enough
+// for a few times the mean allocation, within what fits the table.  The class-level
+// greedy covers whatever is deeper.
+static int table_row(int nc, int64_t n, int64_t budget, int32_t delta_max) {
+    int fit = kMinRow;
+    while (fit * 2 * nc <= kTableCap && fit * 2 <= kMaxRow) fit *= 2;
+    const long long mean = (budget + n - 1) / n;
+    long long need = 4 * mean + 1;
+    if (delta_max > 0 && need > (long long)delta_max + 1) need = (long long)delta_max + 1;
+    int row = kMinRow;
+    while (row < need && row < fit) row *= 2;
+    return row;
 }
 
 static int run_class(const int32_t* c, double alpha0, double beta0, const CommonArgs& a, const Plan& p,
                      const Workspace& w) {
     const int nc = a.g0 + 1;
-    const int depth = table_depth(nc, a.n, a.budget, a.delta_max);
+    const int row = table_row(nc, a.n, a.budget, a.delta_max);
     const int cap = a.delta_max > 0 ? a.delta_max : 0;
     hipLaunchKernelGGL(k_class_hist, dim3(p.nb + 1), dim3(kThreads), 0, a.stream, c, (long long)a.n, (int)a.g0,
-                       alpha0, beta0, p.chunk, p.nb, depth, w.class_hist, w.gain_table, w.surv_table,
+                       alpha0, beta0, p.chunk, p.nb, row, w.class_hist, w.gain_table, w.surv_table,
                        a.dev_status);
     const int mode = a.group_off ? (a.off_t == HORA_I32 ? 1 : 2) : 0;
 #define HORA_LAUNCH_CLASS_WRITE(M)                                                                              \
     hipLaunchKernelGGL((k_class_write<M>), dim3(p.nb), dim3(kThreads), 0, a.stream, c, (long long)a.n,          \
-                       (int)a.g0, alpha0, beta0, (long long)a.budget, cap, p.chunk, p.nb, depth, w.class_hist, \
+                       (int)a.g0, alpha0, beta0, (long long)a.budget, cap, p.chunk, p.nb, row, w.class_hist,   \
                        w.gain_table, w.surv_table, a.delta, a.util, a.group_off, a.summary, a.dev_status)
     if (mode == 0) HORA_LAUNCH_CLASS_WRITE(0);
     else if (mode == 1) HORA_LAUNCH_CLASS_WRITE(1);

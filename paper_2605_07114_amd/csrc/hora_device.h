@@ -48,6 +48,50 @@ __device__ __forceinline__ T wave_incl_scan(T v) {
     return v;
 }
 
+// ---------------------------------------------------------------------------------
+// Wavefront prefix sums on the DPP cross-lane path (no LDS traffic).  The classic GCN
+// sequence: shifts by 1, 2, 3 inside a row of 16 lanes, by 4 and 8 with bank masks, then
+// the two row broadcasts that carry row totals across the four rows.
+// Lanes that a mask disables, or whose source lies outside the row, contribute 0.
+// ---------------------------------------------------------------------------------
+template <int kCtrl, int kRowMask, int kBankMask>
+__device__ __forceinline__ int dpp_take(int v) {
+    return __builtin_amdgcn_update_dpp(0, v, kCtrl, kRowMask, kBankMask, true);
+}
+
+__device__ __forceinline__ int wave_incl_scan_i32(int v) {
+    int t = v + dpp_take<0x111, 0xf, 0xf>(v);      // row_shr:1
+    t += dpp_take<0x112, 0xf, 0xf>(v);             // row_shr:2
+    t += dpp_take<0x113, 0xf, 0xf>(v);             // row_shr:3
+    t += dpp_take<0x114, 0xf, 0xe>(t);             // row_shr:4, banks 1-3
+    t += dpp_take<0x118, 0xf, 0xc>(t);             // row_shr:8, banks 2-3
+    t += dpp_take<0x142, 0xa, 0xf>(t);             // row_bcast:15 into rows 1 and 3
+    t += dpp_take<0x143, 0xc, 0xf>(t);             // row_bcast:31 into rows 2 and 3
+    return t;
+}
+
+// Inclusive scan of non-negative 64-bit values below 2^50 as two 32-bit scans
+// (low 22 bits and the rest), so that no partial sum over 64 lanes overflows.
+__device__ __forceinline__ long long wave_incl_scan_i64(long long v) {
+    const int lo = wave_incl_scan_i32((int)(v & 0x3fffff));
+    const int hi = wave_incl_scan_i32((int)(v >> 22));
+    return (long long)lo + ((long long)hi << 22);
+}
+
+__device__ __forceinline__ int wave_last_i32(int v) { return __builtin_amdgcn_readlane(v, kWave - 1); }
+
+__device__ __forceinline__ long long wave_total_i64(long long v) {   // same range as the scan
+    const int lo = wave_last_i32(wave_incl_scan_i32((int)(v & 0x3fffff)));
+    const int hi = wave_last_i32(wave_incl_scan_i32((int)(v >> 22)));
+    return (long long)lo + ((long long)hi << 22);
+}
+
+// Number of lanes below this one whose bit is set in a wavefront ballot.
+__device__ __forceinline__ int lanes_below(unsigned long long ballot) {
+    return (int)__builtin_amdgcn_mbcnt_hi((unsigned)(ballot >> 32),
+                                          __builtin_amdgcn_mbcnt_lo((unsigned)ballot, 0u));
+}
+
 template <typename T>
 __device__ __forceinline__ T wave_sum(T v) {
 #pragma unroll
