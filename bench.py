@@ -49,18 +49,21 @@ def timed(torch, fn, steps, warmup):
 
 
 def per_launch_events(torch, fn, steps, warmup):
-    """Average duration of one call of fn, from a HIP event pair around every call."""
+    """Average duration of one call of fn: HIP events around `steps` back-to-back calls,
+    repeated a few times (mean and best of the repeats)."""
     for _ in range(warmup):
         fn()
     torch.cuda.synchronize()
-    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
-    for a, b in pairs:
+    means = []
+    for _ in range(5):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         a.record()
-        fn()
+        for _ in range(steps):
+            fn()
         b.record()
-    torch.cuda.synchronize()
-    ms = np.array([a.elapsed_time(b) for a, b in pairs])
-    return float(ms.mean()) * 1e-3, float(ms.min()) * 1e-3
+        torch.cuda.synchronize()
+        means.append(a.elapsed_time(b) / steps)
+    return float(np.mean(means)) * 1e-3, float(np.min(means)) * 1e-3
 
 
 def cpu_baseline(wl, oracle, w_alloc, a_alloc, bcast_inputs):
@@ -142,20 +145,21 @@ def main():
     adv_grpo = torch.empty(n_resp, dtype=torch.float32, device="cuda:0")
     tok_rloo = torch.empty(n_tok, dtype=torch.float32, device="cuda:0")
     tok_grpo = torch.empty(n_tok, dtype=torch.float32, device="cuda:0")
+    bws = sess.broadcast_workspace(n_tok, torch.float32)
 
     def step_path():
         hora.hora_allocate(c2, w2.g0, w2.budget, delta2, sess.dev_status, ws, group_off=goff2)
         hora.hora_group_advantage(goff2, reward2, adv_rloo, hora.ADV_RLOO, sess.dev_status)
         hora.hora_group_advantage(goff2, reward2, adv_grpo, hora.ADV_GRPO, sess.dev_status, eps=w2.eps)
-        hora.hora_token_broadcast(adv_rloo, tok_off2, tok_rloo, n_tok, sess.dev_status)
-        hora.hora_token_broadcast(adv_grpo, tok_off2, tok_grpo, n_tok, sess.dev_status)
+        hora.hora_token_broadcast(adv_rloo, tok_off2, tok_rloo, n_tok, sess.dev_status, bws)
+        hora.hora_token_broadcast(adv_grpo, tok_off2, tok_grpo, n_tok, sess.dev_status, bws)
 
     wall2, ev2 = timed(torch, step_path, max(steps // 4, 10), max(warmup // 4, 3))
     steps2 = max(steps // 4, 10)
     assert sess.status() == 0
 
     def one_broadcast():
-        hora.hora_token_broadcast(adv_rloo, tok_off2, tok_rloo, n_tok, sess.dev_status)
+        hora.hora_token_broadcast(adv_rloo, tok_off2, tok_rloo, n_tok, sess.dev_status, bws)
 
     bc_mean, bc_min = per_launch_events(torch, one_broadcast, steps2, 3)
     bcast_bytes = 4 * n_tok + n_resp * (8 + 4)       # float stores; offsets and advantages in
@@ -192,7 +196,7 @@ def main():
             "tokens_per_s_whole_path": 2 * n_tok / (wall2 / steps2),
         },
         "roofline": {
-            "kernel": "k_token_broadcast<float,float,int64> (large_bcast)",
+            "kernel": "k_row_index + k_token_fill<float,float,int64> (large_bcast)",
             "bound": "hbm",
             "achieved": bcast_gbs,
             "peak": HBM_PEAK_GBS,

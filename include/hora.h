@@ -172,20 +172,28 @@ int hora_group_advantage(int64_t n_groups, const void *group_off, int32_t off_t,
                          int32_t ddof, int32_t *dev_status, void *stream);
 
 /*
+ * Bytes of workspace hora_token_broadcast needs for n_tokens tokens of type out_t
+ * (4 bytes per 4 KiB of output, plus a little).  Device memory, 4-byte aligned, no
+ * initialisation needed; two calls that may run concurrently need separate workspaces.
+ */
+size_t hora_token_broadcast_workspace_bytes(int64_t n_tokens, int32_t out_t);
+
+/*
  * Per-token advantages (Sec. 3.1: the advantage in the objective carries a token
  * index but does not depend on it): tok_adv[t] = adv[j] for tok_off[j] <= t < tok_off[j+1].
  *
- * adv      : device, n_resp values of type adv_t.
+ * adv      : device, n_resp values of type adv_t (n_resp < 2^31).
  * tok_off  : device, n_resp+1 packed token offsets of type off_t, tok_off[0] = 0,
  *            non-decreasing, tok_off[n_resp] = n_tokens (else HORA_ERR_RANGE in
  *            dev_status).  Zero-length responses are allowed.
  * tok_adv  : device out, n_tokens values of type out_t (a binary64 advantage stored as
  *            float is rounded to nearest once).  Must be aligned to its element size;
- *            16-byte alignment gives the fastest path.
+ *            any such alignment runs at full speed.
+ * workspace: device, >= hora_token_broadcast_workspace_bytes(n_tokens, out_t).
  */
 int hora_token_broadcast(int64_t n_resp, const void *adv, int32_t adv_t, const void *tok_off,
                          int32_t off_t, void *tok_adv, int32_t out_t, int64_t n_tokens,
-                         int32_t *dev_status, void *stream);
+                         int32_t *dev_status, void *workspace, size_t workspace_bytes, void *stream);
 
 #ifdef __cplusplus
 }

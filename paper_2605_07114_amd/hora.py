@@ -32,6 +32,7 @@ CLASS_MAX_G0 = 63
 EXPORTS = (
     "hora_status_string", "hora_version", "hora_marginal_gains", "hora_allocate_workspace_bytes",
     "hora_allocate", "hora_allocate_posterior", "hora_group_advantage", "hora_token_broadcast",
+    "hora_token_broadcast_workspace_bytes",
 )
 
 
@@ -70,7 +71,9 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.hora_allocate_posterior.restype = ctypes.c_int
     lib.hora_group_advantage.argtypes = [i64, p, i32, i64, p, p, i32, i32, f64, i32, p, p]
     lib.hora_group_advantage.restype = ctypes.c_int
-    lib.hora_token_broadcast.argtypes = [i64, p, i32, p, i32, p, i32, i64, p, p]
+    lib.hora_token_broadcast_workspace_bytes.argtypes = [i64, i32]
+    lib.hora_token_broadcast_workspace_bytes.restype = sz
+    lib.hora_token_broadcast.argtypes = [i64, p, i32, p, i32, p, i32, i64, p, p, sz, p]
     lib.hora_token_broadcast.restype = ctypes.c_int
     _lib = lib
     return lib
@@ -192,8 +195,13 @@ def hora_group_advantage(group_off: torch.Tensor, reward: torch.Tensor, adv: tor
         int(mode), float(eps), int(ddof), _ptr(dev_status), _stream(stream)), "hora_group_advantage")
 
 
+def hora_token_broadcast_workspace_bytes(n_tokens: int, out_dtype: torch.dtype = torch.float32) -> int:
+    t = {torch.float32: F32, torch.float64: F64}[out_dtype]
+    return int(load_library().hora_token_broadcast_workspace_bytes(int(n_tokens), t))
+
+
 def hora_token_broadcast(adv: torch.Tensor, tok_off: torch.Tensor, tok_adv: torch.Tensor, n_tokens: int,
-                         dev_status: torch.Tensor, stream=None) -> None:
+                         dev_status: torch.Tensor, workspace: torch.Tensor, stream=None) -> None:
     n_resp = adv.numel()
     if tok_off.numel() != n_resp + 1:
         raise ValueError("tok_off needs n_resp + 1 elements")
@@ -202,7 +210,8 @@ def hora_token_broadcast(adv: torch.Tensor, tok_off: torch.Tensor, tok_adv: torc
     _expect(dev_status, torch.int32, 1, "dev_status")
     _check(load_library().hora_token_broadcast(
         n_resp, _ptr(adv), _ftype(adv), _ptr(tok_off), _itype(tok_off), _ptr(tok_adv), _ftype(tok_adv),
-        int(n_tokens), _ptr(dev_status), _stream(stream)), "hora_token_broadcast")
+        int(n_tokens), _ptr(dev_status), _ptr(workspace), workspace.numel() * workspace.element_size(),
+        _stream(stream)), "hora_token_broadcast")
 
 
 # ----------------------------------------------------------------------------
@@ -223,6 +232,7 @@ class Session:
         self.device = torch.device(device)
         self.dev_status = torch.zeros(1, dtype=torch.int32, device=self.device)
         self._workspace = torch.zeros(0, dtype=torch.uint8, device=self.device)
+        self._bcast_workspace = torch.empty(0, dtype=torch.uint8, device=self.device)
 
     def workspace(self, n: int, g0: int) -> torch.Tensor:
         need = hora_allocate_workspace_bytes(n, g0)
@@ -265,10 +275,18 @@ class Session:
         hora_group_advantage(group_off, reward, adv, mode, self.dev_status, eps=eps, ddof=ddof)
         return adv
 
+    def broadcast_workspace(self, n_tokens: int, out_dtype: torch.dtype = torch.float32) -> torch.Tensor:
+        need = hora_token_broadcast_workspace_bytes(n_tokens, out_dtype)
+        if self._bcast_workspace.numel() < need:
+            self._bcast_workspace = torch.empty(need, dtype=torch.uint8, device=self.device)
+        return self._bcast_workspace
+
     def token_broadcast(self, adv: torch.Tensor, tok_off: torch.Tensor, n_tokens: int,
-                        out_dtype: torch.dtype = torch.float32) -> torch.Tensor:
-        tok_adv = torch.empty(n_tokens, dtype=out_dtype, device=self.device)
-        hora_token_broadcast(adv, tok_off, tok_adv, n_tokens, self.dev_status)
+                        out_dtype: torch.dtype = torch.float32,
+                        out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        tok_adv = out if out is not None else torch.empty(n_tokens, dtype=out_dtype, device=self.device)
+        hora_token_broadcast(adv, tok_off, tok_adv, n_tokens, self.dev_status,
+                             self.broadcast_workspace(n_tokens, tok_adv.dtype))
         return tok_adv
 
     def status(self) -> int:

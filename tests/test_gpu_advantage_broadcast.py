@@ -116,7 +116,7 @@ def run_broadcast(gpu, adv, tok_off, out_dtype, itype, skew=0):
     buf = torch.full((total + skew + 5,), float("nan"), dtype=tdt, device="cuda:0")
     out = buf[skew:skew + total]
     print(f"token_broadcast resp={adv.size} tokens={total} {adv.dtype}->{out_dtype} {itype} skew={skew}", flush=True)
-    hora.hora_token_broadcast(dev(torch, adv), dev(torch, tok_off.astype(idt)), out, total, sess.dev_status)
+    sess.token_broadcast(dev(torch, adv), dev(torch, tok_off.astype(idt)), total, out=out)
     assert sess.status() == 0
     return buf
 
@@ -179,8 +179,7 @@ def test_broadcast_shapes_and_edges(gpu, oracle):
     check_broadcast(gpu, oracle, adv, off, "f64", "i64", skew=1)
     # nothing to write
     sess, torch, hora = gpu
-    hora.hora_token_broadcast(dev(torch, adv[:3]), torch.zeros(4, dtype=torch.int64, device="cuda:0"),
-                              torch.zeros(0, dtype=torch.float32, device="cuda:0"), 0, sess.dev_status)
+    sess.token_broadcast(dev(torch, adv[:3].astype(np.float32)), torch.zeros(4, dtype=torch.int64, device="cuda:0"), 0)
     assert sess.status() == 0
 
 
@@ -189,8 +188,7 @@ def test_broadcast_bad_offsets_are_reported(gpu):
     adv = torch.ones(3, dtype=torch.float32, device="cuda:0")
     out = torch.zeros(100, dtype=torch.float32, device="cuda:0")
     for off in ([0, 50, 40, 100], [5, 50, 60, 100], [0, 50, 60, 90]):
-        hora.hora_token_broadcast(adv, torch.tensor(off, dtype=torch.int64, device="cuda:0"), out, 100,
-                                  sess.dev_status)
+        sess.token_broadcast(adv, torch.tensor(off, dtype=torch.int64, device="cuda:0"), 100, out=out)
         assert sess.status() == hora.ERR_RANGE
         sess.dev_status.zero_()
 

@@ -87,11 +87,16 @@ def test_host_argument_validation_needs_no_gpu(lib):
     assert adv(0, fake, 0, 16, fake, fake, 0, 0, 0.0, 0, status, None) == INVALID       # responses without groups
     assert adv(0, fake, 0, 0, fake, fake, 0, 0, 0.0, 0, status, None) == 0
     bc = lib.hora_token_broadcast
-    assert bc(0, fake, 0, fake, 0, fake, 0, 0, status, None) == 0
-    assert bc(0, fake, 0, fake, 0, fake, 0, 5, status, None) == INVALID
-    assert bc(4, fake, 0, fake, 0, fake, 1, 5, status, None) == INVALID                 # float -> double
-    assert bc(4, fake, 0, fake, 0, fake, 0, 1 << 31, status, None) == INVALID           # int32 offsets overflow
-    assert bc(4, fake, 1, fake, 1, ctypes.c_void_p(0x1002), 0, 5, status, None) == INVALID  # misaligned output
+    assert bc(0, fake, 0, fake, 0, fake, 0, 0, status, fake, 1 << 20, None) == 0
+    assert bc(0, fake, 0, fake, 0, fake, 0, 5, status, fake, 1 << 20, None) == INVALID
+    assert bc(4, fake, 0, fake, 0, fake, 1, 5, status, fake, 1 << 20, None) == INVALID        # float -> double
+    assert bc(4, fake, 0, fake, 0, fake, 0, 1 << 31, status, fake, 1 << 30, None) == INVALID  # int32 offsets overflow
+    assert bc(4, fake, 1, fake, 1, ctypes.c_void_p(0x1002), 0, 5, status, fake, 1 << 20, None) == INVALID  # misaligned
+    assert bc(4, fake, 0, fake, 0, fake, 0, 5000, status, None, 0, None) == WORKSPACE
+    assert bc(4, fake, 0, fake, 0, fake, 0, 5000, status, fake, 8, None) == WORKSPACE
+    need = lib.hora_token_broadcast_workspace_bytes(170856406, 0)
+    assert need % 256 == 0 and 4 * 170856406 // 1024 <= need <= 4 * 170856406 // 1024 + 1024
+    assert lib.hora_token_broadcast_workspace_bytes(-1, 0) == 0
     mg = lib.hora_marginal_gains
     assert mg(-1, fake, fake, 4, fake, None, None) == INVALID
     assert mg(0, fake, fake, 4, fake, None, None) == 0
