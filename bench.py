@@ -98,6 +98,8 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain device copy of the token buffer (known size), for scaling HBM counters")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -162,6 +164,9 @@ def main():
         hora.hora_token_broadcast(adv_rloo, tok_off2, tok_rloo, n_tok, sess.dev_status, bws)
 
     bc_mean, bc_min = per_launch_events(torch, one_broadcast, steps2, 3)
+    if args.calibrate_copy:          # reads and writes 4 * n_tok bytes each
+        tok_grpo.copy_(tok_rloo)
+        torch.cuda.synchronize()
     bcast_bytes = 4 * n_tok + n_resp * (8 + 4)       # float stores; offsets and advantages in
     bcast_gbs = bcast_bytes / bc_mean / 1e9
 
