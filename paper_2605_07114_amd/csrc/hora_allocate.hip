@@ -27,14 +27,15 @@
 
 namespace hora {
 
-constexpr int kItems = 8;                     // consecutive prompts per thread and tile
-constexpr int kTile = kThreads * kItems;      // 2048 prompts
-constexpr int kMaxBlocks = 512;               // workgroups of the allocation passes (a power of two)
+constexpr int kBig = 1024;                    // threads per workgroup of the pass-1 / pass-2 / write kernels
+constexpr int kBigWaves = kBig / kWave;       // 16
+constexpr int kItems = 4;                     // consecutive prompts per thread and tile
+constexpr int kTile = kBig * kItems;          // 4096 prompts
+constexpr int kMaxBlocks = 256;               // workgroups of the allocation passes (a power of two)
 constexpr int kMaxClasses = HORA_CLASS_MAX_G0 + 1;
 constexpr int kMinRow = 32;                   // gain-table row length (a power of two), at least
 constexpr int kMaxRow = 256;                  // ... and at most
 constexpr int kTableCap = kMaxClasses * kMinRow;   // doubles per table (2048)
-static_assert(kMaxBlocks == 2 * kThreads, "pass 2 reads two histogram entries per thread and class");
 constexpr int kBisectSteps = 64;              // enough for any 63-bit bracket
 constexpr unsigned kTiedBit = 0x80000000u;
 
@@ -176,8 +177,8 @@ struct EmitCarry {
 };
 
 struct EmitShared {        // LDS exchange between the wavefronts of a workgroup, double-buffered
-    int tied[2][kWaves];
-    long long ksum[2][kWaves];
+    int tied[2][kBigWaves];
+    long long ksum[2][kBigWaves];
 };
 
 template <typename V, typename T>
@@ -227,18 +228,23 @@ __device__ __forceinline__ void emit_tile(int tile_parity, long long pos, long l
         if (kOff != 0) sh->ksum[tile_parity][w] = ks_wave;
     }
     __syncthreads();
-    int t_lower = 0, t_total = 0;
+    // totals of the lower wavefronts: lanes 0..15 hold one wavefront's total each, a DPP
+    // prefix sum inside the first row of 16 lanes gives every wavefront its base
+    const int lane = lane_id();
+    const int t_in = lane < kBigWaves ? sh->tied[tile_parity][lane] : 0;
+    const int t_scan = wave_incl_scan_i32(t_in);
+    const int t_total = __builtin_amdgcn_readlane(t_scan, kBigWaves - 1);
+    const int t_lower = w > 0 ? __builtin_amdgcn_readlane(t_scan, w - 1) : 0;
     long long ks_lower = 0, ks_total = 0;
-#pragma unroll
-    for (int i = 0; i < kWaves; ++i) {
-        const int t = sh->tied[tile_parity][i];
-        if (i < w) t_lower += t;
-        t_total += t;
-        if (kOff != 0) {
-            const long long q = sh->ksum[tile_parity][i];
-            if (i < w) ks_lower += q;
-            ks_total += q;
-        }
+    if (kOff != 0) {
+        const long long q_in = lane < kBigWaves ? sh->ksum[tile_parity][lane] : 0;
+        const long long q_scan = wave_incl_scan_i64(q_in);
+        const int q_lo = (int)(q_scan & 0xffffffffll), q_hi = (int)(q_scan >> 32);
+        ks_total = ((long long)__builtin_amdgcn_readlane(q_hi, kBigWaves - 1) << 32) |
+                   (unsigned)__builtin_amdgcn_readlane(q_lo, kBigWaves - 1);
+        if (w > 0)
+            ks_lower = ((long long)__builtin_amdgcn_readlane(q_hi, w - 1) << 32) |
+                       (unsigned)__builtin_amdgcn_readlane(q_lo, w - 1);
     }
     long long rank = carry.rank_base + t_lower + t_before;
     long long kprior = carry.ks_base + ks_lower + (ks_incl - ks);
@@ -296,12 +302,11 @@ __device__ __forceinline__ void load_items_i32(const int32_t* __restrict__ src, 
     }
 }
 
-__global__ __launch_bounds__(kThreads) void k_class_hist(const int32_t* __restrict__ c, long long n, int g0,
-                                                         double alpha0, double beta0, long long chunk, int nb,
-                                                         int row, int* __restrict__ class_hist,
-                                                         double* __restrict__ gain_table,
-                                                         double* __restrict__ surv_table, int32_t* dev_status) {
-    __shared__ int s_cnt[kWaves][kWave];
+__global__ __launch_bounds__(kBig) void k_class_hist(const int32_t* __restrict__ c, long long n, int g0,
+                                                     double alpha0, double beta0, long long chunk, int nb, int row,
+                                                     int* __restrict__ class_hist, double* __restrict__ gain_table,
+                                                     double* __restrict__ surv_table, int32_t* dev_status) {
+    __shared__ int s_cnt[kBigWaves][kWave];
     const int lane = lane_id();
     if ((int)blockIdx.x == nb) {   // the extra workgroup: tables, one lane per class
         if (threadIdx.x <= (unsigned)g0) {
@@ -352,7 +357,7 @@ __global__ __launch_bounds__(kThreads) void k_class_hist(const int32_t* __restri
     if (threadIdx.x <= (unsigned)g0) {
         int tot = 0;
 #pragma unroll
-        for (int w = 0; w < kWaves; ++w) tot += s_cnt[w][threadIdx.x];
+        for (int w = 0; w < kBigWaves; ++w) tot += s_cnt[w][threadIdx.x];
         class_hist[(long long)threadIdx.x * kMaxBlocks + blockIdx.x] = tot;
     }
     if (bad) report(dev_status, HORA_ERR_RANGE);
@@ -397,7 +402,7 @@ __device__ void solve_by_table(int nc, int row_len, int len, bool rows_end_at_ca
     if (threadIdx.x == 0) sol->found = 0;
     __syncthreads();
     const int row_shift = __ffs(row_len) - 1;
-    for (int idx = (int)threadIdx.x; idx < nc * row_len; idx += kThreads) {
+    for (int idx = (int)threadIdx.x; idx < nc * row_len; idx += kBig) {
         const int c = idx >> row_shift, l = idx & (row_len - 1);
         if (l >= len || s_n[c] == 0) continue;
         const unsigned long long v = gain_bits(s_gain[idx]);
@@ -526,7 +531,7 @@ __device__ void solve_by_greedy(int g0, double alpha0, double beta0, long long c
 // kOff: 0 no offsets, 1 int32 offsets, 2 int64 offsets.
 // ----------------------------------------------------------------------------------
 template <int kOff>
-__global__ __launch_bounds__(kThreads) void k_class_write(const int32_t* __restrict__ c, long long n, int g0,
+__global__ __launch_bounds__(kBig) void k_class_write(const int32_t* __restrict__ c, long long n, int g0,
                                                           double alpha0, double beta0, long long budget, int cap,
                                                           long long chunk, int nb, int row_len,
                                                           const int* __restrict__ class_hist,
@@ -538,7 +543,7 @@ __global__ __launch_bounds__(kThreads) void k_class_write(const int32_t* __restr
                                                           int32_t* dev_status) {
     __shared__ double s_gain[kTableCap];
     __shared__ double s_surv[kTableCap];
-    __shared__ long long s_part[kWaves][2][kMaxClasses];
+    __shared__ long long s_part[2][kMaxClasses * kMaxBlocks / kWave];
     __shared__ long long s_n[kMaxClasses];       // prompts per class, whole batch
     __shared__ long long s_before[kMaxClasses];  // prompts per class in workgroups before this one
     __shared__ ClassSolution s_sol;
@@ -546,7 +551,6 @@ __global__ __launch_bounds__(kThreads) void k_class_write(const int32_t* __restr
 
     const int nc = g0 + 1;
     const int lane = lane_id();
-    const int w = wave_id();
     const long long base = (long long)blockIdx.x * chunk;
     const long long end = base + chunk < n ? base + chunk : n;
     const bool c_vec = (reinterpret_cast<uintptr_t>(c) & 15) == 0;
@@ -563,38 +567,35 @@ __global__ __launch_bounds__(kThreads) void k_class_write(const int32_t* __restr
 
     // tables into LDS, gains beyond `len` replaced by zeros
     const int table_len = nc * row_len;
-    for (int i = (int)threadIdx.x; i < table_len; i += kThreads) {
+    for (int i = (int)threadIdx.x; i < table_len; i += kBig) {
         const double g = gain_table[i];
         s_gain[i] = (i & (row_len - 1)) < len ? g : 0.0;
         s_surv[i] = surv_table[i];
     }
 
-    // class totals and the part that lies before this workgroup: thread t reads the
-    // counts of workgroups t and t + 256 of each class, four classes per round
-    for (int c0 = 0; c0 < nc; c0 += 4) {
-        int h0[4], h1[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int cc = c0 + i < nc ? c0 + i : c0;
-            const int b0 = (int)threadIdx.x, b1 = (int)threadIdx.x + kThreads;
-            h0[i] = b0 < nb ? class_hist[cc * kMaxBlocks + b0] : 0;
-            h1[i] = b1 < nb ? class_hist[cc * kMaxBlocks + b1] : 0;
-        }
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const long long tot = (long long)h0[i] + h1[i];
-            const long long bef = ((int)threadIdx.x < (int)blockIdx.x ? (long long)h0[i] : 0) +
-                                  ((int)threadIdx.x + kThreads < (int)blockIdx.x ? (long long)h1[i] : 0);
-            const long long tot_w = wave_total_i64(tot);
-            const long long bef_w = wave_total_i64(bef);
-            if (lane == 0 && c0 + i < nc) { s_part[w][0][c0 + i] = tot_w; s_part[w][1][c0 + i] = bef_w; }
+    // class totals and the part that lies before this workgroup: the counts of class c
+    // are kMaxBlocks consecutive entries, so every wavefront sums entries of one class
+    {
+        const int entries = nc * kMaxBlocks;
+        for (int i0 = 0; i0 < entries; i0 += kBig) {
+            const int idx = i0 + (int)threadIdx.x;
+            const int b = idx & (kMaxBlocks - 1);
+            int h = 0;
+            if (idx < entries && b < nb) h = class_hist[idx];
+            const long long tot_w = wave_total_i64((long long)h);
+            const long long bef_w = wave_total_i64(b < (int)blockIdx.x ? (long long)h : 0ll);
+            if (lane == 0 && idx < entries) { s_part[0][idx >> 6] = tot_w; s_part[1][idx >> 6] = bef_w; }
         }
     }
     __syncthreads();
     if (threadIdx.x < (unsigned)nc) {
+        constexpr int kSlots = kMaxBlocks / kWave;
         long long tot = 0, bef = 0;
 #pragma unroll
-        for (int i = 0; i < kWaves; ++i) { tot += s_part[i][0][threadIdx.x]; bef += s_part[i][1][threadIdx.x]; }
+        for (int q = 0; q < kSlots; ++q) {
+            tot += s_part[0][threadIdx.x * kSlots + q];
+            bef += s_part[1][threadIdx.x * kSlots + q];
+        }
         s_n[threadIdx.x] = tot;
         s_before[threadIdx.x] = bef;
     }
@@ -858,7 +859,7 @@ __global__ __launch_bounds__(kThreads) void k_bisect_scan(int nb, long long budg
 // BISECT write: delta[i] holds k_i with the tied flag in bit 31 and util[i] the survival
 // product E_i(k_i); a winner's utility takes one more step of the product.
 template <class Src, int kOff>
-__global__ __launch_bounds__(kThreads) void k_bisect_write(Src src, long long n, int g0, long long chunk,
+__global__ __launch_bounds__(kBig) void k_bisect_write(Src src, long long n, int g0, long long chunk,
                                                            const BisectSolution* __restrict__ sol,
                                                            const long long* __restrict__ block_ksum,
                                                            const long long* __restrict__ block_tied,
@@ -991,12 +992,12 @@ static int run_class(const int32_t* c, double alpha0, double beta0, const Common
     const int nc = a.g0 + 1;
     const int row = table_row(nc, a.n, a.budget, a.delta_max);
     const int cap = a.delta_max > 0 ? a.delta_max : 0;
-    hipLaunchKernelGGL(k_class_hist, dim3(p.nb + 1), dim3(kThreads), 0, a.stream, c, (long long)a.n, (int)a.g0,
+    hipLaunchKernelGGL(k_class_hist, dim3(p.nb + 1), dim3(kBig), 0, a.stream, c, (long long)a.n, (int)a.g0,
                        alpha0, beta0, p.chunk, p.nb, row, w.class_hist, w.gain_table, w.surv_table,
                        a.dev_status);
     const int mode = a.group_off ? (a.off_t == HORA_I32 ? 1 : 2) : 0;
 #define HORA_LAUNCH_CLASS_WRITE(M)                                                                              \
-    hipLaunchKernelGGL((k_class_write<M>), dim3(p.nb), dim3(kThreads), 0, a.stream, c, (long long)a.n,          \
+    hipLaunchKernelGGL((k_class_write<M>), dim3(p.nb), dim3(kBig), 0, a.stream, c, (long long)a.n,          \
                        (int)a.g0, alpha0, beta0, (long long)a.budget, cap, p.chunk, p.nb, row, w.class_hist,   \
                        w.gain_table, w.surv_table, a.delta, a.util, a.group_off, a.summary, a.dev_status)
     if (mode == 0) HORA_LAUNCH_CLASS_WRITE(0);
@@ -1025,7 +1026,7 @@ static int run_bisect(const Src& src, const CommonArgs& a, const Plan& p, const 
                        w.sol, w.block_ksum, w.block_tied, a.summary, a.dev_status);
     const int mode = a.group_off ? (a.off_t == HORA_I32 ? 1 : 2) : 0;
 #define HORA_LAUNCH_BISECT_WRITE(M)                                                                          \
-    hipLaunchKernelGGL((k_bisect_write<Src, M>), dim3(p.nb), dim3(kThreads), 0, a.stream, src, n, (int)a.g0, \
+    hipLaunchKernelGGL((k_bisect_write<Src, M>), dim3(p.nb), dim3(kBig), 0, a.stream, src, n, (int)a.g0, \
                        p.chunk, w.sol, w.block_ksum, w.block_tied, a.delta, a.util, a.group_off)
     if (mode == 0) HORA_LAUNCH_BISECT_WRITE(0);
     else if (mode == 1) HORA_LAUNCH_BISECT_WRITE(1);
