@@ -13,8 +13,10 @@
 //         workgroup and evaluates the G0+1 gain sequences once into a table.  Pass 2
 //         (every workgroup on its own, no grid-wide wait) ranks the table entries
 //         against the histogram to find tau, then writes its share of the outputs.
-//  BISECT (any posterior): bisection on the bit pattern of tau; every step counts
-//         #{(i,l) : M_i(l) > tau} with a monotone walk per prompt.
+//  BISECT (any posterior): the bracket of tau's bit pattern is narrowed in passes; in
+//         each pass every prompt walks its gains down to the bracket (a monotone
+//         search) and the gains inside it are tallied per interval, so that a pass
+//         cuts the bracket 128-fold or more (a 256-way bisection step).
 // Both resolve the ties at tau by prompt index with prefix counts.
 #include <hip/hip_runtime.h>
 
@@ -36,20 +38,28 @@ constexpr int kMaxClasses = HORA_CLASS_MAX_G0 + 1;
 constexpr int kMinRow = 32;                   // gain-table row length (a power of two), at least
 constexpr int kMaxRow = 256;                  // ... and at most
 constexpr int kTableCap = kMaxClasses * kMinRow;   // doubles per table (2048)
-constexpr int kBisectSteps = 64;              // enough for any 63-bit bracket
 constexpr unsigned kTiedBit = 0x80000000u;
+
+constexpr int kBins = 256;        // intervals per narrowing pass of the threshold search
+constexpr int kSelectPasses = 9;  // every pass cuts the bracket at least 128-fold: enough for 63 bits
 
 struct AllocHeader {              // 256 bytes at the start of the workspace, zero at rest
     unsigned long long lo_inv;    // ~bits of min_i M_i(W-1), gathered with atomicMax
     unsigned long long hi;        // bits of max_i M_i(0), gathered with atomicMax
-    unsigned long long count;     // pairs counted so far in the running bisection step
-    unsigned int ticket;          // workgroups that have contributed to `count`
-    unsigned int pad0;
+    unsigned long long above;     // pairs above the bracket counted in the running pass
+    unsigned int ticket;          // workgroups that have finished the running pass
+    unsigned int done;            // the bracket has closed: tau = hi_cur
     unsigned long long lo_cur;    // bracket: count_gt(lo_cur) >= budget
     unsigned long long hi_cur;    // bracket: count_gt(hi_cur) <  budget
     unsigned long long pad[26];
 };
 static_assert(sizeof(AllocHeader) == 256, "header size");
+
+struct SelectBins {               // per-interval tallies of one narrowing pass, zero at rest
+    unsigned long long cnt[kBins];       // pairs whose gain falls into the interval
+    unsigned long long vmax[kBins];      // largest gain pattern seen in the interval
+    unsigned long long vmin_inv[kBins];  // ~(smallest gain pattern seen in the interval)
+};
 
 struct BisectSolution {           // written by k_bisect_scan, read by k_bisect_write
     long long r;                  // units for the prompts tied at tau
@@ -78,6 +88,7 @@ static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 struct Workspace {
     AllocHeader* header;
     BisectSolution* sol;
+    SelectBins* bins;
     int* class_hist;        // [kMaxClasses][kMaxBlocks]: prompts of class c in workgroup b
     double* gain_table;     // [nc][row]: M_c(l)
     double* surv_table;     // [nc][row]: E_c(l)
@@ -96,6 +107,8 @@ static Workspace carve(void* base) {
     off += sizeof(AllocHeader);
     w.sol = (BisectSolution*)(ptr + off);
     off += sizeof(BisectSolution);
+    w.bins = (SelectBins*)(ptr + off);
+    off += sizeof(SelectBins);
     w.class_hist = (int*)(ptr + off);
     off += align256((size_t)kMaxClasses * kMaxBlocks * sizeof(int));
     w.gain_table = (double*)(ptr + off);
@@ -664,17 +677,17 @@ __global__ __launch_bounds__(kBig) void k_class_write(const int32_t* __restrict_
 // ----------------------------------------------------------------------------------
 // BISECT pass 0: bracket of tau.  With W = ceil(budget / n) every prompt has at least
 // W gains >= lo = min_i M_i(W-1), so count_ge(lo) >= budget and tau >= lo; and no
-// gain exceeds hi = max_i M_i(0).  Both are gathered with integer atomicMax.
+// gain exceeds hi = max_i M_i(0).  Both are gathered with integer atomicMax; the
+// workgroup that finishes last publishes the bracket (lo - 1, hi].
 // ----------------------------------------------------------------------------------
 template <class Src>
-__global__ __launch_bounds__(kThreads) void k_bisect_bracket(Src src, long long n, long long chunk, long long w_steps,
+__global__ __launch_bounds__(kThreads) void k_select_bracket(Src src, long long n, long long w_steps,
                                                              AllocHeader* __restrict__ hdr, int32_t* dev_status) {
     __shared__ unsigned long long s_red[kWaves];
-    const long long base = (long long)blockIdx.x * chunk;
-    const long long end = base + chunk < n ? base + chunk : n;
     unsigned long long hi = 0, lo_inv = 0;
     bool bad = false;
-    for (long long i = base + threadIdx.x; i < end; i += kThreads) {
+    const long long stride = (long long)gridDim.x * kThreads;
+    for (long long i = (long long)blockIdx.x * kThreads + threadIdx.x; i < n; i += stride) {
         double a, b;
         bad |= !src.load(i, a, b);
         const double s = a + b;
@@ -693,18 +706,26 @@ __global__ __launch_bounds__(kThreads) void k_bisect_bracket(Src src, long long 
     lo_inv = wave_max_u64(lo_inv);
     if (lane_id() == 0) s_red[wave_id()] = hi;
     __syncthreads();
-    if (threadIdx.x == 0) {
-        unsigned long long m = 0;
-        for (int i = 0; i < kWaves; ++i) m = s_red[i] > m ? s_red[i] : m;
-        atomicMax(&hdr->hi, m);
-    }
+    unsigned long long block_hi = 0;
+    for (int i = 0; i < kWaves; ++i) block_hi = s_red[i] > block_hi ? s_red[i] : block_hi;
     __syncthreads();
     if (lane_id() == 0) s_red[wave_id()] = lo_inv;
     __syncthreads();
     if (threadIdx.x == 0) {
-        unsigned long long m = 0;
-        for (int i = 0; i < kWaves; ++i) m = s_red[i] > m ? s_red[i] : m;
-        atomicMax(&hdr->lo_inv, m);
+        unsigned long long block_lo_inv = 0;
+        for (int i = 0; i < kWaves; ++i) block_lo_inv = s_red[i] > block_lo_inv ? s_red[i] : block_lo_inv;
+        atomicMax(&hdr->hi, block_hi);
+        atomicMax(&hdr->lo_inv, block_lo_inv);
+        __threadfence();
+        if (atomicAdd(&hdr->ticket, 1u) == gridDim.x - 1) {
+            __threadfence();
+            const unsigned long long all_hi = atomicMax(&hdr->hi, 0ull);
+            const unsigned long long all_lo = ~atomicMax(&hdr->lo_inv, 0ull);
+            hdr->lo_cur = all_lo - 1ull;
+            hdr->hi_cur = all_hi;
+            hdr->done = (all_hi - (all_lo - 1ull) <= 1ull) ? 1u : 0u;
+            hdr->ticket = 0u;
+        }
     }
     if (bad) report(dev_status, HORA_ERR_RANGE);
 }
@@ -730,53 +751,97 @@ __device__ __forceinline__ long long walk_above(double a, double b, unsigned lon
 }
 
 // ----------------------------------------------------------------------------------
-// BISECT step: count the pairs above the midpoint of the bracket.  The workgroup that
-// contributes last narrows the bracket for the next launch and clears the counters.
-// Invariant: count_gt(lo_cur) >= budget > count_gt(hi_cur).  Step 0 seeds the bracket
-// from pass 0.  Once hi_cur - lo_cur <= 1, tau = hi_cur and later launches return at once.
+// BISECT narrowing pass.  Invariant: count_gt(lo_cur) >= budget > count_gt(hi_cur).
+// The bracket (lo, hi] is cut into at most kBins intervals of 2^shift bit patterns.
+// Every prompt walks its gains down to lo (a monotone search); gains above hi are
+// counted, gains inside the bracket are tallied per interval together with the largest
+// and the smallest pattern seen there.  The workgroup that finishes last finds the
+// interval in which the running count (from the top) reaches the budget and shrinks the
+// bracket to the gains that actually occur in it: (min - 1, max].  When min == max the
+// threshold is that gain.  Each pass cuts the bracket at least 128-fold; gain values
+// that repeat many times (a shared prior) close it in two or three passes.
 // ----------------------------------------------------------------------------------
 template <class Src>
-__global__ __launch_bounds__(kThreads) void k_bisect_step(Src src, long long n, long long chunk, long long budget,
-                                                          long long limit, int step, AllocHeader* __restrict__ hdr) {
+__global__ __launch_bounds__(kThreads) void k_select_pass(Src src, long long n, long long budget, long long limit,
+                                                          AllocHeader* __restrict__ hdr,
+                                                          SelectBins* __restrict__ bins) {
+    __shared__ unsigned long long s_cnt[kBins];
+    __shared__ unsigned long long s_max[kBins];
+    __shared__ unsigned long long s_min_inv[kBins];
     __shared__ long long s_red[kWaves];
-    unsigned long long lo, hi;
-    if (step == 0) {
-        lo = ~hdr->lo_inv - 1ull;
-        hi = hdr->hi;
-    } else {
-        lo = hdr->lo_cur;
-        hi = hdr->hi_cur;
-    }
-    if (hi - lo <= 1ull) {
-        if (step == 0 && blockIdx.x == 0 && threadIdx.x == 0) { hdr->lo_cur = lo; hdr->hi_cur = hi; }
-        return;
-    }
-    const unsigned long long mid = lo + (hi - lo) / 2ull;
-    const long long base = (long long)blockIdx.x * chunk;
-    const long long end = base + chunk < n ? base + chunk : n;
-    long long cnt = 0;
-    for (long long i = base + threadIdx.x; i < end; i += kThreads) {
-        double a, b, g, lf, e;
+    __shared__ int s_last;
+    if (hdr->done) return;
+    const unsigned long long lo = hdr->lo_cur, hi = hdr->hi_cur;
+    const unsigned long long width = hi - lo;                 // >= 2
+    const int bitlen = 64 - __clzll((long long)(width - 1));   // bits of width - 1
+    const int shift = bitlen > 8 ? bitlen - 8 : 0;            // (width - 1) >> shift < kBins
+    for (int j = (int)threadIdx.x; j < kBins; j += kThreads) { s_cnt[j] = 0; s_max[j] = 0; s_min_inv[j] = 0; }
+    __syncthreads();
+
+    long long above = 0;
+    const long long stride = (long long)gridDim.x * kThreads;
+    for (long long i = (long long)blockIdx.x * kThreads + threadIdx.x; i < n; i += stride) {
+        double a, b;
         src.load(i, a, b);
-        cnt += walk_above<false>(a, b, mid, limit, g, lf, e);
-        if (cnt > budget) cnt = budget;  // only the comparison with budget matters
+        const double s = a + b;
+        double g = gain_first(a, s);
+        double lf = 0.0;
+        long long k = 0;
+        unsigned long long gb = gain_bits(g);
+        while (k < limit && gb > lo) {
+            if (gb > hi) {
+                above += 1;
+            } else {
+                const int j = (int)((gb - lo - 1ull) >> shift);
+                atomicAdd(&s_cnt[j], 1ull);
+                atomicMax(&s_max[j], gb);
+                atomicMax(&s_min_inv[j], ~gb);
+            }
+            g = gain_next(g, b, s, lf);
+            lf += 1.0;
+            k += 1;
+            gb = gain_bits(g);
+        }
+        if (above > budget) above = budget;   // only the comparison with the budget matters
     }
-    long long tot = block_sum<long long>(cnt, s_red);
-    if (threadIdx.x == 0) {
-        if (tot > budget) tot = budget;
-        atomicAdd(&hdr->count, (unsigned long long)tot);
-        __threadfence();
-        unsigned int t = atomicAdd(&hdr->ticket, 1u);
-        if (t == gridDim.x - 1) {
-            __threadfence();
-            unsigned long long total = atomicAdd(&hdr->count, 0ull);
-            if (total < (unsigned long long)budget) hi = mid; else lo = mid;
-            hdr->lo_cur = lo;
-            hdr->hi_cur = hi;
-            hdr->count = 0ull;
-            hdr->ticket = 0u;
+    long long above_block = block_sum<long long>(above, s_red);
+    if (above_block > budget) above_block = budget;
+    __syncthreads();
+    for (int j = (int)threadIdx.x; j < kBins; j += kThreads) {
+        const unsigned long long cj = s_cnt[j];
+        if (cj) {
+            atomicAdd(&bins->cnt[j], cj > (unsigned long long)budget ? (unsigned long long)budget : cj);
+            atomicMax(&bins->vmax[j], s_max[j]);
+            atomicMax(&bins->vmin_inv[j], s_min_inv[j]);
         }
     }
+    if (threadIdx.x == 0 && above_block) atomicAdd(&hdr->above, (unsigned long long)above_block);
+    __threadfence();
+    __syncthreads();
+    if (threadIdx.x == 0) s_last = atomicAdd(&hdr->ticket, 1u) == gridDim.x - 1 ? 1 : 0;
+    __syncthreads();
+    if (!s_last) return;
+
+    // last workgroup: running count from the top interval down, one interval per thread
+    __threadfence();
+    static_assert(kBins == kThreads, "one interval per thread");
+    const int j = kBins - 1 - (int)threadIdx.x;               // thread 0 owns the top interval
+    const unsigned long long cj = atomicAdd(&bins->cnt[j], 0ull);
+    const unsigned long long mx = atomicMax(&bins->vmax[j], 0ull);
+    const unsigned long long mn = ~atomicMax(&bins->vmin_inv[j], 0ull);
+    const long long start = (long long)atomicAdd(&hdr->above, 0ull);
+    long long total;
+    long long before = block_excl_scan<long long>((long long)cj, s_red, total);   // pairs in higher intervals
+    before += start;
+    if (cj != 0 && before < budget && budget <= before + (long long)cj) {   // exactly one thread
+        hdr->hi_cur = mx;
+        hdr->lo_cur = mn - 1ull;
+        hdr->done = (mx == mn) ? 1u : 0u;
+    }
+    bins->cnt[j] = 0ull;
+    bins->vmax[j] = 0ull;
+    bins->vmin_inv[j] = 0ull;
+    if (threadIdx.x == 0) { hdr->above = 0ull; hdr->ticket = 0u; }
 }
 
 // ----------------------------------------------------------------------------------
@@ -785,17 +850,17 @@ __global__ __launch_bounds__(kThreads) void k_bisect_step(Src src, long long n, 
 // sums go to block_ksum / block_tied.
 // ----------------------------------------------------------------------------------
 template <class Src>
-__global__ __launch_bounds__(kThreads) void k_bisect_finalize(Src src, long long n, long long chunk, long long budget,
-                                                              long long limit, const AllocHeader* __restrict__ hdr,
-                                                              int32_t* __restrict__ delta, double* __restrict__ util,
-                                                              long long* __restrict__ block_ksum,
-                                                              long long* __restrict__ block_tied) {
-    __shared__ long long s_red[kWaves];
+__global__ __launch_bounds__(kBig) void k_bisect_finalize(Src src, long long n, long long chunk, long long budget,
+                                                          long long limit, const AllocHeader* __restrict__ hdr,
+                                                          int32_t* __restrict__ delta, double* __restrict__ util,
+                                                          long long* __restrict__ block_ksum,
+                                                          long long* __restrict__ block_tied) {
+    __shared__ long long s_red[2][kBigWaves];
     const unsigned long long tau_bits = budget > 0 ? hdr->hi_cur : ~0ull;
     const long long base = (long long)blockIdx.x * chunk;
     const long long end = base + chunk < n ? base + chunk : n;
     long long ks = 0, ts = 0;
-    for (long long i = base + threadIdx.x; i < end; i += kThreads) {
+    for (long long i = base + threadIdx.x; i < end; i += kBig) {
         double a, b, g, lf, e;
         src.load(i, a, b);
         const long long k = walk_above<true>(a, b, tau_bits, limit, g, lf, e);
@@ -805,11 +870,15 @@ __global__ __launch_bounds__(kThreads) void k_bisect_finalize(Src src, long long
         ks += k;
         ts += tied ? 1 : 0;
     }
-    ks = block_sum<long long>(ks, s_red);
-    ts = block_sum<long long>(ts, s_red);
+    ks = wave_total_i64(ks);
+    ts = wave_total_i64(ts);
+    if (lane_id() == 0) { s_red[0][wave_id()] = ks; s_red[1][wave_id()] = ts; }
+    __syncthreads();
     if (threadIdx.x == 0) {
-        block_ksum[blockIdx.x] = ks;
-        block_tied[blockIdx.x] = ts;
+        long long ksum = 0, tsum = 0;
+        for (int i = 0; i < kBigWaves; ++i) { ksum += s_red[0][i]; tsum += s_red[1][i]; }
+        block_ksum[blockIdx.x] = ksum;
+        block_tied[blockIdx.x] = tsum;
     }
 }
 
@@ -849,8 +918,9 @@ __global__ __launch_bounds__(kThreads) void k_bisect_scan(int nb, long long budg
         }
         hdr->lo_inv = 0ull;
         hdr->hi = 0ull;
-        hdr->count = 0ull;
+        hdr->above = 0ull;
         hdr->ticket = 0u;
+        hdr->done = 0u;
         hdr->lo_cur = 0ull;
         hdr->hi_cur = 0ull;
     }
@@ -1013,19 +1083,21 @@ static int run_bisect(const Src& src, const CommonArgs& a, const Plan& p, const 
     long long limit = a.delta_max > 0 ? (long long)a.delta_max : a.budget;
     if (limit > a.budget) limit = a.budget;
     if (a.budget > 0) {
+        long long blocks = (n + kThreads - 1) / kThreads;
+        if (blocks > 2048) blocks = 2048;
         const long long w_steps = (a.budget + n - 1) / n;
-        hipLaunchKernelGGL((k_bisect_bracket<Src>), dim3(p.nb), dim3(kThreads), 0, a.stream, src, n, p.chunk,
+        hipLaunchKernelGGL((k_select_bracket<Src>), dim3((unsigned)blocks), dim3(kThreads), 0, a.stream, src, n,
                            w_steps, w.header, a.dev_status);
-        for (int step = 0; step < kBisectSteps; ++step)
-            hipLaunchKernelGGL((k_bisect_step<Src>), dim3(p.nb), dim3(kThreads), 0, a.stream, src, n, p.chunk,
-                               (long long)a.budget, limit, step, w.header);
+        for (int pass = 0; pass < kSelectPasses; ++pass)
+            hipLaunchKernelGGL((k_select_pass<Src>), dim3((unsigned)blocks), dim3(kThreads), 0, a.stream, src, n,
+                               (long long)a.budget, limit, w.header, w.bins);
     }
-    hipLaunchKernelGGL((k_bisect_finalize<Src>), dim3(p.nb), dim3(kThreads), 0, a.stream, src, n, p.chunk,
+    hipLaunchKernelGGL((k_bisect_finalize<Src>), dim3(p.nb), dim3(kBig), 0, a.stream, src, n, p.chunk,
                        (long long)a.budget, limit, w.header, a.delta, a.util, w.block_ksum, w.block_tied);
     hipLaunchKernelGGL(k_bisect_scan, dim3(1), dim3(kThreads), 0, a.stream, p.nb, (long long)a.budget, w.header,
                        w.sol, w.block_ksum, w.block_tied, a.summary, a.dev_status);
     const int mode = a.group_off ? (a.off_t == HORA_I32 ? 1 : 2) : 0;
-#define HORA_LAUNCH_BISECT_WRITE(M)                                                                          \
+#define HORA_LAUNCH_BISECT_WRITE(M)                                                                      \
     hipLaunchKernelGGL((k_bisect_write<Src, M>), dim3(p.nb), dim3(kBig), 0, a.stream, src, n, (int)a.g0, \
                        p.chunk, w.sol, w.block_ksum, w.block_tied, a.delta, a.util, a.group_off)
     if (mode == 0) HORA_LAUNCH_BISECT_WRITE(0);
