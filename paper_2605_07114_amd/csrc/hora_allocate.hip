@@ -42,6 +42,8 @@ constexpr unsigned kTiedBit = 0x80000000u;
 
 constexpr int kBins = 256;        // intervals per narrowing pass of the threshold search
 constexpr int kSelectPasses = 9;  // every pass cuts the bracket at least 128-fold: enough for 63 bits
+constexpr int kSoloMaxPrompts = 8192;   // up to here one workgroup searches alone
+constexpr int kParallelPasses = 4;   // launched grid-wide; a single-workgroup finisher covers the rest
 
 struct AllocHeader {              // 256 bytes at the start of the workspace, zero at rest
     unsigned long long lo_inv;    // ~bits of min_i M_i(W-1), gathered with atomicMax
@@ -677,17 +679,18 @@ __global__ __launch_bounds__(kBig) void k_class_write(const int32_t* __restrict_
 // ----------------------------------------------------------------------------------
 // BISECT pass 0: bracket of tau.  With W = ceil(budget / n) every prompt has at least
 // W gains >= lo = min_i M_i(W-1), so count_ge(lo) >= budget and tau >= lo; and no
-// gain exceeds hi = max_i M_i(0).  Both are gathered with integer atomicMax; the
-// workgroup that finishes last publishes the bracket (lo - 1, hi].
+// gain exceeds hi = max_i M_i(0).  Both are gathered with integer atomicMax (few
+// workgroups: atomics on one address serialise); the workgroup that finishes last
+// publishes the bracket (lo - 1, hi].
 // ----------------------------------------------------------------------------------
 template <class Src>
-__global__ __launch_bounds__(kThreads) void k_select_bracket(Src src, long long n, long long w_steps,
-                                                             AllocHeader* __restrict__ hdr, int32_t* dev_status) {
-    __shared__ unsigned long long s_red[kWaves];
+__global__ __launch_bounds__(kBig) void k_select_bracket(Src src, long long n, long long w_steps,
+                                                         AllocHeader* __restrict__ hdr, int32_t* dev_status) {
+    __shared__ unsigned long long s_red[2][kBigWaves];
     unsigned long long hi = 0, lo_inv = 0;
     bool bad = false;
-    const long long stride = (long long)gridDim.x * kThreads;
-    for (long long i = (long long)blockIdx.x * kThreads + threadIdx.x; i < n; i += stride) {
+    const long long stride = (long long)gridDim.x * kBig;
+    for (long long i = (long long)blockIdx.x * kBig + threadIdx.x; i < n; i += stride) {
         double a, b;
         bad |= !src.load(i, a, b);
         const double s = a + b;
@@ -704,16 +707,14 @@ __global__ __launch_bounds__(kThreads) void k_select_bracket(Src src, long long 
     }
     hi = wave_max_u64(hi);
     lo_inv = wave_max_u64(lo_inv);
-    if (lane_id() == 0) s_red[wave_id()] = hi;
-    __syncthreads();
-    unsigned long long block_hi = 0;
-    for (int i = 0; i < kWaves; ++i) block_hi = s_red[i] > block_hi ? s_red[i] : block_hi;
-    __syncthreads();
-    if (lane_id() == 0) s_red[wave_id()] = lo_inv;
+    if (lane_id() == 0) { s_red[0][wave_id()] = hi; s_red[1][wave_id()] = lo_inv; }
     __syncthreads();
     if (threadIdx.x == 0) {
-        unsigned long long block_lo_inv = 0;
-        for (int i = 0; i < kWaves; ++i) block_lo_inv = s_red[i] > block_lo_inv ? s_red[i] : block_lo_inv;
+        unsigned long long block_hi = 0, block_lo_inv = 0;
+        for (int i = 0; i < kBigWaves; ++i) {
+            block_hi = s_red[0][i] > block_hi ? s_red[0][i] : block_hi;
+            block_lo_inv = s_red[1][i] > block_lo_inv ? s_red[1][i] : block_lo_inv;
+        }
         atomicMax(&hdr->hi, block_hi);
         atomicMax(&hdr->lo_inv, block_lo_inv);
         __threadfence();
@@ -755,93 +756,154 @@ __device__ __forceinline__ long long walk_above(double a, double b, unsigned lon
 // The bracket (lo, hi] is cut into at most kBins intervals of 2^shift bit patterns.
 // Every prompt walks its gains down to lo (a monotone search); gains above hi are
 // counted, gains inside the bracket are tallied per interval together with the largest
-// and the smallest pattern seen there.  The workgroup that finishes last finds the
-// interval in which the running count (from the top) reaches the budget and shrinks the
-// bracket to the gains that actually occur in it: (min - 1, max].  When min == max the
-// threshold is that gain.  Each pass cuts the bracket at least 128-fold; gain values
-// that repeat many times (a shared prior) close it in two or three passes.
+// and the smallest pattern seen there.  The running count from the top interval down
+// reaches the budget in exactly one interval; the bracket shrinks to the gains that
+// actually occur there, (min - 1, max], and closes when min == max (tau is that gain).
+// Each pass cuts the bracket at least 128-fold; with real-valued posteriors it holds
+// ~1/256 of the previous pass's gains, with a shared prior (few distinct gains, each
+// repeated) it closes in two passes.
+//
+// kSolo = false: the workgroups tally their share and add it to the global intervals;
+// the one that finishes last narrows the bracket for the next launch.
+// kSolo = true: one workgroup repeats passes over all prompts until the bracket closes.
+// It runs after the parallel passes and normally finds the bracket closed already; it is
+// there so that a fixed, small number of launches is correct for any input.
 // ----------------------------------------------------------------------------------
-template <class Src>
-__global__ __launch_bounds__(kThreads) void k_select_pass(Src src, long long n, long long budget, long long limit,
-                                                          AllocHeader* __restrict__ hdr,
-                                                          SelectBins* __restrict__ bins) {
-    __shared__ unsigned long long s_cnt[kBins];
-    __shared__ unsigned long long s_max[kBins];
-    __shared__ unsigned long long s_min_inv[kBins];
-    __shared__ long long s_red[kWaves];
-    __shared__ int s_last;
-    if (hdr->done) return;
-    const unsigned long long lo = hdr->lo_cur, hi = hdr->hi_cur;
-    const unsigned long long width = hi - lo;                 // >= 2
-    const int bitlen = 64 - __clzll((long long)(width - 1));   // bits of width - 1
-    const int shift = bitlen > 8 ? bitlen - 8 : 0;            // (width - 1) >> shift < kBins
-    for (int j = (int)threadIdx.x; j < kBins; j += kThreads) { s_cnt[j] = 0; s_max[j] = 0; s_min_inv[j] = 0; }
-    __syncthreads();
+struct SelectShared {
+    unsigned long long cnt[kBins];
+    unsigned long long vmax[kBins];
+    unsigned long long vmin_inv[kBins];
+    long long red[kBigWaves];
+    unsigned long long lo, hi;
+    int done;
+    int last;
+};
 
-    long long above = 0;
-    const long long stride = (long long)gridDim.x * kThreads;
-    for (long long i = (long long)blockIdx.x * kThreads + threadIdx.x; i < n; i += stride) {
-        double a, b;
-        src.load(i, a, b);
-        const double s = a + b;
-        double g = gain_first(a, s);
-        double lf = 0.0;
-        long long k = 0;
-        unsigned long long gb = gain_bits(g);
-        while (k < limit && gb > lo) {
-            if (gb > hi) {
-                above += 1;
-            } else {
-                const int j = (int)((gb - lo - 1ull) >> shift);
-                atomicAdd(&s_cnt[j], 1ull);
-                atomicMax(&s_max[j], gb);
-                atomicMax(&s_min_inv[j], ~gb);
+template <class Src, bool kSolo>
+__global__ __launch_bounds__(kBig) void k_select_pass(Src src, long long n, long long budget, long long limit,
+                                                      AllocHeader* __restrict__ hdr,
+                                                      SelectBins* __restrict__ bins) {
+    __shared__ SelectShared sh;
+    if (threadIdx.x == 0) { sh.lo = hdr->lo_cur; sh.hi = hdr->hi_cur; sh.done = (int)hdr->done; sh.last = 1; }
+    __syncthreads();
+    const int iters = kSolo ? kSelectPasses : 1;
+    for (int iter = 0; iter < iters; ++iter) {
+        if (sh.done) break;
+        const unsigned long long lo = sh.lo, hi = sh.hi;
+        const unsigned long long width = hi - lo;                  // >= 2
+        const int bitlen = 64 - __clzll((long long)(width - 1));    // bits of width - 1
+        const int shift = bitlen > 8 ? bitlen - 8 : 0;             // (width - 1) >> shift < kBins
+        if (threadIdx.x < kBins) { sh.cnt[threadIdx.x] = 0; sh.vmax[threadIdx.x] = 0; sh.vmin_inv[threadIdx.x] = 0; }
+        __syncthreads();
+
+        long long above = 0;
+        const long long stride = (long long)gridDim.x * kBig;
+        const int lane = lane_id();
+        // all wavefronts run the same number of rounds, so that the ballots below see whole wavefronts
+        for (long long i0 = (long long)blockIdx.x * kBig; i0 < n; i0 += stride) {
+            const long long i = i0 + threadIdx.x;
+            double a = 1.0, b = 1.0;
+            if (i < n) src.load(i, a, b);
+            const double s = a + b;
+            double g = gain_first(a, s);
+            double lf = 0.0;
+            long long k = 0;
+            unsigned long long gb = gain_bits(g);
+            bool active = i < n && k < limit && gb > lo;
+            while (__ballot(active)) {
+                const bool inside = active && gb <= hi;
+                if (active && !inside) above += 1;
+                // lanes that hold the same gain (common under a shared prior) tally once:
+                // up to 8 distinct gains per step through a leader, the rest lane by lane
+                unsigned long long pending = __ballot(inside);
+                for (int round = 0; round < 8 && pending; ++round) {
+                    const int leader = __ffsll((long long)pending) - 1;
+                    const unsigned long long v = read_lane_u64(gb, leader);
+                    const unsigned long long same = __ballot(inside && gb == v);
+                    if (lane == leader) {
+                        const int j = (int)((v - lo - 1ull) >> shift);
+                        atomicAdd(&sh.cnt[j], (unsigned long long)__popcll(same));
+                        if (v > sh.vmax[j]) atomicMax(&sh.vmax[j], v);
+                        if (~v > sh.vmin_inv[j]) atomicMax(&sh.vmin_inv[j], ~v);
+                    }
+                    pending &= ~same;
+                }
+                if (inside && ((pending >> lane) & 1ull)) {
+                    const int j = (int)((gb - lo - 1ull) >> shift);
+                    atomicAdd(&sh.cnt[j], 1ull);
+                    if (gb > sh.vmax[j]) atomicMax(&sh.vmax[j], gb);
+                    if (~gb > sh.vmin_inv[j]) atomicMax(&sh.vmin_inv[j], ~gb);
+                }
+                if (active) {
+                    g = gain_next(g, b, s, lf);
+                    lf += 1.0;
+                    k += 1;
+                    gb = gain_bits(g);
+                    active = k < limit && gb > lo;
+                }
             }
-            g = gain_next(g, b, s, lf);
-            lf += 1.0;
-            k += 1;
-            gb = gain_bits(g);
+            if (above > budget) above = budget;   // only the comparison with the budget matters
         }
-        if (above > budget) above = budget;   // only the comparison with the budget matters
-    }
-    long long above_block = block_sum<long long>(above, s_red);
-    if (above_block > budget) above_block = budget;
-    __syncthreads();
-    for (int j = (int)threadIdx.x; j < kBins; j += kThreads) {
-        const unsigned long long cj = s_cnt[j];
-        if (cj) {
-            atomicAdd(&bins->cnt[j], cj > (unsigned long long)budget ? (unsigned long long)budget : cj);
-            atomicMax(&bins->vmax[j], s_max[j]);
-            atomicMax(&bins->vmin_inv[j], s_min_inv[j]);
-        }
-    }
-    if (threadIdx.x == 0 && above_block) atomicAdd(&hdr->above, (unsigned long long)above_block);
-    __threadfence();
-    __syncthreads();
-    if (threadIdx.x == 0) s_last = atomicAdd(&hdr->ticket, 1u) == gridDim.x - 1 ? 1 : 0;
-    __syncthreads();
-    if (!s_last) return;
+        above = wave_sum<long long>(above);
+        if (lane_id() == 0) sh.red[wave_id()] = above;
+        __syncthreads();
+        long long start = 0;
+#pragma unroll
+        for (int i = 0; i < kBigWaves; ++i) start += sh.red[i];
+        if (start > budget) start = budget;
 
-    // last workgroup: running count from the top interval down, one interval per thread
-    __threadfence();
-    static_assert(kBins == kThreads, "one interval per thread");
-    const int j = kBins - 1 - (int)threadIdx.x;               // thread 0 owns the top interval
-    const unsigned long long cj = atomicAdd(&bins->cnt[j], 0ull);
-    const unsigned long long mx = atomicMax(&bins->vmax[j], 0ull);
-    const unsigned long long mn = ~atomicMax(&bins->vmin_inv[j], 0ull);
-    const long long start = (long long)atomicAdd(&hdr->above, 0ull);
-    long long total;
-    long long before = block_excl_scan<long long>((long long)cj, s_red, total);   // pairs in higher intervals
-    before += start;
-    if (cj != 0 && before < budget && budget <= before + (long long)cj) {   // exactly one thread
-        hdr->hi_cur = mx;
-        hdr->lo_cur = mn - 1ull;
-        hdr->done = (mx == mn) ? 1u : 0u;
+        // tallies of interval j = kBins - 1 - thread: thread 0 owns the top interval
+        const int j = kBins - 1 - (int)threadIdx.x;
+        unsigned long long cj = 0, mx = 0, mn = 0;
+        if (!kSolo) {
+            if (threadIdx.x < kBins && sh.cnt[j]) {
+                const unsigned long long c0 = sh.cnt[j];
+                atomicAdd(&bins->cnt[j], c0 > (unsigned long long)budget ? (unsigned long long)budget : c0);
+                atomicMax(&bins->vmax[j], sh.vmax[j]);
+                atomicMax(&bins->vmin_inv[j], sh.vmin_inv[j]);
+            }
+            if (threadIdx.x == 0 && start) atomicAdd(&hdr->above, (unsigned long long)start);
+            __threadfence();
+            __syncthreads();
+            if (threadIdx.x == 0) sh.last = atomicAdd(&hdr->ticket, 1u) == gridDim.x - 1 ? 1 : 0;
+            __syncthreads();
+            if (!sh.last) return;
+            __threadfence();
+            if (threadIdx.x < kBins) {
+                cj = atomicAdd(&bins->cnt[j], 0ull);
+                mx = atomicMax(&bins->vmax[j], 0ull);
+                mn = ~atomicMax(&bins->vmin_inv[j], 0ull);
+                bins->cnt[j] = 0ull;
+                bins->vmax[j] = 0ull;
+                bins->vmin_inv[j] = 0ull;
+            }
+            start = (long long)atomicAdd(&hdr->above, 0ull);
+        } else if (threadIdx.x < kBins) {
+            cj = sh.cnt[j];
+            mx = sh.vmax[j];
+            mn = ~sh.vmin_inv[j];
+        }
+        if (cj > (unsigned long long)budget) cj = (unsigned long long)budget;
+        __syncthreads();                                     // sh.red is reused
+        // pairs in higher intervals: exclusive prefix over the threads
+        const long long incl = wave_incl_scan<long long>((long long)cj);
+        if (lane_id() == kWave - 1) sh.red[wave_id()] = incl;
+        __syncthreads();
+        long long before = start + incl - (long long)cj;
+        for (int i = 0; i < wave_id(); ++i) before += sh.red[i];
+        if (cj != 0 && before < budget && budget <= before + (long long)cj) {   // exactly one thread
+            sh.hi = mx;
+            sh.lo = mn - 1ull;
+            sh.done = (mx == mn) ? 1 : 0;
+        }
+        __syncthreads();
     }
-    bins->cnt[j] = 0ull;
-    bins->vmax[j] = 0ull;
-    bins->vmin_inv[j] = 0ull;
-    if (threadIdx.x == 0) { hdr->above = 0ull; hdr->ticket = 0u; }
+    if (threadIdx.x == 0) {
+        hdr->lo_cur = sh.lo;
+        hdr->hi_cur = sh.hi;
+        hdr->done = (unsigned)sh.done;
+        if (!kSolo) { hdr->above = 0ull; hdr->ticket = 0u; }
+    }
 }
 
 // ----------------------------------------------------------------------------------
@@ -1083,14 +1145,18 @@ static int run_bisect(const Src& src, const CommonArgs& a, const Plan& p, const 
     long long limit = a.delta_max > 0 ? (long long)a.delta_max : a.budget;
     if (limit > a.budget) limit = a.budget;
     if (a.budget > 0) {
-        long long blocks = (n + kThreads - 1) / kThreads;
-        if (blocks > 2048) blocks = 2048;
+        long long blocks = (n + kBig - 1) / kBig;
+        if (blocks > kMaxBlocks) blocks = kMaxBlocks;
         const long long w_steps = (a.budget + n - 1) / n;
-        hipLaunchKernelGGL((k_select_bracket<Src>), dim3((unsigned)blocks), dim3(kThreads), 0, a.stream, src, n,
+        hipLaunchKernelGGL((k_select_bracket<Src>), dim3((unsigned)blocks), dim3(kBig), 0, a.stream, src, n,
                            w_steps, w.header, a.dev_status);
-        for (int pass = 0; pass < kSelectPasses; ++pass)
-            hipLaunchKernelGGL((k_select_pass<Src>), dim3((unsigned)blocks), dim3(kThreads), 0, a.stream, src, n,
-                               (long long)a.budget, limit, w.header, w.bins);
+        // small batches go straight to the single-workgroup search: fewer launches than passes
+        const int parallel = n > kSoloMaxPrompts ? kParallelPasses : 0;
+        for (int pass = 0; pass < parallel; ++pass)
+            hipLaunchKernelGGL((k_select_pass<Src, false>), dim3((unsigned)blocks), dim3(kBig), 0, a.stream, src,
+                               n, (long long)a.budget, limit, w.header, w.bins);
+        hipLaunchKernelGGL((k_select_pass<Src, true>), dim3(1), dim3(kBig), 0, a.stream, src, n,
+                           (long long)a.budget, limit, w.header, w.bins);
     }
     hipLaunchKernelGGL((k_bisect_finalize<Src>), dim3(p.nb), dim3(kBig), 0, a.stream, src, n, p.chunk,
                        (long long)a.budget, limit, w.header, a.delta, a.util, w.block_ksum, w.block_tied);
