@@ -173,8 +173,9 @@ int hora_group_advantage(int64_t n_groups, const void *group_off, int32_t off_t,
 
 /*
  * Bytes of workspace hora_token_broadcast needs for n_tokens tokens of type out_t
- * (4 bytes per 4 KiB of output, plus a little).  Device memory, 4-byte aligned, no
- * initialisation needed; two calls that may run concurrently need separate workspaces.
+ * (one descriptor of 32 bytes for float, 64 bytes for double output per 4 KiB of
+ * output, plus one).  Device memory, 64-byte aligned, no initialisation needed; two
+ * calls that may run concurrently need separate workspaces.
  */
 size_t hora_token_broadcast_workspace_bytes(int64_t n_tokens, int32_t out_t);
 
