@@ -39,6 +39,7 @@ constexpr int kMinRow = 32;                   // gain-table row length (a power 
 constexpr int kMaxRow = 256;                  // ... and at most
 constexpr int kTableCap = kMaxClasses * kMinRow;   // doubles per table (2048)
 constexpr unsigned kTiedBit = 0x80000000u;
+constexpr int kPairCap = 16384;               // (table entry, class) pairs ranked one per thread when they fit
 
 constexpr int kBins = 256;        // intervals per narrowing pass of the threshold search
 constexpr int kSelectPasses = 9;  // every pass cuts the bracket at least 128-fold: enough for 63 bits
@@ -413,11 +414,45 @@ __device__ __forceinline__ int row_count_above(const double* row, int row_len, u
 
 __device__ void solve_by_table(int nc, int row_len, int len, bool rows_end_at_cap, long long budget,
                                const long long* s_n, const double* s_gain, const double* s_surv,
-                               ClassSolution* sol) {
+                               unsigned short* s_pair, ClassSolution* sol) {
     if (threadIdx.x == 0) sol->found = 0;
     __syncthreads();
     const int row_shift = __ffs(row_len) - 1;
-    for (int idx = (int)threadIdx.x; idx < nc * row_len; idx += kBig) {
+    const int cands = nc * row_len;
+    if (cands * nc <= kPairCap) {
+        // Small tables: one thread per (entry, class) pair does one binary search, then one
+        // thread per entry adds up its nc results.  Pair value: #{l' : M_class(l') > v} in
+        // the low 15 bits, bit 15 set when the class's next gain equals v.
+        for (int pair = (int)threadIdx.x; pair < cands * nc; pair += kBig) {
+            const int idx = pair / nc, cls = pair - idx * nc;
+            const unsigned long long v = gain_bits(s_gain[idx]);
+            const double* row = s_gain + cls * row_len;
+            const int pos = row_count_above(row, row_len, v);
+            s_pair[pair] = (unsigned short)(pos | (gain_bits(row[pos]) == v ? 0x8000 : 0));
+        }
+        __syncthreads();
+        for (int idx = (int)threadIdx.x; idx < cands; idx += kBig) {
+            const int c = idx >> row_shift, l = idx & (row_len - 1);
+            if (l >= len || s_n[c] == 0) continue;
+            long long gt = 0, eq = 0;
+            bool complete = true;
+            for (int cls = 0; cls < nc; ++cls) {
+                const int pr = s_pair[idx * nc + cls];
+                const int pos = pr & 0x7fff;
+                const long long n2 = s_n[cls];
+                gt += n2 * pos;
+                if (pr & 0x8000) eq += n2;
+                if (n2 != 0 && pos >= len && !rows_end_at_cap) complete = false;
+            }
+            if (complete && gt < budget && budget <= gt + eq) {   // every such thread writes the same values
+                sol->tau_bits = gain_bits(s_gain[idx]);
+                sol->r = budget - gt;
+                sol->tie_prompts = eq;
+                sol->found = 1;
+            }
+        }
+    } else
+    for (int idx = (int)threadIdx.x; idx < cands; idx += kBig) {
         const int c = idx >> row_shift, l = idx & (row_len - 1);
         if (l >= len || s_n[c] == 0) continue;
         const unsigned long long v = gain_bits(s_gain[idx]);
@@ -563,6 +598,7 @@ __global__ __launch_bounds__(kBig) void k_class_write(const int32_t* __restrict_
     __shared__ long long s_before[kMaxClasses];  // prompts per class in workgroups before this one
     __shared__ ClassSolution s_sol;
     __shared__ EmitShared s_emit;
+    __shared__ unsigned short s_pair[kPairCap];
 
     const int nc = g0 + 1;
     const int lane = lane_id();
@@ -576,29 +612,49 @@ __global__ __launch_bounds__(kBig) void k_class_write(const int32_t* __restrict_
     const int len = cap_eff < row_len - 1 ? (int)cap_eff : row_len - 1;   // usable gains per row
     const bool rows_end_at_cap = cap_eff <= row_len - 1;
 
-    // first tile of c: issued now, used after the solve
+    // Every global load of the prologue is issued before the first one is used (the
+    // first tile of c, the two tables, the histogram): one round trip to memory instead
+    // of one per stage.
+    constexpr int kTableLoads = kTableCap / kBig;                   // table entries per thread
+    constexpr int kHistLoads = kMaxClasses * kMaxBlocks / kBig;     // histogram entries per thread
+    const int table_len = nc * row_len;
+    const int entries = nc * kMaxBlocks;
+    double tg[kTableLoads], ts[kTableLoads];
+    int hh[kHistLoads];
+#pragma unroll
+    for (int q = 0; q < kTableLoads; ++q) {
+        const int i = q * kBig + (int)threadIdx.x;
+        tg[q] = i < table_len ? gain_table[i] : 0.0;
+        ts[q] = i < table_len ? surv_table[i] : 0.0;
+    }
+#pragma unroll
+    for (int q = 0; q < kHistLoads; ++q) {
+        const int idx = q * kBig + (int)threadIdx.x;
+        hh[q] = (idx < entries && (idx & (kMaxBlocks - 1)) < nb) ? class_hist[idx] : 0;
+    }
     int first_tile[kItems];
     load_items_i32(c, base + (long long)threadIdx.x * kItems, end, c_vec, -1, first_tile);
 
     // tables into LDS, gains beyond `len` replaced by zeros
-    const int table_len = nc * row_len;
-    for (int i = (int)threadIdx.x; i < table_len; i += kBig) {
-        const double g = gain_table[i];
-        s_gain[i] = (i & (row_len - 1)) < len ? g : 0.0;
-        s_surv[i] = surv_table[i];
+#pragma unroll
+    for (int q = 0; q < kTableLoads; ++q) {
+        const int i = q * kBig + (int)threadIdx.x;
+        if (i < table_len) {
+            s_gain[i] = (i & (row_len - 1)) < len ? tg[q] : 0.0;
+            s_surv[i] = ts[q];
+        }
     }
 
     // class totals and the part that lies before this workgroup: the counts of class c
     // are kMaxBlocks consecutive entries, so every wavefront sums entries of one class
-    {
-        const int entries = nc * kMaxBlocks;
-        for (int i0 = 0; i0 < entries; i0 += kBig) {
+#pragma unroll
+    for (int q = 0; q < kHistLoads; ++q) {
+        const int i0 = q * kBig;
+        if (i0 < entries) {   // uniform
             const int idx = i0 + (int)threadIdx.x;
             const int b = idx & (kMaxBlocks - 1);
-            int h = 0;
-            if (idx < entries && b < nb) h = class_hist[idx];
-            const long long tot_w = wave_total_i64((long long)h);
-            const long long bef_w = wave_total_i64(b < (int)blockIdx.x ? (long long)h : 0ll);
+            const long long tot_w = wave_total_i64((long long)hh[q]);
+            const long long bef_w = wave_total_i64(b < (int)blockIdx.x ? (long long)hh[q] : 0ll);
             if (lane == 0 && idx < entries) { s_part[0][idx >> 6] = tot_w; s_part[1][idx >> 6] = bef_w; }
         }
     }
@@ -617,7 +673,7 @@ __global__ __launch_bounds__(kBig) void k_class_write(const int32_t* __restrict_
     __syncthreads();
 
     if (budget > 0) {
-        solve_by_table(nc, row_len, len, rows_end_at_cap, budget, s_n, s_gain, s_surv, &s_sol);
+        solve_by_table(nc, row_len, len, rows_end_at_cap, budget, s_n, s_gain, s_surv, s_pair, &s_sol);
         if (!s_sol.found) solve_by_greedy(g0, alpha0, beta0, cap_eff, budget, s_n, &s_sol, dev_status);
     } else {
         if (threadIdx.x < kMaxClasses) {
