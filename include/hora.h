@@ -150,6 +150,44 @@ int hora_allocate_posterior(int64_t n, int32_t g0, const double *alpha, const do
                             void *stream);
 
 /*
+ * Bytes of workspace hora_allocate_sharded needs for n_shards shards: the gain tables of
+ * the G0+1 classes (kept from call to call and reused while the prior, G0 and the cap
+ * stay the same) and the prefix sums of the shard budgets.  Device memory, 256-byte
+ * aligned; it must be zero-filled once before its first use.  Two calls that may run
+ * concurrently need separate workspaces.
+ */
+size_t hora_allocate_sharded_workspace_bytes(int64_t n_shards);
+
+/*
+ * Phase-B allocation run independently on shards of the batch (App. C: the paper runs
+ * Phase B on four mini-batches of Gamma/4 prompts instead of the whole batch at once;
+ * Prop. 1 then holds inside each shard and the total budget is unchanged).
+ *
+ * Shard s holds the prompts shard_off[s] .. shard_off[s+1]-1 and distributes
+ * shard_budget[s] among them; its delta, util and summary are exactly those of
+ * hora_allocate called on that slice of c with that budget (same prior, same cap, same
+ * tie rule with the prompt index taken inside the batch).  group_off runs over the
+ * whole batch: exclusive prefix sums of g0 + delta_i over all n prompts.
+ *
+ * shard_off    : device, n_shards+1 int64, shard_off[0] = 0, non-decreasing,
+ *                shard_off[n_shards] = n (else HORA_ERR_RANGE in dev_status).  Empty
+ *                shards are allowed.
+ * shard_budget : device, n_shards int64, each >= 0, < 2^31 - 1 without a cap, and at most
+ *                (shard size) * delta_max with one; a positive budget needs a non-empty
+ *                shard (else HORA_ERR_RANGE / HORA_ERR_INFEASIBLE in dev_status; the
+ *                outputs of such a shard are unspecified).
+ * summary      : device out, n_shards entries.  Nullable.
+ * workspace    : device, >= hora_allocate_sharded_workspace_bytes(n_shards).
+ * The other arguments are those of hora_allocate.  One workgroup works on one shard:
+ * meant for many small or medium shards; a single large batch belongs to hora_allocate.
+ */
+int hora_allocate_sharded(int64_t n, int32_t g0, const int32_t *c, double alpha0, double beta0,
+                          int64_t n_shards, const int64_t *shard_off, const int64_t *shard_budget,
+                          int32_t delta_max, int32_t *delta, double *util, void *group_off,
+                          int32_t off_t, hora_alloc_summary *summary, int32_t *dev_status,
+                          void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Group-relative advantages over variable-size groups (Sec. 3.1 for GRPO; Sec. 4
  * "compatible with GRPO-family objectives" and App. E for RLOO).
  *

@@ -182,6 +182,27 @@ int hora_oracle_allocate(int64_t n, const double *alpha, const double *beta, int
 }
 
 /* ---------------------------------------------------------------------------
+ * Sharded Phase B (App. C): the batch is cut into consecutive shards and the
+ * greedy loop above is run on every shard by itself, with the shard's own
+ * budget; the optimality statement then holds inside each shard.  Shard s holds
+ * prompts shard_off[s] .. shard_off[s+1]-1.
+ * ------------------------------------------------------------------------- */
+int hora_oracle_allocate_sharded(int64_t n, const double *alpha, const double *beta, int64_t n_shards,
+                                 const int64_t *shard_off, const int64_t *shard_budget,
+                                 int64_t delta_max, int64_t *delta) {
+    if (n < 0 || n_shards < 0) return ORACLE_ERR_INVALID;
+    if (n_shards == 0) return n == 0 ? ORACLE_OK : ORACLE_ERR_INVALID;
+    if (shard_off[0] != 0 || shard_off[n_shards] != n) return ORACLE_ERR_RANGE;
+    for (int64_t s = 0; s < n_shards; ++s) {
+        int64_t lo = shard_off[s], hi = shard_off[s + 1];
+        if (hi < lo) return ORACLE_ERR_RANGE;
+        int rc = hora_oracle_allocate(hi - lo, alpha + lo, beta + lo, shard_budget[s], delta_max, delta + lo);
+        if (rc != ORACLE_OK) return rc;
+    }
+    return ORACLE_OK;
+}
+
+/* ---------------------------------------------------------------------------
  * Group assembly (Alg. 1 "group assembly"; Sec. 3.2): G_i = G0 + Delta_i,
  * responses of prompt i stored contiguously, pre-rollouts first.
  * off[0] = 0, off[i+1] = off[i] + G_i.

@@ -53,6 +53,8 @@ def lib():
         for f in (_lib.hora_oracle_allocate, _lib.hora_oracle_allocate_scan):
             f.argtypes = [i64, p, p, i64, i64, p]
             f.restype = ctypes.c_int
+        _lib.hora_oracle_allocate_sharded.argtypes = [i64, p, p, i64, p, p, i64, p]
+        _lib.hora_oracle_allocate_sharded.restype = ctypes.c_int
         _lib.hora_oracle_group_offsets.argtypes = [i64, i32, p, p]
         _lib.hora_oracle_group_offsets.restype = None
         _lib.hora_oracle_group_advantage.argtypes = [i64, p, p, p, i32, d, i32]
@@ -105,6 +107,18 @@ def allocate(c: np.ndarray, g0: int, budget: int, delta_max: int = 0, alpha0: fl
              beta0: float = 1.0, scan: bool = False) -> np.ndarray:
     alpha, beta = posterior(c, g0, alpha0, beta0)
     return allocate_posterior(alpha, beta, budget, delta_max, scan=scan)
+
+
+def allocate_sharded(c: np.ndarray, g0: int, shard_off: np.ndarray, shard_budget: np.ndarray,
+                     delta_max: int = 0, alpha0: float = 1.0, beta0: float = 1.0) -> np.ndarray:
+    alpha, beta = posterior(c, g0, alpha0, beta0)
+    shard_off = np.ascontiguousarray(shard_off, dtype=np.int64)
+    shard_budget = np.ascontiguousarray(shard_budget, dtype=np.int64)
+    assert shard_off.size == shard_budget.size + 1
+    delta = np.zeros(alpha.size, dtype=np.int64)
+    _check(lib().hora_oracle_allocate_sharded(alpha.size, _ptr(alpha), _ptr(beta), shard_budget.size,
+                                              _ptr(shard_off), _ptr(shard_budget), int(delta_max), _ptr(delta)))
+    return delta
 
 
 def utilities(alpha: np.ndarray, beta: np.ndarray, delta: np.ndarray) -> np.ndarray:

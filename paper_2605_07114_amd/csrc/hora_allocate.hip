@@ -26,6 +26,7 @@
 
 #include "hora.h"
 #include "hora_device.h"
+#include "hora_alloc_common.h"
 
 namespace hora {
 
@@ -41,8 +42,6 @@ constexpr int kTableCap = kMaxClasses * kMinRow;   // doubles per table (2048)
 constexpr unsigned kTiedBit = 0x80000000u;
 constexpr int kPairCap = 16384;               // (table entry, class) pairs ranked one per thread when they fit
 
-constexpr int kBins = 256;        // intervals per narrowing pass of the threshold search
-constexpr int kSelectPasses = 9;  // every pass cuts the bracket at least 128-fold: enough for 63 bits
 constexpr int kSoloMaxPrompts = 8192;   // up to here one workgroup searches alone
 constexpr int kParallelPasses = 4;   // launched grid-wide; a single-workgroup finisher covers the rest
 
@@ -125,35 +124,6 @@ static Workspace carve(void* base) {
     w.bytes = off;
     return w;
 }
-
-// ----------------------------------------------------------------------------------
-// Posterior sources (Sec. 3.2 Eq. 2; App. D for the per-prompt form).
-// ----------------------------------------------------------------------------------
-struct CountsSource {
-    const int32_t* c;
-    int g0;
-    double alpha0, beta0;
-    __device__ __forceinline__ bool load(long long i, double& a, double& b) const {
-        int x = c[i];
-        bool ok = (x >= 0) && (x <= g0);
-        x = x < 0 ? 0 : (x > g0 ? g0 : x);
-        a = alpha0 + (double)x;
-        b = beta0 + (double)(g0 - x);
-        return ok;
-    }
-};
-
-struct PosteriorSource {
-    const double* alpha;
-    const double* beta;
-    __device__ __forceinline__ bool load(long long i, double& a, double& b) const {
-        a = alpha[i];
-        b = beta[i];
-        bool ok = (a > 0.0) && (b > 0.0) && (a < INFINITY) && (b < INFINITY);
-        if (!ok) { a = 1.0; b = 1.0; }
-        return ok;
-    }
-};
 
 // ----------------------------------------------------------------------------------
 // Gain / utility tables (Eq. 3, Eq. 5): one thread per posterior, l-major output so
@@ -501,12 +471,6 @@ __device__ void solve_by_table(int nc, int row_len, int len, bool rows_end_at_ca
     __syncthreads();
 }
 
-__device__ __forceinline__ unsigned long long read_lane_u64(unsigned long long v, int src) {
-    unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(v & 0xffffffffull), src);
-    unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(v >> 32), src);
-    return ((unsigned long long)hi << 32) | lo;
-}
-
 // Class-level greedy, for allocations deeper than the table.  Lane c of wavefront 0 owns
 // class c: its posterior, its position l_c and the current gain.  Each round takes the
 // largest current gain over the classes that still have prompts and room below the cap;
@@ -785,26 +749,6 @@ __global__ __launch_bounds__(kBig) void k_select_bracket(Src src, long long n, l
         }
     }
     if (bad) report(dev_status, HORA_ERR_RANGE);
-}
-
-// Number of gains of one prompt that exceed tau, at most `limit`; also leaves the next
-// gain (the first one <= tau) in `g`, l as a double in `lf` and, if asked, the survival
-// product E(k) in `e`.
-template <bool kSurvival>
-__device__ __forceinline__ long long walk_above(double a, double b, unsigned long long tau_bits, long long limit,
-                                                double& g, double& lf, double& e) {
-    const double s = a + b;
-    g = gain_first(a, s);
-    lf = 0.0;
-    e = 1.0;
-    long long k = 0;
-    while (k < limit && gain_bits(g) > tau_bits) {
-        if (kSurvival) e = surv_next(e, b, s, lf);
-        g = gain_next(g, b, s, lf);
-        lf += 1.0;
-        k += 1;
-    }
-    return k;
 }
 
 // ----------------------------------------------------------------------------------

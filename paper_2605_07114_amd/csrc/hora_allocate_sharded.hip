@@ -1,0 +1,592 @@
+// Phase-B allocation on independent shards of the batch (App. C: the paper runs Phase B
+// on four mini-batches of Gamma/4 prompts, and Prop. 1 then holds inside each shard).
+//
+// One workgroup owns one shard and finds its threshold gain tau on its own, so there is
+// no grid-wide dependency; then it writes the shard's outputs with the ties at tau
+// resolved by prompt index.  The result of a shard equals that of hora_allocate on the
+// shard's prompts and budget.  Two ways to find tau:
+//  by table (shared prior): gains depend on c only, so a set-up kernel evaluates the
+//    G0+1 gain sequences (once: the workspace keeps them for later calls with the same
+//    prior); a shard takes the histogram of its c and searches the bit pattern of tau in
+//    passes of 256 intervals over the table entries, each entry weighted by its class
+//    count.  No division in the shard's workgroup.
+//  by walks (any posterior, and allocations deeper than the table): windows of the bit
+//    pattern are searched from the largest gain down, every prompt walking its gain
+//    recurrence down to the window.
+//
+// Group offsets run over the whole batch, so they need the budgets of the earlier
+// shards: the set-up kernel also writes their exclusive prefix sums.
+#include <hip/hip_runtime.h>
+
+#include <climits>
+#include <cmath>
+#include <cstdint>
+
+#include "hora.h"
+#include "hora_device.h"
+#include "hora_alloc_common.h"
+
+namespace hora {
+
+constexpr int kShardThreads = 256;
+constexpr int kShardWaves = kShardThreads / kWave;
+constexpr int kPrefixThreads = 1024;
+constexpr unsigned kShardTiedBit = 0x80000000u;
+constexpr unsigned long long kWindowStep = 4ull << 52;   // 4 exponent steps: a factor 16 in value
+// Windows from the largest gain down to zero (at most 2047 / 4), plus the narrowing passes
+// inside the window that holds tau (each cuts the bracket at least 128-fold).
+constexpr int kShardMaxPasses = 512 + 10;
+constexpr int kShardTableCap = 8192;     // entries of the gain table (and of the survival table)
+constexpr int kShardMaxDepth = 512;      // gains per class in the table, at most
+
+// Start of the workspace: says which tables the workspace holds, so that a call with the
+// same prior, G0 and depth as the one before reuses them (the sequences are walked one
+// division after the other, which costs more than a whole small call).  Zero = none.
+struct ShardTableKey {
+    unsigned long long magic;
+    double alpha0, beta0;
+    int g0, depth;
+    unsigned long long pad[28];
+};
+static_assert(sizeof(ShardTableKey) == 256, "key size");
+constexpr unsigned long long kTableMagic = 0x484f52415461626cull;
+constexpr int kShardMaxClasses = HORA_CLASS_MAX_G0 + 1;
+
+// Set-up.  Workgroup 0: exclusive prefix sums of the shard budgets (negative budgets count
+// as 0; the shard's own workgroup reports them); thread t owns a contiguous run of shards.
+// Workgroup 1: the gain and survival sequences of the G0+1 classes, one thread per class
+// (Sec. 3.2 stable update; App. A), `depth` entries each.
+__global__ __launch_bounds__(kPrefixThreads) void k_shard_setup(long long n_shards,
+                                                                const long long* __restrict__ shard_budget,
+                                                                long long* __restrict__ prefix, int g0,
+                                                                double alpha0, double beta0, int depth,
+                                                                ShardTableKey* __restrict__ key,
+                                                                double* __restrict__ gain_table,
+                                                                double* __restrict__ surv_table) {
+    __shared__ long long s_tot[kPrefixThreads / kWave];
+    if (blockIdx.x == 1) {
+        if (depth == 0) return;
+        const bool cached = key->magic == kTableMagic && key->alpha0 == alpha0 && key->beta0 == beta0 &&
+                            key->g0 == g0 && key->depth == depth;
+        if (cached) return;   // uniform: every thread reads the same key
+        __syncthreads();      // all threads have read the key before thread 0 clears it
+        if (threadIdx.x == 0) key->magic = 0ull;
+        if (threadIdx.x <= (unsigned)g0) {
+            const int cls = (int)threadIdx.x;
+            const double a = alpha0 + (double)cls;
+            const double b = beta0 + (double)(g0 - cls);
+            const double s = a + b;
+            double m = gain_first(a, s), e = 1.0, lf = 0.0;
+            for (int l = 0; l < depth; ++l) {
+                gain_table[cls * depth + l] = m;
+                surv_table[cls * depth + l] = e;
+                e = surv_next(e, b, s, lf);
+                m = gain_next(m, b, s, lf);
+                lf += 1.0;
+            }
+        }
+        __threadfence();
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            key->alpha0 = alpha0; key->beta0 = beta0; key->g0 = g0; key->depth = depth;
+            __threadfence();
+            key->magic = kTableMagic;
+        }
+        return;
+    }
+    if (!prefix) return;
+    const long long per = (n_shards + kPrefixThreads - 1) / kPrefixThreads;
+    const long long lo = (long long)threadIdx.x * per;
+    const long long hi = lo + per < n_shards ? lo + per : n_shards;
+    long long sum = 0;
+    for (long long s = lo; s < hi; ++s) {
+        const long long b = shard_budget[s];
+        sum += b > 0 ? b : 0;
+    }
+    const long long incl = wave_incl_scan<long long>(sum);
+    if (lane_id() == kWave - 1) s_tot[wave_id()] = incl;
+    __syncthreads();
+    long long run = incl - sum;
+    for (int w = 0; w < wave_id(); ++w) run += s_tot[w];
+    for (long long s = lo; s < hi; ++s) {
+        prefix[s] = run;
+        const long long b = shard_budget[s];
+        run += b > 0 ? b : 0;
+    }
+}
+
+struct ShardShared {
+    unsigned long long cnt[kBins];
+    unsigned long long vmax[kBins];
+    unsigned long long vmin_inv[kBins];
+    unsigned long long red_u[2][kShardWaves];
+    long long red_i[2][kShardWaves];
+    unsigned long long lo, hi;   // bracket of tau's bit pattern
+    long long above;             // pairs whose gain is > hi
+    int done;                    // 1: hi is tau; 2: ran out of gains
+    int by_table;                // the table search settled tau and the per-class results below
+    long long n_cls[kShardMaxClasses];   // prompts of the shard per class
+    int k_cls[kShardMaxClasses];         // gains of the class above tau
+    int tied_cls[kShardMaxClasses];      // the class's next gain equals tau
+    double e_cls[kShardMaxClasses];      // E_c(k_c)
+};
+
+// sums (a, b) over the workgroup; every thread gets both totals
+__device__ __forceinline__ void shard_sum2(long long& a, long long& b, ShardShared& sh) {
+    a = wave_sum<long long>(a);
+    b = wave_sum<long long>(b);
+    __syncthreads();
+    if (lane_id() == 0) { sh.red_i[0][wave_id()] = a; sh.red_i[1][wave_id()] = b; }
+    __syncthreads();
+    a = 0; b = 0;
+#pragma unroll
+    for (int w = 0; w < kShardWaves; ++w) { a += sh.red_i[0][w]; b += sh.red_i[1][w]; }
+}
+
+// exclusive prefix sums of (a, b) over the threads of the workgroup, and the totals
+__device__ __forceinline__ void shard_scan2(long long a, long long b, long long& a_ex, long long& b_ex,
+                                            long long& a_tot, long long& b_tot, ShardShared& sh) {
+    const long long ai = wave_incl_scan<long long>(a), bi = wave_incl_scan<long long>(b);
+    __syncthreads();
+    if (lane_id() == kWave - 1) { sh.red_i[0][wave_id()] = ai; sh.red_i[1][wave_id()] = bi; }
+    __syncthreads();
+    a_ex = ai - a; b_ex = bi - b; a_tot = 0; b_tot = 0;
+#pragma unroll
+    for (int w = 0; w < kShardWaves; ++w) {
+        const long long x = sh.red_i[0][w], y = sh.red_i[1][w];
+        if (w < wave_id()) { a_ex += x; b_ex += y; }
+        a_tot += x; b_tot += y;
+    }
+}
+
+// Class of prompt i (clamped like CountsSource::load); sources without classes never call it.
+__device__ __forceinline__ int class_of(const CountsSource& src, long long i) {
+    const int x = src.c[i];
+    return x < 0 ? 0 : (x > src.g0 ? src.g0 : x);
+}
+__device__ __forceinline__ int class_of(const PosteriorSource&, long long) { return 0; }
+
+// Threshold by walks.
+// Invariant: exactly `above` pairs have a gain > hi, and above < budget.  A pass cuts
+// (lo, hi] into at most kBins intervals of 2^shift bit patterns and tallies the gains
+// that fall inside (every prompt walks its gains from l = 0 down to lo).  If the
+// running count from the top reaches the budget inside interval j, the bracket
+// shrinks to the gains that occur there, (min - 1, max], and closes when min == max:
+// tau is that gain.  Otherwise the whole window lies above tau: it is added to
+// `above` and the next window, a factor 16 further down in value (4 exponent steps of
+// the bit pattern), is taken.  Going down window by window keeps the walks short: a
+// window's count is a small multiple of the one before it, so the work is a small
+// multiple of the budget, whereas a bracket from a guaranteed lower bound (e.g. the
+// smallest ceil(budget/n)-th gain) can lie orders of magnitude below tau.
+// Counts fit 63 bits: n < 2^40 and one prompt has far fewer than 2^22 gains per window
+// for any threshold a budget below 2^52 can reach.
+template <class Src>
+__device__ bool threshold_by_walks(const Src& src, long long lo_i, long long hi_i, long long budget, long long limit,
+                                   ShardShared& sh, bool& data_bad, unsigned long long& tau_bits) {
+    const int lane = lane_id();
+    unsigned long long top = 0;
+    for (long long i = lo_i + threadIdx.x; i < hi_i; i += kShardThreads) {
+        double a, b;
+        data_bad |= !src.load(i, a, b);
+        const unsigned long long gb = gain_bits(gain_first(a, a + b));
+        top = gb > top ? gb : top;
+    }
+    top = wave_max_u64(top);
+    if (lane == 0) sh.red_u[0][wave_id()] = top;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        unsigned long long all_top = 0;
+        for (int w = 0; w < kShardWaves; ++w) all_top = sh.red_u[0][w] > all_top ? sh.red_u[0][w] : all_top;
+        sh.hi = all_top;
+        sh.lo = all_top > kWindowStep ? all_top - kWindowStep : 0ull;
+        sh.above = 0;
+        sh.done = 0;
+    }
+    __syncthreads();
+
+    for (int pass = 0; pass < kShardMaxPasses; ++pass) {
+        if (sh.done) break;   // uniform: written before the barrier that ends a pass
+        const unsigned long long lo = sh.lo, hi_cur = sh.hi;
+        const long long above = sh.above;
+        const unsigned long long width = hi_cur - lo;                 // >= 2
+        const int bitlen = 64 - __clzll((long long)(width - 1));
+        const int shift = bitlen > 8 ? bitlen - 8 : 0;                // (width - 1) >> shift < kBins
+        static_assert(kBins == kShardThreads, "one interval per thread");
+        sh.cnt[threadIdx.x] = 0; sh.vmax[threadIdx.x] = 0; sh.vmin_inv[threadIdx.x] = 0;
+        __syncthreads();
+        // every wavefront runs whole rounds, so that the ballots see all of its lanes
+        for (long long i0 = lo_i; i0 < hi_i; i0 += kShardThreads) {
+            const long long i = i0 + threadIdx.x;
+            double a = 1.0, b = 1.0;
+            if (i < hi_i) src.load(i, a, b);
+            const double s = a + b;
+            double g = gain_first(a, s);
+            double lf = 0.0;
+            long long k = 0;
+            unsigned long long gb = gain_bits(g);
+            bool active = i < hi_i && k < limit && gb > lo;
+            while (__ballot(active)) {
+                const bool inside = active && gb <= hi_cur;
+                // lanes that hold the same gain (the rule under a shared prior) tally once
+                unsigned long long pending = __ballot(inside);
+                for (int round = 0; round < 8 && pending; ++round) {
+                    const int leader = __ffsll((long long)pending) - 1;
+                    const unsigned long long v = read_lane_u64(gb, leader);
+                    const unsigned long long same = __ballot(inside && gb == v);
+                    if (lane == leader) {
+                        const int j = (int)((v - lo - 1ull) >> shift);
+                        atomicAdd(&sh.cnt[j], (unsigned long long)__popcll(same));
+                        atomicMax(&sh.vmax[j], v);
+                        atomicMax(&sh.vmin_inv[j], ~v);
+                    }
+                    pending &= ~same;
+                }
+                if (inside && ((pending >> lane) & 1ull)) {
+                    const int j = (int)((gb - lo - 1ull) >> shift);
+                    atomicAdd(&sh.cnt[j], 1ull);
+                    atomicMax(&sh.vmax[j], gb);
+                    atomicMax(&sh.vmin_inv[j], ~gb);
+                }
+                if (active) {
+                    g = gain_next(g, b, s, lf);
+                    lf += 1.0;
+                    k += 1;
+                    gb = gain_bits(g);
+                    active = k < limit && gb > lo;
+                }
+            }
+        }
+        __syncthreads();   // the tallies are complete
+        // interval j = kBins - 1 - thread: thread 0 owns the top interval
+        const int j = kBins - 1 - (int)threadIdx.x;
+        const long long cj = (long long)sh.cnt[j];
+        const unsigned long long mx = sh.vmax[j], mn = ~sh.vmin_inv[j];
+        long long before, unused_ex, total, unused_tot;
+        shard_scan2(cj, 0, before, unused_ex, total, unused_tot, sh);
+        before += above;
+        if (above + total < budget) {          // uniform: the whole window is above tau
+            if (threadIdx.x == 0) {
+                sh.above = above + total;
+                sh.hi = lo;
+                sh.lo = lo > kWindowStep ? lo - kWindowStep : 0ull;
+                if (lo == 0ull) sh.done = 2;   // no gains left: the budget does not fit
+            }
+        } else if (cj != 0 && before < budget && budget <= before + cj) {   // exactly one thread
+            sh.above = before;
+            sh.hi = mx;
+            sh.lo = mn - 1ull;
+            sh.done = (mx == mn) ? 1 : 0;
+        }
+        __syncthreads();
+    }
+    tau_bits = sh.hi;
+    return sh.done == 1;   // anything else cannot happen with valid posteriors and a feasible budget
+}
+
+// Threshold by table (shared prior).  Returns false when the table is too shallow for
+// this shard (some class would need gains beyond `depth`); the caller then walks.
+// On success sh.k_cls / sh.tied_cls / sh.e_cls hold the per-class results.
+template <class Src>
+__device__ bool threshold_by_table(const Src& src, long long lo_i, long long hi_i, long long budget, long long limit,
+                                   int depth, const double* __restrict__ gain_table,
+                                   const double* __restrict__ surv_table, ShardShared& sh,
+                                   bool& data_bad, unsigned long long& tau_bits) {
+    const int nc = src.g0 + 1;
+    const int dshift = __ffs(depth) - 1;
+    const int lim = limit < depth ? (int)limit : depth;     // usable gains per class
+    // histogram of c over the shard
+    for (int j = (int)threadIdx.x; j < nc; j += kShardThreads) { sh.n_cls[j] = 0; sh.k_cls[j] = 0; sh.tied_cls[j] = 0; }
+    __syncthreads();
+    for (long long i = lo_i + threadIdx.x; i < hi_i; i += kShardThreads) {
+        int x = src.c[i];
+        if (x < 0 || x > src.g0) { data_bad = true; x = x < 0 ? 0 : src.g0; }
+        atomicAdd((unsigned long long*)&sh.n_cls[x], 1ull);
+    }
+    __syncthreads();
+    // bracket (0, largest first gain of a populated class]
+    if (threadIdx.x == 0) {
+        unsigned long long top = 0;
+        for (int j = 0; j < nc; ++j) {
+            const unsigned long long v = gain_bits(gain_table[j << dshift]);
+            if (sh.n_cls[j] > 0 && v > top) top = v;
+        }
+        sh.lo = 0ull; sh.hi = top; sh.above = 0; sh.done = 0;
+    }
+    __syncthreads();
+    for (int pass = 0; pass < kSelectPasses + 1; ++pass) {
+        if (sh.done) break;
+        const unsigned long long lo = sh.lo, hi_cur = sh.hi;
+        const long long above = sh.above;
+        const unsigned long long width = hi_cur - lo;
+        const int bitlen = width > 1 ? 64 - __clzll((long long)(width - 1)) : 0;
+        const int shift = bitlen > 8 ? bitlen - 8 : 0;
+        sh.cnt[threadIdx.x] = 0; sh.vmax[threadIdx.x] = 0; sh.vmin_inv[threadIdx.x] = 0;
+        __syncthreads();
+        for (int cls = 0; cls < nc; ++cls) {            // rows of classes the shard does not hold are skipped
+            const long long w = sh.n_cls[cls];
+            if (w == 0) continue;
+            const double* row = gain_table + (cls << dshift);
+            for (int l = (int)threadIdx.x; l < lim; l += kShardThreads) {
+                const unsigned long long v = gain_bits(row[l]);
+                if (v > lo && v <= hi_cur) {
+                    const int j = (int)((v - lo - 1ull) >> shift);
+                    atomicAdd(&sh.cnt[j], (unsigned long long)w);
+                    atomicMax(&sh.vmax[j], v);
+                    atomicMax(&sh.vmin_inv[j], ~v);
+                }
+            }
+        }
+        __syncthreads();
+        const int j = kBins - 1 - (int)threadIdx.x;             // thread 0 owns the top interval
+        const long long cj = (long long)sh.cnt[j];
+        const unsigned long long mx = sh.vmax[j], mn = ~sh.vmin_inv[j];
+        long long before, unused_ex, total, unused_tot;
+        shard_scan2(cj, 0, before, unused_ex, total, unused_tot, sh);
+        before += above;
+        if (above + total < budget) {                           // uniform: the table does not hold tau
+            if (threadIdx.x == 0) sh.done = 2;
+        } else if (cj != 0 && before < budget && budget <= before + cj) {   // exactly one thread
+            sh.above = before;
+            sh.hi = mx;
+            sh.lo = mn - 1ull;
+            sh.done = (mx == mn) ? 1 : 0;
+        }
+        __syncthreads();
+    }
+    if (sh.done != 1) return false;
+    tau_bits = sh.hi;
+    // gains above tau per class, and whether the next one equals tau
+    for (int cls = 0; cls < nc; ++cls) {
+        if (sh.n_cls[cls] == 0) continue;
+        const double* row = gain_table + (cls << dshift);
+        for (int l = (int)threadIdx.x; l < lim; l += kShardThreads) {
+            const unsigned long long v = gain_bits(row[l]);
+            if (v > tau_bits) atomicAdd(&sh.k_cls[cls], 1);
+            if (v == tau_bits) sh.tied_cls[cls] = 1;
+        }
+    }
+    if (threadIdx.x == 0) sh.by_table = 1;
+    __syncthreads();
+    if (threadIdx.x < (unsigned)nc) {
+        const int cls = (int)threadIdx.x;
+        const int k = sh.k_cls[cls];
+        // a populated class with every table entry above tau, and more gains beyond the
+        // table: those are missing from the counts
+        if (sh.n_cls[cls] > 0 && k == lim && (long long)lim < limit) sh.by_table = 0;
+        const double a = src.alpha0 + (double)cls, b = src.beta0 + (double)(src.g0 - cls);
+        double e = surv_table[(cls << dshift) + (k < depth ? k : depth - 1)];
+        if (k == depth) e = surv_next(e, b, a + b, (double)(depth - 1));
+        sh.e_cls[cls] = e;
+    }
+    __syncthreads();
+    return sh.by_table != 0;
+}
+
+// kOff: 0 no offsets, 1 int32 offsets, 2 int64 offsets.
+template <class Src, int kOff>
+__global__ __launch_bounds__(kShardThreads) void k_shard_allocate(Src src, long long n, int g0, long long n_shards,
+                                                                  const long long* __restrict__ shard_off,
+                                                                  const long long* __restrict__ shard_budget,
+                                                                  int cap, const long long* __restrict__ prefix,
+                                                                  int depth, const double* __restrict__ gain_table,
+                                                                  const double* __restrict__ surv_table,
+                                                                  int32_t* __restrict__ delta,
+                                                                  double* __restrict__ util,
+                                                                  void* __restrict__ group_off,
+                                                                  hora_alloc_summary* __restrict__ summary,
+                                                                  int32_t* dev_status) {
+    __shared__ ShardShared sh;
+    const long long shard = blockIdx.x;
+    const long long lo_i = shard_off[shard], hi_i = shard_off[shard + 1];
+    const long long budget = shard_budget[shard];
+
+    // the shards must tile [0, n) in order, and the budget must fit the shard
+    bool bad = lo_i < 0 || hi_i < lo_i || hi_i > n || budget < 0 || (shard == 0 && lo_i != 0) ||
+               (shard == n_shards - 1 && hi_i != n);
+    const long long size = bad ? 0 : hi_i - lo_i;
+    bool infeasible = false;
+    if (!bad) {
+        infeasible = (budget > 0 && size == 0) || (cap > 0 && budget > size * (long long)cap) ||
+                     (cap <= 0 && budget >= (1ll << 31) - 1) || budget >= (1ll << 52);
+    }
+    if (bad || infeasible) {
+        if (threadIdx.x == 0) report(dev_status, bad ? HORA_ERR_RANGE : HORA_ERR_INFEASIBLE);
+        return;
+    }
+    long long limit = cap > 0 ? (long long)cap : budget;
+    if (limit > budget) limit = budget;
+
+    // ---- threshold ---------------------------------------------------------------------
+    unsigned long long tau_bits = ~0ull;   // budget 0: nothing is above tau
+    bool data_bad = false;
+    bool by_table = false;
+    if (budget > 0) {
+        if constexpr (Src::kHasClasses)
+            if (depth > 0)
+                by_table = threshold_by_table(src, lo_i, hi_i, budget, limit, depth, gain_table, surv_table, sh,
+                                          data_bad, tau_bits);
+        if (!by_table && !threshold_by_walks(src, lo_i, hi_i, budget, limit, sh, data_bad, tau_bits)) {
+            if (threadIdx.x == 0) report(dev_status, HORA_ERR_RANGE);
+            return;
+        }
+    }
+
+    // ---- k_i, tied flag and E_i(k_i) per prompt; totals --------------------------------
+    long long ks = 0, ts = 0;
+    for (long long i = lo_i + threadIdx.x; i < hi_i; i += kShardThreads) {
+        long long k;
+        bool tied;
+        double e;
+        if (by_table) {
+            const int x = class_of(src, i);
+            k = sh.k_cls[x];
+            tied = sh.tied_cls[x] != 0;
+            e = sh.e_cls[x];
+        } else {
+            double a, b, g, lf;
+            data_bad |= !src.load(i, a, b);
+            k = walk_above<true>(a, b, tau_bits, limit, g, lf, e);
+            tied = (k < limit) && (gain_bits(g) == tau_bits);
+        }
+        delta[i] = (int32_t)((unsigned)k | (tied ? kShardTiedBit : 0u));
+        if (util) util[i] = e;
+        ks += k;
+        ts += tied ? 1 : 0;
+    }
+    if (data_bad) report(dev_status, HORA_ERR_RANGE);
+    shard_sum2(ks, ts, sh);
+    const long long r = budget - ks;
+    if ((r < 0 || r > ts) && threadIdx.x == 0) report(dev_status, HORA_ERR_RANGE);
+    if (summary && threadIdx.x == 0) {
+        summary[shard].tau = budget > 0 ? __longlong_as_double((long long)tau_bits) : 0.0;
+        summary[shard].count_gt = ks;
+        summary[shard].tie_units = r;
+        summary[shard].tie_prompts = ts;
+    }
+
+    // ---- ties by prompt index, final delta, utilities, offsets -------------------------
+    const long long off_base = kOff != 0 ? prefix[shard] : 0;   // units given to earlier shards
+    long long rank_base = 0, k_base = 0;
+    for (long long i0 = lo_i; i0 < hi_i; i0 += kShardThreads) {
+        const long long i = i0 + threadIdx.x;
+        const bool in = i < hi_i;
+        const unsigned raw = in ? (unsigned)delta[i] : 0u;     // written above by this same thread
+        const long long kk = (long long)(raw & ~kShardTiedBit);
+        const long long td = (raw & kShardTiedBit) ? 1 : 0;
+        long long k_ex, t_ex, k_tot, t_tot;
+        shard_scan2(kk, td, k_ex, t_ex, k_tot, t_tot, sh);
+        const long long rank = rank_base + t_ex;
+        const bool win = td && rank < r;
+        if (in) {
+            delta[i] = (int32_t)(kk + (win ? 1 : 0));
+            if (util) {
+                double e = util[i];
+                if (win) {
+                    double a, b;
+                    src.load(i, a, b);
+                    e = surv_next(e, b, a + b, (double)kk);
+                }
+                util[i] = 1.0 - e;
+            }
+            if (kOff != 0) {
+                const long long off = (long long)g0 * i + off_base + k_base + k_ex + (rank < r ? rank : r);
+                const long long next = off + g0 + kk + (win ? 1 : 0);
+                if (kOff == 1) {
+                    reinterpret_cast<int32_t*>(group_off)[i] = (int32_t)off;
+                    if (i == n - 1) reinterpret_cast<int32_t*>(group_off)[n] = (int32_t)next;
+                } else {
+                    reinterpret_cast<long long*>(group_off)[i] = off;
+                    if (i == n - 1) reinterpret_cast<long long*>(group_off)[n] = next;
+                }
+            }
+        }
+        rank_base += t_tot;
+        k_base += k_tot;
+    }
+}
+
+__global__ void k_store_zero_offset(void* group_off, int off64) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        if (off64) *reinterpret_cast<long long*>(group_off) = 0;
+        else *reinterpret_cast<int32_t*>(group_off) = 0;
+    }
+}
+
+static size_t prefix_bytes(int64_t n_shards) {
+    return (((size_t)(n_shards > 0 ? n_shards : 1) * sizeof(long long)) + 255) & ~(size_t)255;
+}
+// table key, the gain and the survival table, then the prefix sums
+static size_t sharded_workspace_bytes(int64_t n_shards) {
+    return sizeof(ShardTableKey) + 2 * (size_t)kShardTableCap * sizeof(double) + prefix_bytes(n_shards);
+}
+
+// Gains per class in the table: a power of two, as many as fit; no more than a cap asks for.
+static int table_depth(int g0, int32_t delta_max) {
+    const int nc = g0 + 1;
+    if (nc > kShardMaxClasses) return 0;
+    int depth = 1;
+    while (depth * 2 * nc <= kShardTableCap && depth * 2 <= kShardMaxDepth) depth *= 2;
+    if (delta_max > 0)
+        while (depth / 2 >= delta_max && depth > 1) depth /= 2;
+    return depth;
+}
+
+}  // namespace hora
+
+using namespace hora;
+
+extern "C" size_t hora_allocate_sharded_workspace_bytes(int64_t n_shards) {
+    if (n_shards < 0) return 0;
+    return sharded_workspace_bytes(n_shards);
+}
+
+extern "C" int hora_allocate_sharded(int64_t n, int32_t g0, const int32_t* c, double alpha0, double beta0,
+                                     int64_t n_shards, const int64_t* shard_off, const int64_t* shard_budget,
+                                     int32_t delta_max, int32_t* delta, double* util, void* group_off,
+                                     int32_t off_t, hora_alloc_summary* summary, int32_t* dev_status,
+                                     void* workspace, size_t workspace_bytes, void* stream) {
+    if (n < 0 || g0 < 0 || n_shards < 0 || !dev_status) return HORA_ERR_INVALID_ARG;
+    if (!(alpha0 > 0.0) || !(beta0 > 0.0) || !std::isfinite(alpha0) || !std::isfinite(beta0))
+        return HORA_ERR_INVALID_ARG;
+    if (group_off && off_t != HORA_I32 && off_t != HORA_I64) return HORA_ERR_INVALID_ARG;
+    if (n >= (1ll << 40) || n_shards > INT_MAX) return HORA_ERR_UNSUPPORTED;
+    if (n > 0 && n_shards == 0) return HORA_ERR_INVALID_ARG;   // the shards must cover every prompt
+    if ((reinterpret_cast<uintptr_t>(delta) & 3) || (reinterpret_cast<uintptr_t>(util) & 7) ||
+        (reinterpret_cast<uintptr_t>(dev_status) & 3) || (reinterpret_cast<uintptr_t>(c) & 3) ||
+        (reinterpret_cast<uintptr_t>(shard_off) & 7) || (reinterpret_cast<uintptr_t>(shard_budget) & 7) ||
+        (reinterpret_cast<uintptr_t>(summary) & 7))
+        return HORA_ERR_INVALID_ARG;
+    if (group_off && (reinterpret_cast<uintptr_t>(group_off) & (off_t == HORA_I32 ? 3 : 7)))
+        return HORA_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    if (n_shards == 0) {   // n == 0 too
+        if (group_off) hipLaunchKernelGGL(k_store_zero_offset, 1, 1, 0, s, group_off, off_t == HORA_I64 ? 1 : 0);
+        return hipGetLastError() == hipSuccess ? HORA_OK : HORA_ERR_HIP;
+    }
+    if (!shard_off || !shard_budget) return HORA_ERR_INVALID_ARG;
+    if (n > 0 && (!c || !delta)) return HORA_ERR_INVALID_ARG;
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255)) return HORA_ERR_WORKSPACE;
+    if (workspace_bytes < sharded_workspace_bytes(n_shards)) return HORA_ERR_WORKSPACE;
+    ShardTableKey* key = (ShardTableKey*)workspace;
+    double* gain_table = (double*)((char*)workspace + sizeof(ShardTableKey));
+    double* surv_table = gain_table + kShardTableCap;
+    long long* prefix = group_off ? (long long*)(surv_table + kShardTableCap) : nullptr;
+    const int depth = table_depth(g0, delta_max);
+    if (group_off && n == 0) hipLaunchKernelGGL(k_store_zero_offset, 1, 1, 0, s, group_off, off_t == HORA_I64 ? 1 : 0);
+    hipLaunchKernelGGL(k_shard_setup, dim3(2), dim3(kPrefixThreads), 0, s, (long long)n_shards,
+                       (const long long*)shard_budget, prefix, (int)g0, alpha0, beta0, depth, key, gain_table,
+                       surv_table);
+    CountsSource src{c, g0, alpha0, beta0};
+    const int cap = delta_max > 0 ? delta_max : 0;
+    const int mode = group_off ? (off_t == HORA_I32 ? 1 : 2) : 0;
+#define HORA_LAUNCH_SHARDS(M)                                                                                   \
+    hipLaunchKernelGGL((k_shard_allocate<CountsSource, M>), dim3((unsigned)n_shards), dim3(kShardThreads), 0, s, \
+                       src, (long long)n, (int)g0, (long long)n_shards, (const long long*)shard_off,            \
+                       (const long long*)shard_budget, cap, prefix, depth, gain_table, surv_table, delta, util,    \
+                       group_off, summary, dev_status)
+    if (mode == 0) HORA_LAUNCH_SHARDS(0);
+    else if (mode == 1) HORA_LAUNCH_SHARDS(1);
+    else HORA_LAUNCH_SHARDS(2);
+#undef HORA_LAUNCH_SHARDS
+    return hipGetLastError() == hipSuccess ? HORA_OK : HORA_ERR_HIP;
+}

@@ -32,7 +32,7 @@ CLASS_MAX_G0 = 63
 EXPORTS = (
     "hora_status_string", "hora_version", "hora_marginal_gains", "hora_allocate_workspace_bytes",
     "hora_allocate", "hora_allocate_posterior", "hora_group_advantage", "hora_token_broadcast",
-    "hora_token_broadcast_workspace_bytes",
+    "hora_token_broadcast_workspace_bytes", "hora_allocate_sharded", "hora_allocate_sharded_workspace_bytes",
 )
 
 
@@ -69,6 +69,10 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.hora_allocate.restype = ctypes.c_int
     lib.hora_allocate_posterior.argtypes = [i64, i32, p, p, i64, i32, p, p, p, i32, p, p, p, sz, p]
     lib.hora_allocate_posterior.restype = ctypes.c_int
+    lib.hora_allocate_sharded_workspace_bytes.argtypes = [i64]
+    lib.hora_allocate_sharded_workspace_bytes.restype = sz
+    lib.hora_allocate_sharded.argtypes = [i64, i32, p, f64, f64, i64, p, p, i32, p, p, p, i32, p, p, p, sz, p]
+    lib.hora_allocate_sharded.restype = ctypes.c_int
     lib.hora_group_advantage.argtypes = [i64, p, i32, i64, p, p, i32, i32, f64, i32, p, p]
     lib.hora_group_advantage.restype = ctypes.c_int
     lib.hora_token_broadcast_workspace_bytes.argtypes = [i64, i32]
@@ -183,6 +187,34 @@ def hora_allocate_posterior(alpha: torch.Tensor, beta: torch.Tensor, g0: int, bu
         "hora_allocate_posterior")
 
 
+def hora_allocate_sharded_workspace_bytes(n_shards: int) -> int:
+    return int(load_library().hora_allocate_sharded_workspace_bytes(int(n_shards)))
+
+
+def hora_allocate_sharded(c: torch.Tensor, g0: int, shard_off: torch.Tensor, shard_budget: torch.Tensor,
+                          delta: torch.Tensor, dev_status: torch.Tensor, workspace: Optional[torch.Tensor], *,
+                          alpha0: float = 1.0, beta0: float = 1.0, delta_max: int = 0,
+                          util: Optional[torch.Tensor] = None, group_off: Optional[torch.Tensor] = None,
+                          summary: Optional[torch.Tensor] = None, stream=None) -> None:
+    n = c.numel()
+    n_shards = shard_budget.numel()
+    _expect(c, torch.int32, n, "c")
+    _expect(shard_off, torch.int64, n_shards + 1, "shard_off")
+    _expect(shard_budget, torch.int64, n_shards, "shard_budget")
+    _expect(delta, torch.int32, n, "delta")
+    _expect(util, torch.float64, n, "util")
+    _expect(dev_status, torch.int32, 1, "dev_status")
+    _expect(summary, torch.int64, 4 * n_shards, "summary")
+    if group_off is not None and group_off.numel() < n + 1:
+        raise ValueError("group_off needs n + 1 elements")
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(load_library().hora_allocate_sharded(
+        n, int(g0), _ptr(c), float(alpha0), float(beta0), n_shards, _ptr(shard_off), _ptr(shard_budget),
+        int(delta_max), _ptr(delta), _ptr(util), _ptr(group_off),
+        _itype(group_off) if group_off is not None else I32, _ptr(summary), _ptr(dev_status), _ptr(workspace),
+        ws_bytes, _stream(stream)), "hora_allocate_sharded")
+
+
 def hora_group_advantage(group_off: torch.Tensor, reward: torch.Tensor, adv: torch.Tensor, mode: int,
                          dev_status: torch.Tensor, *, eps: float = 0.0, ddof: int = 0, stream=None) -> None:
     n_groups = group_off.numel() - 1
@@ -233,6 +265,7 @@ class Session:
         self.dev_status = torch.zeros(1, dtype=torch.int32, device=self.device)
         self._workspace = torch.zeros(0, dtype=torch.uint8, device=self.device)
         self._bcast_workspace = torch.empty(0, dtype=torch.uint8, device=self.device)
+        self._shard_workspace = torch.empty(0, dtype=torch.uint8, device=self.device)
 
     def workspace(self, n: int, g0: int) -> torch.Tensor:
         need = hora_allocate_workspace_bytes(n, g0)
@@ -252,6 +285,24 @@ class Session:
         hora_allocate(c, g0, budget, out.delta, self.dev_status, self.workspace(n, g0), alpha0=alpha0,
                       beta0=beta0, delta_max=delta_max, method=method, util=out.util, group_off=out.group_off,
                       summary=out.summary)
+        return out
+
+    def allocate_sharded(self, c: torch.Tensor, g0: int, shard_off: torch.Tensor, shard_budget: torch.Tensor, *,
+                         alpha0: float = 1.0, beta0: float = 1.0, delta_max: int = 0, want_util: bool = True,
+                         off_dtype: Optional[torch.dtype] = torch.int64,
+                         want_summary: bool = True) -> Allocation:
+        n, n_shards = c.numel(), shard_budget.numel()
+        out = Allocation(
+            delta=torch.empty(n, dtype=torch.int32, device=self.device),
+            util=torch.empty(n, dtype=torch.float64, device=self.device) if want_util else None,
+            group_off=torch.empty(n + 1, dtype=off_dtype, device=self.device) if off_dtype else None,
+            summary=torch.zeros(4 * n_shards, dtype=torch.int64, device=self.device) if want_summary else None)
+        need = hora_allocate_sharded_workspace_bytes(n_shards)
+        if self._shard_workspace.numel() < need:
+            self._shard_workspace = torch.zeros(need, dtype=torch.uint8, device=self.device)
+        hora_allocate_sharded(c, g0, shard_off, shard_budget, out.delta, self.dev_status, self._shard_workspace,
+                              alpha0=alpha0, beta0=beta0, delta_max=delta_max, util=out.util,
+                              group_off=out.group_off, summary=out.summary)
         return out
 
     def allocate_posterior(self, alpha: torch.Tensor, beta: torch.Tensor, g0: int, budget: int, *,

@@ -75,7 +75,42 @@ LARGE_BCAST = Workload("large_bcast", 4096, 8, 8 * 4096, 0, _MIX_STD,
                        float_type="f32", token_type="f32",
                        group_off_type="i32", tok_off_type="i64")
 
-WORKLOADS = {w.name: w for w in (TINY, SMALL, SKEWED, LARGE_ALLOC, LARGE_BCAST)}
+# The paper's own training step (App. C, Tables 3-5): 60 prompts, G0 = 8, G = 32, so a
+# Phase-B budget of 60 * 24, allocated on four shards of 15 prompts.
+PAPER_STEP = Workload("paper_step", 60, 8, 60 * 24, 0, _MIX_STD, ("lognormal", 800.0, 0.6, 32, 2048), 5,
+                      float_type="f32", token_type="f32", group_off_type="i32", tok_off_type="i32",
+                      note="4 shards of 15 prompts")
+PAPER_STEP_SHARDS = 4
+# The same shard shape at scale: 65 536 shards of 16 prompts, G0 = 8, 24 additional rollouts per prompt.
+SHARDED_LARGE = Workload("sharded_large", 1 << 20, 8, 24 << 20, 0, _MIX_STD, None, 6, group_off_type="i32",
+                         note="65536 shards of 16 prompts")
+SHARDED_LARGE_SHARDS = 1 << 16
+
+WORKLOADS = {w.name: w for w in (TINY, SMALL, SKEWED, LARGE_ALLOC, LARGE_BCAST, PAPER_STEP, SHARDED_LARGE)}
+
+
+def equal_shards(n: int, n_shards: int, budget: int) -> Tuple[np.ndarray, np.ndarray]:
+    """Consecutive shards of (almost) equal size with the budget split in proportion to
+    the shard sizes (any remainder of the budget goes to the first shards, one unit each)."""
+    bounds = (np.arange(n_shards + 1, dtype=np.int64) * n) // n_shards
+    sizes = np.diff(bounds)
+    per = budget // n if n else 0
+    shard_budget = sizes * per
+    rest = budget - int(shard_budget.sum())
+    shard_budget[:rest] += 1
+    return bounds, shard_budget.astype(np.int64)
+
+
+def ragged_shards(n: int, n_shards: int, mean_per_prompt: float, seed: int
+                  ) -> Tuple[np.ndarray, np.ndarray]:
+    """Random consecutive shards (some empty) with random budgets; empty shards get none."""
+    rng = np.random.Generator(np.random.PCG64([seed, 0x5A]))
+    cuts = np.sort(rng.integers(0, n + 1, size=max(n_shards - 1, 0)))
+    bounds = np.concatenate(([0], cuts, [n])).astype(np.int64)
+    sizes = np.diff(bounds)
+    shard_budget = rng.poisson(mean_per_prompt * sizes).astype(np.int64)
+    shard_budget[sizes == 0] = 0
+    return bounds, shard_budget
 
 
 def scaled(w: Workload, n: int, name: Optional[str] = None) -> Workload:

@@ -1,0 +1,128 @@
+"""GPU parity of hora_allocate_sharded (App. C: Phase B on independent shards) against the
+CPU oracle, through the C ABI: delta and group offsets bit for bit, utilities within 1e-12."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+UTIL_RTOL = 1e-12
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    from paper_2605_07114_amd import hora
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    hora.load_library()
+    return hora.Session("cuda:0"), torch, hora
+
+
+def dev(torch, a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+
+
+def check_sharded(gpu, oracle, c, g0, bounds, budgets, delta_max=0, off_dtype="i64", check_util=True):
+    sess, torch, hora = gpu
+    print(f"sharded n={c.size} g0={g0} shards={budgets.size} budget={int(budgets.sum())} cap={delta_max}", flush=True)
+    want = oracle.allocate_sharded(c, g0, bounds, budgets, delta_max=delta_max)
+    tdt = {"i32": torch.int32, "i64": torch.int64}[off_dtype]
+    got = sess.allocate_sharded(dev(torch, c), g0, dev(torch, bounds), dev(torch, budgets), delta_max=delta_max,
+                                off_dtype=tdt)
+    assert sess.status() == 0
+    delta = got.delta.cpu().numpy().astype(np.int64)
+    assert np.array_equal(delta, want), np.flatnonzero(delta != want)[:10]
+    assert np.array_equal(got.group_off.cpu().numpy().astype(np.int64), oracle.group_offsets(want, g0))
+    if check_util:
+        alpha, beta = oracle.posterior(c, g0)
+        np.testing.assert_allclose(got.util.cpu().numpy(), oracle.utilities(alpha, beta, want),
+                                   rtol=UTIL_RTOL, atol=0)
+    summ = got.summary.cpu().numpy().reshape(-1, 4)
+    assert np.array_equal(summ[:, 1] + summ[:, 2], budgets)          # count_gt + tie_units = budget
+    assert ((summ[:, 2] >= 0) & (summ[:, 2] <= np.maximum(summ[:, 3], 0))).all()
+    return want
+
+
+def test_paper_step_four_shards(gpu, oracle):
+    from paper_2605_07114_amd import workloads as wl
+    w = wl.PAPER_STEP
+    a = wl.phase_a(w)
+    bounds, budgets = wl.equal_shards(w.n, wl.PAPER_STEP_SHARDS, w.budget)
+    assert budgets.tolist() == [360] * 4
+    check_sharded(gpu, oracle, a.c, w.g0, bounds, budgets, off_dtype="i32")
+
+
+def test_one_shard_equals_the_unsharded_call(gpu, oracle):
+    from paper_2605_07114_amd import workloads as wl
+    sess, torch, hora = gpu
+    w = wl.TINY
+    a = wl.phase_a(w)
+    want = check_sharded(gpu, oracle, a.c, w.g0, np.array([0, w.n], dtype=np.int64),
+                         np.array([w.budget], dtype=np.int64))
+    whole = sess.allocate(dev(torch, a.c), w.g0, w.budget)
+    assert np.array_equal(whole.delta.cpu().numpy().astype(np.int64), want)
+
+
+@pytest.mark.parametrize("g0,n,n_shards,mean", [(4, 3000, 37, 4.0), (8, 2000, 150, 20.0), (2, 5000, 9, 14.0),
+                                                 (16, 700, 25, 9.0)])
+def test_ragged_shards_with_empty_ones(gpu, oracle, g0, n, n_shards, mean):
+    from paper_2605_07114_amd import workloads as wl
+    rng = np.random.default_rng(g0 * 1000 + n)
+    c = rng.integers(0, g0 + 1, n).astype(np.int32)
+    bounds, budgets = wl.ragged_shards(n, n_shards, mean, seed=n)
+    check_sharded(gpu, oracle, c, g0, bounds, budgets)
+
+
+def test_shards_larger_than_a_workgroup_and_cap(gpu, oracle):
+    from paper_2605_07114_amd import workloads as wl
+    w = wl.SMALL
+    a = wl.phase_a(w)
+    bounds, budgets = wl.equal_shards(w.n, 5, w.budget)           # 1638-prompt shards, several tiles each
+    check_sharded(gpu, oracle, a.c, w.g0, bounds, budgets, delta_max=w.delta_max, off_dtype="i32")
+    # a cap that binds: every prompt of a shard ends at the cap, or one short of it
+    c = np.zeros(40, dtype=np.int32)
+    check_sharded(gpu, oracle, c, 4, np.array([0, 10, 40], dtype=np.int64), np.array([30, 85], dtype=np.int64),
+                  delta_max=3)
+
+
+def test_degenerate_shards(gpu, oracle):
+    sess, torch, hora = gpu
+    # zero budgets everywhere; single-prompt shards; all prompts in one class
+    c = np.array([0, 4, 2, 2, 1], dtype=np.int32)
+    check_sharded(gpu, oracle, c, 4, np.array([0, 1, 2, 5], dtype=np.int64), np.array([0, 0, 0], dtype=np.int64))
+    check_sharded(gpu, oracle, c, 4, np.array([0, 1, 2, 3, 4, 5], dtype=np.int64),
+                  np.array([3, 0, 7, 1, 2], dtype=np.int64))
+    check_sharded(gpu, oracle, np.full(100, 3, dtype=np.int32), 8, np.array([0, 50, 100], dtype=np.int64),
+                  np.array([75, 1], dtype=np.int64))
+    # no prompts at all
+    empty = sess.allocate_sharded(dev(torch, np.zeros(0, dtype=np.int32)), 4,
+                                  dev(torch, np.zeros(1, dtype=np.int64)), dev(torch, np.zeros(0, dtype=np.int64)))
+    assert sess.status() == 0 and empty.group_off.cpu().numpy().tolist() == [0]
+
+
+def test_bad_shard_data_is_reported_not_fatal(gpu, oracle):
+    sess, torch, hora = gpu
+    c = dev(torch, np.zeros(8, dtype=np.int32))
+
+    def status_of(bounds, budgets, cap=0):
+        sess.dev_status.zero_()
+        sess.allocate_sharded(c, 4, dev(torch, np.array(bounds, dtype=np.int64)),
+                              dev(torch, np.array(budgets, dtype=np.int64)), delta_max=cap)
+        s = sess.status()
+        sess.dev_status.zero_()
+        return s
+
+    assert status_of([0, 4, 7], [1, 1]) == hora.ERR_RANGE            # does not end at n
+    assert status_of([0, 5, 3, 8], [1, 1, 1]) == hora.ERR_RANGE      # decreasing
+    assert status_of([0, 4, 8], [1, -1]) == hora.ERR_RANGE           # negative budget
+    assert status_of([0, 4, 4, 8], [1, 1, 1]) == hora.ERR_INFEASIBLE  # budget on an empty shard
+    assert status_of([0, 4, 8], [13, 1], cap=3) == hora.ERR_INFEASIBLE
+    assert status_of([0, 4, 8], [12, 1], cap=3) == 0
+
+
+def test_sharded_large_workload(gpu, oracle):
+    """65 536 shards of 16 prompts (the benchmark's sharded workload): delta and offsets."""
+    from paper_2605_07114_amd import workloads as wl
+    w = wl.SHARDED_LARGE
+    a = wl.phase_a(w)
+    bounds, budgets = wl.equal_shards(w.n, wl.SHARDED_LARGE_SHARDS, w.budget)
+    check_sharded(gpu, oracle, a.c, w.g0, bounds, budgets, off_dtype="i32", check_util=False)

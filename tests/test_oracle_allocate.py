@@ -212,3 +212,55 @@ def test_group_offsets(oracle):
     off = oracle.group_offsets(delta, 4)
     assert off.tolist() == [0, 7, 11, 20, 25]
     assert np.array_equal(off[1:], np.cumsum(4 + delta))
+
+
+# ---- sharded Phase B (App. C) --------------------------------------------------------
+def test_sharded_allocation_is_optimal_inside_every_shard(oracle):
+    """Each shard must reach the brute-force optimum of its own budget (exact rationals),
+    spend exactly its budget, and leave the other shards' prompts alone."""
+    rng = np.random.default_rng(31)
+    g0 = 4
+    for trial in range(20):
+        n_shards = int(rng.integers(1, 5))
+        sizes = rng.integers(0, 5, n_shards)
+        bounds = np.concatenate(([0], np.cumsum(sizes))).astype(np.int64)
+        budgets = np.array([int(rng.integers(0, 8)) if s > 0 else 0 for s in sizes], dtype=np.int64)
+        c = rng.integers(0, g0 + 1, int(bounds[-1])).astype(np.int32)
+        delta = oracle.allocate_sharded(c, g0, bounds, budgets)
+        assert (delta >= 0).all()
+        for s in range(n_shards):
+            lo, hi = int(bounds[s]), int(bounds[s + 1])
+            assert delta[lo:hi].sum() == budgets[s]
+            if hi == lo:
+                continue
+            ab = [(Fraction(1 + int(ci)), Fraction(1 + g0 - int(ci))) for ci in c[lo:hi]]
+            got = sum(exact_utility(a, b, int(d)) for (a, b), d in zip(ab, delta[lo:hi]))
+            assert got == brute_force_best(ab, int(budgets[s]), int(budgets[s]))
+            assert exchange_condition_holds(ab, delta[lo:hi], 0)
+
+
+def test_one_shard_is_the_unsharded_allocation_and_sharding_never_helps(oracle):
+    """A single shard over the batch is Alg. 1 itself; with several shards the total hit
+    utility cannot exceed the optimum of the pooled budget (Prop. 1 on the whole batch)."""
+    rng = np.random.default_rng(32)
+    g0 = 8
+    c = rng.integers(0, g0 + 1, 60).astype(np.int32)
+    whole = oracle.allocate(c, g0, 1440)
+    assert np.array_equal(oracle.allocate_sharded(c, g0, [0, 60], [1440]), whole)
+    sharded = oracle.allocate_sharded(c, g0, [0, 15, 30, 45, 60], [360] * 4)
+    assert sharded.sum() == 1440
+
+    def total(delta):
+        return sum(exact_utility(Fraction(1 + int(ci)), Fraction(1 + g0 - int(ci)), int(d))
+                   for ci, d in zip(c, delta))
+    assert total(sharded) <= total(whole)
+
+
+def test_sharded_rejects_bounds_that_do_not_tile_the_batch(oracle):
+    c = np.zeros(6, dtype=np.int32)
+    with pytest.raises(oracle.OracleError):
+        oracle.allocate_sharded(c, 4, [0, 3, 5], [1, 1])        # does not end at n
+    with pytest.raises(oracle.OracleError):
+        oracle.allocate_sharded(c, 4, [0, 4, 3, 6], [1, 1, 1])  # decreasing
+    with pytest.raises(oracle.OracleError):
+        oracle.allocate_sharded(c, 4, [0, 3, 3, 6], [1, 1, 1])  # budget on an empty shard
