@@ -224,10 +224,15 @@ void hora_oracle_group_offsets(int64_t n, int32_t g0, const int64_t *delta, int6
  * mode 1, RLOO (Sec. 4 "compatible with GRPO-family objectives"; App. E):
  * leave-one-out baseline, A_j = R_j - (sum_{k != j} R_k) / (G_i - 1), evaluated
  * as R_j - (S - R_j)/(G_i - 1) with S the group sum; G_i = 1 gives 0.
+ *
+ * mode 2, centred only: A_j = R_j - mean(R), the GRPO advantage without the
+ * division by the standard deviation (the variant that objectives of the
+ * Dr. GRPO kind use; the paper's runs keep the normalised form of Sec. 3.1).
+ * A group whose rewards are all equal gets exactly 0 here too.
  * ------------------------------------------------------------------------- */
 int hora_oracle_group_advantage(int64_t n_groups, const int64_t *off, const double *reward,
                                 double *adv, int32_t mode, double eps, int32_t ddof) {
-    if (n_groups < 0 || (mode != 0 && mode != 1) || (ddof != 0 && ddof != 1) || eps < 0.0)
+    if (n_groups < 0 || mode < 0 || mode > 2 || (ddof != 0 && ddof != 1) || eps < 0.0)
         return ORACLE_ERR_INVALID;
     for (int64_t g = 0; g < n_groups; ++g) {
         int64_t lo = off[g], hi = off[g + 1];
@@ -246,11 +251,15 @@ int hora_oracle_group_advantage(int64_t n_groups, const int64_t *off, const doub
         int all_equal = 1;
         for (int64_t j = lo + 1; j < hi; ++j)
             if (reward[j] != reward[lo]) { all_equal = 0; break; }
-        if (all_equal || size - ddof <= 0) {
+        if (all_equal || (mode == 0 && size - ddof <= 0)) {
             for (int64_t j = lo; j < hi; ++j) adv[j] = 0.0;
             continue;
         }
         double mean = sum / (double)size;
+        if (mode == 2) {
+            for (int64_t j = lo; j < hi; ++j) adv[j] = reward[j] - mean;
+            continue;
+        }
         double ss = 0.0;
         for (int64_t j = lo; j < hi; ++j) {
             double d = reward[j] - mean;
@@ -274,6 +283,70 @@ int hora_oracle_token_broadcast(int64_t n_resp, const double *adv, const int64_t
     for (int64_t j = 0; j < n_resp; ++j) {
         if (tok_off[j + 1] < tok_off[j]) return ORACLE_ERR_RANGE;
         for (int64_t t = tok_off[j]; t < tok_off[j + 1]; ++t) tok_adv[t] = adv[j];
+    }
+    return ORACLE_OK;
+}
+
+/* ---------------------------------------------------------------------------
+ * Loss weight of every token of a response (Sec. 3.1 objective; Sec. 3.2
+ * "Training objective with variable-size groups"): the objective averages over
+ * the tokens of a response (1/|o_j|) and over the responses of a prompt, and
+ * with variable-size groups the 1/G in front becomes 1/G_i, so that every
+ * prompt weighs the same however many additional rollouts it received.
+ *   length_const <= 0:  w_j = 1 / (G_i * |o_j|)
+ *   length_const  > 0:  w_j = 1 / (G_i * length_const)   (a constant in place of
+ *                       |o_j|: length normalisation of the Dr. GRPO kind, which
+ *                       the paper's runs use; the constant is the caller's)
+ * A response without tokens gets weight 0.  One multiply, then one divide.
+ * ------------------------------------------------------------------------- */
+int hora_oracle_response_weights(int64_t n_groups, const int64_t *group_off, const int64_t *tok_off,
+                                 double length_const, double *weight) {
+    if (n_groups < 0) return ORACLE_ERR_INVALID;
+    for (int64_t g = 0; g < n_groups; ++g) {
+        int64_t lo = group_off[g], hi = group_off[g + 1];
+        if (hi < lo) return ORACLE_ERR_RANGE;
+        double size = (double)(hi - lo);
+        for (int64_t j = lo; j < hi; ++j) {
+            int64_t len = tok_off[j + 1] - tok_off[j];
+            if (len < 0) return ORACLE_ERR_RANGE;
+            if (len == 0) { weight[j] = 0.0; continue; }
+            double norm = length_const > 0.0 ? length_const : (double)len;
+            weight[j] = 1.0 / (size * norm);
+        }
+    }
+    return ORACLE_OK;
+}
+
+/* ---------------------------------------------------------------------------
+ * Baseline allocation rules the paper compares with (Sec. 5, Table 2; Sec. 4).
+ *   rule 0, uniform: the fixed-group baseline; every prompt gets the same
+ *           number of additional rollouts.
+ *   rule 1, hard-first: the Phase-B budget goes only to prompts with c_i = 0.
+ * The paper does not say how the budget is split inside the eligible set, nor
+ * what happens when no prompt has c_i = 0.  Reading taken: the eligible prompts
+ * share the budget evenly, the remainder going one unit each to the lowest
+ * indices; with no eligible prompt the rule falls back to uniform.
+ * ------------------------------------------------------------------------- */
+int hora_oracle_allocate_baseline(int64_t n, const int32_t *c, int64_t budget, int64_t delta_max,
+                                  int32_t rule, int64_t *delta) {
+    if (n < 0 || budget < 0 || (rule != 0 && rule != 1)) return ORACLE_ERR_INVALID;
+    if (budget > 0 && n == 0) return ORACLE_ERR_INFEASIBLE;
+    int64_t eligible = 0;
+    if (rule == 1)
+        for (int64_t i = 0; i < n; ++i) eligible += c[i] == 0;
+    int all = (rule == 0) || eligible == 0;
+    if (all) eligible = n;
+    int64_t each = eligible > 0 ? budget / eligible : 0;
+    int64_t rest = eligible > 0 ? budget - each * eligible : 0;
+    if (delta_max > 0 && each + (rest > 0) > delta_max) return ORACLE_ERR_INFEASIBLE;
+    int64_t rank = 0;
+    for (int64_t i = 0; i < n; ++i) {
+        if (all || c[i] == 0) {
+            delta[i] = each + (rank < rest);
+            rank += 1;
+        } else {
+            delta[i] = 0;
+        }
     }
     return ORACLE_OK;
 }

@@ -61,6 +61,10 @@ def lib():
         _lib.hora_oracle_group_advantage.restype = ctypes.c_int
         _lib.hora_oracle_token_broadcast.argtypes = [i64, p, p, p]
         _lib.hora_oracle_token_broadcast.restype = ctypes.c_int
+        _lib.hora_oracle_response_weights.argtypes = [i64, p, p, d, p]
+        _lib.hora_oracle_response_weights.restype = ctypes.c_int
+        _lib.hora_oracle_allocate_baseline.argtypes = [i64, p, i64, i64, i32, p]
+        _lib.hora_oracle_allocate_baseline.restype = ctypes.c_int
     return _lib
 
 
@@ -139,7 +143,7 @@ def group_advantage(group_off: np.ndarray, reward: np.ndarray, mode: str, eps: f
     group_off = np.ascontiguousarray(group_off, dtype=np.int64)
     reward = np.ascontiguousarray(reward, dtype=np.float64)
     adv = np.zeros(reward.size, dtype=np.float64)
-    m = {"grpo": 0, "rloo": 1}[mode]
+    m = {"grpo": 0, "rloo": 1, "center": 2}[mode]
     _check(lib().hora_oracle_group_advantage(group_off.size - 1, _ptr(group_off), _ptr(reward),
                                              _ptr(adv), m, float(eps), int(ddof)))
     return adv
@@ -155,3 +159,44 @@ def token_broadcast(adv: np.ndarray, tok_off: np.ndarray, out: Optional[np.ndarr
     assert out.dtype == np.float64 and out.size >= total
     _check(lib().hora_oracle_token_broadcast(adv.size, _ptr(adv), _ptr(tok_off), _ptr(out)))
     return out
+
+
+def response_weights(group_off: np.ndarray, tok_off: np.ndarray, length_const: float = 0.0) -> np.ndarray:
+    group_off = np.ascontiguousarray(group_off, dtype=np.int64)
+    tok_off = np.ascontiguousarray(tok_off, dtype=np.int64)
+    weight = np.zeros(tok_off.size - 1, dtype=np.float64)
+    _check(lib().hora_oracle_response_weights(group_off.size - 1, _ptr(group_off), _ptr(tok_off),
+                                              float(length_const), _ptr(weight)))
+    return weight
+
+
+def allocate_baseline(c: np.ndarray, budget: int, rule: str, delta_max: int = 0) -> np.ndarray:
+    c = np.ascontiguousarray(c, dtype=np.int32)
+    delta = np.zeros(c.size, dtype=np.int64)
+    _check(lib().hora_oracle_allocate_baseline(c.size, _ptr(c), int(budget), int(delta_max),
+                                               {"uniform": 0, "hard_first": 1}[rule], _ptr(delta)))
+    return delta
+
+
+def pass_at_k(n_samples: np.ndarray, c: np.ndarray, ks) -> Tuple[np.ndarray, np.ndarray]:
+    """Unbiased Pass@K estimator of Sec. 4, Eq. 6, by its definition in exact integer
+    arithmetic: per problem 1 - C(N - c, K) / C(N, K), rounded once to binary64; the
+    benchmark value is the mean over the problems (math.fsum, exactly rounded).
+    Returns (per_problem[len(ks), n], mean[len(ks)])."""
+    import math
+    from fractions import Fraction
+    n_samples = np.asarray(n_samples, dtype=np.int64)
+    c = np.asarray(c, dtype=np.int64)
+    assert n_samples.shape == c.shape and c.ndim == 1
+    memo = {}
+    per = np.zeros((len(ks), c.size), dtype=np.float64)
+    for a, k in enumerate(ks):
+        for i, (nn, cc) in enumerate(zip(n_samples.tolist(), c.tolist())):
+            if not (0 <= cc <= nn and 1 <= k <= nn):
+                raise OracleError(ERR_RANGE)
+            key = (nn, cc, k)
+            if key not in memo:
+                memo[key] = float(1 - Fraction(math.comb(nn - cc, k), math.comb(nn, k)))
+            per[a, i] = memo[key]
+    mean = np.array([math.fsum(row) / c.size if c.size else 0.0 for row in per], dtype=np.float64)
+    return per, mean
