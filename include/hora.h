@@ -48,7 +48,7 @@ typedef enum {
     HORA_ERR_TIMEOUT = -7      /* a bounded device-side wait gave up (via dev_status)          */
 } hora_status;
 
-typedef enum { HORA_ADV_GRPO = 0, HORA_ADV_RLOO = 1 } hora_adv_mode;
+typedef enum { HORA_ADV_GRPO = 0, HORA_ADV_RLOO = 1, HORA_ADV_CENTER = 2 } hora_adv_mode;
 typedef enum { HORA_F32 = 0, HORA_F64 = 1 } hora_ftype;
 typedef enum { HORA_I32 = 0, HORA_I64 = 1 } hora_itype;
 
@@ -58,6 +58,12 @@ typedef enum {
     HORA_ALLOC_CLASS = 1,  /* shared prior only: histogram of c, threshold solved per class       */
     HORA_ALLOC_BISECT = 2  /* bisection on the gain threshold with per-prompt monotone searches   */
 } hora_alloc_method;
+
+/* Baseline allocation rules (hora_allocate_baseline). */
+typedef enum {
+    HORA_RULE_UNIFORM = 0,    /* the same number of additional rollouts for every prompt        */
+    HORA_RULE_HARD_FIRST = 1  /* the budget goes only to prompts with c_i = 0 (Sec. 5, Table 2) */
+} hora_baseline_rule;
 
 /* Largest G0 the CLASS method handles (one wavefront lane per class c = 0..G0). */
 #define HORA_CLASS_MAX_G0 63
@@ -150,6 +156,27 @@ int hora_allocate_posterior(int64_t n, int32_t g0, const double *alpha, const do
                             void *stream);
 
 /*
+ * The allocation rules the paper compares hit-utility allocation with, with the same
+ * outputs as hora_allocate (util[i] is still the hit utility U_i(delta_i) of what the rule
+ * hands out, so that rules can be compared on the paper's own objective, Eq. 4):
+ *   HORA_RULE_UNIFORM    the fixed-group baseline (Sec. 4): every prompt gets
+ *                        budget / n additional rollouts;
+ *   HORA_RULE_HARD_FIRST the hard-first heuristic (Sec. 5, Table 2): the budget goes only
+ *                        to the prompts with c_i = 0.
+ * The paper does not say how the eligible prompts share the budget or what happens when
+ * no prompt has c_i = 0: here they share it evenly, the remainder going one unit each to
+ * the lowest prompt indices, and a batch without such a prompt is allocated uniformly.
+ * A cap that the rule would exceed gives HORA_ERR_INFEASIBLE (return value where the
+ * arguments alone show it, else dev_status).  g0 <= HORA_CLASS_MAX_G0.  summary: tau = 0,
+ * count_gt = budget - tie_units, tie_units = the remainder, tie_prompts = eligible prompts.
+ * Workspace and the other arguments: as for hora_allocate.
+ */
+int hora_allocate_baseline(int64_t n, int32_t g0, const int32_t *c, double alpha0, double beta0,
+                           int64_t budget, int32_t delta_max, int32_t rule, int32_t *delta, double *util,
+                           void *group_off, int32_t off_t, hora_alloc_summary *summary,
+                           int32_t *dev_status, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Bytes of workspace hora_allocate_sharded needs for n_shards shards: the gain tables of
  * the G0+1 classes (kept from call to call and reused while the prior, G0 and the cap
  * stay the same) and the prefix sums of the shard budgets.  Device memory, 256-byte
@@ -196,6 +223,9 @@ int hora_allocate_sharded(int64_t n, int32_t g0, const int32_t *c, double alpha0
  *         std with divisor G_g - ddof.  A group whose rewards are all equal (zero
  *         empirical std) gets exactly 0, as does a group with G_g - ddof <= 0.
  *   RLOO: adv_j = R_j - (S - R_j) / (G_g - 1), S the group's reward sum; G_g = 1 gives 0.
+ *   CENTER: adv_j = R_j - mean, the GRPO form without the division by the standard
+ *         deviation (for objectives of the Dr. GRPO kind; the paper's runs use GRPO as
+ *         written in Sec. 3.1).  A group whose rewards are all equal gets exactly 0.
  * Sums run over the group in storage order in binary64; the result is rounded once
  * when stored as float.
  *
@@ -203,11 +233,32 @@ int hora_allocate_sharded(int64_t n, int32_t g0, const int32_t *c, double alpha0
  *             (else HORA_ERR_RANGE in dev_status).
  * reward, adv : device, n_resp values of type ft (HORA_F32 or HORA_F64); n_resp must
  *             equal group_off[n_groups] (else HORA_ERR_RANGE in dev_status).
- * eps >= 0; ddof is 0 or 1 (both ignored for RLOO).
+ * eps >= 0; ddof is 0 or 1 (both used by GRPO only).
  */
 int hora_group_advantage(int64_t n_groups, const void *group_off, int32_t off_t, int64_t n_resp,
                          const void *reward, void *adv, int32_t ft, int32_t mode, double eps,
                          int32_t ddof, int32_t *dev_status, void *stream);
+
+/*
+ * Per-response loss weights for variable-size groups (Sec. 3.1, objective: mean over the
+ * tokens of a response, then over the responses of a prompt; Sec. 3.2 "Training objective
+ * with variable-size groups": 1/G becomes 1/G_i so that every prompt weighs the same
+ * however many additional rollouts it received):
+ *   length_const <= 0 : weight[j] = 1 / (G_g * len_j),  len_j = tok_off[j+1] - tok_off[j]
+ *   length_const  > 0 : weight[j] = 1 / (G_g * length_const), a constant in place of the
+ *                       response length (length normalisation of the Dr. GRPO kind)
+ * for every response j of group g; 0 for a response without tokens.  Evaluated in binary64
+ * (one multiply, then one divide) and rounded once when stored as float.  Feeding the
+ * result to hora_token_broadcast gives the weight of every token.
+ *
+ * group_off : device, n_groups+1 offsets (as for hora_group_advantage).
+ * tok_off   : device, n_resp+1 packed token offsets, non-decreasing (else HORA_ERR_RANGE
+ *             in dev_status).
+ * weight    : device out, n_resp values of type ft.
+ */
+int hora_response_weights(int64_t n_groups, const void *group_off, int32_t group_off_t, int64_t n_resp,
+                          const void *tok_off, int32_t tok_off_t, double length_const, void *weight,
+                          int32_t ft, int32_t *dev_status, void *stream);
 
 /*
  * Bytes of workspace hora_token_broadcast needs for n_tokens tokens of type out_t
@@ -233,6 +284,30 @@ size_t hora_token_broadcast_workspace_bytes(int64_t n_tokens, int32_t out_t);
 int hora_token_broadcast(int64_t n_resp, const void *adv, int32_t adv_t, const void *tok_off,
                          int32_t off_t, void *tok_adv, int32_t out_t, int64_t n_tokens,
                          int32_t *dev_status, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Bytes of workspace hora_pass_at_k needs (device memory, 8-byte aligned, no
+ * initialisation needed).  n_k <= 64.
+ */
+size_t hora_pass_at_k_workspace_bytes(int64_t n_problems, int32_t n_k);
+
+/*
+ * Unbiased Pass@K estimator (Sec. 4, Eq. 6).  Problem q has a pool of n_samples[q]
+ * samples of which correct[q] are correct; for every K in ks
+ *   per_problem[a * n_problems + q] = 1 - C(n_samples[q] - correct[q], ks[a]) / C(n_samples[q], ks[a])
+ *   mean[a] = the average of that over the problems (the benchmark's Pass@K).
+ * Evaluated in binary64 as a product of quotients (no binomial coefficient is formed).
+ *
+ * n_samples, correct : device, n_problems int32 each; 0 <= correct <= n_samples, and
+ *                      1 <= K <= n_samples for every K (else HORA_ERR_RANGE in dev_status
+ *                      and the value counts as 0).
+ * ks          : HOST, n_k int32 (n_k <= 64), read before the call returns.
+ * per_problem : device out, n_k * n_problems doubles.  Nullable.
+ * mean        : device out, n_k doubles.
+ */
+int hora_pass_at_k(int64_t n_problems, const int32_t *n_samples, const int32_t *correct, int32_t n_k,
+                   const int32_t *ks, double *per_problem, double *mean, int32_t *dev_status,
+                   void *workspace, size_t workspace_bytes, void *stream);
 
 #ifdef __cplusplus
 }

@@ -1,4 +1,5 @@
-// Group-relative advantages over variable-size groups (Sec. 3.1 GRPO; Sec. 4 / App. E RLOO).
+// Group-relative advantages over variable-size groups (Sec. 3.1 GRPO; Sec. 4 / App. E RLOO),
+// and the per-response loss weights of the objective with variable-size groups (Sec. 3.2).
 //
 // A sub-group of L lanes (L a power of two, chosen from the mean group size) owns one
 // group: the lanes stride over the group's rewards, so a wavefront reads a contiguous
@@ -7,6 +8,7 @@
 #include <hip/hip_runtime.h>
 
 #include <climits>
+#include <cmath>
 #include <cstdint>
 
 #include "hora.h"
@@ -71,8 +73,15 @@ __global__ __launch_bounds__(kThreads) void k_group_adv(long long n_groups, cons
         return;
     }
 
-    const bool zero = equal || (size - ddof <= 0);
     const double mean = size > 0 ? sum / (double)size : 0.0;
+    if (mode == HORA_ADV_CENTER) {
+        for (long long j = lo + sub; j < hi; j += L) {
+            const double x = (double)reward[j];
+            adv[j] = (F)(equal ? 0.0 : x - mean);
+        }
+        return;
+    }
+    const bool zero = equal || (size - ddof <= 0);
     double ss = 0.0;
     if (!zero) {
         for (long long j = lo + sub; j < hi; j += L) {
@@ -115,6 +124,46 @@ static int launch_adv(int64_t n_groups, const void* off, int64_t n_resp, const v
     return hipGetLastError() == hipSuccess ? HORA_OK : HORA_ERR_HIP;
 }
 
+// Loss weight of the tokens of every response: 1 / (G_i * |o_j|), or 1 / (G_i * L) with a
+// constant L in place of the response length; 0 for a response without tokens.  kLanes
+// lanes stride over the responses of one group.
+constexpr int kWeightLanes = 8;
+
+template <typename F, typename IG, typename IT>
+__global__ __launch_bounds__(kThreads) void k_response_weights(long long n_groups, const IG* __restrict__ group_off,
+                                                               long long n_resp, const IT* __restrict__ tok_off,
+                                                               double length_const, F* __restrict__ weight,
+                                                               int32_t* dev_status) {
+    const int sub = (int)(threadIdx.x % kWeightLanes);
+    const long long g = ((long long)blockIdx.x * kThreads + threadIdx.x) / kWeightLanes;
+    if (g >= n_groups) return;
+    long long lo = (long long)group_off[g], hi = (long long)group_off[g + 1];
+    bool bad = lo < 0 || hi < lo || hi > n_resp || (g == 0 && lo != 0) || (g == n_groups - 1 && hi != n_resp);
+    if (bad) {
+        lo = lo < 0 ? 0 : (lo > n_resp ? n_resp : lo);
+        hi = hi < lo ? lo : (hi > n_resp ? n_resp : hi);
+    }
+    const double size = (double)(hi - lo);
+    for (long long j = lo + sub; j < hi; j += kWeightLanes) {
+        const long long len = (long long)tok_off[j + 1] - (long long)tok_off[j];
+        bad |= len < 0;
+        const double norm = length_const > 0.0 ? length_const : (double)len;
+        weight[j] = (F)(len <= 0 ? 0.0 : 1.0 / (size * norm));
+    }
+    if (bad) report(dev_status, HORA_ERR_RANGE);
+}
+
+template <typename F, typename IG, typename IT>
+static int launch_weights(int64_t n_groups, const void* group_off, int64_t n_resp, const void* tok_off,
+                          double length_const, void* weight, int32_t* dev_status, hipStream_t stream) {
+    const long long blocks = (n_groups * kWeightLanes + kThreads - 1) / kThreads;
+    if (blocks > INT_MAX) return HORA_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL((k_response_weights<F, IG, IT>), dim3((unsigned)blocks), dim3(kThreads), 0, stream,
+                       (long long)n_groups, (const IG*)group_off, (long long)n_resp, (const IT*)tok_off,
+                       length_const, (F*)weight, dev_status);
+    return hipGetLastError() == hipSuccess ? HORA_OK : HORA_ERR_HIP;
+}
+
 }  // namespace hora
 
 using namespace hora;
@@ -125,7 +174,7 @@ extern "C" int hora_group_advantage(int64_t n_groups, const void* group_off, int
     if (n_groups < 0 || n_resp < 0 || !dev_status) return HORA_ERR_INVALID_ARG;
     if (off_t != HORA_I32 && off_t != HORA_I64) return HORA_ERR_INVALID_ARG;
     if (ft != HORA_F32 && ft != HORA_F64) return HORA_ERR_INVALID_ARG;
-    if (mode != HORA_ADV_GRPO && mode != HORA_ADV_RLOO) return HORA_ERR_INVALID_ARG;
+    if (mode != HORA_ADV_GRPO && mode != HORA_ADV_RLOO && mode != HORA_ADV_CENTER) return HORA_ERR_INVALID_ARG;
     if (!(eps >= 0.0) || (ddof != 0 && ddof != 1)) return HORA_ERR_INVALID_ARG;
     if (n_groups == 0) return n_resp == 0 ? HORA_OK : HORA_ERR_INVALID_ARG;
     if (!group_off) return HORA_ERR_INVALID_ARG;
@@ -144,4 +193,37 @@ extern "C" int hora_group_advantage(int64_t n_groups, const void* group_off, int
     if (off_t == HORA_I32)
         return launch_adv<double, int32_t>(n_groups, group_off, n_resp, reward, adv, mode, eps, ddof, dev_status, s);
     return launch_adv<double, long long>(n_groups, group_off, n_resp, reward, adv, mode, eps, ddof, dev_status, s);
+}
+
+extern "C" int hora_response_weights(int64_t n_groups, const void* group_off, int32_t group_off_t, int64_t n_resp,
+                                     const void* tok_off, int32_t tok_off_t, double length_const, void* weight,
+                                     int32_t ft, int32_t* dev_status, void* stream) {
+    if (n_groups < 0 || n_resp < 0 || !dev_status) return HORA_ERR_INVALID_ARG;
+    if (group_off_t != HORA_I32 && group_off_t != HORA_I64) return HORA_ERR_INVALID_ARG;
+    if (tok_off_t != HORA_I32 && tok_off_t != HORA_I64) return HORA_ERR_INVALID_ARG;
+    if (ft != HORA_F32 && ft != HORA_F64) return HORA_ERR_INVALID_ARG;
+    if (!(length_const == length_const) || length_const == INFINITY) return HORA_ERR_INVALID_ARG;
+    if (n_groups == 0) return n_resp == 0 ? HORA_OK : HORA_ERR_INVALID_ARG;
+    if (!group_off) return HORA_ERR_INVALID_ARG;
+    if (n_resp > 0 && (!tok_off || !weight)) return HORA_ERR_INVALID_ARG;
+    if (group_off_t == HORA_I32 && n_resp >= (1ll << 31)) return HORA_ERR_INVALID_ARG;
+    const uintptr_t fmask = ft == HORA_F32 ? 3 : 7, gmask = group_off_t == HORA_I32 ? 3 : 7,
+                    tmask = tok_off_t == HORA_I32 ? 3 : 7;
+    if ((reinterpret_cast<uintptr_t>(weight) & fmask) || (reinterpret_cast<uintptr_t>(group_off) & gmask) ||
+        (reinterpret_cast<uintptr_t>(tok_off) & tmask))
+        return HORA_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+#define HORA_WEIGHTS(F)                                                                                          \
+    (group_off_t == HORA_I32                                                                                     \
+         ? (tok_off_t == HORA_I32 ? launch_weights<F, int32_t, int32_t>(n_groups, group_off, n_resp, tok_off,    \
+                                                                        length_const, weight, dev_status, s)     \
+                                  : launch_weights<F, int32_t, long long>(n_groups, group_off, n_resp, tok_off,  \
+                                                                          length_const, weight, dev_status, s))  \
+         : (tok_off_t == HORA_I32 ? launch_weights<F, long long, int32_t>(n_groups, group_off, n_resp, tok_off,  \
+                                                                          length_const, weight, dev_status, s)   \
+                                  : launch_weights<F, long long, long long>(n_groups, group_off, n_resp, tok_off, \
+                                                                            length_const, weight, dev_status, s)))
+    if (ft == HORA_F32) return HORA_WEIGHTS(float);
+    return HORA_WEIGHTS(double);
+#undef HORA_WEIGHTS
 }

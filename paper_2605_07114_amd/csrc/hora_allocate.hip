@@ -540,6 +540,51 @@ __device__ void solve_by_greedy(int g0, double alpha0, double beta0, long long c
     __syncthreads();
 }
 
+// Baseline rules the paper compares with (Sec. 5, Table 2 "hard-first"; the fixed-group
+// baseline of Sec. 4), expressed in the terms of the tie pass: every eligible prompt gets
+// `each` units and counts as tied, and the first `rest` of them by index get one more.
+// rule 1: uniform, every prompt is eligible.  rule 2: hard-first, only prompts with
+// c_i = 0 are; the split inside the eligible set is even (the paper does not say), and a
+// batch without such a prompt falls back to uniform.
+__device__ void solve_by_rule(int rule, int g0, double alpha0, double beta0, long long cap_eff, long long budget,
+                              const long long* s_n, ClassSolution* sol, int32_t* dev_status) {
+    if (wave_id() == 0) {
+        const int nc = g0 + 1;
+        const int lane = lane_id();
+        const bool has = lane < nc;
+        const long long ncount = has ? s_n[lane] : 0;
+        long long total = 0;
+        for (int j = 0; j < nc; ++j) total += (long long)read_lane_u64((unsigned long long)ncount, j);
+        const long long hard = (long long)read_lane_u64((unsigned long long)ncount, 0);
+        const bool all = rule == 1 || hard == 0;
+        const long long eligible = all ? total : hard;
+        const long long each = eligible > 0 ? budget / eligible : 0;
+        const long long rest = eligible > 0 ? budget - each * eligible : 0;
+        if (lane == 0 && each + (rest > 0 ? 1 : 0) > cap_eff) report(dev_status, HORA_ERR_INFEASIBLE);
+        const bool mine = has && (all || lane == 0);
+        const long long k = mine ? each : 0;
+        const double a = alpha0 + (double)(has ? lane : 0);
+        const double b = beta0 + (double)(has ? g0 - lane : 0);
+        const double s = a + b;
+        double e = 1.0, lf = 0.0;
+        for (long long l = 0; l < k; ++l) {
+            e = surv_next(e, b, s, lf);
+            lf += 1.0;
+        }
+        sol->k[lane] = (int)k;
+        sol->tied[lane] = mine ? 1 : 0;
+        sol->u0[lane] = 1.0 - e;
+        sol->u1[lane] = 1.0 - surv_next(e, b, s, lf);
+        if (lane == 0) {
+            sol->tau_bits = 0ull;
+            sol->r = rest;
+            sol->tie_prompts = eligible;
+            sol->found = 1;
+        }
+    }
+    __syncthreads();
+}
+
 // ----------------------------------------------------------------------------------
 // CLASS pass 2: solve (redundantly per workgroup), then write the workgroup's chunk.
 // kOff: 0 no offsets, 1 int32 offsets, 2 int64 offsets.
@@ -554,7 +599,7 @@ __global__ __launch_bounds__(kBig) void k_class_write(const int32_t* __restrict_
                                                           int32_t* __restrict__ delta, double* __restrict__ util,
                                                           void* __restrict__ group_off,
                                                           hora_alloc_summary* __restrict__ summary,
-                                                          int32_t* dev_status) {
+                                                          int32_t* dev_status, int rule) {
     __shared__ double s_gain[kTableCap];
     __shared__ double s_surv[kTableCap];
     __shared__ long long s_part[2][kMaxClasses * kMaxBlocks / kWave];
@@ -636,7 +681,9 @@ __global__ __launch_bounds__(kBig) void k_class_write(const int32_t* __restrict_
     }
     __syncthreads();
 
-    if (budget > 0) {
+    if (budget > 0 && rule != 0) {
+        solve_by_rule(rule, g0, alpha0, beta0, cap_eff, budget, s_n, &s_sol, dev_status);
+    } else if (budget > 0) {
         solve_by_table(nc, row_len, len, rows_end_at_cap, budget, s_n, s_gain, s_surv, s_pair, &s_sol);
         if (!s_sol.found) solve_by_greedy(g0, alpha0, beta0, cap_eff, budget, s_n, &s_sol, dev_status);
     } else {
@@ -1120,7 +1167,7 @@ static int table_row(int nc, int64_t n, int64_t budget, int32_t delta_max) {
 }
 
 static int run_class(const int32_t* c, double alpha0, double beta0, const CommonArgs& a, const Plan& p,
-                     const Workspace& w) {
+                     const Workspace& w, int rule) {
     const int nc = a.g0 + 1;
     const int row = table_row(nc, a.n, a.budget, a.delta_max);
     const int cap = a.delta_max > 0 ? a.delta_max : 0;
@@ -1131,7 +1178,7 @@ static int run_class(const int32_t* c, double alpha0, double beta0, const Common
 #define HORA_LAUNCH_CLASS_WRITE(M)                                                                              \
     hipLaunchKernelGGL((k_class_write<M>), dim3(p.nb), dim3(kBig), 0, a.stream, c, (long long)a.n,          \
                        (int)a.g0, alpha0, beta0, (long long)a.budget, cap, p.chunk, p.nb, row, w.class_hist,   \
-                       w.gain_table, w.surv_table, a.delta, a.util, a.group_off, a.summary, a.dev_status)
+                       w.gain_table, w.surv_table, a.delta, a.util, a.group_off, a.summary, a.dev_status, rule)
     if (mode == 0) HORA_LAUNCH_CLASS_WRITE(0);
     else if (mode == 1) HORA_LAUNCH_CLASS_WRITE(1);
     else HORA_LAUNCH_CLASS_WRITE(2);
@@ -1221,7 +1268,32 @@ int hora_allocate(int64_t n, int32_t g0, const int32_t* c, double alpha0, double
         CountsSource src{c, g0, alpha0, beta0};
         return run_bisect(src, a, p, w);
     }
-    return run_class(c, alpha0, beta0, a, p, w);
+    return run_class(c, alpha0, beta0, a, p, w, 0);
+}
+
+int hora_allocate_baseline(int64_t n, int32_t g0, const int32_t* c, double alpha0, double beta0, int64_t budget,
+                           int32_t delta_max, int32_t rule, int32_t* delta, double* util, void* group_off,
+                           int32_t off_t, hora_alloc_summary* summary, int32_t* dev_status, void* workspace,
+                           size_t workspace_bytes, void* stream) {
+    CommonArgs a{n, g0, budget, delta_max, delta, util, group_off, off_t, summary, dev_status,
+                 workspace, workspace_bytes, (hipStream_t)stream};
+    if (rule != HORA_RULE_UNIFORM && rule != HORA_RULE_HARD_FIRST) return HORA_ERR_INVALID_ARG;
+    // feasibility depends on the rule (hard-first needs the data): checked on the device
+    CommonArgs host = a;
+    host.delta_max = 0;
+    int rc = validate_common(host);
+    if (rc != HORA_OK) return rc;
+    if (!(alpha0 > 0.0) || !(beta0 > 0.0) || !std::isfinite(alpha0) || !std::isfinite(beta0))
+        return HORA_ERR_INVALID_ARG;
+    if (g0 > HORA_CLASS_MAX_G0) return HORA_ERR_UNSUPPORTED;
+    if (delta_max > 0 && budget > 0 && (budget + delta_max - 1) / delta_max > n) return HORA_ERR_INFEASIBLE;
+    if (n == 0) return handle_empty(a);
+    if (!c || (reinterpret_cast<uintptr_t>(c) & 3)) return HORA_ERR_INVALID_ARG;
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255)) return HORA_ERR_WORKSPACE;
+    Workspace w = carve(workspace);
+    if (workspace_bytes < w.bytes) return HORA_ERR_WORKSPACE;
+    const Plan p = make_plan(n);
+    return run_class(c, alpha0, beta0, a, p, w, rule == HORA_RULE_UNIFORM ? 1 : 2);
 }
 
 int hora_allocate_posterior(int64_t n, int32_t g0, const double* alpha, const double* beta, int64_t budget,

@@ -23,16 +23,18 @@ LIB_PATH = os.path.join(_HERE, "libhora.so")
 OK = 0
 ERR_INVALID_ARG, ERR_INFEASIBLE, ERR_WORKSPACE, ERR_RANGE = -1, -2, -3, -4
 ERR_HIP, ERR_UNSUPPORTED, ERR_TIMEOUT = -5, -6, -7
-ADV_GRPO, ADV_RLOO = 0, 1
+ADV_GRPO, ADV_RLOO, ADV_CENTER = 0, 1, 2
 F32, F64 = 0, 1
 I32, I64 = 0, 1
 ALLOC_AUTO, ALLOC_CLASS, ALLOC_BISECT = 0, 1, 2
+RULE_UNIFORM, RULE_HARD_FIRST = 0, 1
 CLASS_MAX_G0 = 63
 
 EXPORTS = (
     "hora_status_string", "hora_version", "hora_marginal_gains", "hora_allocate_workspace_bytes",
     "hora_allocate", "hora_allocate_posterior", "hora_group_advantage", "hora_token_broadcast",
     "hora_token_broadcast_workspace_bytes", "hora_allocate_sharded", "hora_allocate_sharded_workspace_bytes",
+    "hora_response_weights", "hora_allocate_baseline", "hora_pass_at_k", "hora_pass_at_k_workspace_bytes",
 )
 
 
@@ -67,6 +69,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.hora_allocate_workspace_bytes.restype = sz
     lib.hora_allocate.argtypes = [i64, i32, p, f64, f64, i64, i32, i32, p, p, p, i32, p, p, p, sz, p]
     lib.hora_allocate.restype = ctypes.c_int
+    lib.hora_allocate_baseline.argtypes = [i64, i32, p, f64, f64, i64, i32, i32, p, p, p, i32, p, p, p, sz, p]
+    lib.hora_allocate_baseline.restype = ctypes.c_int
     lib.hora_allocate_posterior.argtypes = [i64, i32, p, p, i64, i32, p, p, p, i32, p, p, p, sz, p]
     lib.hora_allocate_posterior.restype = ctypes.c_int
     lib.hora_allocate_sharded_workspace_bytes.argtypes = [i64]
@@ -75,6 +79,12 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.hora_allocate_sharded.restype = ctypes.c_int
     lib.hora_group_advantage.argtypes = [i64, p, i32, i64, p, p, i32, i32, f64, i32, p, p]
     lib.hora_group_advantage.restype = ctypes.c_int
+    lib.hora_pass_at_k_workspace_bytes.argtypes = [i64, i32]
+    lib.hora_pass_at_k_workspace_bytes.restype = sz
+    lib.hora_pass_at_k.argtypes = [i64, p, p, i32, p, p, p, p, p, sz, p]
+    lib.hora_pass_at_k.restype = ctypes.c_int
+    lib.hora_response_weights.argtypes = [i64, p, i32, i64, p, i32, f64, p, i32, p, p]
+    lib.hora_response_weights.restype = ctypes.c_int
     lib.hora_token_broadcast_workspace_bytes.argtypes = [i64, i32]
     lib.hora_token_broadcast_workspace_bytes.restype = sz
     lib.hora_token_broadcast.argtypes = [i64, p, i32, p, i32, p, i32, i64, p, p, sz, p]
@@ -167,6 +177,26 @@ def hora_allocate(c: torch.Tensor, g0: int, budget: int, delta: torch.Tensor, de
         _stream(stream)), "hora_allocate")
 
 
+def hora_allocate_baseline(c: torch.Tensor, g0: int, budget: int, rule: int, delta: torch.Tensor,
+                           dev_status: torch.Tensor, workspace: torch.Tensor, *, alpha0: float = 1.0,
+                           beta0: float = 1.0, delta_max: int = 0, util: Optional[torch.Tensor] = None,
+                           group_off: Optional[torch.Tensor] = None, summary: Optional[torch.Tensor] = None,
+                           stream=None) -> None:
+    n = c.numel()
+    _expect(c, torch.int32, n, "c")
+    _expect(delta, torch.int32, n, "delta")
+    _expect(util, torch.float64, n, "util")
+    _expect(dev_status, torch.int32, 1, "dev_status")
+    _expect(summary, torch.int64, 4, "summary")
+    if group_off is not None and group_off.numel() < n + 1:
+        raise ValueError("group_off needs n + 1 elements")
+    _check(load_library().hora_allocate_baseline(
+        n, int(g0), _ptr(c), float(alpha0), float(beta0), int(budget), int(delta_max), int(rule),
+        _ptr(delta), _ptr(util), _ptr(group_off), _itype(group_off) if group_off is not None else I32,
+        _ptr(summary), _ptr(dev_status), _ptr(workspace), workspace.numel() * workspace.element_size(),
+        _stream(stream)), "hora_allocate_baseline")
+
+
 def hora_allocate_posterior(alpha: torch.Tensor, beta: torch.Tensor, g0: int, budget: int, delta: torch.Tensor,
                             dev_status: torch.Tensor, workspace: torch.Tensor, *, delta_max: int = 0,
                             util: Optional[torch.Tensor] = None, group_off: Optional[torch.Tensor] = None,
@@ -227,6 +257,39 @@ def hora_group_advantage(group_off: torch.Tensor, reward: torch.Tensor, adv: tor
         int(mode), float(eps), int(ddof), _ptr(dev_status), _stream(stream)), "hora_group_advantage")
 
 
+def hora_response_weights(group_off: torch.Tensor, tok_off: torch.Tensor, weight: torch.Tensor,
+                          dev_status: torch.Tensor, *, length_const: float = 0.0, stream=None) -> None:
+    n_groups = group_off.numel() - 1
+    n_resp = tok_off.numel() - 1
+    if weight.numel() < n_resp:
+        raise ValueError("weight too small")
+    _expect(dev_status, torch.int32, 1, "dev_status")
+    _check(load_library().hora_response_weights(
+        n_groups, _ptr(group_off), _itype(group_off), n_resp, _ptr(tok_off), _itype(tok_off), float(length_const),
+        _ptr(weight), _ftype(weight), _ptr(dev_status), _stream(stream)), "hora_response_weights")
+
+
+def hora_pass_at_k(n_samples: torch.Tensor, correct: torch.Tensor, ks, mean: torch.Tensor,
+                   dev_status: torch.Tensor, workspace: torch.Tensor, *, per_problem: Optional[torch.Tensor] = None,
+                   stream=None) -> None:
+    n = n_samples.numel()
+    ks = [int(k) for k in ks]
+    _expect(n_samples, torch.int32, n, "n_samples")
+    _expect(correct, torch.int32, n, "correct")
+    _expect(mean, torch.float64, len(ks), "mean")
+    _expect(per_problem, torch.float64, len(ks) * n, "per_problem")
+    _expect(dev_status, torch.int32, 1, "dev_status")
+    host_ks = (ctypes.c_int32 * max(len(ks), 1))(*ks)
+    _check(load_library().hora_pass_at_k(
+        n, _ptr(n_samples), _ptr(correct), len(ks), ctypes.cast(host_ks, ctypes.c_void_p), _ptr(per_problem),
+        _ptr(mean), _ptr(dev_status), _ptr(workspace), workspace.numel() * workspace.element_size(),
+        _stream(stream)), "hora_pass_at_k")
+
+
+def hora_pass_at_k_workspace_bytes(n_problems: int, n_k: int) -> int:
+    return int(load_library().hora_pass_at_k_workspace_bytes(int(n_problems), int(n_k)))
+
+
 def hora_token_broadcast_workspace_bytes(n_tokens: int, out_dtype: torch.dtype = torch.float32) -> int:
     t = {torch.float32: F32, torch.float64: F64}[out_dtype]
     return int(load_library().hora_token_broadcast_workspace_bytes(int(n_tokens), t))
@@ -285,6 +348,18 @@ class Session:
         hora_allocate(c, g0, budget, out.delta, self.dev_status, self.workspace(n, g0), alpha0=alpha0,
                       beta0=beta0, delta_max=delta_max, method=method, util=out.util, group_off=out.group_off,
                       summary=out.summary)
+        return out
+
+    def allocate_baseline(self, c: torch.Tensor, g0: int, budget: int, rule: int, *, delta_max: int = 0,
+                          off_dtype: Optional[torch.dtype] = torch.int64) -> Allocation:
+        n = c.numel()
+        out = Allocation(
+            delta=torch.empty(n, dtype=torch.int32, device=self.device),
+            util=torch.empty(n, dtype=torch.float64, device=self.device),
+            group_off=torch.empty(n + 1, dtype=off_dtype, device=self.device) if off_dtype else None,
+            summary=torch.zeros(4, dtype=torch.int64, device=self.device))
+        hora_allocate_baseline(c, g0, budget, rule, out.delta, self.dev_status, self.workspace(n, g0),
+                               delta_max=delta_max, util=out.util, group_off=out.group_off, summary=out.summary)
         return out
 
     def allocate_sharded(self, c: torch.Tensor, g0: int, shard_off: torch.Tensor, shard_budget: torch.Tensor, *,
