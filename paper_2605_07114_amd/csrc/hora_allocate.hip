@@ -42,13 +42,15 @@ constexpr int kTableCap = kMaxClasses * kMinRow;   // doubles per table (2048)
 constexpr unsigned kTiedBit = 0x80000000u;
 constexpr int kPairCap = 16384;               // (table entry, class) pairs ranked one per thread when they fit
 
-constexpr int kSoloMaxPrompts = 8192;   // up to here one workgroup searches alone
-constexpr int kParallelPasses = 4;   // launched grid-wide; a single-workgroup finisher covers the rest
+constexpr int kSoloMaxPrompts = 2048;   // up to here one workgroup searches alone
+constexpr int kParallelPasses = 7;      // launched grid-wide; a single-workgroup finisher covers the rest
+constexpr unsigned long long kWindowStep = 4ull << 52;   // 4 exponent steps of the bit pattern: a factor 16 in value
+constexpr int kSoloMaxPasses = 512 + 10;   // windows from the largest gain down to zero, plus the narrowing passes
 
 struct AllocHeader {              // 256 bytes at the start of the workspace, zero at rest
-    unsigned long long lo_inv;    // ~bits of min_i M_i(W-1), gathered with atomicMax
+    unsigned long long unused0;
     unsigned long long hi;        // bits of max_i M_i(0), gathered with atomicMax
-    unsigned long long above;     // pairs above the bracket counted in the running pass
+    unsigned long long above;     // pairs whose gain is > hi_cur
     unsigned int ticket;          // workgroups that have finished the running pass
     unsigned int done;            // the bracket has closed: tau = hi_cur
     unsigned long long lo_cur;    // bracket: count_gt(lo_cur) >= budget
@@ -57,11 +59,15 @@ struct AllocHeader {              // 256 bytes at the start of the workspace, ze
 };
 static_assert(sizeof(AllocHeader) == 256, "header size");
 
-struct SelectBins {               // per-interval tallies of one narrowing pass, zero at rest
+struct SelectBins {               // per-interval tallies of one workgroup in one search pass
     unsigned long long cnt[kBins];       // pairs whose gain falls into the interval
     unsigned long long vmax[kBins];      // largest gain pattern seen in the interval
     unsigned long long vmin_inv[kBins];  // ~(smallest gain pattern seen in the interval)
 };
+// One SelectBins per workgroup (kMaxBlocks of them): every workgroup stores its tallies
+// with plain stores and the last one adds them up.  Atomics of all workgroups on one set
+// of intervals serialise at the memory side (hundreds of them per address and pass, each
+// a round trip), which cost more than the walks themselves.
 
 struct BisectSolution {           // written by k_bisect_scan, read by k_bisect_write
     long long r;                  // units for the prompts tied at tau
@@ -110,7 +116,7 @@ static Workspace carve(void* base) {
     w.sol = (BisectSolution*)(ptr + off);
     off += sizeof(BisectSolution);
     w.bins = (SelectBins*)(ptr + off);
-    off += sizeof(SelectBins);
+    off += (size_t)kMaxBlocks * sizeof(SelectBins);
     w.class_hist = (int*)(ptr + off);
     off += align256((size_t)kMaxClasses * kMaxBlocks * sizeof(int));
     w.gain_table = (double*)(ptr + off);
@@ -744,76 +750,55 @@ __global__ __launch_bounds__(kBig) void k_class_write(const int32_t* __restrict_
 }
 
 // ----------------------------------------------------------------------------------
-// BISECT pass 0: bracket of tau.  With W = ceil(budget / n) every prompt has at least
-// W gains >= lo = min_i M_i(W-1), so count_ge(lo) >= budget and tau >= lo; and no
-// gain exceeds hi = max_i M_i(0).  Both are gathered with integer atomicMax (few
-// workgroups: atomics on one address serialise); the workgroup that finishes last
-// publishes the bracket (lo - 1, hi].
+// BISECT pass 0: the largest gain hi = max_i M_i(0), gathered with integer atomicMax (few
+// workgroups: atomics on one address serialise).
 // ----------------------------------------------------------------------------------
 template <class Src>
-__global__ __launch_bounds__(kBig) void k_select_bracket(Src src, long long n, long long w_steps,
-                                                         AllocHeader* __restrict__ hdr, int32_t* dev_status) {
-    __shared__ unsigned long long s_red[2][kBigWaves];
-    unsigned long long hi = 0, lo_inv = 0;
+__global__ __launch_bounds__(kBig) void k_select_top(Src src, long long n, AllocHeader* __restrict__ hdr,
+                                                     int32_t* dev_status) {
+    __shared__ unsigned long long s_red[kBigWaves];
+    unsigned long long hi = 0;
     bool bad = false;
     const long long stride = (long long)gridDim.x * kBig;
     for (long long i = (long long)blockIdx.x * kBig + threadIdx.x; i < n; i += stride) {
         double a, b;
         bad |= !src.load(i, a, b);
-        const double s = a + b;
-        double g = gain_first(a, s);
-        unsigned long long gb = gain_bits(g);
+        const unsigned long long gb = gain_bits(gain_first(a, a + b));
         hi = gb > hi ? gb : hi;
-        double lf = 0.0;
-        for (long long l = 1; l < w_steps; ++l) {
-            g = gain_next(g, b, s, lf);
-            lf += 1.0;
-        }
-        gb = ~gain_bits(g);
-        lo_inv = gb > lo_inv ? gb : lo_inv;
     }
     hi = wave_max_u64(hi);
-    lo_inv = wave_max_u64(lo_inv);
-    if (lane_id() == 0) { s_red[0][wave_id()] = hi; s_red[1][wave_id()] = lo_inv; }
+    if (lane_id() == 0) s_red[wave_id()] = hi;
     __syncthreads();
     if (threadIdx.x == 0) {
-        unsigned long long block_hi = 0, block_lo_inv = 0;
-        for (int i = 0; i < kBigWaves; ++i) {
-            block_hi = s_red[0][i] > block_hi ? s_red[0][i] : block_hi;
-            block_lo_inv = s_red[1][i] > block_lo_inv ? s_red[1][i] : block_lo_inv;
-        }
-        atomicMax(&hdr->hi, block_hi);
-        atomicMax(&hdr->lo_inv, block_lo_inv);
-        __threadfence();
-        if (atomicAdd(&hdr->ticket, 1u) == gridDim.x - 1) {
-            __threadfence();
-            const unsigned long long all_hi = atomicMax(&hdr->hi, 0ull);
-            const unsigned long long all_lo = ~atomicMax(&hdr->lo_inv, 0ull);
-            hdr->lo_cur = all_lo - 1ull;
-            hdr->hi_cur = all_hi;
-            hdr->done = (all_hi - (all_lo - 1ull) <= 1ull) ? 1u : 0u;
-            hdr->ticket = 0u;
-        }
+        unsigned long long block_hi = 0;
+        for (int i = 0; i < kBigWaves; ++i) block_hi = s_red[i] > block_hi ? s_red[i] : block_hi;
+        atomicMax(&hdr->hi, block_hi);   // k_select_move(first) turns it into the first window
     }
     if (bad) report(dev_status, HORA_ERR_RANGE);
 }
 
 // ----------------------------------------------------------------------------------
-// BISECT narrowing pass.  Invariant: count_gt(lo_cur) >= budget > count_gt(hi_cur).
-// The bracket (lo, hi] is cut into at most kBins intervals of 2^shift bit patterns.
-// Every prompt walks its gains down to lo (a monotone search); gains above hi are
-// counted, gains inside the bracket are tallied per interval together with the largest
-// and the smallest pattern seen there.  The running count from the top interval down
-// reaches the budget in exactly one interval; the bracket shrinks to the gains that
-// actually occur there, (min - 1, max], and closes when min == max (tau is that gain).
-// Each pass cuts the bracket at least 128-fold; with real-valued posteriors it holds
-// ~1/256 of the previous pass's gains, with a shared prior (few distinct gains, each
-// repeated) it closes in two passes.
+// BISECT search pass.  Invariant: exactly `above` pairs have a gain > hi_cur, and
+// above < budget.  The bracket (lo, hi] is cut into at most kBins intervals of 2^shift bit
+// patterns.  Every prompt walks its gains from l = 0 down to lo (a monotone search) and
+// the gains inside the bracket are tallied per interval, together with the largest and the
+// smallest pattern seen there.  If the running count from the top interval down reaches
+// the budget in interval j, the bracket shrinks to the gains that actually occur there,
+// (min - 1, max], and closes when min == max (tau is that gain): each such pass cuts the
+// bracket at least 128-fold; with real-valued posteriors it keeps ~1/256 of the gains of
+// the pass before, with a shared prior (few distinct gains, each repeated) it closes in
+// two passes.  Otherwise the whole window lies above tau: its count is added to `above`
+// and the next window, a factor 16 further down in value (4 exponent steps of the bit
+// pattern), is taken.  Searching window by window from the top keeps the walks short: a
+// window's count is a small multiple of the one before, so the work stays a small
+// multiple of the budget, whereas a bracket from a guaranteed lower bound (such as the
+// smallest ceil(budget/n)-th gain) can lie orders of magnitude below tau and make every
+// prompt walk thousands of steps.
 //
-// kSolo = false: the workgroups tally their share and add it to the global intervals;
-// the one that finishes last narrows the bracket for the next launch.
+// kSolo = false: every workgroup tallies its share into a slot of its own; k_select_move
+// adds the slots up and moves the bracket for the next launch.
 // kSolo = true: one workgroup repeats passes over all prompts until the bracket closes.
-// It runs after the parallel passes and normally finds the bracket closed already; it is
+// It runs after the grid-wide passes and normally finds the bracket closed already; it is
 // there so that a fixed, small number of launches is correct for any input.
 // ----------------------------------------------------------------------------------
 struct SelectShared {
@@ -822,28 +807,68 @@ struct SelectShared {
     unsigned long long vmin_inv[kBins];
     long long red[kBigWaves];
     unsigned long long lo, hi;
+    long long above;
     int done;
     int last;
 };
+
+// The step that ends a search pass, run by a whole workgroup: thread t < kBins holds the
+// tally (cj, mx, mn) of interval kBins - 1 - t (thread 0 the top one), the other threads
+// zeros.  Finds the interval in which the running count from the top reaches the budget
+// and shrinks the bracket to the gains seen there, or, when the whole window lies above
+// tau, takes the next window.
+__device__ __forceinline__ void move_bracket(SelectShared& sh, unsigned long long cj, unsigned long long mx,
+                                             unsigned long long mn, long long budget) {
+    const unsigned long long lo = sh.lo;
+    const long long start = sh.above;   // pairs above the bracket
+    if (cj > (unsigned long long)budget) cj = (unsigned long long)budget;
+    __syncthreads();                                     // sh.red is free, the bracket has been read
+    // pairs in higher intervals: exclusive prefix over the threads
+    const long long incl = wave_incl_scan<long long>((long long)cj);
+    if (lane_id() == kWave - 1) sh.red[wave_id()] = incl;
+    __syncthreads();
+    long long before = start + incl - (long long)cj;
+    long long total = 0;
+    for (int i = 0; i < kBigWaves; ++i) {
+        if (i < wave_id()) before += sh.red[i];
+        total += sh.red[i];
+    }
+    if (start + total < budget) {                       // uniform: the whole window is above tau
+        if (threadIdx.x == 0) {
+            sh.above = start + total;
+            sh.hi = lo;
+            sh.lo = lo > kWindowStep ? lo - kWindowStep : 0ull;
+            if (lo == 0ull) sh.done = 2;                // no gains left: the budget does not fit
+        }
+    } else if (cj != 0 && before < budget && budget <= before + (long long)cj) {   // exactly one thread
+        sh.above = before;
+        sh.hi = mx;
+        sh.lo = mn - 1ull;
+        sh.done = (mx == mn) ? 1 : 0;
+    }
+    __syncthreads();
+}
 
 template <class Src, bool kSolo>
 __global__ __launch_bounds__(kBig) void k_select_pass(Src src, long long n, long long budget, long long limit,
                                                       AllocHeader* __restrict__ hdr,
                                                       SelectBins* __restrict__ bins) {
     __shared__ SelectShared sh;
-    if (threadIdx.x == 0) { sh.lo = hdr->lo_cur; sh.hi = hdr->hi_cur; sh.done = (int)hdr->done; sh.last = 1; }
+    if (threadIdx.x == 0) {
+        sh.lo = hdr->lo_cur; sh.hi = hdr->hi_cur; sh.above = (long long)hdr->above; sh.done = (int)hdr->done;
+        sh.last = 1;
+    }
     __syncthreads();
-    const int iters = kSolo ? kSelectPasses : 1;
+    const int iters = kSolo ? kSoloMaxPasses : 1;
     for (int iter = 0; iter < iters; ++iter) {
         if (sh.done) break;
         const unsigned long long lo = sh.lo, hi = sh.hi;
-        const unsigned long long width = hi - lo;                  // >= 2
-        const int bitlen = 64 - __clzll((long long)(width - 1));    // bits of width - 1
+        const unsigned long long width = hi - lo;                  // >= 1
+        const int bitlen = width > 1 ? 64 - __clzll((long long)(width - 1)) : 0;   // bits of width - 1
         const int shift = bitlen > 8 ? bitlen - 8 : 0;             // (width - 1) >> shift < kBins
         if (threadIdx.x < kBins) { sh.cnt[threadIdx.x] = 0; sh.vmax[threadIdx.x] = 0; sh.vmin_inv[threadIdx.x] = 0; }
         __syncthreads();
 
-        long long above = 0;
         const long long stride = (long long)gridDim.x * kBig;
         const int lane = lane_id();
         // all wavefronts run the same number of rounds, so that the ballots below see whole wavefronts
@@ -859,7 +884,6 @@ __global__ __launch_bounds__(kBig) void k_select_pass(Src src, long long n, long
             bool active = i < n && k < limit && gb > lo;
             while (__ballot(active)) {
                 const bool inside = active && gb <= hi;
-                if (active && !inside) above += 1;
                 // lanes that hold the same gain (common under a shared prior) tally once:
                 // up to 8 distinct gains per step through a leader, the rest lane by lane
                 unsigned long long pending = __ballot(inside);
@@ -869,17 +893,18 @@ __global__ __launch_bounds__(kBig) void k_select_pass(Src src, long long n, long
                     const unsigned long long same = __ballot(inside && gb == v);
                     if (lane == leader) {
                         const int j = (int)((v - lo - 1ull) >> shift);
+                        // no result is used: the three updates are issued without a wait
                         atomicAdd(&sh.cnt[j], (unsigned long long)__popcll(same));
-                        if (v > sh.vmax[j]) atomicMax(&sh.vmax[j], v);
-                        if (~v > sh.vmin_inv[j]) atomicMax(&sh.vmin_inv[j], ~v);
+                        atomicMax(&sh.vmax[j], v);
+                        atomicMax(&sh.vmin_inv[j], ~v);
                     }
                     pending &= ~same;
                 }
                 if (inside && ((pending >> lane) & 1ull)) {
                     const int j = (int)((gb - lo - 1ull) >> shift);
                     atomicAdd(&sh.cnt[j], 1ull);
-                    if (gb > sh.vmax[j]) atomicMax(&sh.vmax[j], gb);
-                    if (~gb > sh.vmin_inv[j]) atomicMax(&sh.vmin_inv[j], ~gb);
+                    atomicMax(&sh.vmax[j], gb);
+                    atomicMax(&sh.vmin_inv[j], ~gb);
                 }
                 if (active) {
                     g = gain_next(g, b, s, lf);
@@ -889,67 +914,108 @@ __global__ __launch_bounds__(kBig) void k_select_pass(Src src, long long n, long
                     active = k < limit && gb > lo;
                 }
             }
-            if (above > budget) above = budget;   // only the comparison with the budget matters
         }
-        above = wave_sum<long long>(above);
-        if (lane_id() == 0) sh.red[wave_id()] = above;
-        __syncthreads();
-        long long start = 0;
-#pragma unroll
-        for (int i = 0; i < kBigWaves; ++i) start += sh.red[i];
-        if (start > budget) start = budget;
-
+        __syncthreads();   // the workgroup's tallies are complete
+        if (!kSolo) {
+            // this workgroup's tallies to its own slot (all of them: the slot holds no state);
+            // k_select_move adds the slots up after this kernel has ended
+            SelectBins* mine = bins + blockIdx.x;
+            if (threadIdx.x < kBins) {
+                const unsigned long long c0 = sh.cnt[threadIdx.x];
+                mine->cnt[threadIdx.x] = c0 > (unsigned long long)budget ? (unsigned long long)budget : c0;
+                mine->vmax[threadIdx.x] = sh.vmax[threadIdx.x];
+                mine->vmin_inv[threadIdx.x] = sh.vmin_inv[threadIdx.x];
+            }
+            return;
+        }
         // tallies of interval j = kBins - 1 - thread: thread 0 owns the top interval
         const int j = kBins - 1 - (int)threadIdx.x;
         unsigned long long cj = 0, mx = 0, mn = 0;
-        if (!kSolo) {
-            if (threadIdx.x < kBins && sh.cnt[j]) {
-                const unsigned long long c0 = sh.cnt[j];
-                atomicAdd(&bins->cnt[j], c0 > (unsigned long long)budget ? (unsigned long long)budget : c0);
-                atomicMax(&bins->vmax[j], sh.vmax[j]);
-                atomicMax(&bins->vmin_inv[j], sh.vmin_inv[j]);
-            }
-            if (threadIdx.x == 0 && start) atomicAdd(&hdr->above, (unsigned long long)start);
-            __threadfence();
-            __syncthreads();
-            if (threadIdx.x == 0) sh.last = atomicAdd(&hdr->ticket, 1u) == gridDim.x - 1 ? 1 : 0;
-            __syncthreads();
-            if (!sh.last) return;
-            __threadfence();
-            if (threadIdx.x < kBins) {
-                cj = atomicAdd(&bins->cnt[j], 0ull);
-                mx = atomicMax(&bins->vmax[j], 0ull);
-                mn = ~atomicMax(&bins->vmin_inv[j], 0ull);
-                bins->cnt[j] = 0ull;
-                bins->vmax[j] = 0ull;
-                bins->vmin_inv[j] = 0ull;
-            }
-            start = (long long)atomicAdd(&hdr->above, 0ull);
-        } else if (threadIdx.x < kBins) {
+        if (threadIdx.x < kBins) {
             cj = sh.cnt[j];
             mx = sh.vmax[j];
             mn = ~sh.vmin_inv[j];
         }
-        if (cj > (unsigned long long)budget) cj = (unsigned long long)budget;
-        __syncthreads();                                     // sh.red is reused
-        // pairs in higher intervals: exclusive prefix over the threads
-        const long long incl = wave_incl_scan<long long>((long long)cj);
-        if (lane_id() == kWave - 1) sh.red[wave_id()] = incl;
-        __syncthreads();
-        long long before = start + incl - (long long)cj;
-        for (int i = 0; i < wave_id(); ++i) before += sh.red[i];
-        if (cj != 0 && before < budget && budget <= before + (long long)cj) {   // exactly one thread
-            sh.hi = mx;
-            sh.lo = mn - 1ull;
-            sh.done = (mx == mn) ? 1 : 0;
-        }
-        __syncthreads();
+        move_bracket(sh, cj, mx, mn, budget);
     }
     if (threadIdx.x == 0) {
         hdr->lo_cur = sh.lo;
         hdr->hi_cur = sh.hi;
+        hdr->above = (unsigned long long)sh.above;
         hdr->done = (unsigned)sh.done;
-        if (!kSolo) { hdr->above = 0ull; hdr->ticket = 0u; }
+    }
+}
+
+// ----------------------------------------------------------------------------------
+// Between two grid-wide search passes (one workgroup): adds up the workgroups' interval
+// tallies and moves the bracket.  A kernel of its own rather than "the workgroup that
+// finishes last": the device-wide fences that pattern needs (write back and invalidate
+// the L2 of every die) cost several times the pass itself on this part.
+// first != 0: starts the search from the largest gain instead (window (hi / 16, hi]).
+// ----------------------------------------------------------------------------------
+__global__ __launch_bounds__(kBig) void k_select_move(int nb, long long budget, int first,
+                                                      AllocHeader* __restrict__ hdr,
+                                                      const SelectBins* __restrict__ bins) {
+    __shared__ SelectShared sh;
+    if (first) {
+        if (threadIdx.x == 0) {
+            const unsigned long long all_hi = hdr->hi;
+            hdr->hi_cur = all_hi;
+            hdr->lo_cur = all_hi > kWindowStep ? all_hi - kWindowStep : 0ull;
+            hdr->above = 0ull;
+            hdr->done = 0u;
+        }
+        return;
+    }
+    if (hdr->done) return;
+    if (threadIdx.x == 0) { sh.lo = hdr->lo_cur; sh.hi = hdr->hi_cur; sh.above = (long long)hdr->above; sh.done = 0; }
+    if (threadIdx.x < kBins) { sh.cnt[threadIdx.x] = 0; sh.vmax[threadIdx.x] = 0; sh.vmin_inv[threadIdx.x] = 0; }
+    __syncthreads();
+    // Counts first: thread (q, i) adds interval i of every fourth workgroup, the four partial
+    // sums meet in LDS.  The largest and smallest gain are only needed for the one interval
+    // in which the budget is reached, so they are gathered for that interval alone.
+    static_assert(kBig == 4 * kBins, "four threads per interval");
+    const int bin = (int)threadIdx.x & (kBins - 1), quarter = (int)threadIdx.x / kBins;
+    unsigned long long c1 = 0;
+#pragma unroll 16
+    for (int wg = quarter; wg < nb; wg += 4) c1 += bins[wg].cnt[bin];
+    atomicAdd(&sh.cnt[bin], c1);
+    __syncthreads();
+    const int j = kBins - 1 - (int)threadIdx.x;
+    unsigned long long cj = threadIdx.x < kBins ? sh.cnt[j] : 0ull;
+    if (cj > (unsigned long long)budget) cj = (unsigned long long)budget;
+    // the interval that holds the budget-th pair, if this window holds it at all
+    const long long incl = wave_incl_scan<long long>((long long)cj);
+    if (lane_id() == kWave - 1) sh.red[wave_id()] = incl;
+    if (threadIdx.x == 0) sh.last = -1;
+    __syncthreads();
+    long long before = sh.above + incl - (long long)cj;
+    for (int i = 0; i < wave_id(); ++i) before += sh.red[i];
+    if (cj != 0 && before < budget && budget <= before + (long long)cj) sh.last = j;   // at most one thread
+    __syncthreads();
+    const int hit = sh.last;
+    if (hit >= 0) {
+        unsigned long long m1 = 0, n1 = 0;
+        for (int wg = (int)threadIdx.x; wg < nb; wg += kBig) {
+            const unsigned long long mm = bins[wg].vmax[hit], nn = bins[wg].vmin_inv[hit];
+            m1 = mm > m1 ? mm : m1;
+            n1 = nn > n1 ? nn : n1;
+        }
+        atomicMax(&sh.vmax[hit], m1);
+        atomicMax(&sh.vmin_inv[hit], n1);
+    }
+    __syncthreads();
+    unsigned long long mx = 0, mn = 0;
+    if (threadIdx.x < kBins) {
+        mx = sh.vmax[j];
+        mn = ~sh.vmin_inv[j];
+    }
+    move_bracket(sh, cj, mx, mn, budget);
+    if (threadIdx.x == 0) {
+        hdr->lo_cur = sh.lo;
+        hdr->hi_cur = sh.hi;
+        hdr->above = (unsigned long long)sh.above;
+        hdr->done = (unsigned)sh.done;
     }
 }
 
@@ -1025,7 +1091,6 @@ __global__ __launch_bounds__(kThreads) void k_bisect_scan(int nb, long long budg
             summary->tie_units = r;
             summary->tie_prompts = tcarry;
         }
-        hdr->lo_inv = 0ull;
         hdr->hi = 0ull;
         hdr->above = 0ull;
         hdr->ticket = 0u;
@@ -1194,14 +1259,18 @@ static int run_bisect(const Src& src, const CommonArgs& a, const Plan& p, const 
     if (a.budget > 0) {
         long long blocks = (n + kBig - 1) / kBig;
         if (blocks > kMaxBlocks) blocks = kMaxBlocks;
-        const long long w_steps = (a.budget + n - 1) / n;
-        hipLaunchKernelGGL((k_select_bracket<Src>), dim3((unsigned)blocks), dim3(kBig), 0, a.stream, src, n,
-                           w_steps, w.header, a.dev_status);
+        hipLaunchKernelGGL((k_select_top<Src>), dim3((unsigned)blocks), dim3(kBig), 0, a.stream, src, n, w.header,
+                           a.dev_status);
+        hipLaunchKernelGGL(k_select_move, dim3(1), dim3(kBig), 0, a.stream, (int)blocks, (long long)a.budget, 1,
+                           w.header, w.bins);
         // small batches go straight to the single-workgroup search: fewer launches than passes
         const int parallel = n > kSoloMaxPrompts ? kParallelPasses : 0;
-        for (int pass = 0; pass < parallel; ++pass)
+        for (int pass = 0; pass < parallel; ++pass) {
             hipLaunchKernelGGL((k_select_pass<Src, false>), dim3((unsigned)blocks), dim3(kBig), 0, a.stream, src,
                                n, (long long)a.budget, limit, w.header, w.bins);
+            hipLaunchKernelGGL(k_select_move, dim3(1), dim3(kBig), 0, a.stream, (int)blocks, (long long)a.budget, 0,
+                               w.header, w.bins);
+        }
         hipLaunchKernelGGL((k_select_pass<Src, true>), dim3(1), dim3(kBig), 0, a.stream, src, n,
                            (long long)a.budget, limit, w.header, w.bins);
     }

@@ -208,8 +208,8 @@ __device__ bool threshold_by_walks(const Src& src, long long lo_i, long long hi_
         if (sh.done) break;   // uniform: written before the barrier that ends a pass
         const unsigned long long lo = sh.lo, hi_cur = sh.hi;
         const long long above = sh.above;
-        const unsigned long long width = hi_cur - lo;                 // >= 2
-        const int bitlen = 64 - __clzll((long long)(width - 1));
+        const unsigned long long width = hi_cur - lo;                 // >= 1
+        const int bitlen = width > 1 ? 64 - __clzll((long long)(width - 1)) : 0;
         const int shift = bitlen > 8 ? bitlen - 8 : 0;                // (width - 1) >> shift < kBins
         static_assert(kBins == kShardThreads, "one interval per thread");
         sh.cnt[threadIdx.x] = 0; sh.vmax[threadIdx.x] = 0; sh.vmin_inv[threadIdx.x] = 0;
