@@ -24,6 +24,13 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
 
+# HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE (KiB per dispatch, scaled by what
+# the same counters read for a plain device copy of known size); the figures and the commands
+# are in profiles/hbm_traffic_large_alloc_large_bcast.txt.  Set to None when a kernel named
+# there changes.
+TRAFFIC_BROADCAST_BYTES = 711094374     # k_row_desc + k_token_fill, large_bcast
+TRAFFIC_ALLOCATE_BYTES = 25560678       # k_class_hist + k_class_write, large_alloc
+
 
 def ensure_library():
     from paper_2605_07114_amd import build, hora
@@ -89,6 +96,37 @@ def cpu_baseline(wl, oracle, w_alloc, a_alloc, bcast_inputs):
     dt = time.perf_counter() - t0
     out["broadcast_GBps"] = buf.size * 8 / dt / 1e9
     out["broadcast_sample"] = f"first {n_resp} responses of large_bcast, {buf.size} tokens, binary64 stores"
+    return out
+
+
+def other_paths(torch, hora, wl, sess, a1, c1, w1, delta1, util1, goff1, ws, reps):
+    """Timings of the entry points next to the headline path (HIP events, mean of `reps` calls)."""
+    def mean_us(fn):
+        return per_launch_events(torch, fn, reps, 2)[0] * 1e6
+
+    out = {}
+    # per-prompt posteriors (threshold search by bisection passes) on the large-allocation inputs
+    alpha = torch.from_numpy(1.0 + a1.c.astype(np.float64)).to("cuda:0")
+    beta = torch.from_numpy(1.0 + w1.g0 - a1.c.astype(np.float64)).to("cuda:0")
+    us = mean_us(lambda: hora.hora_allocate_posterior(alpha, beta, w1.g0, w1.budget, delta1, sess.dev_status, ws,
+                                                      util=util1, group_off=goff1))
+    out["allocate_posterior_large_alloc"] = {"us_per_call": us, "prompts_per_s": w1.n / us * 1e6}
+    # sharded Phase B: the paper's own step (4 shards of 15 prompts) and the same shard shape at scale
+    for w, n_shards in ((wl.PAPER_STEP, wl.PAPER_STEP_SHARDS), (wl.SHARDED_LARGE, wl.SHARDED_LARGE_SHARDS)):
+        a = wl.phase_a(w)
+        bounds, budgets = wl.equal_shards(w.n, n_shards, w.budget)
+        c = torch.from_numpy(a.c).to("cuda:0")
+        so, sb = torch.from_numpy(bounds).to("cuda:0"), torch.from_numpy(budgets).to("cuda:0")
+        delta = torch.empty(w.n, dtype=torch.int32, device="cuda:0")
+        util = torch.empty(w.n, dtype=torch.float64, device="cuda:0")
+        goff = torch.empty(w.n + 1, dtype=torch.int32, device="cuda:0")
+        sws = torch.zeros(hora.hora_allocate_sharded_workspace_bytes(n_shards), dtype=torch.uint8, device="cuda:0")
+        us = mean_us(lambda: hora.hora_allocate_sharded(c, w.g0, so, sb, delta, sess.dev_status, sws, util=util,
+                                                        group_off=goff))
+        assert int(delta.sum()) == w.budget
+        out[f"allocate_sharded_{w.name}"] = {"shards": n_shards, "prompts": w.n, "us_per_call": us,
+                                             "prompts_per_s": w.n / us * 1e6}
+    assert sess.status() == 0
     return out
 
 
@@ -170,6 +208,8 @@ def main():
     bcast_bytes = 4 * n_tok + n_resp * (8 + 4)       # float stores; offsets and advantages in
     bcast_gbs = bcast_bytes / bc_mean / 1e9
 
+    extras = other_paths(torch, hora, wl, sess, a1, c1, w1, delta1, util1, goff1, ws, max(steps // 10, 5))
+
     result = {
         "metric": "prompts allocated/s at N=1M; advantage broadcast GB/s as % of HBM peak",
         "value": w1.n / (wall1 / steps),
@@ -201,26 +241,27 @@ def main():
             "tokens_per_s_whole_path": 2 * n_tok / (wall2 / steps2),
         },
         "roofline": {
-            "kernel": "k_row_index + k_token_fill<float,float,int64> (large_bcast)",
+            "kernel": "k_row_desc + k_token_fill<float,float,int64> (large_bcast)",
             "bound": "hbm",
             "achieved": bcast_gbs,
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": bcast_gbs / HBM_PEAK_GBS,
-            "traffic": None,
+            "traffic": TRAFFIC_BROADCAST_BYTES,
             "bytes_per_launch": bcast_bytes,
         },
         "roofline_allocate": {
-            "kernel": "k_class_hist + k_class_solve + k_alloc_write (large_alloc)",
+            "kernel": "k_class_hist + k_class_write (large_alloc)",
             "bound": "hbm",
             "achieved": alloc_bytes / (ev1 / steps) / 1e9,
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": alloc_bytes / (ev1 / steps) / 1e9 / HBM_PEAK_GBS,
-            "traffic": None,
+            "traffic": TRAFFIC_ALLOCATE_BYTES,
             "bytes_per_launch": alloc_bytes,
         },
     }
+    result["other_paths"] = extras
     if not args.no_cpu_baseline:
         from oracle import hora_oracle
         hora_oracle.build()
