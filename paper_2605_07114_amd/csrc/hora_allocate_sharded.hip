@@ -31,6 +31,7 @@ namespace hora {
 constexpr int kShardThreads = 256;
 constexpr int kShardWaves = kShardThreads / kWave;
 constexpr int kPrefixThreads = 1024;
+constexpr int kPrefixChunk = 8 * kPrefixThreads;   // shards per prefix-sum workgroup
 constexpr unsigned kShardTiedBit = 0x80000000u;
 constexpr unsigned long long kWindowStep = 4ull << 52;   // 4 exponent steps: a factor 16 in value
 // Windows from the largest gain down to zero (at most 2047 / 4), plus the narrowing passes
@@ -46,28 +47,72 @@ struct ShardTableKey {
     unsigned long long magic;
     double alpha0, beta0;
     int g0, depth;
-    unsigned long long pad[28];
+    int usable, pad0;
+    unsigned long long pad[27];
 };
 static_assert(sizeof(ShardTableKey) == 256, "key size");
 constexpr unsigned long long kTableMagic = 0x484f52415461626cull;
 constexpr int kShardMaxClasses = HORA_CLASS_MAX_G0 + 1;
+constexpr int kLevelBlock = 64;          // sorted levels per coarse block (one wavefront evaluates a block)
+constexpr int kMaxCoarse = kShardTableCap / kLevelBlock;
+constexpr int kWaveShardMax = 1024;      // larger shards go to the workgroup-per-shard kernel
+constexpr int kWaveShardMeanMax = 256;   // mean shard size up to which the wavefront-per-shard kernel is used
 
-// Set-up.  Workgroup 0: exclusive prefix sums of the shard budgets (negative budgets count
-// as 0; the shard's own workgroup reports them); thread t owns a contiguous run of shards.
+// u16 entries per sorted level (the per-class counts of one level are one 32- or 128-byte row)
+__host__ __device__ inline int level_stride(int nc) { return nc <= 16 ? 16 : 64; }
+
+struct ShardWorkspace {
+    ShardTableKey* key;
+    double* gain_table;              // [nc][depth]  M_c(l)
+    double* surv_table;              // [nc][depth]  E_c(l)
+    unsigned long long* level_bits;  // [nc * usable depth] all table gains, sorted descending
+    unsigned short* level_kge;       // [levels][stride]: #{l : M_c(l) >= that level's gain}
+    int* todo;                       // [0]: number of shards left to the workgroup-per-shard kernel; then their ids
+    long long* prefix;               // [n_shards] budget given to earlier shards
+    size_t bytes;
+};
+
+__host__ inline ShardWorkspace carve_shards(void* base, int64_t n_shards) {
+    ShardWorkspace w;
+    char* ptr = (char*)base;
+    size_t off = 0;
+    const size_t ns = (size_t)(n_shards > 0 ? n_shards : 1);
+    w.key = (ShardTableKey*)(ptr + off); off += sizeof(ShardTableKey);
+    w.gain_table = (double*)(ptr + off); off += (size_t)kShardTableCap * sizeof(double);
+    w.surv_table = (double*)(ptr + off); off += (size_t)kShardTableCap * sizeof(double);
+    w.level_bits = (unsigned long long*)(ptr + off); off += (size_t)kShardTableCap * sizeof(unsigned long long);
+    w.level_kge = (unsigned short*)(ptr + off); off += (size_t)kShardTableCap * 64 * sizeof(unsigned short);
+    w.prefix = (long long*)(ptr + off); off += (ns * sizeof(long long) + 255) & ~(size_t)255;
+    w.todo = (int*)(ptr + off); off += ((ns + 1) * sizeof(int) + 255) & ~(size_t)255;
+    w.bytes = off;
+    return w;
+}
+
+// Set-up.  Workgroup 0 resets the list of left-over shards.  Workgroups 2, 3, ...: exclusive
+// prefix sums of the shard budgets, kPrefixChunk shards each (negative budgets count as 0; the
+// shard's own workgroup reports them).
 // Workgroup 1: the gain and survival sequences of the G0+1 classes, one thread per class
-// (Sec. 3.2 stable update; App. A), `depth` entries each.
+// (Sec. 3.2 stable update; App. A), `depth` entries each; then all gains l < usable of all
+// classes sorted descending into "levels": the position of a gain is the number of gains
+// above it plus, among equal gains, the number of lower classes that hold it, and every
+// level carries, per class, the number of that class's gains >= the level.  With these a
+// shard finds its threshold by a search over levels: count_ge(level) = sum_c n_c * kge_c.
 __global__ __launch_bounds__(kPrefixThreads) void k_shard_setup(long long n_shards,
                                                                 const long long* __restrict__ shard_budget,
                                                                 long long* __restrict__ prefix, int g0,
                                                                 double alpha0, double beta0, int depth,
-                                                                ShardTableKey* __restrict__ key,
+                                                                int usable, ShardTableKey* __restrict__ key,
                                                                 double* __restrict__ gain_table,
-                                                                double* __restrict__ surv_table) {
-    __shared__ long long s_tot[kPrefixThreads / kWave];
+                                                                double* __restrict__ surv_table,
+                                                                unsigned long long* __restrict__ level_bits,
+                                                                unsigned short* __restrict__ level_kge,
+                                                                int* __restrict__ todo) {
+    __shared__ unsigned long long s_raw[kShardTableCap];   // workgroup 0: wavefront totals; workgroup 1: the gains
+    long long* s_tot = reinterpret_cast<long long*>(s_raw);
     if (blockIdx.x == 1) {
         if (depth == 0) return;
         const bool cached = key->magic == kTableMagic && key->alpha0 == alpha0 && key->beta0 == beta0 &&
-                            key->g0 == g0 && key->depth == depth;
+                            key->g0 == g0 && key->depth == depth && key->usable == usable;
         if (cached) return;   // uniform: every thread reads the same key
         __syncthreads();      // all threads have read the key before thread 0 clears it
         if (threadIdx.x == 0) key->magic = 0ull;
@@ -80,38 +125,82 @@ __global__ __launch_bounds__(kPrefixThreads) void k_shard_setup(long long n_shar
             for (int l = 0; l < depth; ++l) {
                 gain_table[cls * depth + l] = m;
                 surv_table[cls * depth + l] = e;
+                s_raw[cls * depth + l] = gain_bits(m);
                 e = surv_next(e, b, s, lf);
                 m = gain_next(m, b, s, lf);
                 lf += 1.0;
             }
         }
+        __syncthreads();
+        // levels: one entry (class, l) at a time per thread; two rounds of searches, the first
+        // for the entry's position, the second to write the per-class counts there
+        const int nc = g0 + 1;
+        const int stride = level_stride(nc);
+        for (int e = (int)threadIdx.x; e < nc * usable; e += kPrefixThreads) {
+            const int cls = e / usable, l = e - cls * usable;
+            const unsigned long long v = s_raw[cls * depth + l];
+            int pos_of = 0;
+            for (int round = 0; round < 2; ++round) {
+                int rank = 0, order = 0;
+                for (int c2 = 0; c2 < nc; ++c2) {
+                    const unsigned long long* row = s_raw + c2 * depth;
+                    int lo = 0, hi = usable;          // first index whose gain is <= v
+                    while (lo < hi) {
+                        const int mid = (lo + hi) >> 1;
+                        if (row[mid] > v) lo = mid + 1; else hi = mid;
+                    }
+                    const int eq = (lo < usable && row[lo] == v) ? 1 : 0;
+                    rank += lo;
+                    if (c2 < cls) order += eq;
+                    if (round == 1) level_kge[(long long)pos_of * stride + c2] = (unsigned short)(lo + eq);
+                }
+                pos_of = rank + order;
+            }
+            level_bits[pos_of] = v;
+        }
         __threadfence();
         __syncthreads();
         if (threadIdx.x == 0) {
-            key->alpha0 = alpha0; key->beta0 = beta0; key->g0 = g0; key->depth = depth;
+            key->alpha0 = alpha0; key->beta0 = beta0; key->g0 = g0; key->depth = depth; key->usable = usable;
             __threadfence();
             key->magic = kTableMagic;
         }
         return;
     }
-    if (!prefix) return;
-    const long long per = (n_shards + kPrefixThreads - 1) / kPrefixThreads;
-    const long long lo = (long long)threadIdx.x * per;
-    const long long hi = lo + per < n_shards ? lo + per : n_shards;
-    long long sum = 0;
-    for (long long s = lo; s < hi; ++s) {
-        const long long b = shard_budget[s];
-        sum += b > 0 ? b : 0;
+    if (blockIdx.x == 0 && threadIdx.x == 0) todo[0] = 0;
+    if (!prefix || blockIdx.x == 0) return;
+    // Workgroup 2 + k: chunk k of kPrefixChunk shards.  It first adds up every budget before
+    // its chunk (all loads independent of one another), then scans its own chunk: thread t
+    // owns 8 consecutive shards (contiguous 64-byte loads and stores).
+    constexpr int kPer = kPrefixChunk / kPrefixThreads;
+    const long long base = (long long)(blockIdx.x - 2) * kPrefixChunk;
+    long long earlier = 0;
+    for (long long i = threadIdx.x; i < base; i += kPrefixThreads) {
+        const long long v = shard_budget[i];
+        earlier += v > 0 ? v : 0;
     }
+    const long long first = base + (long long)threadIdx.x * kPer;
+    long long b[kPer];
+    long long sum = 0;
+#pragma unroll
+    for (int k = 0; k < kPer; ++k) {
+        const long long v = first + k < n_shards ? shard_budget[first + k] : 0;
+        b[k] = v > 0 ? v : 0;
+        sum += b[k];
+    }
+    earlier = wave_sum<long long>(earlier);
     const long long incl = wave_incl_scan<long long>(sum);
-    if (lane_id() == kWave - 1) s_tot[wave_id()] = incl;
+    if (lane_id() == kWave - 1) { s_tot[wave_id()] = incl; s_tot[kPrefixThreads / kWave + wave_id()] = earlier; }
     __syncthreads();
     long long run = incl - sum;
-    for (int w = 0; w < wave_id(); ++w) run += s_tot[w];
-    for (long long s = lo; s < hi; ++s) {
-        prefix[s] = run;
-        const long long b = shard_budget[s];
-        run += b > 0 ? b : 0;
+    for (int w = 0; w < kPrefixThreads / kWave; ++w) {
+        if (w < wave_id()) run += s_tot[w];
+        run += s_tot[kPrefixThreads / kWave + w];
+    }
+#pragma unroll
+    for (int k = 0; k < kPer; ++k) {
+        if (first + k < n_shards) prefix[first + k] = run;
+        run += b[k];
     }
 }
 
@@ -384,19 +473,15 @@ __device__ bool threshold_by_table(const Src& src, long long lo_i, long long hi_
 
 // kOff: 0 no offsets, 1 int32 offsets, 2 int64 offsets.
 template <class Src, int kOff>
-__global__ __launch_bounds__(kShardThreads) void k_shard_allocate(Src src, long long n, int g0, long long n_shards,
-                                                                  const long long* __restrict__ shard_off,
-                                                                  const long long* __restrict__ shard_budget,
-                                                                  int cap, const long long* __restrict__ prefix,
-                                                                  int depth, const double* __restrict__ gain_table,
-                                                                  const double* __restrict__ surv_table,
-                                                                  int32_t* __restrict__ delta,
-                                                                  double* __restrict__ util,
-                                                                  void* __restrict__ group_off,
-                                                                  hora_alloc_summary* __restrict__ summary,
-                                                                  int32_t* dev_status) {
+__device__ void shard_by_workgroup(const Src& src, long long shard, long long n, int g0, long long n_shards,
+                                   const long long* __restrict__ shard_off,
+                                   const long long* __restrict__ shard_budget, int cap,
+                                   const long long* __restrict__ prefix, int depth,
+                                   const double* __restrict__ gain_table, const double* __restrict__ surv_table,
+                                   int32_t* __restrict__ delta, double* __restrict__ util,
+                                   void* __restrict__ group_off, hora_alloc_summary* __restrict__ summary,
+                                   int32_t* dev_status) {
     __shared__ ShardShared sh;
-    const long long shard = blockIdx.x;
     const long long lo_i = shard_off[shard], hi_i = shard_off[shard + 1];
     const long long budget = shard_budget[shard];
 
@@ -505,6 +590,302 @@ __global__ __launch_bounds__(kShardThreads) void k_shard_allocate(Src src, long 
     }
 }
 
+// One workgroup per shard.
+template <class Src, int kOff>
+__global__ __launch_bounds__(kShardThreads) void k_shard_allocate(Src src, long long n, int g0, long long n_shards,
+                                                                  const long long* __restrict__ shard_off,
+                                                                  const long long* __restrict__ shard_budget,
+                                                                  int cap, const long long* __restrict__ prefix,
+                                                                  int depth, const double* __restrict__ gain_table,
+                                                                  const double* __restrict__ surv_table,
+                                                                  int32_t* __restrict__ delta,
+                                                                  double* __restrict__ util,
+                                                                  void* __restrict__ group_off,
+                                                                  hora_alloc_summary* __restrict__ summary,
+                                                                  int32_t* dev_status) {
+    shard_by_workgroup<Src, kOff>(src, (long long)blockIdx.x, n, g0, n_shards, shard_off, shard_budget, cap, prefix,
+                                  depth, gain_table, surv_table, delta, util, group_off, summary, dev_status);
+}
+
+// The shards the wavefront-per-shard kernel left over (todo[0] of them, ids from todo[1]):
+// a fixed number of workgroups takes them in turn.
+template <class Src, int kOff>
+__global__ __launch_bounds__(kShardThreads) void k_shard_allocate_todo(Src src, long long n, int g0,
+                                                                       long long n_shards,
+                                                                       const long long* __restrict__ shard_off,
+                                                                       const long long* __restrict__ shard_budget,
+                                                                       int cap, const long long* __restrict__ prefix,
+                                                                       int depth,
+                                                                       const double* __restrict__ gain_table,
+                                                                       const double* __restrict__ surv_table,
+                                                                       int32_t* __restrict__ delta,
+                                                                       double* __restrict__ util,
+                                                                       void* __restrict__ group_off,
+                                                                       hora_alloc_summary* __restrict__ summary,
+                                                                       const int* __restrict__ todo,
+                                                                       int32_t* dev_status) {
+    const int count = todo[0];
+    for (int idx = (int)blockIdx.x; idx < count; idx += (int)gridDim.x) {
+        shard_by_workgroup<Src, kOff>(src, (long long)todo[1 + idx], n, g0, n_shards, shard_off, shard_budget, cap,
+                                      prefix, depth, gain_table, surv_table, delta, util, group_off, summary,
+                                      dev_status);
+        __syncthreads();   // the LDS state is reused by the next shard
+    }
+}
+
+// ----------------------------------------------------------------------------------
+// Wavefront per shard (shared prior, small shards).  A workgroup of four wavefronts takes
+// four shards; nothing is shared between them but the coarse rows in LDS.
+//  1. histogram of c: lane k counts class k (wavefront ballots);
+//  2. coarse search: lane q evaluates count_ge of the last level of block q (the coarse
+//     rows, one per 64 levels, are in LDS) and the first block that reaches the budget is
+//     taken; fine search: lane t evaluates level 64 q + t of that block (one 32- or
+//     128-byte row per lane from global memory).  tau is the first level whose count_ge
+//     reaches the budget; the level before it gives the gains above tau per class;
+//  3. outputs with the tie pass inside the wavefront (ballot + mbcnt ranks, DPP prefix sums
+//     for the offsets).
+// Two dependent global loads (the shard's c, then the block's rows) plus the per-class
+// look-ups, instead of several passes with workgroup barriers.  A shard the table cannot
+// settle (deeper than the table, more than kWaveShardMax prompts) is put on a list for the
+// workgroup-per-shard code, which a second kernel runs afterwards.
+// ----------------------------------------------------------------------------------
+struct WaveScratch {          // per wavefront, LDS
+    int k[kShardMaxClasses];
+    int tied[kShardMaxClasses];
+    double e[kShardMaxClasses];
+    unsigned rows[2][8];      // the per-class counts of level tau and of the level before (16 classes or fewer)
+};
+
+template <int kOff>
+__global__ __launch_bounds__(kShardThreads) void k_shard_allocate_waves(
+    CountsSource src, long long n, long long n_shards, const long long* __restrict__ shard_off,
+    const long long* __restrict__ shard_budget, int cap, const long long* __restrict__ prefix, int depth, int usable,
+    const double* __restrict__ surv_table, const unsigned long long* __restrict__ level_bits,
+    const unsigned short* __restrict__ level_kge, int* __restrict__ todo, int32_t* __restrict__ delta,
+    double* __restrict__ util, void* __restrict__ group_off, hora_alloc_summary* __restrict__ summary,
+    int32_t* dev_status) {
+    __shared__ unsigned short s_coarse[kMaxCoarse * 64];
+    __shared__ WaveScratch s_wave[kShardWaves];
+    const int g0 = src.g0;
+    const int nc = g0 + 1;
+    const int stride = level_stride(nc);
+    const int levels = nc * usable;
+    const int n_coarse = (levels + kLevelBlock - 1) / kLevelBlock;
+    // the shard's bounds and budget are requested first, so that they travel while the coarse
+    // rows are staged (coarse row q = the last level of block q)
+    const int lane = lane_id();
+    const long long shard = (long long)blockIdx.x * kShardWaves + wave_id();
+    const bool live = shard < n_shards;
+    const long long lo_i = live ? shard_off[shard] : 0, hi_i = live ? shard_off[shard + 1] : 0;
+    const long long budget = live ? shard_budget[shard] : 0;
+    for (int idx = (int)threadIdx.x; idx < n_coarse * stride; idx += kShardThreads) {
+        const int q = idx / stride, k = idx - q * stride;
+        int p = q * kLevelBlock + kLevelBlock - 1;
+        if (p > levels - 1) p = levels - 1;
+        s_coarse[idx] = level_kge[(long long)p * stride + k];
+    }
+    __syncthreads();
+    if (!live) return;
+    WaveScratch& ws = s_wave[wave_id()];
+    bool bad = lo_i < 0 || hi_i < lo_i || hi_i > n || budget < 0 || (shard == 0 && lo_i != 0) ||
+               (shard == n_shards - 1 && hi_i != n);
+    const long long size = bad ? 0 : hi_i - lo_i;
+    bool infeasible = false;
+    if (!bad)
+        infeasible = (budget > 0 && size == 0) || (cap > 0 && budget > size * (long long)cap) ||
+                     (cap <= 0 && budget >= (1ll << 31) - 1) || budget >= (1ll << 52);
+    if (bad || infeasible) {
+        if (lane == 0) report(dev_status, bad ? HORA_ERR_RANGE : HORA_ERR_INFEASIBLE);
+        return;
+    }
+    if (size > kWaveShardMax) {
+        if (lane == 0) todo[1 + atomicAdd(&todo[0], 1)] = (int)shard;
+        return;
+    }
+    const long long limit = cap > 0 ? (budget < cap ? budget : (long long)cap) : budget;
+
+    // ---- 1. histogram: lane k ends up with the number of prompts of class k
+    int n_mine = 0;
+    bool data_bad = false;
+    for (long long i0 = lo_i; i0 < hi_i; i0 += kWave) {
+        const long long i = i0 + lane;
+        int x = -1;
+        if (i < hi_i) {
+            x = src.c[i];
+            if (x < 0 || x > g0) { data_bad = true; x = x < 0 ? 0 : g0; }
+        }
+        for (int k = 0; k < nc; ++k) {
+            const int cnt = __popcll(__ballot(x == k));
+            if (lane == k) n_mine += cnt;
+        }
+    }
+    if (data_bad) report(dev_status, HORA_ERR_RANGE);
+
+    // ---- 2. threshold
+    int k_mine = 0, tied_mine = 0;            // lane c: gains of class c above tau; its next gain equals tau
+    double e_mine = 1.0;                      // lane c: E_c(k_c)
+    long long count_gt = 0, tie_prompts = 0;
+    unsigned long long tau_bits = 0;
+    bool settled = true;
+    if (budget > 0) {
+        // coarse: lane q (and q + 64) evaluates the last level of its block
+        long long cq[2] = {0, 0};
+        for (int k = 0; k < nc; ++k) {
+            const long long nk = (long long)__builtin_amdgcn_readlane(n_mine, k);
+            if (nk == 0) continue;            // uniform
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int q = lane + 64 * h;
+                if (q < n_coarse) cq[h] += nk * (long long)s_coarse[q * stride + k];
+            }
+        }
+        int block = -1;
+        long long before_block = 0;           // count_ge of the last level of the block before
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            if (block < 0) {
+                const unsigned long long reach = __ballot(lane + 64 * h < n_coarse && cq[h] >= budget);
+                if (reach) {
+                    const int first = __ffsll((long long)reach) - 1;
+                    block = first + 64 * h;
+                    if (first > 0) before_block = __shfl(cq[h], first - 1, kWave);
+                    else if (h == 1) before_block = __shfl(cq[0], kWave - 1, kWave);
+                }
+            }
+        }
+        if (block < 0) {
+            settled = false;                  // the table does not reach the budget
+        } else {
+            // fine: lane t evaluates level 64 * block + t
+            const int p = block * kLevelBlock + lane;
+            long long ct = 0;
+            if (p < levels) {
+                const unsigned short* row = level_kge + (long long)p * stride;
+                if (stride == 16) {
+                    const uint4 r0 = *reinterpret_cast<const uint4*>(row);
+                    const uint4 r1 = *reinterpret_cast<const uint4*>(row + 8);
+                    const unsigned w[8] = {r0.x, r0.y, r0.z, r0.w, r1.x, r1.y, r1.z, r1.w};
+#pragma unroll
+                    for (int k = 0; k < 16; ++k) {
+                        const long long nk = (long long)__builtin_amdgcn_readlane(n_mine, k);
+                        const unsigned kge = (k & 1) ? (w[k >> 1] >> 16) : (w[k >> 1] & 0xffffu);
+                        ct += nk * (long long)kge;    // lanes beyond nc hold n = 0
+                    }
+                } else {
+                    for (int k = 0; k < nc; ++k) {
+                        const long long nk = (long long)__builtin_amdgcn_readlane(n_mine, k);
+                        ct += nk * (long long)row[k];
+                    }
+                }
+            }
+            const unsigned long long reach = __ballot(p < levels && ct >= budget);
+            // reach != 0: the block's last level reaches the budget
+            const int t = __ffsll((long long)reach) - 1;
+            const int j = block * kLevelBlock + t;                 // tau = level j
+            count_gt = t > 0 ? __shfl(ct, t - 1, kWave) : before_block;
+            tau_bits = level_bits[j];
+            if (stride == 16) {
+                // the two rows are in the registers of lanes t and t - 1: hand them over through LDS
+                // (level j - 1 of the first lane's block is the coarse row of the block before)
+                const uint4* row = reinterpret_cast<const uint4*>(level_kge + (long long)(p < levels ? p : 0) * stride);
+                if (lane == t || lane == t - 1) {
+                    const uint4 r0 = row[0], r1 = row[1];          // cached: loaded a moment ago
+                    unsigned* dst = ws.rows[lane == t ? 0 : 1];
+                    dst[0] = r0.x; dst[1] = r0.y; dst[2] = r0.z; dst[3] = r0.w;
+                    dst[4] = r1.x; dst[5] = r1.y; dst[6] = r1.z; dst[7] = r1.w;
+                }
+            }
+            if (lane < nc) {
+                int ge, gt;
+                if (stride == 16) {
+                    const unsigned wge = ws.rows[0][lane >> 1];
+                    ge = (int)((lane & 1) ? wge >> 16 : wge & 0xffffu);
+                    if (t > 0) {
+                        const unsigned wgt = ws.rows[1][lane >> 1];
+                        gt = (int)((lane & 1) ? wgt >> 16 : wgt & 0xffffu);
+                    } else {
+                        gt = block > 0 ? (int)s_coarse[(block - 1) * stride + lane] : 0;
+                    }
+                } else {
+                    ge = level_kge[(long long)j * stride + lane];
+                    gt = j > 0 ? level_kge[(long long)(j - 1) * stride + lane] : 0;
+                }
+                k_mine = gt;
+                tied_mine = ge - gt;
+                // every usable gain of a class the shard holds is above tau and the sequence
+                // goes on beyond the table: gains are missing from the counts
+                if (n_mine > 0 && gt == usable && (long long)usable < limit) settled = false;
+                const double a = src.alpha0 + (double)lane, b = src.beta0 + (double)(g0 - lane);
+                double e = surv_table[lane * depth + (gt < depth ? gt : depth - 1)];
+                if (gt == depth) e = surv_next(e, b, a + b, (double)(depth - 1));
+                e_mine = e;
+            }
+            settled = __ballot(!settled) == 0;
+            long long tp = tied_mine ? (long long)n_mine : 0;
+            tie_prompts = wave_sum<long long>(tp);
+        }
+    }
+    if (!settled) {
+        if (lane == 0) todo[1 + atomicAdd(&todo[0], 1)] = (int)shard;
+        return;
+    }
+    const long long r = budget - count_gt;
+    if (summary && lane == 0) {
+        summary[shard].tau = budget > 0 ? __longlong_as_double((long long)tau_bits) : 0.0;
+        summary[shard].count_gt = count_gt;
+        summary[shard].tie_units = r;
+        summary[shard].tie_prompts = tie_prompts;
+    }
+    ws.k[lane] = k_mine;
+    ws.tied[lane] = tied_mine;
+    ws.e[lane] = e_mine;
+    // (same wavefront reads them back below: LDS operations of a wavefront complete in order)
+
+    // ---- 3. outputs
+    const long long off_base = kOff != 0 ? (long long)g0 * lo_i + prefix[shard] : 0;
+    long long rank_base = 0, given = 0;       // tied prompts / units handed out before this tile
+    for (long long i0 = lo_i; i0 < hi_i; i0 += kWave) {
+        const long long i = i0 + lane;
+        const bool in = i < hi_i;
+        int x = 0;
+        if (in) {
+            x = src.c[i];
+            x = x < 0 ? 0 : (x > g0 ? g0 : x);
+        }
+        const int kk = in ? ws.k[x] : 0;
+        const bool td = in && ws.tied[x] != 0;
+        const unsigned long long tied_mask = __ballot(td);
+        const long long rank = rank_base + lanes_below(tied_mask);
+        const bool win = td && rank < r;
+        const int dd = kk + (win ? 1 : 0);
+        const int units = in ? g0 + dd : 0;
+        const long long incl = wave_incl_scan_i64((long long)units);
+        if (in) {
+            delta[i] = dd;
+            if (util) {
+                double e = ws.e[x];
+                if (win) {
+                    const double a = src.alpha0 + (double)x, b = src.beta0 + (double)(g0 - x);
+                    e = surv_next(e, b, a + b, (double)kk);
+                }
+                util[i] = 1.0 - e;
+            }
+            if (kOff != 0) {
+                const long long off = off_base + given + incl - units;
+                if (kOff == 1) {
+                    reinterpret_cast<int32_t*>(group_off)[i] = (int32_t)off;
+                    if (i == n - 1) reinterpret_cast<int32_t*>(group_off)[n] = (int32_t)(off + units);
+                } else {
+                    reinterpret_cast<long long*>(group_off)[i] = off;
+                    if (i == n - 1) reinterpret_cast<long long*>(group_off)[n] = off + units;
+                }
+            }
+        }
+        rank_base += __popcll(tied_mask);
+        given += __shfl(incl, kWave - 1, kWave);
+    }
+}
+
 __global__ void k_store_zero_offset(void* group_off, int off64) {
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         if (off64) *reinterpret_cast<long long*>(group_off) = 0;
@@ -512,13 +893,7 @@ __global__ void k_store_zero_offset(void* group_off, int off64) {
     }
 }
 
-static size_t prefix_bytes(int64_t n_shards) {
-    return (((size_t)(n_shards > 0 ? n_shards : 1) * sizeof(long long)) + 255) & ~(size_t)255;
-}
-// table key, the gain and the survival table, then the prefix sums
-static size_t sharded_workspace_bytes(int64_t n_shards) {
-    return sizeof(ShardTableKey) + 2 * (size_t)kShardTableCap * sizeof(double) + prefix_bytes(n_shards);
-}
+static size_t sharded_workspace_bytes(int64_t n_shards) { return carve_shards(nullptr, n_shards).bytes; }
 
 // Gains per class in the table: a power of two, as many as fit; no more than a cap asks for.
 static int table_depth(int g0, int32_t delta_max) {
@@ -567,23 +942,47 @@ extern "C" int hora_allocate_sharded(int64_t n, int32_t g0, const int32_t* c, do
     if (n > 0 && (!c || !delta)) return HORA_ERR_INVALID_ARG;
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255)) return HORA_ERR_WORKSPACE;
     if (workspace_bytes < sharded_workspace_bytes(n_shards)) return HORA_ERR_WORKSPACE;
-    ShardTableKey* key = (ShardTableKey*)workspace;
-    double* gain_table = (double*)((char*)workspace + sizeof(ShardTableKey));
-    double* surv_table = gain_table + kShardTableCap;
-    long long* prefix = group_off ? (long long*)(surv_table + kShardTableCap) : nullptr;
+    const ShardWorkspace w = carve_shards(workspace, n_shards);
+    long long* prefix = group_off ? w.prefix : nullptr;
     const int depth = table_depth(g0, delta_max);
+    const int usable = (delta_max > 0 && delta_max < depth) ? delta_max : depth;   // gains l < cap only
+    const unsigned setup_blocks = 2 + (group_off ? (unsigned)((n_shards + kPrefixChunk - 1) / kPrefixChunk) : 0u);
     if (group_off && n == 0) hipLaunchKernelGGL(k_store_zero_offset, 1, 1, 0, s, group_off, off_t == HORA_I64 ? 1 : 0);
-    hipLaunchKernelGGL(k_shard_setup, dim3(2), dim3(kPrefixThreads), 0, s, (long long)n_shards,
-                       (const long long*)shard_budget, prefix, (int)g0, alpha0, beta0, depth, key, gain_table,
-                       surv_table);
+    hipLaunchKernelGGL(k_shard_setup, dim3(setup_blocks), dim3(kPrefixThreads), 0, s, (long long)n_shards,
+                       (const long long*)shard_budget, prefix, (int)g0, alpha0, beta0, depth, usable, w.key,
+                       w.gain_table, w.surv_table, w.level_bits, w.level_kge, w.todo);
     CountsSource src{c, g0, alpha0, beta0};
     const int cap = delta_max > 0 ? delta_max : 0;
     const int mode = group_off ? (off_t == HORA_I32 ? 1 : 2) : 0;
-#define HORA_LAUNCH_SHARDS(M)                                                                                   \
-    hipLaunchKernelGGL((k_shard_allocate<CountsSource, M>), dim3((unsigned)n_shards), dim3(kShardThreads), 0, s, \
-                       src, (long long)n, (int)g0, (long long)n_shards, (const long long*)shard_off,            \
-                       (const long long*)shard_budget, cap, prefix, depth, gain_table, surv_table, delta, util,    \
+    // small shards: a wavefront per shard first; what it cannot settle is flagged for the
+    // workgroup-per-shard kernel
+    const bool waves = depth > 0 && n <= (long long)n_shards * kWaveShardMeanMax;
+    if (waves) {
+        const unsigned blocks = (unsigned)((n_shards + kShardWaves - 1) / kShardWaves);
+#define HORA_LAUNCH_WAVES(M)                                                                                     \
+    hipLaunchKernelGGL((k_shard_allocate_waves<M>), dim3(blocks), dim3(kShardThreads), 0, s, src, (long long)n,   \
+                       (long long)n_shards, (const long long*)shard_off, (const long long*)shard_budget, cap,    \
+                       prefix, depth, usable, w.surv_table, w.level_bits, w.level_kge, w.todo, delta, util,      \
                        group_off, summary, dev_status)
+        if (mode == 0) HORA_LAUNCH_WAVES(0);
+        else if (mode == 1) HORA_LAUNCH_WAVES(1);
+        else HORA_LAUNCH_WAVES(2);
+#undef HORA_LAUNCH_WAVES
+    }
+#define HORA_LAUNCH_SHARDS(M)                                                                                   \
+    do {                                                                                                        \
+        if (waves)                                                                                              \
+            hipLaunchKernelGGL((k_shard_allocate_todo<CountsSource, M>), dim3(todo_blocks), dim3(kShardThreads), \
+                               0, s, src, (long long)n, (int)g0, (long long)n_shards,                           \
+                               (const long long*)shard_off, (const long long*)shard_budget, cap, prefix, depth, \
+                               w.gain_table, w.surv_table, delta, util, group_off, summary, w.todo, dev_status); \
+        else                                                                                                    \
+            hipLaunchKernelGGL((k_shard_allocate<CountsSource, M>), dim3((unsigned)n_shards),                   \
+                               dim3(kShardThreads), 0, s, src, (long long)n, (int)g0, (long long)n_shards,      \
+                               (const long long*)shard_off, (const long long*)shard_budget, cap, prefix, depth, \
+                               w.gain_table, w.surv_table, delta, util, group_off, summary, dev_status);        \
+    } while (0)
+    const unsigned todo_blocks = (unsigned)(n_shards < 1024 ? n_shards : 1024);
     if (mode == 0) HORA_LAUNCH_SHARDS(0);
     else if (mode == 1) HORA_LAUNCH_SHARDS(1);
     else HORA_LAUNCH_SHARDS(2);
