@@ -38,7 +38,7 @@
  * Canonical gain: the binary64 value produced by exactly this sequence --
  * s = alpha+beta; M(0) = alpha/s; M(l+1) = (M(l) * (beta+l)) / (s + (l+1)) --
  * one multiply, then one divide, always walked from l = 0.  The paper's argmax
- * has no tie rule; ordering by (canonical gain, prompt index) is this build's
+ * has no tie rule; ordering by (canonical gain, prompt index) is this library's
  * reading, so the rounding of this sequence is part of the result.
  * ------------------------------------------------------------------------- */
 static inline double gain_first(double alpha, double beta) {

@@ -2,7 +2,7 @@
 
 G0 = 4, uniform prior, c = (0, 2, 4), budgets 0..12.  The paper prints no worked
 allocation; rows without ties follow from exact rationals (checked in
-tests/test_oracle_allocate.py), the tied rows record this build's tie rule
+tests/test_oracle_allocate.py), the tied rows record this library's tie rule
 (canonical binary64 gain, then prompt index; Sec. 3.2's argmax states none).
 Run: python tests/golden/make_worked_example.py
 """

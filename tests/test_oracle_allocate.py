@@ -156,7 +156,7 @@ def test_worked_example_g0_4(oracle):
     #   c=0: 1/6, 5/42, 5/56, ...   c=2: 1/2, 3/14, 3/28, 5/84   c=4: 5/6, 5/42, 5/168
     # B = 1..4 and 6..7 involve no tie between the prompts still competing, so those
     # rows follow from the rationals alone.  At B = 5 prompts 0 and 2 tie at 5/42;
-    # either choice is optimal (sum U = 11/6); this build's rule (canonical fp64
+    # either choice is optimal (sum U = 11/6); this library's rule (canonical fp64
     # gain, then index) is recorded in tests/golden/worked_example_g0_4.txt.
     c = np.array([0, 2, 4], dtype=np.int32)
     forced = {0: (0, 0, 0), 1: (0, 0, 1), 2: (0, 1, 1), 3: (0, 2, 1), 4: (1, 2, 1),
