@@ -126,3 +126,45 @@ def test_sharded_large_workload(gpu, oracle):
     a = wl.phase_a(w)
     bounds, budgets = wl.equal_shards(w.n, wl.SHARDED_LARGE_SHARDS, w.budget)
     check_sharded(gpu, oracle, a.c, w.g0, bounds, budgets, off_dtype="i32", check_util=False)
+
+
+def test_wavefront_path_edges(gpu, oracle):
+    """Cases that steer between the wavefront-per-shard kernel and the workgroup-per-shard code
+    that takes what it leaves over."""
+    from paper_2605_07114_amd import workloads as wl
+    sess, torch, hora = gpu
+    rng = np.random.default_rng(77)
+    # a cap that is not a power of two: 9 * 56 table levels, the last block of levels is short
+    w = wl.SMALL
+    a = wl.phase_a(w)
+    bounds, budgets = wl.equal_shards(w.n, 512, w.budget)
+    check_sharded(gpu, oracle, a.c, w.g0, bounds, budgets, delta_max=w.delta_max, off_dtype="i32")
+    # one shard far larger than a wavefront handles among many tiny ones (it goes on the left-over list)
+    sizes = np.concatenate((np.full(50, 10), [2000], np.full(50, 10)))
+    bounds = np.concatenate(([0], np.cumsum(sizes))).astype(np.int64)
+    c = rng.integers(0, 9, int(bounds[-1])).astype(np.int32)
+    budgets = (sizes * 12).astype(np.int64)
+    check_sharded(gpu, oracle, c, 8, bounds, budgets)
+    # allocations deeper than the table: two hard prompts take 1500 rollouts
+    c = np.array([0, 0, 8, 8, 3, 0, 1], dtype=np.int32)
+    check_sharded(gpu, oracle, c, 8, np.array([0, 4, 7], dtype=np.int64), np.array([1500, 40], dtype=np.int64))
+    # budget of one unit, budget equal to the number of prompts, all prompts tied
+    c = np.full(64, 2, dtype=np.int32)
+    check_sharded(gpu, oracle, c, 4, np.array([0, 1, 33, 64], dtype=np.int64), np.array([1, 32, 5], dtype=np.int64))
+
+
+def test_tables_follow_the_prior_between_calls(gpu, oracle):
+    """The workspace keeps the gain tables of the last call: a change of prior, G0 or cap must rebuild them."""
+    sess, torch, hora = gpu
+    rng = np.random.default_rng(78)
+    c = rng.integers(0, 5, 600).astype(np.int32)
+    bounds = np.arange(0, 601, 20, dtype=np.int64)
+    budgets = np.full(30, 70, dtype=np.int64)
+    for alpha0, beta0, cap in ((1.0, 1.0, 0), (0.5, 2.0, 0), (1.0, 1.0, 0), (1.0, 1.0, 9), (3.0, 0.25, 9)):
+        want = oracle.allocate_sharded(c, 4, bounds, budgets, delta_max=cap, alpha0=alpha0, beta0=beta0)
+        got = sess.allocate_sharded(dev(torch, c), 4, dev(torch, bounds), dev(torch, budgets), alpha0=alpha0,
+                                    beta0=beta0, delta_max=cap)
+        assert sess.status() == 0
+        assert np.array_equal(got.delta.cpu().numpy().astype(np.int64), want), (alpha0, beta0, cap)
+        alpha, beta = oracle.posterior(c, 4, alpha0, beta0)
+        np.testing.assert_allclose(got.util.cpu().numpy(), oracle.utilities(alpha, beta, want), rtol=UTIL_RTOL, atol=0)
