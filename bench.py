@@ -126,6 +126,27 @@ def other_paths(torch, hora, wl, sess, a1, c1, w1, delta1, util1, goff1, ws, rep
         assert int(delta.sum()) == w.budget
         out[f"allocate_sharded_{w.name}"] = {"shards": n_shards, "prompts": w.n, "us_per_call": us,
                                              "prompts_per_s": w.n / us * 1e6}
+    # the helpers next to the path, on the large-broadcast shapes: loss weights, baseline rule, Pass@K
+    w2 = wl.LARGE_BCAST
+    a2 = wl.phase_a(w2)
+    c2 = torch.from_numpy(a2.c).to("cuda:0")
+    alloc2 = sess.allocate(c2, w2.g0, w2.budget, off_dtype=torch.int32, want_util=False, want_summary=False)
+    b2 = wl.phase_b(w2, a2, alloc2.delta.cpu().numpy())
+    toff2 = torch.from_numpy(b2.tok_off).to("cuda:0")
+    wts = torch.empty(b2.reward.size, dtype=torch.float32, device="cuda:0")
+    us = mean_us(lambda: hora.hora_response_weights(alloc2.group_off, toff2, wts, sess.dev_status))
+    out["response_weights_large_bcast"] = {"responses": int(b2.reward.size), "us_per_call": us}
+    us = mean_us(lambda: hora.hora_allocate_baseline(c1, w1.g0, w1.budget, hora.RULE_HARD_FIRST, delta1,
+                                                     sess.dev_status, ws, util=util1, group_off=goff1))
+    out["allocate_hard_first_large_alloc"] = {"us_per_call": us, "prompts_per_s": w1.n / us * 1e6}
+    rng = np.random.Generator(np.random.PCG64(7))
+    n_prob, pool, ks = 500, 256, [1, 8, 16, 32, 64, 128, 256]       # the paper's MATH500 evaluation shape
+    corr = torch.from_numpy(rng.binomial(pool, rng.beta(0.5, 0.5, n_prob)).astype(np.int32)).to("cuda:0")
+    pools = torch.full((n_prob,), pool, dtype=torch.int32, device="cuda:0")
+    mean = torch.empty(len(ks), dtype=torch.float64, device="cuda:0")
+    pws = torch.empty(hora.hora_pass_at_k_workspace_bytes(n_prob, len(ks)), dtype=torch.uint8, device="cuda:0")
+    us = mean_us(lambda: hora.hora_pass_at_k(pools, corr, ks, mean, sess.dev_status, pws))
+    out["pass_at_k_500_problems_256_samples_7_ks"] = {"us_per_call": us}
     assert sess.status() == 0
     return out
 
@@ -202,6 +223,9 @@ def main():
         hora.hora_token_broadcast(adv_rloo, tok_off2, tok_rloo, n_tok, sess.dev_status, bws)
 
     bc_mean, bc_min = per_launch_events(torch, one_broadcast, steps2, 3)
+    # what a plain fill of the same buffer reaches in the same run (torch's fill kernel)
+    fill_mean, _ = per_launch_events(torch, lambda: tok_grpo.zero_(), steps2, 3)
+    fill_gbs = 4 * n_tok / fill_mean / 1e9
     if args.calibrate_copy:          # reads and writes 4 * n_tok bytes each
         tok_grpo.copy_(tok_rloo)
         torch.cuda.synchronize()
@@ -234,6 +258,8 @@ def main():
                         f"{n_tok} tokens, int64 packed offsets, f32 token advantages",
             "GBps": bcast_gbs,
             "pct_of_hbm_peak": 100.0 * bcast_gbs / HBM_PEAK_GBS,
+            "plain_fill_GBps": fill_gbs,
+            "pct_of_plain_fill": 100.0 * bcast_gbs / fill_gbs,
             "kernel_ms_mean": bc_mean * 1e3,
             "kernel_ms_min": bc_min * 1e3,
             "whole_path_ms_per_step": wall2 / steps2 * 1e3,
