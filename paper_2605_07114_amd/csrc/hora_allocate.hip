@@ -425,8 +425,19 @@ __device__ void solve_by_table(int nc, int row_len, int len, bool rows_end_at_ca
                 sol->r = budget - gt;
                 sol->tie_prompts = eq;
                 sol->found = 1;
+                // the per-class results are at hand in this entry's pairs
+                for (int cls = 0; cls < nc; ++cls) {
+                    const int pr = s_pair[idx * nc + cls];
+                    const int pos = pr & 0x7fff;
+                    sol->k[cls] = pos;
+                    sol->tied[cls] = (pr & 0x8000) ? 1 : 0;
+                    sol->u0[cls] = 1.0 - s_surv[cls * row_len + pos];
+                    sol->u1[cls] = 1.0 - s_surv[cls * row_len + (pos + 1 < row_len ? pos + 1 : pos)];
+                }
             }
         }
+        __syncthreads();
+        return;
     } else
     for (int idx = (int)threadIdx.x; idx < cands; idx += kBig) {
         const int c = idx >> row_shift, l = idx & (row_len - 1);
@@ -891,6 +902,8 @@ __global__ __launch_bounds__(kBig) void k_select_pass(Src src, long long n, long
                     const int leader = __ffsll((long long)pending) - 1;
                     const unsigned long long v = read_lane_u64(gb, leader);
                     const unsigned long long same = __ballot(inside && gb == v);
+                    // gains that do not repeat (per-prompt posteriors): no point in more rounds
+                    if (round == 0 && same == (1ull << leader) && __popcll(pending) > 8) break;
                     if (lane == leader) {
                         const int j = (int)((v - lo - 1ull) >> shift);
                         // no result is used: the three updates are issued without a wait
