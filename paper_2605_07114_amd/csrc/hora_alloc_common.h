@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "hora.h"
 #include "hora_device.h"
 
 namespace hora {
@@ -68,5 +69,14 @@ __device__ __forceinline__ long long walk_above(double a, double b, unsigned lon
     }
     return k;
 }
+
+// A batch small enough for one workgroup, solved in a single launch (defined with the
+// sharded kernels, whose workgroup-per-shard code it reuses).
+int allocate_small_counts(const CountsSource& src, int64_t n, int32_t g0, int64_t budget, int32_t delta_max,
+                          int32_t* delta, double* util, void* group_off, int32_t off_t, hora_alloc_summary* summary,
+                          int32_t* dev_status, hipStream_t stream);
+int allocate_small_posterior(const PosteriorSource& src, int64_t n, int32_t g0, int64_t budget, int32_t delta_max,
+                             int32_t* delta, double* util, void* group_off, int32_t off_t,
+                             hora_alloc_summary* summary, int32_t* dev_status, hipStream_t stream);
 
 }  // namespace hora

@@ -1264,9 +1264,20 @@ static int run_class(const int32_t* c, double alpha0, double beta0, const Common
     return check_launch();
 }
 
+static int run_small(const CountsSource& src, const CommonArgs& a) {
+    return allocate_small_counts(src, a.n, a.g0, a.budget, a.delta_max, a.delta, a.util, a.group_off, a.off_t,
+                                 a.summary, a.dev_status, a.stream);
+}
+static int run_small(const PosteriorSource& src, const CommonArgs& a) {
+    return allocate_small_posterior(src, a.n, a.g0, a.budget, a.delta_max, a.delta, a.util, a.group_off, a.off_t,
+                                    a.summary, a.dev_status, a.stream);
+}
+
 template <class Src>
 static int run_bisect(const Src& src, const CommonArgs& a, const Plan& p, const Workspace& w) {
     const long long n = a.n;
+    // a batch that one workgroup can hold: one launch does the whole search and the outputs
+    if (n <= kSoloMaxPrompts) return run_small(src, a);
     long long limit = a.delta_max > 0 ? (long long)a.delta_max : a.budget;
     if (limit > a.budget) limit = a.budget;
     if (a.budget > 0) {

@@ -322,6 +322,8 @@ __device__ bool threshold_by_walks(const Src& src, long long lo_i, long long hi_
                     const int leader = __ffsll((long long)pending) - 1;
                     const unsigned long long v = read_lane_u64(gb, leader);
                     const unsigned long long same = __ballot(inside && gb == v);
+                    // gains that do not repeat (per-prompt posteriors): no point in more rounds
+                    if (round == 0 && same == (1ull << leader) && __popcll(pending) > 8) break;
                     if (lane == leader) {
                         const int j = (int)((v - lo - 1ull) >> shift);
                         atomicAdd(&sh.cnt[j], (unsigned long long)__popcll(same));
@@ -472,32 +474,17 @@ __device__ bool threshold_by_table(const Src& src, long long lo_i, long long hi_
 }
 
 // kOff: 0 no offsets, 1 int32 offsets, 2 int64 offsets.
+// The work of one workgroup on the prompts [lo_i, hi_i) with `budget` units (validated by
+// the caller): threshold, per-prompt results, tie pass, outputs.  off_base: rollouts that lie
+// before the shard (g0 per earlier prompt is added here; the budgets of earlier shards come
+// in); summary: this shard's report or NULL.
 template <class Src, int kOff>
-__device__ void shard_by_workgroup(const Src& src, long long shard, long long n, int g0, long long n_shards,
-                                   const long long* __restrict__ shard_off,
-                                   const long long* __restrict__ shard_budget, int cap,
-                                   const long long* __restrict__ prefix, int depth,
-                                   const double* __restrict__ gain_table, const double* __restrict__ surv_table,
-                                   int32_t* __restrict__ delta, double* __restrict__ util,
-                                   void* __restrict__ group_off, hora_alloc_summary* __restrict__ summary,
-                                   int32_t* dev_status) {
+__device__ void shard_core(const Src& src, long long lo_i, long long hi_i, long long budget, long long off_base,
+                           long long n, int g0, int cap, int depth, const double* __restrict__ gain_table,
+                           const double* __restrict__ surv_table, int32_t* __restrict__ delta,
+                           double* __restrict__ util, void* __restrict__ group_off,
+                           hora_alloc_summary* __restrict__ summary, int32_t* dev_status) {
     __shared__ ShardShared sh;
-    const long long lo_i = shard_off[shard], hi_i = shard_off[shard + 1];
-    const long long budget = shard_budget[shard];
-
-    // the shards must tile [0, n) in order, and the budget must fit the shard
-    bool bad = lo_i < 0 || hi_i < lo_i || hi_i > n || budget < 0 || (shard == 0 && lo_i != 0) ||
-               (shard == n_shards - 1 && hi_i != n);
-    const long long size = bad ? 0 : hi_i - lo_i;
-    bool infeasible = false;
-    if (!bad) {
-        infeasible = (budget > 0 && size == 0) || (cap > 0 && budget > size * (long long)cap) ||
-                     (cap <= 0 && budget >= (1ll << 31) - 1) || budget >= (1ll << 52);
-    }
-    if (bad || infeasible) {
-        if (threadIdx.x == 0) report(dev_status, bad ? HORA_ERR_RANGE : HORA_ERR_INFEASIBLE);
-        return;
-    }
     long long limit = cap > 0 ? (long long)cap : budget;
     if (limit > budget) limit = budget;
 
@@ -543,14 +530,13 @@ __device__ void shard_by_workgroup(const Src& src, long long shard, long long n,
     const long long r = budget - ks;
     if ((r < 0 || r > ts) && threadIdx.x == 0) report(dev_status, HORA_ERR_RANGE);
     if (summary && threadIdx.x == 0) {
-        summary[shard].tau = budget > 0 ? __longlong_as_double((long long)tau_bits) : 0.0;
-        summary[shard].count_gt = ks;
-        summary[shard].tie_units = r;
-        summary[shard].tie_prompts = ts;
+        summary->tau = budget > 0 ? __longlong_as_double((long long)tau_bits) : 0.0;
+        summary->count_gt = ks;
+        summary->tie_units = r;
+        summary->tie_prompts = ts;
     }
 
     // ---- ties by prompt index, final delta, utilities, offsets -------------------------
-    const long long off_base = kOff != 0 ? prefix[shard] : 0;   // units given to earlier shards
     long long rank_base = 0, k_base = 0;
     for (long long i0 = lo_i; i0 < hi_i; i0 += kShardThreads) {
         const long long i = i0 + threadIdx.x;
@@ -588,6 +574,75 @@ __device__ void shard_by_workgroup(const Src& src, long long shard, long long n,
         rank_base += t_tot;
         k_base += k_tot;
     }
+}
+
+// Loads and checks one shard's bounds and budget, then runs shard_core on it.
+template <class Src, int kOff>
+__device__ void shard_by_workgroup(const Src& src, long long shard, long long n, int g0, long long n_shards,
+                                   const long long* __restrict__ shard_off,
+                                   const long long* __restrict__ shard_budget, int cap,
+                                   const long long* __restrict__ prefix, int depth,
+                                   const double* __restrict__ gain_table, const double* __restrict__ surv_table,
+                                   int32_t* __restrict__ delta, double* __restrict__ util,
+                                   void* __restrict__ group_off, hora_alloc_summary* __restrict__ summary,
+                                   int32_t* dev_status) {
+    const long long lo_i = shard_off[shard], hi_i = shard_off[shard + 1];
+    const long long budget = shard_budget[shard];
+    // the shards must tile [0, n) in order, and the budget must fit the shard
+    bool bad = lo_i < 0 || hi_i < lo_i || hi_i > n || budget < 0 || (shard == 0 && lo_i != 0) ||
+               (shard == n_shards - 1 && hi_i != n);
+    const long long size = bad ? 0 : hi_i - lo_i;
+    bool infeasible = false;
+    if (!bad) {
+        infeasible = (budget > 0 && size == 0) || (cap > 0 && budget > size * (long long)cap) ||
+                     (cap <= 0 && budget >= (1ll << 31) - 1) || budget >= (1ll << 52);
+    }
+    if (bad || infeasible) {
+        if (threadIdx.x == 0) report(dev_status, bad ? HORA_ERR_RANGE : HORA_ERR_INFEASIBLE);
+        return;
+    }
+    shard_core<Src, kOff>(src, lo_i, hi_i, budget, kOff != 0 ? prefix[shard] : 0, n, g0, cap, depth, gain_table,
+                          surv_table, delta, util, group_off, summary ? summary + shard : nullptr, dev_status);
+}
+
+// A whole batch as one shard, for batches small enough for one workgroup: one launch in place
+// of the pass-by-pass search (any posterior; the arguments have been checked on the host).
+template <class Src, int kOff>
+__global__ __launch_bounds__(kShardThreads) void k_whole_batch(Src src, long long n, int g0, long long budget, int cap,
+                                                               int32_t* __restrict__ delta,
+                                                               double* __restrict__ util,
+                                                               void* __restrict__ group_off,
+                                                               hora_alloc_summary* __restrict__ summary,
+                                                               int32_t* dev_status) {
+    shard_core<Src, kOff>(src, 0, n, budget, 0, n, g0, cap, 0, nullptr, nullptr, delta, util, group_off, summary,
+                          dev_status);
+}
+
+template <class Src>
+static int launch_whole_batch(const Src& src, int64_t n, int32_t g0, int64_t budget, int32_t delta_max,
+                              int32_t* delta, double* util, void* group_off, int32_t off_t,
+                              hora_alloc_summary* summary, int32_t* dev_status, hipStream_t stream) {
+    const int cap = delta_max > 0 ? delta_max : 0;
+    const int mode = group_off ? (off_t == HORA_I32 ? 1 : 2) : 0;
+#define HORA_LAUNCH_WHOLE(M)                                                                                    \
+    hipLaunchKernelGGL((k_whole_batch<Src, M>), dim3(1), dim3(kShardThreads), 0, stream, src, (long long)n,      \
+                       (int)g0, (long long)budget, cap, delta, util, group_off, summary, dev_status)
+    if (mode == 0) HORA_LAUNCH_WHOLE(0);
+    else if (mode == 1) HORA_LAUNCH_WHOLE(1);
+    else HORA_LAUNCH_WHOLE(2);
+#undef HORA_LAUNCH_WHOLE
+    return hipGetLastError() == hipSuccess ? HORA_OK : HORA_ERR_HIP;
+}
+
+int allocate_small_counts(const CountsSource& src, int64_t n, int32_t g0, int64_t budget, int32_t delta_max,
+                          int32_t* delta, double* util, void* group_off, int32_t off_t, hora_alloc_summary* summary,
+                          int32_t* dev_status, hipStream_t stream) {
+    return launch_whole_batch(src, n, g0, budget, delta_max, delta, util, group_off, off_t, summary, dev_status, stream);
+}
+int allocate_small_posterior(const PosteriorSource& src, int64_t n, int32_t g0, int64_t budget, int32_t delta_max,
+                             int32_t* delta, double* util, void* group_off, int32_t off_t,
+                             hora_alloc_summary* summary, int32_t* dev_status, hipStream_t stream) {
+    return launch_whole_batch(src, n, g0, budget, delta_max, delta, util, group_off, off_t, summary, dev_status, stream);
 }
 
 // One workgroup per shard.
