@@ -123,8 +123,11 @@ size_t hora_allocate_workspace_bytes(int64_t n, int32_t g0);
  * n, g0     : number of prompts (>= 0) and pre-rollouts per prompt (>= 0).
  * c         : device, n int32, each in [0, g0] (else HORA_ERR_RANGE in dev_status).
  * alpha0, beta0 : prior, both > 0 and finite (the paper uses 1, 1).
- * budget    : Phase-B budget, 0 <= budget < 2^62; need not be a multiple of n.
- * delta_max : per-prompt cap; <= 0 means none (the paper states none).
+ * budget    : Phase-B budget, >= 0; need not be a multiple of n.  HORA_ERR_UNSUPPORTED
+ *             from 2^52 on, or when one prompt could receive 2^31 - 1 units or more
+ *             (delta is int32): min(budget, delta_max) with a cap, budget without.
+ * delta_max : per-prompt cap; <= 0 means none (the paper states none).  A budget above
+ *             n * delta_max gives HORA_ERR_INFEASIBLE.
  * method    : hora_alloc_method.
  * delta     : device out, n int32.
  * util      : device out, n doubles, U_i(delta_i) by the product recurrence.  Nullable.
@@ -203,6 +206,9 @@ size_t hora_allocate_sharded_workspace_bytes(int64_t n_shards);
  *                (shard size) * delta_max with one; a positive budget needs a non-empty
  *                shard (else HORA_ERR_RANGE / HORA_ERR_INFEASIBLE in dev_status; the
  *                outputs of such a shard are unspecified).
+ * group_off    : as for hora_allocate; with HORA_I32 a total n*g0 + sum of the budgets of
+ *                2^31 or more gives HORA_ERR_RANGE in dev_status (HORA_ERR_INVALID_ARG
+ *                where n*g0 alone shows it).
  * summary      : device out, n_shards entries.  Nullable.
  * workspace    : device, >= hora_allocate_sharded_workspace_bytes(n_shards).
  * The other arguments are those of hora_allocate.  One workgroup works on one shard:

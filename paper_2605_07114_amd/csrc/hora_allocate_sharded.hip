@@ -564,7 +564,10 @@ __device__ void shard_core(const Src& src, long long lo_i, long long hi_i, long 
                 const long long next = off + g0 + kk + (win ? 1 : 0);
                 if (kOff == 1) {
                     reinterpret_cast<int32_t*>(group_off)[i] = (int32_t)off;
-                    if (i == n - 1) reinterpret_cast<int32_t*>(group_off)[n] = (int32_t)next;
+                    if (i == n - 1) {
+                        reinterpret_cast<int32_t*>(group_off)[n] = (int32_t)next;
+                        if (next >= (1ll << 31)) report(dev_status, HORA_ERR_RANGE);   // total does not fit
+                    }
                 } else {
                     reinterpret_cast<long long*>(group_off)[i] = off;
                     if (i == n - 1) reinterpret_cast<long long*>(group_off)[n] = next;
@@ -929,7 +932,10 @@ __global__ __launch_bounds__(kShardThreads) void k_shard_allocate_waves(
                 const long long off = off_base + given + incl - units;
                 if (kOff == 1) {
                     reinterpret_cast<int32_t*>(group_off)[i] = (int32_t)off;
-                    if (i == n - 1) reinterpret_cast<int32_t*>(group_off)[n] = (int32_t)(off + units);
+                    if (i == n - 1) {
+                        reinterpret_cast<int32_t*>(group_off)[n] = (int32_t)(off + units);
+                        if (off + units >= (1ll << 31)) report(dev_status, HORA_ERR_RANGE);   // total does not fit
+                    }
                 } else {
                     reinterpret_cast<long long*>(group_off)[i] = off;
                     if (i == n - 1) reinterpret_cast<long long*>(group_off)[n] = off + units;
@@ -981,6 +987,7 @@ extern "C" int hora_allocate_sharded(int64_t n, int32_t g0, const int32_t* c, do
     if (group_off && off_t != HORA_I32 && off_t != HORA_I64) return HORA_ERR_INVALID_ARG;
     if (n >= (1ll << 40) || n_shards > INT_MAX) return HORA_ERR_UNSUPPORTED;
     if (n > 0 && n_shards == 0) return HORA_ERR_INVALID_ARG;   // the shards must cover every prompt
+    if (group_off && off_t == HORA_I32 && n * (long long)g0 >= (1ll << 31)) return HORA_ERR_INVALID_ARG;
     if ((reinterpret_cast<uintptr_t>(delta) & 3) || (reinterpret_cast<uintptr_t>(util) & 7) ||
         (reinterpret_cast<uintptr_t>(dev_status) & 3) || (reinterpret_cast<uintptr_t>(c) & 3) ||
         (reinterpret_cast<uintptr_t>(shard_off) & 7) || (reinterpret_cast<uintptr_t>(shard_budget) & 7) ||

@@ -168,3 +168,27 @@ def test_tables_follow_the_prior_between_calls(gpu, oracle):
         assert np.array_equal(got.delta.cpu().numpy().astype(np.int64), want), (alpha0, beta0, cap)
         alpha, beta = oracle.posterior(c, 4, alpha0, beta0)
         np.testing.assert_allclose(got.util.cpu().numpy(), oracle.utilities(alpha, beta, want), rtol=UTIL_RTOL, atol=0)
+
+
+def test_int32_offsets_that_overflow_are_reported(gpu):
+    """With 32-bit offsets the total n*g0 + sum of budgets must stay below 2^31; the budgets are
+    device data, so the overflow is found on the device and reported through dev_status."""
+    sess, torch, hora = gpu
+    n, g0, n_shards = 1 << 24, 63, 1 << 16
+    rng = np.random.default_rng(79)
+    c = dev(torch, rng.integers(0, g0 + 1, n).astype(np.int32))
+    bounds = dev(torch, np.arange(0, n + 1, n // n_shards, dtype=np.int64))
+    for per_shard, want_status in ((16000, 0), (16896, hora.ERR_RANGE)):
+        total = n * g0 + n_shards * per_shard
+        assert (total >= 1 << 31) == (want_status != 0)
+        print(f"sharded int32 offsets: total {total}", flush=True)
+        sess.dev_status.zero_()
+        got = sess.allocate_sharded(c, g0, bounds, dev(torch, np.full(n_shards, per_shard, dtype=np.int64)),
+                                    want_util=False, off_dtype=torch.int32, want_summary=False)
+        assert sess.status() == want_status
+        sess.dev_status.zero_()
+        if want_status == 0:
+            assert int(got.group_off[-1]) == total
+            assert int(got.delta.sum(dtype=torch.int64)) == n_shards * per_shard
+            widths = got.group_off[1:].to(torch.int64) - got.group_off[:-1].to(torch.int64)
+            assert bool((widths == got.delta.to(torch.int64) + g0).all())

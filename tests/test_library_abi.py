@@ -103,6 +103,69 @@ def test_host_argument_validation_needs_no_gpu(lib):
     assert mg(0, fake, fake, 4, fake, None, None) == 0
 
 
+def test_host_argument_validation_of_the_later_entry_points(lib):
+    INVALID, INFEASIBLE, WORKSPACE, UNSUPPORTED = -1, -2, -3, -6
+    fake = ctypes.c_void_p(0x1000)
+    status = ctypes.c_void_p(0x2000)
+    odd = ctypes.c_void_p(0x1004)            # 4-byte aligned only
+    big = 1 << 24
+    # sharded allocation
+    sh = lib.hora_allocate_sharded
+    assert sh(-1, 4, fake, 1.0, 1.0, 2, fake, fake, 0, fake, None, None, 0, None, status, fake, big, None) == INVALID
+    assert sh(8, 4, fake, 1.0, -1.0, 2, fake, fake, 0, fake, None, None, 0, None, status, fake, big, None) == INVALID
+    assert sh(8, 4, fake, 1.0, 1.0, 0, fake, fake, 0, fake, None, None, 0, None, status, fake, big, None) == INVALID
+    assert sh(8, 4, fake, 1.0, 1.0, 2, None, fake, 0, fake, None, None, 0, None, status, fake, big, None) == INVALID
+    assert sh(8, 4, fake, 1.0, 1.0, 2, odd, fake, 0, fake, None, None, 0, None, status, fake, big, None) == INVALID
+    assert sh(8, 4, fake, 1.0, 1.0, 2, fake, fake, 0, fake, None, fake, 5, None, status, fake, big, None) == INVALID
+    assert sh(1 << 29, 4, fake, 1.0, 1.0, 2, fake, fake, 0, fake, None, fake, 0, None, status, fake, big, None) == INVALID
+    assert sh(8, 4, fake, 1.0, 1.0, 2, fake, fake, 0, fake, None, None, 0, None, None, fake, big, None) == INVALID
+    assert sh(8, 4, fake, 1.0, 1.0, 2, fake, fake, 0, fake, None, None, 0, None, status, None, 0, None) == WORKSPACE
+    assert sh(8, 4, fake, 1.0, 1.0, 2, fake, fake, 0, fake, None, None, 0, None, status, fake, 64, None) == WORKSPACE
+    assert sh(8, 4, fake, 1.0, 1.0, 1 << 32, fake, fake, 0, fake, None, None, 0, None, status, fake, big, None) == UNSUPPORTED
+    prev = 0
+    for shards in (0, 1, 4, 8192, 8193, 1 << 20):
+        b = lib.hora_allocate_sharded_workspace_bytes(shards)
+        assert b % 256 == 0 and b >= prev and b > 0
+        prev = b
+    assert lib.hora_allocate_sharded_workspace_bytes(-1) == 0
+    # baseline rules
+    base = lib.hora_allocate_baseline
+    assert base(8, 4, fake, 1.0, 1.0, 8, 0, 7, fake, None, None, 0, None, status, fake, big, None) == INVALID      # rule
+    assert base(8, 64, fake, 1.0, 1.0, 8, 0, 0, fake, None, None, 0, None, status, fake, big, None) == UNSUPPORTED # g0
+    assert base(8, 4, fake, 1.0, 1.0, 25, 3, 0, fake, None, None, 0, None, status, fake, big, None) == INFEASIBLE
+    assert base(0, 4, fake, 1.0, 1.0, 1, 0, 1, fake, None, None, 0, None, status, fake, big, None) == INFEASIBLE
+    assert base(8, 4, fake, 1.0, 1.0, 8, 0, 1, fake, None, None, 0, None, status, fake, 16, None) == WORKSPACE
+    # per-prompt posteriors
+    post = lib.hora_allocate_posterior
+    assert post(8, 4, None, fake, 8, 0, fake, None, None, 0, None, status, fake, big, None) == INVALID
+    assert post(8, 4, odd, fake, 8, 0, fake, None, None, 0, None, status, fake, big, None) == INVALID
+    assert post(8, 4, fake, fake, -1, 0, fake, None, None, 0, None, status, fake, big, None) == INVALID
+    assert post(8, 4, fake, fake, 1 << 53, 4, fake, None, None, 0, None, status, fake, big, None) == UNSUPPORTED
+    assert post(8, 4, fake, fake, 8, 0, fake, None, None, 0, None, status, fake, 16, None) == WORKSPACE
+    # loss weights
+    wt = lib.hora_response_weights
+    assert wt(4, fake, 0, 16, fake, 1, 0.0, fake, 0, None, None) == INVALID                  # status word
+    assert wt(4, fake, 3, 16, fake, 1, 0.0, fake, 0, status, None) == INVALID                # offset type
+    assert wt(4, fake, 0, 16, fake, 1, float("nan"), fake, 0, status, None) == INVALID       # length constant
+    assert wt(4, fake, 0, 16, odd, 1, 0.0, fake, 0, status, None) == INVALID                 # int64 offsets misaligned
+    assert wt(0, fake, 0, 16, fake, 1, 0.0, fake, 0, status, None) == INVALID                # responses without groups
+    assert wt(0, fake, 0, 0, fake, 1, 0.0, fake, 0, status, None) == 0
+    # Pass@K (ks is read on the host)
+    pk = lib.hora_pass_at_k
+    ks = (ctypes.c_int32 * 3)(1, 8, 64)
+    bad_ks = (ctypes.c_int32 * 3)(1, 0, 64)
+    need = lib.hora_pass_at_k_workspace_bytes(500, 3)
+    assert need > 0 and need % 256 == 0
+    assert lib.hora_pass_at_k_workspace_bytes(500, 65) == 0
+    assert pk(500, fake, fake, 0, ks, None, fake, status, fake, need, None) == 0               # no K: nothing to do
+    assert pk(500, fake, fake, 65, ks, None, fake, status, fake, need, None) == UNSUPPORTED
+    assert pk(500, fake, fake, 3, None, None, fake, status, fake, need, None) == INVALID
+    assert pk(500, fake, fake, 3, bad_ks, None, fake, status, fake, need, None) == INVALID
+    assert pk(500, None, fake, 3, ks, None, fake, status, fake, need, None) == INVALID
+    assert pk(500, fake, fake, 3, ks, None, fake, status, None, 0, None) == WORKSPACE
+    assert pk(500, fake, fake, 3, ks, None, fake, status, fake, 8, None) == WORKSPACE
+
+
 def test_binding_refuses_to_run_without_the_library(tmp_path):
     from paper_2605_07114_amd import hora
     with pytest.raises(RuntimeError, match="no CPU fallback"):
