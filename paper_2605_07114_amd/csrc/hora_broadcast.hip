@@ -7,22 +7,27 @@
 // whatever the response boundaries are.
 //
 // Pass 1 (k_row_desc, one thread per response): checks the packed offsets and writes one
-// descriptor per row: the ends (relative to the row) of the first four responses that
-// intersect the row and the advantages of the first five, already converted to the
-// output type.  It runs while the memory system is idle, so that pass 2 needs neither a
-// search nor a second dependent load under write load.
+// short descriptor per row: the ends (relative to the row) of the first two responses
+// that intersect the row and the advantages of the first three, already converted to the
+// output type.  A row that more responses intersect gets a flag there and a wide
+// descriptor (four ends, five advantages) in a second array.  It runs while the memory
+// system is idle, so that pass 2 needs neither a search nor, for most rows, a second
+// dependent load under write load.
 //
 // Pass 2 (k_token_fill): a workgroup owns kRows rows; the kGroup workgroups of a
 // super-tile interleave their rows (workgroup g writes rows g, g + kGroup, ...), so the
 // workgroups that run at the same time write one compact window of memory.  Every
-// wavefront reads the descriptors of its rows with scalar loads (issued together, one
-// wait), then each lane picks the response of its vector by comparing its position with
-// the four ends; a wavefront whose 1 KiB lies inside one response takes a splat path
-// decided by scalar compares.  No LDS, no barrier, and no vector load in the streaming
-// part: loads and stores share one memory counter on this part, and a load in the loop
-// body would make every store wait for the one before it.  Rows that intersect more
-// than five responses (runs of very short or empty responses) are flagged by pass 1 and
-// handled afterwards by a search of the packed offsets in global memory.
+// wavefront reads the short descriptors of its rows with one scalar load, then each lane
+// picks the response of its vector by comparing its position with the ends; a wavefront
+// whose 1 KiB lies inside one response takes a splat path decided by scalar compares.
+// No LDS, no barrier, and no vector load in the streaming part: loads and stores share
+// one memory counter on this part, and a load in the loop body would make every store
+// wait for the one before it.  What limits the kernel besides the stores is the number of
+// cache lines of descriptors fetched under write load, so the short descriptors of a
+// workgroup lie next to one another and those of workgroups that run on the same die
+// (workgroup index modulo 8) share cache lines.  Flagged rows are done afterwards, out of
+// line: through the wide descriptor, or, when more than five responses intersect the row
+// (runs of very short or empty responses), by a search of the packed offsets.
 #include <hip/hip_runtime.h>
 
 #include <climits>
@@ -35,10 +40,14 @@ namespace hora {
 
 constexpr int kBcastThreads = 256;   // threads per workgroup of the fill kernel
 constexpr int kRows = 2;             // rows (16-byte vectors per thread) per workgroup
-constexpr int kGroupShift = 4;       // log2 of the workgroups that share a super-tile
+constexpr int kGroupShift = 6;       // log2 of the workgroups that share a super-tile
 constexpr int kGroup = 1 << kGroupShift;
-constexpr int kEnds = 4;             // response ends held by a row descriptor
-constexpr int kVals = kEnds + 1;     // advantages held by a row descriptor
+constexpr int kEnds = 4;             // response ends held by a wide row descriptor
+constexpr int kVals = kEnds + 1;     // advantages held by a wide row descriptor
+constexpr int kShortEnds = 2;        // the same for a short descriptor
+constexpr int kShortVals = kShortEnds + 1;
+constexpr int kDies = 8;             // workgroup w runs on die w % kDies
+constexpr int kDieBlock = 64;        // workgroups whose short descriptors are regrouped by die
 constexpr unsigned kOverflowBit = 0x80000000u;
 
 typedef unsigned v4u __attribute__((ext_vector_type(4)));
@@ -47,70 +56,133 @@ template <typename O> struct VecOf;
 template <> struct VecOf<float> { typedef v4f type; static constexpr int n = 4; };
 template <> struct VecOf<double> { typedef v2d type; static constexpr int n = 2; };
 
-// Row descriptor, an array of 32-bit words (little endian):
-//   words [0, kEnds/2)          ends[k], 16 bits each: end of the k-th response that
+// Row descriptor with E ends, an array of 32-bit words (little endian):
+//   words [0, E/2)              ends[k], 16 bits each: end of the k-th response that
 //                               intersects the row, as an element index relative to the
 //                               row, clamped to [0, row length]; unused entries hold the
 //                               row length
-//   then kVals values of type O vals[k]: advantage of that response
-//   then one word               first: index of the response that holds the row's first
-//                               token; bit 31 is set when more than kVals responses
-//                               intersect the row
-// padded to a power of two (32 bytes for float, 64 for double output with kEnds = 4).
-template <typename O> struct DescLayout {
+//   then E+1 values of type O   vals[k]: advantage of that response
+//   wide descriptors (E = kEnds) then hold one word `first`: index of the response that
+//   holds the row's first token, bit 31 set when more than E+1 responses intersect the
+//   row; short ones (E = kShortEnds) carry their flag in bit 31 of word 0 instead (a row
+//   has at most 1024 elements, so an end needs 11 of its 16 bits).
+// Padded to a power of two: short 16 / 32 bytes, wide 32 / 64 bytes (float / double).
+template <typename O, int E> struct DescLayout {
+    static constexpr bool kWide = E == kEnds;
     static constexpr int kValWords = (int)(sizeof(O) / 4);
-    static constexpr int kValBase = kEnds / 2;
-    static constexpr int kFirstWord = kValBase + kVals * kValWords;
-    static constexpr int kUsed = kFirstWord + 1;
-    static constexpr int kWords = kUsed <= 8 ? 8 : kUsed <= 16 ? 16 : kUsed <= 32 ? 32 : 64;
+    static constexpr int kEndWords = E / 2;
+    static constexpr int kValBase = kValWords == 2 ? (kEndWords + 1) / 2 * 2 : kEndWords;   // doubles on even words
+    static constexpr int kFirstWord = kValBase + (E + 1) * kValWords;
+    static constexpr int kUsed = kFirstWord + (kWide ? 1 : 0);
+    static constexpr int kWords = kUsed <= 4 ? 4 : kUsed <= 8 ? 8 : kUsed <= 16 ? 16 : kUsed <= 32 ? 32 : 64;
     static constexpr int kBytes = kWords * 4;
 };
-static_assert(kEnds % 4 == 0, "values of a double descriptor must be 8-byte aligned");
-template <typename O> struct alignas(DescLayout<O>::kBytes) RowDesc { unsigned u[DescLayout<O>::kWords]; };
+static_assert(kEnds % 2 == 0 && kShortEnds % 2 == 0, "two ends per word");
+static_assert(DescLayout<float, kShortEnds>::kBytes == 16 && DescLayout<double, kShortEnds>::kBytes == 32, "short");
+static_assert(DescLayout<float, kEnds>::kBytes == 32 && DescLayout<double, kEnds>::kBytes == 64, "wide");
+template <typename O, int E> struct alignas(DescLayout<O, E>::kBytes) Desc { unsigned u[DescLayout<O, E>::kWords]; };
+template <typename O> using WideDesc = Desc<O, kEnds>;
+template <typename O> using ShortDesc = Desc<O, kShortEnds>;
 
 __device__ __forceinline__ unsigned val_word(float v, int) { return __float_as_uint(v); }
 __device__ __forceinline__ unsigned val_word(double v, int half) {
     return (unsigned)(half ? __double2hiint(v) : __double2loint(v));
 }
 
-template <typename O>
-__device__ __forceinline__ RowDesc<O> load_row_desc(const RowDesc<O>* __restrict__ desc, long long row) {
-    RowDesc<O> x;
-    const v4u* src = reinterpret_cast<const v4u*>(desc + row);
+// n descriptors that lie next to one another, fetched with 16-byte loads (scalar loads when
+// the address is uniform)
+template <typename O, int E, int N>
+__device__ __forceinline__ void load_descs(const Desc<O, E>* __restrict__ src, Desc<O, E> (&x)[N]) {
+    constexpr int kQuads = DescLayout<O, E>::kWords / 4;
+    const v4u* q = reinterpret_cast<const v4u*>(src);
 #pragma unroll
-    for (int i = 0; i < DescLayout<O>::kWords / 4; ++i) {
-        const v4u q = src[i];
-        x.u[4 * i] = q.x; x.u[4 * i + 1] = q.y; x.u[4 * i + 2] = q.z; x.u[4 * i + 3] = q.w;
+    for (int i = 0; i < N * kQuads; ++i) {
+        const v4u w = q[i];
+        unsigned* dst = x[i / kQuads].u + 4 * (i % kQuads);
+        dst[0] = w.x; dst[1] = w.y; dst[2] = w.z; dst[3] = w.w;
     }
-    return x;
 }
-template <typename O>
-__device__ __forceinline__ int desc_end(const RowDesc<O>& x, int k) {
+template <typename O, int E>
+__device__ __forceinline__ void store_desc(Desc<O, E>* __restrict__ dst, const Desc<O, E>& d) {
+    v4u* q = reinterpret_cast<v4u*>(dst);
+#pragma unroll
+    for (int i = 0; i < DescLayout<O, E>::kWords / 4; ++i) {
+        const v4u w = {d.u[4 * i], d.u[4 * i + 1], d.u[4 * i + 2], d.u[4 * i + 3]};
+        q[i] = w;
+    }
+}
+template <typename O, int E>
+__device__ __forceinline__ int desc_end(const Desc<O, E>& x, int k) {
     const unsigned pair = x.u[k >> 1];
-    return (int)((k & 1) ? pair >> 16 : pair & 0xffffu);
+    return (int)((k & 1) ? (pair >> 16) & 0x7fffu : pair & 0xffffu);
 }
-__device__ __forceinline__ float desc_val(const RowDesc<float>& x, int k) {
-    return __uint_as_float(x.u[DescLayout<float>::kValBase + k]);
+template <int E>
+__device__ __forceinline__ float desc_val(const Desc<float, E>& x, int k) {
+    return __uint_as_float(x.u[DescLayout<float, E>::kValBase + k]);
 }
-__device__ __forceinline__ double desc_val(const RowDesc<double>& x, int k) {
-    return __hiloint2double((int)x.u[DescLayout<double>::kValBase + 2 * k + 1],
-                            (int)x.u[DescLayout<double>::kValBase + 2 * k]);
+template <int E>
+__device__ __forceinline__ double desc_val(const Desc<double, E>& x, int k) {
+    return __hiloint2double((int)x.u[DescLayout<double, E>::kValBase + 2 * k + 1],
+                            (int)x.u[DescLayout<double, E>::kValBase + 2 * k]);
 }
 template <typename O>
-__device__ __forceinline__ unsigned desc_first(const RowDesc<O>& x) { return x.u[DescLayout<O>::kFirstWord]; }
+__device__ __forceinline__ unsigned desc_first(const WideDesc<O>& x) { return x.u[DescLayout<O, kEnds>::kFirstWord]; }
+template <typename O>
+__device__ __forceinline__ bool desc_flagged(const ShortDesc<O>& x) { return (x.u[0] & kOverflowBit) != 0; }
+
+// Fills the ends and values of a descriptor from the ends e[] (tokens, clamped) and the
+// advantages v[] of consecutive responses, for the row whose element 0 is token row_first.
+template <typename O, int E, int N>
+__device__ __forceinline__ void set_desc(Desc<O, E>& d, const long long (&e)[N], const O (&v)[N], long long row_first,
+                                         int row_elems) {
+    static_assert(N >= E + 1, "enough responses loaded");
+#pragma unroll
+    for (int i = 0; i < DescLayout<O, E>::kWords; ++i) d.u[i] = 0u;
+#pragma unroll
+    for (int k = 0; k < E; ++k) {
+        long long rel = e[k] - row_first;
+        rel = rel < 0 ? 0 : (rel > row_elems ? row_elems : rel);
+        d.u[k >> 1] |= (unsigned)rel << (16 * (k & 1));
+    }
+#pragma unroll
+    for (int k = 0; k < E + 1; ++k)
+#pragma unroll
+        for (int h = 0; h < DescLayout<O, E>::kValWords; ++h)
+            d.u[DescLayout<O, E>::kValBase + k * DescLayout<O, E>::kValWords + h] = val_word(v[k], h);
+}
+
+// Where the short descriptors of workgroup w start (in descriptors): workgroup-major, and
+// inside every block of kDieBlock workgroups those with the same w % kDies lie together.
+__host__ __device__ __forceinline__ long long short_slot(long long w) {
+    const long long block = w & ~(long long)(kDieBlock - 1);
+    const int within = (int)(w & (kDieBlock - 1));
+    return (block + (within % kDies) * (kDieBlock / kDies) + within / kDies) * kRows;
+}
+// The workgroup that owns row r, and which of its rows it is.
+__host__ __device__ __forceinline__ long long row_owner(long long row, int& k) {
+    const long long super = row / (kRows * kGroup);
+    const int within = (int)(row - super * (kRows * kGroup));
+    k = within >> kGroupShift;
+    return (super << kGroupShift) + (within & (kGroup - 1));
+}
+// Short-descriptor slots that n_rows rows take up (whole blocks of workgroups).
+__host__ __device__ __forceinline__ long long short_slots(long long n_rows) {
+    const long long wgs = (n_rows + kRows * kGroup - 1) / (kRows * kGroup) * kGroup;
+    return (wgs + kDieBlock - 1) / kDieBlock * kDieBlock * kRows;
+}
 
 // ----------------------------------------------------------------------------------
 // Pass 1.  Row r holds the elements q in [r*row_elems, (r+1)*row_elems) of the aligned
 // index space q = token + skew.  The response that holds a row's first token writes the
-// row's descriptor.  Also the data checks: offsets start at 0, do not decrease, and end
+// row's descriptors.  Also the data checks: offsets start at 0, do not decrease, and end
 // at n_tokens.  Offsets are clamped to [0, n_tokens] before use, so that bad data cannot
 // move any access outside the buffers.
 // ----------------------------------------------------------------------------------
 template <typename A, typename O, typename I>
 __global__ __launch_bounds__(kThreads) void k_row_desc(long long n_resp, const A* __restrict__ adv,
                                                        const I* __restrict__ tok_off, long long n_tokens, int skew,
-                                                       long long n_rows, RowDesc<O>* __restrict__ desc,
-                                                       int32_t* dev_status) {
+                                                       long long n_rows, ShortDesc<O>* __restrict__ short_desc,
+                                                       WideDesc<O>* __restrict__ wide_desc, int32_t* dev_status) {
     constexpr int kRowElems = kBcastThreads * VecOf<O>::n;
     const long long stride = (long long)gridDim.x * kThreads;
     bool bad = false;
@@ -139,28 +211,20 @@ __global__ __launch_bounds__(kThreads) void k_row_desc(long long n_resp, const A
         if (r_max > n_rows - 1) r_max = n_rows - 1;
         for (long long r = r_min; r <= r_max; ++r) {
             const long long row_first = r * kRowElems - skew;   // token of the row's element 0
-            RowDesc<O> d;
-#pragma unroll
-            for (int i = 0; i < DescLayout<O>::kWords; ++i) d.u[i] = 0u;
-#pragma unroll
-            for (int k = 0; k < kEnds; ++k) {
-                long long rel = e[k] - row_first;
-                rel = rel < 0 ? 0 : (rel > kRowElems ? kRowElems : rel);
-                d.u[k >> 1] |= (unsigned)rel << (16 * (k & 1));
-            }
-#pragma unroll
-            for (int k = 0; k < kVals; ++k)
-#pragma unroll
-                for (int h = 0; h < DescLayout<O>::kValWords; ++h)
-                    d.u[DescLayout<O>::kValBase + k * DescLayout<O>::kValWords + h] = val_word(v[k], h);
             long long row_end = row_first + kRowElems;
             if (row_end > n_tokens) row_end = n_tokens;
-            d.u[DescLayout<O>::kFirstWord] = (unsigned)j | (e[kVals - 1] < row_end ? kOverflowBit : 0u);
-            v4u* dst = reinterpret_cast<v4u*>(desc + r);
-#pragma unroll
-            for (int i = 0; i < DescLayout<O>::kWords / 4; ++i) {
-                v4u q = {d.u[4 * i], d.u[4 * i + 1], d.u[4 * i + 2], d.u[4 * i + 3]};
-                dst[i] = q;
+            const bool wide = e[kShortVals - 1] < row_end;      // more than kShortVals responses
+            ShortDesc<O> d;
+            set_desc<O, kShortEnds, kVals>(d, e, v, row_first, kRowElems);
+            if (wide) d.u[0] |= kOverflowBit;
+            int k;
+            const long long w = row_owner(r, k);
+            store_desc<O, kShortEnds>(short_desc + short_slot(w) + k, d);
+            if (wide) {
+                WideDesc<O> x;
+                set_desc<O, kEnds, kVals>(x, e, v, row_first, kRowElems);
+                x.u[DescLayout<O, kEnds>::kFirstWord] = (unsigned)j | (e[kVals - 1] < row_end ? kOverflowBit : 0u);
+                store_desc<O, kEnds>(wide_desc + r, x);
             }
         }
     }
@@ -194,27 +258,27 @@ __device__ __forceinline__ void store_vec(O* __restrict__ out, long long row, lo
     }
 }
 
-template <typename O>
-__device__ __forceinline__ void fill_row(const RowDesc<O>& d, O* __restrict__ out, long long row, long long n_rows,
+template <typename O, int E>
+__device__ __forceinline__ void fill_row(const Desc<O, E>& d, O* __restrict__ out, long long row, long long n_rows,
                                          long long n_tokens, int skew) {
     constexpr int kVec = VecOf<O>::n;
     constexpr int kRowElems = kBcastThreads * kVec;
     constexpr int kWaveElems = kWave * kVec;
     const long long row_first = row * kRowElems - skew;
     const int r0 = (int)threadIdx.x * kVec;
-    int e[kEnds];
-    O v[kVals];
+    int e[E];
+    O v[E + 1];
 #pragma unroll
-    for (int k = 0; k < kEnds; ++k) e[k] = desc_end(d, k);
+    for (int k = 0; k < E; ++k) e[k] = desc_end(d, k);
 #pragma unroll
-    for (int k = 0; k < kVals; ++k) v[k] = desc_val(d, k);
+    for (int k = 0; k < E + 1; ++k) v[k] = desc_val(d, k);
     // the wavefront's elements [w0, w1) of the row: when the first and the last of them
     // belong to the same response, all of them do
     const int w0 = __builtin_amdgcn_readfirstlane(r0) & ~(kWaveElems - 1);
     const int w1 = w0 + kWaveElems;
     int s_first = 0, s_last = 0;
 #pragma unroll
-    for (int k = 0; k < kEnds; ++k) {
+    for (int k = 0; k < E; ++k) {
         s_first += (int)(e[k] <= w0);
         s_last += (int)(e[k] < w1);
     }
@@ -222,7 +286,7 @@ __device__ __forceinline__ void fill_row(const RowDesc<O>& d, O* __restrict__ ou
     if (s_first == s_last) {
         O x = v[0];
 #pragma unroll
-        for (int k = 1; k < kVals; ++k) x = s_first >= k ? v[k] : x;
+        for (int k = 1; k < E + 1; ++k) x = s_first >= k ? v[k] : x;
 #pragma unroll
         for (int i = 0; i < kVec; ++i) vals[i] = x;
     } else {
@@ -231,7 +295,7 @@ __device__ __forceinline__ void fill_row(const RowDesc<O>& d, O* __restrict__ ou
             const int p = r0 + i;
             O x = v[0];
 #pragma unroll
-            for (int k = 0; k < kEnds; ++k) x = p >= e[k] ? v[k + 1] : x;
+            for (int k = 0; k < E; ++k) x = p >= e[k] ? v[k + 1] : x;
             vals[i] = x;
         }
     }
@@ -240,11 +304,11 @@ __device__ __forceinline__ void fill_row(const RowDesc<O>& d, O* __restrict__ ou
 
 // A row that more than kVals responses intersect: every lane searches the packed offsets
 // for the response of its first element, starting from the response of the row's first
-// token.  Kept out of line: its loads must not sit between the stores of the fast rows.
+// token.
 template <typename A, typename O, typename I>
-__device__ __noinline__ void fill_row_by_search(unsigned first, long long n_resp, const A* __restrict__ adv,
-                                                const I* __restrict__ tok_off, O* __restrict__ out, long long row,
-                                                long long n_rows, long long n_tokens, int skew) {
+__device__ __forceinline__ void fill_row_by_search(unsigned first, long long n_resp, const A* __restrict__ adv,
+                                                   const I* __restrict__ tok_off, O* __restrict__ out, long long row,
+                                                   long long n_rows, long long n_tokens, int skew) {
     constexpr int kVec = VecOf<O>::n;
     constexpr int kRowElems = kBcastThreads * kVec;
     const long long row_first = row * kRowElems - skew;
@@ -267,34 +331,45 @@ __device__ __noinline__ void fill_row_by_search(unsigned first, long long n_resp
     store_vec<O>(out, row, n_rows, row_first, n_tokens, r0, vals);
 }
 
+// A row whose short descriptor is flagged: through its wide descriptor, or by the search.
+// Kept out of line: its loads must not sit between the stores of the other rows.
+template <typename A, typename O, typename I>
+__device__ __noinline__ void fill_flagged_row(const WideDesc<O>* __restrict__ wide_desc, long long n_resp,
+                                              const A* __restrict__ adv, const I* __restrict__ tok_off,
+                                              O* __restrict__ out, long long row, long long n_rows,
+                                              long long n_tokens, int skew) {
+    WideDesc<O> x[1];
+    load_descs<O, kEnds, 1>(wide_desc + row, x);
+    const unsigned first = desc_first(x[0]);
+    if (first & kOverflowBit) fill_row_by_search<A, O, I>(first, n_resp, adv, tok_off, out, row, n_rows, n_tokens, skew);
+    else fill_row<O, kEnds>(x[0], out, row, n_rows, n_tokens, skew);
+}
+
 template <typename A, typename O, typename I>
 __global__ __launch_bounds__(kBcastThreads) void k_token_fill(long long n_resp, const A* __restrict__ adv,
                                                               const I* __restrict__ tok_off, O* __restrict__ out,
                                                               long long n_tokens, int skew, long long n_rows,
-                                                              const RowDesc<O>* __restrict__ desc) {
+                                                              const ShortDesc<O>* __restrict__ short_desc,
+                                                              const WideDesc<O>* __restrict__ wide_desc) {
     const long long super = blockIdx.x >> kGroupShift;
     const long long member = blockIdx.x & (kGroup - 1);
     const long long row0 = ((super * kRows) << kGroupShift) + member;   // row k of this workgroup = row0 + k * kGroup
-    RowDesc<O> d[kRows];
-#pragma unroll
-    for (int k = 0; k < kRows; ++k) {   // all descriptor loads first: one wait for the lot
-        const long long row = row0 + ((long long)k << kGroupShift);
-        d[k] = load_row_desc<O>(desc, row < n_rows ? row : n_rows - 1);
-    }
-    bool any_search = false;
+    ShortDesc<O> d[kRows];   // (slots of rows past the end are read but never used)
+    load_descs<O, kShortEnds, kRows>(short_desc + short_slot((long long)blockIdx.x), d);
+    bool any_flagged = false;
 #pragma unroll
     for (int k = 0; k < kRows; ++k) {
         const long long row = row0 + ((long long)k << kGroupShift);
         if (row < n_rows) {
-            if (desc_first(d[k]) & kOverflowBit) any_search = true;
-            else fill_row<O>(d[k], out, row, n_rows, n_tokens, skew);
+            if (desc_flagged(d[k])) any_flagged = true;
+            else fill_row<O, kShortEnds>(d[k], out, row, n_rows, n_tokens, skew);
         }
     }
-    if (any_search) {
+    if (any_flagged) {
         for (int k = 0; k < kRows; ++k) {
             const long long row = row0 + ((long long)k << kGroupShift);
-            if (row < n_rows && (desc_first(d[k]) & kOverflowBit))
-                fill_row_by_search<A, O, I>(desc_first(d[k]), n_resp, adv, tok_off, out, row, n_rows, n_tokens, skew);
+            if (row < n_rows && desc_flagged(d[k]))
+                fill_flagged_row<A, O, I>(wide_desc, n_resp, adv, tok_off, out, row, n_rows, n_tokens, skew);
         }
     }
 }
@@ -305,24 +380,36 @@ static long long rows_for(int64_t n_tokens, int skew) {
     return (n_tokens + skew + row_elems - 1) / row_elems;
 }
 
+// Workspace: the short descriptors (whole blocks of workgroups), then the wide ones (one
+// slot per row), both 256-byte aligned.
+template <typename O>
+static size_t short_area_bytes(long long n_rows) {
+    return ((size_t)short_slots(n_rows) * sizeof(ShortDesc<O>) + 255) & ~(size_t)255;
+}
+template <typename O>
+static size_t workspace_for(long long n_rows) {
+    return short_area_bytes<O>(n_rows) + (((size_t)n_rows * sizeof(WideDesc<O>) + 255) & ~(size_t)255);
+}
+
 template <typename A, typename O, typename I>
 static int launch_broadcast(int64_t n_resp, const void* adv, const void* tok_off, void* out, int64_t n_tokens,
                             int32_t* dev_status, void* workspace, size_t workspace_bytes, hipStream_t stream) {
     const int skew = (int)((reinterpret_cast<uintptr_t>(out) & 15) / sizeof(O));
     const long long n_rows = rows_for<O>(n_tokens, skew);
-    if ((size_t)(n_rows + 1) * sizeof(RowDesc<O>) > workspace_bytes) return HORA_ERR_WORKSPACE;
-    RowDesc<O>* desc = (RowDesc<O>*)workspace;
+    if (workspace_for<O>(n_rows) > workspace_bytes) return HORA_ERR_WORKSPACE;
+    ShortDesc<O>* short_desc = (ShortDesc<O>*)workspace;
+    WideDesc<O>* wide_desc = (WideDesc<O>*)((char*)workspace + short_area_bytes<O>(n_rows));
     long long blocks1 = (n_resp + kThreads - 1) / kThreads;
     if (blocks1 > 65536) blocks1 = 65536;
     hipLaunchKernelGGL((k_row_desc<A, O, I>), dim3((unsigned)blocks1), dim3(kThreads), 0, stream,
-                       (long long)n_resp, (const A*)adv, (const I*)tok_off, (long long)n_tokens, skew, n_rows, desc,
-                       dev_status);
+                       (long long)n_resp, (const A*)adv, (const I*)tok_off, (long long)n_tokens, skew, n_rows,
+                       short_desc, wide_desc, dev_status);
     if (n_rows > 0) {
         const long long supers = (n_rows + kGroup * kRows - 1) / (kGroup * kRows);
         if (supers * kGroup > INT_MAX) return HORA_ERR_UNSUPPORTED;
         hipLaunchKernelGGL((k_token_fill<A, O, I>), dim3((unsigned)(supers * kGroup)), dim3(kBcastThreads), 0,
                            stream, (long long)n_resp, (const A*)adv, (const I*)tok_off, (O*)out,
-                           (long long)n_tokens, skew, n_rows, desc);
+                           (long long)n_tokens, skew, n_rows, short_desc, wide_desc);
     }
     return hipGetLastError() == hipSuccess ? HORA_OK : HORA_ERR_HIP;
 }
@@ -333,9 +420,10 @@ using namespace hora;
 
 extern "C" size_t hora_token_broadcast_workspace_bytes(int64_t n_tokens, int32_t out_t) {
     if (n_tokens < 0 || (out_t != HORA_F32 && out_t != HORA_F64)) return 0;
-    const size_t bytes = out_t == HORA_F32 ? (size_t)(rows_for<float>(n_tokens, 3) + 1) * sizeof(RowDesc<float>)
-                                           : (size_t)(rows_for<double>(n_tokens, 1) + 1) * sizeof(RowDesc<double>);
-    return (bytes + 255) & ~(size_t)255;
+    // the largest skew a caller's pointer can have gives the most rows
+    const size_t bytes = out_t == HORA_F32 ? workspace_for<float>(rows_for<float>(n_tokens, 3))
+                                           : workspace_for<double>(rows_for<double>(n_tokens, 1));
+    return bytes == 0 ? 256 : bytes;
 }
 
 extern "C" int hora_token_broadcast(int64_t n_resp, const void* adv, int32_t adv_t, const void* tok_off,
@@ -356,7 +444,7 @@ extern "C" int hora_token_broadcast(int64_t n_resp, const void* adv, int32_t adv
     if ((reinterpret_cast<uintptr_t>(adv) & amask) || (reinterpret_cast<uintptr_t>(tok_adv) & omask) ||
         (reinterpret_cast<uintptr_t>(tok_off) & imask))
         return HORA_ERR_INVALID_ARG;
-    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 63)) return HORA_ERR_WORKSPACE;
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255)) return HORA_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
 #define HORA_BCAST(A, O)                                                                                      \
     (off_t == HORA_I32 ? launch_broadcast<A, O, int32_t>(n_resp, adv, tok_off, tok_adv, n_tokens, dev_status, \

@@ -162,6 +162,10 @@ def test_broadcast_shapes_and_edges(gpu, oracle):
         "mixed": rng.integers(0, 40000, 300),
         "ragged tail": np.array([16384 * 3 + 1]),
         "exact tiles": np.array([16384, 16384, 8192, 8192]),
+        # 2..6 responses per 4 KiB row: short descriptors, wide ones and the search, side by side
+        "a few per row": rng.integers(170, 520, 6000),
+        "short and long mixed": np.where(rng.random(4000) < 0.5, rng.integers(100, 300, 4000),
+                                         rng.integers(3000, 9000, 4000)),
     }
     for name, lengths in cases.items():
         off = lengths_to_off(lengths.astype(np.int64))
