@@ -268,8 +268,8 @@ int hora_response_weights(int64_t n_groups, const void *group_off, int32_t group
 
 /*
  * Bytes of workspace hora_token_broadcast needs for n_tokens tokens of type out_t
- * (per 4 KiB of output one short descriptor of 16 bytes for float, 32 for double output,
- * and room for a wide one of 32 / 64 bytes).  Device memory, 256-byte aligned, no
+ * (per 8 KiB of output one short descriptor of 32 bytes for float, 64 for double output,
+ * and room for a wide one of 64 / 128 bytes).  Device memory, 256-byte aligned, no
  * initialisation needed; two calls that may run concurrently need separate workspaces.
  */
 size_t hora_token_broadcast_workspace_bytes(int64_t n_tokens, int32_t out_t);

@@ -1,33 +1,30 @@
 // Per-token advantage broadcast (Sec. 3.1: the advantage of a response is the same
 // for all of its tokens).
 //
-// The output is cut into rows of 4 KiB (one 16-byte store per thread of a workgroup),
-// aligned to 16 bytes whatever the caller's pointer is.  Work is balanced by tokens,
-// not by responses, and every store is a 16-byte store to a 16-byte-aligned address
-// whatever the response boundaries are.
+// The output is cut into rows of 8 KiB, aligned to 16 bytes whatever the caller's pointer
+// is; a workgroup writes one row, every lane 32 consecutive bytes as two 16-byte stores.
+// Work is balanced by tokens, not by responses, and every store is a 16-byte store to a
+// 16-byte-aligned address whatever the response boundaries are.
 //
 // Pass 1 (k_row_desc, one thread per response): checks the packed offsets and writes one
-// short descriptor per row: the ends (relative to the row) of the first two responses
-// that intersect the row and the advantages of the first three, already converted to the
+// short descriptor per row: the ends (relative to the row) of the first four responses
+// that intersect the row and the advantages of the first five, already converted to the
 // output type.  A row that more responses intersect gets a flag there and a wide
-// descriptor (four ends, five advantages) in a second array.  It runs while the memory
+// descriptor (eight ends, nine advantages) in a second array.  It runs while the memory
 // system is idle, so that pass 2 needs neither a search nor, for most rows, a second
 // dependent load under write load.
 //
-// Pass 2 (k_token_fill): a workgroup owns kRows rows; the kGroup workgroups of a
-// super-tile interleave their rows (workgroup g writes rows g, g + kGroup, ...), so the
-// workgroups that run at the same time write one compact window of memory.  Every
-// wavefront reads the short descriptors of its rows with one scalar load, then each lane
-// picks the response of its vector by comparing its position with the ends; a wavefront
-// whose 1 KiB lies inside one response takes a splat path decided by scalar compares.
-// No LDS, no barrier, and no vector load in the streaming part: loads and stores share
-// one memory counter on this part, and a load in the loop body would make every store
-// wait for the one before it.  What limits the kernel besides the stores is the number of
-// cache lines of descriptors fetched under write load, so the short descriptors of a
-// workgroup lie next to one another and those of workgroups that run on the same die
-// (workgroup index modulo 8) share cache lines.  Flagged rows are done afterwards, out of
-// line: through the wide descriptor, or, when more than five responses intersect the row
-// (runs of very short or empty responses), by a search of the packed offsets.
+// Pass 2 (k_token_fill): every wavefront reads the short descriptor of its row with one
+// scalar load, then each lane picks the response of each of its elements by comparing
+// its position with the ends; a wavefront whose 2 KiB lie inside one response takes a
+// splat path decided by scalar compares.  No LDS, no barrier, and no vector load in the
+// streaming part: loads and stores share one memory counter on this part, and a load
+// between the stores would make every store wait for the one before it.  What limits the
+// kernel besides the stores is the number of cache lines of descriptors fetched under
+// write load, so the short descriptors of workgroups that run on the same die (workgroup
+// index modulo 8) share cache lines.  Flagged rows go out of line: through the wide
+// descriptor, or, when more than nine responses intersect the row (runs of very short or
+// empty responses), by a search of the packed offsets.
 #include <hip/hip_runtime.h>
 
 #include <climits>
@@ -39,12 +36,10 @@
 namespace hora {
 
 constexpr int kBcastThreads = 256;   // threads per workgroup of the fill kernel
-constexpr int kRows = 2;             // rows (16-byte vectors per thread) per workgroup
-constexpr int kGroupShift = 6;       // log2 of the workgroups that share a super-tile
-constexpr int kGroup = 1 << kGroupShift;
-constexpr int kEnds = 4;             // response ends held by a wide row descriptor
+constexpr int kLaneVecs = 2;         // consecutive 16-byte vectors a lane stores
+constexpr int kEnds = 8;             // response ends held by a wide row descriptor
 constexpr int kVals = kEnds + 1;     // advantages held by a wide row descriptor
-constexpr int kShortEnds = 2;        // the same for a short descriptor
+constexpr int kShortEnds = 4;        // the same for a short descriptor
 constexpr int kShortVals = kShortEnds + 1;
 constexpr int kDies = 8;             // workgroup w runs on die w % kDies
 constexpr int kDieBlock = 64;        // workgroups whose short descriptors are regrouped by die
@@ -56,6 +51,13 @@ template <typename O> struct VecOf;
 template <> struct VecOf<float> { typedef v4f type; static constexpr int n = 4; };
 template <> struct VecOf<double> { typedef v2d type; static constexpr int n = 2; };
 
+template <typename O> struct RowOf {
+    static constexpr int kLaneElems = kLaneVecs * VecOf<O>::n;        // elements a lane writes
+    static constexpr int kWaveElems = kWave * kLaneElems;             // elements a wavefront writes
+    static constexpr int kRowElems = kBcastThreads * kLaneElems;      // elements of a row
+};
+static_assert(RowOf<float>::kRowElems < (1 << 15), "an end and the flag share 16 bits");
+
 // Row descriptor with E ends, an array of 32-bit words (little endian):
 //   words [0, E/2)              ends[k], 16 bits each: end of the k-th response that
 //                               intersects the row, as an element index relative to the
@@ -64,9 +66,9 @@ template <> struct VecOf<double> { typedef v2d type; static constexpr int n = 2;
 //   then E+1 values of type O   vals[k]: advantage of that response
 //   wide descriptors (E = kEnds) then hold one word `first`: index of the response that
 //   holds the row's first token, bit 31 set when more than E+1 responses intersect the
-//   row; short ones (E = kShortEnds) carry their flag in bit 31 of word 0 instead (a row
-//   has at most 1024 elements, so an end needs 11 of its 16 bits).
-// Padded to a power of two: short 16 / 32 bytes, wide 32 / 64 bytes (float / double).
+//   row; short ones (E = kShortEnds) carry their flag in bit 31 of word 0 instead (the
+//   top bit of ends[1], which needs 12 of its 16 bits).
+// Padded to a power of two: short 32 / 64 bytes, wide 64 / 128 bytes (float / double).
 template <typename O, int E> struct DescLayout {
     static constexpr bool kWide = E == kEnds;
     static constexpr int kValWords = (int)(sizeof(O) / 4);
@@ -77,9 +79,9 @@ template <typename O, int E> struct DescLayout {
     static constexpr int kWords = kUsed <= 4 ? 4 : kUsed <= 8 ? 8 : kUsed <= 16 ? 16 : kUsed <= 32 ? 32 : 64;
     static constexpr int kBytes = kWords * 4;
 };
-static_assert(kEnds % 2 == 0 && kShortEnds % 2 == 0, "two ends per word");
-static_assert(DescLayout<float, kShortEnds>::kBytes == 16 && DescLayout<double, kShortEnds>::kBytes == 32, "short");
-static_assert(DescLayout<float, kEnds>::kBytes == 32 && DescLayout<double, kEnds>::kBytes == 64, "wide");
+static_assert(kEnds % 2 == 0 && kShortEnds % 2 == 0 && kShortEnds < kEnds, "two ends per word");
+static_assert(DescLayout<float, kShortEnds>::kBytes == 32 && DescLayout<double, kShortEnds>::kBytes == 64, "short");
+static_assert(DescLayout<float, kEnds>::kBytes == 64 && DescLayout<double, kEnds>::kBytes == 128, "wide");
 template <typename O, int E> struct alignas(DescLayout<O, E>::kBytes) Desc { unsigned u[DescLayout<O, E>::kWords]; };
 template <typename O> using WideDesc = Desc<O, kEnds>;
 template <typename O> using ShortDesc = Desc<O, kShortEnds>;
@@ -89,18 +91,17 @@ __device__ __forceinline__ unsigned val_word(double v, int half) {
     return (unsigned)(half ? __double2hiint(v) : __double2loint(v));
 }
 
-// n descriptors that lie next to one another, fetched with 16-byte loads (scalar loads when
-// the address is uniform)
-template <typename O, int E, int N>
-__device__ __forceinline__ void load_descs(const Desc<O, E>* __restrict__ src, Desc<O, E> (&x)[N]) {
-    constexpr int kQuads = DescLayout<O, E>::kWords / 4;
+// One descriptor, fetched with 16-byte loads (scalar loads when the address is uniform).
+template <typename O, int E>
+__device__ __forceinline__ Desc<O, E> load_desc(const Desc<O, E>* __restrict__ src) {
+    Desc<O, E> x;
     const v4u* q = reinterpret_cast<const v4u*>(src);
 #pragma unroll
-    for (int i = 0; i < N * kQuads; ++i) {
+    for (int i = 0; i < DescLayout<O, E>::kWords / 4; ++i) {
         const v4u w = q[i];
-        unsigned* dst = x[i / kQuads].u + 4 * (i % kQuads);
-        dst[0] = w.x; dst[1] = w.y; dst[2] = w.z; dst[3] = w.w;
+        x.u[4 * i] = w.x; x.u[4 * i + 1] = w.y; x.u[4 * i + 2] = w.z; x.u[4 * i + 3] = w.w;
     }
+    return x;
 }
 template <typename O, int E>
 __device__ __forceinline__ void store_desc(Desc<O, E>* __restrict__ dst, const Desc<O, E>& d) {
@@ -133,15 +134,15 @@ __device__ __forceinline__ bool desc_flagged(const ShortDesc<O>& x) { return (x.
 // Fills the ends and values of a descriptor from the ends e[] (tokens, clamped) and the
 // advantages v[] of consecutive responses, for the row whose element 0 is token row_first.
 template <typename O, int E, int N>
-__device__ __forceinline__ void set_desc(Desc<O, E>& d, const long long (&e)[N], const O (&v)[N], long long row_first,
-                                         int row_elems) {
+__device__ __forceinline__ void set_desc(Desc<O, E>& d, const long long (&e)[N], const O (&v)[N], long long row_first) {
     static_assert(N >= E + 1, "enough responses loaded");
+    constexpr int kRowElems = RowOf<O>::kRowElems;
 #pragma unroll
     for (int i = 0; i < DescLayout<O, E>::kWords; ++i) d.u[i] = 0u;
 #pragma unroll
     for (int k = 0; k < E; ++k) {
         long long rel = e[k] - row_first;
-        rel = rel < 0 ? 0 : (rel > row_elems ? row_elems : rel);
+        rel = rel < 0 ? 0 : (rel > kRowElems ? kRowElems : rel);
         d.u[k >> 1] |= (unsigned)rel << (16 * (k & 1));
     }
 #pragma unroll
@@ -151,24 +152,16 @@ __device__ __forceinline__ void set_desc(Desc<O, E>& d, const long long (&e)[N],
             d.u[DescLayout<O, E>::kValBase + k * DescLayout<O, E>::kValWords + h] = val_word(v[k], h);
 }
 
-// Where the short descriptors of workgroup w start (in descriptors): workgroup-major, and
-// inside every block of kDieBlock workgroups those with the same w % kDies lie together.
-__host__ __device__ __forceinline__ long long short_slot(long long w) {
-    const long long block = w & ~(long long)(kDieBlock - 1);
-    const int within = (int)(w & (kDieBlock - 1));
-    return (block + (within % kDies) * (kDieBlock / kDies) + within / kDies) * kRows;
+// Where the short descriptor of row r (written by workgroup r) is kept: inside every
+// block of kDieBlock rows those with the same r % kDies lie together.
+__host__ __device__ __forceinline__ long long short_slot(long long row) {
+    const long long block = row & ~(long long)(kDieBlock - 1);
+    const int within = (int)(row & (kDieBlock - 1));
+    return block + (within % kDies) * (kDieBlock / kDies) + within / kDies;
 }
-// The workgroup that owns row r, and which of its rows it is.
-__host__ __device__ __forceinline__ long long row_owner(long long row, int& k) {
-    const long long super = row / (kRows * kGroup);
-    const int within = (int)(row - super * (kRows * kGroup));
-    k = within >> kGroupShift;
-    return (super << kGroupShift) + (within & (kGroup - 1));
-}
-// Short-descriptor slots that n_rows rows take up (whole blocks of workgroups).
+// Short-descriptor slots that n_rows rows take up (whole blocks).
 __host__ __device__ __forceinline__ long long short_slots(long long n_rows) {
-    const long long wgs = (n_rows + kRows * kGroup - 1) / (kRows * kGroup) * kGroup;
-    return (wgs + kDieBlock - 1) / kDieBlock * kDieBlock * kRows;
+    return (n_rows + kDieBlock - 1) / kDieBlock * kDieBlock;
 }
 
 // ----------------------------------------------------------------------------------
@@ -183,17 +176,17 @@ __global__ __launch_bounds__(kThreads) void k_row_desc(long long n_resp, const A
                                                        const I* __restrict__ tok_off, long long n_tokens, int skew,
                                                        long long n_rows, ShortDesc<O>* __restrict__ short_desc,
                                                        WideDesc<O>* __restrict__ wide_desc, int32_t* dev_status) {
-    constexpr int kRowElems = kBcastThreads * VecOf<O>::n;
+    constexpr int kRowElems = RowOf<O>::kRowElems;
     const long long stride = (long long)gridDim.x * kThreads;
     bool bad = false;
     for (long long j = (long long)blockIdx.x * kThreads + threadIdx.x; j < n_resp; j += stride) {
-        // every load of this response up front (one round trip): its start, the ends of
-        // the kVals responses from it on, and their advantages
+        // the loads a short descriptor needs up front (one round trip): the start of the
+        // response, the ends of the kShortVals responses from it on, and their advantages
         long long a = (long long)tok_off[j];
         long long e[kVals];
         O v[kVals];
 #pragma unroll
-        for (int k = 0; k < kVals; ++k) {
+        for (int k = 0; k < kShortVals; ++k) {
             e[k] = j + k < n_resp ? (long long)tok_off[j + 1 + k] : n_tokens;
             v[k] = j + k < n_resp ? (O)adv[j + k] : (O)0;
         }
@@ -203,26 +196,34 @@ __global__ __launch_bounds__(kThreads) void k_row_desc(long long n_resp, const A
         if (j == n_resp - 1) bad |= b != n_tokens;
         a = a < 0 ? 0 : (a > n_tokens ? n_tokens : a);
 #pragma unroll
-        for (int k = 0; k < kVals; ++k) e[k] = e[k] < 0 ? 0 : (e[k] > n_tokens ? n_tokens : e[k]);
+        for (int k = 0; k < kShortVals; ++k) e[k] = e[k] < 0 ? 0 : (e[k] > n_tokens ? n_tokens : e[k]);
         b = e[0];
         if (b <= a) continue;
         const long long r_min = a == 0 ? 0 : (a + skew + kRowElems - 1) / kRowElems;
         long long r_max = (b - 1 + skew) / kRowElems;
         if (r_max > n_rows - 1) r_max = n_rows - 1;
+        bool have_rest = false;
         for (long long r = r_min; r <= r_max; ++r) {
             const long long row_first = r * kRowElems - skew;   // token of the row's element 0
             long long row_end = row_first + kRowElems;
             if (row_end > n_tokens) row_end = n_tokens;
             const bool wide = e[kShortVals - 1] < row_end;      // more than kShortVals responses
             ShortDesc<O> d;
-            set_desc<O, kShortEnds, kVals>(d, e, v, row_first, kRowElems);
+            set_desc<O, kShortEnds, kVals>(d, e, v, row_first);
             if (wide) d.u[0] |= kOverflowBit;
-            int k;
-            const long long w = row_owner(r, k);
-            store_desc<O, kShortEnds>(short_desc + short_slot(w) + k, d);
+            store_desc<O, kShortEnds>(short_desc + short_slot(r), d);
             if (wide) {
+                if (!have_rest) {   // a second round of loads, for the few rows that need it
+#pragma unroll
+                    for (int k = kShortVals; k < kVals; ++k) {
+                        long long x = j + k < n_resp ? (long long)tok_off[j + 1 + k] : n_tokens;
+                        e[k] = x < 0 ? 0 : (x > n_tokens ? n_tokens : x);
+                        v[k] = j + k < n_resp ? (O)adv[j + k] : (O)0;
+                    }
+                    have_rest = true;
+                }
                 WideDesc<O> x;
-                set_desc<O, kEnds, kVals>(x, e, v, row_first, kRowElems);
+                set_desc<O, kEnds, kVals>(x, e, v, row_first);
                 x.u[DescLayout<O, kEnds>::kFirstWord] = (unsigned)j | (e[kVals - 1] < row_end ? kOverflowBit : 0u);
                 store_desc<O, kEnds>(wide_desc + r, x);
             }
@@ -234,26 +235,29 @@ __global__ __launch_bounds__(kThreads) void k_row_desc(long long n_resp, const A
 // ----------------------------------------------------------------------------------
 // Pass 2.
 // ----------------------------------------------------------------------------------
-// Stores one thread's vector of a row: whole where every element is a token, element by
-// element in the first and the last row of the output.
+// Stores one lane's elements of a row: whole vectors where every element of the row is a
+// token, element by element in the first and the last row of the output.
 template <typename O>
-__device__ __forceinline__ void store_vec(O* __restrict__ out, long long row, long long n_rows, long long row_first,
-                                          long long n_tokens, int r0, const O (&vals)[VecOf<O>::n]) {
+__device__ __forceinline__ void store_lane(O* __restrict__ out, long long row, long long n_rows, long long row_first,
+                                           long long n_tokens, int r0, const O (&vals)[RowOf<O>::kLaneElems]) {
     typedef typename VecOf<O>::type Vec;
     constexpr int kVec = VecOf<O>::n;
-    constexpr int kRowElems = kBcastThreads * kVec;
+    constexpr int kRowElems = RowOf<O>::kRowElems;
     O* dst = out + (row_first + r0);
     if (row > 0 && row < n_rows - 1) {
-        Vec v;
 #pragma unroll
-        for (int i = 0; i < kVec; ++i) v[i] = vals[i];
-        *reinterpret_cast<Vec*>(dst) = v;
+        for (int q = 0; q < kLaneVecs; ++q) {
+            Vec v;
+#pragma unroll
+            for (int i = 0; i < kVec; ++i) v[i] = vals[q * kVec + i];
+            reinterpret_cast<Vec*>(dst)[q] = v;
+        }
     } else {
         // elements of the row that are tokens: [rel_lo, rel_hi)
         const int rel_lo = row_first < 0 ? (int)(-row_first) : 0;
         const int rel_hi = n_tokens - row_first < kRowElems ? (int)(n_tokens - row_first) : kRowElems;
 #pragma unroll
-        for (int i = 0; i < kVec; ++i)
+        for (int i = 0; i < RowOf<O>::kLaneElems; ++i)
             if (r0 + i >= rel_lo && r0 + i < rel_hi) dst[i] = vals[i];
     }
 }
@@ -261,11 +265,10 @@ __device__ __forceinline__ void store_vec(O* __restrict__ out, long long row, lo
 template <typename O, int E>
 __device__ __forceinline__ void fill_row(const Desc<O, E>& d, O* __restrict__ out, long long row, long long n_rows,
                                          long long n_tokens, int skew) {
-    constexpr int kVec = VecOf<O>::n;
-    constexpr int kRowElems = kBcastThreads * kVec;
-    constexpr int kWaveElems = kWave * kVec;
-    const long long row_first = row * kRowElems - skew;
-    const int r0 = (int)threadIdx.x * kVec;
+    constexpr int kLaneElems = RowOf<O>::kLaneElems;
+    constexpr int kWaveElems = RowOf<O>::kWaveElems;
+    const long long row_first = row * RowOf<O>::kRowElems - skew;
+    const int r0 = (int)threadIdx.x * kLaneElems;
     int e[E];
     O v[E + 1];
 #pragma unroll
@@ -282,16 +285,16 @@ __device__ __forceinline__ void fill_row(const Desc<O, E>& d, O* __restrict__ ou
         s_first += (int)(e[k] <= w0);
         s_last += (int)(e[k] < w1);
     }
-    O vals[kVec];
+    O vals[kLaneElems];
     if (s_first == s_last) {
         O x = v[0];
 #pragma unroll
         for (int k = 1; k < E + 1; ++k) x = s_first >= k ? v[k] : x;
 #pragma unroll
-        for (int i = 0; i < kVec; ++i) vals[i] = x;
+        for (int i = 0; i < kLaneElems; ++i) vals[i] = x;
     } else {
 #pragma unroll
-        for (int i = 0; i < kVec; ++i) {
+        for (int i = 0; i < kLaneElems; ++i) {
             const int p = r0 + i;
             O x = v[0];
 #pragma unroll
@@ -299,7 +302,7 @@ __device__ __forceinline__ void fill_row(const Desc<O, E>& d, O* __restrict__ ou
             vals[i] = x;
         }
     }
-    store_vec<O>(out, row, n_rows, row_first, n_tokens, r0, vals);
+    store_lane<O>(out, row, n_rows, row_first, n_tokens, r0, vals);
 }
 
 // A row that more than kVals responses intersect: every lane searches the packed offsets
@@ -309,10 +312,9 @@ template <typename A, typename O, typename I>
 __device__ __forceinline__ void fill_row_by_search(unsigned first, long long n_resp, const A* __restrict__ adv,
                                                    const I* __restrict__ tok_off, O* __restrict__ out, long long row,
                                                    long long n_rows, long long n_tokens, int skew) {
-    constexpr int kVec = VecOf<O>::n;
-    constexpr int kRowElems = kBcastThreads * kVec;
-    const long long row_first = row * kRowElems - skew;
-    const int r0 = (int)threadIdx.x * kVec;
+    constexpr int kLaneElems = RowOf<O>::kLaneElems;
+    const long long row_first = row * RowOf<O>::kRowElems - skew;
+    const int r0 = (int)threadIdx.x * kLaneElems;
     const long long last = n_resp - 1;
     long long a = (long long)(first & ~kOverflowBit);
     a = a > last ? last : a;
@@ -322,66 +324,52 @@ __device__ __forceinline__ void fill_row_by_search(unsigned first, long long n_r
         const long long mid = (a + b) >> 1;
         if ((long long)tok_off[mid + 1] > p) b = mid; else a = mid + 1;
     }
-    O vals[kVec];
+    O vals[kLaneElems];
 #pragma unroll
-    for (int i = 0; i < kVec; ++i) {
+    for (int i = 0; i < kLaneElems; ++i) {
         while (a < last && (long long)tok_off[a + 1] <= p + i) ++a;
         vals[i] = (O)adv[a];
     }
-    store_vec<O>(out, row, n_rows, row_first, n_tokens, r0, vals);
+    store_lane<O>(out, row, n_rows, row_first, n_tokens, r0, vals);
 }
 
 // A row whose short descriptor is flagged: through its wide descriptor, or by the search.
-// Kept out of line: its loads must not sit between the stores of the other rows.
 template <typename A, typename O, typename I>
-__device__ __noinline__ void fill_flagged_row(const WideDesc<O>* __restrict__ wide_desc, long long n_resp,
+__device__ __forceinline__ void fill_flagged_row(const WideDesc<O>* __restrict__ wide_desc, long long n_resp,
                                               const A* __restrict__ adv, const I* __restrict__ tok_off,
                                               O* __restrict__ out, long long row, long long n_rows,
                                               long long n_tokens, int skew) {
-    WideDesc<O> x[1];
-    load_descs<O, kEnds, 1>(wide_desc + row, x);
-    const unsigned first = desc_first(x[0]);
+    const WideDesc<O> x = load_desc<O, kEnds>(wide_desc + row);
+    const unsigned first = desc_first(x);
     if (first & kOverflowBit) fill_row_by_search<A, O, I>(first, n_resp, adv, tok_off, out, row, n_rows, n_tokens, skew);
-    else fill_row<O, kEnds>(x[0], out, row, n_rows, n_tokens, skew);
+    else fill_row<O, kEnds>(x, out, row, n_rows, n_tokens, skew);
 }
 
+// (eight wavefronts per SIMD: the bytes in flight per compute unit are what hides the
+// latency of the stores, so the register count is held to what full occupancy allows)
 template <typename A, typename O, typename I>
-__global__ __launch_bounds__(kBcastThreads) void k_token_fill(long long n_resp, const A* __restrict__ adv,
+__global__ __launch_bounds__(kBcastThreads) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_token_fill(long long n_resp, const A* __restrict__ adv,
                                                               const I* __restrict__ tok_off, O* __restrict__ out,
                                                               long long n_tokens, int skew, long long n_rows,
                                                               const ShortDesc<O>* __restrict__ short_desc,
                                                               const WideDesc<O>* __restrict__ wide_desc) {
-    const long long super = blockIdx.x >> kGroupShift;
-    const long long member = blockIdx.x & (kGroup - 1);
-    const long long row0 = ((super * kRows) << kGroupShift) + member;   // row k of this workgroup = row0 + k * kGroup
-    ShortDesc<O> d[kRows];   // (slots of rows past the end are read but never used)
-    load_descs<O, kShortEnds, kRows>(short_desc + short_slot((long long)blockIdx.x), d);
-    bool any_flagged = false;
+    const long long row = blockIdx.x;   // the grid has n_rows workgroups
+    const ShortDesc<O> d = load_desc<O, kShortEnds>(short_desc + short_slot(row));
+    // the whole descriptor in one round of loads: without this the part that the flag test
+    // does not need is fetched after the branch, one more wait
 #pragma unroll
-    for (int k = 0; k < kRows; ++k) {
-        const long long row = row0 + ((long long)k << kGroupShift);
-        if (row < n_rows) {
-            if (desc_flagged(d[k])) any_flagged = true;
-            else fill_row<O, kShortEnds>(d[k], out, row, n_rows, n_tokens, skew);
-        }
-    }
-    if (any_flagged) {
-        for (int k = 0; k < kRows; ++k) {
-            const long long row = row0 + ((long long)k << kGroupShift);
-            if (row < n_rows && desc_flagged(d[k]))
-                fill_flagged_row<A, O, I>(wide_desc, n_resp, adv, tok_off, out, row, n_rows, n_tokens, skew);
-        }
-    }
+    for (int i = 0; i < DescLayout<O, kShortEnds>::kWords; i += 4) asm volatile("" : : "s"(d.u[i]));
+    if (!desc_flagged(d)) fill_row<O, kShortEnds>(d, out, row, n_rows, n_tokens, skew);
+    else fill_flagged_row<A, O, I>(wide_desc, n_resp, adv, tok_off, out, row, n_rows, n_tokens, skew);
 }
 
 template <typename O>
 static long long rows_for(int64_t n_tokens, int skew) {
-    const long long row_elems = (long long)kBcastThreads * VecOf<O>::n;
-    return (n_tokens + skew + row_elems - 1) / row_elems;
+    return (n_tokens + skew + RowOf<O>::kRowElems - 1) / RowOf<O>::kRowElems;
 }
 
-// Workspace: the short descriptors (whole blocks of workgroups), then the wide ones (one
-// slot per row), both 256-byte aligned.
+// Workspace: the short descriptors (whole blocks of rows), then the wide ones (one slot
+// per row), both 256-byte aligned.
 template <typename O>
 static size_t short_area_bytes(long long n_rows) {
     return ((size_t)short_slots(n_rows) * sizeof(ShortDesc<O>) + 255) & ~(size_t)255;
@@ -396,6 +384,7 @@ static int launch_broadcast(int64_t n_resp, const void* adv, const void* tok_off
                             int32_t* dev_status, void* workspace, size_t workspace_bytes, hipStream_t stream) {
     const int skew = (int)((reinterpret_cast<uintptr_t>(out) & 15) / sizeof(O));
     const long long n_rows = rows_for<O>(n_tokens, skew);
+    if (n_rows > INT_MAX) return HORA_ERR_UNSUPPORTED;
     if (workspace_for<O>(n_rows) > workspace_bytes) return HORA_ERR_WORKSPACE;
     ShortDesc<O>* short_desc = (ShortDesc<O>*)workspace;
     WideDesc<O>* wide_desc = (WideDesc<O>*)((char*)workspace + short_area_bytes<O>(n_rows));
@@ -404,13 +393,10 @@ static int launch_broadcast(int64_t n_resp, const void* adv, const void* tok_off
     hipLaunchKernelGGL((k_row_desc<A, O, I>), dim3((unsigned)blocks1), dim3(kThreads), 0, stream,
                        (long long)n_resp, (const A*)adv, (const I*)tok_off, (long long)n_tokens, skew, n_rows,
                        short_desc, wide_desc, dev_status);
-    if (n_rows > 0) {
-        const long long supers = (n_rows + kGroup * kRows - 1) / (kGroup * kRows);
-        if (supers * kGroup > INT_MAX) return HORA_ERR_UNSUPPORTED;
-        hipLaunchKernelGGL((k_token_fill<A, O, I>), dim3((unsigned)(supers * kGroup)), dim3(kBcastThreads), 0,
-                           stream, (long long)n_resp, (const A*)adv, (const I*)tok_off, (O*)out,
-                           (long long)n_tokens, skew, n_rows, short_desc, wide_desc);
-    }
+    if (n_rows > 0)
+        hipLaunchKernelGGL((k_token_fill<A, O, I>), dim3((unsigned)n_rows), dim3(kBcastThreads), 0, stream,
+                           (long long)n_resp, (const A*)adv, (const I*)tok_off, (O*)out, (long long)n_tokens, skew,
+                           n_rows, short_desc, wide_desc);
     return hipGetLastError() == hipSuccess ? HORA_OK : HORA_ERR_HIP;
 }
 

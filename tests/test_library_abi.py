@@ -95,8 +95,8 @@ def test_host_argument_validation_needs_no_gpu(lib):
     assert bc(4, fake, 0, fake, 0, fake, 0, 5000, status, None, 0, None) == WORKSPACE
     assert bc(4, fake, 0, fake, 0, fake, 0, 5000, status, fake, 8, None) == WORKSPACE
     need = lib.hora_token_broadcast_workspace_bytes(170856406, 0)
-    rows = (4 * 170856406 + 12 + 4095) // 4096          # 4 KiB rows, worst-case alignment skew
-    assert need % 256 == 0 and 48 * rows <= need <= 48 * (rows + 64) + 512        # a short and a wide descriptor per row
+    rows = (4 * 170856406 + 12 + 8191) // 8192          # 8 KiB rows, worst-case alignment skew
+    assert need % 256 == 0 and 96 * rows <= need <= 96 * (rows + 64) + 512        # a short (32 B) and a wide (64 B) descriptor per row
     assert lib.hora_token_broadcast_workspace_bytes(0, 0) >= 256
     assert lib.hora_token_broadcast_workspace_bytes(-1, 0) == 0
     mg = lib.hora_marginal_gains
