@@ -17,6 +17,8 @@ HIPCC_FLAGS = [
     # the order of binary64 operations is part of the allocation's definition
     "-ffp-contract=off", "-fno-fast-math",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # the leading kernel arguments are handed over in registers instead of being loaded
+    "-mllvm", "-amdgpu-kernarg-preload-count=16",
     "-Wall", "-Wno-unused-function",
 ]
 

@@ -348,11 +348,11 @@ __device__ __forceinline__ void fill_flagged_row(const WideDesc<O>* __restrict__
 // (eight wavefronts per SIMD: the bytes in flight per compute unit are what hides the
 // latency of the stores, so the register count is held to what full occupancy allows)
 template <typename A, typename O, typename I>
-__global__ __launch_bounds__(kBcastThreads) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_token_fill(long long n_resp, const A* __restrict__ adv,
-                                                              const I* __restrict__ tok_off, O* __restrict__ out,
-                                                              long long n_tokens, int skew, long long n_rows,
-                                                              const ShortDesc<O>* __restrict__ short_desc,
-                                                              const WideDesc<O>* __restrict__ wide_desc) {
+__global__ __launch_bounds__(kBcastThreads) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_token_fill(
+    // what every row needs comes first: the leading kernel arguments arrive in registers
+    const ShortDesc<O>* __restrict__ short_desc, O* __restrict__ out, long long n_tokens, long long n_rows, int skew,
+    const WideDesc<O>* __restrict__ wide_desc, long long n_resp, const A* __restrict__ adv,
+    const I* __restrict__ tok_off) {
     const long long row = blockIdx.x;   // the grid has n_rows workgroups
     const ShortDesc<O> d = load_desc<O, kShortEnds>(short_desc + short_slot(row));
     // the whole descriptor in one round of loads: without this the part that the flag test
@@ -395,8 +395,8 @@ static int launch_broadcast(int64_t n_resp, const void* adv, const void* tok_off
                        short_desc, wide_desc, dev_status);
     if (n_rows > 0)
         hipLaunchKernelGGL((k_token_fill<A, O, I>), dim3((unsigned)n_rows), dim3(kBcastThreads), 0, stream,
-                           (long long)n_resp, (const A*)adv, (const I*)tok_off, (O*)out, (long long)n_tokens, skew,
-                           n_rows, short_desc, wide_desc);
+                           (const ShortDesc<O>*)short_desc, (O*)out, (long long)n_tokens, n_rows, skew,
+                           (const WideDesc<O>*)wide_desc, (long long)n_resp, (const A*)adv, (const I*)tok_off);
     return hipGetLastError() == hipSuccess ? HORA_OK : HORA_ERR_HIP;
 }
 
