@@ -3,8 +3,12 @@
 //
 // A sub-group of L lanes (L a power of two, chosen from the mean group size) owns one
 // group: the lanes stride over the group's rewards, so a wavefront reads a contiguous
-// run of the reward array, and combine their partial sums with a butterfly.  All sums
-// are binary64; a float output is rounded once at the store.
+// run of the reward array, and combine their partial sums with a butterfly.  L is about a
+// quarter of the mean group size; a group of up to 8 L responses (1.75 times the mean or more)
+// is read once and kept in registers (two dependent memory round trips per wavefront, offsets then rewards), and
+// what is computed once per group (mean, standard deviation, reciprocals) is repeated by
+// L lanes only: the kernel is bound by instruction issue and latency, not by bytes.
+// All sums are binary64; a float output is rounded once at the store.
 #include <hip/hip_runtime.h>
 
 #include <climits>
@@ -30,6 +34,10 @@ __device__ __forceinline__ int sub_and(int v) {
     return v;
 }
 
+// Rewards a lane keeps in registers: a group of up to L * kKeep responses is read from
+// memory once; what lies beyond is read again in every pass.
+constexpr int kKeep = 8;
+
 template <typename F, typename I, int L>
 __global__ __launch_bounds__(kThreads) void k_group_adv(long long n_groups, const I* __restrict__ off,
                                                         long long n_resp, const F* __restrict__ reward,
@@ -52,58 +60,92 @@ __global__ __launch_bounds__(kThreads) void k_group_adv(long long n_groups, cons
         }
     }
     const long long size = hi - lo;
+    const F* __restrict__ mine = reward + lo + sub;            // this lane's responses: mine[k * L]
+    F* __restrict__ mine_out = adv + lo + sub;
+    const long long count = size - sub;                        // k * L < count: mine[k * L] is in the group
+    const long long rest = lo + sub + (long long)kKeep * L;    // this lane's first response beyond its registers
 
+    // one round of loads
+    double x[kKeep];
+    bool in[kKeep];
+#pragma unroll
+    for (int k = 0; k < kKeep; ++k) {
+        in[k] = (long long)(k * L) < count;
+        x[k] = in[k] ? (double)mine[k * L] : 0.0;
+    }
+    const double first = __shfl(x[0], 0, L);   // reward[lo] (0 for an empty group)
     double sum = 0.0;
     int equal = 1;
-    const double first = size > 0 ? (double)reward[lo] : 0.0;
-    for (long long j = lo + sub; j < hi; j += L) {
-        const double x = (double)reward[j];
-        sum += x;
-        equal &= (x == first) ? 1 : 0;
+#pragma unroll
+    for (int k = 0; k < kKeep; ++k) {
+        sum += x[k];
+        equal &= (!in[k] || x[k] == first) ? 1 : 0;
+    }
+    for (long long j = rest; j < hi; j += L) {
+        const double y = (double)reward[j];
+        sum += y;
+        equal &= (y == first) ? 1 : 0;
     }
     sum = sub_sum<L>(sum);
     equal = sub_and<L>(equal);
 
+    // Every quotient whose divisor belongs to the group is formed as a product with the
+    // divisor's reciprocal (one division per lane instead of one per response): at most
+    // 1.5 units in the last place away from the quotient itself.
     if (mode == HORA_ADV_RLOO) {
-        const double denom = (double)(size - 1);
-        for (long long j = lo + sub; j < hi; j += L) {
-            const double x = (double)reward[j];
-            adv[j] = (F)(size == 1 ? 0.0 : x - (sum - x) / denom);
+        const double inv = size > 1 ? 1.0 / (double)(size - 1) : 0.0;
+#pragma unroll
+        for (int k = 0; k < kKeep; ++k)
+            if (in[k]) mine_out[k * L] = (F)(size == 1 ? 0.0 : x[k] - (sum - x[k]) * inv);
+        for (long long j = rest; j < hi; j += L) {
+            const double y = (double)reward[j];
+            adv[j] = (F)(y - (sum - y) * inv);
         }
         return;
     }
 
     const double mean = size > 0 ? sum / (double)size : 0.0;
     if (mode == HORA_ADV_CENTER) {
-        for (long long j = lo + sub; j < hi; j += L) {
-            const double x = (double)reward[j];
-            adv[j] = (F)(equal ? 0.0 : x - mean);
+#pragma unroll
+        for (int k = 0; k < kKeep; ++k)
+            if (in[k]) mine_out[k * L] = (F)(equal ? 0.0 : x[k] - mean);
+        for (long long j = rest; j < hi; j += L) {
+            const double y = (double)reward[j];
+            adv[j] = (F)(equal ? 0.0 : y - mean);
         }
         return;
     }
     const bool zero = equal || (size - ddof <= 0);
     double ss = 0.0;
     if (!zero) {
-        for (long long j = lo + sub; j < hi; j += L) {
+#pragma unroll
+        for (int k = 0; k < kKeep; ++k) {
+            const double d = x[k] - mean;
+            ss += in[k] ? d * d : 0.0;
+        }
+        for (long long j = rest; j < hi; j += L) {
             const double d = (double)reward[j] - mean;
             ss += d * d;
         }
     }
     ss = sub_sum<L>(ss);
-    const double scale = zero ? 1.0 : sqrt(ss / (double)(size - ddof)) + eps;
-    for (long long j = lo + sub; j < hi; j += L) {
-        const double x = (double)reward[j];
-        adv[j] = (F)(zero ? 0.0 : (x - mean) / scale);
+    const double inv = zero ? 0.0 : 1.0 / (sqrt(ss / (double)(size - ddof)) + eps);
+#pragma unroll
+    for (int k = 0; k < kKeep; ++k)
+        if (in[k]) mine_out[k * L] = (F)(zero ? 0.0 : (x[k] - mean) * inv);
+    for (long long j = rest; j < hi; j += L) {
+        const double y = (double)reward[j];
+        adv[j] = (F)(zero ? 0.0 : (y - mean) * inv);
     }
 }
 
 template <typename F, typename I>
 static int launch_adv(int64_t n_groups, const void* off, int64_t n_resp, const void* reward, void* adv, int mode,
                       double eps, int ddof, int32_t* dev_status, hipStream_t stream) {
-    const long long mean_size = n_groups > 0 ? n_resp / n_groups : 0;
+    // lanes per group: the fewest whose registers hold a group of 1.75 times the mean size
+    const long long roomy = n_groups > 0 ? (7 * n_resp + 4 * n_groups - 1) / (4 * n_groups) : 0;
     int lanes = 1;
-    while (lanes < kWave && lanes * 2 <= mean_size) lanes *= 2;   // largest power of two <= mean size
-    if (lanes < 2) lanes = 2;
+    while (lanes < kWave && (long long)lanes * kKeep < roomy) lanes *= 2;
 #define HORA_LAUNCH_ADV(LL)                                                                                   \
     do {                                                                                                      \
         const long long blocks = (n_groups * LL + kThreads - 1) / kThreads;                                   \
@@ -113,6 +155,7 @@ static int launch_adv(int64_t n_groups, const void* off, int64_t n_resp, const v
                            mode, eps, ddof, dev_status);                                                      \
     } while (0)
     switch (lanes) {
+        case 1: HORA_LAUNCH_ADV(1); break;
         case 2: HORA_LAUNCH_ADV(2); break;
         case 4: HORA_LAUNCH_ADV(4); break;
         case 8: HORA_LAUNCH_ADV(8); break;
