@@ -136,6 +136,17 @@ def other_paths(torch, hora, wl, sess, a1, c1, w1, delta1, util1, goff1, ws, rep
     wts = torch.empty(b2.reward.size, dtype=torch.float32, device="cuda:0")
     us = mean_us(lambda: hora.hora_response_weights(alloc2.group_off, toff2, wts, sess.dev_status))
     out["response_weights_large_bcast"] = {"responses": int(b2.reward.size), "us_per_call": us}
+    # group advantages far beyond the paper's sizes: 2^20 groups of 8..24 responses, binary rewards
+    rng_g = np.random.Generator(np.random.PCG64(11))
+    sizes = rng_g.integers(8, 25, 1 << 20)
+    goff_big = torch.from_numpy(np.concatenate(([0], np.cumsum(sizes))).astype(np.int32)).to("cuda:0")
+    n_big = int(goff_big[-1])
+    rew_big = (torch.rand(n_big, device="cuda:0") < 0.4).to(torch.float32)
+    adv_big = torch.empty_like(rew_big)
+    us = mean_us(lambda: hora.hora_group_advantage(goff_big, rew_big, adv_big, hora.ADV_GRPO, sess.dev_status, eps=1e-6))
+    out["group_advantage_grpo_2^20_groups"] = {"responses": n_big, "us_per_call": us,
+                                               "GBps": (8 * n_big + 4 * (sizes.size + 1)) / us / 1e3}
+    del rew_big, adv_big, goff_big
     us = mean_us(lambda: hora.hora_allocate_baseline(c1, w1.g0, w1.budget, hora.RULE_HARD_FIRST, delta1,
                                                      sess.dev_status, ws, util=util1, group_off=goff1))
     out["allocate_hard_first_large_alloc"] = {"us_per_call": us, "prompts_per_s": w1.n / us * 1e6}

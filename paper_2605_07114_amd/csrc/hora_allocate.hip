@@ -903,7 +903,7 @@ __global__ __launch_bounds__(kBig) void k_select_pass(Src src, long long n, long
                     const unsigned long long v = read_lane_u64(gb, leader);
                     const unsigned long long same = __ballot(inside && gb == v);
                     // gains that do not repeat (per-prompt posteriors): no point in more rounds
-                    if (round == 0 && same == (1ull << leader) && __popcll(pending) > 8) break;
+                    if (round == 0 && same == (1ull << leader)) break;
                     if (lane == leader) {
                         const int j = (int)((v - lo - 1ull) >> shift);
                         // no result is used: the three updates are issued without a wait
@@ -990,8 +990,21 @@ __global__ __launch_bounds__(kBig) void k_select_move(int nb, long long budget, 
     static_assert(kBig == 4 * kBins, "four threads per interval");
     const int bin = (int)threadIdx.x & (kBins - 1), quarter = (int)threadIdx.x / kBins;
     unsigned long long c1 = 0;
-#pragma unroll 16
-    for (int wg = quarter; wg < nb; wg += 4) c1 += bins[wg].cnt[bin];
+    // 32 loads of a thread in flight at once (what the registers of a 1024-thread workgroup
+    // allow): two round trips to memory, not one per few slots
+    constexpr int kBatch = 32;
+    static_assert(kMaxBlocks == 4 * 2 * kBatch, "two batches per thread");
+#pragma unroll 1
+    for (int t0 = 0; t0 < kMaxBlocks / 4; t0 += kBatch) {
+        unsigned long long part[kBatch];
+#pragma unroll
+        for (int t = 0; t < kBatch; ++t) {
+            const int wg = quarter + 4 * (t0 + t);
+            part[t] = wg < nb ? bins[wg].cnt[bin] : 0ull;
+        }
+#pragma unroll
+        for (int t = 0; t < kBatch; ++t) c1 += part[t];
+    }
     atomicAdd(&sh.cnt[bin], c1);
     __syncthreads();
     const int j = kBins - 1 - (int)threadIdx.x;

@@ -323,7 +323,7 @@ __device__ bool threshold_by_walks(const Src& src, long long lo_i, long long hi_
                     const unsigned long long v = read_lane_u64(gb, leader);
                     const unsigned long long same = __ballot(inside && gb == v);
                     // gains that do not repeat (per-prompt posteriors): no point in more rounds
-                    if (round == 0 && same == (1ull << leader) && __popcll(pending) > 8) break;
+                    if (round == 0 && same == (1ull << leader)) break;
                     if (lane == leader) {
                         const int j = (int)((v - lo - 1ull) >> shift);
                         atomicAdd(&sh.cnt[j], (unsigned long long)__popcll(same));
