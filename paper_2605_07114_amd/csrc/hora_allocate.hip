@@ -47,16 +47,21 @@ constexpr int kParallelPasses = 7;      // launched grid-wide; a single-workgrou
 constexpr unsigned long long kWindowStep = 4ull << 52;   // 4 exponent steps of the bit pattern: a factor 16 in value
 constexpr int kSoloMaxPasses = 512 + 10;   // windows from the largest gain down to zero, plus the narrowing passes
 
+struct Bracket {                  // state of the threshold search between two passes
+    unsigned long long lo;        // count_gt(lo) >= budget
+    unsigned long long hi;        // count_gt(hi) <  budget
+    unsigned long long above;     // pairs whose gain is > hi
+    unsigned int done;            // 1: the bracket has closed, tau = hi; 2: ran out of gains
+    unsigned int pending;         // the interval totals of the last pass have not been applied yet
+};
 struct AllocHeader {              // 256 bytes at the start of the workspace, zero at rest
     unsigned long long unused0;
     unsigned long long hi;        // bits of max_i M_i(0), gathered with atomicMax
-    unsigned long long above;     // pairs whose gain is > hi_cur
-    unsigned int ticket;          // workgroups that have finished the running pass
-    unsigned int done;            // the bracket has closed: tau = hi_cur
-    unsigned long long lo_cur;    // bracket: count_gt(lo_cur) >= budget
-    unsigned long long hi_cur;    // bracket: count_gt(hi_cur) <  budget
-    unsigned long long pad[26];
+    Bracket slot[2];              // pass p reads slot[p & 1] and writes slot[(p + 1) & 1]
+    unsigned long long hi_cur;    // tau once the search has ended
+    unsigned long long pad[21];
 };
+static_assert(sizeof(Bracket) == 32, "bracket size");
 static_assert(sizeof(AllocHeader) == 256, "header size");
 
 struct SelectBins {               // per-interval tallies of one workgroup in one search pass
@@ -64,10 +69,10 @@ struct SelectBins {               // per-interval tallies of one workgroup in on
     unsigned long long vmax[kBins];      // largest gain pattern seen in the interval
     unsigned long long vmin_inv[kBins];  // ~(smallest gain pattern seen in the interval)
 };
-// One SelectBins per workgroup (kMaxBlocks of them): every workgroup stores its tallies
-// with plain stores and the last one adds them up.  Atomics of all workgroups on one set
-// of intervals serialise at the memory side (hundreds of them per address and pass, each
-// a round trip), which cost more than the walks themselves.
+// One SelectBins per workgroup (kMaxBlocks of them) and one more for their totals: every
+// workgroup stores its tallies with plain stores, a small kernel adds them up.  Atomics of
+// all workgroups on one set of intervals serialise at the memory side (hundreds of them
+// per address and pass, each a round trip), which cost more than the walks themselves.
 
 struct BisectSolution {           // written by k_bisect_scan, read by k_bisect_write
     long long r;                  // units for the prompts tied at tau
@@ -116,7 +121,7 @@ static Workspace carve(void* base) {
     w.sol = (BisectSolution*)(ptr + off);
     off += sizeof(BisectSolution);
     w.bins = (SelectBins*)(ptr + off);
-    off += (size_t)kMaxBlocks * sizeof(SelectBins);
+    off += (size_t)(kMaxBlocks + 1) * sizeof(SelectBins);   // bins[kMaxBlocks]: the totals
     w.class_hist = (int*)(ptr + off);
     off += align256((size_t)kMaxClasses * kMaxBlocks * sizeof(int));
     w.gain_table = (double*)(ptr + off);
@@ -783,7 +788,7 @@ __global__ __launch_bounds__(kBig) void k_select_top(Src src, long long n, Alloc
     if (threadIdx.x == 0) {
         unsigned long long block_hi = 0;
         for (int i = 0; i < kBigWaves; ++i) block_hi = s_red[i] > block_hi ? s_red[i] : block_hi;
-        atomicMax(&hdr->hi, block_hi);   // k_select_move(first) turns it into the first window
+        atomicMax(&hdr->hi, block_hi);   // the first search pass turns it into the first window
     }
     if (bad) report(dev_status, HORA_ERR_RANGE);
 }
@@ -806,8 +811,13 @@ __global__ __launch_bounds__(kBig) void k_select_top(Src src, long long n, Alloc
 // smallest ceil(budget/n)-th gain) can lie orders of magnitude below tau and make every
 // prompt walk thousands of steps.
 //
-// kSolo = false: every workgroup tallies its share into a slot of its own; k_select_move
-// adds the slots up and moves the bracket for the next launch.
+// kSolo = false: every workgroup tallies its share into a slot of its own; k_select_reduce
+// adds the slots up, and every workgroup of the next pass moves the bracket by those
+// totals for itself (the same arithmetic on the same numbers in every workgroup), which
+// takes a few microseconds less than a one-workgroup kernel in between that has to pull
+// all slots through one compute unit.  The bracket is kept twice: pass p reads slot
+// p & 1, which nobody writes meanwhile, and its first workgroup stores the moved bracket
+// in the other slot for pass p + 1.
 // kSolo = true: one workgroup repeats passes over all prompts until the bracket closes.
 // It runs after the grid-wide passes and normally finds the bracket closed already; it is
 // there so that a fixed, small number of launches is correct for any input.
@@ -820,7 +830,6 @@ struct SelectShared {
     unsigned long long lo, hi;
     long long above;
     int done;
-    int last;
 };
 
 // The step that ends a search pass, run by a whole workgroup: thread t < kBins holds the
@@ -862,14 +871,41 @@ __device__ __forceinline__ void move_bracket(SelectShared& sh, unsigned long lon
 
 template <class Src, bool kSolo>
 __global__ __launch_bounds__(kBig) void k_select_pass(Src src, long long n, long long budget, long long limit,
-                                                      AllocHeader* __restrict__ hdr,
+                                                      int pass, AllocHeader* __restrict__ hdr,
                                                       SelectBins* __restrict__ bins) {
     __shared__ SelectShared sh;
-    if (threadIdx.x == 0) {
-        sh.lo = hdr->lo_cur; sh.hi = hdr->hi_cur; sh.above = (long long)hdr->above; sh.done = (int)hdr->done;
-        sh.last = 1;
+    // the bracket this pass works on: the stored one, moved by the totals of the pass before
+    const Bracket* in = &hdr->slot[pass & 1];
+    const bool pending = pass > 0 && in->pending != 0 && in->done == 0;   // uniform
+    {
+        const SelectBins* totals = bins + kMaxBlocks;
+        const int j = kBins - 1 - (int)threadIdx.x;   // thread 0 owns the top interval
+        unsigned long long cj = 0, mx = 0, mn = 0;
+        if (pending && threadIdx.x < kBins) {
+            cj = totals->cnt[j];
+            mx = totals->vmax[j];
+            mn = ~totals->vmin_inv[j];
+        }
+        if (threadIdx.x == 0) {
+            if (pass == 0) {   // the first window, from the largest gain down
+                const unsigned long long all_hi = hdr->hi;
+                sh.hi = all_hi;
+                sh.lo = all_hi > kWindowStep ? all_hi - kWindowStep : 0ull;
+                sh.above = 0;
+                sh.done = 0;
+            } else {
+                sh.lo = in->lo; sh.hi = in->hi; sh.above = (long long)in->above; sh.done = (int)in->done;
+            }
+        }
+        __syncthreads();
+        if (pending) move_bracket(sh, cj, mx, mn, budget);
     }
-    __syncthreads();
+    if (!kSolo && blockIdx.x == 0 && threadIdx.x == 0) {   // for the next pass
+        Bracket* out = &hdr->slot[(pass + 1) & 1];
+        out->lo = sh.lo; out->hi = sh.hi; out->above = (unsigned long long)sh.above;
+        out->done = (unsigned)sh.done;
+        out->pending = sh.done ? 0u : 1u;                  // this pass tallies unless the search has ended
+    }
     const int iters = kSolo ? kSoloMaxPasses : 1;
     for (int iter = 0; iter < iters; ++iter) {
         if (sh.done) break;
@@ -951,97 +987,54 @@ __global__ __launch_bounds__(kBig) void k_select_pass(Src src, long long n, long
         }
         move_bracket(sh, cj, mx, mn, budget);
     }
-    if (threadIdx.x == 0) {
-        hdr->lo_cur = sh.lo;
-        hdr->hi_cur = sh.hi;
-        hdr->above = (unsigned long long)sh.above;
-        hdr->done = (unsigned)sh.done;
-    }
+    if (kSolo && threadIdx.x == 0) hdr->hi_cur = sh.hi;   // tau
 }
 
 // ----------------------------------------------------------------------------------
-// Between two grid-wide search passes (one workgroup): adds up the workgroups' interval
-// tallies and moves the bracket.  A kernel of its own rather than "the workgroup that
-// finishes last": the device-wide fences that pattern needs (write back and invalidate
-// the L2 of every die) cost several times the pass itself on this part.
-// first != 0: starts the search from the largest gain instead (window (hi / 16, hi]).
+// Between two grid-wide search passes: the interval tallies of the workgroups are added up
+// (counts) and combined (largest, smallest gain) into bins[kMaxBlocks].  kReduceBins
+// intervals per workgroup, 32 lanes per interval striding over the slots.  A kernel of its
+// own rather than "the workgroup that finishes last": the device-wide fences that pattern
+// needs (write back and invalidate the L2 of every die) cost several times the pass itself
+// on this part.
 // ----------------------------------------------------------------------------------
-__global__ __launch_bounds__(kBig) void k_select_move(int nb, long long budget, int first,
-                                                      AllocHeader* __restrict__ hdr,
-                                                      const SelectBins* __restrict__ bins) {
-    __shared__ SelectShared sh;
-    if (first) {
-        if (threadIdx.x == 0) {
-            const unsigned long long all_hi = hdr->hi;
-            hdr->hi_cur = all_hi;
-            hdr->lo_cur = all_hi > kWindowStep ? all_hi - kWindowStep : 0ull;
-            hdr->above = 0ull;
-            hdr->done = 0u;
-        }
-        return;
-    }
-    if (hdr->done) return;
-    if (threadIdx.x == 0) { sh.lo = hdr->lo_cur; sh.hi = hdr->hi_cur; sh.above = (long long)hdr->above; sh.done = 0; }
-    if (threadIdx.x < kBins) { sh.cnt[threadIdx.x] = 0; sh.vmax[threadIdx.x] = 0; sh.vmin_inv[threadIdx.x] = 0; }
-    __syncthreads();
-    // Counts first: thread (q, i) adds interval i of every fourth workgroup, the four partial
-    // sums meet in LDS.  The largest and smallest gain are only needed for the one interval
-    // in which the budget is reached, so they are gathered for that interval alone.
-    static_assert(kBig == 4 * kBins, "four threads per interval");
-    const int bin = (int)threadIdx.x & (kBins - 1), quarter = (int)threadIdx.x / kBins;
-    unsigned long long c1 = 0;
-    // 32 loads of a thread in flight at once (what the registers of a 1024-thread workgroup
-    // allow): two round trips to memory, not one per few slots
-    constexpr int kBatch = 32;
-    static_assert(kMaxBlocks == 4 * 2 * kBatch, "two batches per thread");
-#pragma unroll 1
-    for (int t0 = 0; t0 < kMaxBlocks / 4; t0 += kBatch) {
-        unsigned long long part[kBatch];
+constexpr int kReduceBins = kThreads / 32;   // 8 intervals per workgroup of 256 threads
+
+__global__ __launch_bounds__(kThreads) void k_select_reduce(int nb, int pass, const AllocHeader* __restrict__ hdr,
+                                                            SelectBins* __restrict__ bins) {
+    if (hdr->slot[(pass + 1) & 1].pending == 0) return;   // pass `pass` did not tally: the search has ended
+    const int bin = (int)blockIdx.x * kReduceBins + (int)threadIdx.x / 32;
+    const int sub = (int)threadIdx.x & 31;
+    unsigned long long c = 0, mx = 0, mn = 0;
+    constexpr int kPer = kMaxBlocks / 32;                 // slots per lane, all loads issued at once
+    unsigned long long pc[kPer], pm[kPer], pn[kPer];
 #pragma unroll
-        for (int t = 0; t < kBatch; ++t) {
-            const int wg = quarter + 4 * (t0 + t);
-            part[t] = wg < nb ? bins[wg].cnt[bin] : 0ull;
-        }
+    for (int t = 0; t < kPer; ++t) {
+        const int wg = sub + 32 * t;
+        const bool in = wg < nb;
+        pc[t] = in ? bins[wg].cnt[bin] : 0ull;
+        pm[t] = in ? bins[wg].vmax[bin] : 0ull;
+        pn[t] = in ? bins[wg].vmin_inv[bin] : 0ull;
+    }
 #pragma unroll
-        for (int t = 0; t < kBatch; ++t) c1 += part[t];
+    for (int t = 0; t < kPer; ++t) {
+        c += pc[t];
+        mx = pm[t] > mx ? pm[t] : mx;
+        mn = pn[t] > mn ? pn[t] : mn;
     }
-    atomicAdd(&sh.cnt[bin], c1);
-    __syncthreads();
-    const int j = kBins - 1 - (int)threadIdx.x;
-    unsigned long long cj = threadIdx.x < kBins ? sh.cnt[j] : 0ull;
-    if (cj > (unsigned long long)budget) cj = (unsigned long long)budget;
-    // the interval that holds the budget-th pair, if this window holds it at all
-    const long long incl = wave_incl_scan<long long>((long long)cj);
-    if (lane_id() == kWave - 1) sh.red[wave_id()] = incl;
-    if (threadIdx.x == 0) sh.last = -1;
-    __syncthreads();
-    long long before = sh.above + incl - (long long)cj;
-    for (int i = 0; i < wave_id(); ++i) before += sh.red[i];
-    if (cj != 0 && before < budget && budget <= before + (long long)cj) sh.last = j;   // at most one thread
-    __syncthreads();
-    const int hit = sh.last;
-    if (hit >= 0) {
-        unsigned long long m1 = 0, n1 = 0;
-        for (int wg = (int)threadIdx.x; wg < nb; wg += kBig) {
-            const unsigned long long mm = bins[wg].vmax[hit], nn = bins[wg].vmin_inv[hit];
-            m1 = mm > m1 ? mm : m1;
-            n1 = nn > n1 ? nn : n1;
-        }
-        atomicMax(&sh.vmax[hit], m1);
-        atomicMax(&sh.vmin_inv[hit], n1);
+#pragma unroll
+    for (int d = 16; d > 0; d >>= 1) {
+        c += (unsigned long long)__shfl_xor((long long)c, d, 32);
+        const unsigned long long om = (unsigned long long)__shfl_xor((long long)mx, d, 32);
+        const unsigned long long on = (unsigned long long)__shfl_xor((long long)mn, d, 32);
+        mx = om > mx ? om : mx;
+        mn = on > mn ? on : mn;
     }
-    __syncthreads();
-    unsigned long long mx = 0, mn = 0;
-    if (threadIdx.x < kBins) {
-        mx = sh.vmax[j];
-        mn = ~sh.vmin_inv[j];
-    }
-    move_bracket(sh, cj, mx, mn, budget);
-    if (threadIdx.x == 0) {
-        hdr->lo_cur = sh.lo;
-        hdr->hi_cur = sh.hi;
-        hdr->above = (unsigned long long)sh.above;
-        hdr->done = (unsigned)sh.done;
+    if (sub == 0) {
+        SelectBins* totals = bins + kMaxBlocks;
+        totals->cnt[bin] = c;
+        totals->vmax[bin] = mx;
+        totals->vmin_inv[bin] = mn;
     }
 }
 
@@ -1118,11 +1111,11 @@ __global__ __launch_bounds__(kThreads) void k_bisect_scan(int nb, long long budg
             summary->tie_prompts = tcarry;
         }
         hdr->hi = 0ull;
-        hdr->above = 0ull;
-        hdr->ticket = 0u;
-        hdr->done = 0u;
-        hdr->lo_cur = 0ull;
         hdr->hi_cur = 0ull;
+        for (int i = 0; i < 2; ++i) {
+            hdr->slot[i].lo = 0ull; hdr->slot[i].hi = 0ull; hdr->slot[i].above = 0ull;
+            hdr->slot[i].done = 0u; hdr->slot[i].pending = 0u;
+        }
     }
 }
 
@@ -1298,18 +1291,14 @@ static int run_bisect(const Src& src, const CommonArgs& a, const Plan& p, const 
         if (blocks > kMaxBlocks) blocks = kMaxBlocks;
         hipLaunchKernelGGL((k_select_top<Src>), dim3((unsigned)blocks), dim3(kBig), 0, a.stream, src, n, w.header,
                            a.dev_status);
-        hipLaunchKernelGGL(k_select_move, dim3(1), dim3(kBig), 0, a.stream, (int)blocks, (long long)a.budget, 1,
-                           w.header, w.bins);
-        // small batches go straight to the single-workgroup search: fewer launches than passes
-        const int parallel = n > kSoloMaxPrompts ? kParallelPasses : 0;
-        for (int pass = 0; pass < parallel; ++pass) {
+        for (int pass = 0; pass < kParallelPasses; ++pass) {
             hipLaunchKernelGGL((k_select_pass<Src, false>), dim3((unsigned)blocks), dim3(kBig), 0, a.stream, src,
-                               n, (long long)a.budget, limit, w.header, w.bins);
-            hipLaunchKernelGGL(k_select_move, dim3(1), dim3(kBig), 0, a.stream, (int)blocks, (long long)a.budget, 0,
-                               w.header, w.bins);
+                               n, (long long)a.budget, limit, pass, w.header, w.bins);
+            hipLaunchKernelGGL(k_select_reduce, dim3(kBins / kReduceBins), dim3(kThreads), 0, a.stream, (int)blocks,
+                               pass, w.header, w.bins);
         }
         hipLaunchKernelGGL((k_select_pass<Src, true>), dim3(1), dim3(kBig), 0, a.stream, src, n,
-                           (long long)a.budget, limit, w.header, w.bins);
+                           (long long)a.budget, limit, kParallelPasses, w.header, w.bins);
     }
     hipLaunchKernelGGL((k_bisect_finalize<Src>), dim3(p.nb), dim3(kBig), 0, a.stream, src, n, p.chunk,
                        (long long)a.budget, limit, w.header, a.delta, a.util, w.block_ksum, w.block_tied);
