@@ -378,6 +378,7 @@ struct ClassSolution {      // LDS
     long long r;
     long long tie_prompts;
     int found;
+    int win;                  // a table entry whose value is tau (pairs path)
     int k[kMaxClasses];
     int tied[kMaxClasses];
     double u0[kMaxClasses];   // U_c(k_c)
@@ -425,21 +426,26 @@ __device__ void solve_by_table(int nc, int row_len, int len, bool rows_end_at_ca
                 if (pr & 0x8000) eq += n2;
                 if (n2 != 0 && pos >= len && !rows_end_at_cap) complete = false;
             }
-            if (complete && gt < budget && budget <= gt + eq) {   // every such thread writes the same values
+            if (complete && gt < budget && budget <= gt + eq) {
+                // every such thread writes the same values, except for `win`: entries of equal
+                // value have equal pairs, so whichever lands serves
                 sol->tau_bits = gain_bits(s_gain[idx]);
                 sol->r = budget - gt;
                 sol->tie_prompts = eq;
                 sol->found = 1;
-                // the per-class results are at hand in this entry's pairs
-                for (int cls = 0; cls < nc; ++cls) {
-                    const int pr = s_pair[idx * nc + cls];
-                    const int pos = pr & 0x7fff;
-                    sol->k[cls] = pos;
-                    sol->tied[cls] = (pr & 0x8000) ? 1 : 0;
-                    sol->u0[cls] = 1.0 - s_surv[cls * row_len + pos];
-                    sol->u1[cls] = 1.0 - s_surv[cls * row_len + (pos + 1 < row_len ? pos + 1 : pos)];
-                }
+                sol->win = idx;
             }
+        }
+        __syncthreads();
+        // the per-class results are at hand in the winning entry's pairs: one thread per class
+        if (sol->found && threadIdx.x < (unsigned)nc) {
+            const int cls = (int)threadIdx.x;
+            const int pr = s_pair[sol->win * nc + cls];
+            const int pos = pr & 0x7fff;
+            sol->k[cls] = pos;
+            sol->tied[cls] = (pr & 0x8000) ? 1 : 0;
+            sol->u0[cls] = 1.0 - s_surv[cls * row_len + pos];
+            sol->u1[cls] = 1.0 - s_surv[cls * row_len + (pos + 1 < row_len ? pos + 1 : pos)];
         }
         __syncthreads();
         return;

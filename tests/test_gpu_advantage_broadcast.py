@@ -28,7 +28,7 @@ def check_advantage(gpu, oracle, group_off, reward64, ftype, itype, mode, eps=0.
     idt = {"i32": np.int32, "i64": np.int64}[itype]
     reward = reward64.astype(fdt)
     want = oracle.group_advantage(group_off, reward.astype(np.float64), mode, eps=eps, ddof=ddof)
-    m = {"grpo": hora.ADV_GRPO, "rloo": hora.ADV_RLOO}[mode]
+    m = {"grpo": hora.ADV_GRPO, "rloo": hora.ADV_RLOO, "center": hora.ADV_CENTER}[mode]
     print(f"group_advantage groups={group_off.size - 1} resp={reward.size} {ftype} {itype} {mode}", flush=True)
     got = sess.group_advantage(dev(torch, group_off.astype(idt)), dev(torch, reward), m, eps=eps, ddof=ddof)
     assert sess.status() == 0
@@ -74,6 +74,20 @@ def test_advantage_general_rewards_modes_and_types(gpu, oracle):
                 for ddof in (0, 1):
                     for eps in (0.0, 1e-6):
                         check_advantage(gpu, oracle, off, reward, ftype, itype, "grpo", eps=eps, ddof=ddof)
+
+
+def test_advantage_few_large_groups_among_small_ones(gpu, oracle):
+    """The lanes per group follow the mean size; groups far above it take the path that re-reads
+    what a lane's registers do not hold (one lane per group here, groups of up to 700)."""
+    rng = np.random.default_rng(32)
+    sizes = rng.integers(1, 4, 4000)
+    sizes[[5, 1999, 3999]] = (700, 9, 130)
+    off = np.zeros(sizes.size + 1, dtype=np.int64)
+    np.cumsum(sizes, out=off[1:])
+    reward = rng.integers(0, 2, off[-1]).astype(np.float64)
+    for ftype in ("f64", "f32"):
+        for mode in ("grpo", "rloo", "center"):
+            check_advantage(gpu, oracle, off, reward, ftype, "i32", mode, eps=1e-6)
 
 
 def test_advantage_edge_groups(gpu, oracle):
