@@ -736,6 +736,7 @@ __global__ __launch_bounds__(kShardThreads) void k_shard_allocate_waves(
     const bool live = shard < n_shards;
     const long long lo_i = live ? shard_off[shard] : 0, hi_i = live ? shard_off[shard + 1] : 0;
     const long long budget = live ? shard_budget[shard] : 0;
+    const long long before = (kOff != 0 && live) ? prefix[shard] : 0;   // units of the shards before this one
     for (int idx = (int)threadIdx.x; idx < n_coarse * stride; idx += kShardThreads) {
         const int q = idx / stride, k = idx - q * stride;
         int p = q * kLevelBlock + kLevelBlock - 1;
@@ -817,12 +818,14 @@ __global__ __launch_bounds__(kShardThreads) void k_shard_allocate_waves(
             // fine: lane t evaluates level 64 * block + t
             const int p = block * kLevelBlock + lane;
             long long ct = 0;
+            unsigned w[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};   // this lane's row (16 classes or fewer)
             if (p < levels) {
                 const unsigned short* row = level_kge + (long long)p * stride;
                 if (stride == 16) {
                     const uint4 r0 = *reinterpret_cast<const uint4*>(row);
                     const uint4 r1 = *reinterpret_cast<const uint4*>(row + 8);
-                    const unsigned w[8] = {r0.x, r0.y, r0.z, r0.w, r1.x, r1.y, r1.z, r1.w};
+                    w[0] = r0.x; w[1] = r0.y; w[2] = r0.z; w[3] = r0.w;
+                    w[4] = r1.x; w[5] = r1.y; w[6] = r1.z; w[7] = r1.w;
 #pragma unroll
                     for (int k = 0; k < 16; ++k) {
                         const long long nk = (long long)__builtin_amdgcn_readlane(n_mine, k);
@@ -845,12 +848,10 @@ __global__ __launch_bounds__(kShardThreads) void k_shard_allocate_waves(
             if (stride == 16) {
                 // the two rows are in the registers of lanes t and t - 1: hand them over through LDS
                 // (level j - 1 of the first lane's block is the coarse row of the block before)
-                const uint4* row = reinterpret_cast<const uint4*>(level_kge + (long long)(p < levels ? p : 0) * stride);
                 if (lane == t || lane == t - 1) {
-                    const uint4 r0 = row[0], r1 = row[1];          // cached: loaded a moment ago
                     unsigned* dst = ws.rows[lane == t ? 0 : 1];
-                    dst[0] = r0.x; dst[1] = r0.y; dst[2] = r0.z; dst[3] = r0.w;
-                    dst[4] = r1.x; dst[5] = r1.y; dst[6] = r1.z; dst[7] = r1.w;
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) dst[q] = w[q];
                 }
             }
             if (lane < nc) {
@@ -900,7 +901,7 @@ __global__ __launch_bounds__(kShardThreads) void k_shard_allocate_waves(
     // (same wavefront reads them back below: LDS operations of a wavefront complete in order)
 
     // ---- 3. outputs
-    const long long off_base = kOff != 0 ? (long long)g0 * lo_i + prefix[shard] : 0;
+    const long long off_base = kOff != 0 ? (long long)g0 * lo_i + before : 0;
     long long rank_base = 0, given = 0;       // tied prompts / units handed out before this tile
     for (long long i0 = lo_i; i0 < hi_i; i0 += kWave) {
         const long long i = i0 + lane;
