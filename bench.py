@@ -28,8 +28,8 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
 # the same counters read for a plain device copy of known size); the figures and the commands
 # are in profiles/hbm_traffic_large_alloc_large_bcast.txt.  Set to None when a kernel named
 # there changes.
-TRAFFIC_BROADCAST_BYTES = 692442102     # k_row_desc + k_token_fill, large_bcast
-TRAFFIC_ALLOCATE_BYTES = 25561582       # k_class_hist + k_class_write, large_alloc
+TRAFFIC_BROADCAST_BYTES = 692415223     # k_row_desc + k_token_fill, large_bcast
+TRAFFIC_ALLOCATE_BYTES = 25556462       # k_class_hist + k_class_write, large_alloc
 
 
 def ensure_library():
