@@ -46,20 +46,26 @@ constexpr int kSoloMaxPrompts = 2048;   // up to here one workgroup searches alo
 constexpr int kParallelPasses = 7;      // launched grid-wide; a single-workgroup finisher covers the rest
 constexpr unsigned long long kWindowStep = 4ull << 52;   // 4 exponent steps of the bit pattern: a factor 16 in value
 constexpr int kSoloMaxPasses = 512 + 10;   // windows from the largest gain down to zero, plus the narrowing passes
+constexpr int kListCap = 1024;             // gains a workgroup can set aside for the passes that follow
+constexpr long long kCollectMax = 65536;   // a bracket with no more pairs than this is set aside (256 per workgroup on average)
+constexpr unsigned kFlagPending = 1u;      // Bracket::flags: the totals of the last pass have not been applied yet
+constexpr unsigned kFlagCollected = 2u;    // ... the last pass left (or kept) the bracket's gains in the lists
 
 struct Bracket {                  // state of the threshold search between two passes
     unsigned long long lo;        // count_gt(lo) >= budget
     unsigned long long hi;        // count_gt(hi) <  budget
     unsigned long long above;     // pairs whose gain is > hi
     unsigned int done;            // 1: the bracket has closed, tau = hi; 2: ran out of gains
-    unsigned int pending;         // the interval totals of the last pass have not been applied yet
+    unsigned int flags;           // kFlagPending, kFlagCollected
 };
 struct AllocHeader {              // 256 bytes at the start of the workspace, zero at rest
     unsigned long long unused0;
     unsigned long long hi;        // bits of max_i M_i(0), gathered with atomicMax
     Bracket slot[2];              // pass p reads slot[p & 1] and writes slot[(p + 1) & 1]
     unsigned long long hi_cur;    // tau once the search has ended
-    unsigned long long pad[21];
+    unsigned int lists_ok;        // no workgroup ran out of room in its list (written between passes)
+    unsigned int pad0;
+    unsigned long long pad[20];
 };
 static_assert(sizeof(Bracket) == 32, "bracket size");
 static_assert(sizeof(AllocHeader) == 256, "header size");
@@ -107,6 +113,8 @@ struct Workspace {
     double* surv_table;     // [nc][row]: E_c(l)
     long long* block_ksum;  // [nb] sums, then exclusive prefixes, of k_i          (BISECT)
     long long* block_tied;  // [nb] sums, then exclusive prefixes, of tied flags   (BISECT)
+    unsigned long long* lists;   // [kMaxBlocks][kListCap] gains set aside by the search passes (BISECT)
+    int* list_count;             // [kMaxBlocks] entries in each list, -1 when it did not fit
     size_t bytes;
 };
 
@@ -132,6 +140,10 @@ static Workspace carve(void* base) {
     off += align256((size_t)kMaxBlocks * sizeof(long long));
     w.block_tied = (long long*)(ptr + off);
     off += align256((size_t)kMaxBlocks * sizeof(long long));
+    w.lists = (unsigned long long*)(ptr + off);
+    off += align256((size_t)kMaxBlocks * kListCap * sizeof(unsigned long long));
+    w.list_count = (int*)(ptr + off);
+    off += align256((size_t)kMaxBlocks * sizeof(int));
     w.bytes = off;
     return w;
 }
@@ -835,7 +847,10 @@ struct SelectShared {
     long long red[kBigWaves];
     unsigned long long lo, hi;
     long long above;
+    long long inside;   // pairs in the bracket after a step that narrowed it (-1: not known)
     int done;
+    int hit;            // the last step narrowed the bracket (it did not move to the next window)
+    int list_n;         // gains this workgroup has set aside in this pass
 };
 
 // The step that ends a search pass, run by a whole workgroup: thread t < kBins holds the
@@ -865,12 +880,16 @@ __device__ __forceinline__ void move_bracket(SelectShared& sh, unsigned long lon
             sh.hi = lo;
             sh.lo = lo > kWindowStep ? lo - kWindowStep : 0ull;
             if (lo == 0ull) sh.done = 2;                // no gains left: the budget does not fit
+            sh.hit = 0;
+            sh.inside = -1;
         }
     } else if (cj != 0 && before < budget && budget <= before + (long long)cj) {   // exactly one thread
         sh.above = before;
         sh.hi = mx;
         sh.lo = mn - 1ull;
         sh.done = (mx == mn) ? 1 : 0;
+        sh.hit = 1;
+        sh.inside = (long long)cj;                      // (a count cut off at the budget is no larger than the true one)
     }
     __syncthreads();
 }
@@ -878,11 +897,13 @@ __device__ __forceinline__ void move_bracket(SelectShared& sh, unsigned long lon
 template <class Src, bool kSolo>
 __global__ __launch_bounds__(kBig) void k_select_pass(Src src, long long n, long long budget, long long limit,
                                                       int pass, AllocHeader* __restrict__ hdr,
-                                                      SelectBins* __restrict__ bins) {
+                                                      SelectBins* __restrict__ bins,
+                                                      unsigned long long* __restrict__ lists,
+                                                      int* __restrict__ list_count) {
     __shared__ SelectShared sh;
     // the bracket this pass works on: the stored one, moved by the totals of the pass before
     const Bracket* in = &hdr->slot[pass & 1];
-    const bool pending = pass > 0 && in->pending != 0 && in->done == 0;   // uniform
+    const bool pending = pass > 0 && (in->flags & kFlagPending) != 0 && in->done == 0;   // uniform
     {
         const SelectBins* totals = bins + kMaxBlocks;
         const int j = kBins - 1 - (int)threadIdx.x;   // thread 0 owns the top interval
@@ -902,15 +923,31 @@ __global__ __launch_bounds__(kBig) void k_select_pass(Src src, long long n, long
             } else {
                 sh.lo = in->lo; sh.hi = in->hi; sh.above = (long long)in->above; sh.done = (int)in->done;
             }
+            sh.hit = 0;
+            sh.inside = -1;
+            sh.list_n = 0;
         }
         __syncthreads();
         if (pending) move_bracket(sh, cj, mx, mn, budget);
+    }
+    // Where this pass gets the gains of its bracket from.  A bracket that has been narrowed
+    // to few pairs is set aside while it is walked once more (kCollect: every workgroup
+    // keeps the gains it finds in a list of its own); the passes after that tally from the
+    // lists instead of walking every prompt again (kFromLists) -- brackets only shrink
+    // from there on, so the lists stay a superset of what is needed.  A list that does not
+    // fit (lists_ok == 0) only means that the next pass walks again.
+    enum { kWalk = 0, kCollect = 1, kFromLists = 2 };
+    int mode = kWalk;
+    if (!kSolo && pending && sh.hit && !sh.done) {
+        if ((in->flags & kFlagCollected) != 0 && hdr->lists_ok != 0) mode = kFromLists;
+        else if (sh.inside <= kCollectMax) mode = kCollect;
     }
     if (!kSolo && blockIdx.x == 0 && threadIdx.x == 0) {   // for the next pass
         Bracket* out = &hdr->slot[(pass + 1) & 1];
         out->lo = sh.lo; out->hi = sh.hi; out->above = (unsigned long long)sh.above;
         out->done = (unsigned)sh.done;
-        out->pending = sh.done ? 0u : 1u;                  // this pass tallies unless the search has ended
+        // this pass tallies unless the search has ended
+        out->flags = (sh.done ? 0u : kFlagPending) | (mode != kWalk ? kFlagCollected : 0u);
     }
     const int iters = kSolo ? kSoloMaxPasses : 1;
     for (int iter = 0; iter < iters; ++iter) {
@@ -924,6 +961,19 @@ __global__ __launch_bounds__(kBig) void k_select_pass(Src src, long long n, long
 
         const long long stride = (long long)gridDim.x * kBig;
         const int lane = lane_id();
+        if (mode == kFromLists) {   // (never in the solo kernel)
+            const int have = list_count[blockIdx.x];
+            const unsigned long long* mine = lists + (long long)blockIdx.x * kListCap;
+            for (int e = (int)threadIdx.x; e < have; e += kBig) {
+                const unsigned long long v = mine[e];
+                if (v > lo && v <= hi) {
+                    const int j = (int)((v - lo - 1ull) >> shift);
+                    atomicAdd(&sh.cnt[j], 1ull);
+                    atomicMax(&sh.vmax[j], v);
+                    atomicMax(&sh.vmin_inv[j], ~v);
+                }
+            }
+        } else
         // all wavefronts run the same number of rounds, so that the ballots below see whole wavefronts
         for (long long i0 = (long long)blockIdx.x * kBig; i0 < n; i0 += stride) {
             const long long i = i0 + threadIdx.x;
@@ -937,6 +987,10 @@ __global__ __launch_bounds__(kBig) void k_select_pass(Src src, long long n, long
             bool active = i < n && k < limit && gb > lo;
             while (__ballot(active)) {
                 const bool inside = active && gb <= hi;
+                if (mode == kCollect && inside) {
+                    const int at = atomicAdd(&sh.list_n, 1);
+                    if (at < kListCap) lists[(long long)blockIdx.x * kListCap + at] = gb;
+                }
                 // lanes that hold the same gain (common under a shared prior) tally once:
                 // up to 8 distinct gains per step through a leader, the rest lane by lane
                 unsigned long long pending = __ballot(inside);
@@ -973,7 +1027,8 @@ __global__ __launch_bounds__(kBig) void k_select_pass(Src src, long long n, long
         __syncthreads();   // the workgroup's tallies are complete
         if (!kSolo) {
             // this workgroup's tallies to its own slot (all of them: the slot holds no state);
-            // k_select_move adds the slots up after this kernel has ended
+            // k_select_reduce adds the slots up after this kernel has ended
+            if (mode == kCollect && threadIdx.x == 0) list_count[blockIdx.x] = sh.list_n <= kListCap ? sh.list_n : -1;
             SelectBins* mine = bins + blockIdx.x;
             if (threadIdx.x < kBins) {
                 const unsigned long long c0 = sh.cnt[threadIdx.x];
@@ -1006,9 +1061,16 @@ __global__ __launch_bounds__(kBig) void k_select_pass(Src src, long long n, long
 // ----------------------------------------------------------------------------------
 constexpr int kReduceBins = kThreads / 32;   // 8 intervals per workgroup of 256 threads
 
-__global__ __launch_bounds__(kThreads) void k_select_reduce(int nb, int pass, const AllocHeader* __restrict__ hdr,
-                                                            SelectBins* __restrict__ bins) {
-    if (hdr->slot[(pass + 1) & 1].pending == 0) return;   // pass `pass` did not tally: the search has ended
+__global__ __launch_bounds__(kThreads) void k_select_reduce(int nb, int pass, AllocHeader* __restrict__ hdr,
+                                                            SelectBins* __restrict__ bins,
+                                                            const int* __restrict__ list_count) {
+    const unsigned flags = hdr->slot[(pass + 1) & 1].flags;
+    if ((flags & kFlagPending) == 0) return;   // pass `pass` did not tally: the search has ended
+    if (blockIdx.x == 0 && (flags & kFlagCollected) != 0) {   // did every workgroup's list fit?
+        static_assert(kMaxBlocks <= kThreads, "one thread per list");
+        const int any_bad = __syncthreads_or((int)threadIdx.x < nb && list_count[threadIdx.x] < 0 ? 1 : 0);
+        if (threadIdx.x == 0) hdr->lists_ok = any_bad ? 0u : 1u;
+    }
     const int bin = (int)blockIdx.x * kReduceBins + (int)threadIdx.x / 32;
     const int sub = (int)threadIdx.x & 31;
     unsigned long long c = 0, mx = 0, mn = 0;
@@ -1120,8 +1182,9 @@ __global__ __launch_bounds__(kThreads) void k_bisect_scan(int nb, long long budg
         hdr->hi_cur = 0ull;
         for (int i = 0; i < 2; ++i) {
             hdr->slot[i].lo = 0ull; hdr->slot[i].hi = 0ull; hdr->slot[i].above = 0ull;
-            hdr->slot[i].done = 0u; hdr->slot[i].pending = 0u;
+            hdr->slot[i].done = 0u; hdr->slot[i].flags = 0u;
         }
+        hdr->lists_ok = 0u;
     }
 }
 
@@ -1299,12 +1362,12 @@ static int run_bisect(const Src& src, const CommonArgs& a, const Plan& p, const 
                            a.dev_status);
         for (int pass = 0; pass < kParallelPasses; ++pass) {
             hipLaunchKernelGGL((k_select_pass<Src, false>), dim3((unsigned)blocks), dim3(kBig), 0, a.stream, src,
-                               n, (long long)a.budget, limit, pass, w.header, w.bins);
+                               n, (long long)a.budget, limit, pass, w.header, w.bins, w.lists, w.list_count);
             hipLaunchKernelGGL(k_select_reduce, dim3(kBins / kReduceBins), dim3(kThreads), 0, a.stream, (int)blocks,
-                               pass, w.header, w.bins);
+                               pass, w.header, w.bins, (const int*)w.list_count);
         }
         hipLaunchKernelGGL((k_select_pass<Src, true>), dim3(1), dim3(kBig), 0, a.stream, src, n,
-                           (long long)a.budget, limit, kParallelPasses, w.header, w.bins);
+                           (long long)a.budget, limit, kParallelPasses, w.header, w.bins, w.lists, w.list_count);
     }
     hipLaunchKernelGGL((k_bisect_finalize<Src>), dim3(p.nb), dim3(kBig), 0, a.stream, src, n, p.chunk,
                        (long long)a.budget, limit, w.header, a.delta, a.util, w.block_ksum, w.block_tied);

@@ -236,6 +236,31 @@ def test_per_prompt_posteriors(gpu, oracle):
                                    rtol=UTIL_RTOL, atol=0)
 
 
+def test_posteriors_whose_contested_gains_sit_in_one_workgroup(gpu, oracle):
+    """The search sets the gains of a narrow bracket aside, one list per workgroup.  Here all
+    gains near the threshold belong to prompts of one workgroup's share (the others are hopeless
+    prompts that get nothing), so its list overflows at first and the search has to carry on
+    without it."""
+    sess, torch, hora = gpu
+    rng = np.random.default_rng(23)
+    n, g0 = 200000, 8
+    alpha = np.full(n, 0.01)
+    beta = np.full(n, 60.0)
+    good = slice(5 * 1024, 6 * 1024)                  # one tile of 1024 prompts
+    alpha[good] = rng.uniform(0.5, 9.0, 1024)
+    beta[good] = rng.uniform(0.5, 9.0, 1024)
+    for budget in (1024 * 40, 1024 * 3, 1024 * 300):
+        want = oracle.allocate_posterior(alpha, beta, budget)
+        if budget <= 1024 * 40:
+            assert want[good].sum() == budget        # nothing goes to the hopeless prompts
+        print(f"allocate_posterior one-tile contest n={n} budget={budget}", flush=True)
+        got = sess.allocate_posterior(dev(torch, alpha), dev(torch, beta), g0, budget)
+        assert sess.status() == 0
+        assert np.array_equal(got.delta.cpu().numpy().astype(np.int64), want)
+        np.testing.assert_allclose(got.util.cpu().numpy()[good], oracle.utilities(alpha[good], beta[good], want[good]),
+                                   rtol=UTIL_RTOL, atol=0)
+
+
 def test_learned_prior_collapses_to_the_uniform_prior(gpu, oracle):
     # App. D: s = 2, p = 1/2 gives alpha = 1 + c, beta = 1 + G0 - c
     sess, torch, hora = gpu
