@@ -744,11 +744,14 @@ __global__ __launch_bounds__(kBig) void k_class_write(const int32_t* __restrict_
         summary->tie_prompts = s_sol.tie_prompts;
     }
 
-    EmitCarry carry = {0, 0};
-    for (int cc = 0; cc < nc; ++cc) {
-        carry.rank_base += s_sol.tied[cc] ? s_before[cc] : 0;
-        carry.ks_base += s_before[cc] * s_sol.k[cc];
+    // what the workgroups before this one hold: lane c takes class c, the wavefront adds up
+    long long tied_before = 0, units_before = 0;
+    if (lane < nc) {
+        const long long bef = s_before[lane];
+        tied_before = s_sol.tied[lane] ? bef : 0;
+        units_before = bef * s_sol.k[lane];
     }
+    EmitCarry carry = {wave_total_i64(tied_before), wave_total_i64(units_before)};
 
     int parity = 0;
     for (long long t0 = base; t0 < end; t0 += kTile, parity ^= 1) {
