@@ -22,7 +22,7 @@
 // between the stores would make every store wait for the one before it.  What limits the
 // kernel besides the stores is the number of cache lines of descriptors fetched under
 // write load, so the short descriptors of workgroups that run on the same die (workgroup
-// index modulo 8) share cache lines.  Flagged rows go out of line: through the wide
+// index modulo 8) share cache lines.  Flagged rows take a slower path: through the wide
 // descriptor, or, when more than nine responses intersect the row (runs of very short or
 // empty responses), by a search of the packed offsets.
 #include <hip/hip_runtime.h>
