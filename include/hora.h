@@ -44,8 +44,7 @@ typedef enum {
     HORA_ERR_WORKSPACE = -3,   /* workspace missing or smaller than *_workspace_bytes()        */
     HORA_ERR_RANGE = -4,       /* device data out of range (via dev_status)                    */
     HORA_ERR_HIP = -5,         /* a HIP runtime call or kernel launch failed                   */
-    HORA_ERR_UNSUPPORTED = -6, /* size outside what this entry point / method handles          */
-    HORA_ERR_TIMEOUT = -7      /* a bounded device-side wait gave up (via dev_status)          */
+    HORA_ERR_UNSUPPORTED = -6  /* size outside what this entry point / method handles          */
 } hora_status;
 
 typedef enum { HORA_ADV_GRPO = 0, HORA_ADV_RLOO = 1, HORA_ADV_CENTER = 2 } hora_adv_mode;
@@ -67,6 +66,15 @@ typedef enum {
 
 /* Largest G0 the CLASS method handles (one wavefront lane per class c = 0..G0). */
 #define HORA_CLASS_MAX_G0 63
+
+/*
+ * Largest number of additional rollouts one prompt may receive in one call.  A prompt's
+ * marginal gains are evaluated one after the other (each from the one before), so this
+ * bounds the longest serial chain a kernel can run.  A budget above n * HORA_MAX_DEPTH is
+ * refused on the host (HORA_ERR_UNSUPPORTED); an allocation in which the data would send
+ * more than this to a single prompt is reported through dev_status (HORA_ERR_UNSUPPORTED).
+ */
+#define HORA_MAX_DEPTH (1 << 20)
 
 /* Optional device-side report of one allocation (all fields written by the call). */
 typedef struct {
@@ -124,8 +132,8 @@ size_t hora_allocate_workspace_bytes(int64_t n, int32_t g0);
  * c         : device, n int32, each in [0, g0] (else HORA_ERR_RANGE in dev_status).
  * alpha0, beta0 : prior, both > 0 and finite (the paper uses 1, 1).
  * budget    : Phase-B budget, >= 0; need not be a multiple of n.  HORA_ERR_UNSUPPORTED
- *             from 2^52 on, or when one prompt could receive 2^31 - 1 units or more
- *             (delta is int32): min(budget, delta_max) with a cap, budget without.
+ *             from 2^52 on, and above n * HORA_MAX_DEPTH (some prompt would have to receive
+ *             more than HORA_MAX_DEPTH units).
  * delta_max : per-prompt cap; <= 0 means none (the paper states none).  A budget above
  *             n * delta_max gives HORA_ERR_INFEASIBLE.
  * method    : hora_alloc_method.
@@ -228,7 +236,9 @@ int hora_allocate_sharded(int64_t n, int32_t g0, const int32_t *c, double alpha0
  *   GRPO: adv_j = (R_j - mean) / (std + eps), mean and std over the group's rewards,
  *         std with divisor G_g - ddof.  A group whose rewards are all equal (zero
  *         empirical std) gets exactly 0, as does a group with G_g - ddof <= 0.
- *   RLOO: adv_j = R_j - (S - R_j) / (G_g - 1), S the group's reward sum; G_g = 1 gives 0.
+ *   RLOO: adv_j = R_j - (S - R_j) / (G_g - 1), S the group's reward sum; G_g = 1 gives 0, and so
+ *         does a group whose rewards are all equal (every response equals its leave-one-out
+ *         baseline; the product with the reciprocal of G_g - 1 would leave 1e-16 there).
  *   CENTER: adv_j = R_j - mean, the GRPO form without the division by the standard
  *         deviation (for objectives of the Dr. GRPO kind; the paper's runs use GRPO as
  *         written in Sec. 3.1).  A group whose rewards are all equal gets exactly 0.

@@ -96,10 +96,10 @@ __global__ __launch_bounds__(kThreads) void k_group_adv(long long n_groups, cons
         const double inv = size > 1 ? 1.0 / (double)(size - 1) : 0.0;
 #pragma unroll
         for (int k = 0; k < kKeep; ++k)
-            if (in[k]) mine_out[k * L] = (F)(size == 1 ? 0.0 : x[k] - (sum - x[k]) * inv);
+            if (in[k]) mine_out[k * L] = (F)((size == 1 || equal) ? 0.0 : x[k] - (sum - x[k]) * inv);
         for (long long j = rest; j < hi; j += L) {
             const double y = (double)reward[j];
-            adv[j] = (F)(y - (sum - y) * inv);
+            adv[j] = (F)(equal ? 0.0 : y - (sum - y) * inv);
         }
         return;
     }

@@ -518,8 +518,8 @@ __device__ void solve_by_table(int nc, int row_len, int len, bool rows_end_at_ca
 // in which the remaining budget no longer covers the tied classes fixes tau.  This is
 // Alg. 1's greedy loop run on classes: prompts of one class have identical sequences, so
 // the greedy hands them their l-th unit in one uninterrupted run.
-__device__ void solve_by_greedy(int g0, double alpha0, double beta0, long long cap_eff, long long budget,
-                                const long long* s_n, ClassSolution* sol, int32_t* dev_status) {
+__device__ void solve_by_greedy(int g0, double alpha0, double beta0, long long cap_eff, bool depth_capped,
+                                long long budget, const long long* s_n, ClassSolution* sol, int32_t* dev_status) {
     if (wave_id() == 0) {
         const int nc = g0 + 1;
         const int lane = lane_id();
@@ -545,7 +545,7 @@ __device__ void solve_by_greedy(int g0, double alpha0, double beta0, long long c
                 best = kj > best ? kj : best;
             }
             if (best == 0) {  // nothing left to give to: cannot happen when budget <= n * cap
-                report(dev_status, HORA_ERR_INFEASIBLE);
+                report(dev_status, depth_capped ? HORA_ERR_UNSUPPORTED : HORA_ERR_INFEASIBLE);
                 break;
             }
             const bool at_best = active && key == best;
@@ -564,6 +564,9 @@ __device__ void solve_by_greedy(int g0, double alpha0, double beta0, long long c
                 g = gain_next(g, b, s, lf);
                 lf += 1.0;
                 k += 1;
+                // a class stopped by the depth bound rather than by the caller's cap: the result
+                // is no longer the optimum of the problem that was asked
+                if (depth_capped && k >= cap_eff) report(dev_status, HORA_ERR_UNSUPPORTED);
             }
         }
         sol->k[lane] = has ? (int)k : 0;
@@ -586,8 +589,8 @@ __device__ void solve_by_greedy(int g0, double alpha0, double beta0, long long c
 // rule 1: uniform, every prompt is eligible.  rule 2: hard-first, only prompts with
 // c_i = 0 are; the split inside the eligible set is even (the paper does not say), and a
 // batch without such a prompt falls back to uniform.
-__device__ void solve_by_rule(int rule, int g0, double alpha0, double beta0, long long cap_eff, long long budget,
-                              const long long* s_n, ClassSolution* sol, int32_t* dev_status) {
+__device__ void solve_by_rule(int rule, int g0, double alpha0, double beta0, long long cap_eff, bool depth_capped,
+                              long long budget, const long long* s_n, ClassSolution* sol, int32_t* dev_status) {
     if (wave_id() == 0) {
         const int nc = g0 + 1;
         const int lane = lane_id();
@@ -598,9 +601,12 @@ __device__ void solve_by_rule(int rule, int g0, double alpha0, double beta0, lon
         const long long hard = (long long)read_lane_u64((unsigned long long)ncount, 0);
         const bool all = rule == 1 || hard == 0;
         const long long eligible = all ? total : hard;
-        const long long each = eligible > 0 ? budget / eligible : 0;
+        long long each = eligible > 0 ? budget / eligible : 0;
         const long long rest = eligible > 0 ? budget - each * eligible : 0;
-        if (lane == 0 && each + (rest > 0 ? 1 : 0) > cap_eff) report(dev_status, HORA_ERR_INFEASIBLE);
+        if (each + (rest > 0 ? 1 : 0) > cap_eff) {   // uniform
+            if (lane == 0) report(dev_status, depth_capped ? HORA_ERR_UNSUPPORTED : HORA_ERR_INFEASIBLE);
+            each = cap_eff > 0 ? cap_eff - 1 : 0;    // (keeps the walk below within the depth bound)
+        }
         const bool mine = has && (all || lane == 0);
         const long long k = mine ? each : 0;
         const double a = alpha0 + (double)(has ? lane : 0);
@@ -657,7 +663,10 @@ __global__ __launch_bounds__(kBig) void k_class_write(const int32_t* __restrict_
     const bool d_vec = (reinterpret_cast<uintptr_t>(delta) & 15) == 0;
     const bool u_vec = (reinterpret_cast<uintptr_t>(util) & 15) == 0;
     const bool o_vec = (reinterpret_cast<uintptr_t>(group_off) & 15) == 0;
-    const long long cap_eff = cap > 0 ? (long long)cap : LLONG_MAX;
+    // the caller's cap, and the library's own bound on the depth of one prompt
+    const long long cap_user = cap > 0 ? (long long)cap : LLONG_MAX;
+    const bool depth_capped = cap_user > (long long)HORA_MAX_DEPTH;
+    const long long cap_eff = depth_capped ? (long long)HORA_MAX_DEPTH : cap_user;
     const int len = cap_eff < row_len - 1 ? (int)cap_eff : row_len - 1;   // usable gains per row
     const bool rows_end_at_cap = cap_eff <= row_len - 1;
 
@@ -722,10 +731,11 @@ __global__ __launch_bounds__(kBig) void k_class_write(const int32_t* __restrict_
     __syncthreads();
 
     if (budget > 0 && rule != 0) {
-        solve_by_rule(rule, g0, alpha0, beta0, cap_eff, budget, s_n, &s_sol, dev_status);
+        solve_by_rule(rule, g0, alpha0, beta0, cap_eff, depth_capped, budget, s_n, &s_sol, dev_status);
     } else if (budget > 0) {
         solve_by_table(nc, row_len, len, rows_end_at_cap, budget, s_n, s_gain, s_surv, s_pair, &s_sol);
-        if (!s_sol.found) solve_by_greedy(g0, alpha0, beta0, cap_eff, budget, s_n, &s_sol, dev_status);
+        if (!s_sol.found)
+            solve_by_greedy(g0, alpha0, beta0, cap_eff, depth_capped, budget, s_n, &s_sol, dev_status);
     } else {
         if (threadIdx.x < kMaxClasses) {
             s_sol.k[threadIdx.x] = 0;
@@ -1289,9 +1299,9 @@ static int validate_common(const CommonArgs& a) {
     if (a.budget > 0 && a.n == 0) return HORA_ERR_INFEASIBLE;
     if (a.delta_max > 0 && a.budget > 0 && (a.budget + a.delta_max - 1) / a.delta_max > a.n)
         return HORA_ERR_INFEASIBLE;
-    // delta is int32: the largest value a prompt can get must fit
-    const long long per_prompt_max = a.delta_max > 0 ? (a.budget < a.delta_max ? a.budget : a.delta_max) : a.budget;
-    if (per_prompt_max >= (1ll << 31) - 1) return HORA_ERR_UNSUPPORTED;
+    // more than n * HORA_MAX_DEPTH units: some prompt would have to go deeper than the bound
+    // (n < 2^40 and the bound is 2^20, so the product fits)
+    if (a.n > 0 && a.budget > a.n * (long long)HORA_MAX_DEPTH) return HORA_ERR_UNSUPPORTED;
     if (a.group_off && a.off_t == HORA_I32) {
         const long long total = a.n * (long long)a.g0 + a.budget;
         if (total >= (1ll << 31)) return HORA_ERR_INVALID_ARG;

@@ -10,7 +10,6 @@ extern "C" const char* hora_status_string(int status) {
         case HORA_ERR_RANGE: return "device data out of range";
         case HORA_ERR_HIP: return "HIP runtime error";
         case HORA_ERR_UNSUPPORTED: return "size not supported";
-        case HORA_ERR_TIMEOUT: return "device-side wait timed out";
         default: return "unknown status";
     }
 }

@@ -22,7 +22,8 @@ LIB_PATH = os.path.join(_HERE, "libhora.so")
 
 OK = 0
 ERR_INVALID_ARG, ERR_INFEASIBLE, ERR_WORKSPACE, ERR_RANGE = -1, -2, -3, -4
-ERR_HIP, ERR_UNSUPPORTED, ERR_TIMEOUT = -5, -6, -7
+ERR_HIP, ERR_UNSUPPORTED = -5, -6
+MAX_DEPTH = 1 << 20
 ADV_GRPO, ADV_RLOO, ADV_CENTER = 0, 1, 2
 F32, F64 = 0, 1
 I32, I64 = 0, 1

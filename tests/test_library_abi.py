@@ -43,7 +43,7 @@ def test_every_declared_symbol_is_exported(lib):
 def test_version_and_status_strings(lib):
     assert lib.hora_version() >= 100
     assert lib.hora_status_string(0) == b"ok"
-    for code in range(-7, 0):
+    for code in range(-6, 0):
         assert lib.hora_status_string(code) not in (b"ok", b"unknown status")
     assert lib.hora_status_string(-99) == b"unknown status"
 
@@ -78,6 +78,17 @@ def test_host_argument_validation_needs_no_gpu(lib):
     # class method beyond its G0 limit; int32 delta overflow; int32 offsets overflow
     assert alloc(8, 64, fake, 1.0, 1.0, 8, 0, 1, fake, None, None, 0, None, status, fake, 1 << 20, None) == UNSUPPORTED
     assert alloc(8, 4, fake, 1.0, 1.0, 1 << 33, 0, 0, fake, None, None, 0, None, status, fake, 1 << 20, None) == UNSUPPORTED
+    # the depth bound: a budget that would force some prompt beyond HORA_MAX_DEPTH = 2^20 additional
+    # rollouts is refused on the host (no kernel may run a serial chain of that length)
+    depth = 1 << 20
+    assert alloc(1, 4, fake, 1.0, 1.0, 2_000_000_000, 0, 0, fake, None, None, 0, None, status, fake, 1 << 20, None) == UNSUPPORTED
+    for method in (0, 1, 2):
+        assert alloc(3, 4, fake, 1.0, 1.0, 3 * depth + 1, 0, method, fake, None, None, 0, None, status, fake,
+                     1 << 20, None) == UNSUPPORTED
+    assert lib.hora_allocate_posterior(3, 4, fake, fake, 3 * depth + 1, 0, fake, None, None, 0, None, status, fake,
+                                       1 << 24, None) == UNSUPPORTED
+    assert lib.hora_allocate_baseline(3, 4, fake, 1.0, 1.0, 3 * depth + 1, 0, 1, fake, None, None, 0, None, status,
+                                      fake, 1 << 24, None) == UNSUPPORTED
     assert alloc(1 << 29, 4, fake, 1.0, 1.0, 8, 0, 0, fake, None, fake, 0, None, status, fake, 1 << 30, None) == INVALID
     # advantage / broadcast
     adv = lib.hora_group_advantage

@@ -74,6 +74,78 @@ def test_greedy_with_cap_reaches_brute_force_optimum(oracle):
         assert exchange_condition_holds(ab, delta, cap)
 
 
+# Priors with alpha0 != beta0 and non-integer priors (Sec. 3.2 Eq. 2: alpha_i = alpha0 + c_i,
+# beta_i = beta0 + G0 - c_i).  The posterior is formed HERE in exact rationals, so an oracle
+# that swapped alpha0 and beta0, or added the prior to the wrong side, fails.
+ASYMMETRIC_PRIORS = [(Fraction(1, 2), Fraction(3)), (Fraction(3), Fraction(1, 2)), (Fraction(2), Fraction(13, 4)),
+                     (Fraction(1, 4), Fraction(1, 4)), (Fraction(5), Fraction(1))]
+
+
+@pytest.mark.parametrize("prior", ASYMMETRIC_PRIORS)
+def test_posterior_with_asymmetric_prior_is_eq2(oracle, prior):
+    a0, b0 = prior
+    for g0 in (1, 4, 8):
+        c = np.arange(g0 + 1, dtype=np.int32)
+        alpha, beta = oracle.posterior(c, g0, float(a0), float(b0))
+        for ci in range(g0 + 1):
+            assert Fraction(float(alpha[ci])) == a0 + ci            # successes go to alpha
+            assert Fraction(float(beta[ci])) == b0 + g0 - ci        # failures go to beta
+        # posterior mean = first marginal gain = (alpha0 + c) / (alpha0 + beta0 + G0)
+        for ci in range(g0 + 1):
+            m0 = oracle.marginal_gains(float(alpha[ci]), float(beta[ci]), 1)[0]
+            assert m0 == pytest.approx(float((a0 + ci) / (a0 + b0 + g0)), rel=1e-15)
+
+
+@pytest.mark.parametrize("prior", ASYMMETRIC_PRIORS)
+def test_greedy_with_asymmetric_prior_reaches_brute_force_optimum(oracle, prior):
+    a0, b0 = prior
+    rng = np.random.default_rng(1000 + int(a0 * 8) + int(b0 * 64))
+    for g0 in (2, 4):
+        for trial in range(12):
+            n = int(rng.integers(1, 6))
+            budget = int(rng.integers(0, 9))
+            c = rng.integers(0, g0 + 1, n).astype(np.int32)
+            delta = oracle.allocate(c, g0, budget, alpha0=float(a0), beta0=float(b0))
+            assert delta.sum() == budget and (delta >= 0).all()
+            ab = [(a0 + int(ci), b0 + g0 - int(ci)) for ci in c]
+            got = sum(exact_utility(a, b, int(d)) for (a, b), d in zip(ab, delta))
+            assert got == brute_force_best(ab, budget, budget), (prior, c, budget, delta)
+            assert exchange_condition_holds(ab, delta, 0)
+            # with the prior's two parameters exchanged the same allocation is, in general, no
+            # longer optimal: the test can tell the two readings apart
+    # a case where the exchanged prior provably gives another allocation
+    c = np.array([0, 4, 4, 4], dtype=np.int32)
+    d_ab = oracle.allocate(c, 4, 6, alpha0=float(a0), beta0=float(b0))
+    d_ba = oracle.allocate(c, 4, 6, alpha0=float(b0), beta0=float(a0))
+    ab = [(a0 + int(ci), b0 + 4 - int(ci)) for ci in c]
+    best = brute_force_best(ab, 6, 6)
+    assert sum(exact_utility(a, b, int(d)) for (a, b), d in zip(ab, d_ab)) == best
+    if a0 != b0 and not np.array_equal(d_ab, d_ba):
+        assert sum(exact_utility(a, b, int(d)) for (a, b), d in zip(ab, d_ba)) < best
+
+
+def test_asymmetric_prior_exact_greedy_without_ties(oracle):
+    # prior (1/2, 3), G0 = 4: the gain sequences of different classes never coincide for l < 12
+    # (checked here in rationals), so the optimum of Eq. 4 is unique and Delta itself is pinned.
+    a0, b0, g0 = Fraction(1, 2), Fraction(3), 4
+    c = np.array([0, 1, 2, 3, 4, 2, 0], dtype=np.int32)
+    ab = [(a0 + int(ci), b0 + g0 - int(ci)) for ci in c]
+    classes = sorted(set(ab))
+    seen = {}
+    for a, b in classes:
+        for l in range(12):
+            g = exact_gain(a, b, l)
+            assert seen.setdefault(g, (a, b)) == (a, b)        # no tie between classes
+    for budget in (1, 3, 7, 12, 20):
+        want = [0] * len(ab)
+        for _ in range(budget):
+            gains = [exact_gain(a, b, d) for (a, b), d in zip(ab, want)]
+            best = max(gains)
+            want[gains.index(best)] += 1                        # lowest index among equal prompts
+        got = oracle.allocate(c, g0, budget, alpha0=float(a0), beta0=float(b0))
+        assert got.tolist() == want
+
+
 def test_binding_cap_cases(oracle):
     c = np.zeros(4, dtype=np.int32)
     assert oracle.allocate(c, 4, 12, delta_max=3).tolist() == [3, 3, 3, 3]
