@@ -153,6 +153,27 @@ int hora_allocate(int64_t n, int32_t g0, const int32_t *c, double alpha0, double
                   int32_t *dev_status, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * hora_allocate for callers that cannot allocate device memory or pass a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, results and errors as hora_allocate, without the workspace: the kernels use a
+ * buffer of HORA_STATIC_SCRATCH_BYTES that is part of the library's device image (one copy on
+ * every GPU the library runs on, held until the process ends).  The call allocates nothing.
+ *
+ *  - n above HORA_STATIC_MAX_PROMPTS gives HORA_ERR_UNSUPPORTED (use hora_allocate).
+ *  - All calls on one GPU share that GPU's buffer: calls that may overlap on one GPU
+ *    (different streams, different threads) race; serialise them or use hora_allocate with
+ *    workspaces of their own.
+ *  - The first call on a device looks up the buffer's address (hipGetSymbolAddress); make
+ *    that call outside a stream capture.
+ */
+#define HORA_STATIC_MAX_PROMPTS (1 << 22)
+#define HORA_STATIC_SCRATCH_BYTES (16u << 20)
+int hora_allocate_static(int64_t n, int32_t g0, const int32_t *c, double alpha0, double beta0,
+                         int64_t budget, int32_t delta_max, int32_t method, int32_t *delta, double *util,
+                         void *group_off, int32_t off_t, hora_alloc_summary *summary,
+                         int32_t *dev_status, void *stream);
+
+/*
  * Phase-B allocation for per-prompt posteriors (App. D, prompt-conditioned prior:
  * alpha_i = s_i p_i + c_i, beta_i = s_i (1 - p_i) + G0 - c_i are formed by the caller).
  * Same result definition, outputs and conventions as hora_allocate; always uses the

@@ -23,6 +23,7 @@
 #include <climits>
 #include <cmath>
 #include <cstdint>
+#include <mutex>
 
 #include "hora.h"
 #include "hora_device.h"
@@ -1397,6 +1398,39 @@ static int run_bisect(const Src& src, const CommonArgs& a, const Plan& p, const 
     return check_launch();
 }
 
+// ----------------------------------------------------------------------------------
+// Workspace for callers that cannot allocate (hora_allocate_static): a file-scope device
+// array, one copy per GPU, held until the process ends.  Its name is a host-side stand-in
+// for the symbol, not a device address; the address on the current device comes from
+// hipGetSymbolAddress, is looked up once per device and is what every launch gets.
+// The array starts zero-filled like any device global, which is the state the allocation
+// kernels expect of a workspace and leave behind.
+// ----------------------------------------------------------------------------------
+constexpr size_t kStaticScratchBytes = (size_t)HORA_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[kMaxDevices];   // per device: address of that device's copy of `scratch`
+
+static int static_scratch(void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return HORA_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return HORA_ERR_HIP;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return HORA_OK;
+}
+
+int allocate_shared_prior(int64_t n, int32_t g0, const int32_t* c, double alpha0, double beta0, int64_t budget,
+                          int32_t delta_max, int32_t method, int32_t* delta, double* util, void* group_off,
+                          int32_t off_t, hora_alloc_summary* summary, int32_t* dev_status, void* workspace,
+                          size_t workspace_bytes, hipStream_t stream);
+
 }  // namespace hora
 
 using namespace hora;
@@ -1425,8 +1459,32 @@ int hora_allocate(int64_t n, int32_t g0, const int32_t* c, double alpha0, double
                   int32_t delta_max, int32_t method, int32_t* delta, double* util, void* group_off, int32_t off_t,
                   hora_alloc_summary* summary, int32_t* dev_status, void* workspace, size_t workspace_bytes,
                   void* stream) {
+    return allocate_shared_prior(n, g0, c, alpha0, beta0, budget, delta_max, method, delta, util, group_off, off_t,
+                                 summary, dev_status, workspace, workspace_bytes, (hipStream_t)stream);
+}
+
+int hora_allocate_static(int64_t n, int32_t g0, const int32_t* c, double alpha0, double beta0, int64_t budget,
+                         int32_t delta_max, int32_t method, int32_t* delta, double* util, void* group_off,
+                         int32_t off_t, hora_alloc_summary* summary, int32_t* dev_status, void* stream) {
+    if (n > (int64_t)HORA_STATIC_MAX_PROMPTS) return HORA_ERR_UNSUPPORTED;
+    if (n >= 0 && g0 >= 0 && carve(nullptr).bytes > kStaticScratchBytes) return HORA_ERR_UNSUPPORTED;
+    void* ptr = nullptr;
+    const int rc = static_scratch(&ptr);
+    if (rc != HORA_OK) return rc;
+    return allocate_shared_prior(n, g0, c, alpha0, beta0, budget, delta_max, method, delta, util, group_off, off_t,
+                                 summary, dev_status, ptr, kStaticScratchBytes, (hipStream_t)stream);
+}
+
+}  // extern "C"
+
+namespace hora {
+
+int allocate_shared_prior(int64_t n, int32_t g0, const int32_t* c, double alpha0, double beta0, int64_t budget,
+                          int32_t delta_max, int32_t method, int32_t* delta, double* util, void* group_off,
+                          int32_t off_t, hora_alloc_summary* summary, int32_t* dev_status, void* workspace,
+                          size_t workspace_bytes, hipStream_t stream) {
     CommonArgs a{n, g0, budget, delta_max, delta, util, group_off, off_t, summary, dev_status,
-                 workspace, workspace_bytes, (hipStream_t)stream};
+                 workspace, workspace_bytes, stream};
     int rc = validate_common(a);
     if (rc != HORA_OK) return rc;
     if (!(alpha0 > 0.0) || !(beta0 > 0.0) || !std::isfinite(alpha0) || !std::isfinite(beta0))
@@ -1447,6 +1505,10 @@ int hora_allocate(int64_t n, int32_t g0, const int32_t* c, double alpha0, double
     }
     return run_class(c, alpha0, beta0, a, p, w, 0);
 }
+
+}  // namespace hora
+
+extern "C" {
 
 int hora_allocate_baseline(int64_t n, int32_t g0, const int32_t* c, double alpha0, double beta0, int64_t budget,
                            int32_t delta_max, int32_t rule, int32_t* delta, double* util, void* group_off,

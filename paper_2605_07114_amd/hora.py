@@ -36,6 +36,7 @@ EXPORTS = (
     "hora_allocate", "hora_allocate_posterior", "hora_group_advantage", "hora_token_broadcast",
     "hora_token_broadcast_workspace_bytes", "hora_allocate_sharded", "hora_allocate_sharded_workspace_bytes",
     "hora_response_weights", "hora_allocate_baseline", "hora_pass_at_k", "hora_pass_at_k_workspace_bytes",
+    "hora_allocate_static",
 )
 
 
@@ -70,6 +71,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.hora_allocate_workspace_bytes.restype = sz
     lib.hora_allocate.argtypes = [i64, i32, p, f64, f64, i64, i32, i32, p, p, p, i32, p, p, p, sz, p]
     lib.hora_allocate.restype = ctypes.c_int
+    lib.hora_allocate_static.argtypes = [i64, i32, p, f64, f64, i64, i32, i32, p, p, p, i32, p, p, p]
+    lib.hora_allocate_static.restype = ctypes.c_int
     lib.hora_allocate_baseline.argtypes = [i64, i32, p, f64, f64, i64, i32, i32, p, p, p, i32, p, p, p, sz, p]
     lib.hora_allocate_baseline.restype = ctypes.c_int
     lib.hora_allocate_posterior.argtypes = [i64, i32, p, p, i64, i32, p, p, p, i32, p, p, p, sz, p]
@@ -176,6 +179,24 @@ def hora_allocate(c: torch.Tensor, g0: int, budget: int, delta: torch.Tensor, de
         _ptr(delta), _ptr(util), _ptr(group_off), _itype(group_off) if group_off is not None else I32,
         _ptr(summary), _ptr(dev_status), _ptr(workspace), workspace.numel() * workspace.element_size(),
         _stream(stream)), "hora_allocate")
+
+
+def hora_allocate_static(c: torch.Tensor, g0: int, budget: int, delta: torch.Tensor, dev_status: torch.Tensor, *,
+                         alpha0: float = 1.0, beta0: float = 1.0, delta_max: int = 0, method: int = ALLOC_AUTO,
+                         util: Optional[torch.Tensor] = None, group_off: Optional[torch.Tensor] = None,
+                         summary: Optional[torch.Tensor] = None, stream=None) -> None:
+    n = c.numel()
+    _expect(c, torch.int32, n, "c")
+    _expect(delta, torch.int32, n, "delta")
+    _expect(util, torch.float64, n, "util")
+    _expect(dev_status, torch.int32, 1, "dev_status")
+    _expect(summary, torch.int64, 4, "summary")
+    if group_off is not None and group_off.numel() < n + 1:
+        raise ValueError("group_off needs n + 1 elements")
+    _check(load_library().hora_allocate_static(
+        n, int(g0), _ptr(c), float(alpha0), float(beta0), int(budget), int(delta_max), int(method),
+        _ptr(delta), _ptr(util), _ptr(group_off), _itype(group_off) if group_off is not None else I32,
+        _ptr(summary), _ptr(dev_status), _stream(stream)), "hora_allocate_static")
 
 
 def hora_allocate_baseline(c: torch.Tensor, g0: int, budget: int, rule: int, delta: torch.Tensor,
