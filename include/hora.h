@@ -109,10 +109,10 @@ int hora_marginal_gains(int64_t n, const double *alpha, const double *beta, int3
                         double *gains, double *util, void *stream);
 
 /*
- * Bytes of workspace hora_allocate / hora_allocate_posterior need for n prompts.
- * The workspace is device memory, 256-byte aligned.  It must be zero-filled once
- * before its first use; every call leaves it ready for the next one.  Two calls
- * that may run concurrently need separate workspaces.
+ * Bytes of workspace hora_allocate / hora_allocate_posterior / hora_allocate_baseline need
+ * for n prompts (a workspace sized for n serves every smaller batch).  The workspace is device
+ * memory, 256-byte aligned, and needs no initialisation: nothing is carried from one call to
+ * the next.  Two calls that may run concurrently need separate workspaces.
  */
 size_t hora_allocate_workspace_bytes(int64_t n, int32_t g0);
 
@@ -231,10 +231,10 @@ size_t hora_allocate_sharded_workspace_bytes(int64_t n_shards);
  * shard_off    : device, n_shards+1 int64, shard_off[0] = 0, non-decreasing,
  *                shard_off[n_shards] = n (else HORA_ERR_RANGE in dev_status).  Empty
  *                shards are allowed.
- * shard_budget : device, n_shards int64, each >= 0, < 2^31 - 1 without a cap, and at most
- *                (shard size) * delta_max with one; a positive budget needs a non-empty
- *                shard (else HORA_ERR_RANGE / HORA_ERR_INFEASIBLE in dev_status; the
- *                outputs of such a shard are unspecified).
+ * shard_budget : device, n_shards int64, each >= 0, at most (shard size) * HORA_MAX_DEPTH, and at
+ *                most (shard size) * delta_max with a cap; a positive budget needs a non-empty
+ *                shard (else HORA_ERR_RANGE / HORA_ERR_INFEASIBLE / HORA_ERR_UNSUPPORTED in
+ *                dev_status; the outputs of such a shard are unspecified).
  * group_off    : as for hora_allocate; with HORA_I32 a total n*g0 + sum of the budgets of
  *                2^31 or more gives HORA_ERR_RANGE in dev_status (HORA_ERR_INVALID_ARG
  *                where n*g0 alone shows it).

@@ -50,6 +50,56 @@ __device__ __forceinline__ unsigned long long read_lane_u64(unsigned long long v
     return ((unsigned long long)hi << 32) | lo;
 }
 
+// ----------------------------------------------------------------------------------
+// Tallies of one pass of the threshold search.  The bracket (lo, hi] of tau's bit pattern is
+// cut into at most kBins intervals of 2^shift patterns; per interval the number of gains that
+// fall inside, and the largest and smallest pattern seen there, are kept.
+// ----------------------------------------------------------------------------------
+struct TallyBins {
+    unsigned long long cnt[kBins];       // pairs whose gain falls into the interval
+    unsigned long long vmax[kBins];      // largest gain pattern seen in the interval
+    unsigned long long vmin_inv[kBins];  // ~(smallest gain pattern seen in the interval)
+};
+
+// log2 of the interval width for the bracket (lo, hi]: ((v - lo - 1) >> shift) < kBins for lo < v <= hi.
+__device__ __forceinline__ int bracket_shift(unsigned long long lo, unsigned long long hi) {
+    const unsigned long long width = hi - lo;                  // >= 1
+    const int bitlen = width > 1 ? 64 - __clzll((long long)(width - 1)) : 0;   // bits of width - 1
+    return bitlen > 8 ? bitlen - 8 : 0;
+}
+
+// Every lane of a wavefront offers one gain pattern (`inside` says whether it lies in the
+// bracket); all of them are tallied into `bins` (LDS).  Lanes that hold the same gain (the
+// rule under a shared prior) tally once, through a leader: up to 8 distinct gains per call
+// that way, the rest lane by lane.  A wavefront whose first pending gain does not repeat
+// (per-prompt posteriors never repeat) skips the merging, which is scalar-heavy.
+// Must be called by whole wavefronts.
+__device__ __forceinline__ void tally_gains(TallyBins& bins, bool inside, unsigned long long gb,
+                                            unsigned long long lo, int shift) {
+    const int lane = lane_id();
+    unsigned long long pending = __ballot(inside);
+    for (int round = 0; round < 8 && pending; ++round) {
+        const int leader = __ffsll((long long)pending) - 1;
+        const unsigned long long v = read_lane_u64(gb, leader);
+        const unsigned long long same = __ballot(inside && gb == v);
+        if (round == 0 && same == (1ull << leader)) break;
+        if (lane == leader) {
+            const int j = (int)((v - lo - 1ull) >> shift);
+            // no result is used: the three updates are issued without a wait
+            atomicAdd(&bins.cnt[j], (unsigned long long)__popcll(same));
+            atomicMax(&bins.vmax[j], v);
+            atomicMax(&bins.vmin_inv[j], ~v);
+        }
+        pending &= ~same;
+    }
+    if (inside && ((pending >> lane) & 1ull)) {
+        const int j = (int)((gb - lo - 1ull) >> shift);
+        atomicAdd(&bins.cnt[j], 1ull);
+        atomicMax(&bins.vmax[j], gb);
+        atomicMax(&bins.vmin_inv[j], ~gb);
+    }
+}
+
 // Number of gains of one prompt that exceed tau, at most `limit`; also leaves the next
 // gain (the first one <= tau) in `g`, l as a double in `lf` and, if asked, the survival
 // product E(k) in `e`.

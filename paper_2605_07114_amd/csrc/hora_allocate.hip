@@ -28,126 +28,11 @@
 #include "hora.h"
 #include "hora_device.h"
 #include "hora_alloc_common.h"
+#include "hora_alloc_emit.h"
 
 namespace hora {
 
-constexpr int kBig = 1024;                    // threads per workgroup of the pass-1 / pass-2 / write kernels
-constexpr int kBigWaves = kBig / kWave;       // 16
-constexpr int kItems = 4;                     // consecutive prompts per thread and tile
-constexpr int kTile = kBig * kItems;          // 4096 prompts
-constexpr int kMaxBlocks = 256;               // workgroups of the allocation passes (a power of two)
-constexpr int kMaxClasses = HORA_CLASS_MAX_G0 + 1;
-constexpr int kMinRow = 32;                   // gain-table row length (a power of two), at least
-constexpr int kMaxRow = 256;                  // ... and at most
-constexpr int kTableCap = kMaxClasses * kMinRow;   // doubles per table (2048)
-constexpr unsigned kTiedBit = 0x80000000u;
 constexpr int kPairCap = 16384;               // (table entry, class) pairs ranked one per thread when they fit
-
-constexpr int kSoloMaxPrompts = 2048;   // up to here one workgroup searches alone
-constexpr int kParallelPasses = 7;      // launched grid-wide; a single-workgroup finisher covers the rest
-constexpr unsigned long long kWindowStep = 4ull << 52;   // 4 exponent steps of the bit pattern: a factor 16 in value
-constexpr int kSoloMaxPasses = 512 + 10;   // windows from the largest gain down to zero, plus the narrowing passes
-constexpr int kListCap = 1024;             // gains a workgroup can set aside for the passes that follow
-constexpr long long kCollectMax = 65536;   // a bracket with no more pairs than this is set aside (256 per workgroup on average)
-constexpr unsigned kFlagPending = 1u;      // Bracket::flags: the totals of the last pass have not been applied yet
-constexpr unsigned kFlagCollected = 2u;    // ... the last pass left (or kept) the bracket's gains in the lists
-
-struct Bracket {                  // state of the threshold search between two passes
-    unsigned long long lo;        // count_gt(lo) >= budget
-    unsigned long long hi;        // count_gt(hi) <  budget
-    unsigned long long above;     // pairs whose gain is > hi
-    unsigned int done;            // 1: the bracket has closed, tau = hi; 2: ran out of gains
-    unsigned int flags;           // kFlagPending, kFlagCollected
-};
-struct AllocHeader {              // 256 bytes at the start of the workspace, zero at rest
-    unsigned long long unused0;
-    unsigned long long hi;        // bits of max_i M_i(0), gathered with atomicMax
-    Bracket slot[2];              // pass p reads slot[p & 1] and writes slot[(p + 1) & 1]
-    unsigned long long hi_cur;    // tau once the search has ended
-    unsigned int lists_ok;        // no workgroup ran out of room in its list (written between passes)
-    unsigned int pad0;
-    unsigned long long pad[20];
-};
-static_assert(sizeof(Bracket) == 32, "bracket size");
-static_assert(sizeof(AllocHeader) == 256, "header size");
-
-struct SelectBins {               // per-interval tallies of one workgroup in one search pass
-    unsigned long long cnt[kBins];       // pairs whose gain falls into the interval
-    unsigned long long vmax[kBins];      // largest gain pattern seen in the interval
-    unsigned long long vmin_inv[kBins];  // ~(smallest gain pattern seen in the interval)
-};
-// One SelectBins per workgroup (kMaxBlocks of them) and one more for their totals: every
-// workgroup stores its tallies with plain stores, a small kernel adds them up.  Atomics of
-// all workgroups on one set of intervals serialise at the memory side (hundreds of them
-// per address and pass, each a round trip), which cost more than the walks themselves.
-
-struct BisectSolution {           // written by k_bisect_scan, read by k_bisect_write
-    long long r;                  // units for the prompts tied at tau
-    long long pad[31];
-};
-static_assert(sizeof(BisectSolution) == 256, "solution size");
-
-struct Plan {
-    long long chunk;  // prompts per workgroup, a multiple of kTile
-    int nb;           // workgroups
-};
-
-static Plan make_plan(int64_t n) {
-    long long tiles = (n + kTile - 1) / kTile;
-    long long tpb = (tiles + kMaxBlocks - 1) / kMaxBlocks;
-    if (tpb < 1) tpb = 1;
-    Plan p;
-    p.chunk = tpb * kTile;
-    p.nb = (int)((n + p.chunk - 1) / p.chunk);
-    if (p.nb < 1) p.nb = 1;
-    return p;
-}
-
-static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
-
-struct Workspace {
-    AllocHeader* header;
-    BisectSolution* sol;
-    SelectBins* bins;
-    int* class_hist;        // [kMaxClasses][kMaxBlocks]: prompts of class c in workgroup b
-    double* gain_table;     // [nc][row]: M_c(l)
-    double* surv_table;     // [nc][row]: E_c(l)
-    long long* block_ksum;  // [nb] sums, then exclusive prefixes, of k_i          (BISECT)
-    long long* block_tied;  // [nb] sums, then exclusive prefixes, of tied flags   (BISECT)
-    unsigned long long* lists;   // [kMaxBlocks][kListCap] gains set aside by the search passes (BISECT)
-    int* list_count;             // [kMaxBlocks] entries in each list, -1 when it did not fit
-    size_t bytes;
-};
-
-// The arrays are sized for kMaxBlocks workgroups and kMaxClasses classes whatever n and
-// g0 are, so that a workspace that served one batch serves every other one.
-static Workspace carve(void* base) {
-    Workspace w;
-    char* ptr = (char*)base;
-    size_t off = 0;
-    w.header = (AllocHeader*)(ptr + off);
-    off += sizeof(AllocHeader);
-    w.sol = (BisectSolution*)(ptr + off);
-    off += sizeof(BisectSolution);
-    w.bins = (SelectBins*)(ptr + off);
-    off += (size_t)(kMaxBlocks + 1) * sizeof(SelectBins);   // bins[kMaxBlocks]: the totals
-    w.class_hist = (int*)(ptr + off);
-    off += align256((size_t)kMaxClasses * kMaxBlocks * sizeof(int));
-    w.gain_table = (double*)(ptr + off);
-    off += align256((size_t)kTableCap * sizeof(double));
-    w.surv_table = (double*)(ptr + off);
-    off += align256((size_t)kTableCap * sizeof(double));
-    w.block_ksum = (long long*)(ptr + off);
-    off += align256((size_t)kMaxBlocks * sizeof(long long));
-    w.block_tied = (long long*)(ptr + off);
-    off += align256((size_t)kMaxBlocks * sizeof(long long));
-    w.lists = (unsigned long long*)(ptr + off);
-    off += align256((size_t)kMaxBlocks * kListCap * sizeof(unsigned long long));
-    w.list_count = (int*)(ptr + off);
-    off += align256((size_t)kMaxBlocks * sizeof(int));
-    w.bytes = off;
-    return w;
-}
 
 // ----------------------------------------------------------------------------------
 // Gain / utility tables (Eq. 3, Eq. 5): one thread per posterior, l-major output so
@@ -174,144 +59,10 @@ __global__ __launch_bounds__(kThreads) void k_gain_table(long long n, const doub
 }
 
 // ----------------------------------------------------------------------------------
-// Tie resolution and output of one tile of a workgroup's chunk, shared by both methods.
-//
-// Every thread holds kItems consecutive prompts with k (gains above tau) and the tied
-// flag.  A workgroup scan of the tied flags gives each prompt the number of tied prompts
-// before it; the first r of them (by index) win one more unit.  The group offset of
-// prompt i is g0*i + sum_{i'<i} k_i' + min(tied prompts before i, r).
-// ----------------------------------------------------------------------------------
-struct EmitCarry {
-    long long rank_base;   // tied prompts with a lower index than the current tile
-    long long ks_base;     // sum of k over prompts with a lower index than the current tile
-};
-
-struct EmitShared {        // LDS exchange between the wavefronts of a workgroup, double-buffered
-    int tied[2][kBigWaves];
-    long long ksum[2][kBigWaves];
-};
-
-template <typename V, typename T>
-__device__ __forceinline__ void store_items(T* __restrict__ dst, long long pos, long long end, bool vec_ok,
-                                            const T (&x)[kItems]) {
-    constexpr int kPer = (int)(sizeof(V) / sizeof(T));
-    if (vec_ok && pos + kItems <= end) {
-#pragma unroll
-        for (int q = 0; q < kItems / kPer; ++q) {
-            V v;
-#pragma unroll
-            for (int i = 0; i < kPer; ++i) v[i] = x[q * kPer + i];
-            *reinterpret_cast<V*>(dst + pos + q * kPer) = v;
-        }
-    } else {
-#pragma unroll
-        for (int j = 0; j < kItems; ++j)
-            if (pos + j < end) dst[pos + j] = x[j];
-    }
-}
-
-template <int kOff>
-__device__ __forceinline__ void emit_tile(int tile_parity, long long pos, long long end, long long n, int g0,
-                                          long long r, const int (&kk)[kItems], const int (&td)[kItems],
-                                          EmitCarry& carry, int (&dd)[kItems], bool (&win)[kItems],
-                                          int32_t* __restrict__ delta, void* __restrict__ group_off, bool d_vec,
-                                          bool o_vec, EmitShared* sh) {
-    const int w = wave_id();
-    // tied prompts before this thread inside the wavefront: ballots, no data movement
-    int t_before = 0, t_wave = 0;
-#pragma unroll
-    for (int j = 0; j < kItems; ++j) {
-        const unsigned long long m = __ballot(td[j] != 0);
-        t_before += lanes_below(m);
-        t_wave += __popcll(m);
-    }
-    long long ks = 0, ks_incl = 0, ks_wave = 0;
-    if (kOff != 0) {
-#pragma unroll
-        for (int j = 0; j < kItems; ++j) ks += kk[j];
-        ks_incl = wave_incl_scan_i64(ks);
-        ks_wave = ((long long)wave_last_i32((int)(ks_incl >> 32)) << 32) |
-                  (unsigned)wave_last_i32((int)(ks_incl & 0xffffffffll));
-    }
-    if (lane_id() == 0) {
-        sh->tied[tile_parity][w] = t_wave;
-        if (kOff != 0) sh->ksum[tile_parity][w] = ks_wave;
-    }
-    __syncthreads();
-    // totals of the lower wavefronts: lanes 0..15 hold one wavefront's total each, a DPP
-    // prefix sum inside the first row of 16 lanes gives every wavefront its base
-    const int lane = lane_id();
-    const int t_in = lane < kBigWaves ? sh->tied[tile_parity][lane] : 0;
-    const int t_scan = wave_incl_scan_i32(t_in);
-    const int t_total = __builtin_amdgcn_readlane(t_scan, kBigWaves - 1);
-    const int t_lower = w > 0 ? __builtin_amdgcn_readlane(t_scan, w - 1) : 0;
-    long long ks_lower = 0, ks_total = 0;
-    if (kOff != 0) {
-        const long long q_in = lane < kBigWaves ? sh->ksum[tile_parity][lane] : 0;
-        const long long q_scan = wave_incl_scan_i64(q_in);
-        const int q_lo = (int)(q_scan & 0xffffffffll), q_hi = (int)(q_scan >> 32);
-        ks_total = ((long long)__builtin_amdgcn_readlane(q_hi, kBigWaves - 1) << 32) |
-                   (unsigned)__builtin_amdgcn_readlane(q_lo, kBigWaves - 1);
-        if (w > 0)
-            ks_lower = ((long long)__builtin_amdgcn_readlane(q_hi, w - 1) << 32) |
-                       (unsigned)__builtin_amdgcn_readlane(q_lo, w - 1);
-    }
-    long long rank = carry.rank_base + t_lower + t_before;
-    long long kprior = carry.ks_base + ks_lower + (ks_incl - ks);
-    long long off[kItems + 1];
-#pragma unroll
-    for (int j = 0; j < kItems; ++j) {
-        off[j] = (long long)g0 * (pos + j) + kprior + (rank < r ? rank : r);
-        win[j] = td[j] && rank < r;
-        dd[j] = kk[j] + (win[j] ? 1 : 0);
-        rank += td[j];
-        kprior += kk[j];
-    }
-    off[kItems] = (long long)g0 * (pos + kItems) + kprior + (rank < r ? rank : r);
-
-    store_items<v4i, int32_t>(delta, pos, end, d_vec, dd);
-    if (kOff == 1) {
-        int32_t* go = reinterpret_cast<int32_t*>(group_off);
-        int32_t o32[kItems];
-#pragma unroll
-        for (int j = 0; j < kItems; ++j) o32[j] = (int32_t)off[j];
-        store_items<v4i, int32_t>(go, pos, end, o_vec, o32);
-#pragma unroll
-        for (int j = 0; j < kItems; ++j)
-            if (pos + j == n - 1) go[n] = (int32_t)off[j + 1];
-    } else if (kOff == 2) {
-        long long* go = reinterpret_cast<long long*>(group_off);
-        long long o64[kItems];
-#pragma unroll
-        for (int j = 0; j < kItems; ++j) o64[j] = off[j];
-        store_items<v2l, long long>(go, pos, end, o_vec, o64);
-#pragma unroll
-        for (int j = 0; j < kItems; ++j)
-            if (pos + j == n - 1) go[n] = off[j + 1];
-    }
-    carry.rank_base += t_total;
-    carry.ks_base += ks_total;
-}
-
-// ----------------------------------------------------------------------------------
 // CLASS pass 1: per-workgroup histogram of c (lane k of every wavefront accumulates the
 // count of class k from wavefront ballots), and, in one extra workgroup, the gain and
 // survival tables of the G0+1 classes.
 // ----------------------------------------------------------------------------------
-__device__ __forceinline__ void load_items_i32(const int32_t* __restrict__ src, long long pos, long long end,
-                                               bool vec_ok, int fill, int (&v)[kItems]) {
-    if (vec_ok && pos + kItems <= end) {
-#pragma unroll
-        for (int q = 0; q < kItems / 4; ++q) {
-            const v4i x = *reinterpret_cast<const v4i*>(src + pos + 4 * q);
-            v[4 * q] = x.x; v[4 * q + 1] = x.y; v[4 * q + 2] = x.z; v[4 * q + 3] = x.w;
-        }
-    } else {
-#pragma unroll
-        for (int j = 0; j < kItems; ++j) v[j] = (pos + j < end) ? src[pos + j] : fill;
-    }
-}
-
 __global__ __launch_bounds__(kBig) void k_class_hist(const int32_t* __restrict__ c, long long n, int g0,
                                                      double alpha0, double beta0, long long chunk, int nb, int row,
                                                      int* __restrict__ class_hist, double* __restrict__ gain_table,
@@ -797,462 +548,6 @@ __global__ __launch_bounds__(kBig) void k_class_write(const int32_t* __restrict_
     }
 }
 
-// ----------------------------------------------------------------------------------
-// BISECT pass 0: the largest gain hi = max_i M_i(0), gathered with integer atomicMax (few
-// workgroups: atomics on one address serialise).
-// ----------------------------------------------------------------------------------
-template <class Src>
-__global__ __launch_bounds__(kBig) void k_select_top(Src src, long long n, AllocHeader* __restrict__ hdr,
-                                                     int32_t* dev_status) {
-    __shared__ unsigned long long s_red[kBigWaves];
-    unsigned long long hi = 0;
-    bool bad = false;
-    const long long stride = (long long)gridDim.x * kBig;
-    for (long long i = (long long)blockIdx.x * kBig + threadIdx.x; i < n; i += stride) {
-        double a, b;
-        bad |= !src.load(i, a, b);
-        const unsigned long long gb = gain_bits(gain_first(a, a + b));
-        hi = gb > hi ? gb : hi;
-    }
-    hi = wave_max_u64(hi);
-    if (lane_id() == 0) s_red[wave_id()] = hi;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        unsigned long long block_hi = 0;
-        for (int i = 0; i < kBigWaves; ++i) block_hi = s_red[i] > block_hi ? s_red[i] : block_hi;
-        atomicMax(&hdr->hi, block_hi);   // the first search pass turns it into the first window
-    }
-    if (bad) report(dev_status, HORA_ERR_RANGE);
-}
-
-// ----------------------------------------------------------------------------------
-// BISECT search pass.  Invariant: exactly `above` pairs have a gain > hi_cur, and
-// above < budget.  The bracket (lo, hi] is cut into at most kBins intervals of 2^shift bit
-// patterns.  Every prompt walks its gains from l = 0 down to lo (a monotone search) and
-// the gains inside the bracket are tallied per interval, together with the largest and the
-// smallest pattern seen there.  If the running count from the top interval down reaches
-// the budget in interval j, the bracket shrinks to the gains that actually occur there,
-// (min - 1, max], and closes when min == max (tau is that gain): each such pass cuts the
-// bracket at least 128-fold; with real-valued posteriors it keeps ~1/256 of the gains of
-// the pass before, with a shared prior (few distinct gains, each repeated) it closes in
-// two passes.  Otherwise the whole window lies above tau: its count is added to `above`
-// and the next window, a factor 16 further down in value (4 exponent steps of the bit
-// pattern), is taken.  Searching window by window from the top keeps the walks short: a
-// window's count is a small multiple of the one before, so the work stays a small
-// multiple of the budget, whereas a bracket from a guaranteed lower bound (such as the
-// smallest ceil(budget/n)-th gain) can lie orders of magnitude below tau and make every
-// prompt walk thousands of steps.
-//
-// kSolo = false: every workgroup tallies its share into a slot of its own; k_select_reduce
-// adds the slots up, and every workgroup of the next pass moves the bracket by those
-// totals for itself (the same arithmetic on the same numbers in every workgroup), which
-// takes a few microseconds less than a one-workgroup kernel in between that has to pull
-// all slots through one compute unit.  The bracket is kept twice: pass p reads slot
-// p & 1, which nobody writes meanwhile, and its first workgroup stores the moved bracket
-// in the other slot for pass p + 1.
-// kSolo = true: one workgroup repeats passes over all prompts until the bracket closes.
-// It runs after the grid-wide passes and normally finds the bracket closed already; it is
-// there so that a fixed, small number of launches is correct for any input.
-// ----------------------------------------------------------------------------------
-struct SelectShared {
-    unsigned long long cnt[kBins];
-    unsigned long long vmax[kBins];
-    unsigned long long vmin_inv[kBins];
-    long long red[kBigWaves];
-    unsigned long long lo, hi;
-    long long above;
-    long long inside;   // pairs in the bracket after a step that narrowed it (-1: not known)
-    int done;
-    int hit;            // the last step narrowed the bracket (it did not move to the next window)
-    int list_n;         // gains this workgroup has set aside in this pass
-};
-
-// The step that ends a search pass, run by a whole workgroup: thread t < kBins holds the
-// tally (cj, mx, mn) of interval kBins - 1 - t (thread 0 the top one), the other threads
-// zeros.  Finds the interval in which the running count from the top reaches the budget
-// and shrinks the bracket to the gains seen there, or, when the whole window lies above
-// tau, takes the next window.
-__device__ __forceinline__ void move_bracket(SelectShared& sh, unsigned long long cj, unsigned long long mx,
-                                             unsigned long long mn, long long budget) {
-    const unsigned long long lo = sh.lo;
-    const long long start = sh.above;   // pairs above the bracket
-    if (cj > (unsigned long long)budget) cj = (unsigned long long)budget;
-    __syncthreads();                                     // sh.red is free, the bracket has been read
-    // pairs in higher intervals: exclusive prefix over the threads
-    const long long incl = wave_incl_scan<long long>((long long)cj);
-    if (lane_id() == kWave - 1) sh.red[wave_id()] = incl;
-    __syncthreads();
-    long long before = start + incl - (long long)cj;
-    long long total = 0;
-    for (int i = 0; i < kBigWaves; ++i) {
-        if (i < wave_id()) before += sh.red[i];
-        total += sh.red[i];
-    }
-    if (start + total < budget) {                       // uniform: the whole window is above tau
-        if (threadIdx.x == 0) {
-            sh.above = start + total;
-            sh.hi = lo;
-            sh.lo = lo > kWindowStep ? lo - kWindowStep : 0ull;
-            if (lo == 0ull) sh.done = 2;                // no gains left: the budget does not fit
-            sh.hit = 0;
-            sh.inside = -1;
-        }
-    } else if (cj != 0 && before < budget && budget <= before + (long long)cj) {   // exactly one thread
-        sh.above = before;
-        sh.hi = mx;
-        sh.lo = mn - 1ull;
-        sh.done = (mx == mn) ? 1 : 0;
-        sh.hit = 1;
-        sh.inside = (long long)cj;                      // (a count cut off at the budget is no larger than the true one)
-    }
-    __syncthreads();
-}
-
-template <class Src, bool kSolo>
-__global__ __launch_bounds__(kBig) void k_select_pass(Src src, long long n, long long budget, long long limit,
-                                                      int pass, AllocHeader* __restrict__ hdr,
-                                                      SelectBins* __restrict__ bins,
-                                                      unsigned long long* __restrict__ lists,
-                                                      int* __restrict__ list_count) {
-    __shared__ SelectShared sh;
-    // the bracket this pass works on: the stored one, moved by the totals of the pass before
-    const Bracket* in = &hdr->slot[pass & 1];
-    const bool pending = pass > 0 && (in->flags & kFlagPending) != 0 && in->done == 0;   // uniform
-    {
-        const SelectBins* totals = bins + kMaxBlocks;
-        const int j = kBins - 1 - (int)threadIdx.x;   // thread 0 owns the top interval
-        unsigned long long cj = 0, mx = 0, mn = 0;
-        if (pending && threadIdx.x < kBins) {
-            cj = totals->cnt[j];
-            mx = totals->vmax[j];
-            mn = ~totals->vmin_inv[j];
-        }
-        if (threadIdx.x == 0) {
-            if (pass == 0) {   // the first window, from the largest gain down
-                const unsigned long long all_hi = hdr->hi;
-                sh.hi = all_hi;
-                sh.lo = all_hi > kWindowStep ? all_hi - kWindowStep : 0ull;
-                sh.above = 0;
-                sh.done = 0;
-            } else {
-                sh.lo = in->lo; sh.hi = in->hi; sh.above = (long long)in->above; sh.done = (int)in->done;
-            }
-            sh.hit = 0;
-            sh.inside = -1;
-            sh.list_n = 0;
-        }
-        __syncthreads();
-        if (pending) move_bracket(sh, cj, mx, mn, budget);
-    }
-    // Where this pass gets the gains of its bracket from.  A bracket that has been narrowed
-    // to few pairs is set aside while it is walked once more (kCollect: every workgroup
-    // keeps the gains it finds in a list of its own); the passes after that tally from the
-    // lists instead of walking every prompt again (kFromLists) -- brackets only shrink
-    // from there on, so the lists stay a superset of what is needed.  A list that does not
-    // fit (lists_ok == 0) only means that the next pass walks again.
-    enum { kWalk = 0, kCollect = 1, kFromLists = 2 };
-    int mode = kWalk;
-    if (!kSolo && pending && sh.hit && !sh.done) {
-        if ((in->flags & kFlagCollected) != 0 && hdr->lists_ok != 0) mode = kFromLists;
-        else if (sh.inside <= kCollectMax) mode = kCollect;
-    }
-    if (!kSolo && blockIdx.x == 0 && threadIdx.x == 0) {   // for the next pass
-        Bracket* out = &hdr->slot[(pass + 1) & 1];
-        out->lo = sh.lo; out->hi = sh.hi; out->above = (unsigned long long)sh.above;
-        out->done = (unsigned)sh.done;
-        // this pass tallies unless the search has ended
-        out->flags = (sh.done ? 0u : kFlagPending) | (mode != kWalk ? kFlagCollected : 0u);
-    }
-    const int iters = kSolo ? kSoloMaxPasses : 1;
-    for (int iter = 0; iter < iters; ++iter) {
-        if (sh.done) break;
-        const unsigned long long lo = sh.lo, hi = sh.hi;
-        const unsigned long long width = hi - lo;                  // >= 1
-        const int bitlen = width > 1 ? 64 - __clzll((long long)(width - 1)) : 0;   // bits of width - 1
-        const int shift = bitlen > 8 ? bitlen - 8 : 0;             // (width - 1) >> shift < kBins
-        if (threadIdx.x < kBins) { sh.cnt[threadIdx.x] = 0; sh.vmax[threadIdx.x] = 0; sh.vmin_inv[threadIdx.x] = 0; }
-        __syncthreads();
-
-        const long long stride = (long long)gridDim.x * kBig;
-        const int lane = lane_id();
-        if (mode == kFromLists) {   // (never in the solo kernel)
-            const int have = list_count[blockIdx.x];
-            const unsigned long long* mine = lists + (long long)blockIdx.x * kListCap;
-            for (int e = (int)threadIdx.x; e < have; e += kBig) {
-                const unsigned long long v = mine[e];
-                if (v > lo && v <= hi) {
-                    const int j = (int)((v - lo - 1ull) >> shift);
-                    atomicAdd(&sh.cnt[j], 1ull);
-                    atomicMax(&sh.vmax[j], v);
-                    atomicMax(&sh.vmin_inv[j], ~v);
-                }
-            }
-        } else
-        // all wavefronts run the same number of rounds, so that the ballots below see whole wavefronts
-        for (long long i0 = (long long)blockIdx.x * kBig; i0 < n; i0 += stride) {
-            const long long i = i0 + threadIdx.x;
-            double a = 1.0, b = 1.0;
-            if (i < n) src.load(i, a, b);
-            const double s = a + b;
-            double g = gain_first(a, s);
-            double lf = 0.0;
-            long long k = 0;
-            unsigned long long gb = gain_bits(g);
-            bool active = i < n && k < limit && gb > lo;
-            while (__ballot(active)) {
-                const bool inside = active && gb <= hi;
-                if (mode == kCollect && inside) {
-                    const int at = atomicAdd(&sh.list_n, 1);
-                    if (at < kListCap) lists[(long long)blockIdx.x * kListCap + at] = gb;
-                }
-                // lanes that hold the same gain (common under a shared prior) tally once:
-                // up to 8 distinct gains per step through a leader, the rest lane by lane
-                unsigned long long pending = __ballot(inside);
-                for (int round = 0; round < 8 && pending; ++round) {
-                    const int leader = __ffsll((long long)pending) - 1;
-                    const unsigned long long v = read_lane_u64(gb, leader);
-                    const unsigned long long same = __ballot(inside && gb == v);
-                    // gains that do not repeat (per-prompt posteriors): no point in more rounds
-                    if (round == 0 && same == (1ull << leader)) break;
-                    if (lane == leader) {
-                        const int j = (int)((v - lo - 1ull) >> shift);
-                        // no result is used: the three updates are issued without a wait
-                        atomicAdd(&sh.cnt[j], (unsigned long long)__popcll(same));
-                        atomicMax(&sh.vmax[j], v);
-                        atomicMax(&sh.vmin_inv[j], ~v);
-                    }
-                    pending &= ~same;
-                }
-                if (inside && ((pending >> lane) & 1ull)) {
-                    const int j = (int)((gb - lo - 1ull) >> shift);
-                    atomicAdd(&sh.cnt[j], 1ull);
-                    atomicMax(&sh.vmax[j], gb);
-                    atomicMax(&sh.vmin_inv[j], ~gb);
-                }
-                if (active) {
-                    g = gain_next(g, b, s, lf);
-                    lf += 1.0;
-                    k += 1;
-                    gb = gain_bits(g);
-                    active = k < limit && gb > lo;
-                }
-            }
-        }
-        __syncthreads();   // the workgroup's tallies are complete
-        if (!kSolo) {
-            // this workgroup's tallies to its own slot (all of them: the slot holds no state);
-            // k_select_reduce adds the slots up after this kernel has ended
-            if (mode == kCollect && threadIdx.x == 0) list_count[blockIdx.x] = sh.list_n <= kListCap ? sh.list_n : -1;
-            SelectBins* mine = bins + blockIdx.x;
-            if (threadIdx.x < kBins) {
-                const unsigned long long c0 = sh.cnt[threadIdx.x];
-                mine->cnt[threadIdx.x] = c0 > (unsigned long long)budget ? (unsigned long long)budget : c0;
-                mine->vmax[threadIdx.x] = sh.vmax[threadIdx.x];
-                mine->vmin_inv[threadIdx.x] = sh.vmin_inv[threadIdx.x];
-            }
-            return;
-        }
-        // tallies of interval j = kBins - 1 - thread: thread 0 owns the top interval
-        const int j = kBins - 1 - (int)threadIdx.x;
-        unsigned long long cj = 0, mx = 0, mn = 0;
-        if (threadIdx.x < kBins) {
-            cj = sh.cnt[j];
-            mx = sh.vmax[j];
-            mn = ~sh.vmin_inv[j];
-        }
-        move_bracket(sh, cj, mx, mn, budget);
-    }
-    if (kSolo && threadIdx.x == 0) hdr->hi_cur = sh.hi;   // tau
-}
-
-// ----------------------------------------------------------------------------------
-// Between two grid-wide search passes: the interval tallies of the workgroups are added up
-// (counts) and combined (largest, smallest gain) into bins[kMaxBlocks].  kReduceBins
-// intervals per workgroup, 32 lanes per interval striding over the slots.  A kernel of its
-// own rather than "the workgroup that finishes last": the device-wide fences that pattern
-// needs (write back and invalidate the L2 of every die) cost several times the pass itself
-// on this part.
-// ----------------------------------------------------------------------------------
-constexpr int kReduceBins = kThreads / 32;   // 8 intervals per workgroup of 256 threads
-
-__global__ __launch_bounds__(kThreads) void k_select_reduce(int nb, int pass, AllocHeader* __restrict__ hdr,
-                                                            SelectBins* __restrict__ bins,
-                                                            const int* __restrict__ list_count) {
-    const unsigned flags = hdr->slot[(pass + 1) & 1].flags;
-    if ((flags & kFlagPending) == 0) return;   // pass `pass` did not tally: the search has ended
-    if (blockIdx.x == 0 && (flags & kFlagCollected) != 0) {   // did every workgroup's list fit?
-        static_assert(kMaxBlocks <= kThreads, "one thread per list");
-        const int any_bad = __syncthreads_or((int)threadIdx.x < nb && list_count[threadIdx.x] < 0 ? 1 : 0);
-        if (threadIdx.x == 0) hdr->lists_ok = any_bad ? 0u : 1u;
-    }
-    const int bin = (int)blockIdx.x * kReduceBins + (int)threadIdx.x / 32;
-    const int sub = (int)threadIdx.x & 31;
-    unsigned long long c = 0, mx = 0, mn = 0;
-    constexpr int kPer = kMaxBlocks / 32;                 // slots per lane, all loads issued at once
-    unsigned long long pc[kPer], pm[kPer], pn[kPer];
-#pragma unroll
-    for (int t = 0; t < kPer; ++t) {
-        const int wg = sub + 32 * t;
-        const bool in = wg < nb;
-        pc[t] = in ? bins[wg].cnt[bin] : 0ull;
-        pm[t] = in ? bins[wg].vmax[bin] : 0ull;
-        pn[t] = in ? bins[wg].vmin_inv[bin] : 0ull;
-    }
-#pragma unroll
-    for (int t = 0; t < kPer; ++t) {
-        c += pc[t];
-        mx = pm[t] > mx ? pm[t] : mx;
-        mn = pn[t] > mn ? pn[t] : mn;
-    }
-#pragma unroll
-    for (int d = 16; d > 0; d >>= 1) {
-        c += (unsigned long long)__shfl_xor((long long)c, d, 32);
-        const unsigned long long om = (unsigned long long)__shfl_xor((long long)mx, d, 32);
-        const unsigned long long on = (unsigned long long)__shfl_xor((long long)mn, d, 32);
-        mx = om > mx ? om : mx;
-        mn = on > mn ? on : mn;
-    }
-    if (sub == 0) {
-        SelectBins* totals = bins + kMaxBlocks;
-        totals->cnt[bin] = c;
-        totals->vmax[bin] = mx;
-        totals->vmin_inv[bin] = mn;
-    }
-}
-
-// ----------------------------------------------------------------------------------
-// BISECT finalize: with tau = hi_cur, k_i = #{l : M_i(l) > tau} and the tied flag go
-// to delta[i] (flag in bit 31), the survival product E_i(k_i) to util[i]; per-workgroup
-// sums go to block_ksum / block_tied.
-// ----------------------------------------------------------------------------------
-template <class Src>
-__global__ __launch_bounds__(kBig) void k_bisect_finalize(Src src, long long n, long long chunk, long long budget,
-                                                          long long limit, const AllocHeader* __restrict__ hdr,
-                                                          int32_t* __restrict__ delta, double* __restrict__ util,
-                                                          long long* __restrict__ block_ksum,
-                                                          long long* __restrict__ block_tied) {
-    __shared__ long long s_red[2][kBigWaves];
-    const unsigned long long tau_bits = budget > 0 ? hdr->hi_cur : ~0ull;
-    const long long base = (long long)blockIdx.x * chunk;
-    const long long end = base + chunk < n ? base + chunk : n;
-    long long ks = 0, ts = 0;
-    for (long long i = base + threadIdx.x; i < end; i += kBig) {
-        double a, b, g, lf, e;
-        src.load(i, a, b);
-        const long long k = walk_above<true>(a, b, tau_bits, limit, g, lf, e);
-        const bool tied = (k < limit) && (gain_bits(g) == tau_bits);
-        delta[i] = (int32_t)((unsigned)k | (tied ? kTiedBit : 0u));
-        if (util) util[i] = e;
-        ks += k;
-        ts += tied ? 1 : 0;
-    }
-    ks = wave_total_i64(ks);
-    ts = wave_total_i64(ts);
-    if (lane_id() == 0) { s_red[0][wave_id()] = ks; s_red[1][wave_id()] = ts; }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        long long ksum = 0, tsum = 0;
-        for (int i = 0; i < kBigWaves; ++i) { ksum += s_red[0][i]; tsum += s_red[1][i]; }
-        block_ksum[blockIdx.x] = ksum;
-        block_tied[blockIdx.x] = tsum;
-    }
-}
-
-// BISECT scan (one workgroup): exclusive prefixes over the workgroups, r, the report,
-// and the header back to its rest state.
-__global__ __launch_bounds__(kThreads) void k_bisect_scan(int nb, long long budget, AllocHeader* __restrict__ hdr,
-                                                          BisectSolution* __restrict__ sol,
-                                                          long long* __restrict__ block_ksum,
-                                                          long long* __restrict__ block_tied,
-                                                          hora_alloc_summary* __restrict__ summary,
-                                                          int32_t* dev_status) {
-    __shared__ long long s_scan[kWaves];
-    long long kcarry = 0, tcarry = 0;
-    for (int b0 = 0; b0 < nb; b0 += kThreads) {
-        const int b = b0 + (int)threadIdx.x;
-        const long long kv = b < nb ? block_ksum[b] : 0;
-        const long long tv = b < nb ? block_tied[b] : 0;
-        long long ktot, ttot;
-        const long long kex = block_excl_scan<long long>(kv, s_scan, ktot);
-        const long long tex = block_excl_scan<long long>(tv, s_scan, ttot);
-        if (b < nb) {
-            block_ksum[b] = kcarry + kex;
-            block_tied[b] = tcarry + tex;
-        }
-        kcarry += ktot;
-        tcarry += ttot;
-    }
-    if (threadIdx.x == 0) {
-        const long long r = budget - kcarry;
-        if (r < 0 || r > tcarry) report(dev_status, HORA_ERR_RANGE);  // invalid posteriors upstream
-        sol->r = r;
-        if (summary) {
-            summary->tau = budget > 0 ? __longlong_as_double((long long)hdr->hi_cur) : 0.0;
-            summary->count_gt = kcarry;
-            summary->tie_units = r;
-            summary->tie_prompts = tcarry;
-        }
-        hdr->hi = 0ull;
-        hdr->hi_cur = 0ull;
-        for (int i = 0; i < 2; ++i) {
-            hdr->slot[i].lo = 0ull; hdr->slot[i].hi = 0ull; hdr->slot[i].above = 0ull;
-            hdr->slot[i].done = 0u; hdr->slot[i].flags = 0u;
-        }
-        hdr->lists_ok = 0u;
-    }
-}
-
-// BISECT write: delta[i] holds k_i with the tied flag in bit 31 and util[i] the survival
-// product E_i(k_i); a winner's utility takes one more step of the product.
-template <class Src, int kOff>
-__global__ __launch_bounds__(kBig) void k_bisect_write(Src src, long long n, int g0, long long chunk,
-                                                           const BisectSolution* __restrict__ sol,
-                                                           const long long* __restrict__ block_ksum,
-                                                           const long long* __restrict__ block_tied,
-                                                           int32_t* __restrict__ delta, double* __restrict__ util,
-                                                           void* __restrict__ group_off) {
-    __shared__ EmitShared s_emit;
-    const long long r = sol->r;
-    const long long base = (long long)blockIdx.x * chunk;
-    const long long end = base + chunk < n ? base + chunk : n;
-    const bool d_vec = (reinterpret_cast<uintptr_t>(delta) & 15) == 0;
-    const bool u_vec = (reinterpret_cast<uintptr_t>(util) & 15) == 0;
-    const bool o_vec = (reinterpret_cast<uintptr_t>(group_off) & 15) == 0;
-    EmitCarry carry = {block_tied[blockIdx.x], block_ksum[blockIdx.x]};
-    int parity = 0;
-    for (long long t0 = base; t0 < end; t0 += kTile, parity ^= 1) {
-        const long long pos = t0 + (long long)threadIdx.x * kItems;
-        int raw[kItems];
-        load_items_i32(delta, pos, end, d_vec, 0, raw);
-        int kk[kItems], td[kItems], dd[kItems];
-        bool win[kItems];
-#pragma unroll
-        for (int j = 0; j < kItems; ++j) {
-            kk[j] = (int)((unsigned)raw[j] & ~kTiedBit);
-            td[j] = ((unsigned)raw[j] & kTiedBit) ? 1 : 0;
-        }
-        emit_tile<kOff>(parity, pos, end, n, g0, r, kk, td, carry, dd, win, delta, group_off, d_vec, o_vec,
-                        &s_emit);
-        if (util) {
-            double uu[kItems];
-#pragma unroll
-            for (int j = 0; j < kItems; ++j) {
-                double e = 1.0;
-                if (pos + j < end) {
-                    e = util[pos + j];
-                    if (win[j]) {
-                        double a, b;
-                        src.load(pos + j, a, b);
-                        e = surv_next(e, b, a + b, (double)kk[j]);
-                    }
-                }
-                uu[j] = 1.0 - e;
-            }
-            store_items<v2d, double>(util, pos, end, u_vec, uu);
-        }
-    }
-}
-
 template <typename T>
 __global__ void k_store_one(T* p, T v) {
     if (blockIdx.x == 0 && threadIdx.x == 0) *p = v;
@@ -1265,24 +560,6 @@ __global__ void k_zero_summary(hora_alloc_summary* s) {
 // ----------------------------------------------------------------------------------
 // Host side
 // ----------------------------------------------------------------------------------
-static int check_launch() { return hipGetLastError() == hipSuccess ? HORA_OK : HORA_ERR_HIP; }
-
-struct CommonArgs {
-    int64_t n;
-    int32_t g0;
-    int64_t budget;
-    int32_t delta_max;
-    int32_t* delta;
-    double* util;
-    void* group_off;
-    int32_t off_t;
-    hora_alloc_summary* summary;
-    int32_t* dev_status;
-    void* workspace;
-    size_t workspace_bytes;
-    hipStream_t stream;
-};
-
 static int validate_common(const CommonArgs& a) {
     if (a.n < 0 || a.g0 < 0 || a.budget < 0) return HORA_ERR_INVALID_ARG;
     if (!a.dev_status) return HORA_ERR_INVALID_ARG;
@@ -1353,51 +630,6 @@ static int run_class(const int32_t* c, double alpha0, double beta0, const Common
     return check_launch();
 }
 
-static int run_small(const CountsSource& src, const CommonArgs& a) {
-    return allocate_small_counts(src, a.n, a.g0, a.budget, a.delta_max, a.delta, a.util, a.group_off, a.off_t,
-                                 a.summary, a.dev_status, a.stream);
-}
-static int run_small(const PosteriorSource& src, const CommonArgs& a) {
-    return allocate_small_posterior(src, a.n, a.g0, a.budget, a.delta_max, a.delta, a.util, a.group_off, a.off_t,
-                                    a.summary, a.dev_status, a.stream);
-}
-
-template <class Src>
-static int run_bisect(const Src& src, const CommonArgs& a, const Plan& p, const Workspace& w) {
-    const long long n = a.n;
-    // a batch that one workgroup can hold: one launch does the whole search and the outputs
-    if (n <= kSoloMaxPrompts) return run_small(src, a);
-    long long limit = a.delta_max > 0 ? (long long)a.delta_max : a.budget;
-    if (limit > a.budget) limit = a.budget;
-    if (a.budget > 0) {
-        long long blocks = (n + kBig - 1) / kBig;
-        if (blocks > kMaxBlocks) blocks = kMaxBlocks;
-        hipLaunchKernelGGL((k_select_top<Src>), dim3((unsigned)blocks), dim3(kBig), 0, a.stream, src, n, w.header,
-                           a.dev_status);
-        for (int pass = 0; pass < kParallelPasses; ++pass) {
-            hipLaunchKernelGGL((k_select_pass<Src, false>), dim3((unsigned)blocks), dim3(kBig), 0, a.stream, src,
-                               n, (long long)a.budget, limit, pass, w.header, w.bins, w.lists, w.list_count);
-            hipLaunchKernelGGL(k_select_reduce, dim3(kBins / kReduceBins), dim3(kThreads), 0, a.stream, (int)blocks,
-                               pass, w.header, w.bins, (const int*)w.list_count);
-        }
-        hipLaunchKernelGGL((k_select_pass<Src, true>), dim3(1), dim3(kBig), 0, a.stream, src, n,
-                           (long long)a.budget, limit, kParallelPasses, w.header, w.bins, w.lists, w.list_count);
-    }
-    hipLaunchKernelGGL((k_bisect_finalize<Src>), dim3(p.nb), dim3(kBig), 0, a.stream, src, n, p.chunk,
-                       (long long)a.budget, limit, w.header, a.delta, a.util, w.block_ksum, w.block_tied);
-    hipLaunchKernelGGL(k_bisect_scan, dim3(1), dim3(kThreads), 0, a.stream, p.nb, (long long)a.budget, w.header,
-                       w.sol, w.block_ksum, w.block_tied, a.summary, a.dev_status);
-    const int mode = a.group_off ? (a.off_t == HORA_I32 ? 1 : 2) : 0;
-#define HORA_LAUNCH_BISECT_WRITE(M)                                                                      \
-    hipLaunchKernelGGL((k_bisect_write<Src, M>), dim3(p.nb), dim3(kBig), 0, a.stream, src, n, (int)a.g0, \
-                       p.chunk, w.sol, w.block_ksum, w.block_tied, a.delta, a.util, a.group_off)
-    if (mode == 0) HORA_LAUNCH_BISECT_WRITE(0);
-    else if (mode == 1) HORA_LAUNCH_BISECT_WRITE(1);
-    else HORA_LAUNCH_BISECT_WRITE(2);
-#undef HORA_LAUNCH_BISECT_WRITE
-    return check_launch();
-}
-
 // ----------------------------------------------------------------------------------
 // Workspace for callers that cannot allocate (hora_allocate_static): a file-scope device
 // array, one copy per GPU, held until the process ends.  Its name is a host-side stand-in
@@ -1439,7 +671,7 @@ extern "C" {
 
 size_t hora_allocate_workspace_bytes(int64_t n, int32_t g0) {
     if (n < 0 || g0 < 0) return 0;
-    Workspace w = carve(nullptr);
+    Workspace w = carve(nullptr, n);
     return w.bytes;
 }
 
@@ -1467,7 +699,7 @@ int hora_allocate_static(int64_t n, int32_t g0, const int32_t* c, double alpha0,
                          int32_t delta_max, int32_t method, int32_t* delta, double* util, void* group_off,
                          int32_t off_t, hora_alloc_summary* summary, int32_t* dev_status, void* stream) {
     if (n > (int64_t)HORA_STATIC_MAX_PROMPTS) return HORA_ERR_UNSUPPORTED;
-    if (n >= 0 && g0 >= 0 && carve(nullptr).bytes > kStaticScratchBytes) return HORA_ERR_UNSUPPORTED;
+    if (n >= 0 && g0 >= 0 && carve(nullptr, n).bytes > kStaticScratchBytes) return HORA_ERR_UNSUPPORTED;
     void* ptr = nullptr;
     const int rc = static_scratch(&ptr);
     if (rc != HORA_OK) return rc;
@@ -1496,12 +728,12 @@ int allocate_shared_prior(int64_t n, int32_t g0, const int32_t* c, double alpha0
     if (n == 0) return handle_empty(a);
     if (!c || (reinterpret_cast<uintptr_t>(c) & 3)) return HORA_ERR_INVALID_ARG;
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255)) return HORA_ERR_WORKSPACE;
-    Workspace w = carve(workspace);
+    Workspace w = carve(workspace, n);
     if (workspace_bytes < w.bytes) return HORA_ERR_WORKSPACE;
     const Plan p = make_plan(n);
     if (method == HORA_ALLOC_BISECT) {
         CountsSource src{c, g0, alpha0, beta0};
-        return run_bisect(src, a, p, w);
+        return run_bisect_counts(src, a, p, w);
     }
     return run_class(c, alpha0, beta0, a, p, w, 0);
 }
@@ -1529,7 +761,7 @@ int hora_allocate_baseline(int64_t n, int32_t g0, const int32_t* c, double alpha
     if (n == 0) return handle_empty(a);
     if (!c || (reinterpret_cast<uintptr_t>(c) & 3)) return HORA_ERR_INVALID_ARG;
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255)) return HORA_ERR_WORKSPACE;
-    Workspace w = carve(workspace);
+    Workspace w = carve(workspace, n);
     if (workspace_bytes < w.bytes) return HORA_ERR_WORKSPACE;
     const Plan p = make_plan(n);
     return run_class(c, alpha0, beta0, a, p, w, rule == HORA_RULE_UNIFORM ? 1 : 2);
@@ -1547,11 +779,11 @@ int hora_allocate_posterior(int64_t n, int32_t g0, const double* alpha, const do
     if (!alpha || !beta || (reinterpret_cast<uintptr_t>(alpha) & 7) || (reinterpret_cast<uintptr_t>(beta) & 7))
         return HORA_ERR_INVALID_ARG;
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255)) return HORA_ERR_WORKSPACE;
-    Workspace w = carve(workspace);
+    Workspace w = carve(workspace, n);
     if (workspace_bytes < w.bytes) return HORA_ERR_WORKSPACE;
     const Plan p = make_plan(n);
     PosteriorSource src{alpha, beta};
-    return run_bisect(src, a, p, w);
+    return run_bisect_posterior(src, a, p, w);
 }
 
 }  // extern "C"

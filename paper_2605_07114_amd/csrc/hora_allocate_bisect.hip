@@ -1,0 +1,895 @@
+// Phase-B allocation by threshold search, for any posterior (Sec. 3.2 Eq. 4, Alg. 1 Phase B,
+// Prop. 1; App. D for per-prompt posteriors).
+//
+// By Prop. 1 the allocation is the set of the `budget` largest marginal gains over all
+// (prompt, l) pairs; every prompt's gains decrease strictly, so the set is described by a
+// threshold tau, the budget-th largest gain.  tau is found by a bisection on its bit pattern
+// (positive binary64 values order like their patterns) in which every prompt does a monotone
+// search along its own gain sequence.  A fixed, small number of launches does it for any input:
+//
+//  1. coarse count (k_bisect_coarse): every tile of 4096 prompts walks its prompts' gains
+//     downwards octave by octave (an octave = one exponent step of the pattern), counting them
+//     per quarter octave with wavefront ballots, until the tile has seen its share of the
+//     budget.  If every tile selected its share on its own, the union would hold at least
+//     `budget` gains, all of them above the lowest tile's stopping point: that point is a lower
+//     bound for tau, whatever the data, and no prompt walks much deeper than tau.  The walks
+//     are resumable (state in registers), so going deeper costs no second walk.
+//  2. k_bisect_coarse_reduce adds the tiles' counts up and picks the quarter octave in which
+//     the running count reaches the budget: the first bracket (lo, hi] of tau.
+//  3. two narrowing passes (k_bisect_pass + k_bisect_reduce): the bracket is cut into 256
+//     intervals; the gains inside are tallied per interval (count, largest, smallest) and the
+//     bracket shrinks to the gains seen in the interval where the running count reaches the
+//     budget.  The first pass walks the prompts and sets the gains of the bracket aside (one
+//     list per workgroup), the second one works from the lists and keeps what is left.
+//  4. k_bisect_final (one workgroup) finishes from the lists, usually a few hundred gains.
+//  5. k_bisect_finalize: k_i = #{l : M_i(l) > tau}, the tied flag and E_i(k_i) per prompt;
+//     k_bisect_write: ties at tau by prompt index, delta, utilities, group offsets.
+//
+// Under a shared prior the gains of a bracket are few distinct values, each repeated: the
+// first narrowing pass already closes the bracket and the later kernels return at once.
+#include <hip/hip_runtime.h>
+
+#include <climits>
+#include <cmath>
+#include <cstdint>
+
+#include "hora.h"
+#include "hora_device.h"
+#include "hora_alloc_common.h"
+#include "hora_alloc_emit.h"
+
+namespace hora {
+
+constexpr int kSoloMaxPrompts = 2048;                       // up to here one workgroup searches alone
+constexpr unsigned long long kOne = 0x3ff0000000000000ull;  // pattern of 1.0: no gain exceeds it
+constexpr unsigned long long kOctave = 1ull << 52;          // one exponent step of the pattern
+constexpr int kMaxOctave = 1022;                            // octave o holds (2^-(o+1), 2^-o]; the last one ends at 0
+constexpr int kRing = 2 * kWinOct;                          // octaves of counts a tile keeps in LDS while walking
+constexpr unsigned long long kWindowStep = 4ull << 52;      // fallback windows: a factor 16 in value
+constexpr int kFinalMaxPasses = 600;                        // one-workgroup finisher: windows down to zero plus narrowing passes
+static_assert(kListCap % kBig == 0, "a thread holds a fixed number of list entries");
+static_assert((kWinOct & (kWinOct - 1)) == 0 && kSubBins == 4, "octave window");
+
+__device__ __forceinline__ unsigned long long octave_top(int o) { return kOne - (unsigned long long)o * kOctave; }
+
+// ----------------------------------------------------------------------------------
+// kItems consecutive posteriors per thread (one 16-byte load of c, or four of alpha / beta).
+// Invalid entries are replaced by (1, 1) so that every walk is well defined.
+// ----------------------------------------------------------------------------------
+__device__ __forceinline__ bool load_posteriors(const CountsSource& src, long long pos, long long end,
+                                                double (&a)[kItems], double (&b)[kItems]) {
+    int cls[kItems];
+    load_items_i32(src.c, pos, end, (reinterpret_cast<uintptr_t>(src.c) & 15) == 0, 0, cls);
+    bool ok = true;
+#pragma unroll
+    for (int j = 0; j < kItems; ++j) {
+        int x = cls[j];
+        ok &= (x >= 0) && (x <= src.g0);
+        x = x < 0 ? 0 : (x > src.g0 ? src.g0 : x);
+        a[j] = src.alpha0 + (double)x;
+        b[j] = src.beta0 + (double)(src.g0 - x);
+    }
+    return ok;
+}
+
+__device__ __forceinline__ bool load_posteriors(const PosteriorSource& src, long long pos, long long end,
+                                                double (&a)[kItems], double (&b)[kItems]) {
+    const bool vec = ((reinterpret_cast<uintptr_t>(src.alpha) | reinterpret_cast<uintptr_t>(src.beta)) & 15) == 0;
+    if (vec && pos + kItems <= end) {
+#pragma unroll
+        for (int q = 0; q < kItems / 2; ++q) {
+            const v2d x = *reinterpret_cast<const v2d*>(src.alpha + pos + 2 * q);
+            const v2d y = *reinterpret_cast<const v2d*>(src.beta + pos + 2 * q);
+            a[2 * q] = x.x; a[2 * q + 1] = x.y;
+            b[2 * q] = y.x; b[2 * q + 1] = y.y;
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < kItems; ++j) {
+            a[j] = pos + j < end ? src.alpha[pos + j] : 1.0;
+            b[j] = pos + j < end ? src.beta[pos + j] : 1.0;
+        }
+    }
+    bool ok = true;
+#pragma unroll
+    for (int j = 0; j < kItems; ++j) {
+        const bool good = (a[j] > 0.0) && (b[j] > 0.0) && (a[j] < INFINITY) && (b[j] < INFINITY);
+        if (!good) { a[j] = 1.0; b[j] = 1.0; }
+        ok &= good;
+    }
+    return ok;
+}
+
+// ----------------------------------------------------------------------------------
+// 1. Coarse count.  One tile of kTile prompts at a time (kItems per thread, walked in
+// lockstep so that their divisions overlap).  Octave by octave from the top: every prompt
+// walks its gains down to the octave's lower end, each gain counted in its quarter octave by
+// wavefront ballots (scalar counters, no atomics per gain); after every octave the tile's
+// running total is compared with what it needs: its share of the budget plus a margin, so
+// that tiles of similar prompts all stop in the same octave (any stopping rule that waits
+// for the share is correct; the margin only makes it likely that the octave in which the
+// global count reaches the budget has been walked completely by every tile).
+// LDS keeps a ring of kRing octaves of counts; the slot keeps the last kWinOct.
+// ----------------------------------------------------------------------------------
+template <class Src>
+__global__ __launch_bounds__(kBig) void k_bisect_coarse(Src src, long long n, long long budget, long long limit,
+                                                        long long chunk, CoarseSlot* __restrict__ slots,
+                                                        int32_t* dev_status) {
+    __shared__ unsigned long long s_cnt[kRing][kSubBins];
+    __shared__ unsigned long long s_total;
+    __shared__ int s_alive[4];
+    const long long base = (long long)blockIdx.x * chunk;
+    const long long end = base + chunk < n ? base + chunk : n;
+    const int lane = lane_id();
+    const double limit_d = (double)limit;
+    bool bad = false;
+    for (long long t0 = base; t0 < end; t0 += kTile) {
+        const long long tile_end = t0 + kTile < end ? t0 + kTile : end;
+        const unsigned long long n_u = (unsigned long long)(tile_end - t0);
+        // the tile's share of the budget, rounded up (budget < 2^52 and n_u <= 2^12: no overflow)
+        const unsigned long long share = ((unsigned long long)budget * n_u + (unsigned long long)n - 1ull) /
+                                         (unsigned long long)n;
+        const unsigned long long need = share + (share >> 5) + 64ull;
+        const long long pos = t0 + (long long)threadIdx.x * kItems;
+        double a[kItems], b[kItems], s[kItems], g[kItems], lf[kItems];
+        unsigned long long gb[kItems];
+        bool alive[kItems];
+        bad |= !load_posteriors(src, pos, tile_end, a, b) && pos < tile_end;
+#pragma unroll
+        for (int j = 0; j < kItems; ++j) {
+            s[j] = a[j] + b[j];
+            g[j] = gain_first(a[j], s[j]);
+            lf[j] = 0.0;
+            gb[j] = gain_bits(g[j]);
+            alive[j] = pos + j < tile_end && limit > 0 && gb[j] != 0ull;
+        }
+        if (threadIdx.x < kRing * kSubBins) (&s_cnt[0][0])[threadIdx.x] = 0ull;
+        if (threadIdx.x < 4) s_alive[threadIdx.x] = 0;
+        if (threadIdx.x == 0) s_total = 0ull;
+        __syncthreads();
+        int o = 0;
+        bool any_alive = false;
+        for (;; ++o) {
+            const unsigned long long top = octave_top(o);
+            const unsigned long long bottom = top - kOctave;
+            unsigned c0 = 0, c1 = 0, c2 = 0, c3 = 0;     // wavefront-uniform counts of the four quarter octaves
+            bool any;
+            do {
+                any = false;
+#pragma unroll
+                for (int j = 0; j < kItems; ++j) {
+                    const bool act = alive[j] && gb[j] > bottom;
+                    const int sub = (int)((top - gb[j]) >> 50);
+                    c0 += (unsigned)__popcll(__ballot(act && sub == 0));
+                    c1 += (unsigned)__popcll(__ballot(act && sub == 1));
+                    c2 += (unsigned)__popcll(__ballot(act && sub == 2));
+                    c3 += (unsigned)__popcll(__ballot(act && sub == 3));
+                    if (act) {
+                        g[j] = gain_next(g[j], b[j], s[j], lf[j]);
+                        lf[j] += 1.0;
+                        gb[j] = gain_bits(g[j]);
+                        alive[j] = lf[j] < limit_d && gb[j] != 0ull;
+                    }
+                    any |= act;
+                }
+            } while (__ballot(any));
+            bool mine_alive = false;
+#pragma unroll
+            for (int j = 0; j < kItems; ++j) mine_alive |= alive[j];
+            const bool wave_alive = __ballot(mine_alive) != 0ull;
+            if (lane == 0) {
+                unsigned long long* row = s_cnt[o & (kRing - 1)];
+                if (c0) atomicAdd(&row[0], (unsigned long long)c0);
+                if (c1) atomicAdd(&row[1], (unsigned long long)c1);
+                if (c2) atomicAdd(&row[2], (unsigned long long)c2);
+                if (c3) atomicAdd(&row[3], (unsigned long long)c3);
+                const unsigned all = c0 + c1 + c2 + c3;
+                if (all) atomicAdd(&s_total, (unsigned long long)all);
+                if (wave_alive) s_alive[o & 3] = 1;
+            }
+            __syncthreads();
+            any_alive = s_alive[o & 3] != 0;
+            if (s_total >= need || !any_alive || o == kMaxOctave) break;   // uniform
+            // room for the octave after the next one (nobody reads or adds to these now)
+            if (threadIdx.x < kSubBins) s_cnt[(o + 2) & (kRing - 1)][threadIdx.x] = 0ull;
+            if (threadIdx.x == 0) s_alive[(o + 2) & 3] = 0;
+        }
+        // the tile's slot: the last kWinOct octaves in detail, everything above them as one number
+        if (threadIdx.x < kWave) {
+            const int w = lane >> 2, sub = lane & 3;
+            unsigned long long v = 0ull;
+            if (lane < kWinOct * kSubBins) {
+                const int oct = o - ((o - w) & (kWinOct - 1));   // the octave in [o - 7, o] that is w modulo 8
+                if (oct >= 0) v = s_cnt[oct & (kRing - 1)][sub];
+            }
+            const long long in_window = wave_total_i64((long long)v);
+            CoarseSlot* slot = slots + t0 / kTile;
+            if (lane < kWinOct * kSubBins) slot->cnt[w][sub] = v;
+            if (lane == 0) {
+                slot->cum_top = s_total - (unsigned long long)in_window;
+                slot->stop = o;
+                slot->exhausted = any_alive ? 0 : 1;
+            }
+        }
+        __syncthreads();   // the counters are reused by the next tile
+    }
+    if (bad) report(dev_status, HORA_ERR_RANGE);
+}
+
+// ----------------------------------------------------------------------------------
+// 2. The tiles' coarse counts added up, and the first bracket.  Octave o can be resolved
+// when every tile still has it in detail (o >= stop - 7 for all tiles) and every tile that
+// has gains left walked it completely (o <= stop for those).  Inside that range the quarter
+// octave in which the running count reaches the budget becomes the bracket.  Otherwise (tiles
+// of very different prompts, caps that leave tiles short of their share) a wider bracket that
+// is still correct is taken and the narrowing passes do the rest.
+// One workgroup: the slots are 272 bytes per 4096 prompts.
+// ----------------------------------------------------------------------------------
+__global__ __launch_bounds__(kBig) void k_bisect_coarse_reduce(long long tiles, long long budget,
+                                                               const CoarseSlot* __restrict__ slots,
+                                                               AllocHeader* __restrict__ hdr) {
+    __shared__ int s_smax, s_smin;
+    __shared__ long long s_sum[2 + kWinOct * kSubBins];   // [0] above the range, [1] everything counted, then the bins
+    if (threadIdx.x == 0) { s_smax = 0; s_smin = INT_MAX; }
+    if (threadIdx.x < 2 + kWinOct * kSubBins) s_sum[threadIdx.x] = 0;
+    __syncthreads();
+    int smax = 0, smin = INT_MAX;
+    for (long long u = threadIdx.x; u < tiles; u += kBig) {
+        const int stop = slots[u].stop;
+        smax = stop > smax ? stop : smax;
+        if (!slots[u].exhausted) smin = stop < smin ? stop : smin;
+    }
+    atomicMax(&s_smax, smax);
+    atomicMin(&s_smin, smin);
+    __syncthreads();
+    const int s_max = s_smax;
+    const int s_min = s_smin == INT_MAX ? s_max : s_smin;   // no tile has gains left: everything is counted
+    const int first = s_max - (kWinOct - 1) > 0 ? s_max - (kWinOct - 1) : 0;   // first octave of the range
+    long long base = 0, known = 0;
+    long long bin[kWinOct][kSubBins];
+#pragma unroll
+    for (int w = 0; w < kWinOct; ++w)
+#pragma unroll
+        for (int q = 0; q < kSubBins; ++q) bin[w][q] = 0;
+    for (long long u = threadIdx.x; u < tiles; u += kBig) {
+        const CoarseSlot* slot = slots + u;
+        const int stop = slot->stop;
+        long long top = (long long)slot->cum_top;
+        known += top;
+#pragma unroll
+        for (int w = 0; w < kWinOct; ++w) {
+            const int oct = stop - ((stop - w) & (kWinOct - 1));   // the octave of the slot's row w
+            long long row = 0;
+#pragma unroll
+            for (int q = 0; q < kSubBins; ++q) row += (long long)slot->cnt[w][q];
+            known += oct >= 0 ? row : 0;
+            if (oct >= 0 && oct < first) top += row;
+            if (oct >= first) {   // oct - first is in [0, 7] because stop <= s_max
+#pragma unroll
+                for (int r = 0; r < kWinOct; ++r)
+                    if (oct - first == r) {
+#pragma unroll
+                        for (int q = 0; q < kSubBins; ++q) bin[r][q] += (long long)slot->cnt[w][q];
+                    }
+            }
+        }
+        base += top;
+    }
+    base = wave_sum<long long>(base);
+    known = wave_sum<long long>(known);
+    if (lane_id() == 0) {
+        atomicAdd((unsigned long long*)&s_sum[0], (unsigned long long)base);
+        atomicAdd((unsigned long long*)&s_sum[1], (unsigned long long)known);
+    }
+#pragma unroll
+    for (int r = 0; r < kWinOct; ++r)
+#pragma unroll
+        for (int q = 0; q < kSubBins; ++q) {
+            const long long v = wave_sum<long long>(bin[r][q]);
+            if (lane_id() == 0 && v) atomicAdd((unsigned long long*)&s_sum[2 + r * kSubBins + q], (unsigned long long)v);
+        }
+    __syncthreads();
+    if (threadIdx.x != 0) return;
+    unsigned long long lo = 0ull, hi = kOne;
+    long long above = 0, inside = -1;
+    const long long all_above = s_sum[0];
+    bool found = false;
+    if (all_above >= budget) {
+        lo = octave_top(first);          // count_gt(lo) >= budget already: tau lies above the range
+    } else {
+        long long cum = all_above;
+        int o = first;
+        for (; o <= s_min && !found; ++o) {
+            for (int q = 0; q < kSubBins; ++q) {
+                const long long c = s_sum[2 + (o - first) * kSubBins + q];
+                if (cum + c >= budget) {
+                    hi = octave_top(o) - (unsigned long long)q * (kOctave / kSubBins);
+                    lo = hi - kOctave / kSubBins;
+                    above = cum;
+                    inside = c;
+                    found = true;
+                    break;
+                }
+                cum += c;
+            }
+        }
+        if (!found) {
+            // The range ends above tau.  When it is not empty, the count above its lower end is
+            // complete and the bracket starts there; when it is empty (some tile stopped more
+            // than kWinOct octaves above another: very different prompts), nothing below 1 is.
+            // Downwards the bracket reaches to where every tile has seen its share, or, when the
+            // tiles' counts do not add up to the budget (caps), to zero.
+            if (s_min >= first) {
+                hi = octave_top(s_min + 1);
+                above = cum;
+            }
+            lo = s_sum[1] >= budget ? octave_top(s_max) - kOctave : 0ull;
+        }
+    }
+    hdr->slot[0].lo = lo; hdr->slot[0].hi = hi; hdr->slot[0].above = (unsigned long long)above;
+    hdr->slot[0].done = 0u; hdr->slot[0].flags = 0u;
+    hdr->slot[1].lo = 0ull; hdr->slot[1].hi = 0ull; hdr->slot[1].above = 0ull;
+    hdr->slot[1].done = 0u; hdr->slot[1].flags = 0u;
+    hdr->inside = inside;
+    hdr->tau = 0ull;
+    hdr->lists_ok = 0u;
+}
+
+// ----------------------------------------------------------------------------------
+// 3. Narrowing pass.  Invariant: exactly `above` pairs have a gain > hi, above < budget, and
+// count_gt(lo) >= budget.  The gains inside (lo, hi] are tallied per interval; if the running
+// count from the top interval down reaches the budget in interval j, the bracket shrinks to
+// the gains that occur there, (min - 1, max], and closes when min == max (tau is that gain):
+// each pass cuts the bracket at least 128-fold; with real-valued posteriors it keeps ~1/256
+// of the gains of the pass before, with a shared prior it closes at once.  Every workgroup
+// tallies its share into a slot of its own; k_bisect_reduce adds the slots up, and every
+// workgroup of the next kernel moves the bracket by those totals for itself (the same
+// arithmetic on the same numbers everywhere).  The bracket is kept twice: pass p reads slot
+// p & 1, which nobody writes meanwhile, and its first workgroup stores the moved bracket in
+// the other slot.
+// ----------------------------------------------------------------------------------
+struct SelectShared {
+    TallyBins bins;
+    long long red[kBigWaves];
+    unsigned long long lo, hi;
+    long long above;
+    long long inside;   // pairs in the bracket (-1: not known)
+    int done;
+    int hit;            // the last step narrowed the bracket (it did not move to another window)
+    int list_n;         // gains this workgroup has set aside in this pass
+};
+
+// The step that ends a pass, run by a whole workgroup: thread t < kBins holds the tally
+// (cj, mx, mn) of interval kBins - 1 - t (thread 0 the top one), the other threads zeros.
+// Finds the interval in which the running count from the top reaches the budget and shrinks
+// the bracket to the gains seen there; when the whole bracket lies above tau (possible only
+// for the wide brackets that the coarse count falls back to), takes the window below it.
+__device__ __forceinline__ void move_bracket(SelectShared& sh, unsigned long long cj, unsigned long long mx,
+                                             unsigned long long mn, long long budget) {
+    const unsigned long long lo = sh.lo;
+    const long long start = sh.above;   // pairs above the bracket
+    if (cj > (unsigned long long)budget) cj = (unsigned long long)budget;
+    __syncthreads();                                     // sh.red is free, the bracket has been read
+    const long long incl = wave_incl_scan<long long>((long long)cj);
+    if (lane_id() == kWave - 1) sh.red[wave_id()] = incl;
+    __syncthreads();
+    long long before = start + incl - (long long)cj;     // pairs in higher intervals
+    long long total = 0;
+    for (int i = 0; i < kBigWaves; ++i) {
+        if (i < wave_id()) before += sh.red[i];
+        total += sh.red[i];
+    }
+    if (start + total < budget) {                       // uniform: the whole bracket is above tau
+        if (threadIdx.x == 0) {
+            sh.above = start + total;
+            sh.hi = lo;
+            sh.lo = lo > kWindowStep ? lo - kWindowStep : 0ull;
+            if (lo == 0ull) sh.done = 2;                // no gains left: the budget does not fit
+            sh.hit = 0;
+            sh.inside = -1;
+        }
+    } else if (cj != 0 && before < budget && budget <= before + (long long)cj) {   // exactly one thread
+        sh.above = before;
+        sh.hi = mx;
+        sh.lo = mn - 1ull;
+        sh.done = (mx == mn) ? 1 : 0;
+        sh.hit = 1;
+        sh.inside = (long long)cj;                      // (a count cut off at the budget is no larger than the true one)
+    }
+    __syncthreads();
+}
+
+// Loads the bracket of pass `pass` and, if the pass before tallied, moves it by the totals.
+__device__ __forceinline__ void enter_pass(SelectShared& sh, const AllocHeader* hdr, const SelectBins* bins, int pass,
+                                           long long budget) {
+    const Bracket* in = &hdr->slot[pass & 1];
+    const bool pending = (in->flags & kFlagPending) != 0 && in->done == 0;   // uniform
+    const SelectBins* totals = bins + kMaxBlocks;
+    const int j = kBins - 1 - (int)threadIdx.x;   // thread 0 owns the top interval
+    unsigned long long cj = 0, mx = 0, mn = 0;
+    if (pending && threadIdx.x < kBins) {
+        cj = totals->cnt[j];
+        mx = totals->vmax[j];
+        mn = ~totals->vmin_inv[j];
+    }
+    if (threadIdx.x == 0) {
+        sh.lo = in->lo; sh.hi = in->hi; sh.above = (long long)in->above; sh.done = (int)in->done;
+        sh.hit = 0;
+        sh.inside = pass == 0 ? hdr->inside : -1;
+        sh.list_n = 0;
+    }
+    __syncthreads();
+    if (pending) move_bracket(sh, cj, mx, mn, budget);
+}
+
+// Appends the gains that `keep` marks to the workgroup's list (whole wavefronts call this).
+__device__ __forceinline__ void list_append(SelectShared& sh, unsigned long long* __restrict__ list, bool keep,
+                                            unsigned long long gb) {
+    const unsigned long long m = __ballot(keep);
+    if (m == 0ull) return;
+    int at = 0;
+    if (lane_id() == 0) at = atomicAdd(&sh.list_n, __popcll(m));
+    at = __builtin_amdgcn_readfirstlane(at) + lanes_below(m);
+    if (keep && at < kListCap) list[at] = gb;
+}
+
+template <class Src>
+__global__ __launch_bounds__(kBig) void k_bisect_pass(Src src, long long n, long long budget, long long limit,
+                                                      long long chunk, int pass, AllocHeader* __restrict__ hdr,
+                                                      SelectBins* __restrict__ bins,
+                                                      unsigned long long* __restrict__ lists,
+                                                      int* __restrict__ list_count) {
+    __shared__ SelectShared sh;
+    enter_pass(sh, hdr, bins, pass, budget);
+    const Bracket* in = &hdr->slot[pass & 1];
+    // Where this pass gets the gains of its bracket from.  The pass before may have set the
+    // gains of its own (wider) bracket aside: then this pass tallies from the lists and keeps
+    // what lies in the narrower bracket.  Otherwise it walks the prompts, and sets the
+    // bracket's gains aside when they are few enough.  A list that does not fit only means
+    // that the next pass walks again.
+    const bool from_lists = (in->flags & kFlagCollected) != 0 && hdr->lists_ok != 0;
+    const bool collect = from_lists || (sh.inside >= 0 && sh.inside <= kCollectMax);
+    const bool done = sh.done != 0;
+    if (blockIdx.x == 0 && threadIdx.x == 0) {   // for the next kernel
+        Bracket* out = &hdr->slot[(pass + 1) & 1];
+        out->lo = sh.lo; out->hi = sh.hi; out->above = (unsigned long long)sh.above;
+        out->done = (unsigned)sh.done;
+        out->flags = done ? 0u : (kFlagPending | (collect ? kFlagCollected : 0u));
+    }
+    if (done) return;   // uniform over the grid: every workgroup moved the same bracket
+    const unsigned long long lo = sh.lo, hi = sh.hi;
+    const int shift = bracket_shift(lo, hi);
+    if (threadIdx.x < kBins) { sh.bins.cnt[threadIdx.x] = 0; sh.bins.vmax[threadIdx.x] = 0; sh.bins.vmin_inv[threadIdx.x] = 0; }
+    unsigned long long* mine = lists + (long long)blockIdx.x * kListCap;
+    if (from_lists) {
+        constexpr int kPer = kListCap / kBig;
+        const int have = list_count[blockIdx.x];
+        unsigned long long v[kPer];
+#pragma unroll
+        for (int q = 0; q < kPer; ++q) {
+            const int e = q * kBig + (int)threadIdx.x;
+            v[q] = e < have ? mine[e] : 0ull;
+        }
+        __syncthreads();   // the list has been read (it is rewritten below), the tallies are zero
+#pragma unroll
+        for (int q = 0; q < kPer; ++q) {
+            const bool inside = v[q] > lo && v[q] <= hi;
+            tally_gains(sh.bins, inside, v[q], lo, shift);
+            list_append(sh, mine, inside, v[q]);
+        }
+    } else {
+        __syncthreads();
+        const long long base = (long long)blockIdx.x * chunk;
+        const long long end = base + chunk < n ? base + chunk : n;
+        const double limit_d = (double)limit;
+        for (long long t0 = base; t0 < end; t0 += kTile) {
+            const long long pos = t0 + (long long)threadIdx.x * kItems;
+            double a[kItems], b[kItems], s[kItems], g[kItems], lf[kItems];
+            unsigned long long gb[kItems];
+            bool alive[kItems];
+            load_posteriors(src, pos, end, a, b);
+#pragma unroll
+            for (int j = 0; j < kItems; ++j) {
+                s[j] = a[j] + b[j];
+                g[j] = gain_first(a[j], s[j]);
+                lf[j] = 0.0;
+                gb[j] = gain_bits(g[j]);
+                alive[j] = pos + j < end && limit > 0;
+            }
+            // down to the bracket: the kItems walks in lockstep
+            bool any;
+            do {
+                any = false;
+#pragma unroll
+                for (int j = 0; j < kItems; ++j) {
+                    const bool act = alive[j] && gb[j] > hi;
+                    if (act) {
+                        g[j] = gain_next(g[j], b[j], s[j], lf[j]);
+                        lf[j] += 1.0;
+                        gb[j] = gain_bits(g[j]);
+                        alive[j] = lf[j] < limit_d;
+                    }
+                    any |= act;
+                }
+            } while (any);
+            // through the bracket: whole wavefronts, one prompt of every lane at a time
+#pragma unroll
+            for (int j = 0; j < kItems; ++j) {
+                bool inside = alive[j] && gb[j] > lo;
+                while (__ballot(inside)) {
+                    tally_gains(sh.bins, inside, gb[j], lo, shift);
+                    if (collect) list_append(sh, mine, inside, gb[j]);
+                    if (inside) {
+                        g[j] = gain_next(g[j], b[j], s[j], lf[j]);
+                        lf[j] += 1.0;
+                        gb[j] = gain_bits(g[j]);
+                        inside = lf[j] < limit_d && gb[j] > lo;
+                    }
+                }
+            }
+        }
+    }
+    __syncthreads();   // the workgroup's tallies are complete
+    if (collect && threadIdx.x == 0) list_count[blockIdx.x] = sh.list_n <= kListCap ? sh.list_n : -1;
+    SelectBins* slot = bins + blockIdx.x;
+    if (threadIdx.x < kBins) {
+        const unsigned long long c0 = sh.bins.cnt[threadIdx.x];
+        slot->cnt[threadIdx.x] = c0 > (unsigned long long)budget ? (unsigned long long)budget : c0;
+        slot->vmax[threadIdx.x] = sh.bins.vmax[threadIdx.x];
+        slot->vmin_inv[threadIdx.x] = sh.bins.vmin_inv[threadIdx.x];
+    }
+}
+
+// ----------------------------------------------------------------------------------
+// Between two kernels of the search: the interval tallies of the workgroups are added up
+// (counts) and combined (largest, smallest gain) into bins[kMaxBlocks].  kReduceBins
+// intervals per workgroup, 32 lanes per interval striding over the slots.  A kernel of its
+// own rather than "the workgroup that finishes last": the device-wide fences that pattern
+// needs (write back and invalidate the L2 of every die) cost several times the pass itself
+// on this part.
+// ----------------------------------------------------------------------------------
+constexpr int kReduceBins = kThreads / 32;   // 8 intervals per workgroup of 256 threads
+
+__global__ __launch_bounds__(kThreads) void k_bisect_reduce(int nb, int pass, AllocHeader* __restrict__ hdr,
+                                                            SelectBins* __restrict__ bins,
+                                                            const int* __restrict__ list_count) {
+    const unsigned flags = hdr->slot[(pass + 1) & 1].flags;
+    if ((flags & kFlagPending) == 0) return;   // pass `pass` did not tally: the search has ended
+    if (blockIdx.x == 0) {   // did every workgroup's list fit?
+        static_assert(kMaxBlocks <= kThreads, "one thread per list");
+        const int any_bad = __syncthreads_or((int)threadIdx.x < nb && list_count[threadIdx.x] < 0 ? 1 : 0);
+        if (threadIdx.x == 0) hdr->lists_ok = ((flags & kFlagCollected) != 0 && !any_bad) ? 1u : 0u;
+    }
+    const int bin = (int)blockIdx.x * kReduceBins + (int)threadIdx.x / 32;
+    const int sub = (int)threadIdx.x & 31;
+    unsigned long long c = 0, mx = 0, mn = 0;
+    constexpr int kPer = kMaxBlocks / 32;                 // slots per lane, all loads issued at once
+    unsigned long long pc[kPer], pm[kPer], pn[kPer];
+#pragma unroll
+    for (int t = 0; t < kPer; ++t) {
+        const int wg = sub + 32 * t;
+        const bool in = wg < nb;
+        pc[t] = in ? bins[wg].cnt[bin] : 0ull;
+        pm[t] = in ? bins[wg].vmax[bin] : 0ull;
+        pn[t] = in ? bins[wg].vmin_inv[bin] : 0ull;
+    }
+#pragma unroll
+    for (int t = 0; t < kPer; ++t) {
+        c += pc[t];
+        mx = pm[t] > mx ? pm[t] : mx;
+        mn = pn[t] > mn ? pn[t] : mn;
+    }
+#pragma unroll
+    for (int d = 16; d > 0; d >>= 1) {
+        c += (unsigned long long)__shfl_xor((long long)c, d, 32);
+        const unsigned long long om = (unsigned long long)__shfl_xor((long long)mx, d, 32);
+        const unsigned long long on = (unsigned long long)__shfl_xor((long long)mn, d, 32);
+        mx = om > mx ? om : mx;
+        mn = on > mn ? on : mn;
+    }
+    if (sub == 0) {
+        SelectBins* totals = bins + kMaxBlocks;
+        totals->cnt[bin] = c;
+        totals->vmax[bin] = mx;
+        totals->vmin_inv[bin] = mn;
+    }
+}
+
+// ----------------------------------------------------------------------------------
+// 4. The end of the search, one workgroup: moves the bracket by the totals of the last
+// narrowing pass and, if it is still open, repeats passes on its own until it closes: from
+// the workgroups' lists (what two 256-fold cuts leave of a quarter octave: usually a few
+// hundred gains).  Only when the lists could not hold the bracket (more than half a million
+// distinct gains within 2^-16 of one another) does it walk the prompts itself, which is slow
+// but correct.  Leaves tau in the header.
+// ----------------------------------------------------------------------------------
+template <class Src>
+__global__ __launch_bounds__(kBig) void k_bisect_final(Src src, long long n, long long budget, long long limit,
+                                                       int nb, int pass, AllocHeader* __restrict__ hdr,
+                                                       const SelectBins* __restrict__ bins,
+                                                       const unsigned long long* __restrict__ lists,
+                                                       const int* __restrict__ list_count, int32_t* dev_status) {
+    __shared__ SelectShared sh;
+    enter_pass(sh, hdr, bins, pass, budget);
+    const Bracket* in = &hdr->slot[pass & 1];
+    const bool from_lists = (in->flags & kFlagCollected) != 0 && hdr->lists_ok != 0;
+    const int lane = lane_id();
+    for (int iter = 0; iter < kFinalMaxPasses; ++iter) {
+        if (sh.done) break;   // uniform: written before the barrier that ends move_bracket
+        const unsigned long long lo = sh.lo, hi = sh.hi;
+        const int shift = bracket_shift(lo, hi);
+        if (threadIdx.x < kBins) { sh.bins.cnt[threadIdx.x] = 0; sh.bins.vmax[threadIdx.x] = 0; sh.bins.vmin_inv[threadIdx.x] = 0; }
+        __syncthreads();
+        if (from_lists) {
+            for (int wg = wave_id(); wg < nb; wg += kBigWaves) {
+                const int have = list_count[wg];
+                const unsigned long long* list = lists + (long long)wg * kListCap;
+                for (int e0 = 0; e0 < have; e0 += kWave) {
+                    const int e = e0 + lane;
+                    const unsigned long long v = e < have ? list[e] : 0ull;
+                    tally_gains(sh.bins, v > lo && v <= hi, v, lo, shift);
+                }
+            }
+        } else {
+            for (long long i0 = 0; i0 < n; i0 += kBig) {
+                const long long i = i0 + threadIdx.x;
+                double a = 1.0, b = 1.0;
+                if (i < n) src.load(i, a, b);
+                const double s = a + b;
+                double g = gain_first(a, s);
+                double lf = 0.0;
+                long long k = 0;
+                unsigned long long gb = gain_bits(g);
+                bool active = i < n && k < limit && gb > lo;
+                while (__ballot(active)) {
+                    tally_gains(sh.bins, active && gb <= hi, gb, lo, shift);
+                    if (active) {
+                        g = gain_next(g, b, s, lf);
+                        lf += 1.0;
+                        k += 1;
+                        gb = gain_bits(g);
+                        active = k < limit && gb > lo;
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        const int j = kBins - 1 - (int)threadIdx.x;   // thread 0 owns the top interval
+        unsigned long long cj = 0, mx = 0, mn = 0;
+        if (threadIdx.x < kBins) {
+            cj = sh.bins.cnt[j];
+            mx = sh.bins.vmax[j];
+            mn = ~sh.bins.vmin_inv[j];
+        }
+        move_bracket(sh, cj, mx, mn, budget);
+    }
+    if (threadIdx.x == 0) {
+        hdr->tau = sh.hi;
+        // (cannot happen with valid posteriors and a budget that fits)
+        if (sh.done != 1) report(dev_status, sh.done == 2 ? HORA_ERR_INFEASIBLE : HORA_ERR_RANGE);
+    }
+}
+
+// ----------------------------------------------------------------------------------
+// 5a. With tau known: k_i = #{l : M_i(l) > tau} and the tied flag go to delta[i] (flag in
+// bit 31), the survival product E_i(k_i) to util[i]; per-workgroup sums to block_ksum /
+// block_tied.  kItems prompts per thread, their walks in lockstep.
+// ----------------------------------------------------------------------------------
+template <class Src>
+__global__ __launch_bounds__(kBig) void k_bisect_finalize(Src src, long long n, long long chunk, long long budget,
+                                                          long long limit, int depth_capped,
+                                                          const AllocHeader* __restrict__ hdr,
+                                                          int32_t* __restrict__ delta, double* __restrict__ util,
+                                                          long long* __restrict__ block_ksum,
+                                                          long long* __restrict__ block_tied, int32_t* dev_status) {
+    __shared__ long long s_red[2][kBigWaves];
+    const unsigned long long tau_bits = budget > 0 ? hdr->tau : ~0ull;
+    const long long base = (long long)blockIdx.x * chunk;
+    const long long end = base + chunk < n ? base + chunk : n;
+    const bool d_vec = (reinterpret_cast<uintptr_t>(delta) & 15) == 0;
+    const bool u_vec = (reinterpret_cast<uintptr_t>(util) & 15) == 0;
+    const double limit_d = (double)limit;
+    long long ks = 0, ts = 0;
+    bool too_deep = false;
+    for (long long t0 = base; t0 < end; t0 += kTile) {
+        const long long pos = t0 + (long long)threadIdx.x * kItems;
+        double a[kItems], b[kItems], s[kItems], g[kItems], e[kItems], lf[kItems];
+        bool alive[kItems];
+        load_posteriors(src, pos, end, a, b);
+#pragma unroll
+        for (int j = 0; j < kItems; ++j) {
+            s[j] = a[j] + b[j];
+            g[j] = gain_first(a[j], s[j]);
+            e[j] = 1.0;
+            lf[j] = 0.0;
+            alive[j] = pos + j < end;
+        }
+        bool any;
+        do {
+            any = false;
+#pragma unroll
+            for (int j = 0; j < kItems; ++j) {
+                const bool act = alive[j] && lf[j] < limit_d && gain_bits(g[j]) > tau_bits;
+                if (act) {
+                    e[j] = surv_next(e[j], b[j], s[j], lf[j]);
+                    g[j] = gain_next(g[j], b[j], s[j], lf[j]);
+                    lf[j] += 1.0;
+                }
+                any |= act;
+            }
+        } while (any);
+        int packed[kItems];
+#pragma unroll
+        for (int j = 0; j < kItems; ++j) {
+            const bool at_limit = !(lf[j] < limit_d);
+            const bool tied = alive[j] && !at_limit && gain_bits(g[j]) == tau_bits;
+            // stopped by the library's depth bound with gains above tau left
+            too_deep |= alive[j] && at_limit && depth_capped != 0 && gain_bits(g[j]) > tau_bits;
+            const int k = alive[j] ? (int)lf[j] : 0;
+            packed[j] = (int)((unsigned)k | (tied ? kTiedBit : 0u));
+            ks += k;
+            ts += tied ? 1 : 0;
+        }
+        store_items<v4i, int32_t>(delta, pos, end, d_vec, packed);
+        if (util) store_items<v2d, double>(util, pos, end, u_vec, e);
+    }
+    ks = wave_total_i64(ks);
+    ts = wave_total_i64(ts);
+    if (lane_id() == 0) { s_red[0][wave_id()] = ks; s_red[1][wave_id()] = ts; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        long long ksum = 0, tsum = 0;
+        for (int i = 0; i < kBigWaves; ++i) { ksum += s_red[0][i]; tsum += s_red[1][i]; }
+        block_ksum[blockIdx.x] = ksum;
+        block_tied[blockIdx.x] = tsum;
+    }
+    if (too_deep) report(dev_status, HORA_ERR_UNSUPPORTED);
+}
+
+// ----------------------------------------------------------------------------------
+// 5b. Outputs.  Every workgroup adds up the per-workgroup sums of 5a (what lies before it,
+// and the totals, from which r = budget - sum k follows), then runs the tie pass over its
+// chunk: delta[i] holds k_i with the tied flag in bit 31 and util[i] the survival product
+// E_i(k_i); a winner's utility takes one more step of the product.
+// ----------------------------------------------------------------------------------
+template <class Src, int kOff>
+__global__ __launch_bounds__(kBig) void k_bisect_write(Src src, long long n, int g0, long long chunk, int nb,
+                                                       long long budget, const AllocHeader* __restrict__ hdr,
+                                                       const long long* __restrict__ block_ksum,
+                                                       const long long* __restrict__ block_tied,
+                                                       int32_t* __restrict__ delta, double* __restrict__ util,
+                                                       void* __restrict__ group_off,
+                                                       hora_alloc_summary* __restrict__ summary,
+                                                       int32_t* dev_status) {
+    __shared__ EmitShared s_emit;
+    __shared__ long long s_pre[4][kBigWaves];
+    {
+        static_assert(kMaxBlocks <= kBig, "one thread per workgroup sum");
+        const int t = (int)threadIdx.x;
+        const long long kv = t < nb ? block_ksum[t] : 0, tv = t < nb ? block_tied[t] : 0;
+        const long long k_all = wave_total_i64(kv), t_all = wave_total_i64(tv);
+        const long long k_bef = wave_total_i64(t < (int)blockIdx.x ? kv : 0);
+        const long long t_bef = wave_total_i64(t < (int)blockIdx.x ? tv : 0);
+        if (lane_id() == 0) {
+            s_pre[0][wave_id()] = k_all; s_pre[1][wave_id()] = t_all;
+            s_pre[2][wave_id()] = k_bef; s_pre[3][wave_id()] = t_bef;
+        }
+    }
+    __syncthreads();
+    long long k_all = 0, t_all = 0, k_bef = 0, t_bef = 0;
+#pragma unroll
+    for (int w = 0; w < kBigWaves; ++w) {
+        k_all += s_pre[0][w]; t_all += s_pre[1][w]; k_bef += s_pre[2][w]; t_bef += s_pre[3][w];
+    }
+    const long long r = budget - k_all;
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        if (r < 0 || r > t_all) report(dev_status, HORA_ERR_RANGE);   // invalid posteriors upstream
+        if (summary) {
+            summary->tau = budget > 0 ? __longlong_as_double((long long)hdr->tau) : 0.0;
+            summary->count_gt = k_all;
+            summary->tie_units = r;
+            summary->tie_prompts = t_all;
+        }
+    }
+    const long long base = (long long)blockIdx.x * chunk;
+    const long long end = base + chunk < n ? base + chunk : n;
+    const bool d_vec = (reinterpret_cast<uintptr_t>(delta) & 15) == 0;
+    const bool u_vec = (reinterpret_cast<uintptr_t>(util) & 15) == 0;
+    const bool o_vec = (reinterpret_cast<uintptr_t>(group_off) & 15) == 0;
+    EmitCarry carry = {t_bef, k_bef};
+    int parity = 0;
+    for (long long t0 = base; t0 < end; t0 += kTile, parity ^= 1) {
+        const long long pos = t0 + (long long)threadIdx.x * kItems;
+        int raw[kItems];
+        load_items_i32(delta, pos, end, d_vec, 0, raw);
+        int kk[kItems], td[kItems], dd[kItems];
+        bool win[kItems];
+#pragma unroll
+        for (int j = 0; j < kItems; ++j) {
+            kk[j] = (int)((unsigned)raw[j] & ~kTiedBit);
+            td[j] = ((unsigned)raw[j] & kTiedBit) ? 1 : 0;
+        }
+        emit_tile<kOff>(parity, pos, end, n, g0, r, kk, td, carry, dd, win, delta, group_off, d_vec, o_vec,
+                        &s_emit);
+        if (util) {
+            double uu[kItems];
+#pragma unroll
+            for (int j = 0; j < kItems; ++j) {
+                double e = 1.0;
+                if (pos + j < end) {
+                    e = util[pos + j];
+                    if (win[j]) {
+                        double a, b;
+                        src.load(pos + j, a, b);
+                        e = surv_next(e, b, a + b, (double)kk[j]);
+                    }
+                }
+                uu[j] = 1.0 - e;
+            }
+            store_items<v2d, double>(util, pos, end, u_vec, uu);
+        }
+    }
+}
+
+// ----------------------------------------------------------------------------------
+// Host side
+// ----------------------------------------------------------------------------------
+static int run_small(const CountsSource& src, const CommonArgs& a) {
+    return allocate_small_counts(src, a.n, a.g0, a.budget, a.delta_max, a.delta, a.util, a.group_off, a.off_t,
+                                 a.summary, a.dev_status, a.stream);
+}
+static int run_small(const PosteriorSource& src, const CommonArgs& a) {
+    return allocate_small_posterior(src, a.n, a.g0, a.budget, a.delta_max, a.delta, a.util, a.group_off, a.off_t,
+                                    a.summary, a.dev_status, a.stream);
+}
+
+template <class Src>
+static int run_bisect(const Src& src, const CommonArgs& a, const Plan& p, const Workspace& w) {
+    const long long n = a.n;
+    // a batch that one workgroup can hold: one launch does the whole search and the outputs
+    if (n <= kSoloMaxPrompts) return run_small(src, a);
+    // gains one prompt may contribute: the caller's cap, the budget, the library's depth bound
+    long long wanted = a.delta_max > 0 ? (long long)a.delta_max : a.budget;
+    if (wanted > a.budget) wanted = a.budget;
+    const int depth_capped = wanted > (long long)HORA_MAX_DEPTH ? 1 : 0;
+    const long long limit = depth_capped ? (long long)HORA_MAX_DEPTH : wanted;
+    const long long tiles = (n + kTile - 1) / kTile;
+    if (a.budget > 0) {
+        hipLaunchKernelGGL((k_bisect_coarse<Src>), dim3(p.nb), dim3(kBig), 0, a.stream, src, n, (long long)a.budget,
+                           limit, p.chunk, w.coarse, a.dev_status);
+        hipLaunchKernelGGL(k_bisect_coarse_reduce, dim3(1), dim3(kBig), 0, a.stream, tiles, (long long)a.budget,
+                           (const CoarseSlot*)w.coarse, w.header);
+        for (int pass = 0; pass < 2; ++pass) {
+            hipLaunchKernelGGL((k_bisect_pass<Src>), dim3(p.nb), dim3(kBig), 0, a.stream, src, n,
+                               (long long)a.budget, limit, p.chunk, pass, w.header, w.bins, w.lists, w.list_count);
+            hipLaunchKernelGGL(k_bisect_reduce, dim3(kBins / kReduceBins), dim3(kThreads), 0, a.stream, p.nb, pass,
+                               w.header, w.bins, (const int*)w.list_count);
+        }
+        hipLaunchKernelGGL((k_bisect_final<Src>), dim3(1), dim3(kBig), 0, a.stream, src, n, (long long)a.budget,
+                           limit, p.nb, 2, w.header, (const SelectBins*)w.bins,
+                           (const unsigned long long*)w.lists, (const int*)w.list_count, a.dev_status);
+    }
+    hipLaunchKernelGGL((k_bisect_finalize<Src>), dim3(p.nb), dim3(kBig), 0, a.stream, src, n, p.chunk,
+                       (long long)a.budget, limit, depth_capped, (const AllocHeader*)w.header, a.delta, a.util,
+                       w.block_ksum, w.block_tied, a.dev_status);
+    const int mode = a.group_off ? (a.off_t == HORA_I32 ? 1 : 2) : 0;
+#define HORA_LAUNCH_BISECT_WRITE(M)                                                                       \
+    hipLaunchKernelGGL((k_bisect_write<Src, M>), dim3(p.nb), dim3(kBig), 0, a.stream, src, n, (int)a.g0,  \
+                       p.chunk, p.nb, (long long)a.budget, (const AllocHeader*)w.header,                  \
+                       (const long long*)w.block_ksum, (const long long*)w.block_tied, a.delta, a.util,   \
+                       a.group_off, a.summary, a.dev_status)
+    if (mode == 0) HORA_LAUNCH_BISECT_WRITE(0);
+    else if (mode == 1) HORA_LAUNCH_BISECT_WRITE(1);
+    else HORA_LAUNCH_BISECT_WRITE(2);
+#undef HORA_LAUNCH_BISECT_WRITE
+    return check_launch();
+}
+
+int run_bisect_counts(const CountsSource& src, const CommonArgs& a, const Plan& p, const Workspace& w) {
+    return run_bisect(src, a, p, w);
+}
+int run_bisect_posterior(const PosteriorSource& src, const CommonArgs& a, const Plan& p, const Workspace& w) {
+    return run_bisect(src, a, p, w);
+}
+
+}  // namespace hora

@@ -205,9 +205,7 @@ __global__ __launch_bounds__(kPrefixThreads) void k_shard_setup(long long n_shar
 }
 
 struct ShardShared {
-    unsigned long long cnt[kBins];
-    unsigned long long vmax[kBins];
-    unsigned long long vmin_inv[kBins];
+    TallyBins bins;
     unsigned long long red_u[2][kShardWaves];
     long long red_i[2][kShardWaves];
     unsigned long long lo, hi;   // bracket of tau's bit pattern
@@ -297,11 +295,9 @@ __device__ bool threshold_by_walks(const Src& src, long long lo_i, long long hi_
         if (sh.done) break;   // uniform: written before the barrier that ends a pass
         const unsigned long long lo = sh.lo, hi_cur = sh.hi;
         const long long above = sh.above;
-        const unsigned long long width = hi_cur - lo;                 // >= 1
-        const int bitlen = width > 1 ? 64 - __clzll((long long)(width - 1)) : 0;
-        const int shift = bitlen > 8 ? bitlen - 8 : 0;                // (width - 1) >> shift < kBins
+        const int shift = bracket_shift(lo, hi_cur);
         static_assert(kBins == kShardThreads, "one interval per thread");
-        sh.cnt[threadIdx.x] = 0; sh.vmax[threadIdx.x] = 0; sh.vmin_inv[threadIdx.x] = 0;
+        sh.bins.cnt[threadIdx.x] = 0; sh.bins.vmax[threadIdx.x] = 0; sh.bins.vmin_inv[threadIdx.x] = 0;
         __syncthreads();
         // every wavefront runs whole rounds, so that the ballots see all of its lanes
         for (long long i0 = lo_i; i0 < hi_i; i0 += kShardThreads) {
@@ -315,29 +311,7 @@ __device__ bool threshold_by_walks(const Src& src, long long lo_i, long long hi_
             unsigned long long gb = gain_bits(g);
             bool active = i < hi_i && k < limit && gb > lo;
             while (__ballot(active)) {
-                const bool inside = active && gb <= hi_cur;
-                // lanes that hold the same gain (the rule under a shared prior) tally once
-                unsigned long long pending = __ballot(inside);
-                for (int round = 0; round < 8 && pending; ++round) {
-                    const int leader = __ffsll((long long)pending) - 1;
-                    const unsigned long long v = read_lane_u64(gb, leader);
-                    const unsigned long long same = __ballot(inside && gb == v);
-                    // gains that do not repeat (per-prompt posteriors): no point in more rounds
-                    if (round == 0 && same == (1ull << leader)) break;
-                    if (lane == leader) {
-                        const int j = (int)((v - lo - 1ull) >> shift);
-                        atomicAdd(&sh.cnt[j], (unsigned long long)__popcll(same));
-                        atomicMax(&sh.vmax[j], v);
-                        atomicMax(&sh.vmin_inv[j], ~v);
-                    }
-                    pending &= ~same;
-                }
-                if (inside && ((pending >> lane) & 1ull)) {
-                    const int j = (int)((gb - lo - 1ull) >> shift);
-                    atomicAdd(&sh.cnt[j], 1ull);
-                    atomicMax(&sh.vmax[j], gb);
-                    atomicMax(&sh.vmin_inv[j], ~gb);
-                }
+                tally_gains(sh.bins, active && gb <= hi_cur, gb, lo, shift);
                 if (active) {
                     g = gain_next(g, b, s, lf);
                     lf += 1.0;
@@ -350,8 +324,8 @@ __device__ bool threshold_by_walks(const Src& src, long long lo_i, long long hi_
         __syncthreads();   // the tallies are complete
         // interval j = kBins - 1 - thread: thread 0 owns the top interval
         const int j = kBins - 1 - (int)threadIdx.x;
-        const long long cj = (long long)sh.cnt[j];
-        const unsigned long long mx = sh.vmax[j], mn = ~sh.vmin_inv[j];
+        const long long cj = (long long)sh.bins.cnt[j];
+        const unsigned long long mx = sh.bins.vmax[j], mn = ~sh.bins.vmin_inv[j];
         long long before, unused_ex, total, unused_tot;
         shard_scan2(cj, 0, before, unused_ex, total, unused_tot, sh);
         before += above;
@@ -408,10 +382,8 @@ __device__ bool threshold_by_table(const Src& src, long long lo_i, long long hi_
         if (sh.done) break;
         const unsigned long long lo = sh.lo, hi_cur = sh.hi;
         const long long above = sh.above;
-        const unsigned long long width = hi_cur - lo;
-        const int bitlen = width > 1 ? 64 - __clzll((long long)(width - 1)) : 0;
-        const int shift = bitlen > 8 ? bitlen - 8 : 0;
-        sh.cnt[threadIdx.x] = 0; sh.vmax[threadIdx.x] = 0; sh.vmin_inv[threadIdx.x] = 0;
+        const int shift = bracket_shift(lo, hi_cur);
+        sh.bins.cnt[threadIdx.x] = 0; sh.bins.vmax[threadIdx.x] = 0; sh.bins.vmin_inv[threadIdx.x] = 0;
         __syncthreads();
         for (int cls = 0; cls < nc; ++cls) {            // rows of classes the shard does not hold are skipped
             const long long w = sh.n_cls[cls];
@@ -421,16 +393,16 @@ __device__ bool threshold_by_table(const Src& src, long long lo_i, long long hi_
                 const unsigned long long v = gain_bits(row[l]);
                 if (v > lo && v <= hi_cur) {
                     const int j = (int)((v - lo - 1ull) >> shift);
-                    atomicAdd(&sh.cnt[j], (unsigned long long)w);
-                    atomicMax(&sh.vmax[j], v);
-                    atomicMax(&sh.vmin_inv[j], ~v);
+                    atomicAdd(&sh.bins.cnt[j], (unsigned long long)w);
+                    atomicMax(&sh.bins.vmax[j], v);
+                    atomicMax(&sh.bins.vmin_inv[j], ~v);
                 }
             }
         }
         __syncthreads();
         const int j = kBins - 1 - (int)threadIdx.x;             // thread 0 owns the top interval
-        const long long cj = (long long)sh.cnt[j];
-        const unsigned long long mx = sh.vmax[j], mn = ~sh.vmin_inv[j];
+        const long long cj = (long long)sh.bins.cnt[j];
+        const unsigned long long mx = sh.bins.vmax[j], mn = ~sh.bins.vmin_inv[j];
         long long before, unused_ex, total, unused_tot;
         shard_scan2(cj, 0, before, unused_ex, total, unused_tot, sh);
         before += above;
@@ -487,6 +459,8 @@ __device__ void shard_core(const Src& src, long long lo_i, long long hi_i, long 
     __shared__ ShardShared sh;
     long long limit = cap > 0 ? (long long)cap : budget;
     if (limit > budget) limit = budget;
+    const bool depth_capped = limit > (long long)HORA_MAX_DEPTH;   // the library's bound on one prompt's depth
+    if (depth_capped) limit = (long long)HORA_MAX_DEPTH;
 
     // ---- threshold ---------------------------------------------------------------------
     unsigned long long tau_bits = ~0ull;   // budget 0: nothing is above tau
@@ -519,6 +493,7 @@ __device__ void shard_core(const Src& src, long long lo_i, long long hi_i, long 
             data_bad |= !src.load(i, a, b);
             k = walk_above<true>(a, b, tau_bits, limit, g, lf, e);
             tied = (k < limit) && (gain_bits(g) == tau_bits);
+            if (depth_capped && k == limit && gain_bits(g) > tau_bits) report(dev_status, HORA_ERR_UNSUPPORTED);
         }
         delta[i] = (int32_t)((unsigned)k | (tied ? kShardTiedBit : 0u));
         if (util) util[i] = e;
@@ -579,6 +554,20 @@ __device__ void shard_core(const Src& src, long long lo_i, long long hi_i, long 
     }
 }
 
+// What is wrong with a shard's bounds or budget, if anything: HORA_ERR_RANGE when the shards do
+// not tile [0, n) in order or the budget is negative, HORA_ERR_INFEASIBLE when the budget
+// cannot be placed in the shard, HORA_ERR_UNSUPPORTED when it is beyond the depth bound.
+__device__ __forceinline__ int check_shard(long long shard, long long n_shards, long long n, long long lo_i,
+                                           long long hi_i, long long budget, int cap) {
+    if (lo_i < 0 || hi_i < lo_i || hi_i > n || budget < 0 || (shard == 0 && lo_i != 0) ||
+        (shard == n_shards - 1 && hi_i != n))
+        return HORA_ERR_RANGE;
+    const long long size = hi_i - lo_i;
+    if ((budget > 0 && size == 0) || (cap > 0 && budget > size * (long long)cap)) return HORA_ERR_INFEASIBLE;
+    if (budget > size * (long long)HORA_MAX_DEPTH || budget >= (1ll << 52)) return HORA_ERR_UNSUPPORTED;
+    return HORA_OK;
+}
+
 // Loads and checks one shard's bounds and budget, then runs shard_core on it.
 template <class Src, int kOff>
 __device__ void shard_by_workgroup(const Src& src, long long shard, long long n, int g0, long long n_shards,
@@ -591,17 +580,9 @@ __device__ void shard_by_workgroup(const Src& src, long long shard, long long n,
                                    int32_t* dev_status) {
     const long long lo_i = shard_off[shard], hi_i = shard_off[shard + 1];
     const long long budget = shard_budget[shard];
-    // the shards must tile [0, n) in order, and the budget must fit the shard
-    bool bad = lo_i < 0 || hi_i < lo_i || hi_i > n || budget < 0 || (shard == 0 && lo_i != 0) ||
-               (shard == n_shards - 1 && hi_i != n);
-    const long long size = bad ? 0 : hi_i - lo_i;
-    bool infeasible = false;
-    if (!bad) {
-        infeasible = (budget > 0 && size == 0) || (cap > 0 && budget > size * (long long)cap) ||
-                     (cap <= 0 && budget >= (1ll << 31) - 1) || budget >= (1ll << 52);
-    }
-    if (bad || infeasible) {
-        if (threadIdx.x == 0) report(dev_status, bad ? HORA_ERR_RANGE : HORA_ERR_INFEASIBLE);
+    const int wrong = check_shard(shard, n_shards, n, lo_i, hi_i, budget, cap);
+    if (wrong != HORA_OK) {
+        if (threadIdx.x == 0) report(dev_status, wrong);
         return;
     }
     shard_core<Src, kOff>(src, lo_i, hi_i, budget, kOff != 0 ? prefix[shard] : 0, n, g0, cap, depth, gain_table,
@@ -746,22 +727,17 @@ __global__ __launch_bounds__(kShardThreads) void k_shard_allocate_waves(
     __syncthreads();
     if (!live) return;
     WaveScratch& ws = s_wave[wave_id()];
-    bool bad = lo_i < 0 || hi_i < lo_i || hi_i > n || budget < 0 || (shard == 0 && lo_i != 0) ||
-               (shard == n_shards - 1 && hi_i != n);
-    const long long size = bad ? 0 : hi_i - lo_i;
-    bool infeasible = false;
-    if (!bad)
-        infeasible = (budget > 0 && size == 0) || (cap > 0 && budget > size * (long long)cap) ||
-                     (cap <= 0 && budget >= (1ll << 31) - 1) || budget >= (1ll << 52);
-    if (bad || infeasible) {
-        if (lane == 0) report(dev_status, bad ? HORA_ERR_RANGE : HORA_ERR_INFEASIBLE);
+    const int wrong = check_shard(shard, n_shards, n, lo_i, hi_i, budget, cap);
+    if (wrong != HORA_OK) {
+        if (lane == 0) report(dev_status, wrong);
         return;
     }
+    const long long size = hi_i - lo_i;
     if (size > kWaveShardMax) {
         if (lane == 0) todo[1 + atomicAdd(&todo[0], 1)] = (int)shard;
         return;
     }
-    const long long limit = cap > 0 ? (budget < cap ? budget : (long long)cap) : budget;
+    const long long limit = cap > 0 ? (budget < cap ? budget : (long long)cap) : budget;   // (the table is far shallower than the depth bound)
 
     // ---- 1. histogram: lane k ends up with the number of prompts of class k
     int n_mine = 0;
