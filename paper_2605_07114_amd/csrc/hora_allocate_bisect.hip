@@ -5,28 +5,28 @@
 // (prompt, l) pairs; every prompt's gains decrease strictly, so the set is described by a
 // threshold tau, the budget-th largest gain.  tau is found by a bisection on its bit pattern
 // (positive binary64 values order like their patterns) in which every prompt does a monotone
-// search along its own gain sequence.  A fixed, small number of launches does it for any input:
+// search along its own gain sequence.  Six launches do it for any input:
 //
 //  1. coarse count (k_bisect_coarse): every tile of 4096 prompts walks its prompts' gains
 //     downwards octave by octave (an octave = one exponent step of the pattern), counting them
-//     per quarter octave with wavefront ballots, until the tile has seen its share of the
-//     budget.  If every tile selected its share on its own, the union would hold at least
-//     `budget` gains, all of them above the lowest tile's stopping point: that point is a lower
-//     bound for tau, whatever the data, and no prompt walks much deeper than tau.  The walks
-//     are resumable (state in registers), so going deeper costs no second walk.
-//  2. k_bisect_coarse_reduce adds the tiles' counts up and picks the quarter octave in which
-//     the running count reaches the budget: the first bracket (lo, hi] of tau.
-//  3. two narrowing passes (k_bisect_pass + k_bisect_reduce): the bracket is cut into 256
-//     intervals; the gains inside are tallied per interval (count, largest, smallest) and the
-//     bracket shrinks to the gains seen in the interval where the running count reaches the
-//     budget.  The first pass walks the prompts and sets the gains of the bracket aside (one
-//     list per workgroup), the second one works from the lists and keeps what is left.
-//  4. k_bisect_final (one workgroup) finishes from the lists, usually a few hundred gains.
-//  5. k_bisect_finalize: k_i = #{l : M_i(l) > tau}, the tied flag and E_i(k_i) per prompt;
+//     per quarter octave, until the tile has seen its share of the budget.  If every tile
+//     selected its share on its own, the union would hold at least `budget` gains, all of them
+//     above the lowest tile's stopping point: that point is a lower bound for tau, whatever the
+//     data, and no prompt walks much deeper than tau.  The walks are resumable (state in
+//     registers), so going deeper costs no second walk.
+//  2. first narrowing pass (k_bisect_pass<0>): every workgroup adds the tiles' counts up for
+//     itself and takes the quarter octave in which the running count reaches the budget as the
+//     first bracket (lo, hi] of tau; the bracket is cut into 256 intervals, the gains inside are
+//     tallied per interval (count, largest, smallest) and set aside, one list per workgroup.
+//  3. k_bisect_reduce adds the workgroups' tallies up; the bracket shrinks to the gains seen in
+//     the interval where the running count reaches the budget.
+//  4. k_bisect_pass<1> keeps what the lists hold of the narrower bracket.
+//  5. k_bisect_finalize: every workgroup finishes the search from the lists (usually a few
+//     thousand gains), then k_i = #{l : M_i(l) > tau}, the tied flag and E_i(k_i) per prompt;
 //     k_bisect_write: ties at tau by prompt index, delta, utilities, group offsets.
 //
-// Under a shared prior the gains of a bracket are few distinct values, each repeated: the
-// first narrowing pass already closes the bracket and the later kernels return at once.
+// Under a shared prior the gains of a bracket are few distinct values, each repeated: step 3
+// already closes the bracket and steps 4 and the finisher return at once.
 #include <hip/hip_runtime.h>
 
 #include <climits>
@@ -152,18 +152,20 @@ __global__ __launch_bounds__(kBig) void k_bisect_coarse(Src src, long long n, lo
         for (;; ++o) {
             const unsigned long long top = octave_top(o);
             const unsigned long long bottom = top - kOctave;
-            unsigned c0 = 0, c1 = 0, c2 = 0, c3 = 0;     // wavefront-uniform counts of the four quarter octaves
+            // this lane's counts of the four quarter octaves: 8 bits each in one register, moved
+            // to the wide counters before a field can overflow
+            int c0 = 0, c1 = 0, c2 = 0, c3 = 0;
+            unsigned packed = 0u;
+            int rounds = 0;
             bool any;
             do {
                 any = false;
 #pragma unroll
                 for (int j = 0; j < kItems; ++j) {
                     const bool act = alive[j] && gb[j] > bottom;
-                    const int sub = (int)((top - gb[j]) >> 50);
-                    c0 += (unsigned)__popcll(__ballot(act && sub == 0));
-                    c1 += (unsigned)__popcll(__ballot(act && sub == 1));
-                    c2 += (unsigned)__popcll(__ballot(act && sub == 2));
-                    c3 += (unsigned)__popcll(__ballot(act && sub == 3));
+                    // 8 * quarter octave of the gain: bits 50 and 51 of (top - pattern)
+                    const unsigned shift8 = ((unsigned)((top - gb[j]) >> 32) >> 15) & 0x18u;
+                    packed += act ? (1u << shift8) : 0u;
                     if (act) {
                         g[j] = gain_next(g[j], b[j], s[j], lf[j]);
                         lf[j] += 1.0;
@@ -172,19 +174,32 @@ __global__ __launch_bounds__(kBig) void k_bisect_coarse(Src src, long long n, lo
                     }
                     any |= act;
                 }
+                if (++rounds == 255 / kItems) {   // uniform
+                    c0 += (int)(packed & 0xffu); c1 += (int)((packed >> 8) & 0xffu);
+                    c2 += (int)((packed >> 16) & 0xffu); c3 += (int)(packed >> 24);
+                    packed = 0u;
+                    rounds = 0;
+                }
             } while (__ballot(any));
+            c0 += (int)(packed & 0xffu); c1 += (int)((packed >> 8) & 0xffu);
+            c2 += (int)((packed >> 16) & 0xffu); c3 += (int)(packed >> 24);
             bool mine_alive = false;
 #pragma unroll
             for (int j = 0; j < kItems; ++j) mine_alive |= alive[j];
             const bool wave_alive = __ballot(mine_alive) != 0ull;
+            // (a lane counts at most kItems * limit <= 2^22 gains per octave: the sums fit 32 bits)
+            c0 = wave_last_i32(wave_incl_scan_i32(c0));
+            c1 = wave_last_i32(wave_incl_scan_i32(c1));
+            c2 = wave_last_i32(wave_incl_scan_i32(c2));
+            c3 = wave_last_i32(wave_incl_scan_i32(c3));
             if (lane == 0) {
                 unsigned long long* row = s_cnt[o & (kRing - 1)];
-                if (c0) atomicAdd(&row[0], (unsigned long long)c0);
-                if (c1) atomicAdd(&row[1], (unsigned long long)c1);
-                if (c2) atomicAdd(&row[2], (unsigned long long)c2);
-                if (c3) atomicAdd(&row[3], (unsigned long long)c3);
-                const unsigned all = c0 + c1 + c2 + c3;
-                if (all) atomicAdd(&s_total, (unsigned long long)all);
+                if (c0) atomicAdd(&row[0], (unsigned long long)(unsigned)c0);
+                if (c1) atomicAdd(&row[1], (unsigned long long)(unsigned)c1);
+                if (c2) atomicAdd(&row[2], (unsigned long long)(unsigned)c2);
+                if (c3) atomicAdd(&row[3], (unsigned long long)(unsigned)c3);
+                const unsigned long long all = (unsigned long long)(unsigned)c0 + (unsigned)c1 + (unsigned)c2 + (unsigned)c3;
+                if (all) atomicAdd(&s_total, all);
                 if (wave_alive) s_alive[o & 3] = 1;
             }
             __syncthreads();
@@ -214,125 +229,6 @@ __global__ __launch_bounds__(kBig) void k_bisect_coarse(Src src, long long n, lo
         __syncthreads();   // the counters are reused by the next tile
     }
     if (bad) report(dev_status, HORA_ERR_RANGE);
-}
-
-// ----------------------------------------------------------------------------------
-// 2. The tiles' coarse counts added up, and the first bracket.  Octave o can be resolved
-// when every tile still has it in detail (o >= stop - 7 for all tiles) and every tile that
-// has gains left walked it completely (o <= stop for those).  Inside that range the quarter
-// octave in which the running count reaches the budget becomes the bracket.  Otherwise (tiles
-// of very different prompts, caps that leave tiles short of their share) a wider bracket that
-// is still correct is taken and the narrowing passes do the rest.
-// One workgroup: the slots are 272 bytes per 4096 prompts.
-// ----------------------------------------------------------------------------------
-__global__ __launch_bounds__(kBig) void k_bisect_coarse_reduce(long long tiles, long long budget,
-                                                               const CoarseSlot* __restrict__ slots,
-                                                               AllocHeader* __restrict__ hdr) {
-    __shared__ int s_smax, s_smin;
-    __shared__ long long s_sum[2 + kWinOct * kSubBins];   // [0] above the range, [1] everything counted, then the bins
-    if (threadIdx.x == 0) { s_smax = 0; s_smin = INT_MAX; }
-    if (threadIdx.x < 2 + kWinOct * kSubBins) s_sum[threadIdx.x] = 0;
-    __syncthreads();
-    int smax = 0, smin = INT_MAX;
-    for (long long u = threadIdx.x; u < tiles; u += kBig) {
-        const int stop = slots[u].stop;
-        smax = stop > smax ? stop : smax;
-        if (!slots[u].exhausted) smin = stop < smin ? stop : smin;
-    }
-    atomicMax(&s_smax, smax);
-    atomicMin(&s_smin, smin);
-    __syncthreads();
-    const int s_max = s_smax;
-    const int s_min = s_smin == INT_MAX ? s_max : s_smin;   // no tile has gains left: everything is counted
-    const int first = s_max - (kWinOct - 1) > 0 ? s_max - (kWinOct - 1) : 0;   // first octave of the range
-    long long base = 0, known = 0;
-    long long bin[kWinOct][kSubBins];
-#pragma unroll
-    for (int w = 0; w < kWinOct; ++w)
-#pragma unroll
-        for (int q = 0; q < kSubBins; ++q) bin[w][q] = 0;
-    for (long long u = threadIdx.x; u < tiles; u += kBig) {
-        const CoarseSlot* slot = slots + u;
-        const int stop = slot->stop;
-        long long top = (long long)slot->cum_top;
-        known += top;
-#pragma unroll
-        for (int w = 0; w < kWinOct; ++w) {
-            const int oct = stop - ((stop - w) & (kWinOct - 1));   // the octave of the slot's row w
-            long long row = 0;
-#pragma unroll
-            for (int q = 0; q < kSubBins; ++q) row += (long long)slot->cnt[w][q];
-            known += oct >= 0 ? row : 0;
-            if (oct >= 0 && oct < first) top += row;
-            if (oct >= first) {   // oct - first is in [0, 7] because stop <= s_max
-#pragma unroll
-                for (int r = 0; r < kWinOct; ++r)
-                    if (oct - first == r) {
-#pragma unroll
-                        for (int q = 0; q < kSubBins; ++q) bin[r][q] += (long long)slot->cnt[w][q];
-                    }
-            }
-        }
-        base += top;
-    }
-    base = wave_sum<long long>(base);
-    known = wave_sum<long long>(known);
-    if (lane_id() == 0) {
-        atomicAdd((unsigned long long*)&s_sum[0], (unsigned long long)base);
-        atomicAdd((unsigned long long*)&s_sum[1], (unsigned long long)known);
-    }
-#pragma unroll
-    for (int r = 0; r < kWinOct; ++r)
-#pragma unroll
-        for (int q = 0; q < kSubBins; ++q) {
-            const long long v = wave_sum<long long>(bin[r][q]);
-            if (lane_id() == 0 && v) atomicAdd((unsigned long long*)&s_sum[2 + r * kSubBins + q], (unsigned long long)v);
-        }
-    __syncthreads();
-    if (threadIdx.x != 0) return;
-    unsigned long long lo = 0ull, hi = kOne;
-    long long above = 0, inside = -1;
-    const long long all_above = s_sum[0];
-    bool found = false;
-    if (all_above >= budget) {
-        lo = octave_top(first);          // count_gt(lo) >= budget already: tau lies above the range
-    } else {
-        long long cum = all_above;
-        int o = first;
-        for (; o <= s_min && !found; ++o) {
-            for (int q = 0; q < kSubBins; ++q) {
-                const long long c = s_sum[2 + (o - first) * kSubBins + q];
-                if (cum + c >= budget) {
-                    hi = octave_top(o) - (unsigned long long)q * (kOctave / kSubBins);
-                    lo = hi - kOctave / kSubBins;
-                    above = cum;
-                    inside = c;
-                    found = true;
-                    break;
-                }
-                cum += c;
-            }
-        }
-        if (!found) {
-            // The range ends above tau.  When it is not empty, the count above its lower end is
-            // complete and the bracket starts there; when it is empty (some tile stopped more
-            // than kWinOct octaves above another: very different prompts), nothing below 1 is.
-            // Downwards the bracket reaches to where every tile has seen its share, or, when the
-            // tiles' counts do not add up to the budget (caps), to zero.
-            if (s_min >= first) {
-                hi = octave_top(s_min + 1);
-                above = cum;
-            }
-            lo = s_sum[1] >= budget ? octave_top(s_max) - kOctave : 0ull;
-        }
-    }
-    hdr->slot[0].lo = lo; hdr->slot[0].hi = hi; hdr->slot[0].above = (unsigned long long)above;
-    hdr->slot[0].done = 0u; hdr->slot[0].flags = 0u;
-    hdr->slot[1].lo = 0ull; hdr->slot[1].hi = 0ull; hdr->slot[1].above = 0ull;
-    hdr->slot[1].done = 0u; hdr->slot[1].flags = 0u;
-    hdr->inside = inside;
-    hdr->tau = 0ull;
-    hdr->lists_ok = 0u;
 }
 
 // ----------------------------------------------------------------------------------
@@ -415,7 +311,7 @@ __device__ __forceinline__ void enter_pass(SelectShared& sh, const AllocHeader* 
     if (threadIdx.x == 0) {
         sh.lo = in->lo; sh.hi = in->hi; sh.above = (long long)in->above; sh.done = (int)in->done;
         sh.hit = 0;
-        sh.inside = pass == 0 ? hdr->inside : -1;
+        sh.inside = -1;
         sh.list_n = 0;
     }
     __syncthreads();
@@ -433,33 +329,157 @@ __device__ __forceinline__ void list_append(SelectShared& sh, unsigned long long
     if (keep && at < kListCap) list[at] = gb;
 }
 
-template <class Src>
+// ----------------------------------------------------------------------------------
+// 2. The tiles' coarse counts added up, and the first bracket; run by every workgroup of the
+// first narrowing pass for itself (the slots are 272 bytes per 4096 prompts: reading them all
+// costs less than a launch in between).  Octave o can be resolved when every tile still has it
+// in detail (o >= stop - 7 for all tiles) and every tile that has gains left walked it
+// completely (o <= stop for those).  Inside that range the quarter octave in which the
+// running count reaches the budget becomes the bracket.  Otherwise (tiles of very different
+// prompts, caps that leave tiles short of their share) a wider bracket that is still correct
+// is taken and the narrowing passes do the rest.
+// ----------------------------------------------------------------------------------
+struct CoarseShared {
+    int s_max, s_min;
+    long long sum[2 + kWinOct * kSubBins];   // [0] above the range, [1] everything counted, then the intervals
+};
+
+__device__ __forceinline__ void first_bracket(SelectShared& sh, CoarseShared& cs, long long tiles, long long budget,
+                                              const CoarseSlot* __restrict__ slots) {
+    if (threadIdx.x == 0) { cs.s_max = 0; cs.s_min = INT_MAX; }
+    if (threadIdx.x < 2 + kWinOct * kSubBins) cs.sum[threadIdx.x] = 0;
+    __syncthreads();
+    {
+        int smax = 0, smin = INT_MAX;
+        for (long long u = threadIdx.x; u < tiles; u += kBig) {
+            const int stop = slots[u].stop;
+            smax = stop > smax ? stop : smax;
+            if (!slots[u].exhausted) smin = stop < smin ? stop : smin;
+        }
+        if (__ballot(smax != 0 || smin != INT_MAX)) {   // (wavefronts without a tile have nothing to add)
+#pragma unroll
+            for (int d = kWave / 2; d > 0; d >>= 1) {
+                const int om = __shfl_xor(smax, d, kWave), on = __shfl_xor(smin, d, kWave);
+                smax = om > smax ? om : smax;
+                smin = on < smin ? on : smin;
+            }
+            if (lane_id() == 0) { atomicMax(&cs.s_max, smax); atomicMin(&cs.s_min, smin); }
+        }
+    }
+    __syncthreads();
+    const int s_max = cs.s_max;
+    const int s_min = cs.s_min == INT_MAX ? s_max : cs.s_min;   // no tile has gains left: everything is counted
+    const int first = s_max - (kWinOct - 1) > 0 ? s_max - (kWinOct - 1) : 0;   // first octave of the range
+    // every thread takes one count of one slot at a time (a slot's 32 counts are consecutive:
+    // coalesced loads); what lies above the range and the grand total are summed per thread,
+    // the counts of the range go to LDS by their octave
+    long long base = 0, known = 0;
+    bool mine = false;
+    for (long long idx = threadIdx.x; idx < tiles * (kWinOct * kSubBins); idx += kBig) {
+        mine = true;
+        const long long u = idx / (kWinOct * kSubBins);
+        const int e = (int)(idx % (kWinOct * kSubBins)), w = e / kSubBins, q = e % kSubBins;
+        const CoarseSlot* slot = slots + u;
+        const long long v = (long long)slot->cnt[w][q];
+        const int stop = slot->stop;
+        const int oct = stop - ((stop - w) & (kWinOct - 1));   // the octave of the slot's row w
+        if (e == 0) {
+            const long long top = (long long)slot->cum_top;
+            base += top;
+            known += top;
+        }
+        if (oct < 0) continue;
+        known += v;
+        if (oct < first) base += v;
+        // oct - first is in [0, 7] for the rows of the range, because stop <= s_max
+        else if (v) atomicAdd((unsigned long long*)&cs.sum[2 + (oct - first) * kSubBins + q], (unsigned long long)v);
+    }
+    if (__ballot(mine)) {
+        base = wave_total_i64(base);
+        known = wave_total_i64(known);
+        if (lane_id() == 0) {
+            atomicAdd((unsigned long long*)&cs.sum[0], (unsigned long long)base);
+            atomicAdd((unsigned long long*)&cs.sum[1], (unsigned long long)known);
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        unsigned long long lo = 0ull, hi = kOne;
+        long long above = 0, inside = -1;
+        const long long all_above = cs.sum[0];
+        bool found = false;
+        if (all_above >= budget) {
+            lo = octave_top(first);          // count_gt(lo) >= budget already: tau lies above the range
+        } else {
+            long long cum = all_above;
+            for (int o = first; o <= s_min && !found; ++o) {
+                for (int q = 0; q < kSubBins; ++q) {
+                    const long long c = cs.sum[2 + (o - first) * kSubBins + q];
+                    if (cum + c >= budget) {
+                        hi = octave_top(o) - (unsigned long long)q * (kOctave / kSubBins);
+                        lo = hi - kOctave / kSubBins;
+                        above = cum;
+                        inside = c;
+                        found = true;
+                        break;
+                    }
+                    cum += c;
+                }
+            }
+            if (!found) {
+                // The range ends above tau.  When it is not empty, the count above its lower end is
+                // complete and the bracket starts there; when it is empty (some tile stopped more
+                // than kWinOct octaves above another: very different prompts), nothing below 1 is.
+                // Downwards the bracket reaches to where every tile has seen its share, or, when the
+                // tiles' counts do not add up to the budget (caps), to zero.
+                if (s_min >= first) {
+                    hi = octave_top(s_min + 1);
+                    above = cum;
+                }
+                lo = cs.sum[1] >= budget ? octave_top(s_max) - kOctave : 0ull;
+            }
+        }
+        sh.lo = lo; sh.hi = hi; sh.above = above; sh.inside = inside;
+        sh.done = 0; sh.hit = 0; sh.list_n = 0;
+    }
+    __syncthreads();
+}
+
+// kPass = 0: the first bracket comes from the coarse count; the pass walks the prompts, tallies
+//   the bracket's gains and sets them aside when they are few enough.
+// kPass = 1: the bracket of pass 0 moved by its totals; no tallies, the pass only leaves the
+//   gains of the narrower bracket in the lists for the finisher: from the lists of pass 0, or,
+//   where those did not fit, by walking the prompts again.
+template <class Src, int kPass>
 __global__ __launch_bounds__(kBig) void k_bisect_pass(Src src, long long n, long long budget, long long limit,
-                                                      long long chunk, int pass, AllocHeader* __restrict__ hdr,
-                                                      SelectBins* __restrict__ bins,
+                                                      long long chunk, long long tiles,
+                                                      const CoarseSlot* __restrict__ slots,
+                                                      AllocHeader* __restrict__ hdr, SelectBins* __restrict__ bins,
                                                       unsigned long long* __restrict__ lists,
                                                       int* __restrict__ list_count) {
     __shared__ SelectShared sh;
-    enter_pass(sh, hdr, bins, pass, budget);
-    const Bracket* in = &hdr->slot[pass & 1];
-    // Where this pass gets the gains of its bracket from.  The pass before may have set the
-    // gains of its own (wider) bracket aside: then this pass tallies from the lists and keeps
-    // what lies in the narrower bracket.  Otherwise it walks the prompts, and sets the
-    // bracket's gains aside when they are few enough.  A list that does not fit only means
-    // that the next pass walks again.
-    const bool from_lists = (in->flags & kFlagCollected) != 0 && hdr->lists_ok != 0;
+    bool from_lists = false;
+    if constexpr (kPass == 0) {
+        __shared__ CoarseShared cs;
+        first_bracket(sh, cs, tiles, budget, slots);
+    } else {
+        enter_pass(sh, hdr, bins, kPass, budget);
+        // the pass before set the gains of its (wider) bracket aside and all of them fitted
+        from_lists = (hdr->slot[kPass & 1].flags & kFlagCollected) != 0 && hdr->lists_ok != 0;
+    }
     const bool collect = from_lists || (sh.inside >= 0 && sh.inside <= kCollectMax);
     const bool done = sh.done != 0;
     if (blockIdx.x == 0 && threadIdx.x == 0) {   // for the next kernel
-        Bracket* out = &hdr->slot[(pass + 1) & 1];
+        Bracket* out = &hdr->slot[(kPass + 1) & 1];
         out->lo = sh.lo; out->hi = sh.hi; out->above = (unsigned long long)sh.above;
         out->done = (unsigned)sh.done;
-        out->flags = done ? 0u : (kFlagPending | (collect ? kFlagCollected : 0u));
+        out->flags = done ? 0u : ((kPass == 0 ? kFlagPending : 0u) | (collect ? kFlagCollected : 0u));
     }
     if (done) return;   // uniform over the grid: every workgroup moved the same bracket
+    constexpr bool kTally = kPass == 0;
     const unsigned long long lo = sh.lo, hi = sh.hi;
     const int shift = bracket_shift(lo, hi);
-    if (threadIdx.x < kBins) { sh.bins.cnt[threadIdx.x] = 0; sh.bins.vmax[threadIdx.x] = 0; sh.bins.vmin_inv[threadIdx.x] = 0; }
+    if (kTally && threadIdx.x < kBins) { sh.bins.cnt[threadIdx.x] = 0; sh.bins.vmax[threadIdx.x] = 0; sh.bins.vmin_inv[threadIdx.x] = 0; }
     unsigned long long* mine = lists + (long long)blockIdx.x * kListCap;
     if (from_lists) {
         constexpr int kPer = kListCap / kBig;
@@ -470,14 +490,10 @@ __global__ __launch_bounds__(kBig) void k_bisect_pass(Src src, long long n, long
             const int e = q * kBig + (int)threadIdx.x;
             v[q] = e < have ? mine[e] : 0ull;
         }
-        __syncthreads();   // the list has been read (it is rewritten below), the tallies are zero
+        __syncthreads();   // the list has been read: it is rewritten below
 #pragma unroll
-        for (int q = 0; q < kPer; ++q) {
-            const bool inside = v[q] > lo && v[q] <= hi;
-            tally_gains(sh.bins, inside, v[q], lo, shift);
-            list_append(sh, mine, inside, v[q]);
-        }
-    } else {
+        for (int q = 0; q < kPer; ++q) list_append(sh, mine, v[q] > lo && v[q] <= hi, v[q]);
+    } else if (kTally || collect) {
         __syncthreads();
         const long long base = (long long)blockIdx.x * chunk;
         const long long end = base + chunk < n ? base + chunk : n;
@@ -517,7 +533,7 @@ __global__ __launch_bounds__(kBig) void k_bisect_pass(Src src, long long n, long
             for (int j = 0; j < kItems; ++j) {
                 bool inside = alive[j] && gb[j] > lo;
                 while (__ballot(inside)) {
-                    tally_gains(sh.bins, inside, gb[j], lo, shift);
+                    if (kTally) tally_gains(sh.bins, inside, gb[j], lo, shift);
                     if (collect) list_append(sh, mine, inside, gb[j]);
                     if (inside) {
                         g[j] = gain_next(g[j], b[j], s[j], lf[j]);
@@ -529,14 +545,16 @@ __global__ __launch_bounds__(kBig) void k_bisect_pass(Src src, long long n, long
             }
         }
     }
-    __syncthreads();   // the workgroup's tallies are complete
+    __syncthreads();   // the workgroup's tallies and its list are complete
     if (collect && threadIdx.x == 0) list_count[blockIdx.x] = sh.list_n <= kListCap ? sh.list_n : -1;
-    SelectBins* slot = bins + blockIdx.x;
-    if (threadIdx.x < kBins) {
-        const unsigned long long c0 = sh.bins.cnt[threadIdx.x];
-        slot->cnt[threadIdx.x] = c0 > (unsigned long long)budget ? (unsigned long long)budget : c0;
-        slot->vmax[threadIdx.x] = sh.bins.vmax[threadIdx.x];
-        slot->vmin_inv[threadIdx.x] = sh.bins.vmin_inv[threadIdx.x];
+    if (kTally) {
+        SelectBins* slot = bins + blockIdx.x;
+        if (threadIdx.x < kBins) {
+            const unsigned long long c0 = sh.bins.cnt[threadIdx.x];
+            slot->cnt[threadIdx.x] = c0 > (unsigned long long)budget ? (unsigned long long)budget : c0;
+            slot->vmax[threadIdx.x] = sh.bins.vmax[threadIdx.x];
+            slot->vmin_inv[threadIdx.x] = sh.bins.vmin_inv[threadIdx.x];
+        }
     }
 }
 
@@ -596,24 +614,44 @@ __global__ __launch_bounds__(kThreads) void k_bisect_reduce(int nb, int pass, Al
 }
 
 // ----------------------------------------------------------------------------------
-// 4. The end of the search, one workgroup: moves the bracket by the totals of the last
-// narrowing pass and, if it is still open, repeats passes on its own until it closes: from
-// the workgroups' lists (what two 256-fold cuts leave of a quarter octave: usually a few
-// hundred gains).  Only when the lists could not hold the bracket (more than half a million
-// distinct gains within 2^-16 of one another) does it walk the prompts itself, which is slow
-// but correct.  Leaves tau in the header.
+// 4. The end of the search, run by every workgroup of the output kernel for itself (the same
+// arithmetic on the same numbers everywhere): if the bracket that pass 1 left is still open,
+// narrowing passes are repeated until it closes, from the workgroups' lists (what a 256-fold
+// cut leaves of a quarter octave: usually a few thousand gains in all).  Only when the lists
+// could not hold the bracket (more gains within 2^-10 of one another than the lists have room
+// for, twice in a row) does every workgroup walk all prompts itself, which is slow but correct.
+// Returns tau's pattern; *ok says whether the search ended properly.
 // ----------------------------------------------------------------------------------
 template <class Src>
-__global__ __launch_bounds__(kBig) void k_bisect_final(Src src, long long n, long long budget, long long limit,
-                                                       int nb, int pass, AllocHeader* __restrict__ hdr,
-                                                       const SelectBins* __restrict__ bins,
-                                                       const unsigned long long* __restrict__ lists,
-                                                       const int* __restrict__ list_count, int32_t* dev_status) {
-    __shared__ SelectShared sh;
-    enter_pass(sh, hdr, bins, pass, budget);
-    const Bracket* in = &hdr->slot[pass & 1];
-    const bool from_lists = (in->flags & kFlagCollected) != 0 && hdr->lists_ok != 0;
-    const int lane = lane_id();
+__device__ unsigned long long finish_search(SelectShared& sh, const Src& src, long long n, long long budget,
+                                            long long limit, int nb, const AllocHeader* __restrict__ hdr,
+                                            const unsigned long long* __restrict__ lists,
+                                            const int* __restrict__ list_count, bool* ok) {
+    const Bracket* in = &hdr->slot[0];   // written by pass 1
+    if (threadIdx.x == 0) {
+        sh.lo = in->lo; sh.hi = in->hi; sh.above = (long long)in->above; sh.done = (int)in->done;
+        sh.hit = 0; sh.inside = -1; sh.list_n = 0;
+    }
+    static_assert(kMaxBlocks <= kBig && kMaxBlocks == 4 * kWave, "one thread per list, four wavefronts of them");
+    __shared__ int s_off[kMaxBlocks + 1];   // list b holds the entries s_off[b] .. s_off[b + 1] - 1 of all lists together
+    __shared__ int s_part[4];
+    const int have_mine = (int)threadIdx.x < nb ? list_count[threadIdx.x] : 0;
+    const int overflow = __syncthreads_or(have_mine < 0 ? 1 : 0);
+    const bool from_lists = (in->flags & kFlagCollected) != 0 && !overflow;
+    int total_entries = 0;
+    if (from_lists) {
+        const int incl = wave_incl_scan_i32(have_mine);
+        if (threadIdx.x < kMaxBlocks && lane_id() == kWave - 1) s_part[wave_id()] = incl;
+        __syncthreads();
+        if (threadIdx.x < kMaxBlocks) {
+            int before = 0;
+            for (int w = 0; w < wave_id(); ++w) before += s_part[w];
+            s_off[threadIdx.x + 1] = before + incl;
+            if (threadIdx.x == 0) s_off[0] = 0;
+        }
+        __syncthreads();
+        total_entries = s_off[kMaxBlocks];
+    }
     for (int iter = 0; iter < kFinalMaxPasses; ++iter) {
         if (sh.done) break;   // uniform: written before the barrier that ends move_bracket
         const unsigned long long lo = sh.lo, hi = sh.hi;
@@ -621,14 +659,19 @@ __global__ __launch_bounds__(kBig) void k_bisect_final(Src src, long long n, lon
         if (threadIdx.x < kBins) { sh.bins.cnt[threadIdx.x] = 0; sh.bins.vmax[threadIdx.x] = 0; sh.bins.vmin_inv[threadIdx.x] = 0; }
         __syncthreads();
         if (from_lists) {
-            for (int wg = wave_id(); wg < nb; wg += kBigWaves) {
-                const int have = list_count[wg];
-                const unsigned long long* list = lists + (long long)wg * kListCap;
-                for (int e0 = 0; e0 < have; e0 += kWave) {
-                    const int e = e0 + lane;
-                    const unsigned long long v = e < have ? list[e] : 0ull;
-                    tally_gains(sh.bins, v > lo && v <= hi, v, lo, shift);
+            // all entries of all lists as one sequence: every thread finds the list of its entry
+            // by a search of the offsets (LDS), so that the loads are independent of one another
+            for (int e0 = 0; e0 < total_entries; e0 += kBig) {
+                const int e = e0 + (int)threadIdx.x;
+                unsigned long long v = 0ull;
+                if (e < total_entries) {
+                    int b = 0;
+#pragma unroll
+                    for (int step = kMaxBlocks / 2; step > 0; step >>= 1)
+                        if (s_off[b + step] <= e) b += step;     // the last list that starts at or before e
+                    v = lists[(long long)b * kListCap + (e - s_off[b])];
                 }
+                tally_gains(sh.bins, v > lo && v <= hi, v, lo, shift);
             }
         } else {
             for (long long i0 = 0; i0 < n; i0 += kBig) {
@@ -663,27 +706,38 @@ __global__ __launch_bounds__(kBig) void k_bisect_final(Src src, long long n, lon
         }
         move_bracket(sh, cj, mx, mn, budget);
     }
-    if (threadIdx.x == 0) {
-        hdr->tau = sh.hi;
-        // (cannot happen with valid posteriors and a budget that fits)
-        if (sh.done != 1) report(dev_status, sh.done == 2 ? HORA_ERR_INFEASIBLE : HORA_ERR_RANGE);
-    }
+    __syncthreads();
+    *ok = sh.done == 1;
+    return sh.hi;
 }
 
 // ----------------------------------------------------------------------------------
-// 5a. With tau known: k_i = #{l : M_i(l) > tau} and the tied flag go to delta[i] (flag in
-// bit 31), the survival product E_i(k_i) to util[i]; per-workgroup sums to block_ksum /
+// 5a. The end of the search (4.), then with tau known: k_i = #{l : M_i(l) > tau} and the tied
+// flag go to delta[i] (flag in bit 31), the survival product E_i(k_i) to util[i]; per-workgroup sums to block_ksum /
 // block_tied.  kItems prompts per thread, their walks in lockstep.
 // ----------------------------------------------------------------------------------
 template <class Src>
 __global__ __launch_bounds__(kBig) void k_bisect_finalize(Src src, long long n, long long chunk, long long budget,
-                                                          long long limit, int depth_capped,
-                                                          const AllocHeader* __restrict__ hdr,
+                                                          long long limit, int depth_capped, int nb,
+                                                          AllocHeader* __restrict__ hdr,
+                                                          const unsigned long long* __restrict__ lists,
+                                                          const int* __restrict__ list_count,
                                                           int32_t* __restrict__ delta, double* __restrict__ util,
                                                           long long* __restrict__ block_ksum,
                                                           long long* __restrict__ block_tied, int32_t* dev_status) {
-    __shared__ long long s_red[2][kBigWaves];
-    const unsigned long long tau_bits = budget > 0 ? hdr->tau : ~0ull;
+    __shared__ SelectShared sh;
+    long long (&s_red)[2][kBigWaves] = *reinterpret_cast<long long (*)[2][kBigWaves]>(&sh.bins.cnt[0]);
+    unsigned long long tau_bits = ~0ull;   // budget 0: nothing is above tau
+    if (budget > 0) {
+        bool ok;
+        tau_bits = finish_search(sh, src, n, budget, limit, nb, hdr, lists, list_count, &ok);
+        if (blockIdx.x == 0 && threadIdx.x == 0) {
+            hdr->tau = tau_bits;   // for the report of the output kernel
+            // (cannot happen with valid posteriors and a budget that fits)
+            if (!ok) report(dev_status, sh.done == 2 ? HORA_ERR_INFEASIBLE : HORA_ERR_RANGE);
+        }
+        __syncthreads();   // sh is reused below
+    }
     const long long base = (long long)blockIdx.x * chunk;
     const long long end = base + chunk < n ? base + chunk : n;
     const bool d_vec = (reinterpret_cast<uintptr_t>(delta) & 15) == 0;
@@ -857,20 +911,18 @@ static int run_bisect(const Src& src, const CommonArgs& a, const Plan& p, const 
     if (a.budget > 0) {
         hipLaunchKernelGGL((k_bisect_coarse<Src>), dim3(p.nb), dim3(kBig), 0, a.stream, src, n, (long long)a.budget,
                            limit, p.chunk, w.coarse, a.dev_status);
-        hipLaunchKernelGGL(k_bisect_coarse_reduce, dim3(1), dim3(kBig), 0, a.stream, tiles, (long long)a.budget,
-                           (const CoarseSlot*)w.coarse, w.header);
-        for (int pass = 0; pass < 2; ++pass) {
-            hipLaunchKernelGGL((k_bisect_pass<Src>), dim3(p.nb), dim3(kBig), 0, a.stream, src, n,
-                               (long long)a.budget, limit, p.chunk, pass, w.header, w.bins, w.lists, w.list_count);
-            hipLaunchKernelGGL(k_bisect_reduce, dim3(kBins / kReduceBins), dim3(kThreads), 0, a.stream, p.nb, pass,
-                               w.header, w.bins, (const int*)w.list_count);
-        }
-        hipLaunchKernelGGL((k_bisect_final<Src>), dim3(1), dim3(kBig), 0, a.stream, src, n, (long long)a.budget,
-                           limit, p.nb, 2, w.header, (const SelectBins*)w.bins,
-                           (const unsigned long long*)w.lists, (const int*)w.list_count, a.dev_status);
+        hipLaunchKernelGGL((k_bisect_pass<Src, 0>), dim3(p.nb), dim3(kBig), 0, a.stream, src, n, (long long)a.budget,
+                           limit, p.chunk, tiles, (const CoarseSlot*)w.coarse, w.header, w.bins, w.lists,
+                           w.list_count);
+        hipLaunchKernelGGL(k_bisect_reduce, dim3(kBins / kReduceBins), dim3(kThreads), 0, a.stream, p.nb, 0,
+                           w.header, w.bins, (const int*)w.list_count);
+        hipLaunchKernelGGL((k_bisect_pass<Src, 1>), dim3(p.nb), dim3(kBig), 0, a.stream, src, n, (long long)a.budget,
+                           limit, p.chunk, tiles, (const CoarseSlot*)w.coarse, w.header, w.bins, w.lists,
+                           w.list_count);
     }
     hipLaunchKernelGGL((k_bisect_finalize<Src>), dim3(p.nb), dim3(kBig), 0, a.stream, src, n, p.chunk,
-                       (long long)a.budget, limit, depth_capped, (const AllocHeader*)w.header, a.delta, a.util,
+                       (long long)a.budget, limit, depth_capped, p.nb, w.header,
+                       (const unsigned long long*)w.lists, (const int*)w.list_count, a.delta, a.util,
                        w.block_ksum, w.block_tied, a.dev_status);
     const int mode = a.group_off ? (a.off_t == HORA_I32 ? 1 : 2) : 0;
 #define HORA_LAUNCH_BISECT_WRITE(M)                                                                       \
