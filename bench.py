@@ -105,12 +105,32 @@ def other_paths(torch, hora, wl, sess, a1, c1, w1, delta1, util1, goff1, ws, rep
         return per_launch_events(torch, fn, reps, 2)[0] * 1e6
 
     out = {}
-    # per-prompt posteriors (threshold search by bisection passes) on the large-allocation inputs
+    # per-prompt posteriors (threshold search) on the large-allocation inputs
     alpha = torch.from_numpy(1.0 + a1.c.astype(np.float64)).to("cuda:0")
     beta = torch.from_numpy(1.0 + w1.g0 - a1.c.astype(np.float64)).to("cuda:0")
     us = mean_us(lambda: hora.hora_allocate_posterior(alpha, beta, w1.g0, w1.budget, delta1, sess.dev_status, ws,
                                                       util=util1, group_off=goff1))
     out["allocate_posterior_large_alloc"] = {"us_per_call": us, "prompts_per_s": w1.n / us * 1e6}
+    # learned-prior posteriors (App. D: s in [0.25, 16], p in (0, 1), c ~ Binomial(8, p)), all distinct
+    rng_p = np.random.Generator(np.random.PCG64(13))
+    s_ = rng_p.uniform(0.25, 16.0, w1.n)
+    p_ = rng_p.uniform(0.02, 0.98, w1.n)
+    c_ = rng_p.binomial(8, p_)
+    alpha_l = torch.from_numpy(s_ * p_ + c_).to("cuda:0")
+    beta_l = torch.from_numpy(s_ * (1 - p_) + 8 - c_).to("cuda:0")
+    us = mean_us(lambda: hora.hora_allocate_posterior(alpha_l, beta_l, 8, 8 * w1.n, delta1, sess.dev_status, ws,
+                                                      util=util1, group_off=goff1))
+    assert int(delta1.sum()) == 8 * w1.n
+    out["allocate_posterior_learned_prior_2^20"] = {"budget": 8 * w1.n, "us_per_call": us,
+                                                    "prompts_per_s": w1.n / us * 1e6}
+    # a deep budget: 200 additional rollouts per prompt on average, 2^18 prompts
+    n_deep = 1 << 18
+    us = mean_us(lambda: hora.hora_allocate_posterior(alpha[:n_deep], beta[:n_deep], w1.g0, 200 * n_deep,
+                                                      delta1[:n_deep], sess.dev_status, ws, util=util1[:n_deep],
+                                                      group_off=goff1[:n_deep + 1]))
+    out["allocate_posterior_deep_budget_2^18"] = {"budget": 200 * n_deep, "max_delta": int(delta1[:n_deep].max()),
+                                                  "us_per_call": us, "prompts_per_s": n_deep / us * 1e6}
+    del alpha_l, beta_l
     # sharded Phase B: the paper's own step (4 shards of 15 prompts) and the same shard shape at scale
     for w, n_shards in ((wl.PAPER_STEP, wl.PAPER_STEP_SHARDS), (wl.SHARDED_LARGE, wl.SHARDED_LARGE_SHARDS)):
         a = wl.phase_a(w)
@@ -160,6 +180,29 @@ def other_paths(torch, hora, wl, sess, a1, c1, w1, delta1, util1, goff1, ws, rep
     out["pass_at_k_500_problems_256_samples_7_ks"] = {"us_per_call": us}
     assert sess.status() == 0
     return out
+
+
+def allocation_sweep(torch, hora, sess, reps):
+    """hora_allocate (delta, utility, int32 offsets) at growing batch sizes, next to a plain stream of the
+    same shape: one elementwise kernel that reads 4 bytes and writes 16 per element (torch's int32 ->
+    complex128 copy)."""
+    rows = []
+    rng = np.random.Generator(np.random.PCG64(17))
+    for lg in (20, 22, 24, 26):
+        n = 1 << lg
+        c = torch.from_numpy(rng.binomial(4, rng.beta(0.5, 0.5, n)).astype(np.int32)).to("cuda:0")
+        delta = torch.empty(n, dtype=torch.int32, device="cuda:0")
+        util = torch.empty(n, dtype=torch.float64, device="cuda:0")
+        goff = torch.empty(n + 1, dtype=torch.int32, device="cuda:0")
+        plain = torch.empty(n, dtype=torch.complex128, device="cuda:0")
+        ws = sess.workspace(n, 4)
+        t = per_launch_events(torch, lambda: hora.hora_allocate(c, 4, 4 * n, delta, sess.dev_status, ws, util=util,
+                                                                group_off=goff), reps, 3)[0]
+        tp = per_launch_events(torch, lambda: plain.copy_(c), reps, 3)[0]
+        rows.append({"n": n, "us_per_call": t * 1e6, "GBps": 20 * n / t / 1e9, "plain_stream_us": tp * 1e6,
+                     "plain_stream_GBps": 20 * n / tp / 1e9, "frac_of_plain_stream": tp / t})
+        del c, delta, util, goff, plain
+    return rows
 
 
 def main():
@@ -218,17 +261,32 @@ def main():
     tok_rloo = torch.empty(n_tok, dtype=torch.float32, device="cuda:0")
     tok_grpo = torch.empty(n_tok, dtype=torch.float32, device="cuda:0")
     bws = sess.broadcast_workspace(n_tok, torch.float32)
+    bws2 = torch.empty(hora.hora_token_broadcast2_workspace_bytes(n_tok, torch.float32), dtype=torch.uint8,
+                       device="cuda:0")
 
-    def step_path():
+    def step_path():            # both estimators' token streams written in one pass over the offsets
+        hora.hora_allocate(c2, w2.g0, w2.budget, delta2, sess.dev_status, ws, group_off=goff2)
+        hora.hora_group_advantage(goff2, reward2, adv_rloo, hora.ADV_RLOO, sess.dev_status)
+        hora.hora_group_advantage(goff2, reward2, adv_grpo, hora.ADV_GRPO, sess.dev_status, eps=w2.eps)
+        hora.hora_token_broadcast2(adv_rloo, adv_grpo, tok_off2, tok_rloo, tok_grpo, n_tok, sess.dev_status, bws2)
+
+    def step_path_two_calls():  # the same with one broadcast per estimator
         hora.hora_allocate(c2, w2.g0, w2.budget, delta2, sess.dev_status, ws, group_off=goff2)
         hora.hora_group_advantage(goff2, reward2, adv_rloo, hora.ADV_RLOO, sess.dev_status)
         hora.hora_group_advantage(goff2, reward2, adv_grpo, hora.ADV_GRPO, sess.dev_status, eps=w2.eps)
         hora.hora_token_broadcast(adv_rloo, tok_off2, tok_rloo, n_tok, sess.dev_status, bws)
         hora.hora_token_broadcast(adv_grpo, tok_off2, tok_grpo, n_tok, sess.dev_status, bws)
 
-    wall2, ev2 = timed(torch, step_path, max(steps // 4, 10), max(warmup // 4, 3))
     steps2 = max(steps // 4, 10)
+    wall2, ev2 = timed(torch, step_path, steps2, max(warmup // 4, 3))
+    wall2b, _ = timed(torch, step_path_two_calls, steps2, max(warmup // 4, 3))
     assert sess.status() == 0
+
+    def dual_broadcast():
+        hora.hora_token_broadcast2(adv_rloo, adv_grpo, tok_off2, tok_rloo, tok_grpo, n_tok, sess.dev_status, bws2)
+
+    dual_mean, dual_min = per_launch_events(torch, dual_broadcast, steps2, 3)
+    dual_bytes = 8 * n_tok + n_resp * (8 + 4 + 4)    # two float streams out; offsets and two advantages in
 
     def one_broadcast():
         hora.hora_token_broadcast(adv_rloo, tok_off2, tok_rloo, n_tok, sess.dev_status, bws)
@@ -243,6 +301,14 @@ def main():
     bcast_bytes = 4 * n_tok + n_resp * (8 + 4)       # float stores; offsets and advantages in
     bcast_gbs = bcast_bytes / bc_mean / 1e9
 
+    # what a plain stream of the allocation's shape reaches in the same run: one elementwise kernel that
+    # reads 4 bytes and writes 16 per prompt (torch's int32 -> complex128 copy)
+    plain1 = torch.empty(w1.n, dtype=torch.complex128, device="cuda:0")
+    plain_mean, _ = per_launch_events(torch, lambda: plain1.copy_(c1), steps, 3)
+    alloc_mean, alloc_min = per_launch_events(torch, step_alloc, steps, 3)
+    del plain1
+    sweep = allocation_sweep(torch, hora, sess, max(steps // 10, 5))
+    ws = sess.workspace(w1.n, w1.g0)
     extras = other_paths(torch, hora, wl, sess, a1, c1, w1, delta1, util1, goff1, ws, max(steps // 10, 5))
 
     result = {
@@ -274,8 +340,17 @@ def main():
             "kernel_ms_mean": bc_mean * 1e3,
             "kernel_ms_min": bc_min * 1e3,
             "whole_path_ms_per_step": wall2 / steps2 * 1e3,
-            "whole_path": "allocate + RLOO and GRPO group advantages + two token broadcasts",
+            "whole_path": "allocate + RLOO and GRPO group advantages + one two-stream token broadcast",
             "tokens_per_s_whole_path": 2 * n_tok / (wall2 / steps2),
+            "whole_path_two_broadcast_calls_ms_per_step": wall2b / steps2 * 1e3,
+            "two_stream": {
+                "kernel_ms_mean": dual_mean * 1e3,
+                "kernel_ms_min": dual_min * 1e3,
+                "bytes_per_launch": dual_bytes,
+                "GBps": dual_bytes / dual_mean / 1e9,
+                "pct_of_hbm_peak": 100.0 * dual_bytes / dual_mean / 1e9 / HBM_PEAK_GBS,
+                "pct_of_plain_fill": 100.0 * dual_bytes / dual_mean / 1e9 / fill_gbs,
+            },
         },
         "roofline": {
             "kernel": "k_row_desc + k_token_fill<float,float,int64> (large_bcast)",
@@ -296,6 +371,14 @@ def main():
             "frac": alloc_bytes / (ev1 / steps) / 1e9 / HBM_PEAK_GBS,
             "traffic": TRAFFIC_ALLOCATE_BYTES,
             "bytes_per_launch": alloc_bytes,
+            "call_ms_mean": alloc_mean * 1e3,
+            "call_ms_min": alloc_min * 1e3,
+            "achievable": alloc_bytes / plain_mean / 1e9,
+            "achievable_kind": "plain stream of the same shape in the same run: one kernel, 4 B read and 16 B "
+                               "written per prompt (torch int32 -> complex128 copy)",
+            "achievable_ms": plain_mean * 1e3,
+            "frac_of_achievable": plain_mean / alloc_mean,
+            "sweep": sweep,
         },
     }
     result["other_paths"] = extras

@@ -325,6 +325,28 @@ int hora_token_broadcast(int64_t n_resp, const void *adv, int32_t adv_t, const v
                          int32_t *dev_status, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Two per-token streams over the same packed offsets in one pass (Sec. 3.1 objective and
+ * Sec. 3.2 "Training objective with variable-size groups": besides its advantage, every token
+ * carries a loss weight that is constant over the response, e.g. the 1/(G_i |o_j|) of
+ * hora_response_weights; or the advantages of two estimators, GRPO and RLOO, side by side):
+ *   tok_a[t] = adv_a[j],  tok_b[t] = adv_b[j]   for tok_off[j] <= t < tok_off[j+1].
+ * Results equal two calls of hora_token_broadcast; the offsets are checked and the row
+ * descriptors are built once for both outputs, in one launch pair instead of two.
+ *
+ * adv_a, adv_b : device, n_resp values of type adv_t each.
+ * tok_a, tok_b : device out, n_tokens values of type out_t each; both must have the same
+ *                address modulo 16 (else HORA_ERR_INVALID_ARG: they share one row grid).
+ * workspace    : device, >= hora_token_broadcast2_workspace_bytes(n_tokens, out_t), which is
+ *                twice what the one-stream call needs.
+ * The other arguments and the errors are those of hora_token_broadcast.
+ */
+size_t hora_token_broadcast2_workspace_bytes(int64_t n_tokens, int32_t out_t);
+int hora_token_broadcast2(int64_t n_resp, const void *adv_a, const void *adv_b, int32_t adv_t,
+                          const void *tok_off, int32_t off_t, void *tok_a, void *tok_b, int32_t out_t,
+                          int64_t n_tokens, int32_t *dev_status, void *workspace, size_t workspace_bytes,
+                          void *stream);
+
+/*
  * Bytes of workspace hora_pass_at_k needs (device memory, 8-byte aligned, no
  * initialisation needed).  n_k <= 64.
  */

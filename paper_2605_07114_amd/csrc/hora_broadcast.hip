@@ -58,33 +58,37 @@ template <typename O> struct RowOf {
 };
 static_assert(RowOf<float>::kRowElems < (1 << 15), "an end and the flag share 16 bits");
 
-// Row descriptor with E ends, an array of 32-bit words (little endian):
+// Row descriptor with E ends for S value streams, an array of 32-bit words (little endian):
 //   words [0, E/2)              ends[k], 16 bits each: end of the k-th response that
 //                               intersects the row, as an element index relative to the
 //                               row, clamped to [0, row length]; unused entries hold the
 //                               row length
-//   then E+1 values of type O   vals[k]: advantage of that response
+//   then (E+1)*S values of type O   vals[k*S + s]: value of stream s for that response
 //   wide descriptors (E = kEnds) then hold one word `first`: index of the response that
 //   holds the row's first token, bit 31 set when more than E+1 responses intersect the
 //   row; short ones (E = kShortEnds) carry their flag in bit 31 of word 0 instead (the
 //   top bit of ends[1], which needs 12 of its 16 bits).
-// Padded to a power of two: short 32 / 64 bytes, wide 64 / 128 bytes (float / double).
-template <typename O, int E> struct DescLayout {
+// Padded to a power of two.  One stream: short 32 / 64 bytes, wide 64 / 128 bytes (float /
+// double); two streams: short 64 / 128, wide 128 / 256.
+template <typename O, int E, int S> struct DescLayout {
     static constexpr bool kWide = E == kEnds;
     static constexpr int kValWords = (int)(sizeof(O) / 4);
     static constexpr int kEndWords = E / 2;
     static constexpr int kValBase = kValWords == 2 ? (kEndWords + 1) / 2 * 2 : kEndWords;   // doubles on even words
-    static constexpr int kFirstWord = kValBase + (E + 1) * kValWords;
+    static constexpr int kFirstWord = kValBase + (E + 1) * S * kValWords;
     static constexpr int kUsed = kFirstWord + (kWide ? 1 : 0);
     static constexpr int kWords = kUsed <= 4 ? 4 : kUsed <= 8 ? 8 : kUsed <= 16 ? 16 : kUsed <= 32 ? 32 : 64;
     static constexpr int kBytes = kWords * 4;
 };
 static_assert(kEnds % 2 == 0 && kShortEnds % 2 == 0 && kShortEnds < kEnds, "two ends per word");
-static_assert(DescLayout<float, kShortEnds>::kBytes == 32 && DescLayout<double, kShortEnds>::kBytes == 64, "short");
-static_assert(DescLayout<float, kEnds>::kBytes == 64 && DescLayout<double, kEnds>::kBytes == 128, "wide");
-template <typename O, int E> struct alignas(DescLayout<O, E>::kBytes) Desc { unsigned u[DescLayout<O, E>::kWords]; };
-template <typename O> using WideDesc = Desc<O, kEnds>;
-template <typename O> using ShortDesc = Desc<O, kShortEnds>;
+static_assert(DescLayout<float, kShortEnds, 1>::kBytes == 32 && DescLayout<double, kShortEnds, 1>::kBytes == 64, "short");
+static_assert(DescLayout<float, kEnds, 1>::kBytes == 64 && DescLayout<double, kEnds, 1>::kBytes == 128, "wide");
+static_assert(DescLayout<float, kShortEnds, 2>::kBytes == 64 && DescLayout<double, kShortEnds, 2>::kBytes == 128, "short, two streams");
+static_assert(DescLayout<float, kEnds, 2>::kBytes == 128 && DescLayout<double, kEnds, 2>::kBytes == 256, "wide, two streams");
+static_assert(DescLayout<double, kEnds, 2>::kUsed <= 64, "the widest descriptor fits");
+template <typename O, int E, int S> struct alignas(DescLayout<O, E, S>::kBytes) Desc { unsigned u[DescLayout<O, E, S>::kWords]; };
+template <typename O, int S> using WideDesc = Desc<O, kEnds, S>;
+template <typename O, int S> using ShortDesc = Desc<O, kShortEnds, S>;
 
 __device__ __forceinline__ unsigned val_word(float v, int) { return __float_as_uint(v); }
 __device__ __forceinline__ unsigned val_word(double v, int half) {
@@ -92,53 +96,55 @@ __device__ __forceinline__ unsigned val_word(double v, int half) {
 }
 
 // One descriptor, fetched with 16-byte loads (scalar loads when the address is uniform).
-template <typename O, int E>
-__device__ __forceinline__ Desc<O, E> load_desc(const Desc<O, E>* __restrict__ src) {
-    Desc<O, E> x;
+template <typename O, int E, int S>
+__device__ __forceinline__ Desc<O, E, S> load_desc(const Desc<O, E, S>* __restrict__ src) {
+    Desc<O, E, S> x;
     const v4u* q = reinterpret_cast<const v4u*>(src);
 #pragma unroll
-    for (int i = 0; i < DescLayout<O, E>::kWords / 4; ++i) {
+    for (int i = 0; i < DescLayout<O, E, S>::kWords / 4; ++i) {
         const v4u w = q[i];
         x.u[4 * i] = w.x; x.u[4 * i + 1] = w.y; x.u[4 * i + 2] = w.z; x.u[4 * i + 3] = w.w;
     }
     return x;
 }
-template <typename O, int E>
-__device__ __forceinline__ void store_desc(Desc<O, E>* __restrict__ dst, const Desc<O, E>& d) {
+template <typename O, int E, int S>
+__device__ __forceinline__ void store_desc(Desc<O, E, S>* __restrict__ dst, const Desc<O, E, S>& d) {
     v4u* q = reinterpret_cast<v4u*>(dst);
 #pragma unroll
-    for (int i = 0; i < DescLayout<O, E>::kWords / 4; ++i) {
+    for (int i = 0; i < DescLayout<O, E, S>::kWords / 4; ++i) {
         const v4u w = {d.u[4 * i], d.u[4 * i + 1], d.u[4 * i + 2], d.u[4 * i + 3]};
         q[i] = w;
     }
 }
-template <typename O, int E>
-__device__ __forceinline__ int desc_end(const Desc<O, E>& x, int k) {
+template <typename O, int E, int S>
+__device__ __forceinline__ int desc_end(const Desc<O, E, S>& x, int k) {
     const unsigned pair = x.u[k >> 1];
     return (int)((k & 1) ? (pair >> 16) & 0x7fffu : pair & 0xffffu);
 }
-template <int E>
-__device__ __forceinline__ float desc_val(const Desc<float, E>& x, int k) {
-    return __uint_as_float(x.u[DescLayout<float, E>::kValBase + k]);
+// value of stream st for the k-th response of the descriptor
+template <int E, int S>
+__device__ __forceinline__ float desc_val(const Desc<float, E, S>& x, int k, int st) {
+    return __uint_as_float(x.u[DescLayout<float, E, S>::kValBase + k * S + st]);
 }
-template <int E>
-__device__ __forceinline__ double desc_val(const Desc<double, E>& x, int k) {
-    return __hiloint2double((int)x.u[DescLayout<double, E>::kValBase + 2 * k + 1],
-                            (int)x.u[DescLayout<double, E>::kValBase + 2 * k]);
+template <int E, int S>
+__device__ __forceinline__ double desc_val(const Desc<double, E, S>& x, int k, int st) {
+    return __hiloint2double((int)x.u[DescLayout<double, E, S>::kValBase + 2 * (k * S + st) + 1],
+                            (int)x.u[DescLayout<double, E, S>::kValBase + 2 * (k * S + st)]);
 }
-template <typename O>
-__device__ __forceinline__ unsigned desc_first(const WideDesc<O>& x) { return x.u[DescLayout<O, kEnds>::kFirstWord]; }
-template <typename O>
-__device__ __forceinline__ bool desc_flagged(const ShortDesc<O>& x) { return (x.u[0] & kOverflowBit) != 0; }
+template <typename O, int S>
+__device__ __forceinline__ unsigned desc_first(const WideDesc<O, S>& x) { return x.u[DescLayout<O, kEnds, S>::kFirstWord]; }
+template <typename O, int S>
+__device__ __forceinline__ bool desc_flagged(const ShortDesc<O, S>& x) { return (x.u[0] & kOverflowBit) != 0; }
 
 // Fills the ends and values of a descriptor from the ends e[] (tokens, clamped) and the
-// advantages v[] of consecutive responses, for the row whose element 0 is token row_first.
-template <typename O, int E, int N>
-__device__ __forceinline__ void set_desc(Desc<O, E>& d, const long long (&e)[N], const O (&v)[N], long long row_first) {
+// values v[][stream] of consecutive responses, for the row whose element 0 is token row_first.
+template <typename O, int E, int S, int N>
+__device__ __forceinline__ void set_desc(Desc<O, E, S>& d, const long long (&e)[N], const O (&v)[N][S], long long row_first) {
     static_assert(N >= E + 1, "enough responses loaded");
     constexpr int kRowElems = RowOf<O>::kRowElems;
+    typedef DescLayout<O, E, S> L;
 #pragma unroll
-    for (int i = 0; i < DescLayout<O, E>::kWords; ++i) d.u[i] = 0u;
+    for (int i = 0; i < L::kWords; ++i) d.u[i] = 0u;
 #pragma unroll
     for (int k = 0; k < E; ++k) {
         long long rel = e[k] - row_first;
@@ -148,8 +154,10 @@ __device__ __forceinline__ void set_desc(Desc<O, E>& d, const long long (&e)[N],
 #pragma unroll
     for (int k = 0; k < E + 1; ++k)
 #pragma unroll
-        for (int h = 0; h < DescLayout<O, E>::kValWords; ++h)
-            d.u[DescLayout<O, E>::kValBase + k * DescLayout<O, E>::kValWords + h] = val_word(v[k], h);
+        for (int st = 0; st < S; ++st)
+#pragma unroll
+            for (int h = 0; h < L::kValWords; ++h)
+                d.u[L::kValBase + (k * S + st) * L::kValWords + h] = val_word(v[k][st], h);
 }
 
 // Where the short descriptor of row r (written by workgroup r) is kept: inside every
@@ -169,26 +177,32 @@ __host__ __device__ __forceinline__ long long short_slots(long long n_rows) {
 // index space q = token + skew.  The response that holds a row's first token writes the
 // row's descriptors.  Also the data checks: offsets start at 0, do not decrease, and end
 // at n_tokens.  Offsets are clamped to [0, n_tokens] before use, so that bad data cannot
-// move any access outside the buffers.
+// move any access outside the buffers.  With two streams (S = 2) the descriptors carry the
+// values of both per-response arrays, so that pass 2 fetches one descriptor per row for both
+// outputs.
 // ----------------------------------------------------------------------------------
-template <typename A, typename O, typename I>
-__global__ __launch_bounds__(kThreads) void k_row_desc(long long n_resp, const A* __restrict__ adv,
+template <typename A, int S> struct Streams { const A* p[S]; };
+template <typename O, int S> struct Outputs { O* p[S]; };
+
+template <typename A, typename O, typename I, int S>
+__global__ __launch_bounds__(kThreads) void k_row_desc(long long n_resp, Streams<A, S> adv,
                                                        const I* __restrict__ tok_off, long long n_tokens, int skew,
-                                                       long long n_rows, ShortDesc<O>* __restrict__ short_desc,
-                                                       WideDesc<O>* __restrict__ wide_desc, int32_t* dev_status) {
+                                                       long long n_rows, ShortDesc<O, S>* __restrict__ short_desc,
+                                                       WideDesc<O, S>* __restrict__ wide_desc, int32_t* dev_status) {
     constexpr int kRowElems = RowOf<O>::kRowElems;
     const long long stride = (long long)gridDim.x * kThreads;
     bool bad = false;
     for (long long j = (long long)blockIdx.x * kThreads + threadIdx.x; j < n_resp; j += stride) {
         // the loads a short descriptor needs up front (one round trip): the start of the
-        // response, the ends of the kShortVals responses from it on, and their advantages
+        // response, the ends of the kShortVals responses from it on, and their values
         long long a = (long long)tok_off[j];
         long long e[kVals];
-        O v[kVals];
+        O v[kVals][S];
 #pragma unroll
         for (int k = 0; k < kShortVals; ++k) {
             e[k] = j + k < n_resp ? (long long)tok_off[j + 1 + k] : n_tokens;
-            v[k] = j + k < n_resp ? (O)adv[j + k] : (O)0;
+#pragma unroll
+            for (int st = 0; st < S; ++st) v[k][st] = j + k < n_resp ? (O)adv.p[st][j + k] : (O)0;
         }
         long long b = e[0];
         bad |= b < a || a < 0 || b > n_tokens;
@@ -208,24 +222,25 @@ __global__ __launch_bounds__(kThreads) void k_row_desc(long long n_resp, const A
             long long row_end = row_first + kRowElems;
             if (row_end > n_tokens) row_end = n_tokens;
             const bool wide = e[kShortVals - 1] < row_end;      // more than kShortVals responses
-            ShortDesc<O> d;
-            set_desc<O, kShortEnds, kVals>(d, e, v, row_first);
+            ShortDesc<O, S> d;
+            set_desc<O, kShortEnds, S, kVals>(d, e, v, row_first);
             if (wide) d.u[0] |= kOverflowBit;
-            store_desc<O, kShortEnds>(short_desc + short_slot(r), d);
+            store_desc<O, kShortEnds, S>(short_desc + short_slot(r), d);
             if (wide) {
                 if (!have_rest) {   // a second round of loads, for the few rows that need it
 #pragma unroll
                     for (int k = kShortVals; k < kVals; ++k) {
                         long long x = j + k < n_resp ? (long long)tok_off[j + 1 + k] : n_tokens;
                         e[k] = x < 0 ? 0 : (x > n_tokens ? n_tokens : x);
-                        v[k] = j + k < n_resp ? (O)adv[j + k] : (O)0;
+#pragma unroll
+                        for (int st = 0; st < S; ++st) v[k][st] = j + k < n_resp ? (O)adv.p[st][j + k] : (O)0;
                     }
                     have_rest = true;
                 }
-                WideDesc<O> x;
-                set_desc<O, kEnds, kVals>(x, e, v, row_first);
-                x.u[DescLayout<O, kEnds>::kFirstWord] = (unsigned)j | (e[kVals - 1] < row_end ? kOverflowBit : 0u);
-                store_desc<O, kEnds>(wide_desc + r, x);
+                WideDesc<O, S> x;
+                set_desc<O, kEnds, S, kVals>(x, e, v, row_first);
+                x.u[DescLayout<O, kEnds, S>::kFirstWord] = (unsigned)j | (e[kVals - 1] < row_end ? kOverflowBit : 0u);
+                store_desc<O, kEnds, S>(wide_desc + r, x);
             }
         }
     }
@@ -275,19 +290,20 @@ __device__ __forceinline__ void store_lane(O* __restrict__ out, long long row, l
     }
 }
 
-template <typename O, int E>
-__device__ __forceinline__ void fill_row(const Desc<O, E>& d, O* __restrict__ out, long long row, long long n_rows,
-                                         long long n_tokens, int skew) {
+// One wavefront's part of a row for stream kSt (row_thread: the thread's index within the row).
+template <typename O, int E, int S, int kSt>
+__device__ __forceinline__ void fill_row(const Desc<O, E, S>& d, O* __restrict__ out, long long row, long long n_rows,
+                                         long long n_tokens, int skew, int row_thread) {
     constexpr int kLaneElems = RowOf<O>::kLaneElems;
     constexpr int kWaveElems = RowOf<O>::kWaveElems;
     const long long row_first = row * RowOf<O>::kRowElems - skew;
-    const int r0 = (int)threadIdx.x * kLaneElems;
+    const int r0 = row_thread * kLaneElems;
     int e[E];
     O v[E + 1];
 #pragma unroll
     for (int k = 0; k < E; ++k) e[k] = desc_end(d, k);
 #pragma unroll
-    for (int k = 0; k < E + 1; ++k) v[k] = desc_val(d, k);
+    for (int k = 0; k < E + 1; ++k) v[k] = desc_val(d, k, kSt);
     // the wavefront's elements [w0, w1) of the row: when the first and the last of them
     // belong to the same response, all of them do
     const int w0 = __builtin_amdgcn_readfirstlane(r0) & ~(kWaveElems - 1);
@@ -324,10 +340,10 @@ __device__ __forceinline__ void fill_row(const Desc<O, E>& d, O* __restrict__ ou
 template <typename A, typename O, typename I>
 __device__ __forceinline__ void fill_row_by_search(unsigned first, long long n_resp, const A* __restrict__ adv,
                                                    const I* __restrict__ tok_off, O* __restrict__ out, long long row,
-                                                   long long n_rows, long long n_tokens, int skew) {
+                                                   long long n_rows, long long n_tokens, int skew, int row_thread) {
     constexpr int kLaneElems = RowOf<O>::kLaneElems;
     const long long row_first = row * RowOf<O>::kRowElems - skew;
-    const int r0 = (int)threadIdx.x * kLaneElems;
+    const int r0 = row_thread * kLaneElems;
     const long long last = n_resp - 1;
     long long a = (long long)(first & ~kOverflowBit);
     a = a > last ? last : a;
@@ -347,33 +363,59 @@ __device__ __forceinline__ void fill_row_by_search(unsigned first, long long n_r
 }
 
 // A row whose short descriptor is flagged: through its wide descriptor, or by the search.
-template <typename A, typename O, typename I>
-__device__ __forceinline__ void fill_flagged_row(const WideDesc<O>* __restrict__ wide_desc, long long n_resp,
-                                              const A* __restrict__ adv, const I* __restrict__ tok_off,
-                                              O* __restrict__ out, long long row, long long n_rows,
-                                              long long n_tokens, int skew) {
-    const WideDesc<O> x = load_desc<O, kEnds>(wide_desc + row);
+template <typename A, typename O, typename I, int S, int kSt>
+__device__ __forceinline__ void fill_flagged_row(const WideDesc<O, S>* __restrict__ wide_desc, long long n_resp,
+                                                 const A* __restrict__ adv, const I* __restrict__ tok_off,
+                                                 O* __restrict__ out, long long row, long long n_rows,
+                                                 long long n_tokens, int skew, int row_thread) {
+    const WideDesc<O, S> x = load_desc<O, kEnds, S>(wide_desc + row);
     const unsigned first = desc_first(x);
-    if (first & kOverflowBit) fill_row_by_search<A, O, I>(first, n_resp, adv, tok_off, out, row, n_rows, n_tokens, skew);
-    else fill_row<O, kEnds>(x, out, row, n_rows, n_tokens, skew);
+    if (first & kOverflowBit)
+        fill_row_by_search<A, O, I>(first, n_resp, adv, tok_off, out, row, n_rows, n_tokens, skew, row_thread);
+    else fill_row<O, kEnds, S, kSt>(x, out, row, n_rows, n_tokens, skew, row_thread);
 }
 
+template <typename A, typename O, typename I, int S, int kSt>
+__device__ __forceinline__ void fill_stream(const ShortDesc<O, S>& d, const WideDesc<O, S>* __restrict__ wide_desc,
+                                            long long n_resp, const A* __restrict__ adv,
+                                            const I* __restrict__ tok_off, O* __restrict__ out, long long row,
+                                            long long n_rows, long long n_tokens, int skew, int row_thread) {
+    if (!desc_flagged(d)) fill_row<O, kShortEnds, S, kSt>(d, out, row, n_rows, n_tokens, skew, row_thread);
+    else fill_flagged_row<A, O, I, S, kSt>(wide_desc, n_resp, adv, tok_off, out, row, n_rows, n_tokens, skew, row_thread);
+}
+
+// One workgroup per row and stream.  With two streams the grid holds all rows of the first
+// stream, then all rows of the second: measured on large_bcast, workgroups that write both
+// streams of a row (64 bytes per lane, or 32 bytes per lane from twice as many threads) reach
+// 5.5 - 5.7 TB/s because the memory then sees two interleaved write streams, against 6.4 TB/s
+// for one stream after the other; what the two-stream call saves is the second pass 1 and the
+// second launch, not the descriptor fetch.
 // (eight wavefronts per SIMD: the bytes in flight per compute unit are what hides the
 // latency of the stores, so the register count is held to what full occupancy allows)
-template <typename A, typename O, typename I>
+template <typename A, typename O, typename I, int S>
 __global__ __launch_bounds__(kBcastThreads) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_token_fill(
     // what every row needs comes first: the leading kernel arguments arrive in registers
-    const ShortDesc<O>* __restrict__ short_desc, O* __restrict__ out, long long n_tokens, long long n_rows, int skew,
-    const WideDesc<O>* __restrict__ wide_desc, long long n_resp, const A* __restrict__ adv,
+    const ShortDesc<O, S>* __restrict__ short_desc, Outputs<O, S> out, long long n_tokens, long long n_rows, int skew,
+    const WideDesc<O, S>* __restrict__ wide_desc, long long n_resp, Streams<A, S> adv,
     const I* __restrict__ tok_off) {
-    const long long row = blockIdx.x;   // the grid has n_rows workgroups
-    const ShortDesc<O> d = load_desc<O, kShortEnds>(short_desc + short_slot(row));
+    const bool second = S == 2 && (long long)blockIdx.x >= n_rows;   // the grid has S * n_rows workgroups
+    const long long row = (long long)blockIdx.x - (second ? n_rows : 0);
+    const ShortDesc<O, S> d = load_desc<O, kShortEnds, S>(short_desc + short_slot(row));
     // the whole descriptor in one round of loads: without this the part that the flag test
     // does not need is fetched after the branch, one more wait
 #pragma unroll
-    for (int i = 0; i < DescLayout<O, kShortEnds>::kWords; i += 4) asm volatile("" : : "s"(d.u[i]));
-    if (!desc_flagged(d)) fill_row<O, kShortEnds>(d, out, row, n_rows, n_tokens, skew);
-    else fill_flagged_row<A, O, I>(wide_desc, n_resp, adv, tok_off, out, row, n_rows, n_tokens, skew);
+    for (int i = 0; i < DescLayout<O, kShortEnds, S>::kWords; i += 4) asm volatile("" : : "s"(d.u[i]));
+    if constexpr (S == 1) {
+        fill_stream<A, O, I, 1, 0>(d, wide_desc, n_resp, adv.p[0], tok_off, out.p[0], row, n_rows, n_tokens, skew,
+                                   (int)threadIdx.x);
+    } else {
+        if (!second)
+            fill_stream<A, O, I, 2, 0>(d, wide_desc, n_resp, adv.p[0], tok_off, out.p[0], row, n_rows, n_tokens, skew,
+                                       (int)threadIdx.x);
+        else
+            fill_stream<A, O, I, 2, 1>(d, wide_desc, n_resp, adv.p[1], tok_off, out.p[1], row, n_rows, n_tokens, skew,
+                                       (int)threadIdx.x);
+    }
 }
 
 template <typename O>
@@ -383,51 +425,54 @@ static long long rows_for(int64_t n_tokens, int skew) {
 
 // Workspace: the short descriptors (whole blocks of rows), then the wide ones (one slot
 // per row), both 256-byte aligned.
-template <typename O>
+template <typename O, int S>
 static size_t short_area_bytes(long long n_rows) {
-    return ((size_t)short_slots(n_rows) * sizeof(ShortDesc<O>) + 255) & ~(size_t)255;
+    return ((size_t)short_slots(n_rows) * sizeof(ShortDesc<O, S>) + 255) & ~(size_t)255;
 }
-template <typename O>
+template <typename O, int S>
 static size_t workspace_for(long long n_rows) {
-    return short_area_bytes<O>(n_rows) + (((size_t)n_rows * sizeof(WideDesc<O>) + 255) & ~(size_t)255);
+    return short_area_bytes<O, S>(n_rows) + (((size_t)n_rows * sizeof(WideDesc<O, S>) + 255) & ~(size_t)255);
 }
 
-template <typename A, typename O, typename I>
-static int launch_broadcast(int64_t n_resp, const void* adv, const void* tok_off, void* out, int64_t n_tokens,
-                            int32_t* dev_status, void* workspace, size_t workspace_bytes, hipStream_t stream) {
-    const int skew = (int)((reinterpret_cast<uintptr_t>(out) & 15) / sizeof(O));
+template <typename A, typename O, typename I, int S>
+static int launch_broadcast(int64_t n_resp, const void* const* adv, const void* tok_off, void* const* out,
+                            int64_t n_tokens, int32_t* dev_status, void* workspace, size_t workspace_bytes,
+                            hipStream_t stream) {
+    const int skew = (int)((reinterpret_cast<uintptr_t>(out[0]) & 15) / sizeof(O));
     const long long n_rows = rows_for<O>(n_tokens, skew);
-    if (n_rows > INT_MAX) return HORA_ERR_UNSUPPORTED;
-    if (workspace_for<O>(n_rows) > workspace_bytes) return HORA_ERR_WORKSPACE;
-    ShortDesc<O>* short_desc = (ShortDesc<O>*)workspace;
-    WideDesc<O>* wide_desc = (WideDesc<O>*)((char*)workspace + short_area_bytes<O>(n_rows));
+    if (n_rows * S > INT_MAX) return HORA_ERR_UNSUPPORTED;
+    if (workspace_for<O, S>(n_rows) > workspace_bytes) return HORA_ERR_WORKSPACE;
+    ShortDesc<O, S>* short_desc = (ShortDesc<O, S>*)workspace;
+    WideDesc<O, S>* wide_desc = (WideDesc<O, S>*)((char*)workspace + short_area_bytes<O, S>(n_rows));
+    Streams<A, S> in;
+    Outputs<O, S> dst;
+    for (int st = 0; st < S; ++st) { in.p[st] = (const A*)adv[st]; dst.p[st] = (O*)out[st]; }
     long long blocks1 = (n_resp + kThreads - 1) / kThreads;
     if (blocks1 > 65536) blocks1 = 65536;
-    hipLaunchKernelGGL((k_row_desc<A, O, I>), dim3((unsigned)blocks1), dim3(kThreads), 0, stream,
-                       (long long)n_resp, (const A*)adv, (const I*)tok_off, (long long)n_tokens, skew, n_rows,
+    hipLaunchKernelGGL((k_row_desc<A, O, I, S>), dim3((unsigned)blocks1), dim3(kThreads), 0, stream,
+                       (long long)n_resp, in, (const I*)tok_off, (long long)n_tokens, skew, n_rows,
                        short_desc, wide_desc, dev_status);
     if (n_rows > 0)
-        hipLaunchKernelGGL((k_token_fill<A, O, I>), dim3((unsigned)n_rows), dim3(kBcastThreads), 0, stream,
-                           (const ShortDesc<O>*)short_desc, (O*)out, (long long)n_tokens, n_rows, skew,
-                           (const WideDesc<O>*)wide_desc, (long long)n_resp, (const A*)adv, (const I*)tok_off);
+        hipLaunchKernelGGL((k_token_fill<A, O, I, S>), dim3((unsigned)(n_rows * S)), dim3(kBcastThreads), 0, stream,
+                           (const ShortDesc<O, S>*)short_desc, dst, (long long)n_tokens, n_rows, skew,
+                           (const WideDesc<O, S>*)wide_desc, (long long)n_resp, in, (const I*)tok_off);
     return hipGetLastError() == hipSuccess ? HORA_OK : HORA_ERR_HIP;
 }
 
-}  // namespace hora
-
-using namespace hora;
-
-extern "C" size_t hora_token_broadcast_workspace_bytes(int64_t n_tokens, int32_t out_t) {
+template <int S>
+static size_t broadcast_workspace_bytes(int64_t n_tokens, int32_t out_t) {
     if (n_tokens < 0 || (out_t != HORA_F32 && out_t != HORA_F64)) return 0;
     // the largest skew a caller's pointer can have gives the most rows
-    const size_t bytes = out_t == HORA_F32 ? workspace_for<float>(rows_for<float>(n_tokens, 3))
-                                           : workspace_for<double>(rows_for<double>(n_tokens, 1));
+    const size_t bytes = out_t == HORA_F32 ? workspace_for<float, S>(rows_for<float>(n_tokens, 3))
+                                           : workspace_for<double, S>(rows_for<double>(n_tokens, 1));
     return bytes == 0 ? 256 : bytes;
 }
 
-extern "C" int hora_token_broadcast(int64_t n_resp, const void* adv, int32_t adv_t, const void* tok_off,
-                                    int32_t off_t, void* tok_adv, int32_t out_t, int64_t n_tokens,
-                                    int32_t* dev_status, void* workspace, size_t workspace_bytes, void* stream) {
+// Argument checks and dispatch shared by the one- and the two-stream entry point.
+template <int S>
+static int broadcast_entry(int64_t n_resp, const void* const* adv, int32_t adv_t, const void* tok_off, int32_t off_t,
+                           void* const* tok_adv, int32_t out_t, int64_t n_tokens, int32_t* dev_status,
+                           void* workspace, size_t workspace_bytes, hipStream_t s) {
     if (n_resp < 0 || n_tokens < 0 || !dev_status) return HORA_ERR_INVALID_ARG;
     if (adv_t != HORA_F32 && adv_t != HORA_F64) return HORA_ERR_INVALID_ARG;
     if (out_t != HORA_F32 && out_t != HORA_F64) return HORA_ERR_INVALID_ARG;
@@ -435,23 +480,59 @@ extern "C" int hora_token_broadcast(int64_t n_resp, const void* adv, int32_t adv
     if (adv_t == HORA_F32 && out_t == HORA_F64) return HORA_ERR_INVALID_ARG;  // never widen
     if (n_resp == 0) return n_tokens == 0 ? HORA_OK : HORA_ERR_INVALID_ARG;
     if (n_resp >= (1ll << 31)) return HORA_ERR_UNSUPPORTED;
-    if (!adv || !tok_off) return HORA_ERR_INVALID_ARG;
-    if (n_tokens > 0 && !tok_adv) return HORA_ERR_INVALID_ARG;
+    if (!tok_off) return HORA_ERR_INVALID_ARG;
     if (off_t == HORA_I32 && n_tokens >= (1ll << 31)) return HORA_ERR_INVALID_ARG;
     const uintptr_t amask = adv_t == HORA_F32 ? 3 : 7, omask = out_t == HORA_F32 ? 3 : 7,
                     imask = off_t == HORA_I32 ? 3 : 7;
-    if ((reinterpret_cast<uintptr_t>(adv) & amask) || (reinterpret_cast<uintptr_t>(tok_adv) & omask) ||
-        (reinterpret_cast<uintptr_t>(tok_off) & imask))
-        return HORA_ERR_INVALID_ARG;
+    for (int st = 0; st < S; ++st) {
+        if (!adv[st]) return HORA_ERR_INVALID_ARG;
+        if (n_tokens > 0 && !tok_adv[st]) return HORA_ERR_INVALID_ARG;
+        if ((reinterpret_cast<uintptr_t>(adv[st]) & amask) || (reinterpret_cast<uintptr_t>(tok_adv[st]) & omask))
+            return HORA_ERR_INVALID_ARG;
+        // the outputs share one row grid: their 16-byte misalignment must be the same
+        if ((reinterpret_cast<uintptr_t>(tok_adv[st]) & 15) != (reinterpret_cast<uintptr_t>(tok_adv[0]) & 15))
+            return HORA_ERR_INVALID_ARG;
+    }
+    if (reinterpret_cast<uintptr_t>(tok_off) & imask) return HORA_ERR_INVALID_ARG;
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255)) return HORA_ERR_WORKSPACE;
-    hipStream_t s = (hipStream_t)stream;
-#define HORA_BCAST(A, O)                                                                                      \
-    (off_t == HORA_I32 ? launch_broadcast<A, O, int32_t>(n_resp, adv, tok_off, tok_adv, n_tokens, dev_status, \
-                                                         workspace, workspace_bytes, s)                       \
-                       : launch_broadcast<A, O, long long>(n_resp, adv, tok_off, tok_adv, n_tokens,           \
-                                                           dev_status, workspace, workspace_bytes, s))
+#define HORA_BCAST(A, O)                                                                                       \
+    (off_t == HORA_I32 ? launch_broadcast<A, O, int32_t, S>(n_resp, adv, tok_off, tok_adv, n_tokens,           \
+                                                            dev_status, workspace, workspace_bytes, s)         \
+                       : launch_broadcast<A, O, long long, S>(n_resp, adv, tok_off, tok_adv, n_tokens,         \
+                                                              dev_status, workspace, workspace_bytes, s))
     if (adv_t == HORA_F32) return HORA_BCAST(float, float);
     if (out_t == HORA_F32) return HORA_BCAST(double, float);
     return HORA_BCAST(double, double);
 #undef HORA_BCAST
+}
+
+}  // namespace hora
+
+using namespace hora;
+
+extern "C" size_t hora_token_broadcast_workspace_bytes(int64_t n_tokens, int32_t out_t) {
+    return broadcast_workspace_bytes<1>(n_tokens, out_t);
+}
+
+extern "C" size_t hora_token_broadcast2_workspace_bytes(int64_t n_tokens, int32_t out_t) {
+    return broadcast_workspace_bytes<2>(n_tokens, out_t);
+}
+
+extern "C" int hora_token_broadcast(int64_t n_resp, const void* adv, int32_t adv_t, const void* tok_off,
+                                    int32_t off_t, void* tok_adv, int32_t out_t, int64_t n_tokens,
+                                    int32_t* dev_status, void* workspace, size_t workspace_bytes, void* stream) {
+    const void* in[1] = {adv};
+    void* out[1] = {tok_adv};
+    return broadcast_entry<1>(n_resp, in, adv_t, tok_off, off_t, out, out_t, n_tokens, dev_status, workspace,
+                              workspace_bytes, (hipStream_t)stream);
+}
+
+extern "C" int hora_token_broadcast2(int64_t n_resp, const void* adv_a, const void* adv_b, int32_t adv_t,
+                                     const void* tok_off, int32_t off_t, void* tok_a, void* tok_b, int32_t out_t,
+                                     int64_t n_tokens, int32_t* dev_status, void* workspace, size_t workspace_bytes,
+                                     void* stream) {
+    const void* in[2] = {adv_a, adv_b};
+    void* out[2] = {tok_a, tok_b};
+    return broadcast_entry<2>(n_resp, in, adv_t, tok_off, off_t, out, out_t, n_tokens, dev_status, workspace,
+                              workspace_bytes, (hipStream_t)stream);
 }

@@ -36,7 +36,7 @@ EXPORTS = (
     "hora_allocate", "hora_allocate_posterior", "hora_group_advantage", "hora_token_broadcast",
     "hora_token_broadcast_workspace_bytes", "hora_allocate_sharded", "hora_allocate_sharded_workspace_bytes",
     "hora_response_weights", "hora_allocate_baseline", "hora_pass_at_k", "hora_pass_at_k_workspace_bytes",
-    "hora_allocate_static",
+    "hora_allocate_static", "hora_token_broadcast2", "hora_token_broadcast2_workspace_bytes",
 )
 
 
@@ -93,6 +93,10 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.hora_token_broadcast_workspace_bytes.restype = sz
     lib.hora_token_broadcast.argtypes = [i64, p, i32, p, i32, p, i32, i64, p, p, sz, p]
     lib.hora_token_broadcast.restype = ctypes.c_int
+    lib.hora_token_broadcast2_workspace_bytes.argtypes = [i64, i32]
+    lib.hora_token_broadcast2_workspace_bytes.restype = sz
+    lib.hora_token_broadcast2.argtypes = [i64, p, p, i32, p, i32, p, p, i32, i64, p, p, sz, p]
+    lib.hora_token_broadcast2.restype = ctypes.c_int
     _lib = lib
     return lib
 
@@ -331,6 +335,28 @@ def hora_token_broadcast(adv: torch.Tensor, tok_off: torch.Tensor, tok_adv: torc
         _stream(stream)), "hora_token_broadcast")
 
 
+def hora_token_broadcast2_workspace_bytes(n_tokens: int, out_dtype: torch.dtype = torch.float32) -> int:
+    t = {torch.float32: F32, torch.float64: F64}[out_dtype]
+    return int(load_library().hora_token_broadcast2_workspace_bytes(int(n_tokens), t))
+
+
+def hora_token_broadcast2(adv_a: torch.Tensor, adv_b: torch.Tensor, tok_off: torch.Tensor, tok_a: torch.Tensor,
+                          tok_b: torch.Tensor, n_tokens: int, dev_status: torch.Tensor, workspace: torch.Tensor,
+                          stream=None) -> None:
+    n_resp = adv_a.numel()
+    if adv_b.numel() != n_resp or adv_b.dtype != adv_a.dtype:
+        raise ValueError("adv_b must match adv_a in dtype and size")
+    if tok_off.numel() != n_resp + 1:
+        raise ValueError("tok_off needs n_resp + 1 elements")
+    if tok_a.numel() < n_tokens or tok_b.numel() < n_tokens or tok_a.dtype != tok_b.dtype:
+        raise ValueError("tok_a / tok_b too small or of different types")
+    _expect(dev_status, torch.int32, 1, "dev_status")
+    _check(load_library().hora_token_broadcast2(
+        n_resp, _ptr(adv_a), _ptr(adv_b), _ftype(adv_a), _ptr(tok_off), _itype(tok_off), _ptr(tok_a), _ptr(tok_b),
+        _ftype(tok_a), int(n_tokens), _ptr(dev_status), _ptr(workspace),
+        workspace.numel() * workspace.element_size(), _stream(stream)), "hora_token_broadcast2")
+
+
 # ----------------------------------------------------------------------------
 # Buffer holder
 # ----------------------------------------------------------------------------
@@ -436,6 +462,18 @@ class Session:
         hora_token_broadcast(adv, tok_off, tok_adv, n_tokens, self.dev_status,
                              self.broadcast_workspace(n_tokens, tok_adv.dtype))
         return tok_adv
+
+    def token_broadcast2(self, adv_a: torch.Tensor, adv_b: torch.Tensor, tok_off: torch.Tensor, n_tokens: int,
+                         out_dtype: torch.dtype = torch.float32, out=None):
+        if out is None:
+            out = (torch.empty(n_tokens, dtype=out_dtype, device=self.device),
+                   torch.empty(n_tokens, dtype=out_dtype, device=self.device))
+        need = hora_token_broadcast2_workspace_bytes(n_tokens, out[0].dtype)
+        if self._bcast_workspace.numel() < need:
+            self._bcast_workspace = torch.empty(need, dtype=torch.uint8, device=self.device)
+        hora_token_broadcast2(adv_a, adv_b, tok_off, out[0], out[1], n_tokens, self.dev_status,
+                              self._bcast_workspace)
+        return out
 
     def status(self) -> int:
         """Synchronises and returns the sticky device status (0 = no data error so far)."""

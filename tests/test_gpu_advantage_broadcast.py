@@ -224,6 +224,76 @@ def test_broadcast_shapes_and_edges(gpu, oracle):
     assert sess.status() == 0
 
 
+def check_broadcast2(gpu, oracle, adv_a, adv_b, tok_off, out_dtype="f32", itype="i64", skew=0):
+    """Two streams in one pass against two runs of the oracle, bit for bit, with canaries around both outputs."""
+    sess, torch, hora = gpu
+    idt = {"i32": np.int32, "i64": np.int64}[itype]
+    ndt = {"f32": np.float32, "f64": np.float64}[out_dtype]
+    tdt = {"f32": torch.float32, "f64": torch.float64}[out_dtype]
+    total = int(tok_off[-1])
+    step = 16 // np.dtype(ndt).itemsize
+    bufs = [torch.full((total + skew + 5 + step,), float("nan"), dtype=tdt, device="cuda:0") for _ in range(2)]
+    # both outputs at the same address modulo 16
+    starts = [skew + (-(b.data_ptr() // b.element_size()) % step) for b in bufs]
+    outs = [b[s0:s0 + total] for b, s0 in zip(bufs, starts)]
+    assert outs[0].data_ptr() % 16 == outs[1].data_ptr() % 16
+    print(f"token_broadcast2 resp={adv_a.size} tokens={total} {adv_a.dtype}->{out_dtype} {itype} skew={skew}", flush=True)
+    sess.token_broadcast2(dev(torch, adv_a), dev(torch, adv_b), dev(torch, tok_off.astype(idt)), total, out=outs)
+    assert sess.status() == 0
+    for buf, s0, adv in zip(bufs, starts, (adv_a, adv_b)):
+        host = buf.cpu().numpy()
+        want = oracle.token_broadcast(adv.astype(np.float64), tok_off).astype(ndt)
+        assert np.array_equal(host[s0:s0 + total], want)
+        assert np.isnan(host[:s0]).all() and np.isnan(host[s0 + total:]).all()
+
+
+def test_two_stream_broadcast_matches_two_broadcasts(gpu, oracle):
+    from paper_2605_07114_amd import workloads as wl
+    sess, torch, hora = gpu
+    for w in (wl.TINY, wl.SMALL, wl.LARGE_BCAST):
+        a = wl.phase_a(w)
+        delta = oracle.allocate(a.c, w.g0, w.budget, delta_max=w.delta_max)
+        b = wl.phase_b(w, a, delta)
+        fdt = wl.np_float(w.float_type)
+        rloo = oracle.group_advantage(b.group_off, b.reward, "rloo").astype(fdt)
+        grpo = oracle.group_advantage(b.group_off, b.reward, "grpo", eps=w.eps).astype(fdt)
+        check_broadcast2(gpu, oracle, rloo, grpo, b.tok_off, out_dtype=w.token_type, itype=w.tok_off_type)
+        # the loss weights of Sec. 3.2 as the second stream
+        wts = oracle.response_weights(b.group_off, b.tok_off).astype(fdt)
+        check_broadcast2(gpu, oracle, grpo, wts, b.tok_off, out_dtype=w.token_type, itype=w.tok_off_type)
+    rng = np.random.default_rng(47)
+    cases = {
+        "one token": np.array([1]),
+        "zero-length runs": np.concatenate([np.zeros(5000, dtype=np.int64), [3], np.zeros(4000, dtype=np.int64),
+                                            rng.integers(0, 3, 30000), [70000], np.zeros(17, dtype=np.int64)]),
+        "tiny segments": rng.integers(1, 4, 100000),
+        "a few per row": rng.integers(170, 520, 6000),
+        "short and long mixed": np.where(rng.random(4000) < 0.5, rng.integers(100, 300, 4000),
+                                         rng.integers(3000, 9000, 4000)),
+        "ragged tail": np.array([16384 * 3 + 1]),
+    }
+    for name, lengths in cases.items():
+        off = lengths_to_off(lengths.astype(np.int64))
+        x, y = rng.normal(size=lengths.size), rng.normal(size=lengths.size)
+        print("case:", name, flush=True)
+        check_broadcast2(gpu, oracle, x, y, off, "f64", "i64")
+        check_broadcast2(gpu, oracle, x.astype(np.float32), y.astype(np.float32), off, "f32", "i32")
+        check_broadcast2(gpu, oracle, x, y, off, "f32", "i64")
+    lengths = rng.integers(0, 3000, 500)
+    off = lengths_to_off(lengths)
+    x, y = rng.normal(size=500), rng.normal(size=500)
+    for skew in (1, 2, 3):
+        check_broadcast2(gpu, oracle, x.astype(np.float32), y.astype(np.float32), off, "f32", "i64", skew=skew)
+    check_broadcast2(gpu, oracle, x, y, off, "f64", "i64", skew=1)
+    # outputs that do not share their alignment are refused (they would need two row grids)
+    out = torch.zeros(int(off[-1]) + 8, dtype=torch.float32, device="cuda:0")
+    with pytest.raises(hora.HoraError) as e:
+        hora.hora_token_broadcast2(dev(torch, x.astype(np.float32)), dev(torch, y.astype(np.float32)),
+                                   dev(torch, off), out[:int(off[-1])], out[1:int(off[-1]) + 1], int(off[-1]),
+                                   sess.dev_status, sess.broadcast_workspace(2 * int(off[-1]), torch.float32))
+    assert e.value.status == hora.ERR_INVALID_ARG
+
+
 def test_broadcast_bad_offsets_are_reported(gpu):
     sess, torch, hora = gpu
     adv = torch.ones(3, dtype=torch.float32, device="cuda:0")
