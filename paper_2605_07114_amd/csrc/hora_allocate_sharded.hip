@@ -31,7 +31,7 @@ namespace hora {
 constexpr int kShardThreads = 256;
 constexpr int kShardWaves = kShardThreads / kWave;
 constexpr int kPrefixThreads = 1024;
-constexpr int kPrefixChunk = 8 * kPrefixThreads;   // shards per prefix-sum workgroup
+constexpr int kPrefixGroups = 64;                  // prefix-sum workgroups of the set-up kernel, at most
 constexpr unsigned kShardTiedBit = 0x80000000u;
 constexpr unsigned long long kWindowStep = 4ull << 52;   // 4 exponent steps: a factor 16 in value
 // Windows from the largest gain down to zero (at most 2047 / 4), plus the narrowing passes
@@ -88,16 +88,86 @@ __host__ inline ShardWorkspace carve_shards(void* base, int64_t n_shards) {
     return w;
 }
 
-// Set-up.  Workgroup 0 resets the list of left-over shards.  Workgroups 2, 3, ...: exclusive
-// prefix sums of the shard budgets, kPrefixChunk shards each (negative budgets count as 0; the
-// shard's own workgroup reports them).
-// Workgroup 1: the gain and survival sequences of the G0+1 classes, one thread per class
-// (Sec. 3.2 stable update; App. A), `depth` entries each; then all gains l < usable of all
-// classes sorted descending into "levels": the position of a gain is the number of gains
-// above it plus, among equal gains, the number of lower classes that hold it, and every
-// level carries, per class, the number of that class's gains >= the level.  With these a
-// shard finds its threshold by a search over levels: count_ge(level) = sum_c n_c * kge_c.
-__global__ __launch_bounds__(kPrefixThreads) void k_shard_setup(long long n_shards,
+// The gain and survival sequences of the G0+1 classes, one thread per class (Sec. 3.2 stable
+// update; App. A), `depth` entries each; then all gains l < usable of all classes sorted
+// descending into "levels": the position of a gain is the number of gains above it plus, among
+// equal gains, the number of lower classes that hold it, and every level carries, per class,
+// the number of that class's gains >= the level.  With these a shard finds its threshold by a
+// search over levels: count_ge(level) = sum_c n_c * kge_c.  Run by one whole workgroup; `raw`
+// is where the searches read the gains' patterns from: LDS of nc * depth entries, or NULL to
+// read them back from the table in global memory (slower; for callers short of LDS).
+// The key is cleared first and set last, each side fenced, so that a reader that finds the key
+// it wants finds complete tables.
+__device__ void build_shard_tables(int g0, double alpha0, double beta0, int depth, int usable,
+                                   ShardTableKey* __restrict__ key, double* __restrict__ gain_table,
+                                   double* __restrict__ surv_table, unsigned long long* __restrict__ level_bits,
+                                   unsigned short* __restrict__ level_kge, unsigned long long* raw) {
+    if (threadIdx.x == 0) key->magic = 0ull;
+    __threadfence();
+    __syncthreads();
+    if (threadIdx.x <= (unsigned)g0) {
+        const int cls = (int)threadIdx.x;
+        const double a = alpha0 + (double)cls;
+        const double b = beta0 + (double)(g0 - cls);
+        const double s = a + b;
+        double m = gain_first(a, s), e = 1.0, lf = 0.0;
+        for (int l = 0; l < depth; ++l) {
+            gain_table[cls * depth + l] = m;
+            surv_table[cls * depth + l] = e;
+            if (raw) raw[cls * depth + l] = gain_bits(m);
+            e = surv_next(e, b, s, lf);
+            m = gain_next(m, b, s, lf);
+            lf += 1.0;
+        }
+    }
+    __threadfence();
+    __syncthreads();
+    const unsigned long long* bits = raw ? raw : reinterpret_cast<const unsigned long long*>(gain_table);
+    // levels: one entry (class, l) at a time per thread; two rounds of searches, the first
+    // for the entry's position, the second to write the per-class counts there
+    const int nc = g0 + 1;
+    const int stride = level_stride(nc);
+    for (int e = (int)threadIdx.x; e < nc * usable; e += (int)blockDim.x) {
+        const int cls = e / usable, l = e - cls * usable;
+        const unsigned long long v = bits[cls * depth + l];
+        int pos_of = 0;
+        for (int round = 0; round < 2; ++round) {
+            int rank = 0, order = 0;
+            for (int c2 = 0; c2 < nc; ++c2) {
+                const unsigned long long* row = bits + c2 * depth;
+                int lo = 0, hi = usable;          // first index whose gain is <= v
+                while (lo < hi) {
+                    const int mid = (lo + hi) >> 1;
+                    if (row[mid] > v) lo = mid + 1; else hi = mid;
+                }
+                const int eq = (lo < usable && row[lo] == v) ? 1 : 0;
+                rank += lo;
+                if (c2 < cls) order += eq;
+                if (round == 1) level_kge[(long long)pos_of * stride + c2] = (unsigned short)(lo + eq);
+            }
+            pos_of = rank + order;
+        }
+        level_bits[pos_of] = v;
+    }
+    __threadfence();
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        key->alpha0 = alpha0; key->beta0 = beta0; key->g0 = g0; key->depth = depth; key->usable = usable;
+        __threadfence();
+        key->magic = kTableMagic;
+    }
+}
+
+__device__ __forceinline__ bool shard_tables_match(const ShardTableKey* key, int g0, double alpha0, double beta0,
+                                                   int depth, int usable) {
+    return key->magic == kTableMagic && key->alpha0 == alpha0 && key->beta0 == beta0 && key->g0 == g0 &&
+           key->depth == depth && key->usable == usable;
+}
+
+// Set-up for calls with many shards.  Workgroup 0 empties the list of left-over shards.  Workgroup 1: the tables, unless the workspace holds them
+// already.  Workgroups 2, 3, ...: exclusive prefix sums of the shard budgets, `chunk`
+// shards each (negative budgets count as 0; the shard's own workgroup reports them).
+__global__ __launch_bounds__(kPrefixThreads) void k_shard_setup(long long n_shards, long long chunk,
                                                                 const long long* __restrict__ shard_budget,
                                                                 long long* __restrict__ prefix, int g0,
                                                                 double alpha0, double beta0, int depth,
@@ -107,86 +177,43 @@ __global__ __launch_bounds__(kPrefixThreads) void k_shard_setup(long long n_shar
                                                                 unsigned long long* __restrict__ level_bits,
                                                                 unsigned short* __restrict__ level_kge,
                                                                 int* __restrict__ todo) {
-    __shared__ unsigned long long s_raw[kShardTableCap];   // workgroup 0: wavefront totals; workgroup 1: the gains
+    __shared__ unsigned long long s_raw[kShardTableCap];   // workgroup 1: the gains; prefix workgroups: wavefront totals
     long long* s_tot = reinterpret_cast<long long*>(s_raw);
     if (blockIdx.x == 1) {
         if (depth == 0) return;
-        const bool cached = key->magic == kTableMagic && key->alpha0 == alpha0 && key->beta0 == beta0 &&
-                            key->g0 == g0 && key->depth == depth && key->usable == usable;
-        if (cached) return;   // uniform: every thread reads the same key
-        __syncthreads();      // all threads have read the key before thread 0 clears it
-        if (threadIdx.x == 0) key->magic = 0ull;
-        if (threadIdx.x <= (unsigned)g0) {
-            const int cls = (int)threadIdx.x;
-            const double a = alpha0 + (double)cls;
-            const double b = beta0 + (double)(g0 - cls);
-            const double s = a + b;
-            double m = gain_first(a, s), e = 1.0, lf = 0.0;
-            for (int l = 0; l < depth; ++l) {
-                gain_table[cls * depth + l] = m;
-                surv_table[cls * depth + l] = e;
-                s_raw[cls * depth + l] = gain_bits(m);
-                e = surv_next(e, b, s, lf);
-                m = gain_next(m, b, s, lf);
-                lf += 1.0;
-            }
-        }
-        __syncthreads();
-        // levels: one entry (class, l) at a time per thread; two rounds of searches, the first
-        // for the entry's position, the second to write the per-class counts there
-        const int nc = g0 + 1;
-        const int stride = level_stride(nc);
-        for (int e = (int)threadIdx.x; e < nc * usable; e += kPrefixThreads) {
-            const int cls = e / usable, l = e - cls * usable;
-            const unsigned long long v = s_raw[cls * depth + l];
-            int pos_of = 0;
-            for (int round = 0; round < 2; ++round) {
-                int rank = 0, order = 0;
-                for (int c2 = 0; c2 < nc; ++c2) {
-                    const unsigned long long* row = s_raw + c2 * depth;
-                    int lo = 0, hi = usable;          // first index whose gain is <= v
-                    while (lo < hi) {
-                        const int mid = (lo + hi) >> 1;
-                        if (row[mid] > v) lo = mid + 1; else hi = mid;
-                    }
-                    const int eq = (lo < usable && row[lo] == v) ? 1 : 0;
-                    rank += lo;
-                    if (c2 < cls) order += eq;
-                    if (round == 1) level_kge[(long long)pos_of * stride + c2] = (unsigned short)(lo + eq);
-                }
-                pos_of = rank + order;
-            }
-            level_bits[pos_of] = v;
-        }
-        __threadfence();
-        __syncthreads();
-        if (threadIdx.x == 0) {
-            key->alpha0 = alpha0; key->beta0 = beta0; key->g0 = g0; key->depth = depth; key->usable = usable;
-            __threadfence();
-            key->magic = kTableMagic;
-        }
+        if (shard_tables_match(key, g0, alpha0, beta0, depth, usable)) return;   // uniform: every thread reads the same key
+        __syncthreads();      // all threads have read the key before it is cleared
+        build_shard_tables(g0, alpha0, beta0, depth, usable, key, gain_table, surv_table, level_bits, level_kge, s_raw);
         return;
     }
-    if (blockIdx.x == 0 && threadIdx.x == 0) todo[0] = 0;
+    if (blockIdx.x == 0 && threadIdx.x == 0) todo[0] = 0;   // the list of left-over shards starts empty
     if (!prefix || blockIdx.x == 0) return;
-    // Workgroup 2 + k: chunk k of kPrefixChunk shards.  It first adds up every budget before
-    // its chunk (all loads independent of one another), then scans its own chunk: thread t
-    // owns 8 consecutive shards (contiguous 64-byte loads and stores).
-    constexpr int kPer = kPrefixChunk / kPrefixThreads;
-    const long long base = (long long)(blockIdx.x - 2) * kPrefixChunk;
+    // Workgroup 2 + k: chunk k of `chunk` shards (a multiple of the workgroup size; at most
+    // kPrefixGroups chunks).  It first adds up every budget before its chunk (independent loads,
+    // sixteen in flight per thread), then scans its own chunk: thread t owns chunk / kPrefixThreads
+    // consecutive shards.
+    const long long base = (long long)(blockIdx.x - 2) * chunk;
     long long earlier = 0;
-    for (long long i = threadIdx.x; i < base; i += kPrefixThreads) {
-        const long long v = shard_budget[i];
-        earlier += v > 0 ? v : 0;
-    }
-    const long long first = base + (long long)threadIdx.x * kPer;
-    long long b[kPer];
-    long long sum = 0;
+    {
+        long long i = threadIdx.x;
+        for (; i + 15 * kPrefixThreads < base; i += 16 * kPrefixThreads) {
+            long long v[16];
 #pragma unroll
-    for (int k = 0; k < kPer; ++k) {
+            for (int q = 0; q < 16; ++q) v[q] = shard_budget[i + q * kPrefixThreads];
+#pragma unroll
+            for (int q = 0; q < 16; ++q) earlier += v[q] > 0 ? v[q] : 0;
+        }
+        for (; i < base; i += kPrefixThreads) {
+            const long long v = shard_budget[i];
+            earlier += v > 0 ? v : 0;
+        }
+    }
+    const int per = (int)(chunk / kPrefixThreads);
+    const long long first = base + (long long)threadIdx.x * per;
+    long long sum = 0;
+    for (int k = 0; k < per; ++k) {
         const long long v = first + k < n_shards ? shard_budget[first + k] : 0;
-        b[k] = v > 0 ? v : 0;
-        sum += b[k];
+        sum += v > 0 ? v : 0;
     }
     earlier = wave_sum<long long>(earlier);
     const long long incl = wave_incl_scan<long long>(sum);
@@ -197,10 +224,12 @@ __global__ __launch_bounds__(kPrefixThreads) void k_shard_setup(long long n_shar
         if (w < wave_id()) run += s_tot[w];
         run += s_tot[kPrefixThreads / kWave + w];
     }
-#pragma unroll
-    for (int k = 0; k < kPer; ++k) {
-        if (first + k < n_shards) prefix[first + k] = run;
-        run += b[k];
+    for (int k = 0; k < per; ++k) {
+        if (first + k < n_shards) {
+            prefix[first + k] = run;
+            const long long v = shard_budget[first + k];
+            run += v > 0 ? v : 0;
+        }
     }
 }
 
@@ -585,8 +614,21 @@ __device__ void shard_by_workgroup(const Src& src, long long shard, long long n,
         if (threadIdx.x == 0) report(dev_status, wrong);
         return;
     }
-    shard_core<Src, kOff>(src, lo_i, hi_i, budget, kOff != 0 ? prefix[shard] : 0, n, g0, cap, depth, gain_table,
-                          surv_table, delta, util, group_off, summary ? summary + shard : nullptr, dev_status);
+    long long before = 0;   // units handed to the shards before this one (only the offsets need it)
+    if (kOff != 0) {
+        if (prefix) {
+            before = prefix[shard];
+        } else {            // few shards: the workgroup adds their budgets up itself
+            __shared__ long long s_before[kShardWaves];
+            for (long long t = threadIdx.x; t < shard; t += kShardThreads) {
+                const long long v = shard_budget[t];
+                before += v > 0 ? v : 0;
+            }
+            before = block_sum<long long>(before, s_before);
+        }
+    }
+    shard_core<Src, kOff>(src, lo_i, hi_i, budget, before, n, g0, cap, depth, gain_table, surv_table, delta, util,
+                          group_off, summary ? summary + shard : nullptr, dev_status);
 }
 
 // A whole batch as one shard, for batches small enough for one workgroup: one launch in place
@@ -646,8 +688,8 @@ __global__ __launch_bounds__(kShardThreads) void k_shard_allocate(Src src, long 
                                   depth, gain_table, surv_table, delta, util, group_off, summary, dev_status);
 }
 
-// The shards the wavefront-per-shard kernel left over (todo[0] of them, ids from todo[1]):
-// a fixed number of workgroups takes them in turn.
+// The shards the group kernel left over when it runs without its own fallback (todo[0] of them,
+// ids from todo[1]): a fixed number of workgroups takes them in turn.
 template <class Src, int kOff>
 __global__ __launch_bounds__(kShardThreads) void k_shard_allocate_todo(Src src, long long n, int g0,
                                                                        long long n_shards,
@@ -673,254 +715,328 @@ __global__ __launch_bounds__(kShardThreads) void k_shard_allocate_todo(Src src, 
 }
 
 // ----------------------------------------------------------------------------------
-// Wavefront per shard (shared prior, small shards).  A workgroup of four wavefronts takes
-// four shards; nothing is shared between them but the coarse rows in LDS.
-//  1. histogram of c: lane k counts class k (wavefront ballots);
-//  2. coarse search: lane q evaluates count_ge of the last level of block q (the coarse
-//     rows, one per 64 levels, are in LDS) and the first block that reaches the budget is
-//     taken; fine search: lane t evaluates level 64 q + t of that block (one 32- or
-//     128-byte row per lane from global memory).  tau is the first level whose count_ge
-//     reaches the budget; the level before it gives the gains above tau per class;
-//  3. outputs with the tie pass inside the wavefront (ballot + mbcnt ranks, DPP prefix sums
-//     for the offsets).
-// Two dependent global loads (the shard's c, then the block's rows) plus the per-class
-// look-ups, instead of several passes with workgroup barriers.  A shard the table cannot
-// settle (deeper than the table, more than kWaveShardMax prompts) is put on a list for the
-// workgroup-per-shard code, which a second kernel runs afterwards.
+// Small shards (shared prior): L lanes per shard, 64 / L shards per wavefront (the paper's
+// shards hold 15 prompts: four of them share a wavefront).  Every cross-lane step stays
+// inside the shard's L lanes, so shards of one wavefront do not wait for one another beyond
+// running in lockstep.
+//  1. histogram of c: lane k of the group counts class k (wavefront ballots, the group's bits);
+//  2. coarse search: the group's lanes evaluate count_ge of the last level of every block of
+//     64 sorted levels (coarse rows in LDS); the first block that reaches the budget is taken;
+//     fine search: its 64 levels, 64 / L per lane (one 32- or 128-byte row each from global
+//     memory).  tau is the first level whose count_ge reaches the budget; the level before it
+//     gives the gains above tau per class;
+//  3. outputs with the tie pass inside the group (ballot + mbcnt ranks, group prefix sums for
+//     the offsets).
+// A shard the tables cannot settle (deeper than the tables, more than kWaveShardMax prompts,
+// or no tables yet) is handed to the workgroup-per-shard code.
+//  kFused (few shards, one launch per call): the same workgroup runs that code after its
+//    groups are through; every group adds up the budgets before its shard itself; and when
+//    the workspace does not hold the tables for this prior yet, workgroup 0 builds them at the
+//    end, for the calls that follow.
+//  otherwise (many shards): such shards go on a list that k_shard_allocate_todo works off;
+//    keeping that code out of this kernel more than halves its register count, and with tens
+//    of thousands of groups in flight the occupancy is what hides their memory round trips.
 // ----------------------------------------------------------------------------------
-struct WaveScratch {          // per wavefront, LDS
-    int k[kShardMaxClasses];
-    int tied[kShardMaxClasses];
-    double e[kShardMaxClasses];
-    unsigned rows[2][8];      // the per-class counts of level tau and of the level before (16 classes or fewer)
+constexpr long long kInlineShards = 256;   // up to here a call has no set-up launch
+
+template <int L> struct GroupScratch {   // per shard of the workgroup, LDS
+    int k[L];
+    int tied[L];
+    double e[L];
 };
 
-template <int kOff>
+template <typename T, int L>
+__device__ __forceinline__ T group_sum(T v) {
+#pragma unroll
+    for (int d = L / 2; d > 0; d >>= 1) v += __shfl_xor(v, d, L);
+    return v;
+}
+template <int L>
+__device__ __forceinline__ long long group_max(long long v) {
+#pragma unroll
+    for (int d = L / 2; d > 0; d >>= 1) {
+        const long long o = __shfl_xor(v, d, L);
+        v = o > v ? o : v;
+    }
+    return v;
+}
+template <int L>
+__device__ __forceinline__ long long group_incl_scan(long long v, int sl) {
+#pragma unroll
+    for (int d = 1; d < L; d <<= 1) {
+        const long long o = __shfl_up(v, d, L);
+        if (sl >= d) v += o;
+    }
+    return v;
+}
+
+template <int kOff, int L, bool kFused>
 __global__ __launch_bounds__(kShardThreads) void k_shard_allocate_waves(
     CountsSource src, long long n, long long n_shards, const long long* __restrict__ shard_off,
     const long long* __restrict__ shard_budget, int cap, const long long* __restrict__ prefix, int depth, int usable,
-    const double* __restrict__ surv_table, const unsigned long long* __restrict__ level_bits,
-    const unsigned short* __restrict__ level_kge, int* __restrict__ todo, int32_t* __restrict__ delta,
-    double* __restrict__ util, void* __restrict__ group_off, hora_alloc_summary* __restrict__ summary,
-    int32_t* dev_status) {
+    ShardTableKey* __restrict__ key, double* __restrict__ gain_table, double* __restrict__ surv_table,
+    unsigned long long* __restrict__ level_bits, unsigned short* __restrict__ level_kge, int* __restrict__ todo,
+    int32_t* __restrict__ delta, double* __restrict__ util, void* __restrict__ group_off,
+    hora_alloc_summary* __restrict__ summary, int32_t* dev_status) {
+    constexpr int kPerWave = kWave / L;                  // shards per wavefront
+    constexpr int kPerBlock = kShardWaves * kPerWave;    // shards per workgroup
+    constexpr unsigned long long kGroupMask = L == 64 ? ~0ull : ((1ull << (L & 63)) - 1ull);
     __shared__ unsigned short s_coarse[kMaxCoarse * 64];
-    __shared__ WaveScratch s_wave[kShardWaves];
+    __shared__ GroupScratch<L> s_group[kPerBlock];
+    __shared__ int s_left[kPerBlock];
+    __shared__ int s_left_n, s_tables;
     const int g0 = src.g0;
-    const int nc = g0 + 1;
+    const int nc = g0 + 1;                               // (the host picks L >= nc)
     const int stride = level_stride(nc);
     const int levels = nc * usable;
     const int n_coarse = (levels + kLevelBlock - 1) / kLevelBlock;
+    const int lane = lane_id();
+    const int sub = lane / L, sl = lane % L;             // the shard's slot in the wavefront, the lane in the group
+    const int shift = sub * L;                           // the group's bits in a wavefront ballot
+    const long long first_shard = (long long)blockIdx.x * kPerBlock;
+    const int slot = wave_id() * kPerWave + sub;
+    const long long shard = first_shard + slot;
+    const bool live = shard < n_shards;
     // the shard's bounds and budget are requested first, so that they travel while the coarse
     // rows are staged (coarse row q = the last level of block q)
-    const int lane = lane_id();
-    const long long shard = (long long)blockIdx.x * kShardWaves + wave_id();
-    const bool live = shard < n_shards;
     const long long lo_i = live ? shard_off[shard] : 0, hi_i = live ? shard_off[shard + 1] : 0;
     const long long budget = live ? shard_budget[shard] : 0;
-    const long long before = (kOff != 0 && live) ? prefix[shard] : 0;   // units of the shards before this one
-    for (int idx = (int)threadIdx.x; idx < n_coarse * stride; idx += kShardThreads) {
-        const int q = idx / stride, k = idx - q * stride;
-        int p = q * kLevelBlock + kLevelBlock - 1;
-        if (p > levels - 1) p = levels - 1;
-        s_coarse[idx] = level_kge[(long long)p * stride + k];
+    long long before = 0;                                // units of the shards before this one
+    if (kOff != 0 && live) {
+        if (prefix) {
+            before = prefix[shard];
+        } else {
+            for (long long t = sl; t < shard; t += L) {
+                const long long v = shard_budget[t];
+                before += v > 0 ? v : 0;
+            }
+        }
+    }
+    if (kOff != 0 && !prefix) before = group_sum<long long, L>(before);
+    if (threadIdx.x == 0) {
+        s_left_n = 0;
+        s_tables = shard_tables_match(key, g0, src.alpha0, src.beta0, depth, usable) ? 1 : 0;
     }
     __syncthreads();
-    if (!live) return;
-    WaveScratch& ws = s_wave[wave_id()];
-    const int wrong = check_shard(shard, n_shards, n, lo_i, hi_i, budget, cap);
-    if (wrong != HORA_OK) {
-        if (lane == 0) report(dev_status, wrong);
-        return;
-    }
-    const long long size = hi_i - lo_i;
-    if (size > kWaveShardMax) {
-        if (lane == 0) todo[1 + atomicAdd(&todo[0], 1)] = (int)shard;
-        return;
-    }
-    const long long limit = cap > 0 ? (budget < cap ? budget : (long long)cap) : budget;   // (the table is far shallower than the depth bound)
-
-    // ---- 1. histogram: lane k ends up with the number of prompts of class k
-    int n_mine = 0;
-    bool data_bad = false;
-    for (long long i0 = lo_i; i0 < hi_i; i0 += kWave) {
-        const long long i = i0 + lane;
-        int x = -1;
-        if (i < hi_i) {
-            x = src.c[i];
-            if (x < 0 || x > g0) { data_bad = true; x = x < 0 ? 0 : g0; }
+    const bool tables = s_tables != 0;
+    if (tables)
+        for (int idx = (int)threadIdx.x; idx < n_coarse * stride; idx += kShardThreads) {
+            const int q = idx / stride, k = idx - q * stride;
+            int p = q * kLevelBlock + kLevelBlock - 1;
+            if (p > levels - 1) p = levels - 1;
+            s_coarse[idx] = level_kge[(long long)p * stride + k];
         }
-        for (int k = 0; k < nc; ++k) {
-            const int cnt = __popcll(__ballot(x == k));
-            if (lane == k) n_mine += cnt;
-        }
-    }
-    if (data_bad) report(dev_status, HORA_ERR_RANGE);
-
-    // ---- 2. threshold
-    int k_mine = 0, tied_mine = 0;            // lane c: gains of class c above tau; its next gain equals tau
-    double e_mine = 1.0;                      // lane c: E_c(k_c)
-    long long count_gt = 0, tie_prompts = 0;
-    unsigned long long tau_bits = 0;
-    bool settled = true;
-    if (budget > 0) {
-        // coarse: lane q (and q + 64) evaluates the last level of its block
-        long long cq[2] = {0, 0};
-        for (int k = 0; k < nc; ++k) {
-            const long long nk = (long long)__builtin_amdgcn_readlane(n_mine, k);
-            if (nk == 0) continue;            // uniform
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const int q = lane + 64 * h;
-                if (q < n_coarse) cq[h] += nk * (long long)s_coarse[q * stride + k];
-            }
-        }
-        int block = -1;
-        long long before_block = 0;           // count_ge of the last level of the block before
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            if (block < 0) {
-                const unsigned long long reach = __ballot(lane + 64 * h < n_coarse && cq[h] >= budget);
-                if (reach) {
-                    const int first = __ffsll((long long)reach) - 1;
-                    block = first + 64 * h;
-                    if (first > 0) before_block = __shfl(cq[h], first - 1, kWave);
-                    else if (h == 1) before_block = __shfl(cq[0], kWave - 1, kWave);
-                }
-            }
-        }
-        if (block < 0) {
-            settled = false;                  // the table does not reach the budget
+    __syncthreads();
+    GroupScratch<L>& gs = s_group[slot];
+    bool defer = false;        // the workgroup-per-shard code has to take the shard
+    if (live) {
+        const int wrong = check_shard(shard, n_shards, n, lo_i, hi_i, budget, cap);
+        const long long size = hi_i - lo_i;
+        if (wrong != HORA_OK) {
+            if (sl == 0) report(dev_status, wrong);
+        } else if (!tables || size > kWaveShardMax) {
+            defer = true;
         } else {
-            // fine: lane t evaluates level 64 * block + t
-            const int p = block * kLevelBlock + lane;
-            long long ct = 0;
-            unsigned w[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};   // this lane's row (16 classes or fewer)
-            if (p < levels) {
-                const unsigned short* row = level_kge + (long long)p * stride;
-                if (stride == 16) {
-                    const uint4 r0 = *reinterpret_cast<const uint4*>(row);
-                    const uint4 r1 = *reinterpret_cast<const uint4*>(row + 8);
-                    w[0] = r0.x; w[1] = r0.y; w[2] = r0.z; w[3] = r0.w;
-                    w[4] = r1.x; w[5] = r1.y; w[6] = r1.z; w[7] = r1.w;
+            const long long limit = cap > 0 ? (budget < cap ? budget : (long long)cap) : budget;   // (the tables are far shallower than the depth bound)
+            // ---- 1. histogram: lane k of the group ends up with the number of prompts of class k;
+            // groups narrower than a wavefront also keep all of their counts in every lane's
+            // registers (at most L of them), which saves the shuffles below
+            constexpr int kRegs = L < kWave ? L : 1;
+            int n_mine = 0;
+            int n_all[kRegs];
 #pragma unroll
-                    for (int k = 0; k < 16; ++k) {
-                        const long long nk = (long long)__builtin_amdgcn_readlane(n_mine, k);
-                        const unsigned kge = (k & 1) ? (w[k >> 1] >> 16) : (w[k >> 1] & 0xffffu);
-                        ct += nk * (long long)kge;    // lanes beyond nc hold n = 0
-                    }
+            for (int k = 0; k < kRegs; ++k) n_all[k] = 0;
+            bool data_bad = false;
+            for (long long i0 = lo_i; i0 < hi_i; i0 += L) {
+                const long long i = i0 + sl;
+                int x = -1;
+                if (i < hi_i) {
+                    x = src.c[i];
+                    if (x < 0 || x > g0) { data_bad = true; x = x < 0 ? 0 : g0; }
+                }
+                if constexpr (L < kWave) {
+#pragma unroll
+                    for (int k = 0; k < L; ++k)
+                        if (k < nc) {   // uniform
+                            const int cnt = __popcll((__ballot(x == k) >> shift) & kGroupMask);
+                            n_all[k] += cnt;
+                            if (sl == k) n_mine += cnt;
+                        }
                 } else {
                     for (int k = 0; k < nc; ++k) {
-                        const long long nk = (long long)__builtin_amdgcn_readlane(n_mine, k);
-                        ct += nk * (long long)row[k];
+                        const int cnt = __popcll(__ballot(x == k));
+                        if (sl == k) n_mine += cnt;
                     }
                 }
             }
-            const unsigned long long reach = __ballot(p < levels && ct >= budget);
-            // reach != 0: the block's last level reaches the budget
-            const int t = __ffsll((long long)reach) - 1;
-            const int j = block * kLevelBlock + t;                 // tau = level j
-            count_gt = t > 0 ? __shfl(ct, t - 1, kWave) : before_block;
-            tau_bits = level_bits[j];
-            if (stride == 16) {
-                // the two rows are in the registers of lanes t and t - 1: hand them over through LDS
-                // (level j - 1 of the first lane's block is the coarse row of the block before)
-                if (lane == t || lane == t - 1) {
-                    unsigned* dst = ws.rows[lane == t ? 0 : 1];
-#pragma unroll
-                    for (int q = 0; q < 8; ++q) dst[q] = w[q];
-                }
-            }
-            if (lane < nc) {
-                int ge, gt;
-                if (stride == 16) {
-                    const unsigned wge = ws.rows[0][lane >> 1];
-                    ge = (int)((lane & 1) ? wge >> 16 : wge & 0xffffu);
-                    if (t > 0) {
-                        const unsigned wgt = ws.rows[1][lane >> 1];
-                        gt = (int)((lane & 1) ? wgt >> 16 : wgt & 0xffffu);
-                    } else {
-                        gt = block > 0 ? (int)s_coarse[(block - 1) * stride + lane] : 0;
-                    }
-                } else {
-                    ge = level_kge[(long long)j * stride + lane];
-                    gt = j > 0 ? level_kge[(long long)(j - 1) * stride + lane] : 0;
-                }
-                k_mine = gt;
-                tied_mine = ge - gt;
-                // every usable gain of a class the shard holds is above tau and the sequence
-                // goes on beyond the table: gains are missing from the counts
-                if (n_mine > 0 && gt == usable && (long long)usable < limit) settled = false;
-                const double a = src.alpha0 + (double)lane, b = src.beta0 + (double)(g0 - lane);
-                double e = surv_table[lane * depth + (gt < depth ? gt : depth - 1)];
-                if (gt == depth) e = surv_next(e, b, a + b, (double)(depth - 1));
-                e_mine = e;
-            }
-            settled = __ballot(!settled) == 0;
-            long long tp = tied_mine ? (long long)n_mine : 0;
-            tie_prompts = wave_sum<long long>(tp);
-        }
-    }
-    if (!settled) {
-        if (lane == 0) todo[1 + atomicAdd(&todo[0], 1)] = (int)shard;
-        return;
-    }
-    const long long r = budget - count_gt;
-    if (summary && lane == 0) {
-        summary[shard].tau = budget > 0 ? __longlong_as_double((long long)tau_bits) : 0.0;
-        summary[shard].count_gt = count_gt;
-        summary[shard].tie_units = r;
-        summary[shard].tie_prompts = tie_prompts;
-    }
-    ws.k[lane] = k_mine;
-    ws.tied[lane] = tied_mine;
-    ws.e[lane] = e_mine;
-    // (same wavefront reads them back below: LDS operations of a wavefront complete in order)
+            if (data_bad) report(dev_status, HORA_ERR_RANGE);
+            // the group's count of class k: a register, or lane k's value (a whole wavefront: scalar read)
+            auto count_of = [&](int k) -> long long {
+                if constexpr (L < kWave) return (long long)n_all[k];
+                else return (long long)__builtin_amdgcn_readlane(n_mine, k);
+            };
 
-    // ---- 3. outputs
-    const long long off_base = kOff != 0 ? (long long)g0 * lo_i + before : 0;
-    long long rank_base = 0, given = 0;       // tied prompts / units handed out before this tile
-    for (long long i0 = lo_i; i0 < hi_i; i0 += kWave) {
-        const long long i = i0 + lane;
-        const bool in = i < hi_i;
-        int x = 0;
-        if (in) {
-            x = src.c[i];
-            x = x < 0 ? 0 : (x > g0 ? g0 : x);
-        }
-        const int kk = in ? ws.k[x] : 0;
-        const bool td = in && ws.tied[x] != 0;
-        const unsigned long long tied_mask = __ballot(td);
-        const long long rank = rank_base + lanes_below(tied_mask);
-        const bool win = td && rank < r;
-        const int dd = kk + (win ? 1 : 0);
-        const int units = in ? g0 + dd : 0;
-        const long long incl = wave_incl_scan_i64((long long)units);
-        if (in) {
-            delta[i] = dd;
-            if (util) {
-                double e = ws.e[x];
-                if (win) {
-                    const double a = src.alpha0 + (double)x, b = src.beta0 + (double)(g0 - x);
-                    e = surv_next(e, b, a + b, (double)kk);
-                }
-                util[i] = 1.0 - e;
-            }
-            if (kOff != 0) {
-                const long long off = off_base + given + incl - units;
-                if (kOff == 1) {
-                    reinterpret_cast<int32_t*>(group_off)[i] = (int32_t)off;
-                    if (i == n - 1) {
-                        reinterpret_cast<int32_t*>(group_off)[n] = (int32_t)(off + units);
-                        if (off + units >= (1ll << 31)) report(dev_status, HORA_ERR_RANGE);   // total does not fit
+            // ---- 2. threshold
+            int k_mine = 0, tied_mine = 0;            // lane c of the group: gains of class c above tau; its next gain equals tau
+            double e_mine = 1.0;                      // E_c(k_c)
+            long long count_gt = 0, tie_prompts = 0;
+            unsigned long long tau_bits = 0;
+            bool ok = true;
+            if (budget > 0) {
+                // coarse: the group's lanes share the blocks; the first block whose last level reaches the budget
+                int block = INT_MAX;
+                long long below = 0;                  // largest coarse count that stays under the budget
+                for (int q0 = 0; q0 < n_coarse; q0 += L) {
+                    const int q = q0 + sl;
+                    long long cq = 0;
+                    const bool in = q < n_coarse;
+                    if constexpr (L < kWave) {
+#pragma unroll
+                        for (int k = 0; k < L; ++k)
+                            if (k < nc && in) cq += count_of(k) * (long long)s_coarse[q * stride + k];
+                    } else {
+                        for (int k = 0; k < nc; ++k) {
+                            const long long nk = count_of(k);
+                            if (in) cq += nk * (long long)s_coarse[q * stride + k];
+                        }
                     }
+                    if (in && cq >= budget) block = q < block ? q : block;
+                    if (in && cq < budget) below = cq > below ? cq : below;
+                }
+                block = -(int)group_max<L>((long long)(-block));   // the smallest over the group
+                const long long before_block = group_max<L>(below);       // the counts grow with the level: this is block - 1's
+                if (block == INT_MAX) {
+                    ok = false;                       // the tables do not reach the budget
                 } else {
-                    reinterpret_cast<long long*>(group_off)[i] = off;
-                    if (i == n - 1) reinterpret_cast<long long*>(group_off)[n] = off + units;
+                    // fine: the 64 levels of the block, 64 / L per lane
+                    int under = 0;                    // levels of the block whose count stays under the budget
+                    long long best = before_block;    // ... and the largest such count
+                    for (int t0 = 0; t0 < kLevelBlock; t0 += L) {
+                        const int lvl = block * kLevelBlock + t0 + sl;
+                        const bool in = lvl < levels;
+                        // (lanes past the last level read its row and drop the result)
+                        const unsigned short* row = level_kge + (long long)(in ? lvl : levels - 1) * stride;
+                        long long ct = 0;
+                        if (stride == 16) {
+                            const uint4 r0 = *reinterpret_cast<const uint4*>(row);
+                            const uint4 r1 = *reinterpret_cast<const uint4*>(row + 8);
+                            const unsigned w[8] = {r0.x, r0.y, r0.z, r0.w, r1.x, r1.y, r1.z, r1.w};
+#pragma unroll
+                            for (int k = 0; k < 16; ++k) {
+                                const unsigned kge = (k & 1) ? (w[k >> 1] >> 16) : (w[k >> 1] & 0xffffu);
+                                if (k < nc) ct += count_of(k) * (long long)kge;   // uniform
+                            }
+                        } else if constexpr (L < kWave) {
+#pragma unroll
+                            for (int k = 0; k < L; ++k)
+                                if (k < nc) ct += count_of(k) * (long long)row[k];
+                        } else {
+                            for (int k = 0; k < nc; ++k) ct += count_of(k) * (long long)row[k];
+                        }
+                        if (in && ct < budget) { under += 1; best = ct > best ? ct : best; }
+                    }
+                    const int t = group_sum<int, L>(under);                // the first level that reaches the budget
+                    const int j = block * kLevelBlock + t;                 // tau = level j
+                    count_gt = group_max<L>(best);
+                    tau_bits = level_bits[j];
+                    if (sl < nc) {
+                        const int ge = level_kge[(long long)j * stride + sl];
+                        const int gt = j > 0 ? level_kge[(long long)(j - 1) * stride + sl] : 0;
+                        k_mine = gt;
+                        tied_mine = ge - gt;
+                        // every usable gain of a class the shard holds is above tau and the sequence
+                        // goes on beyond the tables: gains are missing from the counts
+                        if (n_mine > 0 && gt == usable && (long long)usable < limit) ok = false;
+                        const double a = src.alpha0 + (double)sl, b = src.beta0 + (double)(g0 - sl);
+                        double e = surv_table[sl * depth + (gt < depth ? gt : depth - 1)];
+                        if (gt == depth) e = surv_next(e, b, a + b, (double)(depth - 1));
+                        e_mine = e;
+                    }
+                    ok = ((__ballot(!ok) >> shift) & kGroupMask) == 0;
+                    tie_prompts = group_sum<long long, L>(tied_mine ? (long long)n_mine : 0ll);
+                }
+            }
+            if (!ok) {
+                defer = true;
+            } else {
+                const long long r = budget - count_gt;
+                if (summary && sl == 0) {
+                    summary[shard].tau = budget > 0 ? __longlong_as_double((long long)tau_bits) : 0.0;
+                    summary[shard].count_gt = count_gt;
+                    summary[shard].tie_units = r;
+                    summary[shard].tie_prompts = tie_prompts;
+                }
+                gs.k[sl] = k_mine;
+                gs.tied[sl] = tied_mine;
+                gs.e[sl] = e_mine;
+                // (the group's own lanes read them back below: a wavefront's LDS operations complete in order)
+
+                // ---- 3. outputs
+                const long long off_base = kOff != 0 ? (long long)g0 * lo_i + before : 0;
+                long long rank_base = 0, given = 0;       // tied prompts / units handed out before this tile
+                for (long long i0 = lo_i; i0 < hi_i; i0 += L) {
+                    const long long i = i0 + sl;
+                    const bool in = i < hi_i;
+                    int x = 0;
+                    if (in) {
+                        x = src.c[i];
+                        x = x < 0 ? 0 : (x > g0 ? g0 : x);
+                    }
+                    const int kk = in ? gs.k[x] : 0;
+                    const bool td = in && gs.tied[x] != 0;
+                    const unsigned long long tied_mask = (__ballot(td) >> shift) & kGroupMask;
+                    const long long rank = rank_base + __popcll(tied_mask & ((1ull << sl) - 1ull));
+                    const bool win = td && rank < r;
+                    const int dd = kk + (win ? 1 : 0);
+                    const int units = in ? g0 + dd : 0;
+                    const long long incl = group_incl_scan<L>((long long)units, sl);
+                    if (in) {
+                        delta[i] = dd;
+                        if (util) {
+                            double e = gs.e[x];
+                            if (win) {
+                                const double a = src.alpha0 + (double)x, b = src.beta0 + (double)(g0 - x);
+                                e = surv_next(e, b, a + b, (double)kk);
+                            }
+                            util[i] = 1.0 - e;
+                        }
+                        if (kOff != 0) {
+                            const long long off = off_base + given + incl - units;
+                            if (kOff == 1) {
+                                reinterpret_cast<int32_t*>(group_off)[i] = (int32_t)off;
+                                if (i == n - 1) {
+                                    reinterpret_cast<int32_t*>(group_off)[n] = (int32_t)(off + units);
+                                    if (off + units >= (1ll << 31)) report(dev_status, HORA_ERR_RANGE);   // total does not fit
+                                }
+                            } else {
+                                reinterpret_cast<long long*>(group_off)[i] = off;
+                                if (i == n - 1) reinterpret_cast<long long*>(group_off)[n] = off + units;
+                            }
+                        }
+                    }
+                    rank_base += __popcll(tied_mask);
+                    given += __shfl(incl, L - 1, L);
                 }
             }
         }
-        rank_base += __popcll(tied_mask);
-        given += __shfl(incl, kWave - 1, kWave);
+    }
+    if constexpr (!kFused) {
+        if (defer && sl == 0) todo[1 + atomicAdd(&todo[0], 1)] = (int)shard;
+    } else {
+        // ---- the shards that are left: one after the other, the whole workgroup on each
+        if (defer && sl == 0) s_left[atomicAdd(&s_left_n, 1)] = slot;
+        __syncthreads();
+        const int left = s_left_n;
+        for (int idx = 0; idx < left; ++idx) {
+            shard_by_workgroup<CountsSource, kOff>(src, first_shard + s_left[idx], n, g0, n_shards, shard_off,
+                                                   shard_budget, cap, prefix, tables ? depth : 0, gain_table,
+                                                   surv_table, delta, util, group_off, summary, dev_status);
+            __syncthreads();   // the LDS state is reused by the next shard
+        }
+        // ---- no tables yet: workgroup 0 leaves them for the next call
+        if (!tables && blockIdx.x == 0 && depth > 0)
+            build_shard_tables(g0, src.alpha0, src.beta0, depth, usable, key, gain_table, surv_table, level_bits,
+                               level_kge, nullptr);
     }
 }
 
@@ -985,46 +1101,82 @@ extern "C" int hora_allocate_sharded(int64_t n, int32_t g0, const int32_t* c, do
     long long* prefix = group_off ? w.prefix : nullptr;
     const int depth = table_depth(g0, delta_max);
     const int usable = (delta_max > 0 && delta_max < depth) ? delta_max : depth;   // gains l < cap only
-    const unsigned setup_blocks = 2 + (group_off ? (unsigned)((n_shards + kPrefixChunk - 1) / kPrefixChunk) : 0u);
     if (group_off && n == 0) hipLaunchKernelGGL(k_store_zero_offset, 1, 1, 0, s, group_off, off_t == HORA_I64 ? 1 : 0);
-    hipLaunchKernelGGL(k_shard_setup, dim3(setup_blocks), dim3(kPrefixThreads), 0, s, (long long)n_shards,
-                       (const long long*)shard_budget, prefix, (int)g0, alpha0, beta0, depth, usable, w.key,
-                       w.gain_table, w.surv_table, w.level_bits, w.level_kge, w.todo);
     CountsSource src{c, g0, alpha0, beta0};
     const int cap = delta_max > 0 ? delta_max : 0;
     const int mode = group_off ? (off_t == HORA_I32 ? 1 : 2) : 0;
-    // small shards: a wavefront per shard first; what it cannot settle is flagged for the
-    // workgroup-per-shard kernel
+    const int nc = g0 + 1;
+    // small shards: L lanes per shard; what the tables cannot settle is taken by the same
+    // workgroup with the workgroup-per-shard code
     const bool waves = depth > 0 && n <= (long long)n_shards * kWaveShardMeanMax;
-    if (waves) {
-        const unsigned blocks = (unsigned)((n_shards + kShardWaves - 1) / kShardWaves);
-#define HORA_LAUNCH_WAVES(M)                                                                                     \
-    hipLaunchKernelGGL((k_shard_allocate_waves<M>), dim3(blocks), dim3(kShardThreads), 0, s, src, (long long)n,   \
-                       (long long)n_shards, (const long long*)shard_off, (const long long*)shard_budget, cap,    \
-                       prefix, depth, usable, w.surv_table, w.level_bits, w.level_kge, w.todo, delta, util,      \
-                       group_off, summary, dev_status)
-        if (mode == 0) HORA_LAUNCH_WAVES(0);
-        else if (mode == 1) HORA_LAUNCH_WAVES(1);
-        else HORA_LAUNCH_WAVES(2);
-#undef HORA_LAUNCH_WAVES
+    // few shards: no set-up launch (the groups add up the earlier budgets themselves; tables that
+    // are missing are built at the end of the call, for the next one)
+    const bool inline_setup = waves && n_shards <= kInlineShards;
+    if (!inline_setup) {
+        // shards per prefix-sum workgroup: a multiple of the workgroup size, at most kPrefixGroups workgroups
+        long long chunk = (n_shards + kPrefixGroups - 1) / kPrefixGroups;
+        chunk = (chunk + kPrefixThreads - 1) / kPrefixThreads * kPrefixThreads;
+        const unsigned setup_blocks = 2 + (group_off ? (unsigned)((n_shards + chunk - 1) / chunk) : 0u);
+        hipLaunchKernelGGL(k_shard_setup, dim3(setup_blocks), dim3(kPrefixThreads), 0, s, (long long)n_shards, chunk,
+                           (const long long*)shard_budget, prefix, (int)g0, alpha0, beta0, depth, usable, w.key,
+                           w.gain_table, w.surv_table, w.level_bits, w.level_kge, w.todo);
+    } else {
+        prefix = nullptr;
     }
-#define HORA_LAUNCH_SHARDS(M)                                                                                   \
-    do {                                                                                                        \
-        if (waves)                                                                                              \
-            hipLaunchKernelGGL((k_shard_allocate_todo<CountsSource, M>), dim3(todo_blocks), dim3(kShardThreads), \
-                               0, s, src, (long long)n, (int)g0, (long long)n_shards,                           \
-                               (const long long*)shard_off, (const long long*)shard_budget, cap, prefix, depth, \
-                               w.gain_table, w.surv_table, delta, util, group_off, summary, w.todo, dev_status); \
-        else                                                                                                    \
-            hipLaunchKernelGGL((k_shard_allocate<CountsSource, M>), dim3((unsigned)n_shards),                   \
-                               dim3(kShardThreads), 0, s, src, (long long)n, (int)g0, (long long)n_shards,      \
-                               (const long long*)shard_off, (const long long*)shard_budget, cap, prefix, depth, \
-                               w.gain_table, w.surv_table, delta, util, group_off, summary, dev_status);        \
+    if (waves) {
+        const long long mean = n_shards > 0 ? (n + n_shards - 1) / n_shards : 0;
+        const int lanes = (nc <= 16 && mean <= 16) ? 16 : (nc <= 32 && mean <= 32) ? 32 : 64;
+#define HORA_LAUNCH_WAVES(M, LL, FUSED)                                                                          \
+    do {                                                                                                          \
+        const long long per_block = (long long)kShardWaves * (kWave / LL);                                        \
+        const unsigned blocks = (unsigned)((n_shards + per_block - 1) / per_block);                               \
+        hipLaunchKernelGGL((k_shard_allocate_waves<M, LL, FUSED>), dim3(blocks), dim3(kShardThreads), 0, s, src,   \
+                           (long long)n, (long long)n_shards, (const long long*)shard_off,                        \
+                           (const long long*)shard_budget, cap, (const long long*)prefix, depth, usable, w.key,   \
+                           w.gain_table, w.surv_table, w.level_bits, w.level_kge, w.todo, delta, util, group_off, \
+                           summary, dev_status);                                                                  \
     } while (0)
-    const unsigned todo_blocks = (unsigned)(n_shards < 1024 ? n_shards : 1024);
-    if (mode == 0) HORA_LAUNCH_SHARDS(0);
-    else if (mode == 1) HORA_LAUNCH_SHARDS(1);
-    else HORA_LAUNCH_SHARDS(2);
+#define HORA_LAUNCH_WAVES_L(M, FUSED)                               \
+    do {                                                            \
+        if (lanes == 16) HORA_LAUNCH_WAVES(M, 16, FUSED);           \
+        else if (lanes == 32) HORA_LAUNCH_WAVES(M, 32, FUSED);      \
+        else HORA_LAUNCH_WAVES(M, 64, FUSED);                       \
+    } while (0)
+#define HORA_LAUNCH_WAVES_F(M)                                      \
+    do {                                                            \
+        if (inline_setup) HORA_LAUNCH_WAVES_L(M, true);             \
+        else HORA_LAUNCH_WAVES_L(M, false);                         \
+    } while (0)
+        if (mode == 0) HORA_LAUNCH_WAVES_F(0);
+        else if (mode == 1) HORA_LAUNCH_WAVES_F(1);
+        else HORA_LAUNCH_WAVES_F(2);
+#undef HORA_LAUNCH_WAVES_F
+#undef HORA_LAUNCH_WAVES_L
+#undef HORA_LAUNCH_WAVES
+        if (!inline_setup) {   // the shards the groups could not settle (usually none)
+            const unsigned todo_blocks = (unsigned)(n_shards < 1024 ? n_shards : 1024);
+#define HORA_LAUNCH_TODO(M)                                                                                         \
+    hipLaunchKernelGGL((k_shard_allocate_todo<CountsSource, M>), dim3(todo_blocks), dim3(kShardThreads), 0, s, src, \
+                       (long long)n, (int)g0, (long long)n_shards, (const long long*)shard_off,                    \
+                       (const long long*)shard_budget, cap, (const long long*)prefix, depth,                       \
+                       (const double*)w.gain_table, (const double*)w.surv_table, delta, util, group_off, summary,  \
+                       (const int*)w.todo, dev_status)
+            if (mode == 0) HORA_LAUNCH_TODO(0);
+            else if (mode == 1) HORA_LAUNCH_TODO(1);
+            else HORA_LAUNCH_TODO(2);
+#undef HORA_LAUNCH_TODO
+        }
+    } else {
+#define HORA_LAUNCH_SHARDS(M)                                                                                   \
+    hipLaunchKernelGGL((k_shard_allocate<CountsSource, M>), dim3((unsigned)n_shards), dim3(kShardThreads), 0, s, \
+                       src, (long long)n, (int)g0, (long long)n_shards, (const long long*)shard_off,            \
+                       (const long long*)shard_budget, cap, (const long long*)prefix, depth,                    \
+                       (const double*)w.gain_table, (const double*)w.surv_table, delta, util, group_off,        \
+                       summary, dev_status)
+        if (mode == 0) HORA_LAUNCH_SHARDS(0);
+        else if (mode == 1) HORA_LAUNCH_SHARDS(1);
+        else HORA_LAUNCH_SHARDS(2);
 #undef HORA_LAUNCH_SHARDS
+    }
     return hipGetLastError() == hipSuccess ? HORA_OK : HORA_ERR_HIP;
 }
