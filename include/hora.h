@@ -209,6 +209,19 @@ int hora_allocate_baseline(int64_t n, int32_t g0, const int32_t *c, double alpha
                            int32_t *dev_status, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Allocation statistics per Phase-A outcome (Sec. 4, "Allocation dynamics" and its figure: the
+ * share of the prompts with c_i = k and the share of the Phase-B budget they received):
+ *   class_count[k]  = #{i : c[i] = k},   class_budget[k] = sum of delta[i] over those prompts,
+ * k = 0 .. g0.  Works on the result of any of the allocation calls.
+ *
+ * c, delta    : device, n int32 each (c[i] outside [0, g0] or delta[i] < 0: HORA_ERR_RANGE in
+ *               dev_status, the prompt is left out).
+ * class_count, class_budget : device out, g0 + 1 int64 each.  g0 <= HORA_CLASS_MAX_G0.
+ */
+int hora_allocation_shares(int64_t n, int32_t g0, const int32_t *c, const int32_t *delta,
+                           int64_t *class_count, int64_t *class_budget, int32_t *dev_status, void *stream);
+
+/*
  * Bytes of workspace hora_allocate_sharded needs for n_shards shards: the gain tables of
  * the G0+1 classes (kept from call to call and reused while the prior, G0 and the cap
  * stay the same) and the prefix sums of the shard budgets.  Device memory, 256-byte

@@ -10,7 +10,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(ROOT, "include")
 LIB = os.path.join(HERE, "libhora.so")
-SOURCES = ["hora_allocate.hip", "hora_allocate_bisect.hip", "hora_allocate_sharded.hip", "hora_advantage.hip", "hora_broadcast.hip", "hora_passk.hip", "hora_misc.hip"]
+SOURCES = ["hora_allocate.hip", "hora_allocate_bisect.hip", "hora_allocate_sharded.hip", "hora_advantage.hip", "hora_broadcast.hip", "hora_passk.hip", "hora_shares.hip", "hora_misc.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

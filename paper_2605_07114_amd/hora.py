@@ -37,6 +37,7 @@ EXPORTS = (
     "hora_token_broadcast_workspace_bytes", "hora_allocate_sharded", "hora_allocate_sharded_workspace_bytes",
     "hora_response_weights", "hora_allocate_baseline", "hora_pass_at_k", "hora_pass_at_k_workspace_bytes",
     "hora_allocate_static", "hora_token_broadcast2", "hora_token_broadcast2_workspace_bytes",
+    "hora_allocation_shares",
 )
 
 
@@ -73,6 +74,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.hora_allocate.restype = ctypes.c_int
     lib.hora_allocate_static.argtypes = [i64, i32, p, f64, f64, i64, i32, i32, p, p, p, i32, p, p, p]
     lib.hora_allocate_static.restype = ctypes.c_int
+    lib.hora_allocation_shares.argtypes = [i64, i32, p, p, p, p, p, p]
+    lib.hora_allocation_shares.restype = ctypes.c_int
     lib.hora_allocate_baseline.argtypes = [i64, i32, p, f64, f64, i64, i32, i32, p, p, p, i32, p, p, p, sz, p]
     lib.hora_allocate_baseline.restype = ctypes.c_int
     lib.hora_allocate_posterior.argtypes = [i64, i32, p, p, i64, i32, p, p, p, i32, p, p, p, sz, p]
@@ -201,6 +204,19 @@ def hora_allocate_static(c: torch.Tensor, g0: int, budget: int, delta: torch.Ten
         n, int(g0), _ptr(c), float(alpha0), float(beta0), int(budget), int(delta_max), int(method),
         _ptr(delta), _ptr(util), _ptr(group_off), _itype(group_off) if group_off is not None else I32,
         _ptr(summary), _ptr(dev_status), _stream(stream)), "hora_allocate_static")
+
+
+def hora_allocation_shares(c: torch.Tensor, delta: torch.Tensor, g0: int, class_count: torch.Tensor,
+                           class_budget: torch.Tensor, dev_status: torch.Tensor, stream=None) -> None:
+    n = c.numel()
+    _expect(c, torch.int32, n, "c")
+    _expect(delta, torch.int32, n, "delta")
+    _expect(class_count, torch.int64, g0 + 1, "class_count")
+    _expect(class_budget, torch.int64, g0 + 1, "class_budget")
+    _expect(dev_status, torch.int32, 1, "dev_status")
+    _check(load_library().hora_allocation_shares(n, int(g0), _ptr(c), _ptr(delta), _ptr(class_count),
+                                                 _ptr(class_budget), _ptr(dev_status), _stream(stream)),
+           "hora_allocation_shares")
 
 
 def hora_allocate_baseline(c: torch.Tensor, g0: int, budget: int, rule: int, delta: torch.Tensor,

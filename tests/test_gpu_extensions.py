@@ -160,3 +160,40 @@ def test_pass_at_k(gpu, oracle):
     hora.hora_pass_at_k(dev(torch, n), dev(torch, np.array([1, 9], dtype=np.int32)), [4], mean, sess.dev_status, ws)
     assert sess.status() == hora.ERR_RANGE
     sess.dev_status.zero_()
+
+
+def test_allocation_shares_per_class(gpu, oracle):
+    """Sec. 4, allocation dynamics: prompts and Phase-B budget per value of c, against np.bincount on the
+    oracle's allocation (integers, exact), for the batch and the sharded call."""
+    from paper_2605_07114_amd import workloads as wl
+    sess, torch, hora = gpu
+    for w in (wl.TINY, wl.SMALL, wl.SKEWED, wl.LARGE_ALLOC, wl.PAPER_STEP):
+        a = wl.phase_a(w)
+        if w is wl.PAPER_STEP:
+            bounds, budgets = wl.equal_shards(w.n, wl.PAPER_STEP_SHARDS, w.budget)
+            want = oracle.allocate_sharded(a.c, w.g0, bounds, budgets)
+            got = sess.allocate_sharded(dev(torch, a.c), w.g0, dev(torch, bounds), dev(torch, budgets))
+        else:
+            want = oracle.allocate(a.c, w.g0, w.budget, delta_max=w.delta_max)
+            got = sess.allocate(dev(torch, a.c), w.g0, w.budget, delta_max=w.delta_max)
+        count = torch.full((w.g0 + 1,), -1, dtype=torch.int64, device="cuda:0")
+        budget = torch.full((w.g0 + 1,), -1, dtype=torch.int64, device="cuda:0")
+        print(f"allocation_shares {w.name} n={w.n}", flush=True)
+        hora.hora_allocation_shares(dev(torch, a.c), got.delta, w.g0, count, budget, sess.dev_status)
+        assert sess.status() == 0
+        assert np.array_equal(count.cpu().numpy(), np.bincount(a.c, minlength=w.g0 + 1))
+        assert np.array_equal(budget.cpu().numpy(),
+                              np.bincount(a.c, weights=want, minlength=w.g0 + 1).astype(np.int64))
+        assert int(budget.sum()) == w.budget
+    # nothing to count; data out of range is reported and left out
+    count = torch.full((5,), -1, dtype=torch.int64, device="cuda:0")
+    budget = torch.full((5,), -1, dtype=torch.int64, device="cuda:0")
+    empty = torch.zeros(0, dtype=torch.int32, device="cuda:0")
+    hora.hora_allocation_shares(empty, empty, 4, count, budget, sess.dev_status)
+    assert sess.status() == 0 and not count.any() and not budget.any()
+    c = dev(torch, np.array([0, 4, 9, 2, -1, 4], dtype=np.int32))
+    d = dev(torch, np.array([3, 1, 5, 0, 2, 7], dtype=np.int32))
+    hora.hora_allocation_shares(c, d, 4, count, budget, sess.dev_status)
+    assert sess.status() == hora.ERR_RANGE
+    sess.dev_status.zero_()
+    assert count.cpu().tolist() == [1, 0, 1, 0, 2] and budget.cpu().tolist() == [3, 0, 0, 0, 8]
