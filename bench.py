@@ -28,8 +28,8 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
 # the same counters read for a plain device copy of known size); the figures and the commands
 # are in profiles/hbm_traffic_large_alloc_large_bcast.txt.  Set to None when a kernel named
 # there changes.
-TRAFFIC_BROADCAST_BYTES = 692415223     # k_row_desc + k_token_fill, large_bcast
-TRAFFIC_ALLOCATE_BYTES = 25556462       # k_class_hist + k_class_write, large_alloc
+TRAFFIC_BROADCAST_BYTES = 692395767     # k_row_desc + k_token_fill, large_bcast
+TRAFFIC_ALLOCATE_BYTES = 25551470       # k_class_hist + k_class_write, large_alloc
 
 
 def ensure_library():
@@ -211,6 +211,8 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--skip-extras", action="store_true",
+                    help="leave out the size sweep and the entry points next to the headline path (counter runs)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain device copy of the token buffer (known size), for scaling HBM counters")
     args = ap.parse_args()
@@ -307,9 +309,11 @@ def main():
     plain_mean, _ = per_launch_events(torch, lambda: plain1.copy_(c1), steps, 3)
     alloc_mean, alloc_min = per_launch_events(torch, step_alloc, steps, 3)
     del plain1
-    sweep = allocation_sweep(torch, hora, sess, max(steps // 10, 5))
-    ws = sess.workspace(w1.n, w1.g0)
-    extras = other_paths(torch, hora, wl, sess, a1, c1, w1, delta1, util1, goff1, ws, max(steps // 10, 5))
+    sweep, extras = None, None
+    if not args.skip_extras:
+        sweep = allocation_sweep(torch, hora, sess, max(steps // 10, 5))
+        ws = sess.workspace(w1.n, w1.g0)
+        extras = other_paths(torch, hora, wl, sess, a1, c1, w1, delta1, util1, goff1, ws, max(steps // 10, 5))
 
     result = {
         "metric": "prompts allocated/s at N=1M; advantage broadcast GB/s as % of HBM peak",
