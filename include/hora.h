@@ -167,7 +167,7 @@ int hora_allocate(int64_t n, int32_t g0, const int32_t *c, double alpha0, double
  *    that call outside a stream capture.
  */
 #define HORA_STATIC_MAX_PROMPTS (1 << 22)
-#define HORA_STATIC_SCRATCH_BYTES (16u << 20)
+#define HORA_STATIC_SCRATCH_BYTES (64u << 20)
 int hora_allocate_static(int64_t n, int32_t g0, const int32_t *c, double alpha0, double beta0,
                          int64_t budget, int32_t delta_max, int32_t method, int32_t *delta, double *util,
                          void *group_off, int32_t off_t, hora_alloc_summary *summary,

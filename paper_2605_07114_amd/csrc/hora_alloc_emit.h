@@ -24,7 +24,7 @@ constexpr int kTableCap = kMaxClasses * kMinRow;   // doubles per table (2048)
 constexpr unsigned kTiedBit = 0x80000000u;
 
 // ---- threshold search (any posterior) ------------------------------------------------
-constexpr int kWinOct = 8;        // octaves of detail a tile keeps of its coarse count (the last ones it walked)
+constexpr int kWinOct = 4;        // octaves of detail a tile keeps of its coarse count (the last ones it walked)
 constexpr int kSubBins = 4;       // intervals per octave of the coarse count (two mantissa bits)
 constexpr int kListCap = 4096;    // gains a workgroup can set aside for the passes that follow
 constexpr long long kCollectMax = (long long)kMaxBlocks * kListCap / 2;   // brackets up to this size are set aside
@@ -44,7 +44,8 @@ struct AllocHeader {              // 256 bytes at the start of the workspace
     unsigned long long tau;       // tau once the search has ended
     unsigned int lists_ok;        // no workgroup ran out of room in its list (written between passes)
     unsigned int pad0;
-    unsigned long long pad[21];
+    unsigned long long ck_top;    // the coarse count left every prompt's walk state at its first gain <= this pattern
+    unsigned long long pad[20];
 };
 static_assert(sizeof(Bracket) == 32, "bracket size");
 static_assert(sizeof(AllocHeader) == 256, "header size");
@@ -58,7 +59,7 @@ struct CoarseSlot {
     int stop;                                    // last octave walked
     int exhausted;                               // no prompt of the tile has a gain below it (cap, depth bound, underflow)
 };
-static_assert(sizeof(CoarseSlot) == 272, "coarse slot size");
+static_assert(sizeof(CoarseSlot) == 144, "coarse slot size");
 
 struct SelectBins : TallyBins {};  // per-interval tallies of one workgroup in one search pass
 // One SelectBins per workgroup (kMaxBlocks of them) and one more for their totals: every
@@ -95,12 +96,15 @@ struct Workspace {
     unsigned long long* lists;   // [kMaxBlocks][kListCap] gains set aside by the search passes
     int* list_count;             // [kMaxBlocks] entries in each list, -1 when it did not fit
     CoarseSlot* coarse;          // [tiles]
+    double* ck_g;                // [n] walk state of every prompt between the kernels of the search: a gain ...
+    int32_t* ck_l;               // [n] ... and its index l
     size_t bytes;
 };
 
 // Everything but the coarse slots is sized for kMaxBlocks workgroups and kMaxClasses classes
-// whatever n and g0 are; the coarse slots (one per tile of kTile prompts) come last, so that a
-// workspace that served one batch serves every smaller one.
+// whatever n and g0 are; what grows with n (the coarse slots, one per tile of kTile prompts, and
+// the walk states, one per prompt) comes last, so that a workspace that served one batch serves
+// every smaller one.
 inline Workspace carve(void* base, int64_t n) {
     Workspace w;
     char* ptr = (char*)base;
@@ -126,6 +130,11 @@ inline Workspace carve(void* base, int64_t n) {
     w.coarse = (CoarseSlot*)(ptr + off);
     const size_t tiles = (size_t)((n > 0 ? n : 1) + kTile - 1) / kTile;
     off += align256(tiles * sizeof(CoarseSlot));
+    const size_t padded = tiles * (size_t)kTile;
+    w.ck_g = (double*)(ptr + off);
+    off += align256(padded * sizeof(double));
+    w.ck_l = (int32_t*)(ptr + off);
+    off += align256(padded * sizeof(int32_t));
     w.bytes = off;
     return w;
 }

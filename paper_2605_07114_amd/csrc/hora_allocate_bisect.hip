@@ -101,23 +101,177 @@ __device__ __forceinline__ bool load_posteriors(const PosteriorSource& src, long
 }
 
 // ----------------------------------------------------------------------------------
-// 1. Coarse count.  One tile of kTile prompts at a time (kItems per thread, walked in
-// lockstep so that their divisions overlap).  Octave by octave from the top: every prompt
-// walks its gains down to the octave's lower end, each gain counted in its quarter octave by
-// wavefront ballots (scalar counters, no atomics per gain); after every octave the tile's
-// running total is compared with what it needs: its share of the budget plus a margin, so
-// that tiles of similar prompts all stop in the same octave (any stopping rule that waits
-// for the share is correct; the margin only makes it likely that the octave in which the
-// global count reaches the budget has been walked completely by every tile).
-// LDS keeps a ring of kRing octaves of counts; the slot keeps the last kWinOct.
+// Walk states between the kernels (one gain and its index l per prompt; kItems per thread).
 // ----------------------------------------------------------------------------------
+__device__ __forceinline__ void load_states(const double* __restrict__ ck_g, const int32_t* __restrict__ ck_l,
+                                            long long pos, long long end, double (&g)[kItems], double (&lf)[kItems]) {
+    if (pos + kItems <= end) {   // (the arrays are 256-byte aligned and pos is a multiple of kItems)
+#pragma unroll
+        for (int q = 0; q < kItems / 2; ++q) {
+            const v2d x = *reinterpret_cast<const v2d*>(ck_g + pos + 2 * q);
+            g[2 * q] = x.x; g[2 * q + 1] = x.y;
+        }
+        const v4i l = *reinterpret_cast<const v4i*>(ck_l + pos);
+        lf[0] = (double)l.x; lf[1] = (double)l.y; lf[2] = (double)l.z; lf[3] = (double)l.w;
+    } else {
+#pragma unroll
+        for (int j = 0; j < kItems; ++j) {
+            g[j] = pos + j < end ? ck_g[pos + j] : 0.0;
+            lf[j] = pos + j < end ? (double)ck_l[pos + j] : 0.0;
+        }
+    }
+}
+
+__device__ __forceinline__ void store_states(double* __restrict__ ck_g, int32_t* __restrict__ ck_l, long long pos,
+                                             long long end, const double (&g)[kItems], const double (&lf)[kItems]) {
+    int l[kItems];
+#pragma unroll
+    for (int j = 0; j < kItems; ++j) l[j] = (int)lf[j];
+    store_items<v2d, double>(ck_g, pos, end, true, g);
+    store_items<v4i, int32_t>(ck_l, pos, end, true, l);
+}
+
+// ----------------------------------------------------------------------------------
+// 1a. How deep to walk: an estimate from a sample.  kEstSamples prompts spread evenly over the
+// batch are walked octave by octave by the first kEstWaves wavefronts of every workgroup (the
+// same prompts and the same arithmetic everywhere, so all workgroups agree) until the sample
+// has seen its share of the budget and a margin.  The estimate decides only how much work
+// the coarse count does in one go and where the walk states are kept; what the coarse count
+// guarantees does not depend on it, so the sample's gains are only approximated (a reciprocal
+// approximation and a multiplication per step: a quarter of the instructions of a division).
+//   est : the octave in which the sample's count reached its share (walk to its bottom)
+//   ck  : the octave at whose top the walk states are kept: est, or est - 1 when the sample's
+//         count at the bottom of est - 1 was already close to the share
+// Octaves whose gains all exceed n / budget are walked in one go: a prompt has fewer than
+// 1 / x gains above x (they decrease and sum to at most 1), so fewer than `budget` gains
+// exceed n / budget and tau lies below.
+// ----------------------------------------------------------------------------------
+constexpr int kEstWaves = 4;
+constexpr int kEstItems = 2;
+constexpr int kEstSamples = kEstWaves * kWave * kEstItems;   // 512
+
+struct EstimateShared {
+    // [octave & 3]; a wavefront may be an octave ahead of another that still reads the last
+    // octave's entries, so every octave has entries of its own, cleared two octaves ahead
+    unsigned long long count[4];   // gains of the sample in that octave
+    int alive[4];                  // a sample prompt has gains left below that octave
+};
+
+template <class Src>
+__device__ __forceinline__ void estimate_depth(const Src& src, long long n, long long budget, long long limit,
+                                               EstimateShared& es, int& est, int& ck) {
+    const bool walker = threadIdx.x < kEstWaves * kWave;
+    const double limit_d = (double)limit;
+    double b[kEstItems], s[kEstItems], g[kEstItems], lf[kEstItems];
+    unsigned long long gb[kEstItems];
+    bool alive[kEstItems];
+#pragma unroll
+    for (int j = 0; j < kEstItems; ++j) {
+        double a = 1.0;
+        b[j] = 1.0;
+        if (walker) {
+            const long long q = (long long)threadIdx.x * kEstItems + j;
+            src.load((long long)(((unsigned long long)q * (unsigned long long)n) / kEstSamples), a, b[j]);
+        }
+        s[j] = a + b[j];
+        g[j] = gain_first(a, s[j]);
+        lf[j] = 0.0;
+        gb[j] = gain_bits(g[j]);
+        alive[j] = walker && limit > 0 && gb[j] != 0ull;
+    }
+    if (threadIdx.x < 4) {
+        es.count[threadIdx.x] = 0ull;
+        es.alive[threadIdx.x] = 0;
+    }
+    __syncthreads();
+    // the sample's share of the budget, rounded up (budget <= 2^51: no overflow)
+    const unsigned long long want = ((unsigned long long)budget * kEstSamples + (unsigned long long)n - 1ull) /
+                                    (unsigned long long)n;
+    const unsigned long long need = want + (want >> 3) + 16ull;
+    const unsigned long long sure = want - (want >> 3);
+    const unsigned long long ratio = (unsigned long long)budget / (unsigned long long)n;
+    const int lumped = ratio >= 2ull ? 63 - __clzll((long long)ratio) : 0;   // octaves 0 .. lumped - 1 lie above n / budget
+    int o = lumped > 0 ? lumped - 1 : 0;
+    const int first = o;
+    unsigned long long cum = 0ull;      // the sample's count at the bottom of octave o (the same in every thread)
+    unsigned long long before = 0ull;   // ... and of the octave above it
+    for (;; ++o) {
+        if (walker) {
+            const unsigned long long bottom = octave_top(o) - kOctave;
+            int cnt = 0;
+            bool any;
+            do {
+                any = false;
+#pragma unroll
+                for (int j = 0; j < kEstItems; ++j) {
+                    const bool act = alive[j] && gb[j] > bottom;
+                    if (act) {
+                        // (an estimate: the hardware's reciprocal approximation instead of the division)
+                        g[j] = (g[j] * (b[j] + lf[j])) * __builtin_amdgcn_rcp(s[j] + (lf[j] + 1.0));
+                        lf[j] += 1.0;
+                        gb[j] = gain_bits(g[j]);
+                        alive[j] = lf[j] < limit_d && gb[j] != 0ull;
+                        ++cnt;
+                    }
+                    any |= act;
+                }
+            } while (any);
+            bool mine_alive = false;
+#pragma unroll
+            for (int j = 0; j < kEstItems; ++j) mine_alive |= alive[j];
+            const bool wave_alive = __ballot(mine_alive) != 0ull;
+            cnt = wave_last_i32(wave_incl_scan_i32(cnt));
+            if (lane_id() == 0) {
+                if (cnt) atomicAdd(&es.count[o & 3], (unsigned long long)(unsigned)cnt);
+                if (wave_alive) es.alive[o & 3] = 1;
+            }
+        }
+        __syncthreads();
+        before = cum;
+        cum += es.count[o & 3];
+        if (cum >= need || es.alive[o & 3] == 0 || o == kMaxOctave) break;   // uniform
+        if (threadIdx.x == 0) {   // (nobody reads or sets these now)
+            es.count[(o + 2) & 3] = 0ull;
+            es.alive[(o + 2) & 3] = 0;
+        }
+    }
+    est = o;
+    ck = (o > first && before > sure) ? o - 1 : o;   // (before: the count at the bottom of octave o - 1)
+}
+
+// ----------------------------------------------------------------------------------
+// 1b. Coarse count.  One tile of kTile prompts at a time, kItems per thread, walked in
+// lockstep so that their divisions overlap.  Every gain down to the bottom of the estimated
+// octave is counted in one go, per quarter octave of the last kWinOct octaves (a counter per
+// thread and quarter octave in LDS: no conflicts, no reductions per gain), and the first state
+// of every walk at or below the top of octave `ck` is kept for the kernels that follow.  A
+// tile that has not seen its share of the budget by then goes on octave by octave (counts by
+// wavefront ballots), comparing its running total with what it needs after every octave: its
+// share plus a margin (any stopping rule that waits for the share is correct; the margin only
+// makes it likely that the octave in which the global count reaches the budget has been
+// walked completely by every tile).  LDS keeps a ring of kRing octaves of counts; the slot
+// keeps the last kWinOct.
+// ----------------------------------------------------------------------------------
+constexpr int kFine = kWinOct * kSubBins;   // quarter octaves counted per thread in the first go
+static_assert(kFine == kBigWaves, "one wavefront adds up one quarter octave");
+
 template <class Src>
 __global__ __launch_bounds__(kBig) void k_bisect_coarse(Src src, long long n, long long budget, long long limit,
                                                         long long chunk, CoarseSlot* __restrict__ slots,
-                                                        int32_t* dev_status) {
+                                                        AllocHeader* __restrict__ hdr, double* __restrict__ ck_g,
+                                                        int32_t* __restrict__ ck_l, int32_t* dev_status) {
+    __shared__ unsigned s_fine[kFine][kBig];
     __shared__ unsigned long long s_cnt[kRing][kSubBins];
-    __shared__ unsigned long long s_total;
+    __shared__ unsigned long long s_total;       // gains counted in the first go
+    __shared__ unsigned long long s_octave[4];   // [octave & 3] gains counted in an octave after it (see EstimateShared)
     __shared__ int s_alive[4];
+    __shared__ EstimateShared s_est;
+    int est, ck;
+    estimate_depth(src, n, budget, limit, s_est, est, ck);
+    const unsigned long long top_ck = octave_top(ck);
+    if (blockIdx.x == 0 && threadIdx.x == 0) hdr->ck_top = top_ck;
+    const unsigned long long est_bottom = octave_top(est) - kOctave;
+    const unsigned long long fine_top = octave_top(est - (kWinOct - 1));   // (above 1.0 when est < kWinOct - 1: no gain lies there)
     const long long base = (long long)blockIdx.x * chunk;
     const long long end = base + chunk < n ? base + chunk : n;
     const int lane = lane_id();
@@ -131,7 +285,7 @@ __global__ __launch_bounds__(kBig) void k_bisect_coarse(Src src, long long n, lo
                                          (unsigned long long)n;
         const unsigned long long need = share + (share >> 5) + 64ull;
         const long long pos = t0 + (long long)threadIdx.x * kItems;
-        double a[kItems], b[kItems], s[kItems], g[kItems], lf[kItems];
+        double a[kItems], b[kItems], s[kItems], g[kItems], lf[kItems], keep_g[kItems], keep_l[kItems];
         unsigned long long gb[kItems];
         bool alive[kItems];
         bad |= !load_posteriors(src, pos, tile_end, a, b) && pos < tile_end;
@@ -142,86 +296,145 @@ __global__ __launch_bounds__(kBig) void k_bisect_coarse(Src src, long long n, lo
             lf[j] = 0.0;
             gb[j] = gain_bits(g[j]);
             alive[j] = pos + j < tile_end && limit > 0 && gb[j] != 0ull;
+            keep_g[j] = g[j];
+            keep_l[j] = 0.0;
         }
         if (threadIdx.x < kRing * kSubBins) (&s_cnt[0][0])[threadIdx.x] = 0ull;
-        if (threadIdx.x < 4) s_alive[threadIdx.x] = 0;
+        if (threadIdx.x < 4) { s_alive[threadIdx.x] = 0; s_octave[threadIdx.x] = 0ull; }
         if (threadIdx.x == 0) s_total = 0ull;
+#pragma unroll
+        for (int f = 0; f < kFine; ++f) s_fine[f][threadIdx.x] = 0u;
         __syncthreads();
-        int o = 0;
-        bool any_alive = false;
-        for (;; ++o) {
-            const unsigned long long top = octave_top(o);
-            const unsigned long long bottom = top - kOctave;
-            // this lane's counts of the four quarter octaves: 8 bits each in one register, moved
-            // to the wide counters before a field can overflow
-            int c0 = 0, c1 = 0, c2 = 0, c3 = 0;
-            unsigned packed = 0u;
-            int rounds = 0;
+        // everything down to the bottom of octave `est` in one go
+        unsigned higher = 0u;   // gains above the counted octaves (a lane sees at most kItems * limit <= 2^22)
+        {
             bool any;
             do {
                 any = false;
 #pragma unroll
                 for (int j = 0; j < kItems; ++j) {
-                    const bool act = alive[j] && gb[j] > bottom;
-                    // 8 * quarter octave of the gain: bits 50 and 51 of (top - pattern)
-                    const unsigned shift8 = ((unsigned)((top - gb[j]) >> 32) >> 15) & 0x18u;
-                    packed += act ? (1u << shift8) : 0u;
+                    const bool act = alive[j] && gb[j] > est_bottom;
                     if (act) {
+                        if (gb[j] > fine_top) ++higher;
+                        else atomicAdd(&s_fine[(unsigned)((fine_top - gb[j]) >> 50)][threadIdx.x], 1u);
+                        const bool above_ck = gb[j] > top_ck;
                         g[j] = gain_next(g[j], b[j], s[j], lf[j]);
                         lf[j] += 1.0;
                         gb[j] = gain_bits(g[j]);
                         alive[j] = lf[j] < limit_d && gb[j] != 0ull;
+                        if (above_ck) { keep_g[j] = g[j]; keep_l[j] = lf[j]; }
                     }
                     any |= act;
                 }
-                if (++rounds == 255 / kItems) {   // uniform
-                    c0 += (int)(packed & 0xffu); c1 += (int)((packed >> 8) & 0xffu);
-                    c2 += (int)((packed >> 16) & 0xffu); c3 += (int)(packed >> 24);
-                    packed = 0u;
-                    rounds = 0;
-                }
-            } while (__ballot(any));
-            c0 += (int)(packed & 0xffu); c1 += (int)((packed >> 8) & 0xffu);
-            c2 += (int)((packed >> 16) & 0xffu); c3 += (int)(packed >> 24);
+            } while (any);
+        }
+        store_states(ck_g, ck_l, pos, tile_end, keep_g, keep_l);
+        {
             bool mine_alive = false;
 #pragma unroll
             for (int j = 0; j < kItems; ++j) mine_alive |= alive[j];
             const bool wave_alive = __ballot(mine_alive) != 0ull;
-            // (a lane counts at most kItems * limit <= 2^22 gains per octave: the sums fit 32 bits)
-            c0 = wave_last_i32(wave_incl_scan_i32(c0));
-            c1 = wave_last_i32(wave_incl_scan_i32(c1));
-            c2 = wave_last_i32(wave_incl_scan_i32(c2));
-            c3 = wave_last_i32(wave_incl_scan_i32(c3));
+            const long long higher_all = wave_total_i64((long long)higher);
             if (lane == 0) {
-                unsigned long long* row = s_cnt[o & (kRing - 1)];
-                if (c0) atomicAdd(&row[0], (unsigned long long)(unsigned)c0);
-                if (c1) atomicAdd(&row[1], (unsigned long long)(unsigned)c1);
-                if (c2) atomicAdd(&row[2], (unsigned long long)(unsigned)c2);
-                if (c3) atomicAdd(&row[3], (unsigned long long)(unsigned)c3);
-                const unsigned long long all = (unsigned long long)(unsigned)c0 + (unsigned)c1 + (unsigned)c2 + (unsigned)c3;
-                if (all) atomicAdd(&s_total, all);
-                if (wave_alive) s_alive[o & 3] = 1;
+                if (higher_all) atomicAdd(&s_total, (unsigned long long)higher_all);
+                if (wave_alive) s_alive[est & 3] = 1;
             }
-            __syncthreads();
-            any_alive = s_alive[o & 3] != 0;
-            if (s_total >= need || !any_alive || o == kMaxOctave) break;   // uniform
-            // room for the octave after the next one (nobody reads or adds to these now)
-            if (threadIdx.x < kSubBins) s_cnt[(o + 2) & (kRing - 1)][threadIdx.x] = 0ull;
-            if (threadIdx.x == 0) s_alive[(o + 2) & 3] = 0;
+        }
+        __syncthreads();   // the counters of all threads are complete
+        {
+            const int f = wave_id();   // this wavefront adds up quarter octave f of the counted octaves
+            long long acc = 0;
+#pragma unroll
+            for (int i = 0; i < kBig / kWave; ++i) acc += (long long)s_fine[f][lane + kWave * i];
+            acc = wave_total_i64(acc);
+            if (lane == 0 && acc) {
+                const int oct = est - (kWinOct - 1) + f / kSubBins;   // (a count can only be non-zero for oct >= 0)
+                s_cnt[oct & (kRing - 1)][f % kSubBins] = (unsigned long long)acc;
+                atomicAdd(&s_total, (unsigned long long)acc);
+            }
+        }
+        __syncthreads();
+        int o = est;
+        bool any_alive = s_alive[o & 3] != 0;
+        unsigned long long total = s_total;   // the tile's running count (the same in every thread)
+        if (total < need && any_alive && o < kMaxOctave) {
+            // short of its share: the tile goes on octave by octave (the ring's rows for the next
+            // two octaves are still zero)
+            for (o = est + 1;; ++o) {
+                const unsigned long long top = octave_top(o);
+                const unsigned long long bottom = top - kOctave;
+                // this lane's counts of the four quarter octaves: 8 bits each in one register, moved
+                // to the wide counters before a field can overflow
+                int c0 = 0, c1 = 0, c2 = 0, c3 = 0;
+                unsigned packed = 0u;
+                int rounds = 0;
+                bool any;
+                do {
+                    any = false;
+#pragma unroll
+                    for (int j = 0; j < kItems; ++j) {
+                        const bool act = alive[j] && gb[j] > bottom;
+                        // 8 * quarter octave of the gain: bits 50 and 51 of (top - pattern)
+                        const unsigned shift8 = ((unsigned)((top - gb[j]) >> 32) >> 15) & 0x18u;
+                        packed += act ? (1u << shift8) : 0u;
+                        if (act) {
+                            g[j] = gain_next(g[j], b[j], s[j], lf[j]);
+                            lf[j] += 1.0;
+                            gb[j] = gain_bits(g[j]);
+                            alive[j] = lf[j] < limit_d && gb[j] != 0ull;
+                        }
+                        any |= act;
+                    }
+                    if (++rounds == 255 / kItems) {   // uniform
+                        c0 += (int)(packed & 0xffu); c1 += (int)((packed >> 8) & 0xffu);
+                        c2 += (int)((packed >> 16) & 0xffu); c3 += (int)(packed >> 24);
+                        packed = 0u;
+                        rounds = 0;
+                    }
+                } while (__ballot(any));
+                c0 += (int)(packed & 0xffu); c1 += (int)((packed >> 8) & 0xffu);
+                c2 += (int)((packed >> 16) & 0xffu); c3 += (int)(packed >> 24);
+                bool mine_alive = false;
+#pragma unroll
+                for (int j = 0; j < kItems; ++j) mine_alive |= alive[j];
+                const bool wave_alive = __ballot(mine_alive) != 0ull;
+                // (a lane counts at most kItems * limit <= 2^22 gains per octave: the sums fit 32 bits)
+                c0 = wave_last_i32(wave_incl_scan_i32(c0));
+                c1 = wave_last_i32(wave_incl_scan_i32(c1));
+                c2 = wave_last_i32(wave_incl_scan_i32(c2));
+                c3 = wave_last_i32(wave_incl_scan_i32(c3));
+                if (lane == 0) {
+                    unsigned long long* row = s_cnt[o & (kRing - 1)];
+                    if (c0) atomicAdd(&row[0], (unsigned long long)(unsigned)c0);
+                    if (c1) atomicAdd(&row[1], (unsigned long long)(unsigned)c1);
+                    if (c2) atomicAdd(&row[2], (unsigned long long)(unsigned)c2);
+                    if (c3) atomicAdd(&row[3], (unsigned long long)(unsigned)c3);
+                    const unsigned long long all = (unsigned long long)(unsigned)c0 + (unsigned)c1 + (unsigned)c2 + (unsigned)c3;
+                    if (all) atomicAdd(&s_octave[o & 3], all);
+                    if (wave_alive) s_alive[o & 3] = 1;
+                }
+                __syncthreads();
+                any_alive = s_alive[o & 3] != 0;
+                total += s_octave[o & 3];
+                if (total >= need || !any_alive || o == kMaxOctave) break;   // uniform
+                // room for the octave after the next one (nobody reads or adds to these now)
+                if (threadIdx.x < kSubBins) s_cnt[(o + 2) & (kRing - 1)][threadIdx.x] = 0ull;
+                if (threadIdx.x == 0) { s_alive[(o + 2) & 3] = 0; s_octave[(o + 2) & 3] = 0ull; }
+            }
         }
         // the tile's slot: the last kWinOct octaves in detail, everything above them as one number
         if (threadIdx.x < kWave) {
-            const int w = lane >> 2, sub = lane & 3;
+            const int w = lane / kSubBins, sub = lane % kSubBins;
             unsigned long long v = 0ull;
             if (lane < kWinOct * kSubBins) {
-                const int oct = o - ((o - w) & (kWinOct - 1));   // the octave in [o - 7, o] that is w modulo 8
+                const int oct = o - ((o - w) & (kWinOct - 1));   // the octave in [o - kWinOct + 1, o] that is w modulo kWinOct
                 if (oct >= 0) v = s_cnt[oct & (kRing - 1)][sub];
             }
             const long long in_window = wave_total_i64((long long)v);
             CoarseSlot* slot = slots + t0 / kTile;
             if (lane < kWinOct * kSubBins) slot->cnt[w][sub] = v;
             if (lane == 0) {
-                slot->cum_top = s_total - (unsigned long long)in_window;
+                slot->cum_top = total - (unsigned long long)in_window;
                 slot->stop = o;
                 slot->exhausted = any_alive ? 0 : 1;
             }
@@ -370,16 +583,20 @@ __device__ __forceinline__ void first_bracket(SelectShared& sh, CoarseShared& cs
     const int s_max = cs.s_max;
     const int s_min = cs.s_min == INT_MAX ? s_max : cs.s_min;   // no tile has gains left: everything is counted
     const int first = s_max - (kWinOct - 1) > 0 ? s_max - (kWinOct - 1) : 0;   // first octave of the range
-    // every thread takes one count of one slot at a time (a slot's 32 counts are consecutive:
-    // coalesced loads); what lies above the range and the grand total are summed per thread,
-    // the counts of the range go to LDS by their octave
+    // Every thread takes one count of one slot at a time (a slot's counts are consecutive:
+    // coalesced loads), always the same row and interval e of the slots it visits.  What lies
+    // above the range and the grand total are summed per thread; the counts of the range are
+    // kept per octave of the range (the slots of one thread may have stopped at different
+    // octaves), added up over the four lanes of a wavefront that share e, and only then go to
+    // LDS: a few atomics per wavefront instead of one per count.
+    static_assert(kBig % (kWinOct * kSubBins) == 0 && kWave == 4 * kWinOct * kSubBins, "lanes that share an interval");
     long long base = 0, known = 0;
-    bool mine = false;
+    long long part[kWinOct];
+#pragma unroll
+    for (int d = 0; d < kWinOct; ++d) part[d] = 0;
+    const int e = (int)threadIdx.x % (kWinOct * kSubBins), w = e / kSubBins, q = e % kSubBins;
     for (long long idx = threadIdx.x; idx < tiles * (kWinOct * kSubBins); idx += kBig) {
-        mine = true;
-        const long long u = idx / (kWinOct * kSubBins);
-        const int e = (int)(idx % (kWinOct * kSubBins)), w = e / kSubBins, q = e % kSubBins;
-        const CoarseSlot* slot = slots + u;
+        const CoarseSlot* slot = slots + idx / (kWinOct * kSubBins);
         const long long v = (long long)slot->cnt[w][q];
         const int stop = slot->stop;
         const int oct = stop - ((stop - w) & (kWinOct - 1));   // the octave of the slot's row w
@@ -391,16 +608,22 @@ __device__ __forceinline__ void first_bracket(SelectShared& sh, CoarseShared& cs
         if (oct < 0) continue;
         known += v;
         if (oct < first) base += v;
-        // oct - first is in [0, 7] for the rows of the range, because stop <= s_max
-        else if (v) atomicAdd((unsigned long long*)&cs.sum[2 + (oct - first) * kSubBins + q], (unsigned long long)v);
+        // oct - first is in [0, kWinOct - 1] for the rows of the range, because stop <= s_max
+#pragma unroll
+        for (int d = 0; d < kWinOct; ++d) part[d] += (oct - first == d) ? v : 0;
     }
-    if (__ballot(mine)) {
-        base = wave_total_i64(base);
-        known = wave_total_i64(known);
-        if (lane_id() == 0) {
-            atomicAdd((unsigned long long*)&cs.sum[0], (unsigned long long)base);
-            atomicAdd((unsigned long long*)&cs.sum[1], (unsigned long long)known);
-        }
+    base = wave_total_i64(base);
+    known = wave_total_i64(known);
+#pragma unroll
+    for (int d = 0; d < kWinOct; ++d) {
+        part[d] += __shfl_xor(part[d], 16, kWave);
+        part[d] += __shfl_xor(part[d], 32, kWave);
+        if (lane_id() < kWinOct * kSubBins && part[d])
+            atomicAdd((unsigned long long*)&cs.sum[2 + d * kSubBins + q], (unsigned long long)part[d]);
+    }
+    if (lane_id() == 0) {
+        if (base) atomicAdd((unsigned long long*)&cs.sum[0], (unsigned long long)base);
+        if (known) atomicAdd((unsigned long long*)&cs.sum[1], (unsigned long long)known);
     }
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -456,7 +679,8 @@ __global__ __launch_bounds__(kBig) void k_bisect_pass(Src src, long long n, long
                                                       const CoarseSlot* __restrict__ slots,
                                                       AllocHeader* __restrict__ hdr, SelectBins* __restrict__ bins,
                                                       unsigned long long* __restrict__ lists,
-                                                      int* __restrict__ list_count) {
+                                                      int* __restrict__ list_count, double* __restrict__ ck_g,
+                                                      int32_t* __restrict__ ck_l) {
     __shared__ SelectShared sh;
     bool from_lists = false;
     if constexpr (kPass == 0) {
@@ -498,19 +722,24 @@ __global__ __launch_bounds__(kBig) void k_bisect_pass(Src src, long long n, long
         const long long base = (long long)blockIdx.x * chunk;
         const long long end = base + chunk < n ? base + chunk : n;
         const double limit_d = (double)limit;
+        // Where the walks start: pass 0 takes the states that the coarse count kept when they lie
+        // above the bracket (else it starts from l = 0) and leaves every walk's first state at or
+        // below hi in their place, for pass 1 and the output kernel: all later brackets, and tau,
+        // lie at or below this hi.
+        const bool resume = kPass != 0 || hi <= hdr->ck_top;   // uniform
         for (long long t0 = base; t0 < end; t0 += kTile) {
             const long long pos = t0 + (long long)threadIdx.x * kItems;
             double a[kItems], b[kItems], s[kItems], g[kItems], lf[kItems];
             unsigned long long gb[kItems];
             bool alive[kItems];
             load_posteriors(src, pos, end, a, b);
+            if (resume) load_states(ck_g, ck_l, pos, end, g, lf);
 #pragma unroll
             for (int j = 0; j < kItems; ++j) {
                 s[j] = a[j] + b[j];
-                g[j] = gain_first(a[j], s[j]);
-                lf[j] = 0.0;
+                if (!resume) { g[j] = gain_first(a[j], s[j]); lf[j] = 0.0; }
                 gb[j] = gain_bits(g[j]);
-                alive[j] = pos + j < end && limit > 0;
+                alive[j] = pos + j < end && lf[j] < limit_d;
             }
             // down to the bracket: the kItems walks in lockstep
             bool any;
@@ -528,6 +757,7 @@ __global__ __launch_bounds__(kBig) void k_bisect_pass(Src src, long long n, long
                     any |= act;
                 }
             } while (any);
+            if (kPass == 0) store_states(ck_g, ck_l, pos, end, g, lf);
             // through the bracket: whole wavefronts, one prompt of every lane at a time
 #pragma unroll
             for (int j = 0; j < kItems; ++j) {
@@ -722,6 +952,8 @@ __global__ __launch_bounds__(kBig) void k_bisect_finalize(Src src, long long n, 
                                                           AllocHeader* __restrict__ hdr,
                                                           const unsigned long long* __restrict__ lists,
                                                           const int* __restrict__ list_count,
+                                                          const double* __restrict__ ck_g,
+                                                          const int32_t* __restrict__ ck_l,
                                                           int32_t* __restrict__ delta, double* __restrict__ util,
                                                           long long* __restrict__ block_ksum,
                                                           long long* __restrict__ block_tied, int32_t* dev_status) {
@@ -750,12 +982,13 @@ __global__ __launch_bounds__(kBig) void k_bisect_finalize(Src src, long long n, 
         double a[kItems], b[kItems], s[kItems], g[kItems], e[kItems], lf[kItems];
         bool alive[kItems];
         load_posteriors(src, pos, end, a, b);
+        // the gains go on from where the first narrowing pass left them (above tau) ...
+        if (ck_g) load_states(ck_g, ck_l, pos, end, g, lf);
 #pragma unroll
         for (int j = 0; j < kItems; ++j) {
             s[j] = a[j] + b[j];
-            g[j] = gain_first(a[j], s[j]);
+            if (!ck_g) { g[j] = gain_first(a[j], s[j]); lf[j] = 0.0; }
             e[j] = 1.0;
-            lf[j] = 0.0;
             alive[j] = pos + j < end;
         }
         bool any;
@@ -765,13 +998,30 @@ __global__ __launch_bounds__(kBig) void k_bisect_finalize(Src src, long long n, 
             for (int j = 0; j < kItems; ++j) {
                 const bool act = alive[j] && lf[j] < limit_d && gain_bits(g[j]) > tau_bits;
                 if (act) {
-                    e[j] = surv_next(e[j], b[j], s[j], lf[j]);
                     g[j] = gain_next(g[j], b[j], s[j], lf[j]);
                     lf[j] += 1.0;
                 }
                 any |= act;
             }
         } while (any);
+        // ... the survival product takes its k steps from the start
+        if (util) {
+            double le[kItems];
+#pragma unroll
+            for (int j = 0; j < kItems; ++j) le[j] = 0.0;
+            do {
+                any = false;
+#pragma unroll
+                for (int j = 0; j < kItems; ++j) {
+                    const bool act = alive[j] && le[j] < lf[j];
+                    if (act) {
+                        e[j] = surv_next(e[j], b[j], s[j], le[j]);
+                        le[j] += 1.0;
+                    }
+                    any |= act;
+                }
+            } while (any);
+        }
         int packed[kItems];
 #pragma unroll
         for (int j = 0; j < kItems; ++j) {
@@ -910,19 +1160,23 @@ static int run_bisect(const Src& src, const CommonArgs& a, const Plan& p, const 
     const long long tiles = (n + kTile - 1) / kTile;
     if (a.budget > 0) {
         hipLaunchKernelGGL((k_bisect_coarse<Src>), dim3(p.nb), dim3(kBig), 0, a.stream, src, n, (long long)a.budget,
-                           limit, p.chunk, w.coarse, a.dev_status);
+                           limit, p.chunk, w.coarse, w.header, w.ck_g, w.ck_l, a.dev_status);
         hipLaunchKernelGGL((k_bisect_pass<Src, 0>), dim3(p.nb), dim3(kBig), 0, a.stream, src, n, (long long)a.budget,
                            limit, p.chunk, tiles, (const CoarseSlot*)w.coarse, w.header, w.bins, w.lists,
-                           w.list_count);
+                           w.list_count, w.ck_g, w.ck_l);
         hipLaunchKernelGGL(k_bisect_reduce, dim3(kBins / kReduceBins), dim3(kThreads), 0, a.stream, p.nb, 0,
                            w.header, w.bins, (const int*)w.list_count);
         hipLaunchKernelGGL((k_bisect_pass<Src, 1>), dim3(p.nb), dim3(kBig), 0, a.stream, src, n, (long long)a.budget,
                            limit, p.chunk, tiles, (const CoarseSlot*)w.coarse, w.header, w.bins, w.lists,
-                           w.list_count);
+                           w.list_count, w.ck_g, w.ck_l);
     }
+    // (without a budget there was no search and no walk state)
+    const double* state_g = a.budget > 0 ? w.ck_g : nullptr;
+    const int32_t* state_l = a.budget > 0 ? w.ck_l : nullptr;
     hipLaunchKernelGGL((k_bisect_finalize<Src>), dim3(p.nb), dim3(kBig), 0, a.stream, src, n, p.chunk,
                        (long long)a.budget, limit, depth_capped, p.nb, w.header,
-                       (const unsigned long long*)w.lists, (const int*)w.list_count, a.delta, a.util,
+                       (const unsigned long long*)w.lists, (const int*)w.list_count, state_g, state_l, a.delta,
+                       a.util,
                        w.block_ksum, w.block_tied, a.dev_status);
     const int mode = a.group_off ? (a.off_t == HORA_I32 ? 1 : 2) : 0;
 #define HORA_LAUNCH_BISECT_WRITE(M)                                                                       \
