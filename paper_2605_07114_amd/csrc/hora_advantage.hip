@@ -2,12 +2,12 @@
 // and the per-response loss weights of the objective with variable-size groups (Sec. 3.2).
 //
 // A sub-group of L lanes (L a power of two, chosen from the mean group size) owns one
-// group: the lanes stride over the group's rewards, so a wavefront reads a contiguous
-// run of the reward array, and combine their partial sums with a butterfly.  L is about a
-// quarter of the mean group size; a group of up to 8 L responses (1.75 times the mean or more)
-// is read once and kept in registers (two dependent memory round trips per wavefront, offsets then rewards), and
-// what is computed once per group (mean, standard deviation, reciprocals) is repeated by
-// L lanes only: the kernel is bound by instruction issue and latency, not by bytes.
+// group.  Every lane takes runs of 16 bytes of the group's rewards (four floats, two doubles),
+// one load or store per run, so that the lanes of a group cover whole cache lines; the lanes
+// combine their partial sums with a butterfly.  A group of up to 8 L (or 16 L) responses,
+// 1.75 times the mean or more, is read once and kept in registers: two dependent memory round
+// trips per wavefront, offsets then rewards.  What is computed once per group (mean, standard
+// deviation, reciprocals) is repeated by its L lanes.
 // All sums are binary64; a float output is rounded once at the store.
 #include <hip/hip_runtime.h>
 
@@ -35,14 +35,24 @@ __device__ __forceinline__ int sub_and(int v) {
 }
 
 // Rewards a lane keeps in registers: a group of up to L * kKeep responses is read from
-// memory once; what lies beyond is read again in every pass.
-constexpr int kKeep = 8;
+// memory once; what lies beyond is read again in every pass.  A lane's rewards are runs of
+// 16 bytes (four floats, two doubles), moved by one load or store each: the four lanes of a
+// group then cover whole 64-byte lines, where single elements per lane would make every
+// instruction touch a quarter of each line it visits (the address path, not the memory,
+// bounded that form at 0.4 of the peak).
 
-template <typename F, typename I, int L>
+template <typename F> struct Run;
+template <> struct Run<float> { static constexpr int kPer = 4; typedef float V __attribute__((ext_vector_type(4), aligned(4))); };
+template <> struct Run<double> { static constexpr int kPer = 2; typedef double V __attribute__((ext_vector_type(2), aligned(8))); };
+
+template <typename F, typename I, int L, int kKeep>
 __global__ __launch_bounds__(kThreads) void k_group_adv(long long n_groups, const I* __restrict__ off,
                                                         long long n_resp, const F* __restrict__ reward,
                                                         F* __restrict__ adv, int mode, double eps, int ddof,
                                                         int32_t* dev_status) {
+    constexpr int kPer = Run<F>::kPer;        // responses per run
+    constexpr int kRuns = kKeep / kPer;       // runs per lane
+    typedef typename Run<F>::V V;
     const int sub = (int)(threadIdx.x % L);
     const long long g = ((long long)blockIdx.x * kThreads + threadIdx.x) / L;
     const bool live = g < n_groups;
@@ -60,18 +70,31 @@ __global__ __launch_bounds__(kThreads) void k_group_adv(long long n_groups, cons
         }
     }
     const long long size = hi - lo;
-    const F* __restrict__ mine = reward + lo + sub;            // this lane's responses: mine[k * L]
-    F* __restrict__ mine_out = adv + lo + sub;
-    const long long count = size - sub;                        // k * L < count: mine[k * L] is in the group
-    const long long rest = lo + sub + (long long)kKeep * L;    // this lane's first response beyond its registers
+    // run r of this lane holds the responses lo + kPer * (sub + L * r) + i, i < kPer
+    const long long rest = lo + (long long)kKeep * L + sub;    // this lane's first response beyond the registers (stride L)
 
-    // one round of loads
+    // one round of loads: whole runs where the array allows it (what lies beyond the group
+    // but inside the array is loaded and not used)
     double x[kKeep];
     bool in[kKeep];
 #pragma unroll
-    for (int k = 0; k < kKeep; ++k) {
-        in[k] = (long long)(k * L) < count;
-        x[k] = in[k] ? (double)mine[k * L] : 0.0;
+    for (int r = 0; r < kRuns; ++r) {
+        const long long at = (long long)kPer * (sub + L * r);   // position in the group
+        const F* src = reward + lo + at;
+        if (at < size && lo + at + kPer <= n_resp) {
+            const V v = *reinterpret_cast<const V*>(src);
+#pragma unroll
+            for (int i = 0; i < kPer; ++i) {
+                in[r * kPer + i] = at + i < size;
+                x[r * kPer + i] = in[r * kPer + i] ? (double)v[i] : 0.0;
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < kPer; ++i) {
+                in[r * kPer + i] = at + i < size;
+                x[r * kPer + i] = in[r * kPer + i] ? (double)src[i] : 0.0;
+            }
+        }
     }
     const double first = __shfl(x[0], 0, L);   // reward[lo] (0 for an empty group)
     double sum = 0.0;
@@ -89,17 +112,37 @@ __global__ __launch_bounds__(kThreads) void k_group_adv(long long n_groups, cons
     sum = sub_sum<L>(sum);
     equal = sub_and<L>(equal);
 
+    // the kept responses go back run by run: one store where the whole run is the group's
+    auto put = [&](const double (&y)[kKeep]) {
+#pragma unroll
+        for (int r = 0; r < kRuns; ++r) {
+            const long long at = (long long)kPer * (sub + L * r);
+            F* dst = adv + lo + at;
+            if (in[r * kPer + kPer - 1]) {
+                V v;
+#pragma unroll
+                for (int i = 0; i < kPer; ++i) v[i] = (F)y[r * kPer + i];
+                *reinterpret_cast<V*>(dst) = v;
+            } else {
+#pragma unroll
+                for (int i = 0; i < kPer; ++i)
+                    if (in[r * kPer + i]) dst[i] = (F)y[r * kPer + i];
+            }
+        }
+    };
+    double y[kKeep];
+
     // Every quotient whose divisor belongs to the group is formed as a product with the
     // divisor's reciprocal (one division per lane instead of one per response): at most
     // 1.5 units in the last place away from the quotient itself.
     if (mode == HORA_ADV_RLOO) {
         const double inv = size > 1 ? 1.0 / (double)(size - 1) : 0.0;
 #pragma unroll
-        for (int k = 0; k < kKeep; ++k)
-            if (in[k]) mine_out[k * L] = (F)((size == 1 || equal) ? 0.0 : x[k] - (sum - x[k]) * inv);
+        for (int k = 0; k < kKeep; ++k) y[k] = (size == 1 || equal) ? 0.0 : x[k] - (sum - x[k]) * inv;
+        put(y);
         for (long long j = rest; j < hi; j += L) {
-            const double y = (double)reward[j];
-            adv[j] = (F)(equal ? 0.0 : y - (sum - y) * inv);
+            const double z = (double)reward[j];
+            adv[j] = (F)(equal ? 0.0 : z - (sum - z) * inv);
         }
         return;
     }
@@ -107,11 +150,11 @@ __global__ __launch_bounds__(kThreads) void k_group_adv(long long n_groups, cons
     const double mean = size > 0 ? sum / (double)size : 0.0;
     if (mode == HORA_ADV_CENTER) {
 #pragma unroll
-        for (int k = 0; k < kKeep; ++k)
-            if (in[k]) mine_out[k * L] = (F)(equal ? 0.0 : x[k] - mean);
+        for (int k = 0; k < kKeep; ++k) y[k] = equal ? 0.0 : x[k] - mean;
+        put(y);
         for (long long j = rest; j < hi; j += L) {
-            const double y = (double)reward[j];
-            adv[j] = (F)(equal ? 0.0 : y - mean);
+            const double z = (double)reward[j];
+            adv[j] = (F)(equal ? 0.0 : z - mean);
         }
         return;
     }
@@ -131,17 +174,17 @@ __global__ __launch_bounds__(kThreads) void k_group_adv(long long n_groups, cons
     ss = sub_sum<L>(ss);
     const double inv = zero ? 0.0 : 1.0 / (sqrt(ss / (double)(size - ddof)) + eps);
 #pragma unroll
-    for (int k = 0; k < kKeep; ++k)
-        if (in[k]) mine_out[k * L] = (F)(zero ? 0.0 : (x[k] - mean) * inv);
+    for (int k = 0; k < kKeep; ++k) y[k] = zero ? 0.0 : (x[k] - mean) * inv;
+    put(y);
     for (long long j = rest; j < hi; j += L) {
-        const double y = (double)reward[j];
-        adv[j] = (F)(zero ? 0.0 : (y - mean) * inv);
+        const double z = (double)reward[j];
+        adv[j] = (F)(zero ? 0.0 : (z - mean) * inv);
     }
 }
 
-template <typename F, typename I>
-static int launch_adv(int64_t n_groups, const void* off, int64_t n_resp, const void* reward, void* adv, int mode,
-                      double eps, int ddof, int32_t* dev_status, hipStream_t stream) {
+template <typename F, typename I, int kKeep>
+static int launch_adv_keep(int64_t n_groups, const void* off, int64_t n_resp, const void* reward, void* adv,
+                           int mode, double eps, int ddof, int32_t* dev_status, hipStream_t stream) {
     // lanes per group: the fewest whose registers hold a group of 1.75 times the mean size
     const long long roomy = n_groups > 0 ? (7 * n_resp + 4 * n_groups - 1) / (4 * n_groups) : 0;
     int lanes = 1;
@@ -150,7 +193,7 @@ static int launch_adv(int64_t n_groups, const void* off, int64_t n_resp, const v
     do {                                                                                                      \
         const long long blocks = (n_groups * LL + kThreads - 1) / kThreads;                                   \
         if (blocks > INT_MAX) return HORA_ERR_UNSUPPORTED;                                                    \
-        hipLaunchKernelGGL((k_group_adv<F, I, LL>), dim3((unsigned)blocks), dim3(kThreads), 0, stream,         \
+        hipLaunchKernelGGL((k_group_adv<F, I, LL, kKeep>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, \
                            (long long)n_groups, (const I*)off, (long long)n_resp, (const F*)reward, (F*)adv,  \
                            mode, eps, ddof, dev_status);                                                      \
     } while (0)
@@ -165,6 +208,17 @@ static int launch_adv(int64_t n_groups, const void* off, int64_t n_resp, const v
     }
 #undef HORA_LAUNCH_ADV
     return hipGetLastError() == hipSuccess ? HORA_OK : HORA_ERR_HIP;
+}
+
+// Responses a lane keeps: eight, or sixteen where the work per group is large next to the
+// work per response (float rewards with the standard deviation: two divisions and a square
+// root per group and lane): twice the responses per lane halve the lanes that repeat it.
+template <typename F, typename I>
+static int launch_adv(int64_t n_groups, const void* off, int64_t n_resp, const void* reward, void* adv, int mode,
+                      double eps, int ddof, int32_t* dev_status, hipStream_t stream) {
+    if (sizeof(F) == 4 && mode == HORA_ADV_GRPO)
+        return launch_adv_keep<F, I, 16>(n_groups, off, n_resp, reward, adv, mode, eps, ddof, dev_status, stream);
+    return launch_adv_keep<F, I, 8>(n_groups, off, n_resp, reward, adv, mode, eps, ddof, dev_status, stream);
 }
 
 // Loss weight of the tokens of every response: 1 / (G_i * |o_j|), or 1 / (G_i * L) with a

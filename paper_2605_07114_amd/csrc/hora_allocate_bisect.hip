@@ -53,17 +53,28 @@ static_assert((kWinOct & (kWinOct - 1)) == 0 && kSubBins == 4, "octave window");
 __device__ __forceinline__ unsigned long long octave_top(int o) { return kOne - (unsigned long long)o * kOctave; }
 
 // ----------------------------------------------------------------------------------
-// kItems consecutive posteriors per thread (one 16-byte load of c, or four of alpha / beta).
-// Invalid entries are replaced by (1, 1) so that every walk is well defined.
+// kItems consecutive posteriors per thread (one 16-byte load of c, or four of alpha / beta),
+// in two steps: `fetch` only issues the loads, `unpack` checks and converts what came back.
+// A kernel fetches its first tile before the prologue that every workgroup runs for itself
+// (the depth estimate, the sums of the coarse counts, the end of the search), so that the
+// latency of the loads is spent there.  Invalid entries are replaced by (1, 1) so that
+// every walk is well defined.
 // ----------------------------------------------------------------------------------
-__device__ __forceinline__ bool load_posteriors(const CountsSource& src, long long pos, long long end,
-                                                double (&a)[kItems], double (&b)[kItems]) {
-    int cls[kItems];
-    load_items_i32(src.c, pos, end, (reinterpret_cast<uintptr_t>(src.c) & 15) == 0, 0, cls);
+template <class Src> struct Fetched;
+template <> struct Fetched<CountsSource> { int cls[kItems]; };
+template <> struct Fetched<PosteriorSource> { double a[kItems], b[kItems]; };
+
+__device__ __forceinline__ void fetch(const CountsSource& src, long long pos, long long end,
+                                      Fetched<CountsSource>& f) {
+    load_items_i32(src.c, pos, end, (reinterpret_cast<uintptr_t>(src.c) & 15) == 0, 0, f.cls);
+}
+
+__device__ __forceinline__ bool unpack(const CountsSource& src, const Fetched<CountsSource>& f,
+                                       double (&a)[kItems], double (&b)[kItems]) {
     bool ok = true;
 #pragma unroll
     for (int j = 0; j < kItems; ++j) {
-        int x = cls[j];
+        int x = f.cls[j];
         ok &= (x >= 0) && (x <= src.g0);
         x = x < 0 ? 0 : (x > src.g0 ? src.g0 : x);
         a[j] = src.alpha0 + (double)x;
@@ -72,27 +83,33 @@ __device__ __forceinline__ bool load_posteriors(const CountsSource& src, long lo
     return ok;
 }
 
-__device__ __forceinline__ bool load_posteriors(const PosteriorSource& src, long long pos, long long end,
-                                                double (&a)[kItems], double (&b)[kItems]) {
+__device__ __forceinline__ void fetch(const PosteriorSource& src, long long pos, long long end,
+                                      Fetched<PosteriorSource>& f) {
     const bool vec = ((reinterpret_cast<uintptr_t>(src.alpha) | reinterpret_cast<uintptr_t>(src.beta)) & 15) == 0;
     if (vec && pos + kItems <= end) {
 #pragma unroll
         for (int q = 0; q < kItems / 2; ++q) {
             const v2d x = *reinterpret_cast<const v2d*>(src.alpha + pos + 2 * q);
             const v2d y = *reinterpret_cast<const v2d*>(src.beta + pos + 2 * q);
-            a[2 * q] = x.x; a[2 * q + 1] = x.y;
-            b[2 * q] = y.x; b[2 * q + 1] = y.y;
+            f.a[2 * q] = x.x; f.a[2 * q + 1] = x.y;
+            f.b[2 * q] = y.x; f.b[2 * q + 1] = y.y;
         }
     } else {
 #pragma unroll
         for (int j = 0; j < kItems; ++j) {
-            a[j] = pos + j < end ? src.alpha[pos + j] : 1.0;
-            b[j] = pos + j < end ? src.beta[pos + j] : 1.0;
+            f.a[j] = pos + j < end ? src.alpha[pos + j] : 1.0;
+            f.b[j] = pos + j < end ? src.beta[pos + j] : 1.0;
         }
     }
+}
+
+__device__ __forceinline__ bool unpack(const PosteriorSource&, const Fetched<PosteriorSource>& f,
+                                       double (&a)[kItems], double (&b)[kItems]) {
     bool ok = true;
 #pragma unroll
     for (int j = 0; j < kItems; ++j) {
+        a[j] = f.a[j];
+        b[j] = f.b[j];
         const bool good = (a[j] > 0.0) && (b[j] > 0.0) && (a[j] < INFINITY) && (b[j] < INFINITY);
         if (!good) { a[j] = 1.0; b[j] = 1.0; }
         ok &= good;
@@ -100,24 +117,34 @@ __device__ __forceinline__ bool load_posteriors(const PosteriorSource& src, long
     return ok;
 }
 
+template <class Src>
+__device__ __forceinline__ bool load_posteriors(const Src& src, long long pos, long long end,
+                                                double (&a)[kItems], double (&b)[kItems]) {
+    Fetched<Src> f;
+    fetch(src, pos, end, f);
+    return unpack(src, f, a, b);
+}
+
 // ----------------------------------------------------------------------------------
 // Walk states between the kernels (one gain and its index l per prompt; kItems per thread).
 // ----------------------------------------------------------------------------------
-__device__ __forceinline__ void load_states(const double* __restrict__ ck_g, const int32_t* __restrict__ ck_l,
-                                            long long pos, long long end, double (&g)[kItems], double (&lf)[kItems]) {
+struct WalkStates { double g[kItems]; int l[kItems]; };
+
+__device__ __forceinline__ void fetch_states(const double* __restrict__ ck_g, const int32_t* __restrict__ ck_l,
+                                             long long pos, long long end, WalkStates& st) {
     if (pos + kItems <= end) {   // (the arrays are 256-byte aligned and pos is a multiple of kItems)
 #pragma unroll
         for (int q = 0; q < kItems / 2; ++q) {
             const v2d x = *reinterpret_cast<const v2d*>(ck_g + pos + 2 * q);
-            g[2 * q] = x.x; g[2 * q + 1] = x.y;
+            st.g[2 * q] = x.x; st.g[2 * q + 1] = x.y;
         }
         const v4i l = *reinterpret_cast<const v4i*>(ck_l + pos);
-        lf[0] = (double)l.x; lf[1] = (double)l.y; lf[2] = (double)l.z; lf[3] = (double)l.w;
+        st.l[0] = l.x; st.l[1] = l.y; st.l[2] = l.z; st.l[3] = l.w;
     } else {
 #pragma unroll
         for (int j = 0; j < kItems; ++j) {
-            g[j] = pos + j < end ? ck_g[pos + j] : 0.0;
-            lf[j] = pos + j < end ? (double)ck_l[pos + j] : 0.0;
+            st.g[j] = pos + j < end ? ck_g[pos + j] : 0.0;
+            st.l[j] = pos + j < end ? ck_l[pos + j] : 0;
         }
     }
 }
@@ -266,14 +293,16 @@ __global__ __launch_bounds__(kBig) void k_bisect_coarse(Src src, long long n, lo
     __shared__ unsigned long long s_octave[4];   // [octave & 3] gains counted in an octave after it (see EstimateShared)
     __shared__ int s_alive[4];
     __shared__ EstimateShared s_est;
+    const long long base = (long long)blockIdx.x * chunk;
+    const long long end = base + chunk < n ? base + chunk : n;
+    Fetched<Src> first_tile;
+    fetch(src, base + (long long)threadIdx.x * kItems, base + kTile < end ? base + kTile : end, first_tile);
     int est, ck;
     estimate_depth(src, n, budget, limit, s_est, est, ck);
     const unsigned long long top_ck = octave_top(ck);
     if (blockIdx.x == 0 && threadIdx.x == 0) hdr->ck_top = top_ck;
     const unsigned long long est_bottom = octave_top(est) - kOctave;
     const unsigned long long fine_top = octave_top(est - (kWinOct - 1));   // (above 1.0 when est < kWinOct - 1: no gain lies there)
-    const long long base = (long long)blockIdx.x * chunk;
-    const long long end = base + chunk < n ? base + chunk : n;
     const int lane = lane_id();
     const double limit_d = (double)limit;
     bool bad = false;
@@ -288,7 +317,8 @@ __global__ __launch_bounds__(kBig) void k_bisect_coarse(Src src, long long n, lo
         double a[kItems], b[kItems], s[kItems], g[kItems], lf[kItems], keep_g[kItems], keep_l[kItems];
         unsigned long long gb[kItems];
         bool alive[kItems];
-        bad |= !load_posteriors(src, pos, tile_end, a, b) && pos < tile_end;
+        if (t0 != base) fetch(src, pos, tile_end, first_tile);
+        bad |= !unpack(src, first_tile, a, b) && pos < tile_end;
 #pragma unroll
         for (int j = 0; j < kItems; ++j) {
             s[j] = a[j] + b[j];
@@ -561,56 +591,84 @@ __device__ __forceinline__ void first_bracket(SelectShared& sh, CoarseShared& cs
                                               const CoarseSlot* __restrict__ slots) {
     if (threadIdx.x == 0) { cs.s_max = 0; cs.s_min = INT_MAX; }
     if (threadIdx.x < 2 + kWinOct * kSubBins) cs.sum[threadIdx.x] = 0;
-    __syncthreads();
+    // Every thread takes one count of one slot at a time (a slot's counts are consecutive:
+    // coalesced loads), always the same row and interval e of the slots it visits.  The first
+    // kKeep counts of a thread (all of them up to 2^20 prompts) are loaded together with their
+    // slots' stopping octaves and kept in registers, so that one round trip to memory serves
+    // both steps: the range of octaves, and the sums inside it.
+    static_assert(kBig % (kWinOct * kSubBins) == 0 && kWave == 4 * kWinOct * kSubBins, "lanes that share an interval");
+    constexpr int kKeep = 4;
+    constexpr int kPerSlot = kWinOct * kSubBins;
+    const long long counts = tiles * kPerSlot;
+    const int e = (int)threadIdx.x % kPerSlot, w = e / kSubBins, q = e % kSubBins;
+    long long kept_v[kKeep], kept_top[kKeep];
+    int kept_stop[kKeep];
+    bool kept_done[kKeep];
+#pragma unroll
+    for (int i = 0; i < kKeep; ++i) {
+        const long long idx = (long long)i * kBig + threadIdx.x;
+        kept_v[i] = 0; kept_top[i] = 0; kept_stop[i] = -1; kept_done[i] = true;   // (no slot)
+        if (idx < counts) {
+            const CoarseSlot* slot = slots + idx / kPerSlot;
+            kept_v[i] = (long long)slot->cnt[w][q];
+            kept_stop[i] = slot->stop;
+            kept_done[i] = slot->exhausted != 0;
+            if (e == 0) kept_top[i] = (long long)slot->cum_top;
+        }
+    }
+    __syncthreads();   // cs is initialised
     {
         int smax = 0, smin = INT_MAX;
-        for (long long u = threadIdx.x; u < tiles; u += kBig) {
+#pragma unroll
+        for (int i = 0; i < kKeep; ++i) {
+            smax = kept_stop[i] > smax ? kept_stop[i] : smax;
+            if (!kept_done[i]) smin = kept_stop[i] < smin ? kept_stop[i] : smin;
+        }
+        for (long long u = (long long)kKeep * kBig / kPerSlot + threadIdx.x; u < tiles; u += kBig) {   // larger batches
             const int stop = slots[u].stop;
             smax = stop > smax ? stop : smax;
             if (!slots[u].exhausted) smin = stop < smin ? stop : smin;
         }
-        if (__ballot(smax != 0 || smin != INT_MAX)) {   // (wavefronts without a tile have nothing to add)
 #pragma unroll
-            for (int d = kWave / 2; d > 0; d >>= 1) {
-                const int om = __shfl_xor(smax, d, kWave), on = __shfl_xor(smin, d, kWave);
-                smax = om > smax ? om : smax;
-                smin = on < smin ? on : smin;
-            }
-            if (lane_id() == 0) { atomicMax(&cs.s_max, smax); atomicMin(&cs.s_min, smin); }
+        for (int d = kWave / 2; d > 0; d >>= 1) {
+            const int om = __shfl_xor(smax, d, kWave), on = __shfl_xor(smin, d, kWave);
+            smax = om > smax ? om : smax;
+            smin = on < smin ? on : smin;
+        }
+        if (lane_id() == 0) {
+            if (smax != 0) atomicMax(&cs.s_max, smax);
+            if (smin != INT_MAX) atomicMin(&cs.s_min, smin);
         }
     }
     __syncthreads();
     const int s_max = cs.s_max;
     const int s_min = cs.s_min == INT_MAX ? s_max : cs.s_min;   // no tile has gains left: everything is counted
     const int first = s_max - (kWinOct - 1) > 0 ? s_max - (kWinOct - 1) : 0;   // first octave of the range
-    // Every thread takes one count of one slot at a time (a slot's counts are consecutive:
-    // coalesced loads), always the same row and interval e of the slots it visits.  What lies
-    // above the range and the grand total are summed per thread; the counts of the range are
-    // kept per octave of the range (the slots of one thread may have stopped at different
-    // octaves), added up over the four lanes of a wavefront that share e, and only then go to
-    // LDS: a few atomics per wavefront instead of one per count.
-    static_assert(kBig % (kWinOct * kSubBins) == 0 && kWave == 4 * kWinOct * kSubBins, "lanes that share an interval");
+    // What lies above the range and the grand total are summed per thread; the counts of the
+    // range are kept per octave of the range (the slots of one thread may have stopped at
+    // different octaves), added up over the four lanes of a wavefront that share e, and only
+    // then go to LDS: a few atomics per wavefront instead of one per count.
     long long base = 0, known = 0;
     long long part[kWinOct];
 #pragma unroll
     for (int d = 0; d < kWinOct; ++d) part[d] = 0;
-    const int e = (int)threadIdx.x % (kWinOct * kSubBins), w = e / kSubBins, q = e % kSubBins;
-    for (long long idx = threadIdx.x; idx < tiles * (kWinOct * kSubBins); idx += kBig) {
-        const CoarseSlot* slot = slots + idx / (kWinOct * kSubBins);
-        const long long v = (long long)slot->cnt[w][q];
-        const int stop = slot->stop;
+    auto take = [&](long long v, long long top, int stop) {
         const int oct = stop - ((stop - w) & (kWinOct - 1));   // the octave of the slot's row w
-        if (e == 0) {
-            const long long top = (long long)slot->cum_top;
-            base += top;
-            known += top;
-        }
-        if (oct < 0) continue;
+        base += top;
+        known += top;
+        if (oct < 0) return;
         known += v;
         if (oct < first) base += v;
         // oct - first is in [0, kWinOct - 1] for the rows of the range, because stop <= s_max
 #pragma unroll
         for (int d = 0; d < kWinOct; ++d) part[d] += (oct - first == d) ? v : 0;
+    };
+#pragma unroll
+    for (int i = 0; i < kKeep; ++i)
+        if (kept_stop[i] >= 0) take(kept_v[i], kept_top[i], kept_stop[i]);
+    for (long long idx = (long long)kKeep * kBig + threadIdx.x; idx < counts; idx += kBig) {
+        const CoarseSlot* slot = slots + idx / kPerSlot;
+        take((long long)slot->cnt[w][q], e == 0 ? (long long)slot->cum_top : 0, slot->stop);
     }
     base = wave_total_i64(base);
     known = wave_total_i64(known);
@@ -618,7 +676,7 @@ __device__ __forceinline__ void first_bracket(SelectShared& sh, CoarseShared& cs
     for (int d = 0; d < kWinOct; ++d) {
         part[d] += __shfl_xor(part[d], 16, kWave);
         part[d] += __shfl_xor(part[d], 32, kWave);
-        if (lane_id() < kWinOct * kSubBins && part[d])
+        if (lane_id() < kPerSlot && part[d])
             atomicAdd((unsigned long long*)&cs.sum[2 + d * kSubBins + q], (unsigned long long)part[d]);
     }
     if (lane_id() == 0) {
@@ -683,7 +741,14 @@ __global__ __launch_bounds__(kBig) void k_bisect_pass(Src src, long long n, long
                                                       int32_t* __restrict__ ck_l) {
     __shared__ SelectShared sh;
     bool from_lists = false;
+    Fetched<Src> first_tile;
+    WalkStates first_states;
     if constexpr (kPass == 0) {
+        // (pass 0 always walks: the loads of its first tile are under way during the prologue)
+        const long long base = (long long)blockIdx.x * chunk;
+        const long long end = base + chunk < n ? base + chunk : n;
+        fetch(src, base + (long long)threadIdx.x * kItems, end, first_tile);
+        fetch_states(ck_g, ck_l, base + (long long)threadIdx.x * kItems, end, first_states);
         __shared__ CoarseShared cs;
         first_bracket(sh, cs, tiles, budget, slots);
     } else {
@@ -732,12 +797,16 @@ __global__ __launch_bounds__(kBig) void k_bisect_pass(Src src, long long n, long
             double a[kItems], b[kItems], s[kItems], g[kItems], lf[kItems];
             unsigned long long gb[kItems];
             bool alive[kItems];
-            load_posteriors(src, pos, end, a, b);
-            if (resume) load_states(ck_g, ck_l, pos, end, g, lf);
+            if (kPass != 0 || t0 != base) {
+                fetch(src, pos, end, first_tile);
+                fetch_states(ck_g, ck_l, pos, end, first_states);
+            }
+            unpack(src, first_tile, a, b);
 #pragma unroll
             for (int j = 0; j < kItems; ++j) {
                 s[j] = a[j] + b[j];
-                if (!resume) { g[j] = gain_first(a[j], s[j]); lf[j] = 0.0; }
+                if (resume) { g[j] = first_states.g[j]; lf[j] = (double)first_states.l[j]; }
+                else { g[j] = gain_first(a[j], s[j]); lf[j] = 0.0; }
                 gb[j] = gain_bits(g[j]);
                 alive[j] = pos + j < end && lf[j] < limit_d;
             }
@@ -959,6 +1028,13 @@ __global__ __launch_bounds__(kBig) void k_bisect_finalize(Src src, long long n, 
                                                           long long* __restrict__ block_tied, int32_t* dev_status) {
     __shared__ SelectShared sh;
     long long (&s_red)[2][kBigWaves] = *reinterpret_cast<long long (*)[2][kBigWaves]>(&sh.bins.cnt[0]);
+    const long long base = (long long)blockIdx.x * chunk;
+    const long long end = base + chunk < n ? base + chunk : n;
+    // (the loads of the first tile are under way while the search is finished)
+    Fetched<Src> first_tile;
+    WalkStates first_states;
+    fetch(src, base + (long long)threadIdx.x * kItems, end, first_tile);
+    if (ck_g) fetch_states(ck_g, ck_l, base + (long long)threadIdx.x * kItems, end, first_states);
     unsigned long long tau_bits = ~0ull;   // budget 0: nothing is above tau
     if (budget > 0) {
         bool ok;
@@ -970,8 +1046,6 @@ __global__ __launch_bounds__(kBig) void k_bisect_finalize(Src src, long long n, 
         }
         __syncthreads();   // sh is reused below
     }
-    const long long base = (long long)blockIdx.x * chunk;
-    const long long end = base + chunk < n ? base + chunk : n;
     const bool d_vec = (reinterpret_cast<uintptr_t>(delta) & 15) == 0;
     const bool u_vec = (reinterpret_cast<uintptr_t>(util) & 15) == 0;
     const double limit_d = (double)limit;
@@ -981,13 +1055,17 @@ __global__ __launch_bounds__(kBig) void k_bisect_finalize(Src src, long long n, 
         const long long pos = t0 + (long long)threadIdx.x * kItems;
         double a[kItems], b[kItems], s[kItems], g[kItems], e[kItems], lf[kItems];
         bool alive[kItems];
-        load_posteriors(src, pos, end, a, b);
+        if (t0 != base) {
+            fetch(src, pos, end, first_tile);
+            if (ck_g) fetch_states(ck_g, ck_l, pos, end, first_states);
+        }
+        unpack(src, first_tile, a, b);
         // the gains go on from where the first narrowing pass left them (above tau) ...
-        if (ck_g) load_states(ck_g, ck_l, pos, end, g, lf);
 #pragma unroll
         for (int j = 0; j < kItems; ++j) {
             s[j] = a[j] + b[j];
-            if (!ck_g) { g[j] = gain_first(a[j], s[j]); lf[j] = 0.0; }
+            if (ck_g) { g[j] = first_states.g[j]; lf[j] = (double)first_states.l[j]; }
+            else { g[j] = gain_first(a[j], s[j]); lf[j] = 0.0; }
             e[j] = 1.0;
             alive[j] = pos + j < end;
         }
