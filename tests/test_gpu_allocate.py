@@ -261,6 +261,38 @@ def test_posteriors_whose_contested_gains_sit_in_one_workgroup(gpu, oracle):
                                    rtol=UTIL_RTOL, atol=0)
 
 
+def test_depth_estimate_from_an_unrepresentative_sample(gpu, oracle):
+    """The threshold search takes the depth of its first walk from 512 prompts spread evenly
+    over the batch (prompt floor(q n / 512), q < 512).  The estimate only steers the work: with
+    a sample that is nothing like the batch (the sampled prompts all eager, the rest reluctant;
+    the reverse; prompts sorted, so that the tiles differ as much as they can) the allocation
+    must still be the oracle's."""
+    sess, torch, hora = gpu
+    rng = np.random.default_rng(29)
+    n, g0 = 300000, 8
+    sampled = (np.arange(512, dtype=np.int64) * n) // 512
+    cases = {}
+    for name, (c_sample, c_rest) in {"sample decays fast": (g0, 0), "sample decays slowly": (0, g0)}.items():
+        c = np.full(n, c_rest, dtype=np.int32)
+        c[sampled] = c_sample
+        cases[name] = c
+    cases["sorted"] = np.sort(rng.binomial(g0, rng.beta(0.5, 0.5, n)).astype(np.int32))
+    cases["sorted descending"] = cases["sorted"][::-1].copy()
+    for name, c in cases.items():
+        for budget in (4 * n, n // 3, 40 * n):
+            print(f"allocate (threshold search) {name} n={n} budget={budget}", flush=True)
+            check_allocation(gpu, oracle, c, g0, budget, methods=(hora.ALLOC_BISECT,))
+    # the same through per-prompt posteriors, with a cap that some prompts reach
+    alpha = np.where(np.isin(np.arange(n), sampled), 9.0, 0.4) + rng.uniform(0.0, 0.05, n)
+    beta = np.where(np.isin(np.arange(n), sampled), 0.5, 7.0) + rng.uniform(0.0, 0.05, n)
+    for budget, cap in ((4 * n, 0), (6 * n, 9)):
+        want = oracle.allocate_posterior(alpha, beta, budget, delta_max=cap)
+        print(f"allocate_posterior unrepresentative sample n={n} budget={budget} cap={cap}", flush=True)
+        got = sess.allocate_posterior(dev(torch, alpha), dev(torch, beta), g0, budget, delta_max=cap)
+        assert sess.status() == 0
+        assert np.array_equal(got.delta.cpu().numpy().astype(np.int64), want)
+
+
 def test_learned_prior_collapses_to_the_uniform_prior(gpu, oracle):
     # App. D: s = 2, p = 1/2 gives alpha = 1 + c, beta = 1 + G0 - c
     sess, torch, hora = gpu
