@@ -781,7 +781,7 @@ __global__ __launch_bounds__(kShardThreads) void k_shard_allocate_waves(
     constexpr int kPerWave = kWave / L;                  // shards per wavefront
     constexpr int kPerBlock = kShardWaves * kPerWave;    // shards per workgroup
     constexpr unsigned long long kGroupMask = L == 64 ? ~0ull : ((1ull << (L & 63)) - 1ull);
-    __shared__ unsigned short s_coarse[kMaxCoarse * 64];
+    __shared__ __align__(16) unsigned short s_coarse[kMaxCoarse * 64];
     __shared__ GroupScratch<L> s_group[kPerBlock];
     __shared__ int s_left[kPerBlock];
     __shared__ int s_left_n, s_tables;
@@ -817,15 +817,29 @@ __global__ __launch_bounds__(kShardThreads) void k_shard_allocate_waves(
         s_left_n = 0;
         s_tables = shard_tables_match(key, g0, src.alpha0, src.beta0, depth, usable) ? 1 : 0;
     }
+    // The coarse rows are requested before it is known whether the workspace holds the tables
+    // (rows of 16 classes, two 16-byte pieces each, one piece per thread): the answer and the
+    // rows travel together, and rows of a workspace without tables are dropped.
+    static_assert(kMaxCoarse * 2 <= kShardThreads, "one piece of a coarse row per thread");
+    const bool early_rows = stride == 16;
+    uint4 early = {0u, 0u, 0u, 0u};
+    if (early_rows && (int)threadIdx.x < n_coarse * 2) {
+        int p = ((int)threadIdx.x >> 1) * kLevelBlock + kLevelBlock - 1;
+        if (p > levels - 1) p = levels - 1;
+        early = reinterpret_cast<const uint4*>(level_kge + (long long)p * 16)[threadIdx.x & 1];
+    }
     __syncthreads();
     const bool tables = s_tables != 0;
-    if (tables)
+    if (tables && early_rows) {
+        if ((int)threadIdx.x < n_coarse * 2) reinterpret_cast<uint4*>(s_coarse)[threadIdx.x] = early;
+    } else if (tables) {
         for (int idx = (int)threadIdx.x; idx < n_coarse * stride; idx += kShardThreads) {
             const int q = idx / stride, k = idx - q * stride;
             int p = q * kLevelBlock + kLevelBlock - 1;
             if (p > levels - 1) p = levels - 1;
             s_coarse[idx] = level_kge[(long long)p * stride + k];
         }
+    }
     __syncthreads();
     GroupScratch<L>& gs = s_group[slot];
     bool defer = false;        // the workgroup-per-shard code has to take the shard
@@ -847,6 +861,7 @@ __global__ __launch_bounds__(kShardThreads) void k_shard_allocate_waves(
 #pragma unroll
             for (int k = 0; k < kRegs; ++k) n_all[k] = 0;
             bool data_bad = false;
+            int x_first = 0;   // this lane's prompt of the shard's first L prompts (read once, used again for the outputs)
             for (long long i0 = lo_i; i0 < hi_i; i0 += L) {
                 const long long i = i0 + sl;
                 int x = -1;
@@ -854,6 +869,7 @@ __global__ __launch_bounds__(kShardThreads) void k_shard_allocate_waves(
                     x = src.c[i];
                     if (x < 0 || x > g0) { data_bad = true; x = x < 0 ? 0 : g0; }
                 }
+                if (i0 == lo_i) x_first = x < 0 ? 0 : x;
                 if constexpr (L < kWave) {
 #pragma unroll
                     for (int k = 0; k < L; ++k)
@@ -891,9 +907,25 @@ __global__ __launch_bounds__(kShardThreads) void k_shard_allocate_waves(
                     long long cq = 0;
                     const bool in = q < n_coarse;
                     if constexpr (L < kWave) {
+                        if (stride == 16) {
+                            // a row of 16 counts is two 16-byte reads; a shard here has at most 2^10
+                            // prompts and a count is below 2^16: the sum fits 32 bits, one
+                            // multiply-add per class
+                            const uint4 r0 = *reinterpret_cast<const uint4*>(s_coarse + q * 16);
+                            const uint4 r1 = *reinterpret_cast<const uint4*>(s_coarse + q * 16 + 8);
+                            const unsigned w[8] = {r0.x, r0.y, r0.z, r0.w, r1.x, r1.y, r1.z, r1.w};
+                            unsigned c32 = 0u;
 #pragma unroll
-                        for (int k = 0; k < L; ++k)
-                            if (k < nc && in) cq += count_of(k) * (long long)s_coarse[q * stride + k];
+                            for (int k = 0; k < 16; ++k) {
+                                const unsigned kge = (k & 1) ? (w[k >> 1] >> 16) : (w[k >> 1] & 0xffffu);
+                                if (k < L && k < nc) c32 = __umul24((unsigned)n_all[k < L ? k : 0], kge) + c32;   // uniform
+                            }
+                            cq = in ? (long long)c32 : 0;
+                        } else {
+#pragma unroll
+                            for (int k = 0; k < L; ++k)
+                                if (k < nc && in) cq += count_of(k) * (long long)s_coarse[q * stride + k];
+                        }
                     } else {
                         for (int k = 0; k < nc; ++k) {
                             const long long nk = count_of(k);
@@ -921,10 +953,20 @@ __global__ __launch_bounds__(kShardThreads) void k_shard_allocate_waves(
                             const uint4 r0 = *reinterpret_cast<const uint4*>(row);
                             const uint4 r1 = *reinterpret_cast<const uint4*>(row + 8);
                             const unsigned w[8] = {r0.x, r0.y, r0.z, r0.w, r1.x, r1.y, r1.z, r1.w};
+                            if constexpr (L < kWave) {
+                                unsigned c32 = 0u;   // (fits: see the coarse step)
 #pragma unroll
-                            for (int k = 0; k < 16; ++k) {
-                                const unsigned kge = (k & 1) ? (w[k >> 1] >> 16) : (w[k >> 1] & 0xffffu);
-                                if (k < nc) ct += count_of(k) * (long long)kge;   // uniform
+                                for (int k = 0; k < 16; ++k) {
+                                    const unsigned kge = (k & 1) ? (w[k >> 1] >> 16) : (w[k >> 1] & 0xffffu);
+                                    if (k < L && k < nc) c32 = __umul24((unsigned)n_all[k < L ? k : 0], kge) + c32;   // uniform
+                                }
+                                ct = (long long)c32;
+                            } else {
+#pragma unroll
+                                for (int k = 0; k < 16; ++k) {
+                                    const unsigned kge = (k & 1) ? (w[k >> 1] >> 16) : (w[k >> 1] & 0xffffu);
+                                    if (k < nc) ct += count_of(k) * (long long)kge;   // uniform
+                                }
                             }
                         } else if constexpr (L < kWave) {
 #pragma unroll
@@ -978,7 +1020,9 @@ __global__ __launch_bounds__(kShardThreads) void k_shard_allocate_waves(
                     const long long i = i0 + sl;
                     const bool in = i < hi_i;
                     int x = 0;
-                    if (in) {
+                    if (i0 == lo_i) {
+                        x = x_first;
+                    } else if (in) {
                         x = src.c[i];
                         x = x < 0 ? 0 : (x > g0 ? g0 : x);
                     }
