@@ -161,12 +161,19 @@ def other_paths(torch, hora, wl, sess, a1, c1, w1, delta1, util1, goff1, ws, rep
     sizes = rng_g.integers(8, 25, 1 << 20)
     goff_big = torch.from_numpy(np.concatenate(([0], np.cumsum(sizes))).astype(np.int32)).to("cuda:0")
     n_big = int(goff_big[-1])
-    rew_big = (torch.rand(n_big, device="cuda:0") < 0.4).to(torch.float32)
-    adv_big = torch.empty_like(rew_big)
-    us = mean_us(lambda: hora.hora_group_advantage(goff_big, rew_big, adv_big, hora.ADV_GRPO, sess.dev_status, eps=1e-6))
-    out["group_advantage_grpo_2^20_groups"] = {"responses": n_big, "us_per_call": us,
-                                               "GBps": (8 * n_big + 4 * (sizes.size + 1)) / us / 1e3}
-    del rew_big, adv_big, goff_big
+    for dt, tag in ((torch.float32, ""), (torch.float64, "_f64")):
+        rew_big = (torch.rand(n_big, device="cuda:0") < 0.4).to(dt)
+        adv_big = torch.empty_like(rew_big)
+        size = rew_big.element_size()
+        for mode, name in ((hora.ADV_GRPO, "grpo"), (hora.ADV_RLOO, "rloo")):
+            us = mean_us(lambda: hora.hora_group_advantage(goff_big, rew_big, adv_big, mode, sess.dev_status, eps=1e-6))
+            gbps = (2 * size * n_big + 4 * (sizes.size + 1)) / us / 1e3
+            out[f"group_advantage_{name}_2^20_groups{tag}"] = {"responses": n_big, "us_per_call": us, "GBps": gbps,
+                                                               "frac_of_hbm_peak": gbps / 8000.0}
+        us = mean_us(lambda: adv_big.copy_(rew_big))      # a plain copy of the same rewards, for comparison
+        out[f"plain_copy_of_the_rewards{tag}"] = {"us_per_call": us, "GBps": 2 * size * n_big / us / 1e3}
+        del rew_big, adv_big
+    del goff_big
     us = mean_us(lambda: hora.hora_allocate_baseline(c1, w1.g0, w1.budget, hora.RULE_HARD_FIRST, delta1,
                                                      sess.dev_status, ws, util=util1, group_off=goff1))
     out["allocate_hard_first_large_alloc"] = {"us_per_call": us, "prompts_per_s": w1.n / us * 1e6}

@@ -110,9 +110,11 @@ int hora_marginal_gains(int64_t n, const double *alpha, const double *beta, int3
 
 /*
  * Bytes of workspace hora_allocate / hora_allocate_posterior / hora_allocate_baseline need
- * for n prompts (a workspace sized for n serves every smaller batch).  The workspace is device
- * memory, 256-byte aligned, and needs no initialisation: nothing is carried from one call to
- * the next.  Two calls that may run concurrently need separate workspaces.
+ * for n prompts (a workspace sized for n serves every smaller batch): about 10 MB plus 12
+ * bytes per prompt (the threshold search keeps the state of every prompt's walk between its
+ * kernels).  The workspace is device memory, 256-byte aligned, and needs no initialisation:
+ * nothing is carried from one call to the next.  Two calls that may run concurrently need
+ * separate workspaces.
  */
 size_t hora_allocate_workspace_bytes(int64_t n, int32_t g0);
 

@@ -5,15 +5,18 @@
 // (prompt, l) pairs; every prompt's gains decrease strictly, so the set is described by a
 // threshold tau, the budget-th largest gain.  tau is found by a bisection on its bit pattern
 // (positive binary64 values order like their patterns) in which every prompt does a monotone
-// search along its own gain sequence.  Six launches do it for any input:
+// search along its own gain sequence.  Six launches do it for any input, and a prompt's
+// sequence is walked once: each kernel leaves the state of every walk (a gain and its index l)
+// for the next one to go on from.
 //
-//  1. coarse count (k_bisect_coarse): every tile of 4096 prompts walks its prompts' gains
-//     downwards octave by octave (an octave = one exponent step of the pattern), counting them
-//     per quarter octave, until the tile has seen its share of the budget.  If every tile
-//     selected its share on its own, the union would hold at least `budget` gains, all of them
-//     above the lowest tile's stopping point: that point is a lower bound for tau, whatever the
-//     data, and no prompt walks much deeper than tau.  The walks are resumable (state in
-//     registers), so going deeper costs no second walk.
+//  1. coarse count (k_bisect_coarse): a sample of the batch says roughly how deep tau lies
+//     (estimate_depth; it steers the work, nothing relies on it).  Every tile of 4096 prompts
+//     walks its prompts' gains down to that depth in one go, counting them per quarter octave
+//     (an octave = one exponent step of the pattern), and goes on octave by octave until the
+//     tile has seen its share of the budget.  If every tile selected its share on its own, the
+//     union would hold at least `budget` gains, all of them above the lowest tile's stopping
+//     point: that point is a lower bound for tau, whatever the data, and no prompt walks much
+//     deeper than tau.
 //  2. first narrowing pass (k_bisect_pass<0>): every workgroup adds the tiles' counts up for
 //     itself and takes the quarter octave in which the running count reaches the budget as the
 //     first bracket (lo, hi] of tau; the bracket is cut into 256 intervals, the gains inside are
@@ -574,7 +577,7 @@ __device__ __forceinline__ void list_append(SelectShared& sh, unsigned long long
 
 // ----------------------------------------------------------------------------------
 // 2. The tiles' coarse counts added up, and the first bracket; run by every workgroup of the
-// first narrowing pass for itself (the slots are 272 bytes per 4096 prompts: reading them all
+// first narrowing pass for itself (the slots are 144 bytes per 4096 prompts: reading them all
 // costs less than a launch in between).  Octave o can be resolved when every tile still has it
 // in detail (o >= stop - 7 for all tiles) and every tile that has gains left walked it
 // completely (o <= stop for those).  Inside that range the quarter octave in which the
