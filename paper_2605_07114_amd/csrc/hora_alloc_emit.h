@@ -45,7 +45,9 @@ struct AllocHeader {              // 256 bytes at the start of the workspace
     unsigned int lists_ok;        // no workgroup ran out of room in its list (written between passes)
     unsigned int pad0;
     unsigned long long ck_top;    // the coarse count left every prompt's walk state at its first gain <= this pattern
-    unsigned long long pad[20];
+    unsigned int uneven;          // the depth estimate found walks of very different length (pooled walks pay)
+    unsigned int pad1;
+    unsigned long long pad[19];
 };
 static_assert(sizeof(Bracket) == 32, "bracket size");
 static_assert(sizeof(AllocHeader) == 256, "header size");

@@ -185,11 +185,12 @@ struct EstimateShared {
     // octave's entries, so every octave has entries of its own, cleared two octaves ahead
     unsigned long long count[4];   // gains of the sample in that octave
     int alive[4];                  // a sample prompt has gains left below that octave
+    int deepest;                   // most gains of one sample prompt above the estimated depth
 };
 
 template <class Src>
 __device__ __forceinline__ void estimate_depth(const Src& src, long long n, long long budget, long long limit,
-                                               EstimateShared& es, int& est, int& ck) {
+                                               EstimateShared& es, int& est, int& ck, bool& uneven) {
     const bool walker = threadIdx.x < kEstWaves * kWave;
     const double limit_d = (double)limit;
     double b[kEstItems], s[kEstItems], g[kEstItems], lf[kEstItems];
@@ -213,6 +214,7 @@ __device__ __forceinline__ void estimate_depth(const Src& src, long long n, long
         es.count[threadIdx.x] = 0ull;
         es.alive[threadIdx.x] = 0;
     }
+    if (threadIdx.x == 0) es.deepest = 0;
     __syncthreads();
     // the sample's share of the budget, rounded up (budget <= 2^51: no overflow)
     const unsigned long long want = ((unsigned long long)budget * kEstSamples + (unsigned long long)n - 1ull) /
@@ -267,6 +269,28 @@ __device__ __forceinline__ void estimate_depth(const Src& src, long long n, long
     }
     est = o;
     ck = (o > first && before > sure) ? o - 1 : o;   // (before: the count at the bottom of octave o - 1)
+    // how uneven the walks are: the deepest one against the mean (lf is a walk's length by now)
+    if (walker) {
+        double deep = 0.0;
+#pragma unroll
+        for (int j = 0; j < kEstItems; ++j) deep = lf[j] > deep ? lf[j] : deep;
+        int d = (int)(deep < 1.0e9 ? deep : 1.0e9);
+#pragma unroll
+        for (int k = kWave / 2; k > 0; k >>= 1) {
+            const int other = __shfl_xor(d, k, kWave);
+            d = other > d ? other : d;
+        }
+        if (lane_id() == 0 && d > 0) atomicMax(&es.deepest, d);
+    }
+    __syncthreads();
+    // lockstep walks take as many rounds as the deepest prompt of a wavefront, pooled ones
+    // (pooled_walk) as many as its mean, at a higher cost per round: measured, pooling pays for
+    // deep budgets (deepest 592 against a mean of 200: 1.3 times faster; 3266 against 200: 2.7
+    // times) and not for shallow ones whatever their spread (a deepest of 30 against a mean of 8:
+    // no gain in the coarse count, a loss in the output kernel: staging, barriers and scattered
+    // stores weigh more than the idle lanes).  Pooled above a mean of 32 and deepest > 2 mean + 8.
+    uneven = cum > 32ull * kEstSamples &&
+             (unsigned long long)es.deepest * kEstSamples > 2ull * cum + 8ull * kEstSamples;
 }
 
 // ----------------------------------------------------------------------------------
@@ -282,6 +306,62 @@ __device__ __forceinline__ void estimate_depth(const Src& src, long long n, long
 // walked completely by every tile).  LDS keeps a ring of kRing octaves of counts; the slot
 // keeps the last kWinOct.
 // ----------------------------------------------------------------------------------
+// ----------------------------------------------------------------------------------
+// The first go of the coarse count for prompts of very different depth.  In lockstep a
+// wavefront walks as many rounds as its deepest prompt needs; here the 256 prompts of a
+// wavefront are a pool: a lane takes a prompt, produces its gains one per round (one
+// division per round, the first gain a / s included: the same operations in the same order
+// as gain_first / gain_next), counts them as the lockstep walk does, leaves the prompt's
+// walk state when the prompt is through, and takes the next prompt of the pool.  The
+// posteriors come from LDS (pool_a, pool_b: the wavefront's 256 entries).
+// ----------------------------------------------------------------------------------
+__device__ __forceinline__ void pooled_walk(const double* __restrict__ pool_a, const double* __restrict__ pool_b,
+                                            int items, long long first_pos, double limit_d,
+                                            unsigned long long est_bottom, unsigned long long fine_top,
+                                            unsigned long long top_ck, unsigned (*fine)[kBig], unsigned& higher,
+                                            bool& left_alive, double* __restrict__ ck_g,
+                                            int32_t* __restrict__ ck_l) {
+    int next = kWave;                       // the pool's next prompt (the same in every lane)
+    int t = lane_id();                      // this lane's prompt
+    bool have = t < items;
+    double a = have ? pool_a[t] : 1.0, b = have ? pool_b[t] : 1.0;
+    double s = a + b, g = 0.0, l = 0.0;     // l: the index of the gain produced next
+    double keep_g = 0.0, keep_l = 0.0;
+    bool fresh = true, kept = false;
+    while (__ballot(have)) {
+        const double num = fresh ? a : g * (b + (l - 1.0));
+        const double den = fresh ? s : s + l;
+        g = num / den;
+        fresh = false;
+        const unsigned long long gb = gain_bits(g);
+        const bool valid = l < limit_d && gb != 0ull;
+        const bool count = have && valid && gb > est_bottom;
+        if (count) {
+            if (gb > fine_top) ++higher;
+            else atomicAdd(&fine[(unsigned)((fine_top - gb) >> 50)][threadIdx.x], 1u);
+        }
+        // the first state at or below the top of the kept octave, or the one the walk ends in
+        if (have && !kept && (!valid || gb <= top_ck)) { keep_g = g; keep_l = l; kept = true; }
+        const bool through = have && !count;
+        if (count) l += 1.0;
+        const unsigned long long m = __ballot(through);
+        if (m) {                            // uniform
+            if (through) {
+                left_alive |= valid;
+                ck_g[first_pos + t] = keep_g;
+                ck_l[first_pos + t] = (int)keep_l;
+                t = next + lanes_below(m);
+                have = t < items;
+                if (have) { a = pool_a[t]; b = pool_b[t]; s = a + b; }
+                l = 0.0;
+                fresh = true;
+                kept = false;
+            }
+            next += __popcll(m);
+        }
+    }
+}
+
 constexpr int kFine = kWinOct * kSubBins;   // quarter octaves counted per thread in the first go
 static_assert(kFine == kBigWaves, "one wavefront adds up one quarter octave");
 
@@ -296,14 +376,16 @@ __global__ __launch_bounds__(kBig) void k_bisect_coarse(Src src, long long n, lo
     __shared__ unsigned long long s_octave[4];   // [octave & 3] gains counted in an octave after it (see EstimateShared)
     __shared__ int s_alive[4];
     __shared__ EstimateShared s_est;
+    __shared__ double s_pool[2][kTile];          // the tile's posteriors for pooled_walk
     const long long base = (long long)blockIdx.x * chunk;
     const long long end = base + chunk < n ? base + chunk : n;
     Fetched<Src> first_tile;
     fetch(src, base + (long long)threadIdx.x * kItems, base + kTile < end ? base + kTile : end, first_tile);
     int est, ck;
-    estimate_depth(src, n, budget, limit, s_est, est, ck);
+    bool uneven;
+    estimate_depth(src, n, budget, limit, s_est, est, ck, uneven);
     const unsigned long long top_ck = octave_top(ck);
-    if (blockIdx.x == 0 && threadIdx.x == 0) hdr->ck_top = top_ck;
+    if (blockIdx.x == 0 && threadIdx.x == 0) { hdr->ck_top = top_ck; hdr->uneven = uneven ? 1u : 0u; }
     const unsigned long long est_bottom = octave_top(est) - kOctave;
     const unsigned long long fine_top = octave_top(est - (kWinOct - 1));   // (above 1.0 when est < kWinOct - 1: no gain lies there)
     const int lane = lane_id();
@@ -340,7 +422,50 @@ __global__ __launch_bounds__(kBig) void k_bisect_coarse(Src src, long long n, lo
         __syncthreads();
         // everything down to the bottom of octave `est` in one go
         unsigned higher = 0u;   // gains above the counted octaves (a lane sees at most kItems * limit <= 2^22)
-        {
+        bool pooled = uneven;
+        if (pooled) {
+#pragma unroll
+            for (int j = 0; j < kItems; ++j) {
+                s_pool[0][threadIdx.x * kItems + j] = a[j];
+                s_pool[1][threadIdx.x * kItems + j] = b[j];
+            }
+            __syncthreads();   // (a wavefront reads what its own lanes wrote; the barrier also keeps the order)
+            const long long first_pos = t0 + (long long)wave_id() * (kWave * kItems);
+            const long long left = tile_end - first_pos;
+            bool left_alive = false;
+            pooled_walk(s_pool[0] + wave_id() * (kWave * kItems), s_pool[1] + wave_id() * (kWave * kItems),
+                        (int)(left < kWave * kItems ? (left > 0 ? left : 0) : kWave * kItems), first_pos, limit_d,
+                        est_bottom, fine_top, top_ck, s_fine, higher, left_alive, ck_g, ck_l);
+            const bool wave_alive = __ballot(left_alive) != 0ull;
+            const long long higher_all = wave_total_i64((long long)higher);
+            if (lane == 0) {
+                if (higher_all) atomicAdd(&s_total, (unsigned long long)higher_all);
+                if (wave_alive) s_alive[est & 3] = 1;
+            }
+            __syncthreads();   // the counters of all threads are complete
+            {
+                // (a pooled walk cannot go on octave by octave, its walks are not in registers any more:
+                // a tile that is short of its share is walked again, in lockstep)
+                long long acc = 0;
+#pragma unroll
+                for (int i = 0; i < kBig / kWave; ++i) acc += (long long)s_fine[wave_id()][lane + kWave * i];
+                acc = wave_total_i64(acc);
+                if (lane == 0 && acc) atomicAdd(&s_octave[0], (unsigned long long)acc);   // (s_octave[0] is free until then)
+            }
+            __syncthreads();
+            const bool short_of_share = s_total + s_octave[0] < need && s_alive[est & 3] != 0 && est < kMaxOctave;
+            __syncthreads();
+            if (short_of_share) {   // uniform
+                pooled = false;
+                higher = 0u;
+                if (threadIdx.x == 0) { s_total = 0ull; s_alive[est & 3] = 0; }
+#pragma unroll
+                for (int f = 0; f < kFine; ++f) s_fine[f][threadIdx.x] = 0u;
+            }
+            if (threadIdx.x == 0) s_octave[0] = 0ull;
+            __syncthreads();
+        }
+        if (!pooled) {
             bool any;
             do {
                 any = false;
@@ -360,9 +485,7 @@ __global__ __launch_bounds__(kBig) void k_bisect_coarse(Src src, long long n, lo
                     any |= act;
                 }
             } while (any);
-        }
-        store_states(ck_g, ck_l, pos, tile_end, keep_g, keep_l);
-        {
+            store_states(ck_g, ck_l, pos, tile_end, keep_g, keep_l);
             bool mine_alive = false;
 #pragma unroll
             for (int j = 0; j < kItems; ++j) mine_alive |= alive[j];
@@ -1018,6 +1141,39 @@ __device__ unsigned long long finish_search(SelectShared& sh, const Src& src, lo
 // flag go to delta[i] (flag in bit 31), the survival product E_i(k_i) to util[i]; per-workgroup sums to block_ksum /
 // block_tied.  kItems prompts per thread, their walks in lockstep.
 // ----------------------------------------------------------------------------------
+// The survival products E_i(k_i) of one wavefront's 256 prompts, pooled like pooled_walk (the
+// number of steps k_i is known here): a lane takes a prompt, multiplies and divides k_i times,
+// leaves the product in place of the prompt's beta, and takes the next prompt.  LDS arrays of
+// the wavefront: beta (in) / E (out), alpha + beta, k.
+__device__ __forceinline__ void pooled_survival(double* __restrict__ pool_b, const double* __restrict__ pool_s,
+                                                const int* __restrict__ pool_k) {
+    constexpr int kPool = kWave * kItems;
+    int next = kWave;
+    int t = lane_id();
+    bool have = true;
+    double b = pool_b[t], s = pool_s[t], e = 1.0, j = 0.0;
+    double k = (double)pool_k[t];
+    while (__ballot(have)) {
+        if (have && j < k) {
+            e = surv_next(e, b, s, j);
+            j += 1.0;
+        }
+        const bool through = have && !(j < k);
+        const unsigned long long m = __ballot(through);
+        if (m) {   // uniform
+            if (through) {
+                pool_b[t] = e;
+                t = next + lanes_below(m);
+                have = t < kPool;
+                if (have) { b = pool_b[t]; s = pool_s[t]; k = (double)pool_k[t]; }
+                e = 1.0;
+                j = 0.0;
+            }
+            next += __popcll(m);
+        }
+    }
+}
+
 template <class Src>
 __global__ __launch_bounds__(kBig) void k_bisect_finalize(Src src, long long n, long long chunk, long long budget,
                                                           long long limit, int depth_capped, int nb,
@@ -1052,6 +1208,9 @@ __global__ __launch_bounds__(kBig) void k_bisect_finalize(Src src, long long n, 
     const bool d_vec = (reinterpret_cast<uintptr_t>(delta) & 15) == 0;
     const bool u_vec = (reinterpret_cast<uintptr_t>(util) & 15) == 0;
     const double limit_d = (double)limit;
+    const bool uneven = budget > 0 && hdr->uneven != 0;   // (written by the coarse count of this call)
+    __shared__ double s_pool_b[kTile], s_pool_s[kTile];
+    __shared__ int s_pool_k[kTile];
     long long ks = 0, ts = 0;
     bool too_deep = false;
     for (long long t0 = base; t0 < end; t0 += kTile) {
@@ -1085,8 +1244,23 @@ __global__ __launch_bounds__(kBig) void k_bisect_finalize(Src src, long long n, 
                 any |= act;
             }
         } while (any);
-        // ... the survival product takes its k steps from the start
-        if (util) {
+        // ... the survival product takes its k steps from the start: pooled over the wavefront
+        // where the depth estimate found prompts of very different depth, else in lockstep
+        if (util && uneven) {
+#pragma unroll
+            for (int j = 0; j < kItems; ++j) {
+                s_pool_b[threadIdx.x * kItems + j] = b[j];
+                s_pool_s[threadIdx.x * kItems + j] = s[j];
+                s_pool_k[threadIdx.x * kItems + j] = alive[j] ? (int)lf[j] : 0;
+            }
+            __syncthreads();
+            const int at = wave_id() * (kWave * kItems);
+            pooled_survival(s_pool_b + at, s_pool_s + at, s_pool_k + at);
+            __syncthreads();
+#pragma unroll
+            for (int j = 0; j < kItems; ++j) e[j] = s_pool_b[threadIdx.x * kItems + j];
+            __syncthreads();   // the arrays are reused by the next tile
+        } else if (util) {
             double le[kItems];
 #pragma unroll
             for (int j = 0; j < kItems; ++j) le[j] = 0.0;

@@ -293,6 +293,34 @@ def test_depth_estimate_from_an_unrepresentative_sample(gpu, oracle):
         assert np.array_equal(got.delta.cpu().numpy().astype(np.int64), want)
 
 
+def test_deep_budgets_with_walks_of_very_different_length(gpu, oracle):
+    """With a deep budget and prompts whose gain sequences decay at very different rates the
+    threshold search hands a wavefront's prompts to its lanes one by one instead of walking them
+    in lockstep (coarse count and survival products).  Same allocation, same utilities; also when
+    half of the tiles hold nothing but reluctant prompts, so that they end the pooled walk short
+    of their share and are walked again octave by octave."""
+    sess, torch, hora = gpu
+    rng = np.random.default_rng(31)
+    n, g0 = 40000, 8
+    alpha, beta, _ = learned_prior(rng, n, g0)
+    cases = {"mixed": (alpha, beta)}
+    a2, b2 = alpha.copy(), beta.copy()
+    a2[n // 2:] = 0.02 + rng.uniform(0.0, 0.01, n - n // 2)       # hopeless prompts: gains ~ 1e-3 and below
+    b2[n // 2:] = 30.0 + rng.uniform(0.0, 1.0, n - n // 2)
+    cases["half of the tiles reluctant"] = (a2, b2)
+    for name, (al, be) in cases.items():
+        for budget, cap in ((100 * n, 0), (150 * n, 400)):
+            want = oracle.allocate_posterior(al, be, budget, delta_max=cap)
+            print(f"allocate_posterior deep, {name}: n={n} budget={budget} cap={cap} deepest={int(want.max())} "
+                  f"mean={want.mean():.0f}", flush=True)
+            got = sess.allocate_posterior(dev(torch, al), dev(torch, be), g0, budget, delta_max=cap)
+            assert sess.status() == 0
+            assert np.array_equal(got.delta.cpu().numpy().astype(np.int64), want)
+            idx = rng.integers(0, n, 2000)
+            np.testing.assert_allclose(got.util.cpu().numpy()[idx], oracle.utilities(al[idx], be[idx], want[idx]),
+                                       rtol=UTIL_RTOL, atol=0)
+
+
 def test_learned_prior_collapses_to_the_uniform_prior(gpu, oracle):
     # App. D: s = 2, p = 1/2 gives alpha = 1 + c, beta = 1 + G0 - c
     sess, torch, hora = gpu
