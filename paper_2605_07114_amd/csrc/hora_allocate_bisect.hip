@@ -49,6 +49,7 @@ constexpr unsigned long long kOctave = 1ull << 52;          // one exponent step
 constexpr int kMaxOctave = 1022;                            // octave o holds (2^-(o+1), 2^-o]; the last one ends at 0
 constexpr int kRing = 2 * kWinOct;                          // octaves of counts a tile keeps in LDS while walking
 constexpr unsigned long long kWindowStep = 4ull << 52;      // fallback windows: a factor 16 in value
+constexpr long long kDeepRatio = 24;                            // budgets above this many units per prompt: kernels that can pool walks
 constexpr int kFinalMaxPasses = 600;                        // one-workgroup finisher: windows down to zero plus narrowing passes
 static_assert(kListCap % kBig == 0, "a thread holds a fixed number of list entries");
 static_assert((kWinOct & (kWinOct - 1)) == 0 && kSubBins == 4, "octave window");
@@ -365,7 +366,9 @@ __device__ __forceinline__ void pooled_walk(const double* __restrict__ pool_a, c
 constexpr int kFine = kWinOct * kSubBins;   // quarter octaves counted per thread in the first go
 static_assert(kFine == kBigWaves, "one wavefront adds up one quarter octave");
 
-template <class Src>
+// kDeep: the variant for deep budgets (the host's choice, budget > kDeepRatio * n), which
+// can pool its walks; the other one does without that code, its registers and its LDS.
+template <class Src, bool kDeep>
 __global__ __launch_bounds__(kBig) void k_bisect_coarse(Src src, long long n, long long budget, long long limit,
                                                         long long chunk, CoarseSlot* __restrict__ slots,
                                                         AllocHeader* __restrict__ hdr, double* __restrict__ ck_g,
@@ -376,7 +379,6 @@ __global__ __launch_bounds__(kBig) void k_bisect_coarse(Src src, long long n, lo
     __shared__ unsigned long long s_octave[4];   // [octave & 3] gains counted in an octave after it (see EstimateShared)
     __shared__ int s_alive[4];
     __shared__ EstimateShared s_est;
-    __shared__ double s_pool[2][kTile];          // the tile's posteriors for pooled_walk
     const long long base = (long long)blockIdx.x * chunk;
     const long long end = base + chunk < n ? base + chunk : n;
     Fetched<Src> first_tile;
@@ -422,8 +424,9 @@ __global__ __launch_bounds__(kBig) void k_bisect_coarse(Src src, long long n, lo
         __syncthreads();
         // everything down to the bottom of octave `est` in one go
         unsigned higher = 0u;   // gains above the counted octaves (a lane sees at most kItems * limit <= 2^22)
-        bool pooled = uneven;
-        if (pooled) {
+        bool pooled = kDeep && uneven;
+        if constexpr (kDeep) if (pooled) {
+            __shared__ double s_pool[2][kTile];   // the tile's posteriors for pooled_walk
 #pragma unroll
             for (int j = 0; j < kItems; ++j) {
                 s_pool[0][threadIdx.x * kItems + j] = a[j];
@@ -1174,7 +1177,7 @@ __device__ __forceinline__ void pooled_survival(double* __restrict__ pool_b, con
     }
 }
 
-template <class Src>
+template <class Src, bool kDeep>
 __global__ __launch_bounds__(kBig) void k_bisect_finalize(Src src, long long n, long long chunk, long long budget,
                                                           long long limit, int depth_capped, int nb,
                                                           AllocHeader* __restrict__ hdr,
@@ -1189,6 +1192,7 @@ __global__ __launch_bounds__(kBig) void k_bisect_finalize(Src src, long long n, 
     long long (&s_red)[2][kBigWaves] = *reinterpret_cast<long long (*)[2][kBigWaves]>(&sh.bins.cnt[0]);
     const long long base = (long long)blockIdx.x * chunk;
     const long long end = base + chunk < n ? base + chunk : n;
+    const bool uneven = kDeep && budget > 0 && hdr->uneven != 0;   // (written by the coarse count of this call)
     // (the loads of the first tile are under way while the search is finished)
     Fetched<Src> first_tile;
     WalkStates first_states;
@@ -1208,9 +1212,6 @@ __global__ __launch_bounds__(kBig) void k_bisect_finalize(Src src, long long n, 
     const bool d_vec = (reinterpret_cast<uintptr_t>(delta) & 15) == 0;
     const bool u_vec = (reinterpret_cast<uintptr_t>(util) & 15) == 0;
     const double limit_d = (double)limit;
-    const bool uneven = budget > 0 && hdr->uneven != 0;   // (written by the coarse count of this call)
-    __shared__ double s_pool_b[kTile], s_pool_s[kTile];
-    __shared__ int s_pool_k[kTile];
     long long ks = 0, ts = 0;
     bool too_deep = false;
     for (long long t0 = base; t0 < end; t0 += kTile) {
@@ -1246,7 +1247,11 @@ __global__ __launch_bounds__(kBig) void k_bisect_finalize(Src src, long long n, 
         } while (any);
         // ... the survival product takes its k steps from the start: pooled over the wavefront
         // where the depth estimate found prompts of very different depth, else in lockstep
-        if (util && uneven) {
+        bool lockstep = true;
+        if constexpr (kDeep) if (util && uneven) {
+            __shared__ double s_pool_b[kTile], s_pool_s[kTile];
+            __shared__ int s_pool_k[kTile];
+            lockstep = false;
 #pragma unroll
             for (int j = 0; j < kItems; ++j) {
                 s_pool_b[threadIdx.x * kItems + j] = b[j];
@@ -1260,7 +1265,8 @@ __global__ __launch_bounds__(kBig) void k_bisect_finalize(Src src, long long n, 
 #pragma unroll
             for (int j = 0; j < kItems; ++j) e[j] = s_pool_b[threadIdx.x * kItems + j];
             __syncthreads();   // the arrays are reused by the next tile
-        } else if (util) {
+        }
+        if (util && lockstep) {
             double le[kItems];
 #pragma unroll
             for (int j = 0; j < kItems; ++j) le[j] = 0.0;
@@ -1413,9 +1419,16 @@ static int run_bisect(const Src& src, const CommonArgs& a, const Plan& p, const 
     const int depth_capped = wanted > (long long)HORA_MAX_DEPTH ? 1 : 0;
     const long long limit = depth_capped ? (long long)HORA_MAX_DEPTH : wanted;
     const long long tiles = (n + kTile - 1) / kTile;
+    // deep budgets get the kernels that can pool their walks (see estimate_depth: pooling needs a
+    // mean walk of more than 32 steps; the mean is budget / n)
+    const bool deep = a.budget > kDeepRatio * n;
     if (a.budget > 0) {
-        hipLaunchKernelGGL((k_bisect_coarse<Src>), dim3(p.nb), dim3(kBig), 0, a.stream, src, n, (long long)a.budget,
-                           limit, p.chunk, w.coarse, w.header, w.ck_g, w.ck_l, a.dev_status);
+        if (deep)
+            hipLaunchKernelGGL((k_bisect_coarse<Src, true>), dim3(p.nb), dim3(kBig), 0, a.stream, src, n,
+                               (long long)a.budget, limit, p.chunk, w.coarse, w.header, w.ck_g, w.ck_l, a.dev_status);
+        else
+            hipLaunchKernelGGL((k_bisect_coarse<Src, false>), dim3(p.nb), dim3(kBig), 0, a.stream, src, n,
+                               (long long)a.budget, limit, p.chunk, w.coarse, w.header, w.ck_g, w.ck_l, a.dev_status);
         hipLaunchKernelGGL((k_bisect_pass<Src, 0>), dim3(p.nb), dim3(kBig), 0, a.stream, src, n, (long long)a.budget,
                            limit, p.chunk, tiles, (const CoarseSlot*)w.coarse, w.header, w.bins, w.lists,
                            w.list_count, w.ck_g, w.ck_l);
@@ -1428,11 +1441,14 @@ static int run_bisect(const Src& src, const CommonArgs& a, const Plan& p, const 
     // (without a budget there was no search and no walk state)
     const double* state_g = a.budget > 0 ? w.ck_g : nullptr;
     const int32_t* state_l = a.budget > 0 ? w.ck_l : nullptr;
-    hipLaunchKernelGGL((k_bisect_finalize<Src>), dim3(p.nb), dim3(kBig), 0, a.stream, src, n, p.chunk,
-                       (long long)a.budget, limit, depth_capped, p.nb, w.header,
-                       (const unsigned long long*)w.lists, (const int*)w.list_count, state_g, state_l, a.delta,
-                       a.util,
-                       w.block_ksum, w.block_tied, a.dev_status);
+#define HORA_LAUNCH_BISECT_FINALIZE(DEEP)                                                                      \
+    hipLaunchKernelGGL((k_bisect_finalize<Src, DEEP>), dim3(p.nb), dim3(kBig), 0, a.stream, src, n, p.chunk,     \
+                       (long long)a.budget, limit, depth_capped, p.nb, w.header,                                \
+                       (const unsigned long long*)w.lists, (const int*)w.list_count, state_g, state_l, a.delta, \
+                       a.util, w.block_ksum, w.block_tied, a.dev_status)
+    if (deep) HORA_LAUNCH_BISECT_FINALIZE(true);
+    else HORA_LAUNCH_BISECT_FINALIZE(false);
+#undef HORA_LAUNCH_BISECT_FINALIZE
     const int mode = a.group_off ? (a.off_t == HORA_I32 ? 1 : 2) : 0;
 #define HORA_LAUNCH_BISECT_WRITE(M)                                                                       \
     hipLaunchKernelGGL((k_bisect_write<Src, M>), dim3(p.nb), dim3(kBig), 0, a.stream, src, n, (int)a.g0,  \
