@@ -18,6 +18,8 @@
 // shards: the set-up kernel also writes their exclusive prefix sums.
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include <climits>
 #include <cmath>
 #include <cstdint>
@@ -745,33 +747,85 @@ template <int L> struct GroupScratch {   // per shard of the workgroup, LDS
     double e[L];
 };
 
+// Cross-lane steps inside a group of L lanes.  A group of 16 lanes is one row of the DPP
+// cross-lane path: rotations and shifts inside the row are register moves (no LDS crossbar
+// trip, which is what the general shuffles cost); 64-bit values move as two halves.
+template <int kCtrl, int kBankMask>
+__device__ __forceinline__ long long row_take(long long v) {
+    const int lo = __builtin_amdgcn_update_dpp(0, (int)(unsigned)((unsigned long long)v & 0xffffffffull), kCtrl, 0xf,
+                                               kBankMask, true);
+    const int hi = __builtin_amdgcn_update_dpp(0, (int)(unsigned)((unsigned long long)v >> 32), kCtrl, 0xf,
+                                               kBankMask, true);
+    return (long long)(((unsigned long long)(unsigned)hi << 32) | (unsigned long long)(unsigned)lo);
+}
+template <int kCtrl, int kBankMask>
+__device__ __forceinline__ int row_take(int v) {
+    return __builtin_amdgcn_update_dpp(0, v, kCtrl, 0xf, kBankMask, true);
+}
+
 template <typename T, int L>
 __device__ __forceinline__ T group_sum(T v) {
+    if constexpr (L == 16 && (sizeof(T) == 4 || sizeof(T) == 8)) {
+        typedef typename std::conditional<sizeof(T) == 4, int, long long>::type R;
+        R x = (R)v;
+        x += row_take<0x128, 0xf>(x);   // row_ror:8
+        x += row_take<0x124, 0xf>(x);   // row_ror:4
+        x += row_take<0x122, 0xf>(x);   // row_ror:2
+        x += row_take<0x121, 0xf>(x);   // row_ror:1
+        return (T)x;
+    } else {
 #pragma unroll
-    for (int d = L / 2; d > 0; d >>= 1) v += __shfl_xor(v, d, L);
-    return v;
+        for (int d = L / 2; d > 0; d >>= 1) v += __shfl_xor(v, d, L);
+        return v;
+    }
 }
 template <int L>
 __device__ __forceinline__ long long group_max(long long v) {
+    if constexpr (L == 16) {
+        long long o = row_take<0x128, 0xf>(v); v = o > v ? o : v;
+        o = row_take<0x124, 0xf>(v); v = o > v ? o : v;
+        o = row_take<0x122, 0xf>(v); v = o > v ? o : v;
+        o = row_take<0x121, 0xf>(v); v = o > v ? o : v;
+        return v;
+    } else {
 #pragma unroll
-    for (int d = L / 2; d > 0; d >>= 1) {
-        const long long o = __shfl_xor(v, d, L);
-        v = o > v ? o : v;
+        for (int d = L / 2; d > 0; d >>= 1) {
+            const long long o = __shfl_xor(v, d, L);
+            v = o > v ? o : v;
+        }
+        return v;
     }
-    return v;
 }
 template <int L>
 __device__ __forceinline__ long long group_incl_scan(long long v, int sl) {
+    if constexpr (L == 16) {
+        // shifts by 1, 2, 3 inside the row, then by 4 and 8 with bank masks (lanes without a source add 0)
+        long long t = v + row_take<0x111, 0xf>(v) + row_take<0x112, 0xf>(v) + row_take<0x113, 0xf>(v);
+        t += row_take<0x114, 0xe>(t);
+        t += row_take<0x118, 0xc>(t);
+        return t;
+    } else {
 #pragma unroll
-    for (int d = 1; d < L; d <<= 1) {
-        const long long o = __shfl_up(v, d, L);
-        if (sl >= d) v += o;
+        for (int d = 1; d < L; d <<= 1) {
+            const long long o = __shfl_up(v, d, L);
+            if (sl >= d) v += o;
+        }
+        return v;
     }
-    return v;
+}
+// The value of the group's last lane, in every lane of the group.
+template <int L>
+__device__ __forceinline__ long long group_last(long long v) {
+    if constexpr (L == 16) {
+        // lane 15 of the row: keep it alone, then the row's sum
+        return group_sum<long long, L>((lane_id() & 15) == 15 ? v : 0ll);
+    } else {
+        return __shfl(v, L - 1, L);
+    }
 }
 
 template <int kOff, int L, bool kFused>
-__global__ __launch_bounds__(kShardThreads) void k_shard_allocate_waves(
+__global__ __launch_bounds__(kShardThreads, (L == 16 && !kFused) ? 6 : 1) void k_shard_allocate_waves(
     CountsSource src, long long n, long long n_shards, const long long* __restrict__ shard_off,
     const long long* __restrict__ shard_budget, int cap, const long long* __restrict__ prefix, int depth, int usable,
     ShardTableKey* __restrict__ key, double* __restrict__ gain_table, double* __restrict__ surv_table,
@@ -1059,7 +1113,7 @@ __global__ __launch_bounds__(kShardThreads) void k_shard_allocate_waves(
                         }
                     }
                     rank_base += __popcll(tied_mask);
-                    given += __shfl(incl, L - 1, L);
+                    given += group_last<L>(incl);
                 }
             }
         }
