@@ -986,8 +986,13 @@ __global__ __launch_bounds__(kShardThreads, (L == 16 && !kFused) ? 6 : 1) void k
                             if (in) cq += nk * (long long)s_coarse[q * stride + k];
                         }
                     }
-                    if (in && cq >= budget) block = q < block ? q : block;
+                    const bool reached = in && cq >= budget;
+                    if (reached) block = q < block ? q : block;
                     if (in && cq < budget) below = cq > below ? cq : below;
+                    // the counts grow with the level: once every group of the wavefront has a block
+                    // that reaches its budget, the blocks further down cannot be the first
+                    const unsigned long long found = __ballot(reached);
+                    if (__ballot(((found >> shift) & kGroupMask) == 0ull) == 0ull) break;
                 }
                 block = -(int)group_max<L>((long long)(-block));   // the smallest over the group
                 const long long before_block = group_max<L>(below);       // the counts grow with the level: this is block - 1's
