@@ -763,6 +763,22 @@ __device__ __forceinline__ int row_take(int v) {
     return __builtin_amdgcn_update_dpp(0, v, kCtrl, 0xf, kBankMask, true);
 }
 
+// The bits of a wavefront ballot that belong to the lane's group of L lanes (sub = the group's
+// slot in the wavefront), moved down to bit 0: a 32-bit value for the groups that fit one.
+template <int L>
+__device__ __forceinline__ unsigned group_bits(unsigned long long ballot, int sub) {
+    static_assert(L == 16 || L == 32, "narrow groups");
+    const unsigned w = (L == 32 ? sub : (sub >> 1)) ? (unsigned)(ballot >> 32) : (unsigned)ballot;
+    if constexpr (L == 32) return w;
+    else return (w >> ((sub & 1) * 16)) & 0xffffu;
+}
+
+__device__ __forceinline__ int count_bits(unsigned m) { return __popc(m); }
+__device__ __forceinline__ int count_bits(unsigned long long m) { return __popcll(m); }
+// bits of m below bit sl (sl < 32 for the 32-bit form)
+__device__ __forceinline__ int count_below(unsigned m, int sl) { return __popc(m & ((1u << sl) - 1u)); }
+__device__ __forceinline__ int count_below(unsigned long long m, int sl) { return __popcll(m & ((1ull << sl) - 1ull)); }
+
 template <typename T, int L>
 __device__ __forceinline__ T group_sum(T v) {
     if constexpr (L == 16 && (sizeof(T) == 4 || sizeof(T) == 8)) {
@@ -780,9 +796,9 @@ __device__ __forceinline__ T group_sum(T v) {
     }
 }
 template <int L>
-__device__ __forceinline__ long long group_max(long long v) {
+__device__ __forceinline__ int group_max(int v) {
     if constexpr (L == 16) {
-        long long o = row_take<0x128, 0xf>(v); v = o > v ? o : v;
+        int o = row_take<0x128, 0xf>(v); v = o > v ? o : v;
         o = row_take<0x124, 0xf>(v); v = o > v ? o : v;
         o = row_take<0x122, 0xf>(v); v = o > v ? o : v;
         o = row_take<0x121, 0xf>(v); v = o > v ? o : v;
@@ -790,24 +806,24 @@ __device__ __forceinline__ long long group_max(long long v) {
     } else {
 #pragma unroll
         for (int d = L / 2; d > 0; d >>= 1) {
-            const long long o = __shfl_xor(v, d, L);
+            const int o = __shfl_xor(v, d, L);
             v = o > v ? o : v;
         }
         return v;
     }
 }
 template <int L>
-__device__ __forceinline__ long long group_incl_scan(long long v, int sl) {
+__device__ __forceinline__ int group_incl_scan(int v, int sl) {
     if constexpr (L == 16) {
         // shifts by 1, 2, 3 inside the row, then by 4 and 8 with bank masks (lanes without a source add 0)
-        long long t = v + row_take<0x111, 0xf>(v) + row_take<0x112, 0xf>(v) + row_take<0x113, 0xf>(v);
+        int t = v + row_take<0x111, 0xf>(v) + row_take<0x112, 0xf>(v) + row_take<0x113, 0xf>(v);
         t += row_take<0x114, 0xe>(t);
         t += row_take<0x118, 0xc>(t);
         return t;
     } else {
 #pragma unroll
         for (int d = 1; d < L; d <<= 1) {
-            const long long o = __shfl_up(v, d, L);
+            const int o = __shfl_up(v, d, L);
             if (sl >= d) v += o;
         }
         return v;
@@ -815,17 +831,17 @@ __device__ __forceinline__ long long group_incl_scan(long long v, int sl) {
 }
 // The value of the group's last lane, in every lane of the group.
 template <int L>
-__device__ __forceinline__ long long group_last(long long v) {
+__device__ __forceinline__ int group_last(int v) {
     if constexpr (L == 16) {
         // lane 15 of the row: keep it alone, then the row's sum
-        return group_sum<long long, L>((lane_id() & 15) == 15 ? v : 0ll);
+        return group_sum<int, L>((lane_id() & 15) == 15 ? v : 0);
     } else {
         return __shfl(v, L - 1, L);
     }
 }
 
 template <int kOff, int L, bool kFused>
-__global__ __launch_bounds__(kShardThreads, (L == 16 && !kFused) ? 6 : 1) void k_shard_allocate_waves(
+__global__ __launch_bounds__(kShardThreads, (L == 16 && !kFused) ? 8 : 1) void k_shard_allocate_waves(
     CountsSource src, long long n, long long n_shards, const long long* __restrict__ shard_off,
     const long long* __restrict__ shard_budget, int cap, const long long* __restrict__ prefix, int depth, int usable,
     ShardTableKey* __restrict__ key, double* __restrict__ gain_table, double* __restrict__ surv_table,
@@ -834,19 +850,19 @@ __global__ __launch_bounds__(kShardThreads, (L == 16 && !kFused) ? 6 : 1) void k
     hora_alloc_summary* __restrict__ summary, int32_t* dev_status) {
     constexpr int kPerWave = kWave / L;                  // shards per wavefront
     constexpr int kPerBlock = kShardWaves * kPerWave;    // shards per workgroup
-    constexpr unsigned long long kGroupMask = L == 64 ? ~0ull : ((1ull << (L & 63)) - 1ull);
-    __shared__ __align__(16) unsigned short s_coarse[kMaxCoarse * 64];
+    // (16 lanes are chosen for at most 16 classes: their rows have 16 entries)
+    constexpr int kCoarseStride = L == 16 ? 16 : 64;
+    __shared__ __align__(16) unsigned short s_coarse[kMaxCoarse * kCoarseStride];
     __shared__ GroupScratch<L> s_group[kPerBlock];
     __shared__ int s_left[kPerBlock];
     __shared__ int s_left_n, s_tables;
     const int g0 = src.g0;
     const int nc = g0 + 1;                               // (the host picks L >= nc)
-    const int stride = level_stride(nc);
+    const int stride = L == 16 ? 16 : level_stride(nc);
     const int levels = nc * usable;
     const int n_coarse = (levels + kLevelBlock - 1) / kLevelBlock;
     const int lane = lane_id();
     const int sub = lane / L, sl = lane % L;             // the shard's slot in the wavefront, the lane in the group
-    const int shift = sub * L;                           // the group's bits in a wavefront ballot
     const long long first_shard = (long long)blockIdx.x * kPerBlock;
     const int slot = wave_id() * kPerWave + sub;
     const long long shard = first_shard + slot;
@@ -896,6 +912,11 @@ __global__ __launch_bounds__(kShardThreads, (L == 16 && !kFused) ? 6 : 1) void k
     }
     __syncthreads();
     GroupScratch<L>& gs = s_group[slot];
+    // a ballot restricted to the group's lanes, from bit 0 (32 bits wide for the narrow groups)
+    auto group_ballot = [&](bool p) {
+        if constexpr (L == kWave) return (unsigned long long)__ballot(p);
+        else return group_bits<L>(__ballot(p), sub);
+    };
     bool defer = false;        // the workgroup-per-shard code has to take the shard
     if (live) {
         const int wrong = check_shard(shard, n_shards, n, lo_i, hi_i, budget, cap);
@@ -928,7 +949,7 @@ __global__ __launch_bounds__(kShardThreads, (L == 16 && !kFused) ? 6 : 1) void k
 #pragma unroll
                     for (int k = 0; k < L; ++k)
                         if (k < nc) {   // uniform
-                            const int cnt = __popcll((__ballot(x == k) >> shift) & kGroupMask);
+                            const int cnt = count_bits(group_ballot(x == k));
                             n_all[k] += cnt;
                             if (sl == k) n_mine += cnt;
                         }
@@ -941,100 +962,84 @@ __global__ __launch_bounds__(kShardThreads, (L == 16 && !kFused) ? 6 : 1) void k
             }
             if (data_bad) report(dev_status, HORA_ERR_RANGE);
             // the group's count of class k: a register, or lane k's value (a whole wavefront: scalar read)
-            auto count_of = [&](int k) -> long long {
-                if constexpr (L < kWave) return (long long)n_all[k];
-                else return (long long)__builtin_amdgcn_readlane(n_mine, k);
+            auto count_of = [&](int k) -> unsigned {
+                if constexpr (L < kWave) return (unsigned)n_all[k];
+                else return (unsigned)__builtin_amdgcn_readlane(n_mine, k);
+            };
+            // count_ge of a level from its row of per-class counts.  A shard here has at most 2^10
+            // prompts and a class at most 2^9 gains in the tables: a count fits 32 bits, and a
+            // class costs one 24-bit multiply-add.  A row of 16 classes comes as two 16-byte pieces.
+            auto count_row16 = [&](const uint4& r0, const uint4& r1) -> int {
+                const unsigned w[8] = {r0.x, r0.y, r0.z, r0.w, r1.x, r1.y, r1.z, r1.w};
+                unsigned sum = 0u;
+#pragma unroll
+                for (int k = 0; k < 16; ++k) {
+                    const unsigned kge = (k & 1) ? (w[k >> 1] >> 16) : (w[k >> 1] & 0xffffu);
+                    if ((L == kWave || k < L) && k < nc) sum = __umul24(count_of(L == kWave || k < L ? k : 0), kge) + sum;   // uniform
+                }
+                return (int)sum;
+            };
+            auto count_row = [&](const unsigned short* row) -> int {
+                unsigned sum = 0u;
+                if constexpr (L < kWave) {
+#pragma unroll
+                    for (int k = 0; k < L; ++k)
+                        if (k < nc) sum = __umul24(count_of(k), (unsigned)row[k]) + sum;   // uniform
+                } else {
+                    for (int k = 0; k < nc; ++k) sum = __umul24(count_of(k), (unsigned)row[k]) + sum;
+                }
+                return (int)sum;
             };
 
             // ---- 2. threshold
             int k_mine = 0, tied_mine = 0;            // lane c of the group: gains of class c above tau; its next gain equals tau
             double e_mine = 1.0;                      // E_c(k_c)
-            long long count_gt = 0, tie_prompts = 0;
+            int count_gt = 0, tie_prompts = 0;
             unsigned long long tau_bits = 0;
             bool ok = true;
+            const int want = budget < (long long)INT_MAX ? (int)budget : INT_MAX;   // the budget as far as a count can reach
             if (budget > 0) {
                 // coarse: the group's lanes share the blocks; the first block whose last level reaches the budget
                 int block = INT_MAX;
-                long long below = 0;                  // largest coarse count that stays under the budget
+                int below = 0;                        // largest coarse count that stays under the budget
                 for (int q0 = 0; q0 < n_coarse; q0 += L) {
                     const int q = q0 + sl;
-                    long long cq = 0;
                     const bool in = q < n_coarse;
-                    if constexpr (L < kWave) {
-                        if (stride == 16) {
-                            // a row of 16 counts is two 16-byte reads; a shard here has at most 2^10
-                            // prompts and a count is below 2^16: the sum fits 32 bits, one
-                            // multiply-add per class
-                            const uint4 r0 = *reinterpret_cast<const uint4*>(s_coarse + q * 16);
-                            const uint4 r1 = *reinterpret_cast<const uint4*>(s_coarse + q * 16 + 8);
-                            const unsigned w[8] = {r0.x, r0.y, r0.z, r0.w, r1.x, r1.y, r1.z, r1.w};
-                            unsigned c32 = 0u;
-#pragma unroll
-                            for (int k = 0; k < 16; ++k) {
-                                const unsigned kge = (k & 1) ? (w[k >> 1] >> 16) : (w[k >> 1] & 0xffffu);
-                                if (k < L && k < nc) c32 = __umul24((unsigned)n_all[k < L ? k : 0], kge) + c32;   // uniform
-                            }
-                            cq = in ? (long long)c32 : 0;
-                        } else {
-#pragma unroll
-                            for (int k = 0; k < L; ++k)
-                                if (k < nc && in) cq += count_of(k) * (long long)s_coarse[q * stride + k];
-                        }
-                    } else {
-                        for (int k = 0; k < nc; ++k) {
-                            const long long nk = count_of(k);
-                            if (in) cq += nk * (long long)s_coarse[q * stride + k];
-                        }
+                    int cq = 0;
+                    if (stride == 16) {
+                        // (lanes past the last block read its row and drop the result)
+                        const int qr = in ? q : n_coarse - 1;
+                        cq = count_row16(*reinterpret_cast<const uint4*>(s_coarse + qr * 16),
+                                         *reinterpret_cast<const uint4*>(s_coarse + qr * 16 + 8));
+                    } else if (in) {
+                        cq = count_row(s_coarse + q * stride);
                     }
-                    const bool reached = in && cq >= budget;
+                    const bool reached = in && cq >= want;
                     if (reached) block = q < block ? q : block;
-                    if (in && cq < budget) below = cq > below ? cq : below;
+                    if (in && cq < want) below = cq > below ? cq : below;
                     // the counts grow with the level: once every group of the wavefront has a block
                     // that reaches its budget, the blocks further down cannot be the first
-                    const unsigned long long found = __ballot(reached);
-                    if (__ballot(((found >> shift) & kGroupMask) == 0ull) == 0ull) break;
+                    if (__ballot(group_ballot(reached) == 0) == 0ull) break;
                 }
-                block = -(int)group_max<L>((long long)(-block));   // the smallest over the group
-                const long long before_block = group_max<L>(below);       // the counts grow with the level: this is block - 1's
+                block = -group_max<L>(-block);                        // the smallest over the group
+                const int before_block = group_max<L>(below);         // the counts grow with the level: this is block - 1's
                 if (block == INT_MAX) {
                     ok = false;                       // the tables do not reach the budget
                 } else {
                     // fine: the 64 levels of the block, 64 / L per lane
                     int under = 0;                    // levels of the block whose count stays under the budget
-                    long long best = before_block;    // ... and the largest such count
+                    int best = before_block;          // ... and the largest such count
                     for (int t0 = 0; t0 < kLevelBlock; t0 += L) {
                         const int lvl = block * kLevelBlock + t0 + sl;
                         const bool in = lvl < levels;
                         // (lanes past the last level read its row and drop the result)
                         const unsigned short* row = level_kge + (long long)(in ? lvl : levels - 1) * stride;
-                        long long ct = 0;
-                        if (stride == 16) {
-                            const uint4 r0 = *reinterpret_cast<const uint4*>(row);
-                            const uint4 r1 = *reinterpret_cast<const uint4*>(row + 8);
-                            const unsigned w[8] = {r0.x, r0.y, r0.z, r0.w, r1.x, r1.y, r1.z, r1.w};
-                            if constexpr (L < kWave) {
-                                unsigned c32 = 0u;   // (fits: see the coarse step)
-#pragma unroll
-                                for (int k = 0; k < 16; ++k) {
-                                    const unsigned kge = (k & 1) ? (w[k >> 1] >> 16) : (w[k >> 1] & 0xffffu);
-                                    if (k < L && k < nc) c32 = __umul24((unsigned)n_all[k < L ? k : 0], kge) + c32;   // uniform
-                                }
-                                ct = (long long)c32;
-                            } else {
-#pragma unroll
-                                for (int k = 0; k < 16; ++k) {
-                                    const unsigned kge = (k & 1) ? (w[k >> 1] >> 16) : (w[k >> 1] & 0xffffu);
-                                    if (k < nc) ct += count_of(k) * (long long)kge;   // uniform
-                                }
-                            }
-                        } else if constexpr (L < kWave) {
-#pragma unroll
-                            for (int k = 0; k < L; ++k)
-                                if (k < nc) ct += count_of(k) * (long long)row[k];
-                        } else {
-                            for (int k = 0; k < nc; ++k) ct += count_of(k) * (long long)row[k];
-                        }
-                        if (in && ct < budget) { under += 1; best = ct > best ? ct : best; }
+                        int ct;
+                        if (stride == 16)
+                            ct = count_row16(*reinterpret_cast<const uint4*>(row), *reinterpret_cast<const uint4*>(row + 8));
+                        else
+                            ct = count_row(row);
+                        if (in && ct < want) { under += 1; best = ct > best ? ct : best; }
                     }
                     const int t = group_sum<int, L>(under);                // the first level that reaches the budget
                     const int j = block * kLevelBlock + t;                 // tau = level j
@@ -1053,18 +1058,19 @@ __global__ __launch_bounds__(kShardThreads, (L == 16 && !kFused) ? 6 : 1) void k
                         if (gt == depth) e = surv_next(e, b, a + b, (double)(depth - 1));
                         e_mine = e;
                     }
-                    ok = ((__ballot(!ok) >> shift) & kGroupMask) == 0;
-                    tie_prompts = group_sum<long long, L>(tied_mine ? (long long)n_mine : 0ll);
+                    ok = group_ballot(!ok) == 0;
+                    tie_prompts = group_sum<int, L>(tied_mine ? n_mine : 0);
                 }
             }
             if (!ok) {
                 defer = true;
             } else {
-                const long long r = budget - count_gt;
+                const long long r64 = budget - (long long)count_gt;
+                const int r = r64 < (long long)INT_MAX ? (int)r64 : INT_MAX;   // tied prompts that get a unit (ranks are below 2^10)
                 if (summary && sl == 0) {
                     summary[shard].tau = budget > 0 ? __longlong_as_double((long long)tau_bits) : 0.0;
                     summary[shard].count_gt = count_gt;
-                    summary[shard].tie_units = r;
+                    summary[shard].tie_units = r64;
                     summary[shard].tie_prompts = tie_prompts;
                 }
                 gs.k[sl] = k_mine;
@@ -1074,7 +1080,7 @@ __global__ __launch_bounds__(kShardThreads, (L == 16 && !kFused) ? 6 : 1) void k
 
                 // ---- 3. outputs
                 const long long off_base = kOff != 0 ? (long long)g0 * lo_i + before : 0;
-                long long rank_base = 0, given = 0;       // tied prompts / units handed out before this tile
+                int rank_base = 0, given = 0;             // tied prompts / units handed out before this tile (32 bits: see above)
                 for (long long i0 = lo_i; i0 < hi_i; i0 += L) {
                     const long long i = i0 + sl;
                     const bool in = i < hi_i;
@@ -1087,12 +1093,12 @@ __global__ __launch_bounds__(kShardThreads, (L == 16 && !kFused) ? 6 : 1) void k
                     }
                     const int kk = in ? gs.k[x] : 0;
                     const bool td = in && gs.tied[x] != 0;
-                    const unsigned long long tied_mask = (__ballot(td) >> shift) & kGroupMask;
-                    const long long rank = rank_base + __popcll(tied_mask & ((1ull << sl) - 1ull));
+                    const auto tied_mask = group_ballot(td);
+                    const int rank = rank_base + count_below(tied_mask, sl);
                     const bool win = td && rank < r;
                     const int dd = kk + (win ? 1 : 0);
                     const int units = in ? g0 + dd : 0;
-                    const long long incl = group_incl_scan<L>((long long)units, sl);
+                    const int incl = group_incl_scan<L>(units, sl);
                     if (in) {
                         delta[i] = dd;
                         if (util) {
@@ -1104,7 +1110,7 @@ __global__ __launch_bounds__(kShardThreads, (L == 16 && !kFused) ? 6 : 1) void k
                             util[i] = 1.0 - e;
                         }
                         if (kOff != 0) {
-                            const long long off = off_base + given + incl - units;
+                            const long long off = off_base + (long long)(given + incl - units);
                             if (kOff == 1) {
                                 reinterpret_cast<int32_t*>(group_off)[i] = (int32_t)off;
                                 if (i == n - 1) {
@@ -1117,7 +1123,7 @@ __global__ __launch_bounds__(kShardThreads, (L == 16 && !kFused) ? 6 : 1) void k
                             }
                         }
                     }
-                    rank_base += __popcll(tied_mask);
+                    rank_base += count_bits(tied_mask);
                     given += group_last<L>(incl);
                 }
             }
