@@ -146,6 +146,14 @@ def other_paths(torch, hora, wl, sess, a1, c1, w1, delta1, util1, goff1, ws, rep
         assert int(delta.sum()) == w.budget
         out[f"allocate_sharded_{w.name}"] = {"shards": n_shards, "prompts": w.n, "us_per_call": us,
                                              "prompts_per_s": w.n / us * 1e6}
+        # the same call with the Python-side checks and conversions done once (hora.prepared): a
+        # call on a few dozen prompts is bound by them, not by its one kernel
+        run = hora.prepared(hora.hora_allocate_sharded, c, w.g0, so, sb, delta, sess.dev_status, sws, util=util,
+                            group_off=goff)
+        delta.zero_()
+        us_p = mean_us(run)
+        assert int(delta.sum()) == w.budget and sess.status() == 0
+        out[f"allocate_sharded_{w.name}"]["us_per_prepared_call"] = us_p
     # the helpers next to the path, on the large-broadcast shapes: loss weights, baseline rule, Pass@K
     w2 = wl.LARGE_BCAST
     a2 = wl.phase_a(w2)

@@ -12,6 +12,7 @@ from __future__ import annotations
 
 import ctypes
 import os
+import threading
 from dataclasses import dataclass
 from typing import Optional
 
@@ -122,9 +123,17 @@ def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
     return t.data_ptr()
 
 
-def _stream(stream) -> Optional[int]:
+# (torch.cuda.current_stream() builds a Stream object, ~3 us per call; the raw handle is what is passed on)
+_raw_current_stream = getattr(torch._C, "_cuda_getCurrentRawStream", None)
+
+
+def _stream(stream, like: Optional[torch.Tensor] = None) -> Optional[int]:
+    """The HIP stream handle to pass on: `stream` (a torch stream), or the current stream of
+    the device that `like` lives on."""
     if stream is None:
-        stream = torch.cuda.current_stream()
+        if _raw_current_stream is not None and like is not None and like.is_cuda:
+            return _raw_current_stream(like.device.index) or None
+        stream = torch.cuda.current_stream(like.device if like is not None and like.is_cuda else None)
     return stream.cuda_stream or None
 
 
@@ -139,6 +148,47 @@ def _itype(t: torch.Tensor) -> int:
 def _check(status: int, where: str) -> None:
     if status != OK:
         raise HoraError(status, where)
+
+
+_recording = threading.local()
+
+
+def _call(name: str, *args) -> None:
+    """Calls entry point `name` with marshalled arguments (or notes the call down for `prepared`)."""
+    f = getattr(load_library(), name)
+    notes = getattr(_recording, "notes", None)
+    if notes is not None:
+        notes.append((f, args, name))
+        return
+    _check(f(*args), name)
+
+
+def prepared(binding, *args, **kwargs):
+    """Marshals once, calls many times.  Runs `binding` (one of the hora_* functions below that
+    launch work) with the given arguments up to, but not including, the call into the library,
+    and returns a function without arguments that makes that call each time: the same device
+    buffers (the tensors stay referenced by the returned function), sizes and stream.  For
+    loops that repeat a small call: the checks and conversions above cost several microseconds,
+    more than the kernels of a call on a few dozen prompts."""
+    if getattr(_recording, "notes", None) is not None:
+        raise RuntimeError("prepared() calls do not nest")
+    _recording.notes = []
+    try:
+        binding(*args, **kwargs)
+        notes = _recording.notes
+    finally:
+        _recording.notes = None
+    if len(notes) != 1:
+        raise ValueError("prepared() expects a binding that makes exactly one library call")
+    f, cargs, name = notes[0]
+
+    def run() -> None:
+        status = f(*cargs)
+        if status != OK:
+            raise HoraError(status, name)
+
+    run.keeps = (args, kwargs)
+    return run
 
 
 def _expect(t: Optional[torch.Tensor], dtype, numel: int, name: str) -> None:
@@ -164,8 +214,8 @@ def hora_marginal_gains(alpha: torch.Tensor, beta: torch.Tensor, count: int,
     _expect(beta, torch.float64, n, "beta")
     _expect(gains, torch.float64, n * count, "gains")
     _expect(util, torch.float64, n * count, "util")
-    _check(load_library().hora_marginal_gains(n, _ptr(alpha), _ptr(beta), int(count), _ptr(gains), _ptr(util),
-                                              _stream(stream)), "hora_marginal_gains")
+    _call("hora_marginal_gains", n, _ptr(alpha), _ptr(beta), int(count), _ptr(gains), _ptr(util),
+          _stream(stream, alpha))
 
 
 def hora_allocate(c: torch.Tensor, g0: int, budget: int, delta: torch.Tensor, dev_status: torch.Tensor,
@@ -181,11 +231,10 @@ def hora_allocate(c: torch.Tensor, g0: int, budget: int, delta: torch.Tensor, de
     _expect(summary, torch.int64, 4, "summary")
     if group_off is not None and group_off.numel() < n + 1:
         raise ValueError("group_off needs n + 1 elements")
-    _check(load_library().hora_allocate(
-        n, int(g0), _ptr(c), float(alpha0), float(beta0), int(budget), int(delta_max), int(method),
-        _ptr(delta), _ptr(util), _ptr(group_off), _itype(group_off) if group_off is not None else I32,
-        _ptr(summary), _ptr(dev_status), _ptr(workspace), workspace.numel() * workspace.element_size(),
-        _stream(stream)), "hora_allocate")
+    _call("hora_allocate", n, int(g0), _ptr(c), float(alpha0), float(beta0), int(budget), int(delta_max), int(method),
+          _ptr(delta), _ptr(util), _ptr(group_off), _itype(group_off) if group_off is not None else I32,
+          _ptr(summary), _ptr(dev_status), _ptr(workspace), workspace.numel() * workspace.element_size(),
+          _stream(stream, c))
 
 
 def hora_allocate_static(c: torch.Tensor, g0: int, budget: int, delta: torch.Tensor, dev_status: torch.Tensor, *,
@@ -200,10 +249,9 @@ def hora_allocate_static(c: torch.Tensor, g0: int, budget: int, delta: torch.Ten
     _expect(summary, torch.int64, 4, "summary")
     if group_off is not None and group_off.numel() < n + 1:
         raise ValueError("group_off needs n + 1 elements")
-    _check(load_library().hora_allocate_static(
-        n, int(g0), _ptr(c), float(alpha0), float(beta0), int(budget), int(delta_max), int(method),
-        _ptr(delta), _ptr(util), _ptr(group_off), _itype(group_off) if group_off is not None else I32,
-        _ptr(summary), _ptr(dev_status), _stream(stream)), "hora_allocate_static")
+    _call("hora_allocate_static", n, int(g0), _ptr(c), float(alpha0), float(beta0), int(budget), int(delta_max), int(method),
+          _ptr(delta), _ptr(util), _ptr(group_off), _itype(group_off) if group_off is not None else I32,
+          _ptr(summary), _ptr(dev_status), _stream(stream, c))
 
 
 def hora_allocation_shares(c: torch.Tensor, delta: torch.Tensor, g0: int, class_count: torch.Tensor,
@@ -214,9 +262,8 @@ def hora_allocation_shares(c: torch.Tensor, delta: torch.Tensor, g0: int, class_
     _expect(class_count, torch.int64, g0 + 1, "class_count")
     _expect(class_budget, torch.int64, g0 + 1, "class_budget")
     _expect(dev_status, torch.int32, 1, "dev_status")
-    _check(load_library().hora_allocation_shares(n, int(g0), _ptr(c), _ptr(delta), _ptr(class_count),
-                                                 _ptr(class_budget), _ptr(dev_status), _stream(stream)),
-           "hora_allocation_shares")
+    _call("hora_allocation_shares", n, int(g0), _ptr(c), _ptr(delta), _ptr(class_count),
+          _ptr(class_budget), _ptr(dev_status), _stream(stream, c))
 
 
 def hora_allocate_baseline(c: torch.Tensor, g0: int, budget: int, rule: int, delta: torch.Tensor,
@@ -232,11 +279,10 @@ def hora_allocate_baseline(c: torch.Tensor, g0: int, budget: int, rule: int, del
     _expect(summary, torch.int64, 4, "summary")
     if group_off is not None and group_off.numel() < n + 1:
         raise ValueError("group_off needs n + 1 elements")
-    _check(load_library().hora_allocate_baseline(
-        n, int(g0), _ptr(c), float(alpha0), float(beta0), int(budget), int(delta_max), int(rule),
-        _ptr(delta), _ptr(util), _ptr(group_off), _itype(group_off) if group_off is not None else I32,
-        _ptr(summary), _ptr(dev_status), _ptr(workspace), workspace.numel() * workspace.element_size(),
-        _stream(stream)), "hora_allocate_baseline")
+    _call("hora_allocate_baseline", n, int(g0), _ptr(c), float(alpha0), float(beta0), int(budget), int(delta_max), int(rule),
+          _ptr(delta), _ptr(util), _ptr(group_off), _itype(group_off) if group_off is not None else I32,
+          _ptr(summary), _ptr(dev_status), _ptr(workspace), workspace.numel() * workspace.element_size(),
+          _stream(stream, c))
 
 
 def hora_allocate_posterior(alpha: torch.Tensor, beta: torch.Tensor, g0: int, budget: int, delta: torch.Tensor,
@@ -252,11 +298,9 @@ def hora_allocate_posterior(alpha: torch.Tensor, beta: torch.Tensor, g0: int, bu
     _expect(summary, torch.int64, 4, "summary")
     if group_off is not None and group_off.numel() < n + 1:
         raise ValueError("group_off needs n + 1 elements")
-    _check(load_library().hora_allocate_posterior(
-        n, int(g0), _ptr(alpha), _ptr(beta), int(budget), int(delta_max), _ptr(delta), _ptr(util),
-        _ptr(group_off), _itype(group_off) if group_off is not None else I32, _ptr(summary),
-        _ptr(dev_status), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)),
-        "hora_allocate_posterior")
+    _call("hora_allocate_posterior", n, int(g0), _ptr(alpha), _ptr(beta), int(budget), int(delta_max), _ptr(delta), _ptr(util),
+          _ptr(group_off), _itype(group_off) if group_off is not None else I32, _ptr(summary),
+          _ptr(dev_status), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream, alpha))
 
 
 def hora_allocate_sharded_workspace_bytes(n_shards: int) -> int:
@@ -280,11 +324,10 @@ def hora_allocate_sharded(c: torch.Tensor, g0: int, shard_off: torch.Tensor, sha
     if group_off is not None and group_off.numel() < n + 1:
         raise ValueError("group_off needs n + 1 elements")
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
-    _check(load_library().hora_allocate_sharded(
-        n, int(g0), _ptr(c), float(alpha0), float(beta0), n_shards, _ptr(shard_off), _ptr(shard_budget),
-        int(delta_max), _ptr(delta), _ptr(util), _ptr(group_off),
-        _itype(group_off) if group_off is not None else I32, _ptr(summary), _ptr(dev_status), _ptr(workspace),
-        ws_bytes, _stream(stream)), "hora_allocate_sharded")
+    _call("hora_allocate_sharded", n, int(g0), _ptr(c), float(alpha0), float(beta0), n_shards, _ptr(shard_off), _ptr(shard_budget),
+          int(delta_max), _ptr(delta), _ptr(util), _ptr(group_off),
+          _itype(group_off) if group_off is not None else I32, _ptr(summary), _ptr(dev_status), _ptr(workspace),
+          ws_bytes, _stream(stream, c))
 
 
 def hora_group_advantage(group_off: torch.Tensor, reward: torch.Tensor, adv: torch.Tensor, mode: int,
@@ -294,9 +337,8 @@ def hora_group_advantage(group_off: torch.Tensor, reward: torch.Tensor, adv: tor
     if adv.dtype != reward.dtype or adv.numel() < n_resp:
         raise ValueError("adv must match reward in dtype and size")
     _expect(dev_status, torch.int32, 1, "dev_status")
-    _check(load_library().hora_group_advantage(
-        n_groups, _ptr(group_off), _itype(group_off), n_resp, _ptr(reward), _ptr(adv), _ftype(reward),
-        int(mode), float(eps), int(ddof), _ptr(dev_status), _stream(stream)), "hora_group_advantage")
+    _call("hora_group_advantage", n_groups, _ptr(group_off), _itype(group_off), n_resp, _ptr(reward), _ptr(adv), _ftype(reward),
+          int(mode), float(eps), int(ddof), _ptr(dev_status), _stream(stream, group_off))
 
 
 def hora_response_weights(group_off: torch.Tensor, tok_off: torch.Tensor, weight: torch.Tensor,
@@ -306,9 +348,8 @@ def hora_response_weights(group_off: torch.Tensor, tok_off: torch.Tensor, weight
     if weight.numel() < n_resp:
         raise ValueError("weight too small")
     _expect(dev_status, torch.int32, 1, "dev_status")
-    _check(load_library().hora_response_weights(
-        n_groups, _ptr(group_off), _itype(group_off), n_resp, _ptr(tok_off), _itype(tok_off), float(length_const),
-        _ptr(weight), _ftype(weight), _ptr(dev_status), _stream(stream)), "hora_response_weights")
+    _call("hora_response_weights", n_groups, _ptr(group_off), _itype(group_off), n_resp, _ptr(tok_off), _itype(tok_off), float(length_const),
+          _ptr(weight), _ftype(weight), _ptr(dev_status), _stream(stream, group_off))
 
 
 def hora_pass_at_k(n_samples: torch.Tensor, correct: torch.Tensor, ks, mean: torch.Tensor,
@@ -322,10 +363,9 @@ def hora_pass_at_k(n_samples: torch.Tensor, correct: torch.Tensor, ks, mean: tor
     _expect(per_problem, torch.float64, len(ks) * n, "per_problem")
     _expect(dev_status, torch.int32, 1, "dev_status")
     host_ks = (ctypes.c_int32 * max(len(ks), 1))(*ks)
-    _check(load_library().hora_pass_at_k(
-        n, _ptr(n_samples), _ptr(correct), len(ks), ctypes.cast(host_ks, ctypes.c_void_p), _ptr(per_problem),
-        _ptr(mean), _ptr(dev_status), _ptr(workspace), workspace.numel() * workspace.element_size(),
-        _stream(stream)), "hora_pass_at_k")
+    _call("hora_pass_at_k", n, _ptr(n_samples), _ptr(correct), len(ks), ctypes.cast(host_ks, ctypes.c_void_p), _ptr(per_problem),
+          _ptr(mean), _ptr(dev_status), _ptr(workspace), workspace.numel() * workspace.element_size(),
+          _stream(stream, n_samples))
 
 
 def hora_pass_at_k_workspace_bytes(n_problems: int, n_k: int) -> int:
@@ -345,10 +385,9 @@ def hora_token_broadcast(adv: torch.Tensor, tok_off: torch.Tensor, tok_adv: torc
     if tok_adv.numel() < n_tokens:
         raise ValueError("tok_adv too small")
     _expect(dev_status, torch.int32, 1, "dev_status")
-    _check(load_library().hora_token_broadcast(
-        n_resp, _ptr(adv), _ftype(adv), _ptr(tok_off), _itype(tok_off), _ptr(tok_adv), _ftype(tok_adv),
-        int(n_tokens), _ptr(dev_status), _ptr(workspace), workspace.numel() * workspace.element_size(),
-        _stream(stream)), "hora_token_broadcast")
+    _call("hora_token_broadcast", n_resp, _ptr(adv), _ftype(adv), _ptr(tok_off), _itype(tok_off), _ptr(tok_adv), _ftype(tok_adv),
+          int(n_tokens), _ptr(dev_status), _ptr(workspace), workspace.numel() * workspace.element_size(),
+          _stream(stream, adv))
 
 
 def hora_token_broadcast2_workspace_bytes(n_tokens: int, out_dtype: torch.dtype = torch.float32) -> int:
@@ -367,10 +406,9 @@ def hora_token_broadcast2(adv_a: torch.Tensor, adv_b: torch.Tensor, tok_off: tor
     if tok_a.numel() < n_tokens or tok_b.numel() < n_tokens or tok_a.dtype != tok_b.dtype:
         raise ValueError("tok_a / tok_b too small or of different types")
     _expect(dev_status, torch.int32, 1, "dev_status")
-    _check(load_library().hora_token_broadcast2(
-        n_resp, _ptr(adv_a), _ptr(adv_b), _ftype(adv_a), _ptr(tok_off), _itype(tok_off), _ptr(tok_a), _ptr(tok_b),
-        _ftype(tok_a), int(n_tokens), _ptr(dev_status), _ptr(workspace),
-        workspace.numel() * workspace.element_size(), _stream(stream)), "hora_token_broadcast2")
+    _call("hora_token_broadcast2", n_resp, _ptr(adv_a), _ptr(adv_b), _ftype(adv_a), _ptr(tok_off), _itype(tok_off), _ptr(tok_a), _ptr(tok_b),
+          _ftype(tok_a), int(n_tokens), _ptr(dev_status), _ptr(workspace),
+          workspace.numel() * workspace.element_size(), _stream(stream, adv_a))
 
 
 # ----------------------------------------------------------------------------

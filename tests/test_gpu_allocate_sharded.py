@@ -192,3 +192,42 @@ def test_int32_offsets_that_overflow_are_reported(gpu):
             assert int(got.delta.sum(dtype=torch.int64)) == n_shards * per_shard
             widths = got.group_off[1:].to(torch.int64) - got.group_off[:-1].to(torch.int64)
             assert bool((widths == got.delta.to(torch.int64) + g0).all())
+
+
+def test_prepared_call_repeats_the_paper_step(gpu, oracle):
+    """hora.prepared marshals once; every call of what it returns is the same library call:
+    outputs against the oracle after each of two calls (the second on changed counts in the
+    same buffer), and an error status still raises."""
+    from paper_2605_07114_amd import workloads as wl
+    sess, torch, hora = gpu
+    w = wl.PAPER_STEP
+    a = wl.phase_a(w)
+    bounds, budgets = wl.equal_shards(w.n, wl.PAPER_STEP_SHARDS, w.budget)
+    c = dev(torch, a.c)
+    so, sb = dev(torch, bounds), dev(torch, budgets)
+    delta = torch.full((w.n,), -7, dtype=torch.int32, device="cuda:0")
+    util = torch.full((w.n,), float("nan"), dtype=torch.float64, device="cuda:0")
+    goff = torch.full((w.n + 1,), -7, dtype=torch.int32, device="cuda:0")
+    ws = torch.zeros(hora.hora_allocate_sharded_workspace_bytes(budgets.size), dtype=torch.uint8, device="cuda:0")
+    run = hora.prepared(hora.hora_allocate_sharded, c, w.g0, so, sb, delta, sess.dev_status, ws, util=util,
+                        group_off=goff)
+    torch.cuda.synchronize()
+    assert int(delta[0].item()) == -7          # preparing launches nothing
+    counts = a.c
+    for call in range(2):
+        print(f"prepared paper_step call {call}", flush=True)
+        run()
+        torch.cuda.synchronize()
+        assert sess.status() == 0
+        want = oracle.allocate_sharded(counts, w.g0, bounds, budgets)
+        assert np.array_equal(delta.cpu().numpy().astype(np.int64), want)
+        assert np.array_equal(goff.cpu().numpy().astype(np.int64), oracle.group_offsets(want, w.g0))
+        alpha, beta = oracle.posterior(counts, w.g0)
+        np.testing.assert_allclose(util.cpu().numpy(), oracle.utilities(alpha, beta, want), rtol=UTIL_RTOL, atol=0)
+        counts = (w.g0 - counts).astype(np.int32)   # new Phase-A outcomes in the same device buffer
+        c.copy_(dev(torch, counts))
+    # a prepared call whose arguments the library rejects raises like the plain binding
+    bad = hora.prepared(hora.hora_allocate_sharded, c, w.g0, so, sb, delta, sess.dev_status, ws[:256], util=util,
+                        group_off=goff)
+    with pytest.raises(hora.HoraError):
+        bad()

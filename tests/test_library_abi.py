@@ -182,3 +182,19 @@ def test_binding_refuses_to_run_without_the_library(tmp_path):
     from paper_2605_07114_amd import hora
     with pytest.raises(RuntimeError, match="no CPU fallback"):
         hora.load_library(str(tmp_path / "libhora.so"))
+
+
+def test_prepared_refuses_what_the_binding_refuses():
+    """hora.prepared runs the binding's own checks (here: a host tensor where a device buffer
+    is expected) and leaves the module ready for the next call."""
+    import torch
+    from paper_2605_07114_amd import hora
+    c = torch.zeros(8, dtype=torch.int32)
+    delta = torch.zeros(8, dtype=torch.int32)
+    status = torch.zeros(1, dtype=torch.int32)
+    ws = torch.zeros(1024, dtype=torch.uint8)
+    for _ in range(2):
+        with pytest.raises(ValueError):
+            hora.prepared(hora.hora_allocate, c, 4, 8, delta, status, ws)
+    with pytest.raises(ValueError):
+        hora.prepared(hora.hora_allocate_workspace_bytes, 8, 4)   # makes no launching call
