@@ -200,7 +200,9 @@ __device__ __forceinline__ void store_items(T* __restrict__ dst, long long pos, 
     }
 }
 
-template <int kOff>
+// kTiedOnly: delta already holds k for every prompt that is not tied (the caller's kernel
+// before stored it): only threads with a tied prompt among theirs store delta again.
+template <int kOff, bool kTiedOnly = false>
 __device__ __forceinline__ void emit_tile(int tile_parity, long long pos, long long end, long long n, int g0,
                                           long long r, const int (&kk)[kItems], const int (&td)[kItems],
                                           EmitCarry& carry, int (&dd)[kItems], bool (&win)[kItems],
@@ -259,7 +261,14 @@ __device__ __forceinline__ void emit_tile(int tile_parity, long long pos, long l
     }
     off[kItems] = (long long)g0 * (pos + kItems) + kprior + (rank < r ? rank : r);
 
-    store_items<v4i, int32_t>(delta, pos, end, d_vec, dd);
+    if constexpr (kTiedOnly) {
+        bool any_tied = false;
+#pragma unroll
+        for (int j = 0; j < kItems; ++j) any_tied |= td[j] != 0;
+        if (any_tied) store_items<v4i, int32_t>(delta, pos, end, d_vec, dd);
+    } else {
+        store_items<v4i, int32_t>(delta, pos, end, d_vec, dd);
+    }
     if (kOff == 1) {
         int32_t* go = reinterpret_cast<int32_t*>(group_off);
         int32_t o32[kItems];

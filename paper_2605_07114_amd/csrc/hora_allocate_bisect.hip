@@ -25,8 +25,9 @@
 //     the interval where the running count reaches the budget.
 //  4. k_bisect_pass<1> keeps what the lists hold of the narrower bracket.
 //  5. k_bisect_finalize: every workgroup finishes the search from the lists (usually a few
-//     thousand gains), then k_i = #{l : M_i(l) > tau}, the tied flag and E_i(k_i) per prompt;
-//     k_bisect_write: ties at tau by prompt index, delta, utilities, group offsets.
+//     thousand gains), then k_i = #{l : M_i(l) > tau} and U_i = 1 - E_i(k_i) per prompt (final
+//     for every prompt whose next gain is below tau; a tied prompt is flagged and keeps E_i(k_i));
+//     k_bisect_write: ties at tau by prompt index (tied prompts rewritten), group offsets.
 //
 // Under a shared prior the gains of a bracket are few distinct values, each repeated: step 3
 // already closes the bracket and steps 4 and the finisher return at once.
@@ -1141,8 +1142,8 @@ __device__ unsigned long long finish_search(SelectShared& sh, const Src& src, lo
 
 // ----------------------------------------------------------------------------------
 // 5a. The end of the search (4.), then with tau known: k_i = #{l : M_i(l) > tau} and the tied
-// flag go to delta[i] (flag in bit 31), the survival product E_i(k_i) to util[i]; per-workgroup sums to block_ksum /
-// block_tied.  kItems prompts per thread, their walks in lockstep.
+// flag go to delta[i] (flag in bit 31); util[i] gets U_i = 1 - E_i(k_i), or the survival product
+// E_i(k_i) itself for a tied prompt; per-workgroup sums to block_ksum / block_tied.  kItems prompts per thread, their walks in lockstep.
 // ----------------------------------------------------------------------------------
 // The survival products E_i(k_i) of one wavefront's 256 prompts, pooled like pooled_walk (the
 // number of steps k_i is known here): a lane takes a prompt, multiplies and divides k_i times,
@@ -1283,7 +1284,10 @@ __global__ __launch_bounds__(kBig) void k_bisect_finalize(Src src, long long n, 
                 }
             } while (any);
         }
+        // what is final already is stored as such: k and U = 1 - E(k) of a prompt that is not
+        // tied; a tied prompt leaves k with the flag and E(k) itself, for the tie pass
         int packed[kItems];
+        double uu[kItems];
 #pragma unroll
         for (int j = 0; j < kItems; ++j) {
             const bool at_limit = !(lf[j] < limit_d);
@@ -1292,11 +1296,12 @@ __global__ __launch_bounds__(kBig) void k_bisect_finalize(Src src, long long n, 
             too_deep |= alive[j] && at_limit && depth_capped != 0 && gain_bits(g[j]) > tau_bits;
             const int k = alive[j] ? (int)lf[j] : 0;
             packed[j] = (int)((unsigned)k | (tied ? kTiedBit : 0u));
+            uu[j] = tied ? e[j] : 1.0 - e[j];
             ks += k;
             ts += tied ? 1 : 0;
         }
         store_items<v4i, int32_t>(delta, pos, end, d_vec, packed);
-        if (util) store_items<v2d, double>(util, pos, end, u_vec, e);
+        if (util) store_items<v2d, double>(util, pos, end, u_vec, uu);
     }
     ks = wave_total_i64(ks);
     ts = wave_total_i64(ts);
@@ -1314,8 +1319,9 @@ __global__ __launch_bounds__(kBig) void k_bisect_finalize(Src src, long long n, 
 // ----------------------------------------------------------------------------------
 // 5b. Outputs.  Every workgroup adds up the per-workgroup sums of 5a (what lies before it,
 // and the totals, from which r = budget - sum k follows), then runs the tie pass over its
-// chunk: delta[i] holds k_i with the tied flag in bit 31 and util[i] the survival product
-// E_i(k_i); a winner's utility takes one more step of the product.
+// chunk.  delta[i] holds k_i, with the tied flag in bit 31 for a tied prompt; util[i] holds
+// the final U_i of a prompt that is not tied and the survival product E_i(k_i) of a tied one
+// (a winner's takes one more step of the product): only tied prompts are written again.
 // ----------------------------------------------------------------------------------
 template <class Src, int kOff>
 __global__ __launch_bounds__(kBig) void k_bisect_write(Src src, long long n, int g0, long long chunk, int nb,
@@ -1359,7 +1365,6 @@ __global__ __launch_bounds__(kBig) void k_bisect_write(Src src, long long n, int
     const long long base = (long long)blockIdx.x * chunk;
     const long long end = base + chunk < n ? base + chunk : n;
     const bool d_vec = (reinterpret_cast<uintptr_t>(delta) & 15) == 0;
-    const bool u_vec = (reinterpret_cast<uintptr_t>(util) & 15) == 0;
     const bool o_vec = (reinterpret_cast<uintptr_t>(group_off) & 15) == 0;
     EmitCarry carry = {t_bef, k_bef};
     int parity = 0;
@@ -1374,24 +1379,20 @@ __global__ __launch_bounds__(kBig) void k_bisect_write(Src src, long long n, int
             kk[j] = (int)((unsigned)raw[j] & ~kTiedBit);
             td[j] = ((unsigned)raw[j] & kTiedBit) ? 1 : 0;
         }
-        emit_tile<kOff>(parity, pos, end, n, g0, r, kk, td, carry, dd, win, delta, group_off, d_vec, o_vec,
-                        &s_emit);
+        emit_tile<kOff, true>(parity, pos, end, n, g0, r, kk, td, carry, dd, win, delta, group_off, d_vec, o_vec,
+                              &s_emit);
         if (util) {
-            double uu[kItems];
 #pragma unroll
-            for (int j = 0; j < kItems; ++j) {
-                double e = 1.0;
-                if (pos + j < end) {
-                    e = util[pos + j];
+            for (int j = 0; j < kItems; ++j)
+                if (td[j]) {   // (set for prompts below `end` only)
+                    double e = util[pos + j];
                     if (win[j]) {
                         double a, b;
                         src.load(pos + j, a, b);
                         e = surv_next(e, b, a + b, (double)kk[j]);
                     }
+                    util[pos + j] = 1.0 - e;
                 }
-                uu[j] = 1.0 - e;
-            }
-            store_items<v2d, double>(util, pos, end, u_vec, uu);
         }
     }
 }
