@@ -192,7 +192,7 @@ struct EstimateShared {
 
 template <class Src>
 __device__ __forceinline__ void estimate_depth(const Src& src, long long n, long long budget, long long limit,
-                                               EstimateShared& es, int& est, int& ck, bool& uneven) {
+                                               EstimateShared& es, int& est, int& ck, bool& uneven, int& deepest) {
     const bool walker = threadIdx.x < kEstWaves * kWave;
     const double limit_d = (double)limit;
     double b[kEstItems], s[kEstItems], g[kEstItems], lf[kEstItems];
@@ -293,6 +293,7 @@ __device__ __forceinline__ void estimate_depth(const Src& src, long long n, long
     // stores weigh more than the idle lanes).  Pooled above a mean of 32 and deepest > 2 mean + 8.
     uneven = cum > 32ull * kEstSamples &&
              (unsigned long long)es.deepest * kEstSamples > 2ull * cum + 8ull * kEstSamples;
+    deepest = es.deepest;
 }
 
 // ----------------------------------------------------------------------------------
@@ -364,6 +365,55 @@ __device__ __forceinline__ void pooled_walk(const double* __restrict__ pool_a, c
     }
 }
 
+// ----------------------------------------------------------------------------------
+// Regrouping the walks of a wavefront.  A wavefront holds kItems walks per lane and steps
+// item j of its lanes as long as any lane's item j is active, so walks of different length
+// leave most lanes idle towards the end.  When the active walks would fit fewer items per
+// lane, the wavefront's 64 * kItems walks are permuted (a stable partition: the active ones
+// first, item-major) so that the active ones fill the lanes of the first items: a field at a
+// time through 2 KB of LDS per wavefront.  Nothing leaves the wavefront, whose LDS operations
+// complete in order: no workgroup barrier is needed.  Position p = j * 64 + lane stands for
+// item j of lane `lane`.
+// ----------------------------------------------------------------------------------
+struct WaveStage { double v[kWave * kItems]; };
+
+__device__ __forceinline__ void wave_phase() {   // orders the wavefront's LDS phases for the compiler (emits nothing)
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+// Where every walk goes (whole wavefronts call this); `total` = the number of active walks.
+__device__ __forceinline__ void regroup_plan(const bool (&act)[kItems], int total, int (&dest)[kItems]) {
+    int act_before = 0, idle_before = 0;
+#pragma unroll
+    for (int j = 0; j < kItems; ++j) {
+        const unsigned long long m = __ballot(act[j]);
+        const int below = lanes_below(m);
+        dest[j] = act[j] ? act_before + below : total + idle_before + (lane_id() - below);
+        act_before += __popcll(m);
+        idle_before += kWave - __popcll(m);
+    }
+}
+
+__device__ __forceinline__ void regroup(WaveStage& st, const int (&dest)[kItems], double (&x)[kItems]) {
+#pragma unroll
+    for (int j = 0; j < kItems; ++j) st.v[dest[j]] = x[j];
+    wave_phase();
+#pragma unroll
+    for (int j = 0; j < kItems; ++j) x[j] = st.v[j * kWave + lane_id()];
+    wave_phase();
+}
+__device__ __forceinline__ void regroup(WaveStage& st, const int (&dest)[kItems], int (&x)[kItems]) {
+    int* v = reinterpret_cast<int*>(st.v);
+#pragma unroll
+    for (int j = 0; j < kItems; ++j) v[dest[j]] = x[j];
+    wave_phase();
+#pragma unroll
+    for (int j = 0; j < kItems; ++j) x[j] = v[j * kWave + lane_id()];
+    wave_phase();
+}
+
+constexpr int kRegroupGain = 6;             // items saved x rounds left from which a regrouping pays (a gain step: ~55 instructions)
 constexpr int kFine = kWinOct * kSubBins;   // quarter octaves counted per thread in the first go
 static_assert(kFine == kBigWaves, "one wavefront adds up one quarter octave");
 
@@ -375,6 +425,10 @@ __global__ __launch_bounds__(kBig) void k_bisect_coarse(Src src, long long n, lo
                                                         AllocHeader* __restrict__ hdr, double* __restrict__ ck_g,
                                                         int32_t* __restrict__ ck_l, int32_t* dev_status) {
     __shared__ unsigned s_fine[kFine][kBig];
+    // the tile's posteriors for pooled_walk (kDeep), and later, or otherwise, the wavefronts' stages for regroup
+    __shared__ double s_f64[kDeep ? 2 * kTile : kBigWaves * kWave * kItems];
+    static_assert(sizeof(WaveStage) * kBigWaves <= sizeof(double) * 2 * kTile, "the stages fit the pool's arrays");
+    WaveStage* const s_stage = reinterpret_cast<WaveStage*>(s_f64);
     __shared__ unsigned long long s_cnt[kRing][kSubBins];
     __shared__ unsigned long long s_total;       // gains counted in the first go
     __shared__ unsigned long long s_octave[4];   // [octave & 3] gains counted in an octave after it (see EstimateShared)
@@ -384,9 +438,9 @@ __global__ __launch_bounds__(kBig) void k_bisect_coarse(Src src, long long n, lo
     const long long end = base + chunk < n ? base + chunk : n;
     Fetched<Src> first_tile;
     fetch(src, base + (long long)threadIdx.x * kItems, base + kTile < end ? base + kTile : end, first_tile);
-    int est, ck;
+    int est, ck, deepest;
     bool uneven;
-    estimate_depth(src, n, budget, limit, s_est, est, ck, uneven);
+    estimate_depth(src, n, budget, limit, s_est, est, ck, uneven, deepest);
     const unsigned long long top_ck = octave_top(ck);
     if (blockIdx.x == 0 && threadIdx.x == 0) { hdr->ck_top = top_ck; hdr->uneven = uneven ? 1u : 0u; }
     const unsigned long long est_bottom = octave_top(est) - kOctave;
@@ -427,7 +481,7 @@ __global__ __launch_bounds__(kBig) void k_bisect_coarse(Src src, long long n, lo
         unsigned higher = 0u;   // gains above the counted octaves (a lane sees at most kItems * limit <= 2^22)
         bool pooled = kDeep && uneven;
         if constexpr (kDeep) if (pooled) {
-            __shared__ double s_pool[2][kTile];   // the tile's posteriors for pooled_walk
+            double (&s_pool)[2][kTile] = *reinterpret_cast<double (*)[2][kTile]>(s_f64);
 #pragma unroll
             for (int j = 0; j < kItems; ++j) {
                 s_pool[0][threadIdx.x * kItems + j] = a[j];
@@ -470,13 +524,49 @@ __global__ __launch_bounds__(kBig) void k_bisect_coarse(Src src, long long n, lo
             __syncthreads();
         }
         if (!pooled) {
-            bool any;
-            do {
-                any = false;
+            // (the counters are per thread, not per prompt: a walk may change lanes on its way)
+            WaveStage& stage = s_stage[wave_id()];
+            int home[kItems];          // where in the wavefront's 256 prompts the walk in item j came from
+#pragma unroll
+            for (int j = 0; j < kItems; ++j) home[j] = j * kWave + lane;
+            int in_use = kItems;       // items per lane that may hold an active walk
+            // A regrouping costs about as much as five steps of one item (seven fields through LDS): it is
+            // worth it when items saved x rounds left exceeds that, the rounds left taken from the deepest
+            // walk of the estimate's sample.
+            for (int round = 0;; ++round) {
+                bool act[kItems];
+                int total = 0;
 #pragma unroll
                 for (int j = 0; j < kItems; ++j) {
-                    const bool act = alive[j] && gb[j] > est_bottom;
-                    if (act) {
+                    act[j] = alive[j] && gb[j] > est_bottom;
+                    total += __popcll(__ballot(act[j]));
+                }
+                if (total == 0) break;                      // uniform over the wavefront
+                const int fewer = in_use - (total + kWave - 1) / kWave;
+                if (fewer > 0 && fewer * (deepest - round) >= kRegroupGain) {   // uniform
+                    int dest[kItems], flags[kItems];
+                    regroup_plan(act, total, dest);
+#pragma unroll
+                    for (int j = 0; j < kItems; ++j) flags[j] = home[j] | (alive[j] ? 0x10000 : 0);
+                    regroup(stage, dest, b);
+                    regroup(stage, dest, s);
+                    regroup(stage, dest, g);
+                    regroup(stage, dest, lf);
+                    regroup(stage, dest, keep_g);
+                    regroup(stage, dest, keep_l);
+                    regroup(stage, dest, flags);
+                    in_use = (total + kWave - 1) / kWave;
+#pragma unroll
+                    for (int j = 0; j < kItems; ++j) {
+                        home[j] = flags[j] & 0xffff;
+                        alive[j] = (flags[j] & 0x10000) != 0;
+                        gb[j] = gain_bits(g[j]);
+                        act[j] = j * kWave + lane < total;
+                    }
+                }
+#pragma unroll
+                for (int j = 0; j < kItems; ++j) {
+                    if (act[j]) {
                         if (gb[j] > fine_top) ++higher;
                         else atomicAdd(&s_fine[(unsigned)((fine_top - gb[j]) >> 50)][threadIdx.x], 1u);
                         const bool above_ck = gb[j] > top_ck;
@@ -486,10 +576,18 @@ __global__ __launch_bounds__(kBig) void k_bisect_coarse(Src src, long long n, lo
                         alive[j] = lf[j] < limit_d && gb[j] != 0ull;
                         if (above_ck) { keep_g[j] = g[j]; keep_l[j] = lf[j]; }
                     }
-                    any |= act;
                 }
-            } while (any);
-            store_states(ck_g, ck_l, pos, tile_end, keep_g, keep_l);
+            }
+            {   // the kept states go back to where their prompts are in memory (item j of lane L: prompt pos + j)
+                double kg[kItems], kl[kItems];
+#pragma unroll
+                for (int j = 0; j < kItems; ++j) { kg[j] = keep_g[j]; kl[j] = keep_l[j]; }
+                if (in_use != kItems) {   // uniform over the wavefront: walks have moved
+                    regroup(stage, home, kg);
+                    regroup(stage, home, kl);
+                }
+                store_states(ck_g, ck_l, pos, tile_end, kg, kl);
+            }
             bool mine_alive = false;
 #pragma unroll
             for (int j = 0; j < kItems; ++j) mine_alive |= alive[j];
@@ -1081,13 +1179,38 @@ __device__ unsigned long long finish_search(SelectShared& sh, const Src& src, lo
         __syncthreads();
         total_entries = s_off[kMaxBlocks];
     }
+    // Usually all lists together hold a few thousand gains: then every thread fetches its share
+    // once (all loads under way together) and the passes below work on registers.
+    constexpr int kHeld = 8;   // list entries a thread holds
+    const bool held = from_lists && total_entries <= kHeld * kBig && sh.done == 0;   // uniform
+    unsigned long long mine[kHeld];
+#pragma unroll
+    for (int q = 0; q < kHeld; ++q) mine[q] = 0ull;   // (no gain: outside every bracket)
+    if (held) {
+#pragma unroll
+        for (int q = 0; q < kHeld; ++q) {
+            const int e = q * kBig + (int)threadIdx.x;
+            if (e < total_entries) {
+                int b = 0;
+#pragma unroll
+                for (int step = kMaxBlocks / 2; step > 0; step >>= 1)
+                    if (s_off[b + step] <= e) b += step;     // the last list that starts at or before e
+                mine[q] = lists[(long long)b * kListCap + (e - s_off[b])];
+            }
+        }
+    }
     for (int iter = 0; iter < kFinalMaxPasses; ++iter) {
         if (sh.done) break;   // uniform: written before the barrier that ends move_bracket
         const unsigned long long lo = sh.lo, hi = sh.hi;
         const int shift = bracket_shift(lo, hi);
         if (threadIdx.x < kBins) { sh.bins.cnt[threadIdx.x] = 0; sh.bins.vmax[threadIdx.x] = 0; sh.bins.vmin_inv[threadIdx.x] = 0; }
         __syncthreads();
-        if (from_lists) {
+        if (held) {
+#pragma unroll
+            for (int q = 0; q < kHeld; ++q)
+                if (q * kBig < total_entries)   // uniform
+                    tally_gains(sh.bins, mine[q] > lo && mine[q] <= hi, mine[q], lo, shift);
+        } else if (from_lists) {
             // all entries of all lists as one sequence: every thread finds the list of its entry
             // by a search of the offsets (LDS), so that the loads are independent of one another
             for (int e0 = 0; e0 < total_entries; e0 += kBig) {
