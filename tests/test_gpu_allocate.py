@@ -321,6 +321,35 @@ def test_deep_budgets_with_walks_of_very_different_length(gpu, oracle):
                                        rtol=UTIL_RTOL, atol=0)
 
 
+def test_a_few_deep_walks_in_every_wavefront(gpu, oracle):
+    """While the coarse count walks, a wavefront whose active walks would fit fewer items per
+    lane permutes its 256 walks across its lanes, and permutes the kept walk states back before
+    they are stored.  Here every block of 256 prompts holds a handful of prompts whose gains
+    decay slowly among prompts that are done after a step or two (so the regrouping goes from
+    four items per lane to one early), the batch ends in a ragged tile, and a cap stops the
+    deepest walks.  Allocation and offsets bit for bit, utilities within 1e-12."""
+    sess, torch, hora = gpu
+    rng = np.random.default_rng(37)
+    n, g0 = 5 * 4096 + 777, 8
+    alpha = rng.uniform(6.0, 9.0, n)            # fast decay: a gain or two above any threshold of interest
+    beta = rng.uniform(0.3, 1.0, n)
+    deep = np.zeros(n, dtype=bool)
+    for start in range(0, n, 256):
+        pick = start + rng.choice(min(256, n - start), size=min(5, n - start), replace=False)
+        deep[pick] = True
+    alpha[deep] = rng.uniform(0.2, 0.6, int(deep.sum()))     # slow decay: dozens of gains in the same range
+    beta[deep] = rng.uniform(1.0, 3.0, int(deep.sum()))
+    for budget, cap in ((3 * n, 0), (4 * n, 30), (6 * n, 0)):
+        want = oracle.allocate_posterior(alpha, beta, budget, delta_max=cap)
+        print(f"allocate_posterior few deep walks n={n} budget={budget} cap={cap} deepest={int(want.max())} "
+              f"median={int(np.median(want))}", flush=True)
+        got = sess.allocate_posterior(dev(torch, alpha), dev(torch, beta), g0, budget, delta_max=cap)
+        assert sess.status() == 0
+        assert np.array_equal(got.delta.cpu().numpy().astype(np.int64), want)
+        assert np.array_equal(got.group_off.cpu().numpy(), oracle.group_offsets(want, g0))
+        np.testing.assert_allclose(got.util.cpu().numpy(), oracle.utilities(alpha, beta, want), rtol=UTIL_RTOL, atol=0)
+
+
 def test_learned_prior_collapses_to_the_uniform_prior(gpu, oracle):
     # App. D: s = 2, p = 1/2 gives alpha = 1 + c, beta = 1 + G0 - c
     sess, torch, hora = gpu
