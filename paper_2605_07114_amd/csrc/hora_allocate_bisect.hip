@@ -26,8 +26,9 @@
 //  4. k_bisect_pass<1> keeps what the lists hold of the narrower bracket.
 //  5. k_bisect_finalize: every workgroup finishes the search from the lists (usually a few
 //     thousand gains), then k_i = #{l : M_i(l) > tau} and U_i = 1 - E_i(k_i) per prompt (final
-//     for every prompt whose next gain is below tau; a tied prompt is flagged and keeps E_i(k_i));
-//     k_bisect_write: ties at tau by prompt index (tied prompts rewritten), group offsets.
+//     for every prompt that gets no unit at tau; a tied prompt is flagged and leaves the utility
+//     of one more unit aside); k_bisect_write: ties at tau by prompt index (tied prompts rewritten),
+//     group offsets.
 //
 // Under a shared prior the gains of a bracket are few distinct values, each repeated: step 3
 // already closes the bracket and steps 4 and the finisher return at once.
@@ -1265,8 +1266,8 @@ __device__ unsigned long long finish_search(SelectShared& sh, const Src& src, lo
 
 // ----------------------------------------------------------------------------------
 // 5a. The end of the search (4.), then with tau known: k_i = #{l : M_i(l) > tau} and the tied
-// flag go to delta[i] (flag in bit 31); util[i] gets U_i = 1 - E_i(k_i), or the survival product
-// E_i(k_i) itself for a tied prompt; per-workgroup sums to block_ksum / block_tied.  kItems prompts per thread, their walks in lockstep.
+// flag go to delta[i] (flag in bit 31); util[i] gets U_i = 1 - E_i(k_i), and a tied prompt's
+// 1 - E_i(k_i + 1) goes where its walk state was; per-workgroup sums to block_ksum / block_tied.  kItems prompts per thread, their walks in lockstep.
 // ----------------------------------------------------------------------------------
 // The survival products E_i(k_i) of one wavefront's 256 prompts, pooled like pooled_walk (the
 // number of steps k_i is known here): a lane takes a prompt, multiplies and divides k_i times,
@@ -1307,8 +1308,7 @@ __global__ __launch_bounds__(kBig) void k_bisect_finalize(Src src, long long n, 
                                                           AllocHeader* __restrict__ hdr,
                                                           const unsigned long long* __restrict__ lists,
                                                           const int* __restrict__ list_count,
-                                                          const double* __restrict__ ck_g,
-                                                          const int32_t* __restrict__ ck_l,
+                                                          double* ck_g, const int32_t* __restrict__ ck_l,
                                                           int32_t* __restrict__ delta, double* __restrict__ util,
                                                           long long* __restrict__ block_ksum,
                                                           long long* __restrict__ block_tied, int32_t* dev_status) {
@@ -1407,8 +1407,9 @@ __global__ __launch_bounds__(kBig) void k_bisect_finalize(Src src, long long n, 
                 }
             } while (any);
         }
-        // what is final already is stored as such: k and U = 1 - E(k) of a prompt that is not
-        // tied; a tied prompt leaves k with the flag and E(k) itself, for the tie pass
+        // what is final already is stored as such: k and U = 1 - E(k); a tied prompt leaves k
+        // with the flag, and what its utility becomes if the tie pass gives it a unit,
+        // 1 - E(k + 1), where its walk state was (nobody reads that again)
         int packed[kItems];
         double uu[kItems];
 #pragma unroll
@@ -1419,7 +1420,8 @@ __global__ __launch_bounds__(kBig) void k_bisect_finalize(Src src, long long n, 
             too_deep |= alive[j] && at_limit && depth_capped != 0 && gain_bits(g[j]) > tau_bits;
             const int k = alive[j] ? (int)lf[j] : 0;
             packed[j] = (int)((unsigned)k | (tied ? kTiedBit : 0u));
-            uu[j] = tied ? e[j] : 1.0 - e[j];
+            uu[j] = 1.0 - e[j];
+            if (tied && util) ck_g[pos + j] = 1.0 - surv_next(e[j], b[j], s[j], lf[j]);   // (ties need a budget: ck_g is there)
             ks += k;
             ts += tied ? 1 : 0;
         }
@@ -1443,14 +1445,15 @@ __global__ __launch_bounds__(kBig) void k_bisect_finalize(Src src, long long n, 
 // 5b. Outputs.  Every workgroup adds up the per-workgroup sums of 5a (what lies before it,
 // and the totals, from which r = budget - sum k follows), then runs the tie pass over its
 // chunk.  delta[i] holds k_i, with the tied flag in bit 31 for a tied prompt; util[i] holds
-// the final U_i of a prompt that is not tied and the survival product E_i(k_i) of a tied one
-// (a winner's takes one more step of the product): only tied prompts are written again.
+// U_i(k_i), and for a tied prompt win_util[i] what it becomes with one more unit: only tied
+// prompts are written again, the utility only of those that get a unit.
 // ----------------------------------------------------------------------------------
 template <class Src, int kOff>
 __global__ __launch_bounds__(kBig) void k_bisect_write(Src src, long long n, int g0, long long chunk, int nb,
                                                        long long budget, const AllocHeader* __restrict__ hdr,
                                                        const long long* __restrict__ block_ksum,
                                                        const long long* __restrict__ block_tied,
+                                                       const double* __restrict__ win_util,
                                                        int32_t* __restrict__ delta, double* __restrict__ util,
                                                        void* __restrict__ group_off,
                                                        hora_alloc_summary* __restrict__ summary,
@@ -1507,15 +1510,7 @@ __global__ __launch_bounds__(kBig) void k_bisect_write(Src src, long long n, int
         if (util) {
 #pragma unroll
             for (int j = 0; j < kItems; ++j)
-                if (td[j]) {   // (set for prompts below `end` only)
-                    double e = util[pos + j];
-                    if (win[j]) {
-                        double a, b;
-                        src.load(pos + j, a, b);
-                        e = surv_next(e, b, a + b, (double)kk[j]);
-                    }
-                    util[pos + j] = 1.0 - e;
-                }
+                if (win[j]) util[pos + j] = win_util[pos + j];   // (a tied prompt below `end` that gets a unit)
         }
     }
 }
@@ -1563,7 +1558,7 @@ static int run_bisect(const Src& src, const CommonArgs& a, const Plan& p, const 
                            w.list_count, w.ck_g, w.ck_l);
     }
     // (without a budget there was no search and no walk state)
-    const double* state_g = a.budget > 0 ? w.ck_g : nullptr;
+    double* state_g = a.budget > 0 ? w.ck_g : nullptr;
     const int32_t* state_l = a.budget > 0 ? w.ck_l : nullptr;
 #define HORA_LAUNCH_BISECT_FINALIZE(DEEP)                                                                      \
     hipLaunchKernelGGL((k_bisect_finalize<Src, DEEP>), dim3(p.nb), dim3(kBig), 0, a.stream, src, n, p.chunk,     \
@@ -1577,7 +1572,8 @@ static int run_bisect(const Src& src, const CommonArgs& a, const Plan& p, const 
 #define HORA_LAUNCH_BISECT_WRITE(M)                                                                       \
     hipLaunchKernelGGL((k_bisect_write<Src, M>), dim3(p.nb), dim3(kBig), 0, a.stream, src, n, (int)a.g0,  \
                        p.chunk, p.nb, (long long)a.budget, (const AllocHeader*)w.header,                  \
-                       (const long long*)w.block_ksum, (const long long*)w.block_tied, a.delta, a.util,   \
+                       (const long long*)w.block_ksum, (const long long*)w.block_tied,                    \
+                       (const double*)w.ck_g, a.delta, a.util,                                            \
                        a.group_off, a.summary, a.dev_status)
     if (mode == 0) HORA_LAUNCH_BISECT_WRITE(0);
     else if (mode == 1) HORA_LAUNCH_BISECT_WRITE(1);
