@@ -193,7 +193,8 @@ struct EstimateShared {
 
 template <class Src>
 __device__ __forceinline__ void estimate_depth(const Src& src, long long n, long long budget, long long limit,
-                                               EstimateShared& es, int& est, int& ck, bool& uneven, int& deepest) {
+                                               EstimateShared& es, int& est, int& ck, bool& uneven,
+                                               bool& very_uneven, int& deepest) {
     const bool walker = threadIdx.x < kEstWaves * kWave;
     const double limit_d = (double)limit;
     double b[kEstItems], s[kEstItems], g[kEstItems], lf[kEstItems];
@@ -294,6 +295,10 @@ __device__ __forceinline__ void estimate_depth(const Src& src, long long n, long
     // stores weigh more than the idle lanes).  Pooled above a mean of 32 and deepest > 2 mean + 8.
     uneven = cum > 32ull * kEstSamples &&
              (unsigned long long)es.deepest * kEstSamples > 2ull * cum + 8ull * kEstSamples;
+    // The coarse count's lockstep walks regroup as they thin out (regroup_plan), which beats its pooled
+    // walks up to a deepest walk of several times the mean (measured at a mean of 200: deepest 592,
+    // lockstep 746 us against 828 us pooled; deepest 3266, 3031 us against 2721 us).
+    very_uneven = uneven && (unsigned long long)es.deepest * kEstSamples > 6ull * cum;
     deepest = es.deepest;
 }
 
@@ -440,8 +445,8 @@ __global__ __launch_bounds__(kBig) void k_bisect_coarse(Src src, long long n, lo
     Fetched<Src> first_tile;
     fetch(src, base + (long long)threadIdx.x * kItems, base + kTile < end ? base + kTile : end, first_tile);
     int est, ck, deepest;
-    bool uneven;
-    estimate_depth(src, n, budget, limit, s_est, est, ck, uneven, deepest);
+    bool uneven, very_uneven;
+    estimate_depth(src, n, budget, limit, s_est, est, ck, uneven, very_uneven, deepest);
     const unsigned long long top_ck = octave_top(ck);
     if (blockIdx.x == 0 && threadIdx.x == 0) { hdr->ck_top = top_ck; hdr->uneven = uneven ? 1u : 0u; }
     const unsigned long long est_bottom = octave_top(est) - kOctave;
@@ -480,7 +485,7 @@ __global__ __launch_bounds__(kBig) void k_bisect_coarse(Src src, long long n, lo
         __syncthreads();
         // everything down to the bottom of octave `est` in one go
         unsigned higher = 0u;   // gains above the counted octaves (a lane sees at most kItems * limit <= 2^22)
-        bool pooled = kDeep && uneven;
+        bool pooled = kDeep && very_uneven;
         if constexpr (kDeep) if (pooled) {
             double (&s_pool)[2][kTile] = *reinterpret_cast<double (*)[2][kTile]>(s_f64);
 #pragma unroll
