@@ -420,6 +420,7 @@ __device__ __forceinline__ void regroup(WaveStage& st, const int (&dest)[kItems]
 }
 
 constexpr int kRegroupGain = 6;             // items saved x rounds left from which a regrouping pays (a gain step: ~55 instructions)
+constexpr int kRegroupGainSurvival = 10;    // ... for the survival products (a step: ~22 instructions, six fields to move)
 constexpr int kFine = kWinOct * kSubBins;   // quarter octaves counted per thread in the first go
 static_assert(kFine == kBigWaves, "one wavefront adds up one quarter octave");
 
@@ -448,7 +449,7 @@ __global__ __launch_bounds__(kBig) void k_bisect_coarse(Src src, long long n, lo
     bool uneven, very_uneven;
     estimate_depth(src, n, budget, limit, s_est, est, ck, uneven, very_uneven, deepest);
     const unsigned long long top_ck = octave_top(ck);
-    if (blockIdx.x == 0 && threadIdx.x == 0) { hdr->ck_top = top_ck; hdr->uneven = uneven ? 1u : 0u; }
+    if (blockIdx.x == 0 && threadIdx.x == 0) { hdr->ck_top = top_ck; hdr->uneven = very_uneven ? 2u : (uneven ? 1u : 0u); }   // (2: the output kernel pools too)
     const unsigned long long est_bottom = octave_top(est) - kOctave;
     const unsigned long long fine_top = octave_top(est - (kWinOct - 1));   // (above 1.0 when est < kWinOct - 1: no gain lies there)
     const int lane = lane_id();
@@ -1321,7 +1322,7 @@ __global__ __launch_bounds__(kBig) void k_bisect_finalize(Src src, long long n, 
     long long (&s_red)[2][kBigWaves] = *reinterpret_cast<long long (*)[2][kBigWaves]>(&sh.bins.cnt[0]);
     const long long base = (long long)blockIdx.x * chunk;
     const long long end = base + chunk < n ? base + chunk : n;
-    const bool uneven = kDeep && budget > 0 && hdr->uneven != 0;   // (written by the coarse count of this call)
+    const bool uneven = kDeep && budget > 0 && hdr->uneven == 2u;   // very uneven (written by the coarse count of this call)
     // (the loads of the first tile are under way while the search is finished)
     Fetched<Src> first_tile;
     WalkStates first_states;
@@ -1394,6 +1395,65 @@ __global__ __launch_bounds__(kBig) void k_bisect_finalize(Src src, long long n, 
 #pragma unroll
             for (int j = 0; j < kItems; ++j) e[j] = s_pool_b[threadIdx.x * kItems + j];
             __syncthreads();   // the arrays are reused by the next tile
+        }
+        if constexpr (kDeep) if (util && lockstep) {
+            // deep but not very uneven: in lockstep, the products that still have steps to take
+            // regrouped as they thin out (regroup_plan; k is known, so is the number of rounds
+            // left).  The walk works on copies: the prompts' own values stay with their lanes.
+            // (Not for shallow budgets: measured, no gain at a mean depth of 8 and 2 us lost at 4.)
+            lockstep = false;
+            __shared__ WaveStage s_stage[kBigWaves];
+            WaveStage& stage = s_stage[wave_id()];
+            double wb[kItems], ws[kItems], wk[kItems], le[kItems];
+            int home[kItems];
+            int deepest = 0;
+#pragma unroll
+            for (int j = 0; j < kItems; ++j) {
+                wb[j] = b[j];
+                ws[j] = s[j];
+                wk[j] = alive[j] ? lf[j] : 0.0;
+                le[j] = 0.0;
+                home[j] = j * kWave + lane_id();
+                deepest = (int)wk[j] > deepest ? (int)wk[j] : deepest;
+            }
+#pragma unroll
+            for (int d = kWave / 2; d > 0; d >>= 1) {
+                const int other = __shfl_xor(deepest, d, kWave);
+                deepest = other > deepest ? other : deepest;
+            }
+            int in_use = kItems;
+            for (int round = 0;; ++round) {
+                bool act[kItems];
+                int total = 0;
+#pragma unroll
+                for (int j = 0; j < kItems; ++j) {
+                    act[j] = le[j] < wk[j];
+                    total += __popcll(__ballot(act[j]));
+                }
+                if (total == 0) break;                      // uniform over the wavefront
+                const int fewer = in_use - (total + kWave - 1) / kWave;
+                if (fewer > 0 && fewer * (deepest - round) >= kRegroupGainSurvival) {   // uniform
+                    int dest[kItems];
+                    regroup_plan(act, total, dest);
+                    regroup(stage, dest, wb);
+                    regroup(stage, dest, ws);
+                    regroup(stage, dest, wk);
+                    regroup(stage, dest, le);
+                    regroup(stage, dest, e);
+                    regroup(stage, dest, home);
+                    in_use = (total + kWave - 1) / kWave;
+#pragma unroll
+                    for (int j = 0; j < kItems; ++j) act[j] = j * kWave + lane_id() < total;
+                }
+#pragma unroll
+                for (int j = 0; j < kItems; ++j) {
+                    if (act[j]) {
+                        e[j] = surv_next(e[j], wb[j], ws[j], le[j]);
+                        le[j] += 1.0;
+                    }
+                }
+            }
+            if (in_use != kItems) regroup(stage, home, e);   // uniform: back to the prompts' lanes
         }
         if (util && lockstep) {
             double le[kItems];
