@@ -16,7 +16,9 @@
 //     tile has seen its share of the budget.  If every tile selected its share on its own, the
 //     union would hold at least `budget` gains, all of them above the lowest tile's stopping
 //     point: that point is a lower bound for tau, whatever the data, and no prompt walks much
-//     deeper than tau.
+//     deeper than tau.  A wavefront walks four prompts per lane in lockstep and regroups the
+//     walks that are still active as the others end (regroup_plan), or, for deep budgets with
+//     a few very deep prompts, hands its prompts to its lanes one by one (pooled_walk).
 //  2. first narrowing pass (k_bisect_pass<0>): every workgroup adds the tiles' counts up for
 //     itself and takes the quarter octave in which the running count reaches the budget as the
 //     first bracket (lo, hi] of tau; the bracket is cut into 256 intervals, the gains inside are
