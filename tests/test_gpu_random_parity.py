@@ -94,3 +94,44 @@ def test_random_batches(gpu, oracle, seed):
         host = buf.cpu().numpy()
         assert np.array_equal(host[skew:skew + total], oracle.token_broadcast(vals.astype(np.float64), tok_off).astype(vals.dtype)), tag
         assert np.isnan(host[:skew]).all() and np.isnan(host[skew + total:]).all(), tag
+
+
+@pytest.mark.parametrize("seed", [201, 202])
+def test_random_posteriors(gpu, oracle, seed):
+    """Per-prompt posteriors of four kinds (learned priors; a few slowly decaying gain sequences
+    among fast ones; a shared prior written per prompt; blocks of very different prompts), with
+    budgets from a tenth of a unit to 150 units per prompt and caps: walks of very different
+    length inside a wavefront and inside a batch.  Allocation and offsets bit for bit, utilities
+    within 1e-12."""
+    sess, torch, hora = gpu
+    rng = np.random.default_rng(seed)
+    for case in range(70):
+        n = int(rng.integers(2049, 50000))
+        g0 = int(rng.choice([2, 4, 8]))
+        kind = int(rng.integers(0, 4))
+        if kind == 0:
+            s = rng.uniform(0.25, 16.0, n)
+            p = rng.uniform(0.02, 0.98, n)
+            c = rng.binomial(g0, p)
+            alpha, beta = s * p + c, s * (1 - p) + g0 - c
+        elif kind == 1:
+            alpha, beta = rng.uniform(4.0, 9.0, n), rng.uniform(0.3, 1.0, n)
+            slow = rng.random(n) < rng.uniform(0.005, 0.1)
+            alpha[slow] = rng.uniform(0.1, 0.7, int(slow.sum()))
+            beta[slow] = rng.uniform(1.0, 4.0, int(slow.sum()))
+        elif kind == 2:
+            c = rng.binomial(g0, rng.beta(0.5, 0.5, n))
+            alpha, beta = 1.0 + c, 1.0 + g0 - c.astype(np.float64)
+        else:
+            alpha = np.repeat(rng.uniform(0.1, 9.0, (n + 999) // 1000), 1000)[:n] + rng.uniform(0, 0.01, n)
+            beta = np.repeat(rng.uniform(0.3, 9.0, (n + 999) // 1000), 1000)[:n] + rng.uniform(0, 0.01, n)
+        budget = int(min(float(rng.choice([0.1, 0.7, 2.0, 5.0, 9.0, 20.0, 30.0, 60.0, 150.0])) * n, 600000))
+        cap = int(rng.choice([0, 0, 0, 3, 17, 60]))
+        if cap > 0:
+            budget = min(budget, cap * n)
+        tag = f"seed {seed} case {case}: n={n} g0={g0} kind={kind} budget={budget} cap={cap}"
+        print(tag, flush=True)
+        want = oracle.allocate_posterior(alpha, beta, budget, delta_max=cap)
+        got = sess.allocate_posterior(dev(torch, alpha), dev(torch, beta), g0, budget, delta_max=cap)
+        assert sess.status() == 0, tag
+        assert allocation_matches(got, want, oracle.utilities(alpha, beta, want), oracle.group_offsets(want, g0)), tag
