@@ -27,6 +27,18 @@ __device__ __forceinline__ double sub_sum(double v) {
     return v;
 }
 
+// 1 / d for d > 0: the hardware's approximation, two Newton steps and a residual step (the
+// division's own sequence without its scaling and special cases): the rounded quotient
+// where d and 1 / d are normal numbers (beyond that it ends in 0 or infinity like the
+// quotient does), at a quarter of the instructions of a division; every lane of a group
+// repeats it.
+__device__ __forceinline__ double reciprocal(double d) {
+    double r = __builtin_amdgcn_rcp(d);
+    r = __builtin_fma(__builtin_fma(-d, r, 1.0), r, r);
+    r = __builtin_fma(__builtin_fma(-d, r, 1.0), r, r);
+    return __builtin_fma(__builtin_fma(-d, r, 1.0), r, r);   // (the division's own last step: the residual of the quotient)
+}
+
 template <int L>
 __device__ __forceinline__ int sub_and(int v) {
 #pragma unroll
@@ -77,23 +89,31 @@ __global__ __launch_bounds__(kThreads) void k_group_adv(long long n_groups, cons
     // but inside the array is loaded and not used)
     double x[kKeep];
     bool in[kKeep];
+    const F* const src0 = reward + lo + kPer * sub;    // this lane's first run
+    F* const dst0 = adv + lo + kPer * sub;
+    // responses of the group from this lane's first run on (as far as the registers reach)
+    int ahead = (int)(size - kPer * sub < (long long)kKeep * L ? (size - kPer * sub > 0 ? size - kPer * sub : 0)
+                                                              : (long long)kKeep * L);
+    // (the compiler is kept from folding the 32-bit count back into 64-bit comparisons with the group's size)
+    asm volatile("" : "+v"(ahead));
 #pragma unroll
     for (int r = 0; r < kRuns; ++r) {
-        const long long at = (long long)kPer * (sub + L * r);   // position in the group
-        const F* src = reward + lo + at;
-        if (at < size && lo + at + kPer <= n_resp) {
+        const int at = kPer * L * r;                   // from this lane's first run
+        const F* src = src0 + at;
+        const int have = ahead - at;                   // responses of the group from this run on (may be <= 0)
+        F raw[kPer];
+        if (have > 0 && lo + kPer * sub + at + kPer <= n_resp) {
             const V v = *reinterpret_cast<const V*>(src);
 #pragma unroll
-            for (int i = 0; i < kPer; ++i) {
-                in[r * kPer + i] = at + i < size;
-                x[r * kPer + i] = in[r * kPer + i] ? (double)v[i] : 0.0;
-            }
+            for (int i = 0; i < kPer; ++i) raw[i] = v[i];
         } else {
 #pragma unroll
-            for (int i = 0; i < kPer; ++i) {
-                in[r * kPer + i] = at + i < size;
-                x[r * kPer + i] = in[r * kPer + i] ? (double)src[i] : 0.0;
-            }
+            for (int i = 0; i < kPer; ++i) raw[i] = i < have ? src[i] : (F)0;
+        }
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) {
+            in[r * kPer + i] = i < have;
+            x[r * kPer + i] = (double)(in[r * kPer + i] ? raw[i] : (F)0);
         }
     }
     const double first = __shfl(x[0], 0, L);   // reward[lo] (0 for an empty group)
@@ -116,8 +136,7 @@ __global__ __launch_bounds__(kThreads) void k_group_adv(long long n_groups, cons
     auto put = [&](const double (&y)[kKeep]) {
 #pragma unroll
         for (int r = 0; r < kRuns; ++r) {
-            const long long at = (long long)kPer * (sub + L * r);
-            F* dst = adv + lo + at;
+            F* dst = dst0 + kPer * L * r;
             if (in[r * kPer + kPer - 1]) {
                 V v;
 #pragma unroll
@@ -133,21 +152,26 @@ __global__ __launch_bounds__(kThreads) void k_group_adv(long long n_groups, cons
     double y[kKeep];
 
     // Every quotient whose divisor belongs to the group is formed as a product with the
-    // divisor's reciprocal (one division per lane instead of one per response): at most
-    // 1.5 units in the last place away from the quotient itself.
+    // divisor's reciprocal (`reciprocal`: once per lane instead of a division per response):
+    // a few units in the last place away from the quotient itself, against a tolerance of 1e-12.
     if (mode == HORA_ADV_RLOO) {
-        const double inv = size > 1 ? 1.0 / (double)(size - 1) : 0.0;
+        // (a group of one, or of equal rewards, gets exact zeros: both factors vanish)
+        const bool none = size <= 1 || equal;
+        const double inv = none ? 0.0 : reciprocal((double)(size - 1));
+        const double own = none ? 0.0 : 1.0;
+        // (product and difference rounded separately, as the definition's quotient and difference
+        // are: a response that equals the mean of the others gets an exact zero where it does there)
 #pragma unroll
-        for (int k = 0; k < kKeep; ++k) y[k] = (size == 1 || equal) ? 0.0 : x[k] - (sum - x[k]) * inv;
+        for (int k = 0; k < kKeep; ++k) y[k] = own * x[k] - (sum - x[k]) * inv;
         put(y);
         for (long long j = rest; j < hi; j += L) {
             const double z = (double)reward[j];
-            adv[j] = (F)(equal ? 0.0 : z - (sum - z) * inv);
+            adv[j] = (F)(own * z - (sum - z) * inv);
         }
         return;
     }
 
-    const double mean = size > 0 ? sum / (double)size : 0.0;
+    const double mean = size > 0 ? sum * reciprocal((double)size) : 0.0;
     if (mode == HORA_ADV_CENTER) {
 #pragma unroll
         for (int k = 0; k < kKeep; ++k) y[k] = equal ? 0.0 : x[k] - mean;
@@ -172,13 +196,14 @@ __global__ __launch_bounds__(kThreads) void k_group_adv(long long n_groups, cons
         }
     }
     ss = sub_sum<L>(ss);
-    const double inv = zero ? 0.0 : 1.0 / (sqrt(ss / (double)(size - ddof)) + eps);
+    const double inv = zero ? 0.0 : reciprocal(sqrt(ss * reciprocal((double)(size - ddof))) + eps);
+    // (inv = 0 for a group without variance: the sum with +0 makes every product a +0)
 #pragma unroll
-    for (int k = 0; k < kKeep; ++k) y[k] = zero ? 0.0 : (x[k] - mean) * inv;
+    for (int k = 0; k < kKeep; ++k) y[k] = __builtin_fma(x[k] - mean, inv, 0.0);
     put(y);
     for (long long j = rest; j < hi; j += L) {
         const double z = (double)reward[j];
-        adv[j] = (F)(zero ? 0.0 : (z - mean) * inv);
+        adv[j] = (F)__builtin_fma(z - mean, inv, 0.0);
     }
 }
 
