@@ -20,10 +20,32 @@
 
 namespace hora {
 
+// Cross-lane steps inside a sub-group of L lanes.  Inside a row of 16 lanes they are DPP
+// operand modifiers (register moves: quad permutations, the mirror of 8 and of 16 lanes); only
+// what crosses rows takes the LDS-routed shuffle.  A double moves as two halves.
+template <int kCtrl>
+__device__ __forceinline__ int dpp_take(int v) {
+    return __builtin_amdgcn_update_dpp(0, v, kCtrl, 0xf, 0xf, true);
+}
+template <int kCtrl>
+__device__ __forceinline__ double dpp_take(double v) {
+    const long long bits = __double_as_longlong(v);
+    const int lo = dpp_take<kCtrl>((int)(unsigned)((unsigned long long)bits & 0xffffffffull));
+    const int hi = dpp_take<kCtrl>((int)(unsigned)((unsigned long long)bits >> 32));
+    return __longlong_as_double((long long)(((unsigned long long)(unsigned)hi << 32) | (unsigned)lo));
+}
+constexpr int kQuadXor1 = 0xb1, kQuadXor2 = 0x4e;       // quad_perm [1,0,3,2], [2,3,0,1]
+constexpr int kHalfMirror = 0x141, kRowMirror = 0x140;  // lane i <-> 7 - i, 15 - i inside its row
+
 template <int L>
 __device__ __forceinline__ double sub_sum(double v) {
+    // quads first, then the other quad of the 8 (any of its lanes holds its sum), then the other 8
+    if (L >= 2) v += dpp_take<kQuadXor1>(v);
+    if (L >= 4) v += dpp_take<kQuadXor2>(v);
+    if (L >= 8) v += dpp_take<kHalfMirror>(v);
+    if (L >= 16) v += dpp_take<kRowMirror>(v);
 #pragma unroll
-    for (int d = L / 2; d > 0; d >>= 1) v += __shfl_xor(v, d, L);
+    for (int d = 16; d < L; d <<= 1) v += __shfl_xor(v, d, L);
     return v;
 }
 
@@ -41,9 +63,22 @@ __device__ __forceinline__ double reciprocal(double d) {
 
 template <int L>
 __device__ __forceinline__ int sub_and(int v) {
+    if (L >= 2) v &= dpp_take<kQuadXor1>(v);
+    if (L >= 4) v &= dpp_take<kQuadXor2>(v);
+    if (L >= 8) v &= dpp_take<kHalfMirror>(v);
+    if (L >= 16) v &= dpp_take<kRowMirror>(v);
 #pragma unroll
-    for (int d = L / 2; d > 0; d >>= 1) v &= __shfl_xor(v, d, L);
+    for (int d = 16; d < L; d <<= 1) v &= __shfl_xor(v, d, L);
     return v;
+}
+
+// The value of the sub-group's first lane, in all of its lanes.
+template <int L>
+__device__ __forceinline__ double sub_first(double v) {
+    if (L == 1) return v;
+    if (L == 2) return dpp_take<0xa0>(v);   // quad_perm [0,0,2,2]
+    if (L == 4) return dpp_take<0x00>(v);   // quad_perm [0,0,0,0]
+    return __shfl(v, 0, L);
 }
 
 // Rewards a lane keeps in registers: a group of up to L * kKeep responses is read from
@@ -116,7 +151,7 @@ __global__ __launch_bounds__(kThreads) void k_group_adv(long long n_groups, cons
             x[r * kPer + i] = (double)(in[r * kPer + i] ? raw[i] : (F)0);
         }
     }
-    const double first = __shfl(x[0], 0, L);   // reward[lo] (0 for an empty group)
+    const double first = sub_first<L>(x[0]);   // reward[lo] (0 for an empty group)
     double sum = 0.0;
     int equal = 1;
 #pragma unroll

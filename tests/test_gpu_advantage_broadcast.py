@@ -72,7 +72,9 @@ def test_advantage_parity_on_the_workloads(gpu, oracle, name):
 
 def test_advantage_general_rewards_modes_and_types(gpu, oracle):
     rng = np.random.default_rng(31)
-    for n_groups, lo, hi in ((1, 1, 1), (1, 700, 700), (257, 1, 3), (5000, 1, 40), (300, 30, 900), (6, 3000, 9000)):
+    # (mean sizes that take 1, 2, 4, 8, 16, 32 and 64 lanes per group: every cross-lane path of the kernel)
+    for n_groups, lo, hi in ((1, 1, 1), (1, 700, 700), (257, 1, 3), (900, 2, 9), (5000, 1, 40), (400, 20, 80),
+                             (300, 60, 160), (300, 30, 900), (6, 3000, 9000)):
         sizes = rng.integers(lo, hi + 1, n_groups)
         off = np.zeros(n_groups + 1, dtype=np.int64)
         np.cumsum(sizes, out=off[1:])
