@@ -279,9 +279,10 @@ int hora_allocate_sharded(int64_t n, int32_t g0, const int32_t *c, double alpha0
  *         deviation (for objectives of the Dr. GRPO kind; the paper's runs use GRPO as
  *         written in Sec. 3.1).  A group whose rewards are all equal gets exactly 0.
  * Evaluated in binary64 (partial sums per lane, then combined); a quotient whose divisor
- * is the same for the whole group (G_g - 1, std + eps) is formed as a product with the
- * divisor's reciprocal, at most 1.5 units in the last place of binary64 away from the
- * quotient.  The result is rounded once when stored as float.
+ * is the same for the whole group (G_g, G_g - 1, std + eps) is formed as a product with the
+ * divisor's reciprocal (itself the rounded quotient 1 / divisor for normal numbers), and the
+ * last step of GRPO is one fused multiply-add: a few units in the last place of binary64
+ * away from the expression as written.  The result is rounded once when stored as float.
  *
  * group_off : device, n_groups+1 offsets of type off_t, group_off[0] = 0, non-decreasing
  *             (else HORA_ERR_RANGE in dev_status).
