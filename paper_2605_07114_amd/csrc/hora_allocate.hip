@@ -400,7 +400,6 @@ __global__ __launch_bounds__(kBig) void k_class_write(const int32_t* __restrict_
                                                           int32_t* dev_status, int rule) {
     __shared__ double s_gain[kTableCap];
     __shared__ double s_surv[kTableCap];
-    __shared__ long long s_part[2][kMaxClasses * kMaxBlocks / kWave];
     __shared__ long long s_n[kMaxClasses];       // prompts per class, whole batch
     __shared__ long long s_before[kMaxClasses];  // prompts per class in workgroups before this one
     __shared__ ClassSolution s_sol;
@@ -426,11 +425,11 @@ __global__ __launch_bounds__(kBig) void k_class_write(const int32_t* __restrict_
     // first tile of c, the two tables, the histogram): one round trip to memory instead
     // of one per stage.
     constexpr int kTableLoads = kTableCap / kBig;                   // table entries per thread
-    constexpr int kHistLoads = kMaxClasses * kMaxBlocks / kBig;     // histogram entries per thread
+    constexpr int kClassRounds = kMaxClasses / kBigWaves;           // classes per wavefront: a class's counts are one 1 KB row
+    static_assert(kMaxBlocks == 4 * kWave && kMaxClasses % kBigWaves == 0, "a wavefront reads a class's row as 16-byte pieces");
     const int table_len = nc * row_len;
-    const int entries = nc * kMaxBlocks;
     double tg[kTableLoads], ts[kTableLoads];
-    int hh[kHistLoads];
+    v4i hh[kClassRounds];
 #pragma unroll
     for (int q = 0; q < kTableLoads; ++q) {
         const int i = q * kBig + (int)threadIdx.x;
@@ -438,9 +437,11 @@ __global__ __launch_bounds__(kBig) void k_class_write(const int32_t* __restrict_
         ts[q] = i < table_len ? surv_table[i] : 0.0;
     }
 #pragma unroll
-    for (int q = 0; q < kHistLoads; ++q) {
-        const int idx = q * kBig + (int)threadIdx.x;
-        hh[q] = (idx < entries && (idx & (kMaxBlocks - 1)) < nb) ? class_hist[idx] : 0;
+    for (int q = 0; q < kClassRounds; ++q) {
+        const int cls = wave_id() + kBigWaves * q;
+        v4i v = {0, 0, 0, 0};
+        if (cls < nc) v = *reinterpret_cast<const v4i*>(class_hist + cls * kMaxBlocks + lane * 4);   // uniform per wavefront
+        hh[q] = v;
     }
     int first_tile[kItems];
     load_items_i32(c, base + (long long)threadIdx.x * kItems, end, c_vec, -1, first_tile);
@@ -455,30 +456,25 @@ __global__ __launch_bounds__(kBig) void k_class_write(const int32_t* __restrict_
         }
     }
 
-    // class totals and the part that lies before this workgroup: the counts of class c
-    // are kMaxBlocks consecutive entries, so every wavefront sums entries of one class
+    // class totals and the part that lies before this workgroup: a wavefront adds up the
+    // kMaxBlocks counts of its class, four per lane (entries of workgroups that do not exist
+    // are whatever an earlier call left there: masked)
 #pragma unroll
-    for (int q = 0; q < kHistLoads; ++q) {
-        const int i0 = q * kBig;
-        if (i0 < entries) {   // uniform
-            const int idx = i0 + (int)threadIdx.x;
-            const int b = idx & (kMaxBlocks - 1);
-            const long long tot_w = wave_total_i64((long long)hh[q]);
-            const long long bef_w = wave_total_i64(b < (int)blockIdx.x ? (long long)hh[q] : 0ll);
-            if (lane == 0 && idx < entries) { s_part[0][idx >> 6] = tot_w; s_part[1][idx >> 6] = bef_w; }
-        }
-    }
-    __syncthreads();
-    if (threadIdx.x < (unsigned)nc) {
-        constexpr int kSlots = kMaxBlocks / kWave;
-        long long tot = 0, bef = 0;
+    for (int q = 0; q < kClassRounds; ++q) {
+        const int cls = wave_id() + kBigWaves * q;
+        if (cls < nc) {   // uniform per wavefront
+            const int e[4] = {hh[q].x, hh[q].y, hh[q].z, hh[q].w};
+            long long tot = 0, bef = 0;
 #pragma unroll
-        for (int q = 0; q < kSlots; ++q) {
-            tot += s_part[0][threadIdx.x * kSlots + q];
-            bef += s_part[1][threadIdx.x * kSlots + q];
+            for (int i = 0; i < 4; ++i) {
+                const int b = lane * 4 + i;
+                tot += b < nb ? (long long)e[i] : 0ll;
+                bef += b < (int)blockIdx.x ? (long long)e[i] : 0ll;   // (blockIdx.x < nb)
+            }
+            tot = wave_total_i64(tot);
+            bef = wave_total_i64(bef);
+            if (lane == 0) { s_n[cls] = tot; s_before[cls] = bef; }
         }
-        s_n[threadIdx.x] = tot;
-        s_before[threadIdx.x] = bef;
     }
     __syncthreads();
 
