@@ -56,7 +56,6 @@ static_assert(sizeof(ShardTableKey) == 256, "key size");
 constexpr unsigned long long kTableMagic = 0x484f52415461626cull;
 constexpr int kShardMaxClasses = HORA_CLASS_MAX_G0 + 1;
 constexpr int kLevelBlock = 64;          // sorted levels per coarse block (one wavefront evaluates a block)
-constexpr int kMaxCoarse = kShardTableCap / kLevelBlock;
 constexpr int kWaveShardMax = 1024;      // larger shards go to the workgroup-per-shard kernel
 constexpr int kWaveShardMeanMax = 256;   // mean shard size up to which the wavefront-per-shard kernel is used
 
@@ -723,9 +722,9 @@ __global__ __launch_bounds__(kShardThreads) void k_shard_allocate_todo(Src src, 
 // running in lockstep.
 //  1. histogram of c: lane k of the group counts class k (wavefront ballots, the group's bits);
 //  2. coarse search: the group's lanes evaluate count_ge of the last level of every block of
-//     64 sorted levels (coarse rows in LDS); the first block that reaches the budget is taken;
-//     fine search: its 64 levels, 64 / L per lane (one 32- or 128-byte row each from global
-//     memory).  tau is the first level whose count_ge reaches the budget; the level before it
+//     64 sorted levels (32 for 16-lane groups; coarse rows in LDS); the first block that
+//     reaches the budget is taken; fine search: the block's levels, L at a time (one 32- or
+//     128-byte row each from global memory).  tau is the first level whose count_ge reaches the budget; the level before it
 //     gives the gains above tau per class;
 //  3. outputs with the tie pass inside the group (ballot + mbcnt ranks, group prefix sums for
 //     the offsets).
@@ -852,7 +851,14 @@ __global__ __launch_bounds__(kShardThreads, (L == 16 && !kFused) ? 8 : 1) void k
     constexpr int kPerBlock = kShardWaves * kPerWave;    // shards per workgroup
     // (16 lanes are chosen for at most 16 classes: their rows have 16 entries)
     constexpr int kCoarseStride = L == 16 ? 16 : 64;
-    __shared__ __align__(16) unsigned short s_coarse[kMaxCoarse * kCoarseStride];
+    // Levels per block.  A 16-lane group looks at a block's levels L at a time, and the kernel is
+    // bound by its vector instructions: blocks of 32 levels (two rounds instead of four) for twice
+    // the rows in LDS, which 32-byte rows can afford; of 16 levels (one round) where a call has few
+    // shards and LDS does not limit how many wavefronts are resident (measured: 22.7 -> 20.9 us for
+    // 65536 shards with 32, 21.5 us with 16; 5.7 -> 5.3 / 4.5 us for four shards).
+    constexpr int kBlock = L == 16 ? (kFused ? 16 : 32) : kLevelBlock;
+    constexpr int kRowsMax = kShardTableCap / kBlock;
+    __shared__ __align__(16) unsigned short s_coarse[kRowsMax * kCoarseStride];
     __shared__ GroupScratch<L> s_group[kPerBlock];
     __shared__ int s_left[kPerBlock];
     __shared__ int s_left_n, s_tables;
@@ -860,7 +866,7 @@ __global__ __launch_bounds__(kShardThreads, (L == 16 && !kFused) ? 8 : 1) void k
     const int nc = g0 + 1;                               // (the host picks L >= nc)
     const int stride = L == 16 ? 16 : level_stride(nc);
     const int levels = nc * usable;
-    const int n_coarse = (levels + kLevelBlock - 1) / kLevelBlock;
+    const int n_coarse = (levels + kBlock - 1) / kBlock;
     const int lane = lane_id();
     const int sub = lane / L, sl = lane % L;             // the shard's slot in the wavefront, the lane in the group
     const long long first_shard = (long long)blockIdx.x * kPerBlock;
@@ -888,24 +894,33 @@ __global__ __launch_bounds__(kShardThreads, (L == 16 && !kFused) ? 8 : 1) void k
         s_tables = shard_tables_match(key, g0, src.alpha0, src.beta0, depth, usable) ? 1 : 0;
     }
     // The coarse rows are requested before it is known whether the workspace holds the tables
-    // (rows of 16 classes, two 16-byte pieces each, one piece per thread): the answer and the
+    // (rows of 16 classes, two 16-byte pieces each, kEarly pieces per thread): the answer and the
     // rows travel together, and rows of a workspace without tables are dropped.
-    static_assert(kMaxCoarse * 2 <= kShardThreads, "one piece of a coarse row per thread");
+    constexpr int kEarly = (kRowsMax * 2 + kShardThreads - 1) / kShardThreads;
     const bool early_rows = stride == 16;
-    uint4 early = {0u, 0u, 0u, 0u};
-    if (early_rows && (int)threadIdx.x < n_coarse * 2) {
-        int p = ((int)threadIdx.x >> 1) * kLevelBlock + kLevelBlock - 1;
-        if (p > levels - 1) p = levels - 1;
-        early = reinterpret_cast<const uint4*>(level_kge + (long long)p * 16)[threadIdx.x & 1];
+    uint4 early[kEarly];
+#pragma unroll
+    for (int i = 0; i < kEarly; ++i) {
+        const int piece = i * kShardThreads + (int)threadIdx.x;
+        early[i] = uint4{0u, 0u, 0u, 0u};
+        if (early_rows && piece < n_coarse * 2) {
+            int p = (piece >> 1) * kBlock + kBlock - 1;
+            if (p > levels - 1) p = levels - 1;
+            early[i] = reinterpret_cast<const uint4*>(level_kge + (long long)p * 16)[piece & 1];
+        }
     }
     __syncthreads();
     const bool tables = s_tables != 0;
     if (tables && early_rows) {
-        if ((int)threadIdx.x < n_coarse * 2) reinterpret_cast<uint4*>(s_coarse)[threadIdx.x] = early;
+#pragma unroll
+        for (int i = 0; i < kEarly; ++i) {
+            const int piece = i * kShardThreads + (int)threadIdx.x;
+            if (piece < n_coarse * 2) reinterpret_cast<uint4*>(s_coarse)[piece] = early[i];
+        }
     } else if (tables) {
         for (int idx = (int)threadIdx.x; idx < n_coarse * stride; idx += kShardThreads) {
             const int q = idx / stride, k = idx - q * stride;
-            int p = q * kLevelBlock + kLevelBlock - 1;
+            int p = q * kBlock + kBlock - 1;
             if (p > levels - 1) p = levels - 1;
             s_coarse[idx] = level_kge[(long long)p * stride + k];
         }
@@ -1026,11 +1041,11 @@ __global__ __launch_bounds__(kShardThreads, (L == 16 && !kFused) ? 8 : 1) void k
                 if (block == INT_MAX) {
                     ok = false;                       // the tables do not reach the budget
                 } else {
-                    // fine: the 64 levels of the block, 64 / L per lane
+                    // fine: the levels of the block, kBlock / L per lane
                     int under = 0;                    // levels of the block whose count stays under the budget
                     int best = before_block;          // ... and the largest such count
-                    for (int t0 = 0; t0 < kLevelBlock; t0 += L) {
-                        const int lvl = block * kLevelBlock + t0 + sl;
+                    for (int t0 = 0; t0 < kBlock; t0 += L) {
+                        const int lvl = block * kBlock + t0 + sl;
                         const bool in = lvl < levels;
                         // (lanes past the last level read its row and drop the result)
                         const unsigned short* row = level_kge + (long long)(in ? lvl : levels - 1) * stride;
@@ -1042,7 +1057,7 @@ __global__ __launch_bounds__(kShardThreads, (L == 16 && !kFused) ? 8 : 1) void k
                         if (in && ct < want) { under += 1; best = ct > best ? ct : best; }
                     }
                     const int t = group_sum<int, L>(under);                // the first level that reaches the budget
-                    const int j = block * kLevelBlock + t;                 // tau = level j
+                    const int j = block * kBlock + t;                      // tau = level j
                     count_gt = group_max<L>(best);
                     tau_bits = level_bits[j];
                     if (sl < nc) {
