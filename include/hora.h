@@ -140,7 +140,12 @@ size_t hora_allocate_workspace_bytes(int64_t n, int32_t g0);
  *             n * delta_max gives HORA_ERR_INFEASIBLE.
  * method    : hora_alloc_method.
  * delta     : device out, n int32.
- * util      : device out, n doubles, U_i(delta_i) by the product recurrence.  Nullable.
+ * util      : device out, n doubles, U_i(delta_i) = 1 - E_i(delta_i) (App. A), U_i(0) = 0
+ *             exactly.  HORA_ALLOC_CLASS takes E from the product recurrence; the bisection
+ *             method takes it from the last gain of its search, E(k) = M(k) (alpha + beta + k)
+ *             / alpha (the ratio of the two closed forms of App. A).  Both lie within a few
+ *             1e-16 of E per step of the true value; U is a difference from 1, so its
+ *             relative accuracy is that divided by U.  Nullable.
  * group_off : device out, n+1 offsets of type off_t: exclusive prefix sums of
  *             g0 + delta_i (group i holds responses group_off[i] .. group_off[i+1]-1,
  *             pre-rollouts first).  Nullable.  With HORA_I32 the total n*g0 + budget

@@ -27,9 +27,10 @@
 //     the interval where the running count reaches the budget.
 //  4. k_bisect_pass<1> keeps what the lists hold of the narrower bracket.
 //  5. k_bisect_finalize: every workgroup finishes the search from the lists (usually a few
-//     thousand gains), then k_i = #{l : M_i(l) > tau} and U_i = 1 - E_i(k_i) per prompt (final
-//     for every prompt that gets no unit at tau; a tied prompt is flagged and leaves the utility
-//     of one more unit aside); k_bisect_write: ties at tau by prompt index (tied prompts rewritten),
+//     thousand gains), then k_i = #{l : M_i(l) > tau} and U_i = 1 - E_i(k_i) per prompt, E from
+//     the gain the walk ends with (E(l) = M(l) (alpha + beta + l) / alpha, App. A), final for
+//     every prompt that gets no unit at tau; a tied prompt is flagged and leaves the utility
+//     of one more unit aside; k_bisect_write: ties at tau by prompt index (tied prompts rewritten),
 //     group offsets.
 //
 // Under a shared prior the gains of a bracket are few distinct values, each repeated: step 3
@@ -181,6 +182,15 @@ __device__ __forceinline__ void store_states(double* __restrict__ ck_g, int32_t*
 // 1 / x gains above x (they decrease and sum to at most 1), so fewer than `budget` gains
 // exceed n / budget and tau lies below.
 // ----------------------------------------------------------------------------------
+// Shares of the budget, worked out by the host: a 64-bit division in a kernel is a long sequence
+// of vector instructions, run by every wavefront of every workgroup.
+struct BudgetShares {
+    unsigned long long sample;      // of the depth estimate's sample, rounded up
+    unsigned long long per_prompt;  // budget / n, rounded down
+    unsigned long long tile;        // of a full tile, rounded up
+    unsigned long long last_tile;   // of the batch's last tile (n - its start prompts), rounded up
+};
+
 constexpr int kEstWaves = 4;
 constexpr int kEstItems = 2;
 constexpr int kEstSamples = kEstWaves * kWave * kEstItems;   // 512
@@ -194,7 +204,7 @@ struct EstimateShared {
 };
 
 template <class Src>
-__device__ __forceinline__ void estimate_depth(const Src& src, long long n, long long budget, long long limit,
+__device__ __forceinline__ void estimate_depth(const Src& src, long long n, const BudgetShares& shares, long long limit,
                                                EstimateShared& es, int& est, int& ck, bool& uneven,
                                                bool& very_uneven, int& deepest) {
     const bool walker = threadIdx.x < kEstWaves * kWave;
@@ -222,12 +232,10 @@ __device__ __forceinline__ void estimate_depth(const Src& src, long long n, long
     }
     if (threadIdx.x == 0) es.deepest = 0;
     __syncthreads();
-    // the sample's share of the budget, rounded up (budget <= 2^51: no overflow)
-    const unsigned long long want = ((unsigned long long)budget * kEstSamples + (unsigned long long)n - 1ull) /
-                                    (unsigned long long)n;
+    const unsigned long long want = shares.sample;
     const unsigned long long need = want + (want >> 3) + 16ull;
     const unsigned long long sure = want - (want >> 3);
-    const unsigned long long ratio = (unsigned long long)budget / (unsigned long long)n;
+    const unsigned long long ratio = shares.per_prompt;
     const int lumped = ratio >= 2ull ? 63 - __clzll((long long)ratio) : 0;   // octaves 0 .. lumped - 1 lie above n / budget
     int o = lumped > 0 ? lumped - 1 : 0;
     const int first = o;
@@ -422,14 +430,13 @@ __device__ __forceinline__ void regroup(WaveStage& st, const int (&dest)[kItems]
 }
 
 constexpr int kRegroupGain = 6;             // items saved x rounds left from which a regrouping pays (a gain step: ~55 instructions)
-constexpr int kRegroupGainSurvival = 10;    // ... for the survival products (a step: ~22 instructions, six fields to move)
 constexpr int kFine = kWinOct * kSubBins;   // quarter octaves counted per thread in the first go
 static_assert(kFine == kBigWaves, "one wavefront adds up one quarter octave");
 
 // kDeep: the variant for deep budgets (the host's choice, budget > kDeepRatio * n), which
 // can pool its walks; the other one does without that code, its registers and its LDS.
 template <class Src, bool kDeep>
-__global__ __launch_bounds__(kBig) void k_bisect_coarse(Src src, long long n, long long budget, long long limit,
+__global__ __launch_bounds__(kBig) void k_bisect_coarse(Src src, long long n, BudgetShares shares, long long limit,
                                                         long long chunk, CoarseSlot* __restrict__ slots,
                                                         AllocHeader* __restrict__ hdr, double* __restrict__ ck_g,
                                                         int32_t* __restrict__ ck_l, int32_t* dev_status) {
@@ -449,9 +456,9 @@ __global__ __launch_bounds__(kBig) void k_bisect_coarse(Src src, long long n, lo
     fetch(src, base + (long long)threadIdx.x * kItems, base + kTile < end ? base + kTile : end, first_tile);
     int est, ck, deepest;
     bool uneven, very_uneven;
-    estimate_depth(src, n, budget, limit, s_est, est, ck, uneven, very_uneven, deepest);
+    estimate_depth(src, n, shares, limit, s_est, est, ck, uneven, very_uneven, deepest);
     const unsigned long long top_ck = octave_top(ck);
-    if (blockIdx.x == 0 && threadIdx.x == 0) { hdr->ck_top = top_ck; hdr->uneven = very_uneven ? 2u : (uneven ? 1u : 0u); }   // (2: the output kernel pools too)
+    if (blockIdx.x == 0 && threadIdx.x == 0) { hdr->ck_top = top_ck; hdr->uneven = very_uneven ? 2u : (uneven ? 1u : 0u); }
     const unsigned long long est_bottom = octave_top(est) - kOctave;
     const unsigned long long fine_top = octave_top(est - (kWinOct - 1));   // (above 1.0 when est < kWinOct - 1: no gain lies there)
     const int lane = lane_id();
@@ -459,10 +466,8 @@ __global__ __launch_bounds__(kBig) void k_bisect_coarse(Src src, long long n, lo
     bool bad = false;
     for (long long t0 = base; t0 < end; t0 += kTile) {
         const long long tile_end = t0 + kTile < end ? t0 + kTile : end;
-        const unsigned long long n_u = (unsigned long long)(tile_end - t0);
-        // the tile's share of the budget, rounded up (budget < 2^52 and n_u <= 2^12: no overflow)
-        const unsigned long long share = ((unsigned long long)budget * n_u + (unsigned long long)n - 1ull) /
-                                         (unsigned long long)n;
+        // the tile's share of the budget (only the batch's last tile can be short)
+        const unsigned long long share = t0 + kTile <= n ? shares.tile : shares.last_tile;
         const unsigned long long need = share + (share >> 5) + 64ull;
         const long long pos = t0 + (long long)threadIdx.x * kItems;
         double a[kItems], b[kItems], s[kItems], g[kItems], lf[kItems], keep_g[kItems], keep_l[kItems];
@@ -742,16 +747,23 @@ struct SelectShared {
 // for the wide brackets that the coarse count falls back to), takes the window below it.
 __device__ __forceinline__ void move_bracket(SelectShared& sh, unsigned long long cj, unsigned long long mx,
                                              unsigned long long mn, long long budget) {
+    static_assert(kBins % kWave == 0 && kBins / kWave <= kBigWaves, "the tallies fill whole wavefronts");
+    constexpr int kTallyWaves = kBins / kWave;
+    // (the caller's barrier lies between the last change of the bracket and these reads; the
+    // barrier below between them and the next change)
     const unsigned long long lo = sh.lo;
     const long long start = sh.above;   // pairs above the bracket
     if (cj > (unsigned long long)budget) cj = (unsigned long long)budget;
-    __syncthreads();                                     // sh.red is free, the bracket has been read
-    const long long incl = wave_incl_scan<long long>((long long)cj);
-    if (lane_id() == kWave - 1) sh.red[wave_id()] = incl;
+    long long incl = 0;
+    if (wave_id() < kTallyWaves) {       // uniform per wavefront: the others hold zeros
+        incl = (long long)wave_incl_scan_u64(cj);
+        if (lane_id() == kWave - 1) sh.red[wave_id()] = incl;
+    }
     __syncthreads();
     long long before = start + incl - (long long)cj;     // pairs in higher intervals
     long long total = 0;
-    for (int i = 0; i < kBigWaves; ++i) {
+#pragma unroll
+    for (int i = 0; i < kTallyWaves; ++i) {
         if (i < wave_id()) before += sh.red[i];
         total += sh.red[i];
     }
@@ -819,21 +831,51 @@ __device__ __forceinline__ void list_append(SelectShared& sh, unsigned long long
 // prompts, caps that leave tiles short of their share) a wider bracket that is still correct
 // is taken and the narrowing passes do the rest.
 // ----------------------------------------------------------------------------------
-struct CoarseShared {
-    int s_max, s_min;
-    long long sum[2 + kWinOct * kSubBins];   // [0] above the range, [1] everything counted, then the intervals
+// One entry of the sums below: of the counts seen so far, t belongs to the lowest octave among
+// them (o; octaves are numbered downwards, so the largest number) and r to the octaves above it.
+struct LowestOctave { int o; long long t, r; };
+__device__ __forceinline__ LowestOctave join(const LowestOctave& x, const LowestOctave& y) {
+    LowestOctave z;
+    z.o = x.o > y.o ? x.o : y.o;
+    z.t = (x.o == z.o ? x.t : 0) + (y.o == z.o ? y.t : 0);
+    z.r = x.r + y.r + (x.o == z.o ? 0 : x.t) + (y.o == z.o ? 0 : y.t);
+    return z;
+}
+
+struct CoarseShared {   // what each wavefront found in its slots
+    int o[kBigWaves][kWinOct * kSubBins];
+    long long t[kBigWaves][kWinOct * kSubBins], r[kBigWaves][kWinOct * kSubBins];
+    long long tops[kWave];   // per row of 16 lanes of every wavefront
+    int smax[kWave], smin[kWave];
 };
 
+// The largest value of a wavefront, in every lane: rotations inside the rows of 16 lanes, then
+// the four rows' results as scalars.
+__device__ __forceinline__ int wave_max_i32(int v) {
+    int o = dpp_take<0x128, 0xf, 0xf>(v); v = o > v ? o : v;   // row_ror:8
+    o = dpp_take<0x124, 0xf, 0xf>(v); v = o > v ? o : v;       // row_ror:4
+    o = dpp_take<0x122, 0xf, 0xf>(v); v = o > v ? o : v;       // row_ror:2
+    o = dpp_take<0x121, 0xf, 0xf>(v); v = o > v ? o : v;       // row_ror:1
+    const int a = __builtin_amdgcn_readlane(v, 0), b = __builtin_amdgcn_readlane(v, 16);
+    const int c = __builtin_amdgcn_readlane(v, 32), d = __builtin_amdgcn_readlane(v, 48);
+    const int ab = a > b ? a : b, cd = c > d ? c : d;
+    return ab > cd ? ab : cd;
+}
+
+// Every thread takes one count of one slot at a time (a slot's counts are consecutive: coalesced
+// loads), always the same ring row w and interval q of the slots it visits, all loads of the
+// first kKeep rounds (everything up to 2^20 prompts) under way together.  Which octave a ring
+// row holds depends on where its tile stopped, and which octaves form the range depends on all
+// tiles: so a thread sums its counts per "lowest octave seen so far" (join), a wavefront joins
+// the four lanes that share (w, q) and leaves 16 such entries in LDS.  After a barrier the first
+// wavefront joins the 16 wavefronts' entries in the order of the range (lane j of each row of
+// 16: octave first + j / 4, interval j % 4) and finds the bracket by a prefix sum over 16 lanes.
+// One wavefront, because its fifteen neighbours would share its four vector units: the same
+// instructions sixteen times take four times as long as once, and a second barrier costs less.
 __device__ __forceinline__ void first_bracket(SelectShared& sh, CoarseShared& cs, long long tiles, long long budget,
                                               const CoarseSlot* __restrict__ slots) {
-    if (threadIdx.x == 0) { cs.s_max = 0; cs.s_min = INT_MAX; }
-    if (threadIdx.x < 2 + kWinOct * kSubBins) cs.sum[threadIdx.x] = 0;
-    // Every thread takes one count of one slot at a time (a slot's counts are consecutive:
-    // coalesced loads), always the same row and interval e of the slots it visits.  The first
-    // kKeep counts of a thread (all of them up to 2^20 prompts) are loaded together with their
-    // slots' stopping octaves and kept in registers, so that one round trip to memory serves
-    // both steps: the range of octaves, and the sums inside it.
     static_assert(kBig % (kWinOct * kSubBins) == 0 && kWave == 4 * kWinOct * kSubBins, "lanes that share an interval");
+    static_assert(kWinOct == 4 && kBigWaves == kWinOct * kSubBins, "one lane per wavefront's entry, ring of four octaves");
     constexpr int kKeep = 4;
     constexpr int kPerSlot = kWinOct * kSubBins;
     const long long counts = tiles * kPerSlot;
@@ -853,98 +895,88 @@ __device__ __forceinline__ void first_bracket(SelectShared& sh, CoarseShared& cs
             if (e == 0) kept_top[i] = (long long)slot->cum_top;
         }
     }
-    __syncthreads();   // cs is initialised
-    {
-        int smax = 0, smin = INT_MAX;
-#pragma unroll
-        for (int i = 0; i < kKeep; ++i) {
-            smax = kept_stop[i] > smax ? kept_stop[i] : smax;
-            if (!kept_done[i]) smin = kept_stop[i] < smin ? kept_stop[i] : smin;
-        }
-        for (long long u = (long long)kKeep * kBig / kPerSlot + threadIdx.x; u < tiles; u += kBig) {   // larger batches
-            const int stop = slots[u].stop;
-            smax = stop > smax ? stop : smax;
-            if (!slots[u].exhausted) smin = stop < smin ? stop : smin;
-        }
-#pragma unroll
-        for (int d = kWave / 2; d > 0; d >>= 1) {
-            const int om = __shfl_xor(smax, d, kWave), on = __shfl_xor(smin, d, kWave);
-            smax = om > smax ? om : smax;
-            smin = on < smin ? on : smin;
-        }
-        if (lane_id() == 0) {
-            if (smax != 0) atomicMax(&cs.s_max, smax);
-            if (smin != INT_MAX) atomicMin(&cs.s_min, smin);
-        }
-    }
-    __syncthreads();
-    const int s_max = cs.s_max;
-    const int s_min = cs.s_min == INT_MAX ? s_max : cs.s_min;   // no tile has gains left: everything is counted
-    const int first = s_max - (kWinOct - 1) > 0 ? s_max - (kWinOct - 1) : 0;   // first octave of the range
-    // What lies above the range and the grand total are summed per thread; the counts of the
-    // range are kept per octave of the range (the slots of one thread may have stopped at
-    // different octaves), added up over the four lanes of a wavefront that share e, and only
-    // then go to LDS: a few atomics per wavefront instead of one per count.
-    long long base = 0, known = 0;
-    long long part[kWinOct];
-#pragma unroll
-    for (int d = 0; d < kWinOct; ++d) part[d] = 0;
-    auto take = [&](long long v, long long top, int stop) {
+    LowestOctave acc{-1, 0, 0};
+    long long tops = 0;
+    int smax = 0, smin = INT_MAX;
+    auto take = [&](long long v, long long top, int stop, bool exhausted) {
+        if (stop < 0) return;
+        smax = stop > smax ? stop : smax;
+        if (!exhausted) smin = stop < smin ? stop : smin;
+        tops += top;
         const int oct = stop - ((stop - w) & (kWinOct - 1));   // the octave of the slot's row w
-        base += top;
-        known += top;
-        if (oct < 0) return;
-        known += v;
-        if (oct < first) base += v;
-        // oct - first is in [0, kWinOct - 1] for the rows of the range, because stop <= s_max
-#pragma unroll
-        for (int d = 0; d < kWinOct; ++d) part[d] += (oct - first == d) ? v : 0;
+        if (oct >= 0) acc = join(acc, LowestOctave{oct, v, 0});
     };
 #pragma unroll
-    for (int i = 0; i < kKeep; ++i)
-        if (kept_stop[i] >= 0) take(kept_v[i], kept_top[i], kept_stop[i]);
-    for (long long idx = (long long)kKeep * kBig + threadIdx.x; idx < counts; idx += kBig) {
+    for (int i = 0; i < kKeep; ++i) take(kept_v[i], kept_top[i], kept_stop[i], kept_done[i]);
+    for (long long idx = (long long)kKeep * kBig + threadIdx.x; idx < counts; idx += kBig) {   // larger batches
         const CoarseSlot* slot = slots + idx / kPerSlot;
-        take((long long)slot->cnt[w][q], e == 0 ? (long long)slot->cum_top : 0, slot->stop);
+        take((long long)slot->cnt[w][q], e == 0 ? (long long)slot->cum_top : 0, slot->stop, slot->exhausted != 0);
     }
-    base = wave_total_i64(base);
-    known = wave_total_i64(known);
 #pragma unroll
-    for (int d = 0; d < kWinOct; ++d) {
-        part[d] += __shfl_xor(part[d], 16, kWave);
-        part[d] += __shfl_xor(part[d], 32, kWave);
-        if (lane_id() < kPerSlot && part[d])
-            atomicAdd((unsigned long long*)&cs.sum[2 + d * kSubBins + q], (unsigned long long)part[d]);
+    for (int d = kPerSlot; d < kWave; d <<= 1) {
+        LowestOctave other;
+        other.o = __shfl_xor(acc.o, d, kWave);
+        other.t = __shfl_xor(acc.t, d, kWave);
+        other.r = __shfl_xor(acc.r, d, kWave);
+        acc = join(acc, other);
     }
-    if (lane_id() == 0) {
-        if (base) atomicAdd((unsigned long long*)&cs.sum[0], (unsigned long long)base);
-        if (known) atomicAdd((unsigned long long*)&cs.sum[1], (unsigned long long)known);
+    if (lane_id() < kPerSlot) {
+        cs.o[wave_id()][e] = acc.o; cs.t[wave_id()][e] = acc.t; cs.r[wave_id()][e] = acc.r;
+    }
+    // the 16 lanes of a row see the same slots: the row's first lane has its sum of cum_top and
+    // its extremes of the stopping octaves
+    if (e == 0) {
+        const int row = wave_id() * (kWave / kPerSlot) + lane_id() / kPerSlot;
+        cs.tops[row] = tops; cs.smax[row] = smax; cs.smin[row] = smin;
     }
     __syncthreads();
-    if (threadIdx.x == 0) {
+    if (wave_id() == 0) {
+        const int j = lane_id() & (kPerSlot - 1), part = lane_id() / kPerSlot;
+        const int s_max = wave_max_i32(cs.smax[lane_id()]);
+        const int min_seen = -wave_max_i32(-cs.smin[lane_id()]);
+        const int s_min = min_seen == INT_MAX ? s_max : min_seen;   // no tile has gains left: everything is counted
+        const int first = s_max - (kWinOct - 1) > 0 ? s_max - (kWinOct - 1) : 0;   // first octave of the range
+        const long long tops_all = wave_total_i64(cs.tops[lane_id()]);
+        const int oct_j = first + j / kSubBins;
+        const int e_j = (oct_j & (kWinOct - 1)) * kSubBins + (j % kSubBins);   // the ring row that can hold that octave
+        // each row of 16 lanes joins four wavefronts' entries, then the four rows are joined
+        LowestOctave all{-1, 0, 0};
+#pragma unroll
+        for (int v = 0; v < kBigWaves / 4; ++v) {
+            const int from = part * (kBigWaves / 4) + v;
+            all = join(all, LowestOctave{cs.o[from][e_j], cs.t[from][e_j], cs.r[from][e_j]});
+        }
+#pragma unroll
+        for (int d = kPerSlot; d < kWave; d <<= 1) {
+            LowestOctave other;
+            other.o = __shfl_xor(all.o, d, kWave);
+            other.t = __shfl_xor(all.t, d, kWave);
+            other.r = __shfl_xor(all.r, d, kWave);
+            all = join(all, other);
+        }
+        const bool low = lane_id() < kPerSlot;             // one copy of the 16 entries
+        // (an entry's lowest octave is the range's octave oct_j or lies a multiple of four above it)
+        const bool in_range = all.o == oct_j;
+        const long long c = (low && in_range) ? all.t : 0;
+        const long long all_above = tops_all + wave_total_i64(low ? all.r + (in_range ? 0 : all.t) : 0);
+        const long long known = all_above + wave_total_i64(c);
+        const long long incl = wave_incl_scan_i64(c);
         unsigned long long lo = 0ull, hi = kOne;
         long long above = 0, inside = -1;
-        const long long all_above = cs.sum[0];
-        bool found = false;
         if (all_above >= budget) {
-            lo = octave_top(first);          // count_gt(lo) >= budget already: tau lies above the range
+            lo = octave_top(first);              // count_gt(lo) >= budget already: tau lies above the range
         } else {
-            long long cum = all_above;
-            for (int o = first; o <= s_min && !found; ++o) {
-                for (int q = 0; q < kSubBins; ++q) {
-                    const long long c = cs.sum[2 + (o - first) * kSubBins + q];
-                    if (cum + c >= budget) {
-                        hi = octave_top(o) - (unsigned long long)q * (kOctave / kSubBins);
-                        lo = hi - kOctave / kSubBins;
-                        above = cum;
-                        inside = c;
-                        found = true;
-                        break;
-                    }
-                    cum += c;
-                }
-            }
-            if (!found) {
+            // octaves up to s_min were walked completely by every tile that has gains left
+            const unsigned long long reach = __ballot(low && oct_j <= s_min && all_above + incl >= budget);
+            if (reach) {
+                const int f = __builtin_ctzll(reach);
+                const long long cf = (long long)read_lane_u64((unsigned long long)c, f);
+                const long long upto = (long long)read_lane_u64((unsigned long long)incl, f);
+                hi = octave_top(first + f / kSubBins) - (unsigned long long)(f % kSubBins) * (kOctave / kSubBins);
+                lo = hi - kOctave / kSubBins;
+                above = all_above + upto - cf;
+                inside = cf;
+            } else {
                 // The range ends above tau.  When it is not empty, the count above its lower end is
                 // complete and the bracket starts there; when it is empty (some tile stopped more
                 // than kWinOct octaves above another: very different prompts), nothing below 1 is.
@@ -952,13 +984,16 @@ __device__ __forceinline__ void first_bracket(SelectShared& sh, CoarseShared& cs
                 // tiles' counts do not add up to the budget (caps), to zero.
                 if (s_min >= first) {
                     hi = octave_top(s_min + 1);
-                    above = cum;
+                    above = all_above +
+                            (long long)read_lane_u64((unsigned long long)incl, (s_min - first) * kSubBins + kSubBins - 1);
                 }
-                lo = cs.sum[1] >= budget ? octave_top(s_max) - kOctave : 0ull;
+                lo = known >= budget ? octave_top(s_max) - kOctave : 0ull;
             }
         }
-        sh.lo = lo; sh.hi = hi; sh.above = above; sh.inside = inside;
-        sh.done = 0; sh.hit = 0; sh.list_n = 0;
+        if (lane_id() == 0) {
+            sh.lo = lo; sh.hi = hi; sh.above = above; sh.inside = inside;
+            sh.done = 0; sh.hit = 0; sh.list_n = 0;
+        }
     }
     __syncthreads();
 }
@@ -993,17 +1028,20 @@ __global__ __launch_bounds__(kBig) void k_bisect_pass(Src src, long long n, long
         // the pass before set the gains of its (wider) bracket aside and all of them fitted
         from_lists = (hdr->slot[kPass & 1].flags & kFlagCollected) != 0 && hdr->lists_ok != 0;
     }
-    const bool collect = from_lists || (sh.inside >= 0 && sh.inside <= kCollectMax);
-    const bool done = sh.done != 0;
+    const unsigned long long b_lo = sh.lo, b_hi = sh.hi;   // the pass's bracket, the pairs above it and inside it
+    const long long b_above = sh.above, b_inside = sh.inside;
+    const int b_done = sh.done;
+    const bool collect = from_lists || (b_inside >= 0 && b_inside <= kCollectMax);
+    const bool done = b_done != 0;
     if (blockIdx.x == 0 && threadIdx.x == 0) {   // for the next kernel
         Bracket* out = &hdr->slot[(kPass + 1) & 1];
-        out->lo = sh.lo; out->hi = sh.hi; out->above = (unsigned long long)sh.above;
-        out->done = (unsigned)sh.done;
+        out->lo = b_lo; out->hi = b_hi; out->above = (unsigned long long)b_above;
+        out->done = (unsigned)b_done;
         out->flags = done ? 0u : ((kPass == 0 ? kFlagPending : 0u) | (collect ? kFlagCollected : 0u));
     }
     if (done) return;   // uniform over the grid: every workgroup moved the same bracket
     constexpr bool kTally = kPass == 0;
-    const unsigned long long lo = sh.lo, hi = sh.hi;
+    const unsigned long long lo = b_lo, hi = b_hi;
     const int shift = bracket_shift(lo, hi);
     if (kTally && threadIdx.x < kBins) { sh.bins.cnt[threadIdx.x] = 0; sh.bins.vmax[threadIdx.x] = 0; sh.bins.vmin_inv[threadIdx.x] = 0; }
     unsigned long long* mine = lists + (long long)blockIdx.x * kListCap;
@@ -1164,6 +1202,8 @@ __device__ unsigned long long finish_search(SelectShared& sh, const Src& src, lo
                                             const unsigned long long* __restrict__ lists,
                                             const int* __restrict__ list_count, bool* ok) {
     const Bracket* in = &hdr->slot[0];   // written by pass 1
+    // (the tallies start from zero; the barriers below lie between this and the first pass)
+    if (threadIdx.x < kBins) { sh.bins.cnt[threadIdx.x] = 0; sh.bins.vmax[threadIdx.x] = 0; sh.bins.vmin_inv[threadIdx.x] = 0; }
     if (threadIdx.x == 0) {
         sh.lo = in->lo; sh.hi = in->hi; sh.above = (long long)in->above; sh.done = (int)in->done;
         sh.hit = 0; sh.inside = -1; sh.list_n = 0;
@@ -1212,8 +1252,6 @@ __device__ unsigned long long finish_search(SelectShared& sh, const Src& src, lo
         if (sh.done) break;   // uniform: written before the barrier that ends move_bracket
         const unsigned long long lo = sh.lo, hi = sh.hi;
         const int shift = bracket_shift(lo, hi);
-        if (threadIdx.x < kBins) { sh.bins.cnt[threadIdx.x] = 0; sh.bins.vmax[threadIdx.x] = 0; sh.bins.vmin_inv[threadIdx.x] = 0; }
-        __syncthreads();
         if (held) {
 #pragma unroll
             for (int q = 0; q < kHeld; ++q)
@@ -1260,10 +1298,11 @@ __device__ unsigned long long finish_search(SelectShared& sh, const Src& src, lo
         __syncthreads();
         const int j = kBins - 1 - (int)threadIdx.x;   // thread 0 owns the top interval
         unsigned long long cj = 0, mx = 0, mn = 0;
-        if (threadIdx.x < kBins) {
+        if (threadIdx.x < kBins) {   // (and cleared for the next pass by the thread that read them)
             cj = sh.bins.cnt[j];
             mx = sh.bins.vmax[j];
             mn = ~sh.bins.vmin_inv[j];
+            sh.bins.cnt[j] = 0; sh.bins.vmax[j] = 0; sh.bins.vmin_inv[j] = 0;
         }
         move_bracket(sh, cj, mx, mn, budget);
     }
@@ -1277,40 +1316,7 @@ __device__ unsigned long long finish_search(SelectShared& sh, const Src& src, lo
 // flag go to delta[i] (flag in bit 31); util[i] gets U_i = 1 - E_i(k_i), and a tied prompt's
 // 1 - E_i(k_i + 1) goes where its walk state was; per-workgroup sums to block_ksum / block_tied.  kItems prompts per thread, their walks in lockstep.
 // ----------------------------------------------------------------------------------
-// The survival products E_i(k_i) of one wavefront's 256 prompts, pooled like pooled_walk (the
-// number of steps k_i is known here): a lane takes a prompt, multiplies and divides k_i times,
-// leaves the product in place of the prompt's beta, and takes the next prompt.  LDS arrays of
-// the wavefront: beta (in) / E (out), alpha + beta, k.
-__device__ __forceinline__ void pooled_survival(double* __restrict__ pool_b, const double* __restrict__ pool_s,
-                                                const int* __restrict__ pool_k) {
-    constexpr int kPool = kWave * kItems;
-    int next = kWave;
-    int t = lane_id();
-    bool have = true;
-    double b = pool_b[t], s = pool_s[t], e = 1.0, j = 0.0;
-    double k = (double)pool_k[t];
-    while (__ballot(have)) {
-        if (have && j < k) {
-            e = surv_next(e, b, s, j);
-            j += 1.0;
-        }
-        const bool through = have && !(j < k);
-        const unsigned long long m = __ballot(through);
-        if (m) {   // uniform
-            if (through) {
-                pool_b[t] = e;
-                t = next + lanes_below(m);
-                have = t < kPool;
-                if (have) { b = pool_b[t]; s = pool_s[t]; k = (double)pool_k[t]; }
-                e = 1.0;
-                j = 0.0;
-            }
-            next += __popcll(m);
-        }
-    }
-}
-
-template <class Src, bool kDeep>
+template <class Src>
 __global__ __launch_bounds__(kBig) void k_bisect_finalize(Src src, long long n, long long chunk, long long budget,
                                                           long long limit, int depth_capped, int nb,
                                                           AllocHeader* __restrict__ hdr,
@@ -1324,7 +1330,6 @@ __global__ __launch_bounds__(kBig) void k_bisect_finalize(Src src, long long n, 
     long long (&s_red)[2][kBigWaves] = *reinterpret_cast<long long (*)[2][kBigWaves]>(&sh.bins.cnt[0]);
     const long long base = (long long)blockIdx.x * chunk;
     const long long end = base + chunk < n ? base + chunk : n;
-    const bool uneven = kDeep && budget > 0 && hdr->uneven == 2u;   // very uneven (written by the coarse count of this call)
     // (the loads of the first tile are under way while the search is finished)
     Fetched<Src> first_tile;
     WalkStates first_states;
@@ -1377,102 +1382,14 @@ __global__ __launch_bounds__(kBig) void k_bisect_finalize(Src src, long long n, 
                 any |= act;
             }
         } while (any);
-        // ... the survival product takes its k steps from the start: pooled over the wavefront
-        // where the depth estimate found prompts of very different depth, else in lockstep
-        bool lockstep = true;
-        if constexpr (kDeep) if (util && uneven) {
-            __shared__ double s_pool_b[kTile], s_pool_s[kTile];
-            __shared__ int s_pool_k[kTile];
-            lockstep = false;
+        // ... and the survival product follows from the gain the walk ended with, without a walk of
+        // its own: App. A gives E(l) = B(alpha, beta + l) / B(alpha, beta) and M(l) =
+        // B(alpha + 1, beta + l) / B(alpha, beta), whose ratio is alpha / (alpha + beta + l), so
+        // E(k) = M(k) (alpha + beta + k) / alpha.  Two roundings on top of the gain's own (a few
+        // 1e-16 of E per step, like the product's); E(0) = 1 exactly.
+        if (util) {
 #pragma unroll
-            for (int j = 0; j < kItems; ++j) {
-                s_pool_b[threadIdx.x * kItems + j] = b[j];
-                s_pool_s[threadIdx.x * kItems + j] = s[j];
-                s_pool_k[threadIdx.x * kItems + j] = alive[j] ? (int)lf[j] : 0;
-            }
-            __syncthreads();
-            const int at = wave_id() * (kWave * kItems);
-            pooled_survival(s_pool_b + at, s_pool_s + at, s_pool_k + at);
-            __syncthreads();
-#pragma unroll
-            for (int j = 0; j < kItems; ++j) e[j] = s_pool_b[threadIdx.x * kItems + j];
-            __syncthreads();   // the arrays are reused by the next tile
-        }
-        if constexpr (kDeep) if (util && lockstep) {
-            // deep but not very uneven: in lockstep, the products that still have steps to take
-            // regrouped as they thin out (regroup_plan; k is known, so is the number of rounds
-            // left).  The walk works on copies: the prompts' own values stay with their lanes.
-            // (Not for shallow budgets: measured, no gain at a mean depth of 8 and 2 us lost at 4.)
-            lockstep = false;
-            __shared__ WaveStage s_stage[kBigWaves];
-            WaveStage& stage = s_stage[wave_id()];
-            double wb[kItems], ws[kItems], wk[kItems], le[kItems];
-            int home[kItems];
-            int deepest = 0;
-#pragma unroll
-            for (int j = 0; j < kItems; ++j) {
-                wb[j] = b[j];
-                ws[j] = s[j];
-                wk[j] = alive[j] ? lf[j] : 0.0;
-                le[j] = 0.0;
-                home[j] = j * kWave + lane_id();
-                deepest = (int)wk[j] > deepest ? (int)wk[j] : deepest;
-            }
-#pragma unroll
-            for (int d = kWave / 2; d > 0; d >>= 1) {
-                const int other = __shfl_xor(deepest, d, kWave);
-                deepest = other > deepest ? other : deepest;
-            }
-            int in_use = kItems;
-            for (int round = 0;; ++round) {
-                bool act[kItems];
-                int total = 0;
-#pragma unroll
-                for (int j = 0; j < kItems; ++j) {
-                    act[j] = le[j] < wk[j];
-                    total += __popcll(__ballot(act[j]));
-                }
-                if (total == 0) break;                      // uniform over the wavefront
-                const int fewer = in_use - (total + kWave - 1) / kWave;
-                if (fewer > 0 && fewer * (deepest - round) >= kRegroupGainSurvival) {   // uniform
-                    int dest[kItems];
-                    regroup_plan(act, total, dest);
-                    regroup(stage, dest, wb);
-                    regroup(stage, dest, ws);
-                    regroup(stage, dest, wk);
-                    regroup(stage, dest, le);
-                    regroup(stage, dest, e);
-                    regroup(stage, dest, home);
-                    in_use = (total + kWave - 1) / kWave;
-#pragma unroll
-                    for (int j = 0; j < kItems; ++j) act[j] = j * kWave + lane_id() < total;
-                }
-#pragma unroll
-                for (int j = 0; j < kItems; ++j) {
-                    if (act[j]) {
-                        e[j] = surv_next(e[j], wb[j], ws[j], le[j]);
-                        le[j] += 1.0;
-                    }
-                }
-            }
-            if (in_use != kItems) regroup(stage, home, e);   // uniform: back to the prompts' lanes
-        }
-        if (util && lockstep) {
-            double le[kItems];
-#pragma unroll
-            for (int j = 0; j < kItems; ++j) le[j] = 0.0;
-            do {
-                any = false;
-#pragma unroll
-                for (int j = 0; j < kItems; ++j) {
-                    const bool act = alive[j] && le[j] < lf[j];
-                    if (act) {
-                        e[j] = surv_next(e[j], b[j], s[j], le[j]);
-                        le[j] += 1.0;
-                    }
-                    any |= act;
-                }
-            } while (any);
+            for (int j = 0; j < kItems; ++j) e[j] = lf[j] > 0.0 ? (g[j] * (s[j] + lf[j])) / a[j] : 1.0;
         }
         // what is final already is stored as such: k and U = 1 - E(k); a tied prompt leaves k
         // with the flag, and what its utility becomes if the tie pass gives it a unit,
@@ -1526,9 +1443,10 @@ __global__ __launch_bounds__(kBig) void k_bisect_write(Src src, long long n, int
                                                        hora_alloc_summary* __restrict__ summary,
                                                        int32_t* dev_status) {
     __shared__ EmitShared s_emit;
-    __shared__ long long s_pre[4][kBigWaves];
-    {
-        static_assert(kMaxBlocks <= kBig, "one thread per workgroup sum");
+    constexpr int kSumWaves = kMaxBlocks / kWave;   // the wavefronts that hold the workgroups' sums
+    __shared__ long long s_pre[4][kSumWaves];
+    if (wave_id() < kSumWaves) {   // (the other wavefronts would add up zeros on the same vector units)
+        static_assert(kMaxBlocks <= kBig && kMaxBlocks % kWave == 0, "one thread per workgroup sum");
         const int t = (int)threadIdx.x;
         const long long kv = t < nb ? block_ksum[t] : 0, tv = t < nb ? block_tied[t] : 0;
         const long long k_all = wave_total_i64(kv), t_all = wave_total_i64(tv);
@@ -1542,7 +1460,7 @@ __global__ __launch_bounds__(kBig) void k_bisect_write(Src src, long long n, int
     __syncthreads();
     long long k_all = 0, t_all = 0, k_bef = 0, t_bef = 0;
 #pragma unroll
-    for (int w = 0; w < kBigWaves; ++w) {
+    for (int w = 0; w < kSumWaves; ++w) {
         k_all += s_pre[0][w]; t_all += s_pre[1][w]; k_bef += s_pre[2][w]; t_bef += s_pre[3][w];
     }
     const long long r = budget - k_all;
@@ -1567,17 +1485,20 @@ __global__ __launch_bounds__(kBig) void k_bisect_write(Src src, long long n, int
         load_items_i32(delta, pos, end, d_vec, 0, raw);
         int kk[kItems], td[kItems], dd[kItems];
         bool win[kItems];
+        double with_unit[kItems];   // a tied prompt's utility if it gets a unit: on its way during the tie pass
 #pragma unroll
         for (int j = 0; j < kItems; ++j) {
             kk[j] = (int)((unsigned)raw[j] & ~kTiedBit);
             td[j] = ((unsigned)raw[j] & kTiedBit) ? 1 : 0;
+            with_unit[j] = 0.0;
+            if (util && td[j]) with_unit[j] = win_util[pos + j];   // (tied: a prompt below `end`)
         }
         emit_tile<kOff, true>(parity, pos, end, n, g0, r, kk, td, carry, dd, win, delta, group_off, d_vec, o_vec,
                               &s_emit);
         if (util) {
 #pragma unroll
             for (int j = 0; j < kItems; ++j)
-                if (win[j]) util[pos + j] = win_util[pos + j];   // (a tied prompt below `end` that gets a unit)
+                if (win[j]) util[pos + j] = with_unit[j];   // (a tied prompt that gets a unit)
         }
     }
 }
@@ -1609,12 +1530,20 @@ static int run_bisect(const Src& src, const CommonArgs& a, const Plan& p, const 
     // mean walk of more than 32 steps; the mean is budget / n)
     const bool deep = a.budget > kDeepRatio * n;
     if (a.budget > 0) {
+        // shares of the budget, rounded up (budget < 2^52, at most 2^12 prompts: no overflow)
+        const unsigned long long b_u = (unsigned long long)a.budget, n_u = (unsigned long long)n;
+        const unsigned long long n_last = n_u - (unsigned long long)(tiles - 1) * kTile;
+        BudgetShares shares;
+        shares.sample = (b_u * kEstSamples + n_u - 1ull) / n_u;
+        shares.per_prompt = b_u / n_u;
+        shares.tile = (b_u * kTile + n_u - 1ull) / n_u;
+        shares.last_tile = (b_u * n_last + n_u - 1ull) / n_u;
         if (deep)
-            hipLaunchKernelGGL((k_bisect_coarse<Src, true>), dim3(p.nb), dim3(kBig), 0, a.stream, src, n,
-                               (long long)a.budget, limit, p.chunk, w.coarse, w.header, w.ck_g, w.ck_l, a.dev_status);
+            hipLaunchKernelGGL((k_bisect_coarse<Src, true>), dim3(p.nb), dim3(kBig), 0, a.stream, src, n, shares,
+                               limit, p.chunk, w.coarse, w.header, w.ck_g, w.ck_l, a.dev_status);
         else
-            hipLaunchKernelGGL((k_bisect_coarse<Src, false>), dim3(p.nb), dim3(kBig), 0, a.stream, src, n,
-                               (long long)a.budget, limit, p.chunk, w.coarse, w.header, w.ck_g, w.ck_l, a.dev_status);
+            hipLaunchKernelGGL((k_bisect_coarse<Src, false>), dim3(p.nb), dim3(kBig), 0, a.stream, src, n, shares,
+                               limit, p.chunk, w.coarse, w.header, w.ck_g, w.ck_l, a.dev_status);
         hipLaunchKernelGGL((k_bisect_pass<Src, 0>), dim3(p.nb), dim3(kBig), 0, a.stream, src, n, (long long)a.budget,
                            limit, p.chunk, tiles, (const CoarseSlot*)w.coarse, w.header, w.bins, w.lists,
                            w.list_count, w.ck_g, w.ck_l);
@@ -1627,14 +1556,10 @@ static int run_bisect(const Src& src, const CommonArgs& a, const Plan& p, const 
     // (without a budget there was no search and no walk state)
     double* state_g = a.budget > 0 ? w.ck_g : nullptr;
     const int32_t* state_l = a.budget > 0 ? w.ck_l : nullptr;
-#define HORA_LAUNCH_BISECT_FINALIZE(DEEP)                                                                      \
-    hipLaunchKernelGGL((k_bisect_finalize<Src, DEEP>), dim3(p.nb), dim3(kBig), 0, a.stream, src, n, p.chunk,     \
-                       (long long)a.budget, limit, depth_capped, p.nb, w.header,                                \
-                       (const unsigned long long*)w.lists, (const int*)w.list_count, state_g, state_l, a.delta, \
-                       a.util, w.block_ksum, w.block_tied, a.dev_status)
-    if (deep) HORA_LAUNCH_BISECT_FINALIZE(true);
-    else HORA_LAUNCH_BISECT_FINALIZE(false);
-#undef HORA_LAUNCH_BISECT_FINALIZE
+    hipLaunchKernelGGL((k_bisect_finalize<Src>), dim3(p.nb), dim3(kBig), 0, a.stream, src, n, p.chunk,
+                       (long long)a.budget, limit, depth_capped, p.nb, w.header, (const unsigned long long*)w.lists,
+                       (const int*)w.list_count, state_g, state_l, a.delta, a.util, w.block_ksum, w.block_tied,
+                       a.dev_status);
     const int mode = a.group_off ? (a.off_t == HORA_I32 ? 1 : 2) : 0;
 #define HORA_LAUNCH_BISECT_WRITE(M)                                                                       \
     hipLaunchKernelGGL((k_bisect_write<Src, M>), dim3(p.nb), dim3(kBig), 0, a.stream, src, n, (int)a.g0,  \

@@ -78,6 +78,15 @@ __device__ __forceinline__ long long wave_incl_scan_i64(long long v) {
     return (long long)lo + ((long long)hi << 22);
 }
 
+// Inclusive scan of any 64-bit values whose sums fit 64 bits, as three 32-bit scans (pieces of
+// 22, 21 and 21 bits: a piece's sum over 64 lanes stays below 2^28).
+__device__ __forceinline__ unsigned long long wave_incl_scan_u64(unsigned long long v) {
+    const unsigned lo = (unsigned)wave_incl_scan_i32((int)(v & 0x3fffffull));
+    const unsigned mid = (unsigned)wave_incl_scan_i32((int)((v >> 22) & 0x1fffffull));
+    const unsigned hi = (unsigned)wave_incl_scan_i32((int)(v >> 43));
+    return (unsigned long long)lo + ((unsigned long long)mid << 22) + ((unsigned long long)hi << 43);
+}
+
 __device__ __forceinline__ int wave_last_i32(int v) { return __builtin_amdgcn_readlane(v, kWave - 1); }
 
 __device__ __forceinline__ long long wave_total_i64(long long v) {   // same range as the scan
