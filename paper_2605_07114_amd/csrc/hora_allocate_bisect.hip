@@ -236,8 +236,10 @@ __device__ __forceinline__ void estimate_depth(const Src& src, long long n, cons
     const unsigned long long need = want + (want >> 3) + 16ull;
     const unsigned long long sure = want - (want >> 3);
     const unsigned long long ratio = shares.per_prompt;
-    const int lumped = ratio >= 2ull ? 63 - __clzll((long long)ratio) : 0;   // octaves 0 .. lumped - 1 lie above n / budget
-    int o = lumped > 0 ? lumped - 1 : 0;
+    // A prompt's gains add up to less than 1, so fewer than 1 / t of them exceed t, and tau <= n / budget
+    // <= 2^-lumped: octaves 0 .. lumped - 1 lie above tau and are counted together with octave `lumped`.
+    const int lumped = ratio >= 2ull ? 63 - __clzll((long long)ratio) : 0;
+    int o = lumped;
     const int first = o;
     unsigned long long cum = 0ull;      // the sample's count at the bottom of octave o (the same in every thread)
     unsigned long long before = 0ull;   // ... and of the octave above it
