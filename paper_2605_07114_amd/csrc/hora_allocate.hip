@@ -147,7 +147,19 @@ struct ClassSolution {      // LDS
     int tied[kMaxClasses];
     double u0[kMaxClasses];   // U_c(k_c)
     double u1[kMaxClasses];   // U_c(k_c + 1)
+    long long tied_before;    // tied prompts in the workgroups before this one
+    long long units_before;   // sum of k over the prompts of the workgroups before this one
 };
+
+// What the workgroups before this one hold, from the per-class counts of their prompts: run by
+// the first wavefront (lane c: class c with its k and tied flag; other lanes pass zeros) at the
+// end of a solver, so that the sixteen wavefronts do not each add up the same numbers.
+__device__ __forceinline__ void sums_before(ClassSolution* sol, const long long* s_before, bool has, int k, bool tied) {
+    const long long bef = has ? s_before[lane_id()] : 0;
+    const long long tb = wave_total_i64(tied ? bef : 0);
+    const long long ub = wave_total_i64(bef * k);
+    if (lane_id() == 0) { sol->tied_before = tb; sol->units_before = ub; }
+}
 
 // #{l : row[l] > v} for a decreasing row of `row_len` (power of two) entries whose last
 // entry is not above v.
@@ -159,8 +171,8 @@ __device__ __forceinline__ int row_count_above(const double* row, int row_len, u
 }
 
 __device__ void solve_by_table(int nc, int row_len, int len, bool rows_end_at_cap, long long budget,
-                               const long long* s_n, const double* s_gain, const double* s_surv,
-                               unsigned short* s_pair, ClassSolution* sol) {
+                               const long long* s_n, const long long* s_before, const double* s_gain,
+                               const double* s_surv, unsigned short* s_pair, ClassSolution* sol) {
     if (threadIdx.x == 0) sol->found = 0;
     __syncthreads();
     const int row_shift = __ffs(row_len) - 1;
@@ -202,14 +214,21 @@ __device__ void solve_by_table(int nc, int row_len, int len, bool rows_end_at_ca
         }
         __syncthreads();
         // the per-class results are at hand in the winning entry's pairs: one thread per class
-        if (sol->found && threadIdx.x < (unsigned)nc) {
-            const int cls = (int)threadIdx.x;
-            const int pr = s_pair[sol->win * nc + cls];
-            const int pos = pr & 0x7fff;
-            sol->k[cls] = pos;
-            sol->tied[cls] = (pr & 0x8000) ? 1 : 0;
-            sol->u0[cls] = 1.0 - s_surv[cls * row_len + pos];
-            sol->u1[cls] = 1.0 - s_surv[cls * row_len + (pos + 1 < row_len ? pos + 1 : pos)];
+        if (wave_id() == 0) {
+            const int cls = lane_id();
+            const bool has = sol->found && cls < nc;
+            int pos = 0;
+            bool tied = false;
+            if (has) {
+                const int pr = s_pair[sol->win * nc + cls];
+                pos = pr & 0x7fff;
+                tied = (pr & 0x8000) != 0;
+                sol->k[cls] = pos;
+                sol->tied[cls] = tied ? 1 : 0;
+                sol->u0[cls] = 1.0 - s_surv[cls * row_len + pos];
+                sol->u1[cls] = 1.0 - s_surv[cls * row_len + (pos + 1 < row_len ? pos + 1 : pos)];
+            }
+            sums_before(sol, s_before, has, pos, tied);
         }
         __syncthreads();
         return;
@@ -251,14 +270,21 @@ __device__ void solve_by_table(int nc, int row_len, int len, bool rows_end_at_ca
         }
     }
     __syncthreads();
-    if (sol->found && threadIdx.x < (unsigned)nc) {
-        const int c = (int)threadIdx.x;
-        const double* row = s_gain + c * row_len;
-        const int cnt = row_count_above(row, row_len, sol->tau_bits);
-        sol->k[c] = cnt;
-        sol->tied[c] = gain_bits(row[cnt]) == sol->tau_bits ? 1 : 0;
-        sol->u0[c] = 1.0 - s_surv[c * row_len + cnt];
-        sol->u1[c] = 1.0 - s_surv[c * row_len + (cnt + 1 < row_len ? cnt + 1 : cnt)];
+    if (wave_id() == 0) {
+        const int c = lane_id();
+        const bool has = sol->found && c < nc;
+        int cnt = 0;
+        bool tied = false;
+        if (has) {
+            const double* row = s_gain + c * row_len;
+            cnt = row_count_above(row, row_len, sol->tau_bits);
+            tied = gain_bits(row[cnt]) == sol->tau_bits;
+            sol->k[c] = cnt;
+            sol->tied[c] = tied ? 1 : 0;
+            sol->u0[c] = 1.0 - s_surv[c * row_len + cnt];
+            sol->u1[c] = 1.0 - s_surv[c * row_len + (cnt + 1 < row_len ? cnt + 1 : cnt)];
+        }
+        sums_before(sol, s_before, has, cnt, tied);
     }
     __syncthreads();
 }
@@ -271,7 +297,8 @@ __device__ void solve_by_table(int nc, int row_len, int len, bool rows_end_at_ca
 // Alg. 1's greedy loop run on classes: prompts of one class have identical sequences, so
 // the greedy hands them their l-th unit in one uninterrupted run.
 __device__ void solve_by_greedy(int g0, double alpha0, double beta0, long long cap_eff, bool depth_capped,
-                                long long budget, const long long* s_n, ClassSolution* sol, int32_t* dev_status) {
+                                long long budget, const long long* s_n, const long long* s_before,
+                                ClassSolution* sol, int32_t* dev_status) {
     if (wave_id() == 0) {
         const int nc = g0 + 1;
         const int lane = lane_id();
@@ -325,6 +352,7 @@ __device__ void solve_by_greedy(int g0, double alpha0, double beta0, long long c
         sol->tied[lane] = (has && tied) ? 1 : 0;
         sol->u0[lane] = 1.0 - e;
         sol->u1[lane] = 1.0 - surv_next(e, b, s, lf);
+        sums_before(sol, s_before, has, has ? (int)k : 0, has && tied);
         if (lane == 0) {
             sol->tau_bits = tau_bits;
             sol->r = tie_prompts > 0 ? remaining : 0;
@@ -342,7 +370,8 @@ __device__ void solve_by_greedy(int g0, double alpha0, double beta0, long long c
 // c_i = 0 are; the split inside the eligible set is even (the paper does not say), and a
 // batch without such a prompt falls back to uniform.
 __device__ void solve_by_rule(int rule, int g0, double alpha0, double beta0, long long cap_eff, bool depth_capped,
-                              long long budget, const long long* s_n, ClassSolution* sol, int32_t* dev_status) {
+                              long long budget, const long long* s_n, const long long* s_before, ClassSolution* sol,
+                              int32_t* dev_status) {
     if (wave_id() == 0) {
         const int nc = g0 + 1;
         const int lane = lane_id();
@@ -373,6 +402,7 @@ __device__ void solve_by_rule(int rule, int g0, double alpha0, double beta0, lon
         sol->tied[lane] = mine ? 1 : 0;
         sol->u0[lane] = 1.0 - e;
         sol->u1[lane] = 1.0 - surv_next(e, b, s, lf);
+        sums_before(sol, s_before, has, (int)k, mine);
         if (lane == 0) {
             sol->tau_bits = 0ull;
             sol->r = rest;
@@ -479,11 +509,11 @@ __global__ __launch_bounds__(kBig) void k_class_write(const int32_t* __restrict_
     __syncthreads();
 
     if (budget > 0 && rule != 0) {
-        solve_by_rule(rule, g0, alpha0, beta0, cap_eff, depth_capped, budget, s_n, &s_sol, dev_status);
+        solve_by_rule(rule, g0, alpha0, beta0, cap_eff, depth_capped, budget, s_n, s_before, &s_sol, dev_status);
     } else if (budget > 0) {
-        solve_by_table(nc, row_len, len, rows_end_at_cap, budget, s_n, s_gain, s_surv, s_pair, &s_sol);
+        solve_by_table(nc, row_len, len, rows_end_at_cap, budget, s_n, s_before, s_gain, s_surv, s_pair, &s_sol);
         if (!s_sol.found)
-            solve_by_greedy(g0, alpha0, beta0, cap_eff, depth_capped, budget, s_n, &s_sol, dev_status);
+            solve_by_greedy(g0, alpha0, beta0, cap_eff, depth_capped, budget, s_n, s_before, &s_sol, dev_status);
     } else {
         if (threadIdx.x < kMaxClasses) {
             s_sol.k[threadIdx.x] = 0;
@@ -491,7 +521,10 @@ __global__ __launch_bounds__(kBig) void k_class_write(const int32_t* __restrict_
             s_sol.u0[threadIdx.x] = 0.0;
             s_sol.u1[threadIdx.x] = 0.0;
         }
-        if (threadIdx.x == 0) { s_sol.tau_bits = 0; s_sol.r = 0; s_sol.tie_prompts = 0; s_sol.found = 1; }
+        if (threadIdx.x == 0) {
+            s_sol.tau_bits = 0; s_sol.r = 0; s_sol.tie_prompts = 0; s_sol.found = 1;
+            s_sol.tied_before = 0; s_sol.units_before = 0;
+        }
         __syncthreads();
     }
     const long long r = s_sol.r;
@@ -502,14 +535,7 @@ __global__ __launch_bounds__(kBig) void k_class_write(const int32_t* __restrict_
         summary->tie_prompts = s_sol.tie_prompts;
     }
 
-    // what the workgroups before this one hold: lane c takes class c, the wavefront adds up
-    long long tied_before = 0, units_before = 0;
-    if (lane < nc) {
-        const long long bef = s_before[lane];
-        tied_before = s_sol.tied[lane] ? bef : 0;
-        units_before = bef * s_sol.k[lane];
-    }
-    EmitCarry carry = {wave_total_i64(tied_before), wave_total_i64(units_before)};
+    EmitCarry carry = {s_sol.tied_before, s_sol.units_before};   // what the workgroups before this one hold
 
     int parity = 0;
     for (long long t0 = base; t0 < end; t0 += kTile, parity ^= 1) {
