@@ -45,8 +45,7 @@ struct AllocHeader {              // 256 bytes at the start of the workspace
     unsigned int lists_ok;        // no workgroup ran out of room in its list (written between passes)
     unsigned int pad0;
     unsigned long long ck_top;    // the coarse count left every prompt's walk state at its first gain <= this pattern
-    unsigned int uneven;          // the depth estimate found walks of different length: 1 uneven, 2 very uneven (pooled walks pay)
-    unsigned int pad1;
+    unsigned int pad1[2];
     unsigned long long pad[19];
 };
 static_assert(sizeof(Bracket) == 32, "bracket size");

@@ -460,7 +460,7 @@ __global__ __launch_bounds__(kBig) void k_bisect_coarse(Src src, long long n, Bu
     bool uneven, very_uneven;
     estimate_depth(src, n, shares, limit, s_est, est, ck, uneven, very_uneven, deepest);
     const unsigned long long top_ck = octave_top(ck);
-    if (blockIdx.x == 0 && threadIdx.x == 0) { hdr->ck_top = top_ck; hdr->uneven = very_uneven ? 2u : (uneven ? 1u : 0u); }
+    if (blockIdx.x == 0 && threadIdx.x == 0) hdr->ck_top = top_ck;
     const unsigned long long est_bottom = octave_top(est) - kOctave;
     const unsigned long long fine_top = octave_top(est - (kWinOct - 1));   // (above 1.0 when est < kWinOct - 1: no gain lies there)
     const int lane = lane_id();
