@@ -157,7 +157,7 @@ struct ClassSolution {      // LDS
 __device__ __forceinline__ void sums_before(ClassSolution* sol, const long long* s_before, bool has, int k, bool tied) {
     const long long bef = has ? s_before[lane_id()] : 0;
     const long long tb = wave_total_i64(tied ? bef : 0);
-    const long long ub = wave_total_i64(bef * k);
+    const long long ub = (long long)wave_total_u64((unsigned long long)(bef * k));   // (up to the budget: beyond the two-piece sums)
     if (lane_id() == 0) { sol->tied_before = tb; sol->units_before = ub; }
 }
 

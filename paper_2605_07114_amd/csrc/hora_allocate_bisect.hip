@@ -938,7 +938,8 @@ __device__ __forceinline__ void first_bracket(SelectShared& sh, CoarseShared& cs
         const int min_seen = -wave_max_i32(-cs.smin[lane_id()]);
         const int s_min = min_seen == INT_MAX ? s_max : min_seen;   // no tile has gains left: everything is counted
         const int first = s_max - (kWinOct - 1) > 0 ? s_max - (kWinOct - 1) : 0;   // first octave of the range
-        const long long tops_all = wave_total_i64(cs.tops[lane_id()]);
+        // (counts up to a few times the budget: sums over the full 64-bit range)
+        const long long tops_all = (long long)wave_total_u64((unsigned long long)cs.tops[lane_id()]);
         const int oct_j = first + j / kSubBins;
         const int e_j = (oct_j & (kWinOct - 1)) * kSubBins + (j % kSubBins);   // the ring row that can hold that octave
         // each row of 16 lanes joins four wavefronts' entries, then the four rows are joined
@@ -960,9 +961,10 @@ __device__ __forceinline__ void first_bracket(SelectShared& sh, CoarseShared& cs
         // (an entry's lowest octave is the range's octave oct_j or lies a multiple of four above it)
         const bool in_range = all.o == oct_j;
         const long long c = (low && in_range) ? all.t : 0;
-        const long long all_above = tops_all + wave_total_i64(low ? all.r + (in_range ? 0 : all.t) : 0);
-        const long long known = all_above + wave_total_i64(c);
-        const long long incl = wave_incl_scan_i64(c);
+        const long long all_above =
+            tops_all + (long long)wave_total_u64((unsigned long long)(low ? all.r + (in_range ? 0 : all.t) : 0));
+        const long long known = all_above + (long long)wave_total_u64((unsigned long long)c);
+        const long long incl = (long long)wave_incl_scan_u64((unsigned long long)c);
         unsigned long long lo = 0ull, hi = kOne;
         long long above = 0, inside = -1;
         if (all_above >= budget) {
@@ -1451,8 +1453,8 @@ __global__ __launch_bounds__(kBig) void k_bisect_write(Src src, long long n, int
         static_assert(kMaxBlocks <= kBig && kMaxBlocks % kWave == 0, "one thread per workgroup sum");
         const int t = (int)threadIdx.x;
         const long long kv = t < nb ? block_ksum[t] : 0, tv = t < nb ? block_tied[t] : 0;
-        const long long k_all = wave_total_i64(kv), t_all = wave_total_i64(tv);
-        const long long k_bef = wave_total_i64(t < (int)blockIdx.x ? kv : 0);
+        const long long k_all = (long long)wave_total_u64((unsigned long long)kv), t_all = wave_total_i64(tv);
+        const long long k_bef = (long long)wave_total_u64((unsigned long long)(t < (int)blockIdx.x ? kv : 0));
         const long long t_bef = wave_total_i64(t < (int)blockIdx.x ? tv : 0);
         if (lane_id() == 0) {
             s_pre[0][wave_id()] = k_all; s_pre[1][wave_id()] = t_all;

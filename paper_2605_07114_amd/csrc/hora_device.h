@@ -87,6 +87,13 @@ __device__ __forceinline__ unsigned long long wave_incl_scan_u64(unsigned long l
     return (unsigned long long)lo + ((unsigned long long)mid << 22) + ((unsigned long long)hi << 43);
 }
 
+__device__ __forceinline__ unsigned long long wave_total_u64(unsigned long long v) {
+    const unsigned long long t = wave_incl_scan_u64(v);
+    const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(t & 0xffffffffull), kWave - 1);
+    const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(t >> 32), kWave - 1);
+    return ((unsigned long long)hi << 32) | lo;
+}
+
 __device__ __forceinline__ int wave_last_i32(int v) { return __builtin_amdgcn_readlane(v, kWave - 1); }
 
 __device__ __forceinline__ long long wave_total_i64(long long v) {   // same range as the scan
