@@ -48,7 +48,12 @@
 
 namespace hora {
 
-constexpr int kSoloMaxPrompts = 2048;                       // up to here one workgroup searches alone
+// Up to here one workgroup searches alone, in one launch.  With counts it reads the gains from
+// tables; with per-prompt posteriors it walks every prompt again in every pass of its search,
+// which the six launches below overtake early (measured, learned-prior posteriors, 8 units per
+// prompt: 29 us at 256 prompts, 51 at 512, 217 at 2048, against 58-60 us for the six launches).
+constexpr int kSoloMaxPrompts = 2048;
+constexpr int kSoloMaxPosteriors = 384;
 constexpr unsigned long long kOne = 0x3ff0000000000000ull;  // pattern of 1.0: no gain exceeds it
 constexpr unsigned long long kOctave = 1ull << 52;          // one exponent step of the pattern
 constexpr int kMaxOctave = 1022;                            // octave o holds (2^-(o+1), 2^-o]; the last one ends at 0
@@ -1510,6 +1515,8 @@ __global__ __launch_bounds__(kBig) void k_bisect_write(Src src, long long n, int
 // ----------------------------------------------------------------------------------
 // Host side
 // ----------------------------------------------------------------------------------
+constexpr long long solo_max(const CountsSource&) { return kSoloMaxPrompts; }
+constexpr long long solo_max(const PosteriorSource&) { return kSoloMaxPosteriors; }
 static int run_small(const CountsSource& src, const CommonArgs& a) {
     return allocate_small_counts(src, a.n, a.g0, a.budget, a.delta_max, a.delta, a.util, a.group_off, a.off_t,
                                  a.summary, a.dev_status, a.stream);
@@ -1523,7 +1530,7 @@ template <class Src>
 static int run_bisect(const Src& src, const CommonArgs& a, const Plan& p, const Workspace& w) {
     const long long n = a.n;
     // a batch that one workgroup can hold: one launch does the whole search and the outputs
-    if (n <= kSoloMaxPrompts) return run_small(src, a);
+    if (n <= solo_max(src)) return run_small(src, a);
     // gains one prompt may contribute: the caller's cap, the budget, the library's depth bound
     long long wanted = a.delta_max > 0 ? (long long)a.delta_max : a.budget;
     if (wanted > a.budget) wanted = a.budget;
