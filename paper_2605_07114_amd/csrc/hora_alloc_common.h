@@ -108,26 +108,6 @@ __device__ __forceinline__ void tally_gains(TallyBins& bins, bool inside, unsign
     }
 }
 
-// Number of gains of one prompt that exceed tau, at most `limit`; also leaves the next
-// gain (the first one <= tau) in `g`, l as a double in `lf` and, if asked, the survival
-// product E(k) in `e`.
-template <bool kSurvival>
-__device__ __forceinline__ long long walk_above(double a, double b, unsigned long long tau_bits, long long limit,
-                                                double& g, double& lf, double& e) {
-    const double s = a + b;
-    g = gain_first(a, s);
-    lf = 0.0;
-    e = 1.0;
-    long long k = 0;
-    while (k < limit && gain_bits(g) > tau_bits) {
-        if (kSurvival) e = surv_next(e, b, s, lf);
-        g = gain_next(g, b, s, lf);
-        lf += 1.0;
-        k += 1;
-    }
-    return k;
-}
-
 // A batch small enough for one workgroup, solved in a single launch (defined with the
 // sharded kernels, whose workgroup-per-shard code it reuses).
 int allocate_small_counts(const CountsSource& src, int64_t n, int32_t g0, int64_t budget, int32_t delta_max,

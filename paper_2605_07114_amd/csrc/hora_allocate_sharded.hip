@@ -286,7 +286,8 @@ __device__ __forceinline__ int class_of(const PosteriorSource&, long long) { ret
 // Threshold by walks.
 // Invariant: exactly `above` pairs have a gain > hi, and above < budget.  A pass cuts
 // (lo, hi] into at most kBins intervals of 2^shift bit patterns and tallies the gains
-// that fall inside (every prompt walks its gains from l = 0 down to lo).  If the
+// that fall inside (every prompt walks its gains down to lo: from the state the pass before
+// left for the first two prompts of a thread, from l = 0 for the others).  If the
 // running count from the top reaches the budget inside interval j, the bracket
 // shrinks to the gains that occur there, (min - 1, max], and closes when min == max:
 // tau is that gain.  Otherwise the whole window lies above tau: it is added to
@@ -297,9 +298,15 @@ __device__ __forceinline__ int class_of(const PosteriorSource&, long long) { ret
 // smallest ceil(budget/n)-th gain) can lie orders of magnitude below tau.
 // Counts fit 63 bits: n < 2^40 and one prompt has far fewer than 2^22 gains per window
 // for any threshold a budget below 2^52 can reach.
+constexpr int kResume = 2;   // prompts per thread whose walk states are kept from pass to pass
+struct WalkResume {          // per thread: the first state at or below the last pass's hi (at or above tau)
+    double g[kResume], l[kResume];
+    bool valid;
+};
+
 template <class Src>
 __device__ bool threshold_by_walks(const Src& src, long long lo_i, long long hi_i, long long budget, long long limit,
-                                   ShardShared& sh, bool& data_bad, unsigned long long& tau_bits) {
+                                   ShardShared& sh, bool& data_bad, unsigned long long& tau_bits, WalkResume& rs) {
     const int lane = lane_id();
     unsigned long long top = 0;
     for (long long i = lo_i + threadIdx.x; i < hi_i; i += kShardThreads) {
@@ -321,6 +328,16 @@ __device__ bool threshold_by_walks(const Src& src, long long lo_i, long long hi_
     }
     __syncthreads();
 
+    // The first kResume prompts of a thread (all of them up to 512 prompts per shard) do not walk
+    // from l = 0 again in every pass: a pass leaves each walk's first state at or below its hi
+    // and the state it ended in (the first at or below its lo).  A bracket only moves down, so
+    // the next pass goes on from the former, or from the latter when the bracket has moved to
+    // the window below (its hi is the last pass's lo).  What the last pass leaves serves the
+    // caller's output walk too: tau is the last hi.
+    double (&at_hi_g)[kResume] = rs.g, (&at_hi_l)[kResume] = rs.l;
+    double at_lo_g[kResume], at_lo_l[kResume];
+    bool resumable = false;                  // the states above are those of the pass before
+    unsigned long long last_lo = 0ull;       // ... whose bracket ended here
     for (int pass = 0; pass < kShardMaxPasses; ++pass) {
         if (sh.done) break;   // uniform: written before the barrier that ends a pass
         const unsigned long long lo = sh.lo, hi_cur = sh.hi;
@@ -329,17 +346,22 @@ __device__ bool threshold_by_walks(const Src& src, long long lo_i, long long hi_
         static_assert(kBins == kShardThreads, "one interval per thread");
         sh.bins.cnt[threadIdx.x] = 0; sh.bins.vmax[threadIdx.x] = 0; sh.bins.vmin_inv[threadIdx.x] = 0;
         __syncthreads();
-        // every wavefront runs whole rounds, so that the ballots see all of its lanes
-        for (long long i0 = lo_i; i0 < hi_i; i0 += kShardThreads) {
+        const bool from_lo = resumable && hi_cur <= last_lo;   // uniform
+        // one round of the workgroup: a prompt per thread, walked from (g, lf) down to lo; every
+        // wavefront runs whole rounds, so that the ballots see all of its lanes
+        auto walk_round = [&](long long i0, bool resume, double g0_, double l0_, double& hi_g, double& hi_l,
+                              double& lo_g, double& lo_l) {
             const long long i = i0 + threadIdx.x;
             double a = 1.0, b = 1.0;
             if (i < hi_i) src.load(i, a, b);
             const double s = a + b;
-            double g = gain_first(a, s);
-            double lf = 0.0;
-            long long k = 0;
+            double g = resume ? g0_ : gain_first(a, s);
+            double lf = resume ? l0_ : 0.0;
+            long long k = (long long)lf;
             unsigned long long gb = gain_bits(g);
             bool active = i < hi_i && k < limit && gb > lo;
+            bool kept = gb <= hi_cur;
+            hi_g = g; hi_l = lf;
             while (__ballot(active)) {
                 tally_gains(sh.bins, active && gb <= hi_cur, gb, lo, shift);
                 if (active) {
@@ -348,9 +370,24 @@ __device__ bool threshold_by_walks(const Src& src, long long lo_i, long long hi_
                     k += 1;
                     gb = gain_bits(g);
                     active = k < limit && gb > lo;
+                    if (!kept) { hi_g = g; hi_l = lf; kept = gb <= hi_cur; }
                 }
             }
+            lo_g = g; lo_l = lf;
+        };
+#pragma unroll
+        for (int r = 0; r < kResume; ++r) {
+            const long long i0 = lo_i + (long long)r * kShardThreads;
+            if (i0 < hi_i)   // uniform
+                walk_round(i0, resumable, from_lo ? at_lo_g[r] : at_hi_g[r], from_lo ? at_lo_l[r] : at_hi_l[r],
+                           at_hi_g[r], at_hi_l[r], at_lo_g[r], at_lo_l[r]);
         }
+        for (long long i0 = lo_i + (long long)kResume * kShardThreads; i0 < hi_i; i0 += kShardThreads) {
+            double unused[4];
+            walk_round(i0, false, 0.0, 0.0, unused[0], unused[1], unused[2], unused[3]);
+        }
+        resumable = true;
+        last_lo = lo;
         __syncthreads();   // the tallies are complete
         // interval j = kBins - 1 - thread: thread 0 owns the top interval
         const int j = kBins - 1 - (int)threadIdx.x;
@@ -375,6 +412,7 @@ __device__ bool threshold_by_walks(const Src& src, long long lo_i, long long hi_
         __syncthreads();
     }
     tau_bits = sh.hi;
+    rs.valid = resumable;
     return sh.done == 1;   // anything else cannot happen with valid posteriors and a feasible budget
 }
 
@@ -496,12 +534,14 @@ __device__ void shard_core(const Src& src, long long lo_i, long long hi_i, long 
     unsigned long long tau_bits = ~0ull;   // budget 0: nothing is above tau
     bool data_bad = false;
     bool by_table = false;
+    WalkResume rs;
+    rs.valid = false;
     if (budget > 0) {
         if constexpr (Src::kHasClasses)
             if (depth > 0)
                 by_table = threshold_by_table(src, lo_i, hi_i, budget, limit, depth, gain_table, surv_table, sh,
                                           data_bad, tau_bits);
-        if (!by_table && !threshold_by_walks(src, lo_i, hi_i, budget, limit, sh, data_bad, tau_bits)) {
+        if (!by_table && !threshold_by_walks(src, lo_i, hi_i, budget, limit, sh, data_bad, tau_bits, rs)) {
             if (threadIdx.x == 0) report(dev_status, HORA_ERR_RANGE);
             return;
         }
@@ -509,7 +549,8 @@ __device__ void shard_core(const Src& src, long long lo_i, long long hi_i, long 
 
     // ---- k_i, tied flag and E_i(k_i) per prompt; totals --------------------------------
     long long ks = 0, ts = 0;
-    for (long long i = lo_i + threadIdx.x; i < hi_i; i += kShardThreads) {
+    int round = 0;
+    for (long long i = lo_i + threadIdx.x; i < hi_i; i += kShardThreads, ++round) {
         long long k;
         bool tied;
         double e;
@@ -519,9 +560,24 @@ __device__ void shard_core(const Src& src, long long lo_i, long long hi_i, long 
             tied = sh.tied_cls[x] != 0;
             e = sh.e_cls[x];
         } else {
-            double a, b, g, lf;
+            // the walk goes on from where the search left it (the first prompts of a thread), else
+            // from l = 0, down to the first gain M(k) at or below tau; the survival product follows
+            // from that gain: E(k) = M(k) (alpha + beta + k) / alpha (App. A: the ratio of the closed
+            // forms of M and E), E(0) = 1
+            double a, b;
             data_bad |= !src.load(i, a, b);
-            k = walk_above<true>(a, b, tau_bits, limit, g, lf, e);
+            const double s = a + b;
+            double g = gain_first(a, s), lf = 0.0;
+#pragma unroll
+            for (int q = 0; q < kResume; ++q)
+                if (rs.valid && round == q) { g = rs.g[q]; lf = rs.l[q]; }
+            k = (long long)lf;
+            while (k < limit && gain_bits(g) > tau_bits) {
+                g = gain_next(g, b, s, lf);
+                lf += 1.0;
+                k += 1;
+            }
+            e = k > 0 ? (g * (s + lf)) / a : 1.0;
             tied = (k < limit) && (gain_bits(g) == tau_bits);
             if (depth_capped && k == limit && gain_bits(g) > tau_bits) report(dev_status, HORA_ERR_UNSUPPORTED);
         }
