@@ -29,7 +29,7 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
 # are in profiles/hbm_traffic_large_alloc_large_bcast.txt.  Set to None when a kernel named
 # there changes.
 TRAFFIC_BROADCAST_BYTES = 692395767     # k_row_desc + k_token_fill, large_bcast
-TRAFFIC_ALLOCATE_BYTES = 25546350       # k_class_hist + k_class_write, large_alloc
+TRAFFIC_ALLOCATE_BYTES = 25555438       # k_class_hist + k_class_write, large_alloc
 
 
 def ensure_library():
@@ -123,6 +123,16 @@ def other_paths(torch, hora, wl, sess, a1, c1, w1, delta1, util1, goff1, ws, rep
     assert int(delta1.sum()) == 8 * w1.n
     out["allocate_posterior_learned_prior_2^20"] = {"budget": 8 * w1.n, "us_per_call": us,
                                                     "prompts_per_s": w1.n / us * 1e6}
+    # the same posteriors at the sizes of one training step and up (B = 8N): one workgroup alone, one
+    # tile in one launch, the six launches
+    sweep = []
+    for n_s in (60, 256, 1024, 4096, 1 << 16, 1 << 18):
+        us = mean_us(lambda: hora.hora_allocate_posterior(alpha_l[:n_s], beta_l[:n_s], 8, 8 * n_s, delta1[:n_s],
+                                                          sess.dev_status, ws, util=util1[:n_s],
+                                                          group_off=goff1[:n_s + 1]))
+        assert int(delta1[:n_s].sum()) == 8 * n_s
+        sweep.append({"n": n_s, "us_per_call": us})
+    out["allocate_posterior_learned_prior_sweep"] = sweep
     # a deep budget: 200 additional rollouts per prompt on average, 2^18 prompts
     n_deep = 1 << 18
     us = mean_us(lambda: hora.hora_allocate_posterior(alpha[:n_deep], beta[:n_deep], w1.g0, 200 * n_deep,
