@@ -350,6 +350,27 @@ def test_a_few_deep_walks_in_every_wavefront(gpu, oracle):
         np.testing.assert_allclose(got.util.cpu().numpy(), oracle.utilities(alpha, beta, want), rtol=UTIL_RTOL, atol=0)
 
 
+def test_posteriors_beyond_a_million_prompts(gpu, oracle):
+    """More tiles than the first narrowing pass keeps in registers when it adds up the tiles'
+    coarse counts (256 tiles of 4096 prompts): learned-prior posteriors (App. D) in a batch of
+    385 tiles, the last one ragged.  Allocation and offsets bit for bit, utilities within 1e-12."""
+    sess, torch, hora = gpu
+    rng = np.random.default_rng(41)
+    n, g0 = (1 << 20) + (1 << 19) + 777, 8
+    s = rng.uniform(0.25, 16.0, n)
+    p = rng.uniform(0.02, 0.98, n)
+    c = rng.binomial(g0, p)
+    alpha, beta = s * p + c, s * (1 - p) + g0 - c
+    budget = 3 * n
+    want = oracle.allocate_posterior(alpha, beta, budget)
+    print(f"allocate_posterior n={n} budget={budget} deepest={int(want.max())}", flush=True)
+    got = sess.allocate_posterior(dev(torch, alpha), dev(torch, beta), g0, budget)
+    assert sess.status() == 0
+    assert np.array_equal(got.delta.cpu().numpy().astype(np.int64), want)
+    assert np.array_equal(got.group_off.cpu().numpy(), oracle.group_offsets(want, g0))
+    np.testing.assert_allclose(got.util.cpu().numpy(), oracle.utilities(alpha, beta, want), rtol=UTIL_RTOL, atol=0)
+
+
 def test_learned_prior_collapses_to_the_uniform_prior(gpu, oracle):
     # App. D: s = 2, p = 1/2 gives alpha = 1 + c, beta = 1 + G0 - c
     sess, torch, hora = gpu
