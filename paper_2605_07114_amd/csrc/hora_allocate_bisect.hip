@@ -49,11 +49,12 @@
 namespace hora {
 
 // Up to here one workgroup searches alone, in one launch.  With counts it reads the gains from
-// tables; with per-prompt posteriors it walks every prompt again in every pass of its search,
-// which the six launches below overtake early (measured, learned-prior posteriors, 8 units per
-// prompt: 29 us at 256 prompts, 51 at 512, 217 at 2048, against 58-60 us for the six launches).
+// tables.  With per-prompt posteriors it walks: its first 512 prompts (two per thread) keep
+// their walk states from pass to pass, the ones after them walk from l = 0 in every pass, and
+// the six steps below take over (measured, learned-prior posteriors, 8 units per prompt: 21 us
+// at 60 prompts, 23 at 256; 47 us for one tile in one launch).
 constexpr int kSoloMaxPrompts = 2048;
-constexpr int kSoloMaxPosteriors = 384;
+constexpr int kSoloMaxPosteriors = 512;
 constexpr unsigned long long kOne = 0x3ff0000000000000ull;  // pattern of 1.0: no gain exceeds it
 constexpr unsigned long long kOctave = 1ull << 52;          // one exponent step of the pattern
 constexpr int kMaxOctave = 1022;                            // octave o holds (2^-(o+1), 2^-o]; the last one ends at 0

@@ -36,9 +36,10 @@ constexpr int kPrefixThreads = 1024;
 constexpr int kPrefixGroups = 64;                  // prefix-sum workgroups of the set-up kernel, at most
 constexpr unsigned kShardTiedBit = 0x80000000u;
 constexpr unsigned long long kWindowStep = 4ull << 52;   // 4 exponent steps: a factor 16 in value
-// Windows from the largest gain down to zero (at most 2047 / 4), plus the narrowing passes
-// inside the window that holds tau (each cuts the bracket at least 128-fold).
-constexpr int kShardMaxPasses = 512 + 10;
+constexpr unsigned long long kOctaveStep = 1ull << 52;   // one exponent step: a factor 2
+// Windows from the largest gain down to zero (at most 2047 of one octave), plus the narrowing
+// passes inside the window that holds tau (each cuts the bracket at least 128-fold).
+constexpr int kShardMaxPasses = 2048 + 10;
 constexpr int kShardTableCap = 8192;     // entries of the gain table (and of the survival table)
 constexpr int kShardMaxDepth = 512;      // gains per class in the table, at most
 
@@ -291,9 +292,9 @@ __device__ __forceinline__ int class_of(const PosteriorSource&, long long) { ret
 // running count from the top reaches the budget inside interval j, the bracket
 // shrinks to the gains that occur there, (min - 1, max], and closes when min == max:
 // tau is that gain.  Otherwise the whole window lies above tau: it is added to
-// `above` and the next window, a factor 16 further down in value (4 exponent steps of
-// the bit pattern), is taken.  Going down window by window keeps the walks short: a
-// window's count is a small multiple of the one before it, so the work is a small
+// `above` and the next window further down in value is taken (one exponent step of the
+// bit pattern, or four: see `window` below).  Going down window by window keeps the walks
+// short: a window's count is a small multiple of the one before it, so the work is a small
 // multiple of the budget, whereas a bracket from a guaranteed lower bound (e.g. the
 // smallest ceil(budget/n)-th gain) can lie orders of magnitude below tau.
 // Counts fit 63 bits: n < 2^40 and one prompt has far fewer than 2^22 gains per window
@@ -308,6 +309,12 @@ template <class Src>
 __device__ bool threshold_by_walks(const Src& src, long long lo_i, long long hi_i, long long budget, long long limit,
                                    ShardShared& sh, bool& data_bad, unsigned long long& tau_bits, WalkResume& rs) {
     const int lane = lane_id();
+    // Every walk of a window goes down to the window's lower end, past tau in the window that
+    // holds it: with windows of a factor 16 a walk takes up to 16^(1/(1+alpha)) times the steps
+    // it needs.  Where every walk goes on from pass to pass (see below) a window costs only its
+    // barriers, so the windows are single octaves; larger shards, whose later prompts walk from
+    // l = 0 in every pass, keep the wide ones.
+    const unsigned long long window = hi_i - lo_i <= (long long)kResume * kShardThreads ? kOctaveStep : kWindowStep;
     unsigned long long top = 0;
     for (long long i = lo_i + threadIdx.x; i < hi_i; i += kShardThreads) {
         double a, b;
@@ -322,7 +329,15 @@ __device__ bool threshold_by_walks(const Src& src, long long lo_i, long long hi_
         unsigned long long all_top = 0;
         for (int w = 0; w < kShardWaves; ++w) all_top = sh.red_u[0][w] > all_top ? sh.red_u[0][w] : all_top;
         sh.hi = all_top;
-        sh.lo = all_top > kWindowStep ? all_top - kWindowStep : 0ull;
+        // A prompt's gains add up to less than 1, so fewer than 1 / t of them exceed t and tau <=
+        // size / budget: the first window reaches down to the bottom of the octave that holds
+        // 2^-lumped, where 2^lumped <= budget / size (from the leading bits: at most one too small).
+        const long long size = hi_i - lo_i;
+        const int lumped = (63 - __clzll(budget)) - (63 - __clzll(size)) - 1;   // (budget, size > 0 here)
+        const unsigned long long first_lo = lumped > 0 ? 0x3ff0000000000000ull - (unsigned long long)(lumped + 1) * kOctaveStep : ~0ull;
+        unsigned long long lo0 = all_top > window ? all_top - window : 0ull;
+        if (first_lo < lo0) lo0 = first_lo;
+        sh.lo = lo0;
         sh.above = 0;
         sh.done = 0;
     }
@@ -393,14 +408,23 @@ __device__ bool threshold_by_walks(const Src& src, long long lo_i, long long hi_
         const int j = kBins - 1 - (int)threadIdx.x;
         const long long cj = (long long)sh.bins.cnt[j];
         const unsigned long long mx = sh.bins.vmax[j], mn = ~sh.bins.vmin_inv[j];
-        long long before, unused_ex, total, unused_tot;
-        shard_scan2(cj, 0, before, unused_ex, total, unused_tot, sh);
-        before += above;
+        // running count from the top interval down (the barrier above lies between the last
+        // reads of the wavefront totals and these writes)
+        const long long incl = (long long)wave_incl_scan_u64((unsigned long long)cj);
+        if (lane == kWave - 1) sh.red_i[0][wave_id()] = incl;
+        __syncthreads();
+        long long before = above + incl - cj, total = 0;
+#pragma unroll
+        for (int w = 0; w < kShardWaves; ++w) {
+            const long long x = sh.red_i[0][w];
+            if (w < wave_id()) before += x;
+            total += x;
+        }
         if (above + total < budget) {          // uniform: the whole window is above tau
             if (threadIdx.x == 0) {
                 sh.above = above + total;
                 sh.hi = lo;
-                sh.lo = lo > kWindowStep ? lo - kWindowStep : 0ull;
+                sh.lo = lo > window ? lo - window : 0ull;
                 if (lo == 0ull) sh.done = 2;   // no gains left: the budget does not fit
             }
         } else if (cj != 0 && before < budget && budget <= before + cj) {   // exactly one thread
