@@ -164,6 +164,20 @@ def other_paths(torch, hora, wl, sess, a1, c1, w1, delta1, util1, goff1, ws, rep
         us_p = mean_us(run)
         assert int(delta.sum()) == w.budget and sess.status() == 0
         out[f"allocate_sharded_{w.name}"]["us_per_prepared_call"] = us_p
+        if w is wl.PAPER_STEP:
+            # the step's batch as one shard (the unsharded optimum of the same 60 prompts), next to
+            # hora_allocate on it: the sharded call keeps its gain tables from call to call and is one launch
+            one_off = torch.tensor([0, w.n], dtype=torch.int64, device="cuda:0")
+            one_bud = torch.tensor([w.budget], dtype=torch.int64, device="cuda:0")
+            us_1 = mean_us(lambda: hora.hora_allocate_sharded(c, w.g0, one_off, one_bud, delta, sess.dev_status, sws,
+                                                              util=util, group_off=goff))
+            by_shard = delta.clone()
+            ws_small = sess.workspace(w.n, w.g0)
+            us_a = mean_us(lambda: hora.hora_allocate(c, w.g0, w.budget, delta, sess.dev_status, ws_small, util=util,
+                                                      group_off=goff))
+            assert torch.equal(by_shard, delta) and sess.status() == 0
+            out["allocate_paper_step_as_one_batch"] = {"prompts": w.n, "us_per_call_sharded_one_shard": us_1,
+                                                       "us_per_call_hora_allocate": us_a}
     # the helpers next to the path, on the large-broadcast shapes: loss weights, baseline rule, Pass@K
     w2 = wl.LARGE_BCAST
     a2 = wl.phase_a(w2)
