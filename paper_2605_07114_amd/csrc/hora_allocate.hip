@@ -69,22 +69,32 @@ __global__ __launch_bounds__(kBig) void k_class_hist(const int32_t* __restrict__
                                                      double* __restrict__ surv_table, int32_t* dev_status) {
     __shared__ int s_cnt[kBigWaves][kWave];
     const int lane = lane_id();
-    if ((int)blockIdx.x == nb) {   // the extra workgroup: tables, one lane per class
-        if (threadIdx.x <= (unsigned)g0) {
+    if ((int)blockIdx.x == nb) {
+        // the extra workgroup: tables, one lane per class and sequence (a row is one chain of
+        // divisions: the gains on the first wavefront, the survival products on the second, so
+        // that the two chains of a class run side by side on two vector units)
+        static_assert(kMaxClasses <= kWave, "a wavefront holds a lane per class");
+        if (wave_id() < 2 && lane <= g0) {
             const double a = alpha0 + (double)lane;
             const double b = beta0 + (double)(g0 - lane);
             const double s = a + b;
-            double m = gain_first(a, s);
-            double e = 1.0;
             double lf = 0.0;
-            double* grow = gain_table + (long long)lane * row;
-            double* srow = surv_table + (long long)lane * row;
-            for (int l = 0; l < row; ++l) {
-                grow[l] = m;
-                srow[l] = e;
-                e = surv_next(e, b, s, lf);
-                m = gain_next(m, b, s, lf);
-                lf += 1.0;
+            if (wave_id() == 0) {   // uniform per wavefront
+                double m = gain_first(a, s);
+                double* grow = gain_table + (long long)lane * row;
+                for (int l = 0; l < row; ++l) {
+                    grow[l] = m;
+                    m = gain_next(m, b, s, lf);
+                    lf += 1.0;
+                }
+            } else {
+                double e = 1.0;
+                double* srow = surv_table + (long long)lane * row;
+                for (int l = 0; l < row; ++l) {
+                    srow[l] = e;
+                    e = surv_next(e, b, s, lf);
+                    lf += 1.0;
+                }
             }
         }
         return;
