@@ -183,8 +183,7 @@ __device__ __forceinline__ int row_count_above(const double* row, int row_len, u
 __device__ void solve_by_table(int nc, int row_len, int len, bool rows_end_at_cap, long long budget,
                                const long long* s_n, const long long* s_before, const double* s_gain,
                                const double* s_surv, unsigned short* s_pair, ClassSolution* sol) {
-    if (threadIdx.x == 0) sol->found = 0;
-    __syncthreads();
+    // (sol->found is cleared by the caller before the barrier that precedes this call)
     const int row_shift = __ffs(row_len) - 1;
     const int cands = nc * row_len;
     if (cands * nc <= kPairCap) {
@@ -516,6 +515,7 @@ __global__ __launch_bounds__(kBig) void k_class_write(const int32_t* __restrict_
             if (lane == 0) { s_n[cls] = tot; s_before[cls] = bef; }
         }
     }
+    if (threadIdx.x == 0) s_sol.found = 0;   // (for solve_by_table)
     __syncthreads();
 
     if (budget > 0 && rule != 0) {
