@@ -35,6 +35,9 @@
 //
 // Under a shared prior the gains of a bracket are few distinct values, each repeated: step 3
 // already closes the bracket and steps 4 and the finisher return at once.
+// The steps are device functions with a kernel around each; a batch of one tile runs all of
+// them in one launch (k_bisect_tile), and up to a few hundred prompts one workgroup searches
+// alone with other code (k_whole_batch, with the sharded kernels).
 #include <hip/hip_runtime.h>
 
 #include <climits>
