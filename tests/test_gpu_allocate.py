@@ -350,6 +350,30 @@ def test_a_few_deep_walks_in_every_wavefront(gpu, oracle):
         np.testing.assert_allclose(got.util.cpu().numpy(), oracle.utilities(alpha, beta, want), rtol=UTIL_RTOL, atol=0)
 
 
+@pytest.mark.parametrize("n", [1, 60, 511, 512, 513, 4095, 4096, 4097])
+def test_posteriors_around_the_sizes_where_the_method_changes(gpu, oracle, n):
+    """Per-prompt posteriors at the sizes of one training step and at the batch sizes where the
+    library changes its way of working: one workgroup that searches alone (up to 512 prompts),
+    one tile whose steps run in a single launch (up to 4096), the launches of the general path.
+    Learned-prior posteriors (App. D), 8 and 24 units per prompt, one run with a cap that binds.
+    Allocation and offsets bit for bit, utilities within 1e-12."""
+    sess, torch, hora = gpu
+    rng = np.random.default_rng(1000 + n)
+    g0 = 8
+    s = rng.uniform(0.25, 16.0, n)
+    p = rng.uniform(0.02, 0.98, n)
+    c = rng.binomial(g0, p)
+    alpha, beta = s * p + c, s * (1 - p) + g0 - c
+    for budget, cap in ((8 * n, 0), (24 * n, 0), (24 * n, 40), (1, 0)):
+        want = oracle.allocate_posterior(alpha, beta, budget, delta_max=cap)
+        print(f"allocate_posterior n={n} budget={budget} cap={cap} deepest={int(want.max())}", flush=True)
+        got = sess.allocate_posterior(dev(torch, alpha), dev(torch, beta), g0, budget, delta_max=cap)
+        assert sess.status() == 0
+        assert np.array_equal(got.delta.cpu().numpy().astype(np.int64), want)
+        assert np.array_equal(got.group_off.cpu().numpy(), oracle.group_offsets(want, g0))
+        np.testing.assert_allclose(got.util.cpu().numpy(), oracle.utilities(alpha, beta, want), rtol=UTIL_RTOL, atol=0)
+
+
 def test_posteriors_beyond_a_million_prompts(gpu, oracle):
     """More tiles than the first narrowing pass keeps in registers when it adds up the tiles'
     coarse counts (256 tiles of 4096 prompts): learned-prior posteriors (App. D) in a batch of
