@@ -216,6 +216,66 @@ __device__ __forceinline__ void emit_tile(int tile_parity, long long pos, long l
         t_before += lanes_below(m);
         t_wave += __popcll(m);
     }
+    if constexpr (kOff == 1) {
+        // 32-bit offsets: the caller has checked that the last offset, n * g0 + budget, is below
+        // 2^31, so every sum of k and every offset fits 32 bits; ranks are counted from
+        // min(tied prompts before the tile, r), which decides the same winners and offsets
+        // (a rank only matters below r) and keeps them below 2^32 whatever n is.
+        int ks = 0;
+#pragma unroll
+        for (int j = 0; j < kItems; ++j) ks += kk[j];
+        const int ks_incl = wave_incl_scan_i32(ks);
+        const int ks_wave = wave_last_i32(ks_incl);
+        if (lane_id() == 0) {
+            sh->tied[tile_parity][w] = t_wave;
+            sh->ksum[tile_parity][w] = (long long)ks_wave;
+        }
+        __syncthreads();
+        const int lane = lane_id();
+        const int t_in = lane < kBigWaves ? sh->tied[tile_parity][lane] : 0;
+        const int t_scan = wave_incl_scan_i32(t_in);
+        const int t_total = __builtin_amdgcn_readlane(t_scan, kBigWaves - 1);
+        const int t_lower = w > 0 ? __builtin_amdgcn_readlane(t_scan, w - 1) : 0;
+        const int q_in = lane < kBigWaves ? (int)sh->ksum[tile_parity][lane] : 0;
+        const int q_scan = wave_incl_scan_i32(q_in);
+        const int ks_total = __builtin_amdgcn_readlane(q_scan, kBigWaves - 1);
+        const int ks_lower = w > 0 ? __builtin_amdgcn_readlane(q_scan, w - 1) : 0;
+        const unsigned r32 = r > 0 ? (unsigned)r : 0u;   // (r <= budget < 2^31; negative only after an error that is reported)
+        const unsigned rank_base = carry.rank_base < r ? (unsigned)carry.rank_base : r32;
+        unsigned rank = rank_base + (unsigned)(t_lower + t_before);
+        int kprior = (int)carry.ks_base + ks_lower + (ks_incl - ks);
+        // g0 * pos is below 2^31 (or g0 is 0): the low 32 bits of the product are the product
+        const int first = (int)((unsigned)g0 * (unsigned)(unsigned long long)pos);
+        int32_t o32[kItems + 1];
+#pragma unroll
+        for (int j = 0; j < kItems; ++j) {
+            o32[j] = first + g0 * j + kprior + (int)(rank < r32 ? rank : r32);
+            win[j] = td[j] && rank < r32;
+            dd[j] = kk[j] + (win[j] ? 1 : 0);
+            rank += (unsigned)td[j];
+            kprior += kk[j];
+        }
+        o32[kItems] = first + g0 * kItems + kprior + (int)(rank < r32 ? rank : r32);
+        if constexpr (kTiedOnly) {
+            bool any_tied = false;
+#pragma unroll
+            for (int j = 0; j < kItems; ++j) any_tied |= td[j] != 0;
+            if (any_tied) store_items<v4i, int32_t>(delta, pos, end, d_vec, dd);
+        } else {
+            store_items<v4i, int32_t>(delta, pos, end, d_vec, dd);
+        }
+        int32_t* go = reinterpret_cast<int32_t*>(group_off);
+        int32_t first_four[kItems];
+#pragma unroll
+        for (int j = 0; j < kItems; ++j) first_four[j] = o32[j];
+        store_items<v4i, int32_t>(go, pos, end, o_vec, first_four);
+#pragma unroll
+        for (int j = 0; j < kItems; ++j)
+            if (pos + j == n - 1) go[n] = o32[j + 1];
+        carry.rank_base += t_total;
+        carry.ks_base += ks_total;
+        return;
+    }
     long long ks = 0, ks_incl = 0, ks_wave = 0;
     if (kOff != 0) {
 #pragma unroll
@@ -268,16 +328,7 @@ __device__ __forceinline__ void emit_tile(int tile_parity, long long pos, long l
     } else {
         store_items<v4i, int32_t>(delta, pos, end, d_vec, dd);
     }
-    if (kOff == 1) {
-        int32_t* go = reinterpret_cast<int32_t*>(group_off);
-        int32_t o32[kItems];
-#pragma unroll
-        for (int j = 0; j < kItems; ++j) o32[j] = (int32_t)off[j];
-        store_items<v4i, int32_t>(go, pos, end, o_vec, o32);
-#pragma unroll
-        for (int j = 0; j < kItems; ++j)
-            if (pos + j == n - 1) go[n] = (int32_t)off[j + 1];
-    } else if (kOff == 2) {
+    if (kOff == 2) {
         long long* go = reinterpret_cast<long long*>(group_off);
         long long o64[kItems];
 #pragma unroll

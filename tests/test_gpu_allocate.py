@@ -350,6 +350,27 @@ def test_a_few_deep_walks_in_every_wavefront(gpu, oracle):
         np.testing.assert_allclose(got.util.cpu().numpy(), oracle.utilities(alpha, beta, want), rtol=UTIL_RTOL, atol=0)
 
 
+@pytest.mark.parametrize("n,g0,per", [(3 * (1 << 20) + 5, 4, 3), ((1 << 21) + 4097, 0, 2)])
+def test_offsets_over_several_tiles_per_workgroup(gpu, oracle, n, g0, per):
+    """Beyond 2^20 prompts a workgroup handles several tiles and carries its running sums from
+    tile to tile; 32-bit offsets are formed in 32-bit arithmetic, 64-bit ones in 64-bit.  Both
+    methods, both offset types, G0 = 0 included (the offsets are then the prefix sums of delta)."""
+    sess, torch, hora = gpu
+    rng = np.random.default_rng(n % 1000)
+    c = rng.binomial(g0, rng.beta(0.5, 0.5, n)).astype(np.int32) if g0 else np.zeros(n, dtype=np.int32)
+    budget = per * n
+    want = oracle.allocate(c, g0, budget)
+    off = oracle.group_offsets(want, g0)
+    dc = dev(torch, c)
+    for method in (hora.ALLOC_CLASS, hora.ALLOC_BISECT):
+        for dt in (torch.int32, torch.int64):
+            print(f"allocate n={n} g0={g0} budget={budget} method={method} offsets={dt}", flush=True)
+            got = sess.allocate(dc, g0, budget, method=method, off_dtype=dt)
+            assert sess.status() == 0
+            assert np.array_equal(got.delta.cpu().numpy().astype(np.int64), want)
+            assert np.array_equal(got.group_off.cpu().numpy().astype(np.int64), off)
+
+
 @pytest.mark.parametrize("n", [1, 60, 511, 512, 513, 4095, 4096, 4097])
 def test_posteriors_around_the_sizes_where_the_method_changes(gpu, oracle, n):
     """Per-prompt posteriors at the sizes of one training step and at the batch sizes where the
