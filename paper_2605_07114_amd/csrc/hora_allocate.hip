@@ -153,8 +153,7 @@ struct ClassSolution {      // LDS
     long long tie_prompts;
     int found;
     int win;                  // a table entry whose value is tau (pairs path)
-    int k[kMaxClasses];
-    int tied[kMaxClasses];
+    unsigned kt[kMaxClasses];  // gains of the class above tau, with kTiedBit when its next gain equals tau
     double u0[kMaxClasses];   // U_c(k_c)
     double u1[kMaxClasses];   // U_c(k_c + 1)
     long long tied_before;    // tied prompts in the workgroups before this one
@@ -232,8 +231,7 @@ __device__ void solve_by_table(int nc, int row_len, int len, bool rows_end_at_ca
                 const int pr = s_pair[sol->win * nc + cls];
                 pos = pr & 0x7fff;
                 tied = (pr & 0x8000) != 0;
-                sol->k[cls] = pos;
-                sol->tied[cls] = tied ? 1 : 0;
+                sol->kt[cls] = (unsigned)pos | (tied ? kTiedBit : 0u);
                 sol->u0[cls] = 1.0 - s_surv[cls * row_len + pos];
                 sol->u1[cls] = 1.0 - s_surv[cls * row_len + (pos + 1 < row_len ? pos + 1 : pos)];
             }
@@ -288,8 +286,7 @@ __device__ void solve_by_table(int nc, int row_len, int len, bool rows_end_at_ca
             const double* row = s_gain + c * row_len;
             cnt = row_count_above(row, row_len, sol->tau_bits);
             tied = gain_bits(row[cnt]) == sol->tau_bits;
-            sol->k[c] = cnt;
-            sol->tied[c] = tied ? 1 : 0;
+            sol->kt[c] = (unsigned)cnt | (tied ? kTiedBit : 0u);
             sol->u0[c] = 1.0 - s_surv[c * row_len + cnt];
             sol->u1[c] = 1.0 - s_surv[c * row_len + (cnt + 1 < row_len ? cnt + 1 : cnt)];
         }
@@ -357,8 +354,7 @@ __device__ void solve_by_greedy(int g0, double alpha0, double beta0, long long c
                 if (depth_capped && k >= cap_eff) report(dev_status, HORA_ERR_UNSUPPORTED);
             }
         }
-        sol->k[lane] = has ? (int)k : 0;
-        sol->tied[lane] = (has && tied) ? 1 : 0;
+        sol->kt[lane] = has ? ((unsigned)k | (tied ? kTiedBit : 0u)) : 0u;
         sol->u0[lane] = 1.0 - e;
         sol->u1[lane] = 1.0 - surv_next(e, b, s, lf);
         sums_before(sol, s_before, has, has ? (int)k : 0, has && tied);
@@ -407,8 +403,7 @@ __device__ void solve_by_rule(int rule, int g0, double alpha0, double beta0, lon
             e = surv_next(e, b, s, lf);
             lf += 1.0;
         }
-        sol->k[lane] = (int)k;
-        sol->tied[lane] = mine ? 1 : 0;
+        sol->kt[lane] = (unsigned)k | (mine ? kTiedBit : 0u);
         sol->u0[lane] = 1.0 - e;
         sol->u1[lane] = 1.0 - surv_next(e, b, s, lf);
         sums_before(sol, s_before, has, (int)k, mine);
@@ -526,8 +521,7 @@ __global__ __launch_bounds__(kBig) void k_class_write(const int32_t* __restrict_
             solve_by_greedy(g0, alpha0, beta0, cap_eff, depth_capped, budget, s_n, s_before, &s_sol, dev_status);
     } else {
         if (threadIdx.x < kMaxClasses) {
-            s_sol.k[threadIdx.x] = 0;
-            s_sol.tied[threadIdx.x] = 0;
+            s_sol.kt[threadIdx.x] = 0u;
             s_sol.u0[threadIdx.x] = 0.0;
             s_sol.u1[threadIdx.x] = 0.0;
         }
@@ -563,8 +557,9 @@ __global__ __launch_bounds__(kBig) void k_class_write(const int32_t* __restrict_
             if (pos + j < end) {
                 const int x = cls[j] < 0 ? 0 : (cls[j] > g0 ? g0 : cls[j]);
                 cls[j] = x;
-                kk[j] = s_sol.k[x];
-                td[j] = s_sol.tied[x];
+                const unsigned kt = s_sol.kt[x];
+                kk[j] = (int)(kt & ~kTiedBit);
+                td[j] = (kt & kTiedBit) ? 1 : 0;
             } else {
                 cls[j] = 0; kk[j] = 0; td[j] = 0;
             }
@@ -574,7 +569,7 @@ __global__ __launch_bounds__(kBig) void k_class_write(const int32_t* __restrict_
         if (util) {
             double uu[kItems];
 #pragma unroll
-            for (int j = 0; j < kItems; ++j) uu[j] = win[j] ? s_sol.u1[cls[j]] : s_sol.u0[cls[j]];
+            for (int j = 0; j < kItems; ++j) uu[j] = (win[j] ? s_sol.u1 : s_sol.u0)[cls[j]];   // (one LDS read)
             store_items<v2d, double>(util, pos, end, u_vec, uu);
         }
     }
