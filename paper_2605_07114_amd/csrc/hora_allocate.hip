@@ -32,7 +32,11 @@
 
 namespace hora {
 
-constexpr int kPairCap = 16384;               // (table entry, class) pairs ranked one per thread when they fit
+// (table entry, class) pairs ranked one per thread when a round or two of the workgroup cover them
+// (G0 = 4 with rows of 32: 800 pairs, 13.8 us against 14.4 us); beyond that a thread per entry
+// that searches four rows at a time is faster (G0 = 8 with rows of 128: 10 368 pairs, 22 us
+// against 26 us)
+constexpr int kPairCap = 2048;
 
 // ----------------------------------------------------------------------------------
 // Gain / utility tables (Eq. 3, Eq. 5): one thread per posterior, l-major output so
