@@ -133,8 +133,8 @@ size_t hora_allocate_workspace_bytes(int64_t n, int32_t g0);
  * The call evaluates the gain tables of the G0+1 classes afresh every time (its workspace
  * needs no preparation and keeps nothing).  For the batch of one training step (some
  * dozens to a thousand prompts) hora_allocate_sharded with a single shard returns the
- * same delta, util and offsets in one launch and keeps its tables between calls: about
- * a third of the time at 60 prompts with 24 units each.
+ * same delta, util and offsets in one launch and keeps its tables between calls: 40 % of
+ * the time at 60 prompts with 24 units each.
  *
  * n, g0     : number of prompts (>= 0) and pre-rollouts per prompt (>= 0).
  * c         : device, n int32, each in [0, g0] (else HORA_ERR_RANGE in dev_status).
