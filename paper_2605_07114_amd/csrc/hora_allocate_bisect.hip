@@ -51,13 +51,13 @@
 
 namespace hora {
 
-// Up to here one workgroup searches alone, in one launch.  With counts it reads the gains from
-// tables.  With per-prompt posteriors it walks: its first 512 prompts (two per thread) keep
-// their walk states from pass to pass, the ones after them walk from l = 0 in every pass, and
-// the six steps below take over (measured, learned-prior posteriors, 8 units per prompt: 21 us
-// at 60 prompts, 23 at 256; 47 us for one tile in one launch).
-constexpr int kSoloMaxPrompts = 2048;
-constexpr int kSoloMaxPosteriors = 512;
+// Up to here one workgroup searches alone, in one launch, by walks: its first 512 prompts (two
+// per thread) keep their walk states from pass to pass, the ones after them would walk from
+// l = 0 in every pass, so the six steps below take over there (measured, learned-prior
+// posteriors, 8 units per prompt: 21 us at 60 prompts, 23 at 256, 39 at 512; 47 us for one
+// tile in one launch; counts through this method: 29 / 56 us at 60 / 512 prompts, and 87 us
+// at 513 while this bound was 2048).
+constexpr int kSoloMaxPrompts = 512;
 constexpr unsigned long long kOne = 0x3ff0000000000000ull;  // pattern of 1.0: no gain exceeds it
 constexpr unsigned long long kOctave = 1ull << 52;          // one exponent step of the pattern
 constexpr int kMaxOctave = 1022;                            // octave o holds (2^-(o+1), 2^-o]; the last one ends at 0
@@ -1594,8 +1594,6 @@ __global__ __launch_bounds__(kBig) void k_bisect_tile(Src src, long long n, int 
 // ----------------------------------------------------------------------------------
 // Host side
 // ----------------------------------------------------------------------------------
-constexpr long long solo_max(const CountsSource&) { return kSoloMaxPrompts; }
-constexpr long long solo_max(const PosteriorSource&) { return kSoloMaxPosteriors; }
 static int run_small(const CountsSource& src, const CommonArgs& a) {
     return allocate_small_counts(src, a.n, a.g0, a.budget, a.delta_max, a.delta, a.util, a.group_off, a.off_t,
                                  a.summary, a.dev_status, a.stream);
@@ -1609,7 +1607,7 @@ template <class Src>
 static int run_bisect(const Src& src, const CommonArgs& a, const Plan& p, const Workspace& w) {
     const long long n = a.n;
     // a batch that one workgroup can hold: one launch does the whole search and the outputs
-    if (n <= solo_max(src)) return run_small(src, a);
+    if (n <= kSoloMaxPrompts) return run_small(src, a);
     // gains one prompt may contribute: the caller's cap, the budget, the library's depth bound
     long long wanted = a.delta_max > 0 ? (long long)a.delta_max : a.budget;
     if (wanted > a.budget) wanted = a.budget;
