@@ -19,8 +19,8 @@ constexpr int kTile = kBig * kItems;          // 4096 prompts
 constexpr int kMaxBlocks = 256;               // workgroups of the allocation passes (a power of two)
 constexpr int kMaxClasses = HORA_CLASS_MAX_G0 + 1;
 constexpr int kMinRow = 32;                   // gain-table row length (a power of two), at least
-constexpr int kMaxRow = 256;                  // ... and at most
-constexpr int kTableCap = kMaxClasses * kMinRow;   // doubles per table (2048)
+constexpr int kMaxRow = 512;                  // ... and at most
+constexpr int kTableCap = 2 * kMaxClasses * kMinRow;   // doubles per table (4096: rows of 512 up to G0 = 7, of 256 up to G0 = 15)
 constexpr unsigned kTiedBit = 0x80000000u;
 
 // ---- threshold search (any posterior) ------------------------------------------------

@@ -425,7 +425,9 @@ __device__ void solve_by_rule(int rule, int g0, double alpha0, double beta0, lon
 // CLASS pass 2: solve (redundantly per workgroup), then write the workgroup's chunk.
 // kOff: 0 no offsets, 1 int32 offsets, 2 int64 offsets.
 // ----------------------------------------------------------------------------------
-template <int kOff>
+// kCap: doubles of LDS per table, kTableCap or half of it (the host's choice by the tables'
+// size: the common small tables do not pay for the room of the large ones).
+template <int kOff, int kCap>
 __global__ __launch_bounds__(kBig) void k_class_write(const int32_t* __restrict__ c, long long n, int g0,
                                                           double alpha0, double beta0, long long budget, int cap,
                                                           long long chunk, int nb, int row_len,
@@ -436,8 +438,9 @@ __global__ __launch_bounds__(kBig) void k_class_write(const int32_t* __restrict_
                                                           void* __restrict__ group_off,
                                                           hora_alloc_summary* __restrict__ summary,
                                                           int32_t* dev_status, int rule) {
-    __shared__ double s_gain[kTableCap];
-    __shared__ double s_surv[kTableCap];
+    static_assert(kCap == kTableCap || kCap == kTableCap / 2, "table room");
+    __shared__ double s_gain[kCap];
+    __shared__ double s_surv[kCap];
     __shared__ long long s_n[kMaxClasses];       // prompts per class, whole batch
     __shared__ long long s_before[kMaxClasses];  // prompts per class in workgroups before this one
     __shared__ ClassSolution s_sol;
@@ -462,7 +465,7 @@ __global__ __launch_bounds__(kBig) void k_class_write(const int32_t* __restrict_
     // Every global load of the prologue is issued before the first one is used (the
     // first tile of c, the two tables, the histogram): one round trip to memory instead
     // of one per stage.
-    constexpr int kTableLoads = kTableCap / kBig;                   // table entries per thread
+    constexpr int kTableLoads = kCap / kBig;                        // table entries per thread
     constexpr int kClassRounds = kMaxClasses / kBigWaves;           // classes per wavefront: a class's counts are one 1 KB row
     static_assert(kMaxBlocks == 4 * kWave && kMaxClasses % kBigWaves == 0, "a wavefront reads a class's row as 16-byte pieces");
     const int table_len = nc * row_len;
@@ -471,8 +474,11 @@ __global__ __launch_bounds__(kBig) void k_class_write(const int32_t* __restrict_
 #pragma unroll
     for (int q = 0; q < kTableLoads; ++q) {
         const int i = q * kBig + (int)threadIdx.x;
-        tg[q] = i < table_len ? gain_table[i] : 0.0;
-        ts[q] = i < table_len ? surv_table[i] : 0.0;
+        tg[q] = 0.0; ts[q] = 0.0;
+        if (q * kBig < table_len) {   // uniform: small tables skip the later rounds
+            tg[q] = i < table_len ? gain_table[i] : 0.0;
+            ts[q] = i < table_len ? surv_table[i] : 0.0;
+        }
     }
 #pragma unroll
     for (int q = 0; q < kClassRounds; ++q) {
@@ -488,7 +494,7 @@ __global__ __launch_bounds__(kBig) void k_class_write(const int32_t* __restrict_
 #pragma unroll
     for (int q = 0; q < kTableLoads; ++q) {
         const int i = q * kBig + (int)threadIdx.x;
-        if (i < table_len) {
+        if (q * kBig < table_len && i < table_len) {
             s_gain[i] = (i & (row_len - 1)) < len ? tg[q] : 0.0;
             s_surv[i] = ts[q];
         }
@@ -650,13 +656,19 @@ static int run_class(const int32_t* c, double alpha0, double beta0, const Common
                        alpha0, beta0, p.chunk, p.nb, row, w.class_hist, w.gain_table, w.surv_table,
                        a.dev_status);
     const int mode = a.group_off ? (a.off_t == HORA_I32 ? 1 : 2) : 0;
-#define HORA_LAUNCH_CLASS_WRITE(M)                                                                              \
-    hipLaunchKernelGGL((k_class_write<M>), dim3(p.nb), dim3(kBig), 0, a.stream, c, (long long)a.n,          \
+#define HORA_LAUNCH_CLASS_WRITE(M, CAP)                                                                         \
+    hipLaunchKernelGGL((k_class_write<M, CAP>), dim3(p.nb), dim3(kBig), 0, a.stream, c, (long long)a.n,     \
                        (int)a.g0, alpha0, beta0, (long long)a.budget, cap, p.chunk, p.nb, row, w.class_hist,   \
                        w.gain_table, w.surv_table, a.delta, a.util, a.group_off, a.summary, a.dev_status, rule)
-    if (mode == 0) HORA_LAUNCH_CLASS_WRITE(0);
-    else if (mode == 1) HORA_LAUNCH_CLASS_WRITE(1);
-    else HORA_LAUNCH_CLASS_WRITE(2);
+#define HORA_LAUNCH_CLASS_WRITE_BY_SIZE(M)                               \
+    do {                                                                 \
+        if (nc * row <= kTableCap / 2) HORA_LAUNCH_CLASS_WRITE(M, kTableCap / 2); \
+        else HORA_LAUNCH_CLASS_WRITE(M, kTableCap);                      \
+    } while (0)
+    if (mode == 0) HORA_LAUNCH_CLASS_WRITE_BY_SIZE(0);
+    else if (mode == 1) HORA_LAUNCH_CLASS_WRITE_BY_SIZE(1);
+    else HORA_LAUNCH_CLASS_WRITE_BY_SIZE(2);
+#undef HORA_LAUNCH_CLASS_WRITE_BY_SIZE
 #undef HORA_LAUNCH_CLASS_WRITE
     return check_launch();
 }
