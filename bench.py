@@ -29,7 +29,7 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
 # are in profiles/hbm_traffic_large_alloc_large_bcast.txt.  Set to None when a kernel named
 # there changes.
 TRAFFIC_BROADCAST_BYTES = 692395767     # k_row_desc + k_token_fill, large_bcast
-TRAFFIC_ALLOCATE_BYTES = 25548270       # k_class_hist + k_class_write, large_alloc
+TRAFFIC_ALLOCATE_BYTES = 25532911       # k_class_hist + k_class_write, large_alloc
 
 
 def ensure_library():
