@@ -200,8 +200,11 @@ struct BudgetShares {
     unsigned long long last_tile;   // of the batch's last tile (n - its start prompts), rounded up
 };
 
-constexpr int kEstWaves = 4;
-constexpr int kEstItems = 2;
+// (eight wavefronts with one sample per lane: two walkers per vector unit fill each other's
+// waits; four with two samples per lane took 3 % longer per call, sixteen with one, i.e. twice
+// the sample, were no faster than four)
+constexpr int kEstWaves = 8;
+constexpr int kEstItems = 1;
 constexpr int kEstSamples = kEstWaves * kWave * kEstItems;   // 512
 
 struct EstimateShared {
